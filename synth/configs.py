@@ -1,0 +1,84 @@
+"""Workload shapes and the chain order of trainable tensors.
+
+The tensor order is the execution order of the trainable tensors in the
+forward pass (Section 5: the list of trainable tensors sorted by execution
+order); index 0 is the input-most tensor, index N-1 the output-most one.
+"""
+from dataclasses import dataclass, field
+from typing import List, Tuple
+
+
+@dataclass(frozen=True)
+class MLPConfig:
+    """ReLU multi-layer perceptron without biases: dims[0] -> ... -> dims[-1]."""
+    name: str
+    dims: Tuple[int, ...]
+    batch: int
+    dtype: str = "f32"
+    kind: str = "mlp"
+
+    @property
+    def classes(self) -> int:
+        return self.dims[-1]
+
+
+@dataclass(frozen=True)
+class ViTConfig:
+    """Pre-LN vision-transformer encoder fed with flattened patches."""
+    name: str
+    batch: int
+    tokens: int        # patches + 1 CLS token
+    patch_dim: int     # flattened patch length (16*16*3 = 768)
+    width: int         # D
+    heads: int         # H, head size = D / H
+    mlp: int           # F
+    blocks: int        # L
+    classes: int       # C
+    dtype: str = "bf16"
+    kind: str = "vit"
+    ln_eps: float = 1e-6
+
+    @property
+    def head_dim(self) -> int:
+        return self.width // self.heads
+
+    @property
+    def rows(self) -> int:
+        return self.batch * self.tokens
+
+
+CONFIGS = {
+    # BASELINE configs[0]: 4-layer ReLU MLP, fp32, batch 32
+    "mlp": MLPConfig("mlp", (256, 256, 256, 256, 10), 32),
+    # BASELINE configs[1]/[2]: ViT-B/16 shape, batch 64
+    "vit_b": ViTConfig("vit_b", 64, 197, 768, 768, 12, 3072, 12, 200),
+    # BASELINE configs[3]: ViT-L/16 shape, batch 32
+    "vit_l": ViTConfig("vit_l", 32, 197, 768, 1024, 16, 4096, 24, 200),
+    # small cases the oracle finishes in well under a second
+    "mlp_tiny": MLPConfig("mlp_tiny", (8, 8, 8, 4), 4),
+    "mlp5": MLPConfig("mlp5", (6, 6, 6, 6, 6, 3), 4),
+    "vit_tiny": ViTConfig("vit_tiny", 2, 5, 12, 16, 2, 32, 2, 7),
+    # spans several GEMM tiles with ragged tails in every dimension
+    "vit_small": ViTConfig("vit_small", 3, 197, 200, 192, 3, 320, 2, 50),
+    "vit_mid": ViTConfig("vit_mid", 5, 197, 768, 384, 6, 1536, 3, 200),
+}
+
+
+def tensor_specs(cfg) -> List[Tuple[str, Tuple[int, ...]]]:
+    """(name, shape) of every trainable tensor in chain order."""
+    if cfg.kind == "mlp":
+        return [(f"fc{i}.W", (cfg.dims[i + 1], cfg.dims[i])) for i in range(len(cfg.dims) - 1)]
+    if cfg.kind == "vit":
+        D, F = cfg.width, cfg.mlp
+        out = [("patch.W", (D, cfg.patch_dim)), ("patch.b", (D,)), ("cls", (D,)), ("pos", (cfg.tokens, D))]
+        for l in range(cfg.blocks):
+            p = f"blk{l}."
+            out += [(p + "ln1.g", (D,)), (p + "ln1.b", (D,)),
+                    (p + "qkv.W", (3 * D, D)), (p + "qkv.b", (3 * D,)),
+                    (p + "proj.W", (D, D)), (p + "proj.b", (D,)),
+                    (p + "ln2.g", (D,)), (p + "ln2.b", (D,)),
+                    (p + "fc1.W", (F, D)), (p + "fc1.b", (F,)),
+                    (p + "fc2.W", (D, F)), (p + "fc2.b", (D,))]
+        out += [("lnf.g", (D,)), ("lnf.b", (D,)), ("head.W", (cfg.classes, D)), ("head.b", (cfg.classes,))]
+        return out
+    raise ValueError(cfg.kind)
