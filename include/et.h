@@ -1,0 +1,175 @@
+/* et.h - C ABI of the elastic selective training step for one MI355X (gfx950).
+ *
+ * The library implements the hot path of ElasticTrainer: a training step in
+ * which a runtime mask picks the trainable tensors (Section 2.2, Eq. 1/Eq. 3),
+ * a per-tensor importance reduction (Eq. 2), a tensor timing profiler
+ * (Section 5) and the tensor selector (Section 6).
+ *
+ * Conventions
+ *   - Tensor index i = 0 .. N-1 runs in forward execution order (Section 5);
+ *     i = 0 is the input-most tensor, i = N-1 the output-most one.
+ *   - Every function returns an int status: 0 = ET_OK, negative = error,
+ *     positive = informational.  Nothing throws; there is no global state.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers ordinary host
+ *     memory.  The library never allocates or frees device memory: weights,
+ *     optimizer state, gradients and the workspace belong to the caller and are
+ *     borrowed from et_bind() until et_destroy() or the next et_bind().
+ *   - All device work is enqueued on the HIP stream given to et_create();
+ *     only functions that return values to host memory wait for it.
+ *   - Calls on one context must not overlap.
+ */
+#ifndef ET_H_
+#define ET_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define ET_OK 0
+#define ET_INFEASIBLE 1 /* the budget is below the forward time: empty mask returned */
+#define ET_EINVAL (-1)  /* bad argument (null pointer, size, alignment, range)      */
+#define ET_ENOMEM (-2)  /* host allocation failed or workspace too small            */
+#define ET_EHIP (-3)    /* a HIP runtime call failed                                */
+#define ET_ENAN (-4)    /* an importance value is NaN or infinite                   */
+#define ET_ESTATE (-5)  /* call order: et_bind() has not been called                */
+
+/* model kinds */
+#define ET_MLP 0 /* ReLU multi-layer perceptron without biases                      */
+#define ET_VIT 1 /* pre-LN vision transformer encoder on flattened patches          */
+
+/* storage types of weights and activations */
+#define ET_F32 0  /* float32 everywhere                                             */
+#define ET_BF16 1 /* bf16 weights/activations, float32 accumulation and statistics  */
+
+/* optimizers (Section 8: Adam for ViT, SGD with momentum and decoupled decay otherwise) */
+#define ET_ADAM 0
+#define ET_SGDW 1
+
+#define ET_MAX_MLP_LAYERS 16
+
+typedef struct et_ctx et_ctx;
+
+/* Shape of the network.  Matrix weights are stored [out, in] row-major.
+ * ET_MLP: dims[0..n_layers], x is [batch, dims[0]] float32; tensors fc0.W .. fc{n-1}.W.
+ * ET_VIT: x is [batch, tokens-1, patch_dim]; the tensors are, in order,
+ *   patch.W [width, patch_dim], patch.b, cls [width], pos [tokens, width], then per block
+ *   ln1.g, ln1.b, qkv.W [3 width, width], qkv.b, proj.W, proj.b, ln2.g, ln2.b,
+ *   fc1.W [mlp, width], fc1.b, fc2.W [width, mlp], fc2.b, then lnf.g, lnf.b,
+ *   head.W [classes, width], head.b.  width, patch_dim, mlp, classes and the head size
+ *   width/heads must be multiples of 8 (16-byte rows); tokens is arbitrary.
+ * Labels are int32 in [0, classes). The loss is the mean softmax cross-entropy. */
+typedef struct {
+  int32_t kind;  /* ET_MLP | ET_VIT */
+  int32_t dtype; /* ET_F32 (MLP) | ET_BF16 (ViT) */
+  int32_t batch;
+  int32_t n_layers;                    /* ET_MLP */
+  int32_t dims[ET_MAX_MLP_LAYERS + 1]; /* ET_MLP */
+  int32_t tokens, patch_dim, width, heads, mlp, blocks, classes; /* ET_VIT */
+  float ln_eps;                        /* ET_VIT */
+} et_model_desc;
+
+/* Optimizer hyper-parameters of one step; every constant is explicit.
+ *   ET_ADAM: m = b1 m + (1-b1) g; v = b2 v + (1-b2) g^2;
+ *            w -= lr (m / (1-b1^step)) / (sqrt(v / (1-b2^step)) + eps); step >= 1 is the global step.
+ *   ET_SGDW: m = momentum m + g; w -= lr m + lr wd w.
+ * State of a tensor that is not selected is left untouched (frozen). */
+typedef struct {
+  int32_t kind; /* ET_ADAM | ET_SGDW */
+  float lr, beta1, beta2, eps, momentum, wd;
+  uint64_t step;
+} et_opt;
+
+/* Build the static operation chain of the model.  `hip_stream` is a hipStream_t (NULL = the
+ * default stream).  Allocates host memory only. */
+int et_create(const et_model_desc* desc, void* hip_stream, et_ctx** out);
+int et_destroy(et_ctx* ctx);
+
+/* Number of trainable tensors N, and per tensor its element count, storage type and name
+ * (the string lives as long as the context). */
+int et_num_tensors(const et_ctx* ctx, int32_t* n);
+int et_tensor_info(const et_ctx* ctx, int32_t i, size_t* numel, int32_t* dtype, const char** name);
+
+/* Bytes of device workspace the context needs (activations kept for the backward pass,
+ * gradient streams, reduction partials). */
+size_t et_workspace_bytes(const et_ctx* ctx);
+
+/* Number of optimizer-state buffers per tensor expected by et_bind():
+ *   ET_BF16 models: 3 = { float32 master weights, m, v }  (ET_SGDW uses the first two)
+ *   ET_F32  models: 2 = { m, v }                          (ET_SGDW uses the first)     */
+int et_state_slots(const et_ctx* ctx, int32_t* k);
+
+/* Lend the device buffers.  w_dev[i]: weights of tensor i in the model's storage type;
+ * grad_dev[i]: float32 [numel_i]; opt_state_dev[i*k + s]: float32 [numel_i] (k from
+ * et_state_slots; may be NULL as a whole if et_train_step is only called with opt == NULL);
+ * workspace_dev: at least et_workspace_bytes() bytes, 256-byte aligned.  The arrays of
+ * pointers are host arrays and are copied.  The workspace is cleared on the stream. */
+int et_bind(et_ctx* ctx, void* const* w_dev, void* const* opt_state_dev, void* const* grad_dev,
+            void* workspace_dev, size_t workspace_bytes);
+
+/* Tensor Timing Profiler (Section 5).  Runs `warmup` untimed and `reps` timed full training
+ * iterations (all tensors selected, no optimizer update of the weights), timing every kernel
+ * in place with HIP events, takes the median per kernel and attributes the times to tensors:
+ *   t_dw_ns[i]: computing tensor i's gradient plus its optimizer update (Section 5.1: T3, T2);
+ *   t_dy_ns[i]: passing the error gradient through tensor i towards tensor i-1 (T1); biases
+ *               and LayerNorm shifts have 0 (Section 5.1 footnote); backward kernels of
+ *               operations without weights (ReLU/GELU, attention core, residual additions)
+ *               are charged to the tensor that must be passed for them to run (Section 5.3);
+ *               a LayerNorm's input-gradient kernel is charged to its gain (Section 5.2);
+ *   t_fwd_ns:   the whole forward pass including the loss and its gradient.
+ * Host outputs; waits for the stream. */
+int et_profile(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, int32_t warmup, int32_t reps,
+               uint64_t* t_fwd_ns, uint64_t* t_dw_ns /*[N]*/, uint64_t* t_dy_ns /*[N]*/);
+
+/* Tensor Importance Evaluator (Eq. 2, with the gradient at the current weights, Eq. 5 at c=0):
+ * one full backward pass on (x, y) without update, then
+ *   importance[i] = sum_e grad_i[e] * (w_snapshot_i[e] - w_i[e])
+ * for every tensor in ONE reduction launch.  w_snapshot_dev[i] has the model's storage type
+ * and tensor i's size: the weights that undoing the recent update would restore.  Leaves
+ * the gradients of all tensors in grad_dev.  Host output; waits for the stream. */
+int et_importance(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, void* const* w_snapshot_dev /*[N]*/,
+                  double* importance_host /*[N]*/);
+
+/* Tensor Selector (Eq. 3 solved exactly on integers; Sections 3.3 and 6).  Pure host code,
+ * no context, no device.  Maximises the summed importance of the selected tensors subject to
+ *   t_fwd + sum_{i selected} t_dw[i] + sum_{i > i*} t_dy[i] <= rho * T_full,
+ * i* being the smallest selected index and T_full the same expression for all tensors
+ * selected (Section 2.2: the worked example and Eq. 7 leave out t_dy of i* itself).
+ *   rho_ppm: the speed-up objective rho in parts per million (500000 = 50 %);
+ *   tq:      time resolution T_q of Eq. 8: if 0 < tq < T_b (T_b = full backward time) every
+ *            time becomes floor(t * tq / T_b); tq = 0 keeps nanoseconds;
+ *   budget:  floor(rho_ppm * T_full / 1e6) - t_fwd; negative: ET_INFEASIBLE and an empty mask;
+ *   importance is quantised to integers rint(I * 2^(40-e)), 2^(e-1) <= max|I| < 2^e;
+ *   ties:    larger summed importance first; among equals the mask that is smallest when
+ *            read as a binary number with tensor 0 as the most significant bit.
+ * mask_out[i] = 1 if tensor i is selected.  predicted_ns (nullable) = the unquantised
+ * time-model value of the returned mask. */
+int et_select(int32_t n, const double* importance, const uint64_t* t_dw_ns, const uint64_t* t_dy_ns,
+              uint64_t t_fwd_ns, uint32_t rho_ppm, uint32_t tq, uint8_t* mask_out /*[N]*/,
+              uint64_t* predicted_ns);
+
+/* One elastic selective training iteration (Section 2.2): forward pass and loss; then, from
+ * the output backwards, the weight gradient of every selected tensor and the error-gradient
+ * passing down to (not through) the input-most selected tensor; then the optimizer update of
+ * the selected tensors only.  mask_host[i] != 0 selects tensor i; it steers which kernels are
+ * launched.  An empty mask launches no backward kernel.  grad_dev[i] of an unselected tensor
+ * is not written; its weights and optimizer state keep their bytes.  opt == NULL skips the
+ * update (gradients only).  loss_host == NULL makes the call fully asynchronous; otherwise it
+ * waits for the stream and stores the loss. */
+int et_train_step(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, const uint8_t* mask_host /*[N]*/,
+                  const et_opt* opt, float* loss_host);
+
+/* Counters of the last et_train_step/et_importance call on this context: kernels launched in
+ * the forward pass, in the backward pass and in the optimizer update. */
+int et_last_launch_counts(const et_ctx* ctx, int32_t* forward, int32_t* backward, int32_t* update);
+
+/* Human-readable text for a status code. */
+const char* et_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ET_H_ */

@@ -1,0 +1,27 @@
+/* et_debug.h - kernel-level entry points for tests and tuning.  Not needed to run the training
+ * step; they expose single kernels of the library so that each can be checked in isolation. */
+#ifndef ET_DEBUG_H_
+#define ET_DEBUG_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* bf16 MFMA GEMM used for the forward product, the error-gradient passing and the weight
+ * gradient (Section 5.1):  C[i][j] = alpha * sum_k A(i,k) * B(j,k) + bias[j] + residual[i][j]
+ *   A(i,k) = a_t ? A[k*lda + i] : A[i*lda + k],   B(j,k) = b_t ? B[k*ldb + j] : B[j*ldb + k].
+ * All pointers are device pointers; A, B, bias (nullable) bf16; residual (nullable) fp32 [M][N];
+ * C is fp32 if c_f32 else bf16, leading dimension ldc.  split_k > 1 needs c_f32, ldc == N and
+ * `partials` with M*N*split_k floats.  tile: 0 = automatic, otherwise a tile id of the library.
+ * stream: hipStream_t.  Returns 0, or -1 for a rejected argument, -3 for a HIP error. */
+int et_debug_gemm_bf16(const void* A, const void* B, void* C, int M, int N, int K, int lda, int ldb, int ldc,
+                       int a_t, int b_t, int c_f32, float alpha, const void* bias, const float* residual,
+                       int split_k, float* partials, int tile, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ET_DEBUG_H_ */

@@ -1,0 +1,150 @@
+// Internal launch interface of the HIP kernels (gfx950).  Not part of the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace et {
+
+typedef __bf16 bf16;
+
+// ------------------------------------------------------------------------------------------
+// bf16 MFMA GEMM:  D[i][j] = alpha * sum_k A(i,k) * B(j,k)   (fp32 accumulation)
+//   A(i,k) = a_t ? A[k*lda + i] : A[i*lda + k]      (a_t: the reduction index is the slow one)
+//   B(j,k) = b_t ? B[k*ldb + j] : B[j*ldb + k]
+// so forward (X W^T) is (a_t,b_t) = (0,0), input gradient (dY W) is (0,1) and weight gradient
+// (dY^T X) is (1,1).  Requirements (checked on the host): 16-byte aligned bases, lda/ldb/ldc
+// multiples of 8; an operand that is not transposed must have finite data up to K rounded up to 8
+// in every row (the tail is multiplied by zeros or must itself be zero).
+// ------------------------------------------------------------------------------------------
+enum EpiMode : int {
+  EPI_PLAIN = 0,     // C = v
+  EPI_GELU_FWD = 1,  // C = v (pre-activation, bf16), C2 = gelu(v) (bf16)
+  EPI_GELU_BWD = 2,  // C = v * gelu'(U)
+};
+
+struct GemmDesc {
+  const bf16* A = nullptr;
+  const bf16* B = nullptr;
+  int M = 0, N = 0, K = 0;
+  int lda = 0, ldb = 0;
+  bool a_t = false, b_t = false;
+  // batching: blockIdx.z = outer * z_inner + inner; offsets in elements
+  int z_outer = 1, z_inner = 1;
+  long long sAo = 0, sAi = 0, sBo = 0, sBi = 0, sCo = 0, sCi = 0;
+  // split-K (weight gradients): > 1 writes fp32 partials to `partials` and reduces them in a
+  // fixed order with a second kernel; batching must then be off
+  int split_k = 1;
+  float* partials = nullptr;
+  // epilogue: v = alpha * acc + bias[j] + residual[i][j]
+  float alpha = 1.f;
+  const bf16* bias = nullptr;      // per output column
+  const float* residual = nullptr; // fp32 [M][ldr]
+  int ldr = 0;
+  int mode = EPI_PLAIN;
+  void* C = nullptr;               // bf16 or fp32 [M][ldc]
+  int ldc = 0;
+  bool c_f32 = false;
+  bf16* C2 = nullptr;              // EPI_GELU_FWD
+  const bf16* U = nullptr;         // EPI_GELU_BWD, same leading dimension as C
+  int tile = 0;                    // 0 = choose by shape; else a TileId (tuning/tests)
+};
+
+// returns hipSuccess, or hipErrorInvalidValue when a requirement above is violated
+// *launches (nullable) receives the number of kernels launched (1, or 2 with split-K)
+hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches = nullptr);
+// fp32 partial elements needed for a split-K call
+size_t gemm_bf16_partial_elems(int M, int N, int split_k);
+
+// ------------------------------------------------------------------------------------------
+// fp32 GEMM (true fp32 FMA), same operand convention, for the fp32 MLP workload
+//   relu_out: C = max(v, 0);  mask: C = v * (mask[i][j] > 0)  (ReLU backward, ldmask = ldc)
+// ------------------------------------------------------------------------------------------
+struct GemmF32Desc {
+  const float* A = nullptr;
+  const float* B = nullptr;
+  float* C = nullptr;
+  int M = 0, N = 0, K = 0, lda = 0, ldb = 0, ldc = 0;
+  bool a_t = false, b_t = false;
+  bool relu_out = false;
+  const float* mask = nullptr;
+};
+hipError_t gemm_f32(const GemmF32Desc& d, hipStream_t s);
+
+// ------------------------------------------------------------------------------------------
+// row-wise and reduction kernels (HBM bound)
+// ------------------------------------------------------------------------------------------
+// LayerNorm forward over rows of an fp32 matrix; in_stride = elements between consecutive rows
+hipError_t layernorm_fwd(const float* h, long long in_stride, const bf16* gain, const bf16* shift, float eps,
+                         bf16* out, float* mean, float* rstd, int rows, int D, hipStream_t s);
+// LayerNorm input gradient: dh = skip + LN'(d); writes fp32 and a bf16 copy.  skip may be null.
+// out_stride lets the result be scattered (final LayerNorm on CLS rows); skip uses out_stride too.
+hipError_t layernorm_bwd_dx(const bf16* d, const float* h, long long in_stride, const float* mean, const float* rstd,
+                            const bf16* gain, const float* skip, float* dh, bf16* dh_bf16, long long out_stride,
+                            int rows, int D, hipStream_t s);
+// column sums over rows: out[c] = sum_r d[r][c] * (h ? (h[r][c]-mean[r])*rstd[r] : 1)
+//   d is bf16 (d_f32 == nullptr) or fp32; two deterministic stages through `partials`
+hipError_t colsum(const bf16* d, const float* d_f32, long long d_stride, const float* h, long long h_stride,
+                  const float* mean, const float* rstd, float* out, float* partials, int rows, int cols,
+                  hipStream_t s);
+size_t colsum_partial_elems(int rows, int cols);
+// sum over the batch: out[t][c] = sum_b d[b][t][c]   (t < T_out; fp32 in/out)
+hipError_t batchsum(const float* d, float* out, int B, long long batch_stride, int n, hipStream_t s);
+
+// softmax over the first `cols` entries of each fp32 row (ld elements apart); bf16 result, tail zeroed
+hipError_t softmax_rows(const float* s, bf16* p, int rows, int cols, int ld, hipStream_t stream);
+// dS = scale * P * (dP - sum(dP*P)); bf16 result, tail zeroed
+hipError_t softmax_bwd_rows(const float* dp, const bf16* p, bf16* ds, float scale, int rows, int cols, int ld,
+                            hipStream_t stream);
+
+// mean softmax cross-entropy: loss (1 float), dlogits fp32 and (if not null) a bf16 copy [B][ld16], zero padded
+hipError_t xent(const float* logits, const int32_t* y, int B, int C, float* loss, float* dlogits, bf16* dlogits_bf16,
+                int ld16, hipStream_t s);
+
+// ViT embedding: h0[b][0] = cls + pos[0]; h0[b][t] = e[b][t-1] + pos[t]  (e fp32 [B*(T-1)][D])
+hipError_t embed_assemble(const float* e, const bf16* cls, const bf16* pos, float* h0, int B, int T, int D, hipStream_t s);
+// drop the CLS rows: out[b*(T-1)+t-1] = bf16(d[b][t]) for t >= 1
+hipError_t gather_patch_rows(const float* d, bf16* out, int B, int T, int D, hipStream_t s);
+// fill with zeros (a kernel, so that it may be captured in a graph)
+hipError_t fill_zero(void* p, size_t bytes, hipStream_t s);
+// fp32 -> bf16
+hipError_t cast_bf16(const float* in, bf16* out, size_t n, hipStream_t s);
+
+// ------------------------------------------------------------------------------------------
+// importance (Eq. 2) and masked optimizer update over a table of tensors
+// ------------------------------------------------------------------------------------------
+struct TensorSeg {       // one chunk of one tensor
+  const float* g;        // gradient
+  const void* w;         // current weights (bf16 or fp32)
+  const void* w_snap;    // snapshot
+  uint32_t n;            // elements in this chunk
+  uint32_t tensor;       // tensor index
+};
+// stage 1: one block per segment -> partial[seg]; stage 2: per tensor, fixed-order sum -> double
+hipError_t importance_reduce(const TensorSeg* segs_dev, int n_segs, const uint32_t* seg_begin_dev, int n_tensors,
+                             bool bf16_weights, double* partial_dev, double* out_dev, hipStream_t s);
+
+struct UpdateSeg {
+  const float* g;
+  void* w;        // model weights (bf16 or fp32)
+  float* master;  // fp32 master weights (bf16 models), else null
+  float* m;
+  float* v;       // Adam only
+  uint32_t n;
+  uint32_t tensor;
+};
+constexpr int MAX_TENSORS = 1024;
+struct SelectionBits {   // bit i set: tensor i is selected; passed by value as a kernel argument
+  uint64_t bits[MAX_TENSORS / 64];
+};
+struct OptParams {
+  int kind;       // 0 Adam, 1 SGDW
+  float lr, beta1, beta2, eps, momentum, wd;
+  float bc1, bc2; // 1 - beta1^t, 1 - beta2^t
+  int dry;        // 1: compute, then store the values that were loaded (timing without side effects)
+};
+// segs_dev lists the chunks of ALL tensors; chunks of tensors outside `sel` exit immediately
+hipError_t masked_update(const UpdateSeg* segs_dev, int n_segs, bool bf16_weights, const SelectionBits& sel,
+                         OptParams p, hipStream_t s);
+
+}  // namespace et

@@ -1,0 +1,140 @@
+// Tensor importance reduction (Eq. 2) and the masked optimizer update (Section 8), both driven
+// by a device table of tensor chunks so that one launch covers every tensor of the model.
+//
+// importance: I_k = sum_i g_i * (w_snapshot_i - w_i).  Stage 1: one 256-thread workgroup per
+// chunk of at most SEG_ELEMS elements; every thread streams 16-byte loads of g, w and w_snapshot
+// (coalesced across the wave), keeps four fp32 partial sums, then the workgroup combines them in
+// double precision with cross-lane shuffles inside each 64-lane wave and a 4-entry LDS exchange.
+// Stage 2: one thread per tensor adds that tensor's chunk sums in ascending order.  No atomics:
+// the result is bit-reproducible.
+//
+// update: one workgroup per chunk; a chunk whose tensor is not in the selection bit set returns
+// at once, so unselected weights and optimizer state are neither read nor written.
+#include "kernels.h"
+
+namespace et {
+namespace {
+
+typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ double wave_sum_d(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+template <bool BF16W>
+__global__ __launch_bounds__(256) void importance_stage1(const TensorSeg* __restrict__ segs,
+                                                         double* __restrict__ partial) {
+  __shared__ double red[4];
+  const TensorSeg sg = segs[blockIdx.x];
+  const float* __restrict__ g = sg.g;
+  const uint32_t n = sg.n;
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  if (BF16W) {
+    const bf16* __restrict__ w = (const bf16*)sg.w;
+    const bf16* __restrict__ ws = (const bf16*)sg.w_snap;
+    const bool vec = (((uintptr_t)g | (uintptr_t)w | (uintptr_t)ws) & 15) == 0;
+    const uint32_t n8 = vec ? n / 8 : 0;
+    for (uint32_t i = threadIdx.x; i < n8; i += 256) {
+      const float4 g0 = ((const float4*)g)[2 * i], g1 = ((const float4*)g)[2 * i + 1];
+      const bf16x8 wv = ((const bf16x8*)w)[i], sv = ((const bf16x8*)ws)[i];
+      a0 += g0.x * ((float)sv[0] - (float)wv[0]) + g0.y * ((float)sv[1] - (float)wv[1]);
+      a1 += g0.z * ((float)sv[2] - (float)wv[2]) + g0.w * ((float)sv[3] - (float)wv[3]);
+      a2 += g1.x * ((float)sv[4] - (float)wv[4]) + g1.y * ((float)sv[5] - (float)wv[5]);
+      a3 += g1.z * ((float)sv[6] - (float)wv[6]) + g1.w * ((float)sv[7] - (float)wv[7]);
+    }
+    for (uint32_t i = n8 * 8 + threadIdx.x; i < n; i += 256) a0 += g[i] * ((float)ws[i] - (float)w[i]);
+  } else {
+    const float* __restrict__ w = (const float*)sg.w;
+    const float* __restrict__ ws = (const float*)sg.w_snap;
+    const bool vec = (((uintptr_t)g | (uintptr_t)w | (uintptr_t)ws) & 15) == 0;
+    const uint32_t n4 = vec ? n / 4 : 0;
+    for (uint32_t i = threadIdx.x; i < n4; i += 256) {
+      const float4 gv = ((const float4*)g)[i], wv = ((const float4*)w)[i], sv = ((const float4*)ws)[i];
+      a0 += gv.x * (sv.x - wv.x);
+      a1 += gv.y * (sv.y - wv.y);
+      a2 += gv.z * (sv.z - wv.z);
+      a3 += gv.w * (sv.w - wv.w);
+    }
+    for (uint32_t i = n4 * 4 + threadIdx.x; i < n; i += 256) a0 += g[i] * (ws[i] - w[i]);
+  }
+  double s = wave_sum_d(((double)a0 + (double)a1) + ((double)a2 + (double)a3));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) partial[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ void importance_stage2(const double* __restrict__ partial, const uint32_t* __restrict__ seg_begin,
+                                  int n_tensors, double* __restrict__ out) {
+  const int k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= n_tensors) return;
+  double s = 0.0;
+  for (uint32_t i = seg_begin[k]; i < seg_begin[k + 1]; i++) s += partial[i];
+  out[k] = s;
+}
+
+template <bool BF16W>
+__global__ __launch_bounds__(256) void masked_update_kernel(const UpdateSeg* __restrict__ segs, SelectionBits sel,
+                                                            OptParams p) {
+  const UpdateSeg sg = segs[blockIdx.x];
+  if (!((sel.bits[sg.tensor >> 6] >> (sg.tensor & 63)) & 1ull)) return;
+  const float* __restrict__ g = sg.g;
+  float* __restrict__ m = sg.m;
+  float* __restrict__ v = sg.v;
+  float* __restrict__ wf = BF16W ? sg.master : (float*)sg.w;
+  bf16* __restrict__ wb = (bf16*)sg.w;
+  for (uint32_t i = threadIdx.x; i < sg.n; i += 256) {
+    const float gi = g[i];
+    const float w_old = wf[i];
+    float w = w_old;
+    if (p.kind == 0) {
+      const float m_old = m[i], v_old = v[i];
+      const float mi = p.beta1 * m_old + (1.f - p.beta1) * gi;
+      const float vi = p.beta2 * v_old + (1.f - p.beta2) * gi * gi;
+      m[i] = p.dry ? m_old : mi;
+      v[i] = p.dry ? v_old : vi;
+      w -= p.lr * (mi / p.bc1) / (sqrtf(vi / p.bc2) + p.eps);
+    } else {
+      const float m_old = m[i];
+      const float mi = p.momentum * m_old + gi;
+      m[i] = p.dry ? m_old : mi;
+      w = w - p.lr * mi - p.lr * p.wd * w;
+    }
+    if (p.dry) {
+      wf[i] = w_old;
+      if (BF16W) wb[i] = wb[i];
+    } else {
+      wf[i] = w;
+      if (BF16W) wb[i] = (bf16)w;
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t importance_reduce(const TensorSeg* segs_dev, int n_segs, const uint32_t* seg_begin_dev, int n_tensors,
+                             bool bf16_weights, double* partial_dev, double* out_dev, hipStream_t s) {
+  if (n_segs <= 0 || n_tensors <= 0) return hipErrorInvalidValue;
+  if (bf16_weights)
+    hipLaunchKernelGGL((importance_stage1<true>), dim3(n_segs), dim3(256), 0, s, segs_dev, partial_dev);
+  else
+    hipLaunchKernelGGL((importance_stage1<false>), dim3(n_segs), dim3(256), 0, s, segs_dev, partial_dev);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(importance_stage2, dim3((n_tensors + 63) / 64), dim3(64), 0, s, partial_dev, seg_begin_dev,
+                     n_tensors, out_dev);
+  return hipGetLastError();
+}
+
+hipError_t masked_update(const UpdateSeg* segs_dev, int n_segs, bool bf16_weights, const SelectionBits& sel,
+                         OptParams p, hipStream_t s) {
+  if (n_segs <= 0) return hipErrorInvalidValue;
+  if (bf16_weights)
+    hipLaunchKernelGGL((masked_update_kernel<true>), dim3(n_segs), dim3(256), 0, s, segs_dev, sel, p);
+  else
+    hipLaunchKernelGGL((masked_update_kernel<false>), dim3(n_segs), dim3(256), 0, s, segs_dev, sel, p);
+  return hipGetLastError();
+}
+
+}  // namespace et

@@ -1,0 +1,427 @@
+// HBM-bound kernels of the training step: LayerNorm forward/backward, softmax forward/backward,
+// cross-entropy, column and batch reductions (bias / LayerNorm gain and shift / embedding
+// gradients, Sections 5.1 and 5.2), embedding assembly.  One 64-lane wave owns one row in the
+// row-wise kernels; reductions inside a wave use cross-lane shuffles, all sums have a fixed
+// order so results are bit-reproducible.
+#include "kernels.h"
+
+namespace et {
+namespace {
+
+constexpr int WAVE = 64;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+  return v;
+}
+
+typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// ---------------------------------------------------------------------------------------------
+// LayerNorm forward: out = (h - mean) * rstd * gain + shift, statistics in fp32 (two passes)
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void layernorm_fwd_kernel(const float* __restrict__ h, long long in_stride,
+                                                            const bf16* __restrict__ gain,
+                                                            const bf16* __restrict__ shift, float eps,
+                                                            bf16* __restrict__ out, float* __restrict__ mean,
+                                                            float* __restrict__ rstd, int rows, int D) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const float4* x = (const float4*)(h + (long long)row * in_stride);
+  const int n4 = D >> 2;
+  float s = 0.f;
+  for (int i = lane; i < n4; i += WAVE) {
+    const float4 v = x[i];
+    s += (v.x + v.y) + (v.z + v.w);
+  }
+  const float mu = wave_sum(s) / (float)D;
+  float q = 0.f;
+  for (int i = lane; i < n4; i += WAVE) {
+    const float4 v = x[i];
+    const float a = v.x - mu, b = v.y - mu, c = v.z - mu, d = v.w - mu;
+    q += (a * a + b * b) + (c * c + d * d);
+  }
+  const float rs = 1.f / sqrtf(wave_sum(q) / (float)D + eps);
+  if (lane == 0) {
+    mean[row] = mu;
+    rstd[row] = rs;
+  }
+  bf16x4* o = (bf16x4*)(out + (long long)row * D);
+  const bf16x4* g4 = (const bf16x4*)gain;
+  const bf16x4* b4 = (const bf16x4*)shift;
+  for (int i = lane; i < n4; i += WAVE) {
+    const float4 v = x[i];
+    const bf16x4 g = g4[i], b = b4[i];
+    bf16x4 r;
+    r[0] = (bf16)((v.x - mu) * rs * (float)g[0] + (float)b[0]);
+    r[1] = (bf16)((v.y - mu) * rs * (float)g[1] + (float)b[1]);
+    r[2] = (bf16)((v.z - mu) * rs * (float)g[2] + (float)b[2]);
+    r[3] = (bf16)((v.w - mu) * rs * (float)g[3] + (float)b[3]);
+    o[i] = r;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// LayerNorm input gradient (+ residual branch): with xhat = (h-mean)*rstd, t = d*gain,
+//   dh = skip + rstd * (t - mean(t) - xhat * mean(t*xhat))
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void layernorm_bwd_dx_kernel(const bf16* __restrict__ d, const float* __restrict__ h,
+                                                               long long in_stride, const float* __restrict__ mean,
+                                                               const float* __restrict__ rstd,
+                                                               const bf16* __restrict__ gain,
+                                                               const float* __restrict__ skip, float* __restrict__ dh,
+                                                               bf16* __restrict__ dh16, long long out_stride, int rows,
+                                                               int D) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const float4* x = (const float4*)(h + (long long)row * in_stride);
+  const bf16x4* d4 = (const bf16x4*)(d + (long long)row * D);
+  const bf16x4* g4 = (const bf16x4*)gain;
+  const int n4 = D >> 2;
+  const float mu = mean[row], rs = rstd[row];
+  float s1 = 0.f, s2 = 0.f;
+  for (int i = lane; i < n4; i += WAVE) {
+    const float4 v = x[i];
+    const bf16x4 dv = d4[i], g = g4[i];
+    const float t0 = (float)dv[0] * (float)g[0], t1 = (float)dv[1] * (float)g[1];
+    const float t2 = (float)dv[2] * (float)g[2], t3 = (float)dv[3] * (float)g[3];
+    s1 += (t0 + t1) + (t2 + t3);
+    s2 += (t0 * ((v.x - mu) * rs) + t1 * ((v.y - mu) * rs)) + (t2 * ((v.z - mu) * rs) + t3 * ((v.w - mu) * rs));
+  }
+  const float m1 = wave_sum(s1) / (float)D, m2 = wave_sum(s2) / (float)D;
+  const float4* sk = skip ? (const float4*)(skip + (long long)row * out_stride) : nullptr;
+  float4* o = (float4*)(dh + (long long)row * out_stride);
+  bf16x4* o16 = dh16 ? (bf16x4*)(dh16 + (long long)row * out_stride) : nullptr;
+  for (int i = lane; i < n4; i += WAVE) {
+    const float4 v = x[i];
+    const bf16x4 dv = d4[i], g = g4[i];
+    float4 r;
+    r.x = rs * ((float)dv[0] * (float)g[0] - m1 - (v.x - mu) * rs * m2);
+    r.y = rs * ((float)dv[1] * (float)g[1] - m1 - (v.y - mu) * rs * m2);
+    r.z = rs * ((float)dv[2] * (float)g[2] - m1 - (v.z - mu) * rs * m2);
+    r.w = rs * ((float)dv[3] * (float)g[3] - m1 - (v.w - mu) * rs * m2);
+    if (sk) {
+      const float4 k = sk[i];
+      r.x += k.x; r.y += k.y; r.z += k.z; r.w += k.w;
+    }
+    o[i] = r;
+    if (o16) {
+      bf16x4 q;
+      q[0] = (bf16)r.x; q[1] = (bf16)r.y; q[2] = (bf16)r.z; q[3] = (bf16)r.w;
+      o16[i] = q;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// column sums, stage 1: a block of 32 column-threads (8 columns each) x 8 row-threads sums
+// CS_ROWS rows of 256 columns; stage 2 adds the row-chunk partials in ascending order
+// ---------------------------------------------------------------------------------------------
+constexpr int CS_ROWS = 128;
+
+template <bool F32IN, bool XHAT>
+__global__ __launch_bounds__(256) void colsum_stage1(const bf16* __restrict__ d16, const float* __restrict__ d32,
+                                                     long long d_stride, const float* __restrict__ h,
+                                                     long long h_stride, const float* __restrict__ mean,
+                                                     const float* __restrict__ rstd, float* __restrict__ partials,
+                                                     int rows, int cols) {
+  __shared__ float red[8][256];
+  const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
+  const int c0 = blockIdx.x * 256 + cx * 8;
+  const int r_begin = blockIdx.y * CS_ROWS, r_end = min(rows, r_begin + CS_ROWS);
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; j++) acc[j] = 0.f;
+  if (c0 < cols) {
+    for (int r = r_begin + ry; r < r_end; r += 8) {
+      float v[8];
+      if (F32IN) {
+        const float4 a = *(const float4*)(d32 + (long long)r * d_stride + c0);
+        const float4 b = *(const float4*)(d32 + (long long)r * d_stride + c0 + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+      } else {
+        const bf16x8 a = *(const bf16x8*)(d16 + (long long)r * d_stride + c0);
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = (float)a[j];
+      }
+      if (XHAT) {
+        const float mu = mean[r], rs = rstd[r];
+        const float4 a = *(const float4*)(h + (long long)r * h_stride + c0);
+        const float4 b = *(const float4*)(h + (long long)r * h_stride + c0 + 4);
+        v[0] *= (a.x - mu) * rs; v[1] *= (a.y - mu) * rs; v[2] *= (a.z - mu) * rs; v[3] *= (a.w - mu) * rs;
+        v[4] *= (b.x - mu) * rs; v[5] *= (b.y - mu) * rs; v[6] *= (b.z - mu) * rs; v[7] *= (b.w - mu) * rs;
+      }
+#pragma unroll
+      for (int j = 0; j < 8; j++) acc[j] += v[j];
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; j++) red[ry][cx * 8 + j] = acc[j];
+  __syncthreads();
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c < cols) {
+    float s = red[0][threadIdx.x];
+#pragma unroll
+    for (int k = 1; k < 8; k++) s += red[k][threadIdx.x];
+    partials[(long long)blockIdx.y * cols + c] = s;
+  }
+}
+
+__global__ void colsum_stage2(const float* __restrict__ partials, float* __restrict__ out, int chunks, int cols) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= cols) return;
+  float s = partials[c];
+  for (int k = 1; k < chunks; k++) s += partials[(long long)k * cols + c];
+  out[c] = s;
+}
+
+__global__ void batchsum_kernel(const float* __restrict__ d, float* __restrict__ out, int B, long long batch_stride,
+                                int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float s = d[i];
+  for (int b = 1; b < B; b++) s += d[(long long)b * batch_stride + i];
+  out[i] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// softmax rows (attention probabilities) and its backward
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void softmax_rows_kernel(const float* __restrict__ s, bf16* __restrict__ p, int rows,
+                                                           int cols, int ld) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const float* x = s + (long long)row * ld;
+  bf16* o = p + (long long)row * ld;
+  float mx = -INFINITY;
+  for (int i = lane; i < cols; i += WAVE) mx = fmaxf(mx, x[i]);
+  mx = wave_max(mx);
+  float sum = 0.f;
+  for (int i = lane; i < cols; i += WAVE) sum += __expf(x[i] - mx);
+  const float inv = 1.f / wave_sum(sum);
+  for (int i = lane; i < ld; i += WAVE) o[i] = (bf16)(i < cols ? __expf(x[i] - mx) * inv : 0.f);
+}
+
+__global__ __launch_bounds__(256) void softmax_bwd_rows_kernel(const float* __restrict__ dp, const bf16* __restrict__ p,
+                                                               bf16* __restrict__ ds, float scale, int rows, int cols,
+                                                               int ld) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const float* g = dp + (long long)row * ld;
+  const bf16* pr = p + (long long)row * ld;
+  bf16* o = ds + (long long)row * ld;
+  float dot = 0.f;
+  for (int i = lane; i < cols; i += WAVE) dot += g[i] * (float)pr[i];
+  dot = wave_sum(dot);
+  for (int i = lane; i < ld; i += WAVE) o[i] = (bf16)(i < cols ? scale * (float)pr[i] * (g[i] - dot) : 0.f);
+}
+
+// ---------------------------------------------------------------------------------------------
+// mean softmax cross-entropy and its gradient; one block, waves take rows in turn
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void xent_kernel(const float* __restrict__ logits, const int32_t* __restrict__ y,
+                                                   int B, int C, float* __restrict__ loss, float* __restrict__ dl,
+                                                   bf16* __restrict__ dl16, int ld16) {
+  __shared__ float wsum[4];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float acc = 0.f;  // meaningful in lane 0
+  const float invB = 1.f / (float)B;
+  for (int r = wave; r < B; r += 4) {
+    const float* x = logits + (long long)r * C;
+    float mx = -INFINITY;
+    for (int i = lane; i < C; i += WAVE) mx = fmaxf(mx, x[i]);
+    mx = wave_max(mx);
+    float sum = 0.f;
+    for (int i = lane; i < C; i += WAVE) sum += expf(x[i] - mx);
+    sum = wave_sum(sum);
+    const float lse = logf(sum) + mx;
+    const int label = y[r];
+    acc += lse - x[label];
+    for (int i = lane; i < ld16; i += WAVE) {
+      float gval = 0.f;
+      if (i < C) {
+        gval = (expf(x[i] - lse) - (i == label ? 1.f : 0.f)) * invB;
+        dl[(long long)r * C + i] = gval;
+      }
+      if (dl16) dl16[(long long)r * ld16 + i] = (bf16)gval;
+    }
+  }
+  if (lane == 0) wsum[wave] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) *loss = ((wsum[0] + wsum[1]) + (wsum[2] + wsum[3])) * invB;
+}
+
+// ---------------------------------------------------------------------------------------------
+// embedding assembly, CLS-row drop, fill, cast
+// ---------------------------------------------------------------------------------------------
+__global__ void embed_assemble_kernel(const float* __restrict__ e, const bf16* __restrict__ cls,
+                                      const bf16* __restrict__ pos, float* __restrict__ h0, int B, int T, int D) {
+  const long long i4 = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+  const int d4 = D >> 2;
+  if (i4 >= (long long)B * T * d4) return;
+  const int c = (int)(i4 % d4) * 4;
+  const long long bt = i4 / d4;
+  const int t = (int)(bt % T);
+  const long long b = bt / T;
+  const bf16x4 pv = *(const bf16x4*)(pos + (long long)t * D + c);
+  float4 r;
+  if (t == 0) {
+    const bf16x4 cv = *(const bf16x4*)(cls + c);
+    r = make_float4((float)cv[0], (float)cv[1], (float)cv[2], (float)cv[3]);
+  } else {
+    r = *(const float4*)(e + (b * (T - 1) + (t - 1)) * D + c);
+  }
+  r.x += (float)pv[0]; r.y += (float)pv[1]; r.z += (float)pv[2]; r.w += (float)pv[3];
+  *(float4*)(h0 + bt * D + c) = r;
+}
+
+__global__ void gather_patch_rows_kernel(const float* __restrict__ d, bf16* __restrict__ out, int B, int T, int D) {
+  const long long i4 = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+  const int d4 = D >> 2;
+  if (i4 >= (long long)B * (T - 1) * d4) return;
+  const int c = (int)(i4 % d4) * 4;
+  const long long bp = i4 / d4;
+  const int p = (int)(bp % (T - 1));
+  const long long b = bp / (T - 1);
+  const float4 v = *(const float4*)(d + (b * T + p + 1) * D + c);
+  bf16x4 q;
+  q[0] = (bf16)v.x; q[1] = (bf16)v.y; q[2] = (bf16)v.z; q[3] = (bf16)v.w;
+  *(bf16x4*)(out + bp * D + c) = q;
+}
+
+__global__ void fill_zero_kernel(uint4* __restrict__ p, size_t n16, unsigned char* __restrict__ tail, size_t ntail) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+  if (blockIdx.x == 0 && threadIdx.x < ntail) tail[threadIdx.x] = 0;
+}
+
+__global__ void cast_bf16_kernel(const float* __restrict__ in, bf16* __restrict__ out, size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += stride) out[i] = (bf16)in[i];
+}
+
+inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+inline bool al8(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 7) == 0; }
+
+}  // namespace
+
+hipError_t layernorm_fwd(const float* h, long long in_stride, const bf16* gain, const bf16* shift, float eps, bf16* out,
+                         float* mean, float* rstd, int rows, int D, hipStream_t s) {
+  if (rows <= 0 || D <= 0 || (D & 3) || (in_stride & 3) || !al16(h) || !al8(gain) || !al8(shift) || !al8(out))
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(layernorm_fwd_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, h, in_stride, gain, shift, eps, out,
+                     mean, rstd, rows, D);
+  return hipGetLastError();
+}
+
+hipError_t layernorm_bwd_dx(const bf16* d, const float* h, long long in_stride, const float* mean, const float* rstd,
+                            const bf16* gain, const float* skip, float* dh, bf16* dh16, long long out_stride, int rows,
+                            int D, hipStream_t s) {
+  if (rows <= 0 || D <= 0 || (D & 3) || (in_stride & 3) || (out_stride & 3) || !al16(h) || !al8(d) || !al8(gain) ||
+      !al16(dh) || (skip && !al16(skip)) || (dh16 && !al8(dh16)))
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(layernorm_bwd_dx_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, d, h, in_stride, mean, rstd, gain,
+                     skip, dh, dh16, out_stride, rows, D);
+  return hipGetLastError();
+}
+
+size_t colsum_partial_elems(int rows, int cols) { return (size_t)((rows + CS_ROWS - 1) / CS_ROWS) * cols; }
+
+hipError_t colsum(const bf16* d, const float* d_f32, long long d_stride, const float* h, long long h_stride,
+                  const float* mean, const float* rstd, float* out, float* partials, int rows, int cols,
+                  hipStream_t s) {
+  if (rows <= 0 || cols <= 0 || (cols & 7) || (d_stride & 7) || (h && (h_stride & 3)) || (!d && !d_f32) || !partials)
+    return hipErrorInvalidValue;
+  if ((d && !al16(d)) || (d_f32 && !al16(d_f32)) || (h && !al16(h))) return hipErrorInvalidValue;
+  const int chunks = (rows + CS_ROWS - 1) / CS_ROWS;
+  dim3 grid((cols + 255) / 256, chunks), block(256);
+  if (d_f32) {
+    if (h)
+      hipLaunchKernelGGL((colsum_stage1<true, true>), grid, block, 0, s, d, d_f32, d_stride, h, h_stride, mean, rstd,
+                         partials, rows, cols);
+    else
+      hipLaunchKernelGGL((colsum_stage1<true, false>), grid, block, 0, s, d, d_f32, d_stride, h, h_stride, mean, rstd,
+                         partials, rows, cols);
+  } else {
+    if (h)
+      hipLaunchKernelGGL((colsum_stage1<false, true>), grid, block, 0, s, d, d_f32, d_stride, h, h_stride, mean, rstd,
+                         partials, rows, cols);
+    else
+      hipLaunchKernelGGL((colsum_stage1<false, false>), grid, block, 0, s, d, d_f32, d_stride, h, h_stride, mean, rstd,
+                         partials, rows, cols);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(colsum_stage2, dim3((cols + 255) / 256), dim3(256), 0, s, partials, out, chunks, cols);
+  return hipGetLastError();
+}
+
+hipError_t batchsum(const float* d, float* out, int B, long long batch_stride, int n, hipStream_t s) {
+  if (B <= 0 || n <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(batchsum_kernel, dim3((n + 255) / 256), dim3(256), 0, s, d, out, B, batch_stride, n);
+  return hipGetLastError();
+}
+
+hipError_t softmax_rows(const float* sc, bf16* p, int rows, int cols, int ld, hipStream_t s) {
+  if (rows <= 0 || cols <= 0 || ld < cols) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(softmax_rows_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, sc, p, rows, cols, ld);
+  return hipGetLastError();
+}
+
+hipError_t softmax_bwd_rows(const float* dp, const bf16* p, bf16* ds, float scale, int rows, int cols, int ld,
+                            hipStream_t s) {
+  if (rows <= 0 || cols <= 0 || ld < cols) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(softmax_bwd_rows_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, dp, p, ds, scale, rows, cols, ld);
+  return hipGetLastError();
+}
+
+hipError_t xent(const float* logits, const int32_t* y, int B, int C, float* loss, float* dlogits, bf16* dlogits_bf16,
+                int ld16, hipStream_t s) {
+  if (B <= 0 || C <= 0 || ld16 < C) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(xent_kernel, dim3(1), dim3(256), 0, s, logits, y, B, C, loss, dlogits, dlogits_bf16, ld16);
+  return hipGetLastError();
+}
+
+hipError_t embed_assemble(const float* e, const bf16* cls, const bf16* pos, float* h0, int B, int T, int D,
+                          hipStream_t s) {
+  if ((D & 3) || !al16(e) || !al8(cls) || !al8(pos) || !al16(h0)) return hipErrorInvalidValue;
+  const long long n = (long long)B * T * (D / 4);
+  hipLaunchKernelGGL(embed_assemble_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, e, cls, pos, h0, B, T, D);
+  return hipGetLastError();
+}
+
+hipError_t gather_patch_rows(const float* d, bf16* out, int B, int T, int D, hipStream_t s) {
+  if ((D & 3) || !al16(d) || !al8(out)) return hipErrorInvalidValue;
+  const long long n = (long long)B * (T - 1) * (D / 4);
+  hipLaunchKernelGGL(gather_patch_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, d, out, B, T, D);
+  return hipGetLastError();
+}
+
+hipError_t fill_zero(void* p, size_t bytes, hipStream_t s) {
+  if (!al16(p)) return hipErrorInvalidValue;
+  if (bytes == 0) return hipSuccess;
+  const size_t n16 = bytes / 16, ntail = bytes % 16;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  if (blocks == 0) blocks = 1;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (uint4*)p, n16,
+                     (unsigned char*)p + n16 * 16, ntail);
+  return hipGetLastError();
+}
+
+hipError_t cast_bf16(const float* in, bf16* out, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, in, out, n);
+  return hipGetLastError();
+}
+
+}  // namespace et

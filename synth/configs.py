@@ -59,7 +59,7 @@ CONFIGS = {
     "mlp5": MLPConfig("mlp5", (6, 6, 6, 6, 6, 3), 4),
     "vit_tiny": ViTConfig("vit_tiny", 2, 5, 12, 16, 2, 32, 2, 7),
     # spans several GEMM tiles with ragged tails in every dimension
-    "vit_small": ViTConfig("vit_small", 3, 197, 200, 192, 3, 320, 2, 50),
+    "vit_small": ViTConfig("vit_small", 3, 197, 200, 192, 3, 320, 2, 56),
     "vit_mid": ViTConfig("vit_mid", 5, 197, 768, 384, 6, 1536, 3, 200),
 }
 

@@ -1,0 +1,78 @@
+"""et_select (host code of the library, runs without a GPU) against the oracle: bit-identical
+masks on identical inputs, by enumeration for N <= 16 and by the paper's recurrence beyond."""
+import numpy as np
+import pytest
+
+from oracle import select as osel
+from paper_2312_14227_amd import binding as et
+from test_oracle_select import _random_instance
+
+
+def _lib(inst):
+    imp, t_dw, t_dy, t_fwd, rho, Tq = inst
+    return et.et_select(imp, t_dw, t_dy, t_fwd, rho, Tq)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_masks_match_enumeration(seed):
+    rng = np.random.default_rng(1000 + seed)
+    for _ in range(500):
+        inst = _random_instance(rng, int(rng.integers(1, 15)))
+        want = osel.select_enumerate(*inst)
+        st, mask, pred = _lib(inst)
+        assert st == want["status"], inst
+        assert list(mask) == list(want["mask"]), inst
+        assert pred == want["predicted_ns"]
+
+
+def test_sixteen_tensors_enumerated():
+    rng = np.random.default_rng(77)
+    for _ in range(12):
+        inst = _random_instance(rng, 16)
+        want = osel.select_enumerate(*inst)
+        st, mask, pred = _lib(inst)
+        assert (st, list(mask), pred) == (want["status"], list(want["mask"]), want["predicted_ns"])
+
+
+def _profile_like(rng, N, scale_ns):
+    """Times shaped like a profiled transformer: matrices cost much more than vectors, vector
+    tensors pass gradients for free."""
+    kind = rng.integers(0, 3, N)
+    t_dw = np.where(kind == 0, rng.integers(20, 80, N), rng.integers(1, 6, N)) * scale_ns
+    t_dy = np.where(kind == 0, rng.integers(20, 120, N), np.where(kind == 1, 0, rng.integers(2, 30, N))) * scale_ns
+    imp = rng.standard_normal(N) * np.exp(rng.standard_normal(N))
+    t_fwd = int(0.5 * (t_dw.sum() + t_dy.sum()))
+    return imp, [int(t) for t in t_dw], [int(t) for t in t_dy], t_fwd
+
+
+@pytest.mark.parametrize("N,Tq", [(40, 500), (152, 1000), (152, 10_000), (296, 10_000)])
+def test_masks_match_the_paper_recurrence_on_large_instances(N, Tq):
+    rng = np.random.default_rng(N + Tq)
+    imp, t_dw, t_dy, t_fwd = _profile_like(rng, N, 1000)
+    for rho in (300_000, 400_000, 500_000, 600_000, 700_000, 1_000_000):
+        want = osel.select_recurrence(imp, t_dw, t_dy, t_fwd, rho, Tq)
+        st, mask, pred = et.et_select(imp, t_dw, t_dy, t_fwd, rho, Tq)
+        assert st == want["status"]
+        assert list(mask) == list(want["mask"]), (N, Tq, rho)
+        assert pred == want["predicted_ns"]
+        if st == et.ET_OK and rho < 1_000_000:
+            # the quantised model is optimistic by at most one unit per charged term
+            assert pred <= rho * osel.t_full(t_fwd, t_dw, t_dy) // 1_000_000 + 2 * N * (sum(t_dw) + sum(t_dy[1:])) // Tq
+
+
+def test_error_paths():
+    assert et.et_select([1.0, 2.0], [5, 5], [5, 5], 1000, 100_000, 0)[0] == et.ET_INFEASIBLE
+    with pytest.raises(et.EtError) as e:
+        et.et_select([1.0, float("nan")], [5, 5], [5, 5], 10, 500_000, 0)
+    assert e.value.status == et.ET_ENAN
+    with pytest.raises(et.EtError) as e:
+        et.et_select([], [], [], 10, 500_000, 0)
+    assert e.value.status == et.ET_EINVAL
+    with pytest.raises(et.EtError) as e:       # nanosecond resolution on a long step: table too large
+        et.et_select([1.0] * 200, [10 ** 8] * 200, [10 ** 8] * 200, 10 ** 9, 900_000, 0)
+    assert e.value.status == et.ET_ENOMEM
+    # all-zero importance and all-zero times are fine
+    st, mask, _ = et.et_select([0.0, 0.0], [0, 0], [0, 0], 0, 500_000, 1000)
+    assert st == et.ET_OK and not mask.any()
+    st, mask, _ = et.et_select([1.0, 2.0], [0, 0], [0, 0], 0, 500_000, 1000)
+    assert st == et.ET_OK and list(mask) == [1, 1]
