@@ -1,0 +1,170 @@
+"""Benchmark of the elastic selective training step on one MI355X.
+
+One "step" = one pass of the whole hot path over one synthetic batch: forward, loss, masked
+backward (weight gradients of the selected tensors, gradient passing down to the input-most
+selected one), masked optimizer update.  The mask is produced the way the method prescribes:
+profile on the device (et_profile), evaluate importance (et_importance), select with the budget
+rho (et_select).  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: selective train steps/s at rho (default 0.5) on the ViT-B-shaped workload,
+the roofline of the dominant kernel (bf16 MFMA GEMM) measured with HIP events inside real steps,
+and the fp64 CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+GEMM_CLASS_NAMES = {0: "gemm_bf16_kernel<forward X*W^T>", 1: "gemm_bf16_kernel<passing dY*W>",
+                    2: "gemm_bf16_kernel<gradient dY^T*X>"}
+
+
+def timed_steps(s, xt, yt, mask, make_opt_fn, n, first_step):
+    import torch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n):
+        s.train_step(xt, yt, mask, make_opt_fn(first_step + i), want_loss=False)
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def cpu_baseline(cfg, mask, sample_batch, opt_kind, hp):
+    """The oracle, as it stands, on a smaller batch of the same workload (seeded like the bench)."""
+    from oracle import nets, optim
+    from synth import make_workload
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    wl = make_workload(cfg, seed=0, batch=sample_batch)
+    W = [w.astype(np.float64) for w in wl.weights]
+    state = [(np.zeros(w.shape), np.zeros(w.shape)) for w in W]
+    t0 = time.perf_counter()
+    r = nets.step(cfg, W, wl.x, wl.y, mask)
+    optim.masked_update(opt_kind, mask, W, state, r["grads"], step=1, **hp)
+    dt = time.perf_counter() - t0
+    steps_per_s = (sample_batch / cfg.batch) / dt
+    return {"value": steps_per_s, "unit": "steps/s", "cores": int(threads), "kind": "oracle",
+            "sample": "one fp64 oracle selective step (same mask, same seed) at batch %d of %d took %.1f s; "
+                      "rate scaled by %d/%d" % (sample_batch, cfg.batch, dt, sample_batch, cfg.batch)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="vit_b")
+    ap.add_argument("--rho", type=float, default=0.5)
+    ap.add_argument("--tq", type=int, default=10000)
+    ap.add_argument("--cpu-sample-batch", type=int, default=64)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % a.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2312_14227_amd import binding as et
+    from paper_2312_14227_amd.session import Session, make_opt
+    from synth import CONFIGS, make_workload
+
+    cfg = CONFIGS[a.config]
+    wl = make_workload(cfg, seed=0)
+    N = len(wl.weights)
+    s = Session(cfg, wl.weights)
+    xt, yt = s.put_input(wl.x, wl.y)
+    snap = s.put_snapshot(wl.snapshot)
+    opt_kind = "adam" if cfg.kind == "vit" else "sgdw"
+    hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, momentum=0.9, wd=5e-4)
+    mk = lambda step: make_opt(opt_kind, step=step, **hp)
+
+    # ---- the method's own pipeline: profile -> importance -> select
+    t_fwd, t_dw, t_dy = s.profile(xt, yt, warmup=3, reps=7)
+    imp = s.importance(xt, yt, snap)
+    t0 = time.perf_counter()
+    status, mask, predicted_ns = et.et_select(imp, t_dw, t_dy, t_fwd, int(round(a.rho * 1e6)), a.tq)
+    t_select_ms = (time.perf_counter() - t0) * 1e3
+    t_full_model_ns = int(t_fwd) + int(t_dw.sum()) + int(t_dy[1:].sum())
+    ones = np.ones(N, dtype=np.uint8)
+
+    # ---- timed region: W warm-up steps, then exactly K selective steps
+    timed_steps(s, xt, yt, mask, mk, a.warmup, 1)
+    dt = timed_steps(s, xt, yt, mask, mk, a.steps, 1 + a.warmup)
+    ms_per_step = dt / a.steps * 1e3
+    # full training for the ratio (same protocol)
+    timed_steps(s, xt, yt, ones, mk, max(2, a.warmup // 2), 1)
+    dt_full = timed_steps(s, xt, yt, ones, mk, a.steps, 1)
+    full_ms = dt_full / a.steps * 1e3
+
+    # ---- kernel classes inside the same selective steps, HIP events on the launch stream
+    et.et_kernel_timing(s.ctx, 1)
+    timed_steps(s, xt, yt, mask, mk, a.steps, 1)
+    classes = {c: et.et_kernel_timing_read(s.ctx, c) for c in range(5)}
+    et.et_kernel_timing(s.ctx, 1)
+    s.importance(xt, yt, snap)
+    imp_n, imp_ns, imp_bytes = et.et_kernel_timing_read(s.ctx, 3)
+    et.et_kernel_timing(s.ctx, 0)
+
+    gemm = {c: classes[c] for c in (0, 1, 2) if classes[c][0] > 0}
+    roofline = None
+    by_kernel = {}
+    for c, (n, ns, work) in gemm.items():
+        by_kernel[GEMM_CLASS_NAMES[c]] = {"launches_per_step": n / a.steps, "avg_us": ns / n / 1e3,
+                                          "tflops": work / ns / 1e3, "frac": work / ns / 1e3 / PEAK_BF16_TFLOPS}
+    if gemm:
+        dom = max(gemm, key=lambda c: gemm[c][1])
+        n, ns, work = gemm[dom]
+        roofline = {"bound": "mfma", "kernel": GEMM_CLASS_NAMES[dom], "achieved": work / ns / 1e3,
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": work / ns / 1e3 / PEAK_BF16_TFLOPS,
+                    "traffic": None, "avg_launch_us": ns / n / 1e3, "flops_per_launch": work / n,
+                    "launches_per_step": n / a.steps}
+        all_ns = sum(v[1] for v in gemm.values())
+        all_work = sum(v[2] for v in gemm.values())
+        roofline["all_gemm_tflops"] = all_work / all_ns / 1e3
+        roofline["all_gemm_frac"] = all_work / all_ns / 1e3 / PEAK_BF16_TFLOPS
+        roofline["gemm_ms_per_step"] = all_ns / a.steps / 1e6
+    upd_n, upd_ns, upd_bytes = classes[4]
+
+    out = {
+        "metric": "selective train steps/sec at rho=%.2g (%s)" % (a.rho, cfg.name),
+        "value": a.steps / dt, "unit": "steps/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": "%s: batch %d, %d tensors, rho=%.2g, Tq=%d, Adam lr 1e-4" % (
+            cfg.name, cfg.batch, N, a.rho, a.tq) if cfg.kind == "vit" else "%s: batch %d, %d tensors, rho=%.2g" % (
+            cfg.name, cfg.batch, N, a.rho)},
+        "roofline": roofline,
+        "cpu_baseline": None,
+        "selected_tensors": int(mask.sum()), "first_selected": int(np.argmax(mask)) if mask.any() else None,
+        "select_status": int(status), "t_select_ms": t_select_ms,
+        "full_ms_per_step": full_ms, "selective_over_full": ms_per_step / full_ms,
+        "predicted_ms": predicted_ns / 1e6, "predicted_full_ms": t_full_model_ns / 1e6,
+        "measured_over_predicted": ms_per_step / (predicted_ns / 1e6),
+        "full_measured_over_predicted": full_ms / (t_full_model_ns / 1e6),
+        "t_fwd_ms": t_fwd / 1e6,
+        "gemm_by_kernel": by_kernel,
+        "importance": {"gbps": imp_bytes / imp_ns if imp_ns else None, "us": imp_ns / 1e3, "bytes": imp_bytes,
+                       "frac_of_hbm_peak": imp_bytes / imp_ns / PEAK_HBM_GBS if imp_ns else None},
+        "update": {"gbps": upd_bytes / upd_ns if upd_ns else None, "us": upd_ns / max(upd_n, 1) / 1e3,
+                   "frac_of_hbm_peak": upd_bytes / upd_ns / PEAK_HBM_GBS if upd_ns else None},
+    }
+    s.close()
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, mask, min(a.cpu_sample_batch, cfg.batch), opt_kind, hp)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -7,6 +7,8 @@ import ctypes as C
 import os
 
 import numpy as np
+import torch  # noqa: F401  (first: libet.so must bind to the HIP runtime torch has already loaded, so
+#                            that the device pointers torch hands out and our launches share one runtime)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libet.so")
@@ -56,6 +58,9 @@ def _load():
                                 C.c_uint32, C.POINTER(C.c_uint8), C.POINTER(u64)]),
         "et_train_step": (C.c_int, [vp, vp, vp, C.POINTER(C.c_uint8), C.POINTER(et_opt), C.POINTER(C.c_float)]),
         "et_last_launch_counts": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]),
+        "et_kernel_timing": (C.c_int, [vp, i32]),
+        "et_kernel_timing_read": (C.c_int, [vp, i32, C.POINTER(u64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+        "et_last_hip_error": (C.c_char_p, [vp]),
         "et_strerror": (C.c_char_p, [C.c_int]),
         "et_debug_gemm_bf16": (C.c_int, [vp, vp, vp] + [C.c_int] * 9 + [C.c_float, vp, vp, C.c_int, vp, C.c_int, vp]),
     }
@@ -68,15 +73,21 @@ def _load():
 _lib = _load()
 EXPORTS = ["et_create", "et_destroy", "et_num_tensors", "et_tensor_info", "et_workspace_bytes", "et_state_slots",
            "et_bind", "et_profile", "et_importance", "et_select", "et_train_step", "et_last_launch_counts",
-           "et_strerror", "et_debug_gemm_bf16"]
+           "et_kernel_timing", "et_kernel_timing_read", "et_last_hip_error", "et_strerror", "et_debug_gemm_bf16"]
 
 
 def strerror(status):
     return _lib.et_strerror(int(status)).decode()
 
 
-def _check(status, where, allow=()):
+def et_last_hip_error(ctx):
+    return _lib.et_last_hip_error(ctx).decode()
+
+
+def _check(status, where, allow=(), ctx=None):
     if status != ET_OK and status not in allow:
+        if status == ET_EHIP and ctx is not None:
+            where = "%s [%s]" % (where, et_last_hip_error(ctx))
         raise EtError(status, where)
     return status
 
@@ -135,7 +146,7 @@ def et_state_slots(ctx):
 def et_bind(ctx, w_dev, opt_state_dev, grad_dev, workspace_dev, workspace_bytes):
     st = _ptr_array(opt_state_dev) if opt_state_dev is not None else None
     _check(_lib.et_bind(ctx, _ptr_array(w_dev), st, _ptr_array(grad_dev), C.c_void_p(workspace_dev), workspace_bytes),
-           "et_bind")
+           "et_bind", ctx=ctx)
 
 
 def et_profile(ctx, x_dev, y_dev, warmup, reps):
@@ -143,7 +154,7 @@ def et_profile(ctx, x_dev, y_dev, warmup, reps):
     t_fwd = C.c_uint64()
     t_dw, t_dy = (C.c_uint64 * n)(), (C.c_uint64 * n)()
     _check(_lib.et_profile(ctx, C.c_void_p(x_dev), C.c_void_p(y_dev), warmup, reps, C.byref(t_fwd), t_dw, t_dy),
-           "et_profile")
+           "et_profile", ctx=ctx)
     return t_fwd.value, np.array(t_dw[:], dtype=np.uint64), np.array(t_dy[:], dtype=np.uint64)
 
 
@@ -151,7 +162,7 @@ def et_importance(ctx, x_dev, y_dev, w_snapshot_dev):
     n = et_num_tensors(ctx)
     out = (C.c_double * n)()
     _check(_lib.et_importance(ctx, C.c_void_p(x_dev), C.c_void_p(y_dev), _ptr_array(w_snapshot_dev), out),
-           "et_importance")
+           "et_importance", ctx=ctx)
     return np.array(out[:], dtype=np.float64)
 
 
@@ -175,7 +186,7 @@ def et_train_step(ctx, x_dev, y_dev, mask, opt=None, want_loss=True):
     loss = C.c_float()
     _check(_lib.et_train_step(ctx, C.c_void_p(x_dev), C.c_void_p(y_dev), m.ctypes.data_as(C.POINTER(C.c_uint8)),
                               C.byref(opt) if opt is not None else None, C.byref(loss) if want_loss else None),
-           "et_train_step")
+           "et_train_step", ctx=ctx)
     return loss.value if want_loss else None
 
 
@@ -183,6 +194,17 @@ def et_last_launch_counts(ctx):
     f, b, u = C.c_int32(), C.c_int32(), C.c_int32()
     _check(_lib.et_last_launch_counts(ctx, C.byref(f), C.byref(b), C.byref(u)), "et_last_launch_counts")
     return f.value, b.value, u.value
+
+
+def et_kernel_timing(ctx, enable):
+    _check(_lib.et_kernel_timing(ctx, int(enable)), "et_kernel_timing", ctx=ctx)
+
+
+def et_kernel_timing_read(ctx, kernel_class):
+    """(launches, total_ns, work) of one kernel class since timing was enabled."""
+    n, ns, w = C.c_uint64(), C.c_double(), C.c_double()
+    _check(_lib.et_kernel_timing_read(ctx, kernel_class, C.byref(n), C.byref(ns), C.byref(w)), "et_kernel_timing_read", ctx=ctx)
+    return n.value, ns.value, w.value
 
 
 def et_debug_gemm_bf16(A, B, Cp, M, N, K, lda, ldb, ldc, a_t, b_t, c_f32, alpha=1.0, bias=0, residual=0, split_k=1,

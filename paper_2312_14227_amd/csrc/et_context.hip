@@ -39,6 +39,12 @@ struct Scope {  // one timed region of the profile
   hipEvent_t e0, e1;
 };
 
+struct KernelRecord {  // one timed kernel launch (measurement support)
+  int cls;
+  double work;
+  hipEvent_t e0, e1;
+};
+
 struct VitBlockBufs {
   float *h_in, *h_mid, *mean1, *rstd1, *mean2, *rstd2;
   bf16 *a1, *qkv, *p, *o, *a2, *u, *ga;
@@ -94,6 +100,12 @@ struct et_ctx {
   std::vector<hipEvent_t> event_pool;
   size_t events_used = 0;
   hipError_t hip_err = hipSuccess;
+
+  // per-kernel-class timing
+  bool ktiming = false;
+  std::vector<KernelRecord> krecs;
+  std::vector<hipEvent_t> kevent_pool;
+  size_t kevents_used = 0;
 };
 
 namespace {
@@ -368,8 +380,38 @@ et::GemmDesc linear_dw(et_ctx* c, const bf16* dY, int ldy, const bf16* X, int ld
   return g;
 }
 
+// bracket a launch with events while per-kernel timing is on
+struct KernelTimer {
+  et_ctx* c;
+  bool on = false;
+  size_t idx = 0;
+  KernelTimer(et_ctx* ctx, int cls, double work) : c(ctx) {
+    if (!c->ktiming) return;
+    KernelRecord r;
+    r.cls = cls;
+    r.work = work;
+    for (hipEvent_t* ev : {&r.e0, &r.e1}) {
+      if (c->kevents_used == c->kevent_pool.size()) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) { c->hip_err = hipErrorOutOfMemory; return; }
+        c->kevent_pool.push_back(e);
+      }
+      *ev = c->kevent_pool[c->kevents_used++];
+    }
+    (void)hipEventRecord(r.e0, c->stream);
+    idx = c->krecs.size();
+    c->krecs.push_back(r);
+    on = true;
+  }
+  ~KernelTimer() {
+    if (on) (void)hipEventRecord(c->krecs[idx].e1, c->stream);
+  }
+};
+
 int launch_gemm(et_ctx* c, const et::GemmDesc& g) {
   int n = 0;
+  const int cls = g.a_t ? 2 : (g.b_t ? 1 : 0);
+  KernelTimer kt(c, cls, 2.0 * g.M * g.N * (double)g.K * g.z_outer * g.z_inner);
   hipError_t e = et::gemm_bf16(g, c->stream, &n);
   if (e != hipSuccess) { c->hip_err = e; return ET_EHIP; }
   c->launches[c->cur_phase] += n;
@@ -680,6 +722,12 @@ int run_update(et_ctx* c, const uint8_t* mask, const et_opt* opt, bool dry) {
   p.dry = dry ? 1 : 0;
   c->cur_phase = PH_UPD;
   Region r(c, PH_UPD, -1);
+  double sel_elems = 0.0;
+  for (size_t i = 0; i < N; i++)
+    if (mask[i]) sel_elems += (double)c->tensors[i].numel;
+  // bytes per selected element: read g + fp32 weight + moments, write fp32 weight + moments (+ bf16 copy)
+  const double per_elem = (opt->kind == ET_ADAM ? 28.0 : 20.0) + (c->bf16_model ? 2.0 : 0.0);
+  KernelTimer kt(c, 4, sel_elems * per_elem);
   ET_K(1, et::masked_update(c->upd_segs_dev, (int)c->n_segs, c->bf16_model, sel, p, c->stream));
   return ET_OK;
 }
@@ -705,6 +753,8 @@ const char* et_strerror(int status) {
     default: return "unknown status";
   }
 }
+
+const char* et_last_hip_error(const et_ctx* c) { return c ? hipGetErrorString(c->hip_err) : "no context"; }
 
 int et_create(const et_model_desc* desc, void* hip_stream, et_ctx** out) {
   if (!desc || !out) return ET_EINVAL;
@@ -738,6 +788,7 @@ int et_create(const et_model_desc* desc, void* hip_stream, et_ctx** out) {
 int et_destroy(et_ctx* c) {
   if (!c) return ET_EINVAL;
   for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->kevent_pool) (void)hipEventDestroy(e);
   delete c;
   return ET_OK;
 }
@@ -857,6 +908,34 @@ int et_last_launch_counts(const et_ctx* c, int32_t* forward, int32_t* backward, 
   return ET_OK;
 }
 
+int et_kernel_timing(et_ctx* c, int32_t enable) {
+  if (!c) return ET_EINVAL;
+  ET_HIP(hipStreamSynchronize(c->stream));
+  c->ktiming = enable != 0;
+  c->krecs.clear();
+  c->kevents_used = 0;
+  return ET_OK;
+}
+
+int et_kernel_timing_read(et_ctx* c, int32_t kernel_class, uint64_t* launches, double* total_ns, double* work) {
+  if (!c || kernel_class < 0 || kernel_class >= ET_NUM_KERNEL_CLASSES) return ET_EINVAL;
+  ET_HIP(hipStreamSynchronize(c->stream));
+  uint64_t n = 0;
+  double ns = 0.0, w = 0.0;
+  for (const KernelRecord& r : c->krecs) {
+    if (r.cls != kernel_class) continue;
+    float ms = 0.f;
+    ET_HIP(hipEventElapsedTime(&ms, r.e0, r.e1));
+    n++;
+    ns += (double)ms * 1e6;
+    w += r.work;
+  }
+  if (launches) *launches = n;
+  if (total_ns) *total_ns = ns;
+  if (work) *work = w;
+  return ET_OK;
+}
+
 int et_importance(et_ctx* c, const void* x_dev, const int32_t* y_dev, void* const* w_snapshot_dev,
                   double* importance_host) {
   if (!c || !x_dev || !y_dev || !w_snapshot_dev || !importance_host) return ET_EINVAL;
@@ -878,6 +957,9 @@ int et_importance(et_ctx* c, const void* x_dev, const int32_t* y_dev, void* cons
   ET_HIP(hipMemcpyAsync(c->imp_segs_dev, c->imp_segs_host.data(), sizeof(et::TensorSeg) * c->n_segs,
                         hipMemcpyHostToDevice, c->stream));
   c->cur_phase = PH_DW;
+  double imp_bytes = 0.0;
+  for (size_t i = 0; i < N; i++) imp_bytes += (double)c->tensors[i].numel * (4.0 + 2.0 * wsize);
+  KernelTimer kt(c, 3, imp_bytes);
   ET_K(2, et::importance_reduce(c->imp_segs_dev, (int)c->n_segs, c->seg_begin_dev, (int)N, c->bf16_model,
                                 c->imp_partial_dev, c->imp_out_dev, c->stream));
   ET_HIP(hipMemcpyAsync(importance_host, c->imp_out_dev, sizeof(double) * N, hipMemcpyDeviceToHost, c->stream));

@@ -1,0 +1,53 @@
+"""Writes tests/golden/<config>_seed<seed>.npz: the oracle's results at the full size of a
+benchmark workload, sampled so that the file stays small.  Calls only the oracle and the seeded
+generators.  Usage:  python tests/golden/make_full_size_golden.py vit_b [seed] [batch]
+
+Stored per tensor k: 512 seeded element indices idx_k, the oracle gradient at those elements
+g_k (all tensors selected; by the invariant of selective training these are also the values for
+any mask that selects k), the gradient's L2 norm, and Eq. 2's importance with its magnitude sum
+for the workload's snapshot.  Also the loss and the logits.
+"""
+import os
+import sys
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+
+from oracle import importance as oimp  # noqa: E402
+from synth import CONFIGS, make_workload  # noqa: E402
+
+SAMPLES = 512
+
+
+def sample_indices(k, numel, seed):
+    rng = np.random.default_rng([seed, 900 + k])
+    if numel <= SAMPLES:
+        return np.arange(numel, dtype=np.int64)
+    return np.sort(rng.choice(numel, size=SAMPLES, replace=False)).astype(np.int64)
+
+
+def main():
+    name = sys.argv[1]
+    seed = int(sys.argv[2]) if len(sys.argv) > 2 else 0
+    cfg = CONFIGS[name]
+    batch = int(sys.argv[3]) if len(sys.argv) > 3 else cfg.batch
+    wl = make_workload(cfg, seed=seed, batch=batch)
+    I, r = oimp.importance(cfg, wl.weights, wl.snapshot, wl.x, wl.y)
+    A = oimp.abs_importance_from_grads(r["grads"], wl.weights, wl.snapshot)
+    out = dict(loss=np.float64(r["loss"]), logits=r["logits"], importance=I, abs_importance=A,
+               batch=np.int64(batch), seed=np.int64(seed),
+               gnorm=np.array([np.linalg.norm(g.ravel()) for g in r["grads"]]))
+    for k, g in enumerate(r["grads"]):
+        idx = sample_indices(k, g.size, seed)
+        out["idx_%d" % k] = idx.astype(np.int32)
+        out["g_%d" % k] = g.ravel()[idx]
+    tag = name if batch == cfg.batch else "%s_b%d" % (name, batch)
+    path = os.path.join(ROOT, "tests", "golden", "%s_seed%d.npz" % (tag, seed))
+    np.savez_compressed(path, **out)
+    print("wrote", path, os.path.getsize(path), "bytes; loss", r["loss"])
+
+
+if __name__ == "__main__":
+    main()

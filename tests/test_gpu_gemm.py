@@ -1,0 +1,97 @@
+"""bf16 MFMA GEMM kernel against a float64 matmul of the same bf16 inputs, through the C ABI."""
+import numpy as np
+import pytest
+
+from synth import bf16_round
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # (M, N, K, a_t, b_t) : several tiles and ragged tails in every dimension
+    (197, 197, 64, 0, 0), (197, 64, 197, 0, 1), (197, 64, 197, 1, 1), (200, 768, 64, 1, 1),
+    (300, 200, 136, 0, 0), (300, 136, 200, 0, 1), (136, 200, 300, 1, 1),
+    (1000, 768, 768, 0, 0), (1000, 768, 3072, 0, 1), (768, 768, 5000, 1, 1), (64, 200, 768, 0, 0),
+    (3, 8, 8, 0, 0), (129, 129 + 7, 72, 0, 1),
+]
+
+
+def _run(M, N, K, a_t, b_t, c_f32, bias, residual, split_k, tile, seed):
+    import torch
+    from paper_2312_14227_amd import binding as et
+    rng = np.random.default_rng(seed)
+    K8, M8, N8 = (K + 7) // 8 * 8, (M + 7) // 8 * 8, (N + 7) // 8 * 8
+    A = np.zeros((K, M8) if a_t else (M, K8), dtype=np.float32)
+    B = np.zeros((K, N8) if b_t else (N, K8), dtype=np.float32)
+    if a_t:
+        A[:, :M] = bf16_round(rng.standard_normal((K, M)).astype(np.float32))
+    else:
+        A[:, :K] = bf16_round(rng.standard_normal((M, K)).astype(np.float32))
+    if b_t:
+        B[:, :N] = bf16_round(rng.standard_normal((K, N)).astype(np.float32))
+    else:
+        B[:, :K] = bf16_round(rng.standard_normal((N, K)).astype(np.float32))
+    Am = A[:, :M].T.astype(np.float64) if a_t else A[:, :K].astype(np.float64)
+    Bm = B[:, :N].T.astype(np.float64) if b_t else B[:, :K].astype(np.float64)
+    ref = Am @ Bm.T
+    scale = np.abs(Am) @ np.abs(Bm).T
+    dev = "cuda:0"
+    At = torch.from_numpy(A).to(dev).to(torch.bfloat16)
+    Bt = torch.from_numpy(B).to(dev).to(torch.bfloat16)
+    ldc = N8 if not split_k > 1 else N
+    Ct = torch.full((M, ldc), float("nan"), device=dev, dtype=torch.float32 if c_f32 else torch.bfloat16)
+    bias_t = res_t = None
+    if bias:
+        b = bf16_round(rng.standard_normal(N).astype(np.float32))
+        bias_t = torch.from_numpy(b).to(dev).to(torch.bfloat16)
+        ref = ref + b.astype(np.float64)
+    if residual:
+        r = rng.standard_normal((M, N)).astype(np.float32)
+        res_t = torch.from_numpy(r).to(dev)
+        ref = ref + r.astype(np.float64)
+    part = torch.empty(M * N * split_k, device=dev, dtype=torch.float32) if split_k > 1 else None
+    st = et.et_debug_gemm_bf16(At.data_ptr(), Bt.data_ptr(), Ct.data_ptr(), M, N, K, A.shape[1], B.shape[1], ldc, a_t,
+                               b_t, c_f32, 1.0, bias_t.data_ptr() if bias else 0, res_t.data_ptr() if residual else 0,
+                               split_k, part.data_ptr() if part is not None else 0, tile,
+                               torch.cuda.current_stream().cuda_stream)
+    assert st == 0
+    torch.cuda.synchronize()
+    got = Ct.float().cpu().numpy().astype(np.float64)[:, :N]
+    # fp32 accumulation of exact bf16 products, then one rounding of the output
+    bound = 2e-6 * scale * np.sqrt(K) + 1e-6 + (0 if c_f32 else 2.0 ** -8 * np.abs(ref))
+    bad = np.abs(got - ref) > bound
+    assert not bad.any(), (int(bad.sum()), float(np.abs(got - ref).max()))
+    if ldc > N and not c_f32:
+        assert torch.isnan(Ct[:, N:].float()).all()        # nothing written outside the N columns
+
+
+@pytest.mark.parametrize("M,N,K,a_t,b_t", CASES)
+def test_gemm_layouts_fp32_out(M, N, K, a_t, b_t):
+    _run(M, N, K, a_t, b_t, 1, False, False, 1, 0, seed=M + N + K)
+
+
+@pytest.mark.parametrize("M,N,K,a_t,b_t", CASES[:8])
+def test_gemm_bf16_out_bias_residual(M, N, K, a_t, b_t):
+    _run(M, N, K, a_t, b_t, 0, True, True, 1, 0, seed=7 + M)
+
+
+@pytest.mark.parametrize("tile", [1, 3])
+@pytest.mark.parametrize("M,N,K,a_t,b_t", [(300, 200, 136, 0, 0), (300, 136, 200, 0, 1), (136, 200, 300, 1, 1)])
+def test_gemm_every_tile_shape(M, N, K, a_t, b_t, tile):
+    _run(M, N, K, a_t, b_t, 1, True, False, 1, tile, seed=tile)
+
+
+@pytest.mark.parametrize("split", [2, 5, 16])
+def test_gemm_split_k_weight_gradient(split):
+    _run(768, 200, 5000, 1, 1, 1, False, False, split, 0, seed=split)
+    _run(136, 200, 300, 1, 1, 1, False, False, split, 0, seed=split + 1)
+
+
+def test_gemm_rejects_bad_arguments():
+    import torch
+    from paper_2312_14227_amd import binding as et
+    t = torch.zeros(64 * 64, device="cuda:0", dtype=torch.bfloat16)
+    c = torch.zeros(64 * 64, device="cuda:0", dtype=torch.float32)
+    assert et.et_debug_gemm_bf16(t.data_ptr(), t.data_ptr(), c.data_ptr(), 16, 16, 16, 12, 16, 16, 0, 0, 1) == et.ET_EINVAL
+    assert et.et_debug_gemm_bf16(t.data_ptr() + 2, t.data_ptr(), c.data_ptr(), 16, 16, 16, 16, 16, 16, 0, 0, 1) == et.ET_EINVAL
+    assert et.et_debug_gemm_bf16(t.data_ptr(), t.data_ptr(), c.data_ptr(), 16, 16, 16, 16, 16, 16, 1, 0, 1) == et.ET_EINVAL
+    assert et.et_debug_gemm_bf16(0, t.data_ptr(), c.data_ptr(), 16, 16, 16, 16, 16, 16, 0, 0, 1) == et.ET_EINVAL

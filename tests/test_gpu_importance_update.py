@@ -1,0 +1,127 @@
+"""Importance (Eq. 2), the masked optimizer update, the profiler and the selection on
+GPU-produced inputs, against the oracle."""
+import numpy as np
+import pytest
+
+from gpu_util import rel_l2, tol_for
+from oracle import importance as oimp
+from oracle import optim as oopt
+from oracle import select as osel
+from synth import CONFIGS, make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def _session(cfg, wl, **kw):
+    from paper_2312_14227_amd.session import Session
+    return Session(cfg, wl.weights, **kw)
+
+
+@pytest.mark.parametrize("name", ["mlp", "vit_small"])
+def test_importance_matches_oracle(name):
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg, seed=0, init="random")
+    N = len(wl.weights)
+    I_ref, r = oimp.importance(cfg, wl.weights, wl.snapshot, wl.x, wl.y)
+    A_ref = oimp.abs_importance_from_grads(r["grads"], wl.weights, wl.snapshot)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    snap = s.put_snapshot(wl.snapshot)
+    I = s.importance(xt, yt, snap)
+    tol = tol_for(cfg)
+    worst = 0.0
+    for k in range(N):
+        # I_k is a cancelling signed sum, so its error is judged against the larger of |I_k| and a
+        # tenth of the sum of magnitudes A_k = sum |g dw| (a gradient error of relative size tol
+        # moves I_k by at most tol * |g| |dw| ~ 1.5 tol A_k, and by far less when uncorrelated)
+        bound = tol * max(abs(I_ref[k]), 0.1 * A_ref[k])
+        worst = max(worst, abs(I[k] - I_ref[k]) / bound)
+        assert abs(I[k] - I_ref[k]) <= bound, (wl.names[k], I[k], I_ref[k], A_ref[k])
+    print("worst importance error / bound: %.3f" % worst)
+    # the reduction in isolation: same gradients (read back from the device) on both sides
+    g_dev = [s.grads_host(k).reshape(wl.weights[k].shape) for k in range(N)]
+    I_iso = oimp.importance_from_grads(g_dev, wl.weights, wl.snapshot)
+    A_iso = oimp.abs_importance_from_grads(g_dev, wl.weights, wl.snapshot)
+    for k in range(N):
+        assert abs(I[k] - I_iso[k]) <= 1e-5 * A_iso[k] + 1e-300, (wl.names[k], I[k], I_iso[k])
+    # a second call gives the same bits (fixed reduction order)
+    assert np.array_equal(I, s.importance(xt, yt, snap))
+    s.close()
+
+
+@pytest.mark.parametrize("name,kind", [("mlp", "sgdw"), ("vit_small", "adam"), ("vit_small", "sgdw")])
+def test_masked_update(name, kind):
+    import torch
+    from paper_2312_14227_amd.session import make_opt
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg, seed=1, init="random")
+    N = len(wl.weights)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    rng = np.random.default_rng(5)
+    mask = (rng.random(N) < 0.5).astype(np.uint8)
+    mask[0], mask[N - 1] = 1, 0
+    # the C ABI carries the hyper-parameters as float32: give the oracle the same values
+    hp = {k: float(np.float32(v)) for k, v in dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, momentum=0.9,
+                                                    wd=5e-2).items()}
+    w_ref = [w.astype(np.float64) for w in wl.weights]
+    st_ref = [(np.zeros(w.shape), np.zeros(w.shape)) if kind == "adam" else (np.zeros(w.shape),) for w in wl.weights]
+    bf16 = cfg.dtype == "bf16"
+    for step in (1, 2, 3):
+        before_w = [w.clone() for w in s.w]
+        before_s = [[t.clone() for t in slots] for slots in s.state]
+        s.train_step(xt, yt, mask, make_opt(kind, step=step, **hp))
+        torch.cuda.synchronize()
+        assert s.launch_counts()[2] == 1
+        grads = [s.grads_host(k).reshape(wl.weights[k].shape) if mask[k] else None for k in range(N)]
+        w_ref, st_ref = oopt.masked_update(kind, mask, w_ref, st_ref, grads, step=step, **hp)
+        for k in range(N):
+            if not mask[k]:
+                assert torch.equal(s.w[k], before_w[k]), wl.names[k]
+                for a, b in zip(s.state[k], before_s[k]):
+                    assert torch.equal(a, b), wl.names[k]
+                continue
+            fp = (s.state[k][0] if bf16 else s.w[k]).cpu().numpy().astype(np.float64).reshape(w_ref[k].shape)
+            np.testing.assert_allclose(fp, w_ref[k], rtol=2e-6, atol=step * 2e-3 * hp["lr"], err_msg=wl.names[k])
+            m_dev = s.state[k][1 if bf16 else 0].cpu().numpy().astype(np.float64).reshape(w_ref[k].shape)
+            np.testing.assert_allclose(m_dev, st_ref[k][0], rtol=1e-5, atol=1e-6 * np.abs(st_ref[k][0]).max() + 1e-30,
+                                       err_msg=wl.names[k])
+            if kind == "adam":
+                v_dev = s.state[k][2 if bf16 else 1].cpu().numpy().astype(np.float64).reshape(w_ref[k].shape)
+                np.testing.assert_allclose(v_dev, st_ref[k][1], rtol=1e-5, atol=1e-6 * np.abs(st_ref[k][1]).max() + 1e-30,
+                                           err_msg=wl.names[k])
+            if bf16:     # the bf16 copy is the rounded master weight
+                assert torch.equal(s.w[k].reshape(-1), s.state[k][0].to(torch.bfloat16)), wl.names[k]
+    s.close()
+
+
+@pytest.mark.parametrize("name", ["mlp", "vit_small"])
+def test_profile_and_select_bit_exact_on_device_inputs(name):
+    from paper_2312_14227_amd import binding as et
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg, seed=0, init="random")
+    N = len(wl.weights)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    w_before = [w.clone() for w in s.w]
+    t_fwd, t_dw, t_dy = s.profile(xt, yt, warmup=1, reps=3)
+    import torch
+    for a, b in zip(w_before, s.w):
+        assert torch.equal(a, b)                       # profiling leaves the weights alone
+    assert t_fwd > 0 and (t_dw > 0).all()
+    names = wl.names
+    for k in range(N):
+        leaf = names[k].split(".")[-1]
+        if cfg.kind == "vit" and (leaf == "b" or names[k] in ("pos", "patch.b")):
+            assert t_dy[k] == 0, names[k]              # biases and shifts pass gradients for free
+    assert t_dy[0] == 0                                 # never passed
+    snap = s.put_snapshot(wl.snapshot)
+    I = s.importance(xt, yt, snap)
+    for rho in (300_000, 400_000, 500_000, 600_000, 700_000, 1_000_000):
+        for Tq in (1000, 10_000):
+            st, mask, pred = et.et_select(I, t_dw, t_dy, t_fwd, rho, Tq)
+            want = osel.select(I, t_dw, t_dy, t_fwd, rho, Tq)
+            assert st == want["status"]
+            assert list(mask) == list(want["mask"]), (rho, Tq)
+            assert pred == want["predicted_ns"]
+    s.close()
