@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--tq", type=int, default=10000)
     ap.add_argument("--cpu-sample-batch", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB plain copy kernel (known traffic, for scaling hardware counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % a.gpus,
@@ -160,6 +162,11 @@ def main():
         "update": {"gbps": upd_bytes / upd_ns if upd_ns else None, "us": upd_ns / max(upd_n, 1) / 1e3,
                    "frac_of_hbm_peak": upd_bytes / upd_ns / PEAK_HBM_GBS if upd_ns else None},
     }
+    if a.copy_calibration:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        assert et.et_debug_copy(dst.data_ptr(), src.data_ptr(), 1 << 30, torch.cuda.current_stream().cuda_stream) == 0
+        torch.cuda.synchronize()
     s.close()
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, mask, min(a.cpu_sample_batch, cfg.batch), opt_kind, hp)

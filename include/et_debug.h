@@ -13,13 +13,19 @@ extern "C" {
 /* bf16 MFMA GEMM used for the forward product, the error-gradient passing and the weight
  * gradient (Section 5.1):  C[i][j] = alpha * sum_k A(i,k) * B(j,k) + bias[j] + residual[i][j]
  *   A(i,k) = a_t ? A[k*lda + i] : A[i*lda + k],   B(j,k) = b_t ? B[k*ldb + j] : B[j*ldb + k].
- * All pointers are device pointers; A, B, bias (nullable) bf16; residual (nullable) fp32 [M][N];
+ * All pointers are device pointers; A, B, bias (nullable) bf16; residual (nullable) fp32 [M][ldc];
  * C is fp32 if c_f32 else bf16, leading dimension ldc.  split_k > 1 needs c_f32, ldc == N and
- * `partials` with M*N*split_k floats.  tile: 0 = automatic, otherwise a tile id of the library.
+ * `partials` with M*N*split_k floats.  A residual needs c_f32 and a_t = b_t = 0.  tile: 0 =
+ * automatic, otherwise a tile id of the library (1, 3: register-staged 128x128, 128x64; 5, 7:
+ * direct-to-LDS 256x256, 256x128); adding 256 runs the main loop without storing (tuning).
  * stream: hipStream_t.  Returns 0, or -1 for a rejected argument, -3 for a HIP error. */
 int et_debug_gemm_bf16(const void* A, const void* B, void* C, int M, int N, int K, int lda, int ldb, int ldc,
                        int a_t, int b_t, int c_f32, float alpha, const void* bias, const float* residual,
                        int split_k, float* partials, int tile, void* stream);
+
+/* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16; 16-byte aligned device
+ * pointers).  Used to calibrate hardware traffic counters against a known size. */
+int et_debug_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -175,11 +175,13 @@ struct Region {
   }
 };
 
+// split of the reduction dimension for a weight gradient [Mo][No] reduced over K rows: as many
+// chunks as keep one wave of 256x256 tiles on the 256 CUs, each chunk at least 4 slices of 64
 int split_for(int Mo, int No, int K) {
-  const int tiles = ((Mo + 127) / 128) * ((No + 127) / 128);
-  int s = (512 + tiles - 1) / tiles;
+  const int tiles = ((Mo + 255) / 256) * ((No + 255) / 256);
+  int s = 256 / tiles;
   const int slices = (K + 63) / 64;
-  s = std::min(s, std::max(1, slices / 4));  // at least 4 slices of 64 per chunk
+  s = std::min(s, std::max(1, slices / 4));
   return std::max(1, std::min(s, 64));
 }
 

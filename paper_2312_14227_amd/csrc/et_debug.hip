@@ -11,9 +11,25 @@ extern "C" int et_debug_gemm_bf16(const void* A, const void* B, void* C, int M, 
   g.A = (const et::bf16*)A; g.B = (const et::bf16*)B; g.C = C;
   g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
   g.a_t = a_t != 0; g.b_t = b_t != 0; g.c_f32 = c_f32 != 0; g.alpha = alpha;
-  g.bias = (const et::bf16*)bias; g.residual = residual; g.ldr = N;
-  g.split_k = split_k < 1 ? 1 : split_k; g.partials = partials; g.tile = tile;
+  g.bias = (const et::bf16*)bias; g.residual = residual; g.ldr = ldc;
+  g.split_k = split_k < 1 ? 1 : split_k; g.partials = partials; g.tile = tile & 255; g.no_store = (tile & 256) != 0;
   const hipError_t e = et::gemm_bf16(g, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return ET_EINVAL;
   return e == hipSuccess ? ET_OK : ET_EHIP;
+}
+
+namespace {
+__global__ void et_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+}  // namespace
+
+extern "C" int et_debug_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || (bytes & 15) || ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15))
+    return ET_EINVAL;
+  if (bytes == 0) return ET_OK;
+  hipLaunchKernelGGL(et_copy_kernel, dim3(256 * 8), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst,
+                     bytes / 16);
+  return hipGetLastError() == hipSuccess ? ET_OK : ET_EHIP;
 }

@@ -1,0 +1,580 @@
+// bf16 MFMA GEMM kernels for gfx950: D[i][j] = alpha * sum_k A(i,k) B(j,k), fp32 accumulation.
+//
+// The dense contractions of the training step (Section 5.1: forward product, error-gradient
+// passing T1, weight gradient T3) all reduce to this form with either operand optionally stored
+// with the reduction index as the slow one:
+//   forward   Y  = X  W^T : A = X  [M][K],  B = W [N][K]                          (a_t = 0, b_t = 0)
+//   passing   dX = dY W   : A = dY [M][N'], B = W [N'][K'] read as B(j=k', k=n')  (b_t = 1)
+//   gradient  dW = dY^T X : A = dY [M'][N'] read as A(i=n', k=m), B = X likewise  (a_t = b_t = 1)
+//
+// Common design: one workgroup computes a BM x BN tile with v_mfma_f32_32x32x16_bf16; 64-lane
+// waves in a WGM x WGN grid each own a (BM/WGM) x (BN/WGN) sub-tile.
+//   - operand with contiguous reduction index: the LDS tile keeps rows of k values, 16-byte chunks
+//     XOR-swizzled with the row so that the ds_read_b128 of 8 consecutive rows hit distinct banks;
+//     a lane reads its 8 consecutive k values directly;
+//   - operand with the reduction index slow ("transposed"): LDS keeps the global layout
+//     [k-rows][tile rows] and the lanes fetch their 2 x 4 k values with ds_read_b64_tr_b16, the
+//     LDS transpose read of gfx950: in every group of 16 lanes, lane 4c+a supplies the address of
+//     4 consecutive elements of k-row c, and lane i receives element i of k-rows 0..3.
+// Two main loops share this:
+//   gemm_staged_kernel: K slices of 64 through two LDS buffers, the global loads of slice t+1 are
+//     issued into registers before the MFMAs of slice t (small tiles, several workgroups per CU;
+//     any K, with a predicated last slice);
+//   gemm_dma_kernel: K slices of 32 loaded with global_load_lds_dwordx4 straight into a ring of
+//     LDS stages, several slices in flight (large tiles; K a multiple of 32).
+// Rows beyond the matrix edge are clamped to valid addresses (their products are never stored).
+// Epilogue: every wave passes its accumulators through a private LDS area, 32 rows at a time, so
+// that each lane ends up with 4 consecutive columns of one row: bias, residual, GELU and the
+// stores then work on 8- and 16-byte vectors and whole 128-byte lines.
+// Workgroup ids are remapped so that consecutive tiles run on the same XCD (ids are dealt
+// round-robin over the 8 XCDs, each with its own L2), in groups of 8 tile rows.
+#pragma once
+#include "kernels.h"
+
+namespace et {
+namespace gemm {
+
+typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int NUM_XCD = 8;
+
+// compile-time epilogues
+enum Epi : int {
+  E_F32 = 0,        // C fp32 = alpha*v + bias
+  E_F32_RES = 1,    // C fp32 = alpha*v + bias + residual
+  E_BF16 = 2,       // C bf16 = alpha*v + bias
+  E_GELU_FWD = 3,   // C bf16 = v + bias (pre-activation), C2 bf16 = gelu(v + bias)
+  E_GELU_BWD = 4,   // C bf16 = v * gelu'(U)
+  E_PARTIAL = 5,    // split-K partial: C fp32 [z][M][N] = v
+};
+
+struct Params {
+  const bf16* A;
+  const bf16* B;
+  int M, N, K;
+  int lda, ldb;
+  int z_inner;
+  long long sAo, sAi, sBo, sBi, sCo, sCi;
+  int split_k, k_chunk;  // split_k > 1: blockIdx.z picks [z*k_chunk, (z+1)*k_chunk)
+  float alpha;
+  const bf16* bias;
+  const float* residual;
+  int ldr;
+  void* C;
+  int ldc;
+  bf16* C2;
+  const bf16* U;
+  int no_store;          // tuning aid: run the main loop, store nothing
+};
+
+__device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.f + erff(u * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float u) {
+  return 0.5f * (1.f + erff(u * 0.70710678118654752f)) + u * __expf(-0.5f * u * u) * 0.39894228040143268f;
+}
+
+__device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char* p) {
+  s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
+  return __builtin_bit_cast(bf16x4, v);
+}
+
+// tile coordinates of this workgroup
+template <int BM, int BN>
+__device__ __forceinline__ void tile_coords(const Params& g, int& m0, int& n0) {
+  const int tiles_n = (g.N + BN - 1) / BN;
+  const int tiles_m = (g.M + BM - 1) / BM;
+  const int nt = tiles_m * tiles_n;
+  const int w = blockIdx.x;
+  const int xcd = w % NUM_XCD, idx = w / NUM_XCD;
+  const int per = nt / NUM_XCD, rem = nt % NUM_XCD;
+  const int t = xcd * per + (xcd < rem ? xcd : rem) + idx;  // undo the round-robin XCD dealing
+  constexpr int GROUP = 8;                                   // 8 tile rows, walked column by column
+  const int gsz = GROUP * tiles_n;
+  const int grp = t / gsz, in = t % gsz;
+  const int first = grp * GROUP;
+  const int gm = min(tiles_m - first, GROUP);
+  m0 = (first + in % gm) * BM;
+  n0 = (in / gm) * BN;
+}
+
+// batch / split-K bookkeeping
+__device__ __forceinline__ void batch_offsets(const Params& g, const bf16*& A, const bf16*& B, long long& c_off,
+                                              int& k_begin, int& k_end) {
+  const int z = blockIdx.z;
+  A = g.A;
+  B = g.B;
+  k_begin = 0;
+  k_end = g.K;
+  if (g.split_k > 1) {
+    k_begin = z * g.k_chunk;
+    k_end = min(g.K, k_begin + g.k_chunk);
+    c_off = (long long)z * g.M * g.N;
+  } else {
+    const int zo = z / g.z_inner, zi = z % g.z_inner;
+    A += zo * g.sAo + zi * g.sAi;
+    B += zo * g.sBo + zi * g.sBi;
+    c_off = zo * g.sCo + zi * g.sCi;
+  }
+}
+
+// -------------------------------------------------------------------------------------------------
+// Epilogue of one wave.  acc[mi][ni][r] holds element (mi*32 + (r/4)*8 + (lane/32)*4 + r%4,
+// ni*32 + lane%32) of the wave's TM x TN sub-tile whose top-left corner is (row0, col0).
+// `stage` is this wave's private LDS area of 32 * TN floats.
+// -------------------------------------------------------------------------------------------------
+template <int EPI, int MI, int NI>
+__device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI][NI], float* stage, int row0, int col0,
+                                              long long c_off, int lane) {
+  constexpr int TN = NI * 32;
+  constexpr int CPL = TN / 4;    // lanes per row when reading back 4 columns each
+  constexpr int RPI = 64 / CPL;  // rows covered by one wave-wide read
+  const int l32 = lane & 31, khalf = lane >> 5;
+  const int c4 = (lane % CPL) * 4, rsub = lane / CPL;
+  const int col = col0 + c4;
+  const bool col_any = col < g.N, col_full = col + 3 < g.N;
+  const int ld = EPI == E_PARTIAL ? g.N : g.ldc;
+  float bias[4] = {0.f, 0.f, 0.f, 0.f};
+  if (EPI != E_PARTIAL && EPI != E_GELU_BWD && g.bias && col_any) {
+    if (col_full) {
+      const bf16x4 b = *(const bf16x4*)(g.bias + col);
+#pragma unroll
+      for (int j = 0; j < 4; j++) bias[j] = (float)b[j];
+    } else {
+      for (int j = 0; j < 4 && col + j < g.N; j++) bias[j] = (float)g.bias[col + j];
+    }
+  }
+#pragma unroll
+  for (int mi = 0; mi < MI; mi++) {
+#pragma unroll
+    for (int ni = 0; ni < NI; ni++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) stage[((r >> 2) * 8 + khalf * 4 + (r & 3)) * TN + ni * 32 + l32] = acc[mi][ni][r];
+    // the same wave reads back: LDS operations of one wave complete in order
+#pragma unroll
+    for (int it = 0; it < 32 / RPI; it++) {
+      const int rr = it * RPI + rsub;
+      const float4 raw = *(const float4*)(stage + rr * TN + c4);
+      const int row = row0 + mi * 32 + rr;
+      if (row >= g.M || !col_any) continue;
+      float v[4] = {raw.x, raw.y, raw.z, raw.w};
+      const long long ci = c_off + (long long)row * ld + col;
+      if (EPI != E_PARTIAL) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) v[j] = v[j] * g.alpha + bias[j];
+      }
+      if (col_full) {
+        if (EPI == E_F32_RES) {
+          const float4 rs = *(const float4*)(g.residual + (long long)row * g.ldr + col);
+          v[0] += rs.x; v[1] += rs.y; v[2] += rs.z; v[3] += rs.w;
+        }
+        if (EPI == E_GELU_BWD) {
+          const bf16x4 u = *(const bf16x4*)(g.U + ci);
+#pragma unroll
+          for (int j = 0; j < 4; j++) v[j] *= gelu_grad_f((float)u[j]);
+        }
+        if (EPI == E_F32 || EPI == E_F32_RES || EPI == E_PARTIAL) {
+          *(float4*)((float*)g.C + ci) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+          bf16x4 o;
+#pragma unroll
+          for (int j = 0; j < 4; j++) o[j] = (bf16)v[j];
+          *(bf16x4*)((bf16*)g.C + ci) = o;
+          if (EPI == E_GELU_FWD) {
+            bf16x4 o2;
+#pragma unroll
+            for (int j = 0; j < 4; j++) o2[j] = (bf16)gelu_f(v[j]);
+            *(bf16x4*)(g.C2 + ci) = o2;
+          }
+        }
+      } else {  // ragged right edge: element by element
+        for (int j = 0; j < 4 && col + j < g.N; j++) {
+          float x = v[j];
+          if (EPI == E_F32_RES) x += g.residual[(long long)row * g.ldr + col + j];
+          if (EPI == E_GELU_BWD) x *= gelu_grad_f((float)g.U[ci + j]);
+          if (EPI == E_F32 || EPI == E_F32_RES || EPI == E_PARTIAL) {
+            ((float*)g.C)[ci + j] = x;
+          } else {
+            ((bf16*)g.C)[ci + j] = (bf16)x;
+            if (EPI == E_GELU_FWD) g.C2[ci + j] = (bf16)gelu_f(x);
+          }
+        }
+      }
+    }
+  }
+}
+
+// =================================================================================================
+// register-staged kernel: K slices of 64, two LDS buffers
+// =================================================================================================
+constexpr int SBK = 64;
+
+template <int ROWS, bool T>
+struct StagedLds {
+  static constexpr int PITCH = T ? (ROWS * 2 + 32) : (SBK * 2);   // transposed: k-rows padded by 32 B
+  static constexpr int BYTES = T ? (SBK * PITCH) : (ROWS * PITCH);
+};
+
+template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, int EPI>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_staged_kernel(Params g) {
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int TM = BM / WGM, TN = BN / WGN;
+  constexpr int MI = TM / 32, NI = TN / 32;
+  constexpr int A_VECS = BM * SBK / 8 / NT, B_VECS = BN * SBK / 8 / NT;
+  static_assert(A_VECS * NT * 8 == BM * SBK && B_VECS * NT * 8 == BN * SBK, "tile/threads mismatch");
+  typedef StagedLds<BM, AT> LA;
+  typedef StagedLds<BN, BT> LB;
+  constexpr int STAGE = LA::BYTES + LB::BYTES;
+  constexpr int EPI_BYTES = WGM * WGN * 32 * TN * 4;
+  constexpr int SMEM = 2 * STAGE > EPI_BYTES ? 2 * STAGE : EPI_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave / WGN, wave_n = wave % WGN;
+  int m0, n0;
+  tile_coords<BM, BN>(g, m0, n0);
+  const bf16* A;
+  const bf16* B;
+  long long c_off;
+  int k_begin, k_end;
+  batch_offsets(g, A, B, c_off, k_begin, k_end);
+  const int k_end_pad = min((g.K + 7) & ~7, ((k_end + 7) & ~7));
+  const int nk = (k_end - k_begin + SBK - 1) / SBK;
+
+  // per-thread source pointers of its 16-byte pieces (slice 0); rows/columns clamped into the matrix
+  const bf16* pa[A_VECS];
+  const bf16* pb[B_VECS];
+  int ka[A_VECS], kb[B_VECS];  // k index (within a slice) each piece starts at
+#pragma unroll
+  for (int p = 0; p < A_VECS; p++) {
+    const int v = tid + p * NT;
+    if (!AT) {
+      const int row = v >> 3, kc = v & 7;
+      ka[p] = kc * 8;
+      pa[p] = A + (long long)min(m0 + row, g.M - 1) * g.lda + k_begin + kc * 8;
+    } else {
+      const int kr = v / (BM / 8), ic = v % (BM / 8);
+      int gi = m0 + ic * 8;
+      if (gi + 8 > ((g.M + 7) & ~7)) gi = 0;
+      ka[p] = kr;
+      pa[p] = A + (long long)(k_begin + kr) * g.lda + gi;
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < B_VECS; p++) {
+    const int v = tid + p * NT;
+    if (!BT) {
+      const int row = v >> 3, kc = v & 7;
+      kb[p] = kc * 8;
+      pb[p] = B + (long long)min(n0 + row, g.N - 1) * g.ldb + k_begin + kc * 8;
+    } else {
+      const int kr = v / (BN / 8), jc = v % (BN / 8);
+      int gj = n0 + jc * 8;
+      if (gj + 8 > ((g.N + 7) & ~7)) gj = 0;
+      kb[p] = kr;
+      pb[p] = B + (long long)(k_begin + kr) * g.ldb + gj;
+    }
+  }
+  const long long a_step = AT ? (long long)SBK * g.lda : SBK;
+  const long long b_step = BT ? (long long)SBK * g.ldb : SBK;
+
+  uint4 ra[A_VECS], rb[B_VECS];
+  // full slices need no predicate; the last slice of a ragged K zero-fills beyond the end
+  auto load_global = [&](int kt) {
+    const int k0 = k_begin + kt * SBK;
+    const bool full = k0 + SBK <= k_end;
+#pragma unroll
+    for (int p = 0; p < A_VECS; p++) {
+      const bool ok = full || (k0 + ka[p] < (AT ? k_end : k_end_pad));
+      ra[p] = ok ? *(const uint4*)pa[p] : make_uint4(0, 0, 0, 0);
+      pa[p] += a_step;
+    }
+#pragma unroll
+    for (int p = 0; p < B_VECS; p++) {
+      const bool ok = full || (k0 + kb[p] < (BT ? k_end : k_end_pad));
+      rb[p] = ok ? *(const uint4*)pb[p] : make_uint4(0, 0, 0, 0);
+      pb[p] += b_step;
+    }
+  };
+
+  auto store_lds = [&](int buf) {
+    unsigned char* sa = smem + buf * STAGE;
+    unsigned char* sb = sa + LA::BYTES;
+#pragma unroll
+    for (int p = 0; p < A_VECS; p++) {
+      const int v = tid + p * NT;
+      int off;
+      if (!AT) {
+        const int row = v >> 3, kc = v & 7;
+        off = row * LA::PITCH + ((kc ^ (row & 7)) << 4);
+      } else {
+        const int kr = v / (BM / 8), ic = v % (BM / 8);
+        off = kr * LA::PITCH + (ic << 4);
+      }
+      *(uint4*)(sa + off) = ra[p];
+    }
+#pragma unroll
+    for (int p = 0; p < B_VECS; p++) {
+      const int v = tid + p * NT;
+      int off;
+      if (!BT) {
+        const int row = v >> 3, kc = v & 7;
+        off = row * LB::PITCH + ((kc ^ (row & 7)) << 4);
+      } else {
+        const int kr = v / (BN / 8), jc = v % (BN / 8);
+        off = kr * LB::PITCH + (jc << 4);
+      }
+      *(uint4*)(sb + off) = rb[p];
+    }
+  };
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; mi++)
+#pragma unroll
+    for (int ni = 0; ni < NI; ni++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[mi][ni][r] = 0.f;
+
+  const int l32 = lane & 31, khalf = lane >> 5;          // direct: row, which 8 of the 16 k
+  const int grp = lane >> 4, r16 = lane & 15;            // transposed: 16-lane groups
+  const int tr_col = (grp & 1) * 16 + 4 * (r16 & 3);     // first of the 4 elements addressed
+  const int tr_krow = (grp >> 1) * 8 + (r16 >> 2);       // k-row addressed (first read)
+
+  auto compute = [&](int buf) {
+    const unsigned char* sa = smem + buf * STAGE;
+    const unsigned char* sb = sa + LA::BYTES;
+#pragma unroll
+    for (int ks = 0; ks < SBK / 16; ks++) {
+      bf16x8 af[MI], bfr[NI];
+#pragma unroll
+      for (int mi = 0; mi < MI; mi++) {
+        const int rbase = wave_m * TM + mi * 32;
+        if (!AT) {
+          const int row = rbase + l32, chunk = ks * 2 + khalf;
+          af[mi] = *(const bf16x8*)(sa + row * LA::PITCH + ((chunk ^ (row & 7)) << 4));
+        } else {
+          const unsigned char* p = sa + (ks * 16 + tr_krow) * LA::PITCH + (rbase + tr_col) * 2;
+          bf16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * LA::PITCH);
+          af[mi] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+      }
+#pragma unroll
+      for (int ni = 0; ni < NI; ni++) {
+        const int rbase = wave_n * TN + ni * 32;
+        if (!BT) {
+          const int row = rbase + l32, chunk = ks * 2 + khalf;
+          bfr[ni] = *(const bf16x8*)(sb + row * LB::PITCH + ((chunk ^ (row & 7)) << 4));
+        } else {
+          const unsigned char* p = sb + (ks * 16 + tr_krow) * LB::PITCH + (rbase + tr_col) * 2;
+          bf16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * LB::PITCH);
+          bfr[ni] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+      }
+#pragma unroll
+      for (int mi = 0; mi < MI; mi++)
+#pragma unroll
+        for (int ni = 0; ni < NI; ni++)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+    }
+  };
+
+  if (nk > 0) {
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; kt++) {
+      if (kt + 1 < nk) load_global(kt + 1);
+      compute(kt & 1);
+      if (kt + 1 < nk) store_lds((kt + 1) & 1);
+      __syncthreads();
+    }
+  }
+  if (g.no_store) return;
+  wave_epilogue<EPI, MI, NI>(g, acc, (float*)smem + wave * 32 * TN, m0 + wave_m * TM, n0 + wave_n * TN, c_off, lane);
+}
+
+// =================================================================================================
+// direct-to-LDS kernel: K slices of 32, ring of LDS stages filled by global_load_lds_dwordx4
+// =================================================================================================
+// Each lane's 16 bytes of a wave-wide load land at (load's LDS base) + 16 * lane, so the bank
+// swizzle is applied on the global side: the lane computes which 16-byte piece belongs at its
+// fixed LDS position.
+//   - operand with contiguous reduction index: position = row * 4 + (chunk ^ ((row >> 1) & 3))
+//     (rows of 64 B; 8 consecutive rows of one chunk column fall into distinct banks);
+//   - transposed operand: [32 k-rows][tile rows]; 16-byte chunk j of k-row k sits at
+//     j ^ ((k & 3) << 1), so the 4 k-rows touched by one ds_read_b64_tr_b16 use distinct banks.
+// The loads go through inline assembly and are waited for with explicit s_waitcnt vmcnt(n): the
+// compiler would otherwise wait for ALL outstanding loads before any LDS read.
+constexpr int DBK = 32;
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+
+template <int BM, int BN, int WGM, int WGN, int RING, bool AT, bool BT, int EPI>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(Params g) {
+  constexpr int NW = WGM * WGN;
+  constexpr int TM = BM / WGM, TN = BN / WGN;
+  constexpr int MI = TM / 32, NI = TN / 32;
+  constexpr int A_BYTES = BM * DBK * 2, B_BYTES = BN * DBK * 2, STAGE = A_BYTES + B_BYTES;
+  constexpr int A_LOADS = BM / 16 / NW, B_LOADS = BN / 16 / NW;  // wave-wide 1 KiB loads per wave and slice
+  constexpr int LOADS = A_LOADS + B_LOADS;
+  static_assert(A_LOADS * 16 * NW == BM && B_LOADS * 16 * NW == BN, "tile/waves mismatch");
+  static_assert(RING >= 3 && RING * STAGE <= 160 * 1024, "LDS ring too large");
+  static_assert(NW * 32 * TN * 4 <= RING * STAGE, "epilogue staging does not fit");
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[RING * STAGE];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave / WGN, wave_n = wave % WGN;
+  int m0, n0;
+  tile_coords<BM, BN>(g, m0, n0);
+  const bf16* A;
+  const bf16* B;
+  long long c_off;
+  int k_begin, k_end;
+  batch_offsets(g, A, B, c_off, k_begin, k_end);
+  const int nk = (k_end - k_begin) / DBK;
+
+  // per-lane global source of each of this wave's loads (slice 0)
+  const bf16* ga[A_LOADS];
+  const bf16* gb[B_LOADS];
+#pragma unroll
+  for (int i = 0; i < A_LOADS; i++) {
+    const int q = wave * A_LOADS + i;  // which 1 KiB piece of the A stage
+    if (!AT) {
+      const int row = q * 16 + (lane >> 2);
+      const int chunk = (lane & 3) ^ ((row >> 1) & 3);
+      ga[i] = A + (long long)min(m0 + row, g.M - 1) * g.lda + k_begin + chunk * 8;
+    } else {
+      constexpr int CR = BM / 8;  // 16-byte chunks per k-row
+      const int pos = q * 64 + lane;
+      const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << 1);
+      int gi = m0 + j * 8;
+      if (gi + 8 > ((g.M + 7) & ~7)) gi = 0;
+      ga[i] = A + (long long)(k_begin + k) * g.lda + gi;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < B_LOADS; i++) {
+    const int q = wave * B_LOADS + i;
+    if (!BT) {
+      const int row = q * 16 + (lane >> 2);
+      const int chunk = (lane & 3) ^ ((row >> 1) & 3);
+      gb[i] = B + (long long)min(n0 + row, g.N - 1) * g.ldb + k_begin + chunk * 8;
+    } else {
+      constexpr int CR = BN / 8;
+      const int pos = q * 64 + lane;
+      const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << 1);
+      int gj = n0 + j * 8;
+      if (gj + 8 > ((g.N + 7) & ~7)) gj = 0;
+      gb[i] = B + (long long)(k_begin + k) * g.ldb + gj;
+    }
+  }
+  const long long a_step = AT ? (long long)DBK * g.lda : DBK;
+  const long long b_step = BT ? (long long)DBK * g.ldb : DBK;
+  const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) unsigned char*)smem;
+
+  auto issue = [&](int stage) {
+    const unsigned sa = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + wave * A_LOADS * 1024);
+    const unsigned sb = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + A_BYTES + wave * B_LOADS * 1024);
+#pragma unroll
+    for (int i = 0; i < A_LOADS; i++) {
+      dma16(ga[i], sa + i * 1024);
+      ga[i] += a_step;
+    }
+#pragma unroll
+    for (int i = 0; i < B_LOADS; i++) {
+      dma16(gb[i], sb + i * 1024);
+      gb[i] += b_step;
+    }
+  };
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; mi++)
+#pragma unroll
+    for (int ni = 0; ni < NI; ni++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[mi][ni][r] = 0.f;
+
+  const int l32 = lane & 31, khalf = lane >> 5;
+  const int grp16 = lane >> 4, r16 = lane & 15;
+  const int tr_col = (grp16 & 1) * 16 + 4 * (r16 & 3);
+  const int tr_krow = (grp16 >> 1) * 8 + (r16 >> 2);
+  const int tr_swz = (r16 >> 2) << 1;  // (k & 3) << 1, the same for both halves of the 8 k values
+
+  auto load_a = [&](const unsigned char* sa, int ks, int mi) -> bf16x8 {
+    const int rbase = wave_m * TM + mi * 32;
+    if (!AT) {
+      const int row = rbase + l32, chunk = ks * 2 + khalf;
+      return *(const bf16x8*)(sa + row * 64 + ((chunk ^ ((row >> 1) & 3)) << 4));
+    } else {
+      const int col = rbase + tr_col;
+      const unsigned char* p = sa + (ks * 16 + tr_krow) * (BM * 2) + (((col >> 3) ^ tr_swz) << 4) + ((col >> 2) & 1) * 8;
+      bf16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * (BM * 2));
+      return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+  };
+  auto load_b = [&](const unsigned char* sb, int ks, int ni) -> bf16x8 {
+    const int rbase = wave_n * TN + ni * 32;
+    if (!BT) {
+      const int row = rbase + l32, chunk = ks * 2 + khalf;
+      return *(const bf16x8*)(sb + row * 64 + ((chunk ^ ((row >> 1) & 3)) << 4));
+    } else {
+      const int col = rbase + tr_col;
+      const unsigned char* p = sb + (ks * 16 + tr_krow) * (BN * 2) + (((col >> 3) ^ tr_swz) << 4) + ((col >> 2) & 1) * 8;
+      bf16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * (BN * 2));
+      return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+  };
+
+  // prologue: RING-1 slices in flight
+#pragma unroll
+  for (int s = 0; s < RING - 1; s++)
+    if (s < nk) issue(s);
+
+  for (int kt = 0; kt < nk; kt++) {
+    // slice kt must have landed; up to RING-2 younger slices may still be in flight
+    const int younger = min(RING - 2, nk - 1 - kt);
+    if (younger >= 2) wait_vmcnt<2 * LOADS>();
+    else if (younger == 1) wait_vmcnt<LOADS>();
+    else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();  // slice kt visible to all waves; stage of slice kt-1 free again
+    if (kt + RING - 1 < nk) issue((kt + RING - 1) % RING);
+    const unsigned char* sa = smem + (kt % RING) * STAGE;
+    const unsigned char* sb = sa + A_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < DBK / 16; ks++) {
+      bf16x8 af[MI], bfr[NI];
+#pragma unroll
+      for (int mi = 0; mi < MI; mi++) af[mi] = load_a(sa, ks, mi);
+#pragma unroll
+      for (int ni = 0; ni < NI; ni++) bfr[ni] = load_b(sb, ks, ni);
+#pragma unroll
+      for (int mi = 0; mi < MI; mi++)
+#pragma unroll
+        for (int ni = 0; ni < NI; ni++)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+    }
+  }
+  if (g.no_store) return;
+  __syncthreads();  // every wave is done with the stages before they are reused for the epilogue
+  wave_epilogue<EPI, MI, NI>(g, acc, (float*)smem + wave * 32 * TN, m0 + wave_m * TM, n0 + wave_n * TN, c_off, lane);
+}
+
+// host side: pick the instantiation for (layout, epilogue); returns false if that pair is not built
+typedef hipError_t (*LaunchFn)(const Params&, dim3 grid, hipStream_t);
+LaunchFn staged_128x128(bool a_t, bool b_t, int epi);
+LaunchFn staged_128x64(bool a_t, bool b_t, int epi);
+LaunchFn dma_256x256(bool a_t, bool b_t, int epi);
+LaunchFn dma_256x128(bool a_t, bool b_t, int epi);
+
+}  // namespace gemm
+}  // namespace et

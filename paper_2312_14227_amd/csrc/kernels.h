@@ -13,9 +13,11 @@ typedef __bf16 bf16;
 //   A(i,k) = a_t ? A[k*lda + i] : A[i*lda + k]      (a_t: the reduction index is the slow one)
 //   B(j,k) = b_t ? B[k*ldb + j] : B[j*ldb + k]
 // so forward (X W^T) is (a_t,b_t) = (0,0), input gradient (dY W) is (0,1) and weight gradient
-// (dY^T X) is (1,1).  Requirements (checked on the host): 16-byte aligned bases, lda/ldb/ldc
-// multiples of 8; an operand that is not transposed must have finite data up to K rounded up to 8
-// in every row (the tail is multiplied by zeros or must itself be zero).
+// (dY^T X) is (1,1).  Requirements (checked on the host): 16-byte aligned bases, lda/ldb multiples
+// of 8, ldc and the C batch strides multiples of 4; an operand that is not transposed must have
+// finite data up to K rounded up to 8 in every row (the tail is multiplied by zeros or must itself
+// be zero).  Only the (layout, epilogue) pairs the training step uses are built: a residual needs
+// fp32 output and (0,0); GELU forward needs (0,0), GELU backward (0,1), split-K (1,1).
 // ------------------------------------------------------------------------------------------
 enum EpiMode : int {
   EPI_PLAIN = 0,     // C = v
@@ -48,6 +50,7 @@ struct GemmDesc {
   bf16* C2 = nullptr;              // EPI_GELU_FWD
   const bf16* U = nullptr;         // EPI_GELU_BWD, same leading dimension as C
   int tile = 0;                    // 0 = choose by shape; else a TileId (tuning/tests)
+  bool no_store = false;           // tuning aid: run the main loop, store nothing
 };
 
 // returns hipSuccess, or hipErrorInvalidValue when a requirement above is violated

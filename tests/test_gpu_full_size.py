@@ -1,0 +1,61 @@
+"""Parity at the full size of the benchmark workload (ViT-B shape, batch 64), in the launch
+configuration bench.py times, against oracle values stored by tests/golden/make_full_size_golden.py
+(512 seeded gradient elements per tensor, gradient norms, loss, importance)."""
+import os
+
+import numpy as np
+import pytest
+
+from gpu_util import rel_l2
+from synth import CONFIGS, make_workload
+
+pytestmark = pytest.mark.gpu
+GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "vit_b_seed0.npz")
+
+
+def test_vit_b_full_size_gradients_importance_and_masks():
+    import torch
+    from paper_2312_14227_amd.session import Session
+    G = np.load(GOLD)
+    cfg = CONFIGS["vit_b"]
+    assert int(G["batch"]) == cfg.batch
+    wl = make_workload(cfg, seed=int(G["seed"]))
+    N = len(wl.weights)
+    s = Session(cfg, wl.weights, with_state=False)
+    xt, yt = s.put_input(wl.x, wl.y)
+    snap = s.put_snapshot(wl.snapshot)
+    tol = 2e-2
+    I = s.importance(xt, yt, snap)                 # full backward, gradients stay in the buffers
+    torch.cuda.synchronize()
+    full = [g.clone() for g in s.grad]
+    worst, worst_i = 0.0, 0.0
+    for k in range(N):
+        idx = torch.from_numpy(G["idx_%d" % k].astype(np.int64)).to(s.dev)
+        got = full[k][idx].cpu().numpy()
+        err = rel_l2(got, G["g_%d" % k])
+        worst = max(worst, err)
+        assert err <= tol, (wl.names[k], err)
+        nrm = float(torch.linalg.vector_norm(full[k].double()))
+        assert abs(nrm - G["gnorm"][k]) <= tol * G["gnorm"][k], (wl.names[k], nrm, G["gnorm"][k])
+        # a gradient within tol (relative L2) moves g.dw by at most tol |g| |dw| (Cauchy-Schwarz)
+        dwn = float(np.linalg.norm((wl.snapshot[k].astype(np.float64) - wl.weights[k].astype(np.float64)).ravel()))
+        bound = tol * max(abs(G["importance"][k]), G["gnorm"][k] * dwn)
+        worst_i = max(worst_i, abs(I[k] - G["importance"][k]) / bound)
+        assert abs(I[k] - G["importance"][k]) <= bound, (wl.names[k], I[k], G["importance"][k])
+    print("worst sampled relative L2 gradient error at full size: %.3e; worst importance error / bound: %.3f"
+          % (worst, worst_i))
+    # a selective step: selected gradients are the very same numbers, the rest is not written
+    rng = np.random.default_rng(0)
+    mask = np.zeros(N, dtype=np.uint8)
+    mask[87:] = rng.random(N - 87) < 0.3
+    mask[87] = 1
+    for g in s.grad:
+        g.fill_(float("nan"))
+    loss = s.train_step(xt, yt, mask)
+    assert abs(loss - float(G["loss"])) <= tol * float(G["loss"])
+    for k in range(N):
+        if mask[k]:
+            assert torch.equal(s.grad[k], full[k]), wl.names[k]
+        else:
+            assert bool(s.grad[k].isnan().all()), wl.names[k]
+    s.close()

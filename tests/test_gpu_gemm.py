@@ -45,9 +45,9 @@ def _run(M, N, K, a_t, b_t, c_f32, bias, residual, split_k, tile, seed):
         bias_t = torch.from_numpy(b).to(dev).to(torch.bfloat16)
         ref = ref + b.astype(np.float64)
     if residual:
-        r = rng.standard_normal((M, N)).astype(np.float32)
+        r = rng.standard_normal((M, ldc)).astype(np.float32)       # same leading dimension as C
         res_t = torch.from_numpy(r).to(dev)
-        ref = ref + r.astype(np.float64)
+        ref = ref + r[:, :N].astype(np.float64)
     part = torch.empty(M * N * split_k, device=dev, dtype=torch.float32) if split_k > 1 else None
     st = et.et_debug_gemm_bf16(At.data_ptr(), Bt.data_ptr(), Ct.data_ptr(), M, N, K, A.shape[1], B.shape[1], ldc, a_t,
                                b_t, c_f32, 1.0, bias_t.data_ptr() if bias else 0, res_t.data_ptr() if residual else 0,
@@ -70,14 +70,27 @@ def test_gemm_layouts_fp32_out(M, N, K, a_t, b_t):
 
 
 @pytest.mark.parametrize("M,N,K,a_t,b_t", CASES[:8])
-def test_gemm_bf16_out_bias_residual(M, N, K, a_t, b_t):
-    _run(M, N, K, a_t, b_t, 0, True, True, 1, 0, seed=7 + M)
+def test_gemm_bf16_out_bias(M, N, K, a_t, b_t):
+    _run(M, N, K, a_t, b_t, 0, True, False, 1, 0, seed=7 + M)
+
+
+@pytest.mark.parametrize("M,N,K", [(197, 197, 64), (300, 200, 136), (1000, 768, 768), (64, 200, 768)])
+def test_gemm_fp32_out_bias_residual(M, N, K):
+    _run(M, N, K, 0, 0, 1, True, True, 1, 0, seed=11 + M)
 
 
 @pytest.mark.parametrize("tile", [1, 3])
 @pytest.mark.parametrize("M,N,K,a_t,b_t", [(300, 200, 136, 0, 0), (300, 136, 200, 0, 1), (136, 200, 300, 1, 1)])
 def test_gemm_every_tile_shape(M, N, K, a_t, b_t, tile):
     _run(M, N, K, a_t, b_t, 1, True, False, 1, tile, seed=tile)
+
+
+@pytest.mark.parametrize("tile", [5, 7])
+@pytest.mark.parametrize("M,N,K,a_t,b_t", [(700, 520, 160, 0, 0), (700, 160, 512, 0, 1), (520, 264, 704, 1, 1),
+                                           (1000, 768, 768, 0, 0), (200, 768, 64, 1, 1), (3, 8, 32, 0, 0)])
+def test_gemm_direct_to_lds_tiles(M, N, K, a_t, b_t, tile):
+    _run(M, N, K, a_t, b_t, 1, True, a_t == 0 and b_t == 0, 1, tile, seed=tile + M)
+    _run(M, N, K, a_t, b_t, 0, True, False, 1, tile, seed=tile + N)
 
 
 @pytest.mark.parametrize("split", [2, 5, 16])

@@ -31,10 +31,11 @@ def test_importance_matches_oracle(name):
     tol = tol_for(cfg)
     worst = 0.0
     for k in range(N):
-        # I_k is a cancelling signed sum, so its error is judged against the larger of |I_k| and a
-        # tenth of the sum of magnitudes A_k = sum |g dw| (a gradient error of relative size tol
-        # moves I_k by at most tol * |g| |dw| ~ 1.5 tol A_k, and by far less when uncorrelated)
-        bound = tol * max(abs(I_ref[k]), 0.1 * A_ref[k])
+        # I_k is a cancelling signed sum: a gradient within tol (relative L2) moves g.dw by at most
+        # tol |g| |dw| (Cauchy-Schwarz), so the error is judged against the larger of |I_k| and that
+        gn = np.linalg.norm(r["grads"][k].ravel())
+        dwn = np.linalg.norm((wl.snapshot[k].astype(np.float64) - wl.weights[k].astype(np.float64)).ravel())
+        bound = tol * max(abs(I_ref[k]), gn * dwn)
         worst = max(worst, abs(I[k] - I_ref[k]) / bound)
         assert abs(I[k] - I_ref[k]) <= bound, (wl.names[k], I[k], I_ref[k], A_ref[k])
     print("worst importance error / bound: %.3f" % worst)
