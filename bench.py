@@ -113,7 +113,7 @@ def main():
     # ---- kernel classes inside the same selective steps, HIP events on the launch stream
     et.et_kernel_timing(s.ctx, 1)
     timed_steps(s, xt, yt, mask, mk, a.steps, 1)
-    classes = {c: et.et_kernel_timing_read(s.ctx, c) for c in range(5)}
+    classes = {c: et.et_kernel_timing_read(s.ctx, c) for c in range(7)}
     et.et_kernel_timing(s.ctx, 1)
     s.importance(xt, yt, snap)
     imp_n, imp_ns, imp_bytes = et.et_kernel_timing_read(s.ctx, 3)
@@ -159,6 +159,9 @@ def main():
         "gemm_by_kernel": by_kernel,
         "importance": {"gbps": imp_bytes / imp_ns if imp_ns else None, "us": imp_ns / 1e3, "bytes": imp_bytes,
                        "frac_of_hbm_peak": imp_bytes / imp_ns / PEAK_HBM_GBS if imp_ns else None},
+        "attention": {name: ({"launches_per_step": classes[c][0] / a.steps, "avg_us": classes[c][1] / classes[c][0] / 1e3,
+                              "tflops": classes[c][2] / classes[c][1] / 1e3} if classes[c][0] else None)
+                      for name, c in (("forward", 5), ("backward", 6))},
         "update": {"gbps": upd_bytes / upd_ns if upd_ns else None, "us": upd_ns / max(upd_n, 1) / 1e3,
                    "frac_of_hbm_peak": upd_bytes / upd_ns / PEAK_HBM_GBS if upd_ns else None},
     }

@@ -1,0 +1,365 @@
+// Fused attention core for short sequences (tokens <= 224, head size 64): forward
+// O = softmax(Q K^T / sqrt(d)) V and its backward (dQ, dK, dV), one workgroup per (batch, head).
+// These are the "attention operations" the paper counts among the non-trainable layers (Section
+// 5.4): they hold no weights, their backward time is charged to the tensor whose passing needs it.
+//
+// Everything of one head fits on chip: K and V (forward) or Q, K, V, dO (backward) are staged in
+// LDS once, rows beyond the sequence zero-filled; the score matrix never goes to memory.
+//
+// Register layout trick.  v_mfma_f32_32x32x16_bf16 returns a 32x32 tile with lane l holding
+// column l%32 and rows (r/4)*8 + (l/32)*4 + r%4 (r = 0..15).  Scores are computed TRANSPOSED,
+// S^T = K Q^T, so a lane holds ONE query (l%32) and 16 keys per 32-key tile: the softmax over keys
+// is an in-lane loop plus one exchange with lane l^32.  The same registers, converted to bf16, are
+// exactly an MFMA A operand (row = query l%32, 8 reduction slots per lane) for P V, with the
+// reduction slots meaning keys (e/4)*8 + (l/32)*4 + e%4 of a 16-key group; the matching B operand
+// (V with the same key order, one column d per lane) is what two ds_read_b64_tr_b16 deliver from
+// V stored [key][d].  No shuffle or LDS round trip between the two matrix products.
+// The backward pass uses the mirrored trick (S = Q K^T, a lane holds one key) for dK and dV.
+#include "kernels.h"
+
+namespace et {
+namespace {
+
+typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int DH = 64;
+constexpr int NWAVES = 8, NTHREADS = NWAVES * 64;
+constexpr int PITCH = 160;  // bytes per LDS row of 64 bf16: 128 + 32 keeps 4 consecutive rows in distinct banks
+
+__device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char* p) {
+  s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
+  return __builtin_bit_cast(bf16x4, v);
+}
+
+// rows [0, T) of a [T][64] bf16 matrix (row stride ld elements) into LDS rows of PITCH bytes; rows
+// [T, rows_pad) are zero-filled
+__device__ __forceinline__ void stage_rows(unsigned char* dst, const bf16* src, long long ld, int T, int rows_pad,
+                                           int tid, int nthreads) {
+  for (int v = tid; v < rows_pad * 8; v += nthreads) {
+    const int row = v >> 3, c = v & 7;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (row < T) val = *(const uint4*)(src + (long long)row * ld + c * 8);
+    *(uint4*)(dst + row * PITCH + c * 16) = val;
+  }
+}
+
+// A- or B-operand fragment of rows [row0, row0+32) for reduction slice ks (16 of the 64 columns):
+// lane l gets row row0 + l%32, columns ks*16 + (l/32)*8 .. +7
+__device__ __forceinline__ bf16x8 frag_direct(const unsigned char* m, int row0, int ks, int lane) {
+  return *(const bf16x8*)(m + (row0 + (lane & 31)) * PITCH + (ks * 2 + (lane >> 5)) * 16);
+}
+
+// B-operand fragment for a reduction over ROWS of a matrix stored [row][64]: lane l gets column
+// col0 + l%32 and the 8 rows  row0 + (e/4)*8 + (l/32)*4 + e%4  (e = 0..7)
+__device__ __forceinline__ bf16x8 frag_rows_tr(const unsigned char* m, int row0, int col0, int lane) {
+  const int g = lane >> 4, r16 = lane & 15;
+  const unsigned char* p = m + (row0 + (g >> 1) * 4 + (r16 >> 2)) * PITCH + (col0 + (g & 1) * 16 + 4 * (r16 & 3)) * 2;
+  const bf16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 8 * PITCH);
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// element r of an MFMA result tile: row offset inside the 32x32 tile
+__device__ __forceinline__ int tile_row(int r, int lane) { return (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); }
+
+// -------------------------------------------------------------------------------------------------
+// forward
+// -------------------------------------------------------------------------------------------------
+template <int KT>
+__global__ __launch_bounds__(NTHREADS) void attention_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ out,
+                                                                 float* __restrict__ lse, int T, int H, float scale) {
+  constexpr int TP = KT * 32;
+  __shared__ __attribute__((aligned(16))) unsigned char sk[TP * PITCH];
+  __shared__ __attribute__((aligned(16))) unsigned char sv[TP * PITCH];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.x / H, h = blockIdx.x % H;
+  const int D = H * DH;
+  const long long ld = 3LL * D;
+  const bf16* q = qkv + (long long)b * T * ld + h * DH;
+  const bf16* k = q + D;
+  const bf16* v = q + 2 * D;
+  stage_rows(sk, k, ld, T, TP, tid, NTHREADS);
+  stage_rows(sv, v, ld, T, TP, tid, NTHREADS);
+  __syncthreads();
+
+  const int l32 = lane & 31, khalf = lane >> 5;
+  for (int qt = wave; qt < KT; qt += NWAVES) {
+    // Q fragments straight from memory (B operand: row = query, 8 consecutive d)
+    const int qrow = min(qt * 32 + l32, T - 1);
+    bf16x8 qf[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) qf[ks] = *(const bf16x8*)(q + (long long)qrow * ld + ks * 16 + khalf * 8);
+
+    // S^T tile kt: lane holds query l%32 and keys kt*32 + tile_row(r); scaled, masked beyond T
+    auto scores = [&](int kt) -> f32x16 {
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 4; ks++)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct(sk, kt * 32, ks, lane), qf[ks], acc, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[r] = kt * 32 + tile_row(r, lane) < T ? acc[r] * scale : -INFINITY;
+      return acc;
+    };
+
+    // sweep 1: running maximum and sum of exponentials over this lane's keys
+    float mx = -INFINITY, sum = 0.f;
+#pragma unroll 1
+    for (int kt = 0; kt < KT; kt++) {
+      const f32x16 st = scores(kt);
+      float tmax = st[0];
+#pragma unroll
+      for (int r = 1; r < 16; r++) tmax = fmaxf(tmax, st[r]);
+      const float nmx = fmaxf(mx, tmax);
+      if (nmx != -INFINITY) {
+        float part = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; r++) part += __expf(st[r] - nmx);
+        sum = sum * __expf(mx - nmx) + part;
+        mx = nmx;
+      }
+    }
+    // the other half of the keys lives in lane l^32
+    const float omx = __shfl_xor(mx, 32, 64), osum = __shfl_xor(sum, 32, 64);
+    const float M = fmaxf(mx, omx);
+    const float S = sum * __expf(mx - M) + osum * __expf(omx - M);
+    const float inv = 1.f / S;
+    if (khalf == 0 && qt * 32 + l32 < T) lse[((long long)b * H + h) * T + qt * 32 + l32] = M + logf(S);
+
+    // sweep 2: O = P V; the probabilities of a tile are already an A operand
+    f32x16 o[2];
+#pragma unroll
+    for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
+#pragma unroll 1
+    for (int kt = 0; kt < KT; kt++) {
+      const f32x16 st = scores(kt);
+#pragma unroll
+      for (int j = 0; j < 2; j++) {
+        bf16x8 pf;
+#pragma unroll
+        for (int e = 0; e < 8; e++) pf[e] = (bf16)(__expf(st[j * 8 + e] - M) * inv);
+#pragma unroll
+        for (int dt = 0; dt < 2; dt++)
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, frag_rows_tr(sv, kt * 32 + j * 16, dt * 32, lane), o[dt], 0, 0, 0);
+      }
+    }
+    // result tile: lane holds column d = dt*32 + l%32, rows = queries
+#pragma unroll
+    for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int row = qt * 32 + tile_row(r, lane);
+        if (row < T) out[((long long)b * T + row) * D + h * DH + dt * 32 + l32] = (bf16)o[dt][r];
+      }
+  }
+}
+
+// -------------------------------------------------------------------------------------------------
+// backward: dS = P * (dP - rowsum(P*dP)) / sqrt(d);  dQ = dS K,  dK = dS^T Q,  dV = P^T dO
+// -------------------------------------------------------------------------------------------------
+template <int KT>
+__global__ __launch_bounds__(NTHREADS) void attention_bwd_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
+                                                            const float* __restrict__ lse, bf16* __restrict__ dqkv,
+                                                            int T, int H, float scale) {
+  constexpr int TP = KT * 32;
+  __shared__ __attribute__((aligned(16))) unsigned char sq[TP * PITCH];
+  __shared__ __attribute__((aligned(16))) unsigned char sk[TP * PITCH];
+  __shared__ __attribute__((aligned(16))) unsigned char sv[TP * PITCH];
+  __shared__ __attribute__((aligned(16))) unsigned char sdo[TP * PITCH];
+  __shared__ __attribute__((aligned(16))) float s_lse[TP];
+  __shared__ __attribute__((aligned(16))) float s_dot[TP];  // rowsum(P * dP) per query
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.x / H, h = blockIdx.x % H;
+  const int D = H * DH;
+  const long long ld = 3LL * D;
+  const bf16* q = qkv + (long long)b * T * ld + h * DH;
+  stage_rows(sq, q, ld, T, TP, tid, NTHREADS);
+  stage_rows(sk, q + D, ld, T, TP, tid, NTHREADS);
+  stage_rows(sv, q + 2 * D, ld, T, TP, tid, NTHREADS);
+  stage_rows(sdo, dout + (long long)b * T * D + h * DH, D, T, TP, tid, NTHREADS);
+  // padded queries get lse = +inf, so their probabilities vanish
+  for (int i = tid; i < TP; i += NTHREADS) s_lse[i] = i < T ? lse[((long long)b * H + h) * T + i] : INFINITY;
+  __syncthreads();
+
+  const int l32 = lane & 31, khalf = lane >> 5;
+
+  // ---- pass A: a wave owns 32 queries (one per lane pair); first the row dot products, then dQ
+  for (int qt = wave; qt < KT; qt += NWAVES) {
+    bf16x8 qf[4], dof[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) {
+      qf[ks] = frag_direct(sq, qt * 32, ks, lane);
+      dof[ks] = frag_direct(sdo, qt * 32, ks, lane);
+    }
+    const float my_lse = s_lse[qt * 32 + l32];
+    float dot = 0.f;
+#pragma unroll 1
+    for (int sweep = 0; sweep < 2; sweep++) {
+      f32x16 dq[2];
+#pragma unroll
+      for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) dq[dt][r] = 0.f;
+      const float my_dot = dot;  // complete (both lane halves) in the second sweep
+#pragma unroll 1
+      for (int kt = 0; kt < KT; kt++) {
+        f32x16 st, dp;
+#pragma unroll
+        for (int r = 0; r < 16; r++) { st[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+          st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct(sk, kt * 32, ks, lane), qf[ks], st, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct(sv, kt * 32, ks, lane), dof[ks], dp, 0, 0, 0);
+        }
+        float pr[16];
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int key = kt * 32 + tile_row(r, lane);
+          pr[r] = key < T ? __expf(st[r] * scale - my_lse) : 0.f;
+        }
+        if (sweep == 0) {
+#pragma unroll
+          for (int r = 0; r < 16; r++) dot += pr[r] * dp[r];
+        } else {
+#pragma unroll
+          for (int j = 0; j < 2; j++) {
+            bf16x8 dsf;
+#pragma unroll
+            for (int e = 0; e < 8; e++) dsf[e] = (bf16)(pr[j * 8 + e] * (dp[j * 8 + e] - my_dot) * scale);
+#pragma unroll
+            for (int dt = 0; dt < 2; dt++)
+              dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, frag_rows_tr(sk, kt * 32 + j * 16, dt * 32, lane), dq[dt], 0, 0, 0);
+          }
+        }
+      }
+      if (sweep == 0) {
+        dot += __shfl_xor(dot, 32, 64);
+        if (khalf == 0) s_dot[qt * 32 + l32] = dot;
+      } else {
+#pragma unroll
+        for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) {
+            const int row = qt * 32 + tile_row(r, lane);
+            if (row < T) dqkv[((long long)b * T + row) * ld + h * DH + dt * 32 + l32] = (bf16)dq[dt][r];
+          }
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- pass B: a wave owns 32 keys (one per lane pair): S = Q K^T tiles with lane = key
+  for (int kt = wave; kt < KT; kt += NWAVES) {
+    bf16x8 kf[4], vf[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) {
+      kf[ks] = frag_direct(sk, kt * 32, ks, lane);
+      vf[ks] = frag_direct(sv, kt * 32, ks, lane);
+    }
+    const bool key_ok = kt * 32 + l32 < T;
+    f32x16 dk[2], dv[2];
+#pragma unroll
+    for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
+#pragma unroll 1
+    for (int qt = 0; qt < KT; qt++) {
+      f32x16 st, dp;
+#pragma unroll
+      for (int r = 0; r < 16; r++) { st[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < 4; ks++) {
+        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct(sq, qt * 32, ks, lane), kf[ks], st, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct(sdo, qt * 32, ks, lane), vf[ks], dp, 0, 0, 0);
+      }
+      // rows of the tile are queries qt*32 + tile_row(r): their lse / dot come in groups of 4
+      float pr[16], ds[16];
+#pragma unroll
+      for (int a = 0; a < 4; a++) {
+        const float4 l4 = *(const float4*)(s_lse + qt * 32 + a * 8 + khalf * 4);
+        const float4 d4 = *(const float4*)(s_dot + qt * 32 + a * 8 + khalf * 4);
+        const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+          const int r = a * 4 + c;
+          const float p = key_ok ? __expf(st[r] * scale - lv[c]) : 0.f;
+          pr[r] = p;
+          ds[r] = p * (dp[r] - dv4[c]) * scale;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 2; j++) {
+        bf16x8 pf, dsf;
+#pragma unroll
+        for (int e = 0; e < 8; e++) { pf[e] = (bf16)pr[j * 8 + e]; dsf[e] = (bf16)ds[j * 8 + e]; }
+#pragma unroll
+        for (int dt = 0; dt < 2; dt++) {
+          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, frag_rows_tr(sdo, qt * 32 + j * 16, dt * 32, lane), dv[dt], 0, 0, 0);
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, frag_rows_tr(sq, qt * 32 + j * 16, dt * 32, lane), dk[dt], 0, 0, 0);
+        }
+      }
+    }
+#pragma unroll
+    for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int row = kt * 32 + tile_row(r, lane);
+        if (row < T) {
+          const long long base = ((long long)b * T + row) * ld + h * DH + dt * 32 + l32;
+          dqkv[base + D] = (bf16)dk[dt][r];
+          dqkv[base + 2 * D] = (bf16)dv[dt][r];
+        }
+      }
+  }
+}
+
+template <int KT>
+hipError_t launch_fwd(const bf16* qkv, bf16* out, float* lse, int B, int T, int H, float scale, hipStream_t s) {
+  hipLaunchKernelGGL((attention_fwd_kernel<KT>), dim3(B * H), dim3(NTHREADS), 0, s, qkv, out, lse, T, H, scale);
+  return hipGetLastError();
+}
+template <int KT>
+hipError_t launch_bwd(const bf16* qkv, const bf16* dout, const float* lse, bf16* dqkv, int B, int T, int H, float scale,
+                      hipStream_t s) {
+  hipLaunchKernelGGL((attention_bwd_kernel<KT>), dim3(B * H), dim3(NTHREADS), 0, s, qkv, dout, lse, dqkv, T, H, scale);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool attention_fused_supported(int T, int head_dim) { return head_dim == DH && T >= 1 && T <= 224; }
+
+hipError_t attention_fwd(const bf16* qkv, bf16* out, float* lse, int B, int T, int H, int head_dim, float scale,
+                         hipStream_t s) {
+  if (!attention_fused_supported(T, head_dim) || B < 1 || H < 1) return hipErrorInvalidValue;
+  switch ((T + 31) / 32) {
+    case 1: return launch_fwd<1>(qkv, out, lse, B, T, H, scale, s);
+    case 2: return launch_fwd<2>(qkv, out, lse, B, T, H, scale, s);
+    case 3: return launch_fwd<3>(qkv, out, lse, B, T, H, scale, s);
+    case 4: return launch_fwd<4>(qkv, out, lse, B, T, H, scale, s);
+    case 5: return launch_fwd<5>(qkv, out, lse, B, T, H, scale, s);
+    case 6: return launch_fwd<6>(qkv, out, lse, B, T, H, scale, s);
+    default: return launch_fwd<7>(qkv, out, lse, B, T, H, scale, s);
+  }
+}
+
+hipError_t attention_bwd(const bf16* qkv, const bf16* dout, const float* lse, bf16* dqkv, int B, int T, int H,
+                         int head_dim, float scale, hipStream_t s) {
+  if (!attention_fused_supported(T, head_dim) || B < 1 || H < 1) return hipErrorInvalidValue;
+  switch ((T + 31) / 32) {
+    case 1: return launch_bwd<1>(qkv, dout, lse, dqkv, B, T, H, scale, s);
+    case 2: return launch_bwd<2>(qkv, dout, lse, dqkv, B, T, H, scale, s);
+    case 3: return launch_bwd<3>(qkv, dout, lse, dqkv, B, T, H, scale, s);
+    case 4: return launch_bwd<4>(qkv, dout, lse, dqkv, B, T, H, scale, s);
+    case 5: return launch_bwd<5>(qkv, dout, lse, dqkv, B, T, H, scale, s);
+    case 6: return launch_bwd<6>(qkv, dout, lse, dqkv, B, T, H, scale, s);
+    default: return launch_bwd<7>(qkv, dout, lse, dqkv, B, T, H, scale, s);
+  }
+}
+
+}  // namespace et

@@ -46,7 +46,7 @@ struct KernelRecord {  // one timed kernel launch (measurement support)
 };
 
 struct VitBlockBufs {
-  float *h_in, *h_mid, *mean1, *rstd1, *mean2, *rstd2;
+  float *h_in, *h_mid, *mean1, *rstd1, *mean2, *rstd2, *lse;
   bf16 *a1, *qkv, *p, *o, *a2, *u, *ga;
 };
 
@@ -240,6 +240,7 @@ int build_vit(et_ctx* c) {
     reserve(c, &b.a1, b16 * M * D);
     reserve(c, &b.qkv, b16 * M * 3 * D);
     reserve(c, &b.p, b16 * B * H * T * ldT);
+    reserve(c, &b.lse, f32 * B * H * T);
     reserve(c, &b.o, b16 * M * D);
     reserve(c, &b.a2, b16 * M * D);
     reserve(c, &b.u, b16 * M * F);
@@ -446,23 +447,28 @@ int vit_forward(et_ctx* c, const void* x, const int32_t* y) {
       g.C = b.qkv;
       ET_G(g);
     }
-    {  // S = scale * Q K^T per (batch, head)
-      et::GemmDesc g;
-      g.A = b.qkv; g.lda = 3 * v.D; g.B = b.qkv + v.D; g.ldb = 3 * v.D; g.M = v.T; g.N = v.T; g.K = v.dh;
-      g.z_outer = v.B; g.z_inner = v.H;
-      g.sAo = (long long)v.T * 3 * v.D; g.sAi = v.dh; g.sBo = g.sAo; g.sBi = v.dh;
-      g.C = c->s_f32; g.c_f32 = true; g.ldc = v.ldT; g.sCo = (long long)v.H * v.T * v.ldT; g.sCi = (long long)v.T * v.ldT;
-      g.alpha = v.scale;
-      ET_G(g);
-    }
-    ET_K(1, et::softmax_rows(c->s_f32, b.p, v.B * v.H * v.T, v.T, v.ldT, c->stream));
-    {  // O = P V
-      et::GemmDesc g;
-      g.A = b.p; g.lda = v.ldT; g.B = b.qkv + 2 * v.D; g.b_t = true; g.ldb = 3 * v.D; g.M = v.T; g.N = v.dh; g.K = v.T;
-      g.z_outer = v.B; g.z_inner = v.H;
-      g.sAo = (long long)v.H * v.T * v.ldT; g.sAi = (long long)v.T * v.ldT; g.sBo = (long long)v.T * 3 * v.D; g.sBi = v.dh;
-      g.C = b.o; g.ldc = v.D; g.sCo = (long long)v.T * v.D; g.sCi = v.dh;
-      ET_G(g);
+    if (et::attention_fused_supported(v.T, v.dh)) {
+      KernelTimer kt(c, 5, 4.0 * v.B * v.H * (double)v.T * v.T * v.dh);
+      ET_K(1, et::attention_fwd(b.qkv, b.o, b.lse, v.B, v.T, v.H, v.dh, v.scale, c->stream));
+    } else {
+      {  // S = scale * Q K^T per (batch, head)
+        et::GemmDesc g;
+        g.A = b.qkv; g.lda = 3 * v.D; g.B = b.qkv + v.D; g.ldb = 3 * v.D; g.M = v.T; g.N = v.T; g.K = v.dh;
+        g.z_outer = v.B; g.z_inner = v.H;
+        g.sAo = (long long)v.T * 3 * v.D; g.sAi = v.dh; g.sBo = g.sAo; g.sBi = v.dh;
+        g.C = c->s_f32; g.c_f32 = true; g.ldc = v.ldT; g.sCo = (long long)v.H * v.T * v.ldT; g.sCi = (long long)v.T * v.ldT;
+        g.alpha = v.scale;
+        ET_G(g);
+      }
+      ET_K(1, et::softmax_rows(c->s_f32, b.p, v.B * v.H * v.T, v.T, v.ldT, c->stream));
+      {  // O = P V
+        et::GemmDesc g;
+        g.A = b.p; g.lda = v.ldT; g.B = b.qkv + 2 * v.D; g.b_t = true; g.ldb = 3 * v.D; g.M = v.T; g.N = v.dh; g.K = v.T;
+        g.z_outer = v.B; g.z_inner = v.H;
+        g.sAo = (long long)v.H * v.T * v.ldT; g.sAi = (long long)v.T * v.ldT; g.sBo = (long long)v.T * 3 * v.D; g.sBi = v.dh;
+        g.C = b.o; g.ldc = v.D; g.sCo = (long long)v.T * v.D; g.sCi = v.dh;
+        ET_G(g);
+      }
     }
     {
       et::GemmDesc g = linear_fwd(b.o, W(t0 + 4), W(t0 + 5), v.M, v.D, v.D);
@@ -495,6 +501,11 @@ int vit_forward(et_ctx* c, const void* x, const int32_t* y) {
 }
 
 int vit_attention_backward(et_ctx* c, const VitDims& v, VitBlockBufs& b) {
+  if (et::attention_fused_supported(v.T, v.dh)) {
+    KernelTimer kt(c, 6, 8.0 * v.B * v.H * (double)v.T * v.T * v.dh);
+    ET_K(1, et::attention_bwd(b.qkv, c->dattn, b.lse, c->dqkv, v.B, v.T, v.H, v.dh, v.scale, c->stream));
+    return ET_OK;
+  }
   const long long sQo = (long long)v.T * 3 * v.D, sPo = (long long)v.H * v.T * v.ldT, sPi = (long long)v.T * v.ldT;
   const long long sOo = (long long)v.T * v.D;
   auto batched = [&](et::GemmDesc& g) { g.z_outer = v.B; g.z_inner = v.H; };

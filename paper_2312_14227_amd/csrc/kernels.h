@@ -100,6 +100,15 @@ hipError_t softmax_rows(const float* s, bf16* p, int rows, int cols, int ld, hip
 hipError_t softmax_bwd_rows(const float* dp, const bf16* p, bf16* ds, float scale, int rows, int cols, int ld,
                             hipStream_t stream);
 
+// fused attention core (tokens <= 224, head size 64), one workgroup per (batch, head):
+//   forward: out[b][t][h*64+d] = softmax(Q K^T * scale) V, lse[b][h][t] = log-sum-exp of the scaled scores
+//   backward: dqkv (same layout as qkv) from dout, recomputing the probabilities from lse
+bool attention_fused_supported(int T, int head_dim);
+hipError_t attention_fwd(const bf16* qkv, bf16* out, float* lse, int B, int T, int H, int head_dim, float scale,
+                         hipStream_t s);
+hipError_t attention_bwd(const bf16* qkv, const bf16* dout, const float* lse, bf16* dqkv, int B, int T, int H,
+                         int head_dim, float scale, hipStream_t s);
+
 // mean softmax cross-entropy: loss (1 float), dlogits fp32 and (if not null) a bf16 copy [B][ld16], zero padded
 hipError_t xent(const float* logits, const int32_t* y, int B, int C, float* loss, float* dlogits, bf16* dlogits_bf16,
                 int ld16, hipStream_t s);

@@ -121,10 +121,10 @@ __global__ __launch_bounds__(256) void layernorm_bwd_dx_kernel(const bf16* __res
 }
 
 // ---------------------------------------------------------------------------------------------
-// column sums, stage 1: a block of 32 column-threads (8 columns each) x 8 row-threads sums
-// CS_ROWS rows of 256 columns; stage 2 adds the row-chunk partials in ascending order
+// column sums, stage 1: a block of 8 column-threads (8 columns each) x 32 row-threads sums
+// CS_ROWS rows of 64 columns; stage 2 adds the row-chunk partials in ascending order
 // ---------------------------------------------------------------------------------------------
-constexpr int CS_ROWS = 128;
+constexpr int CS_ROWS = 512, CS_COLS = 64;
 
 template <bool F32IN, bool XHAT>
 __global__ __launch_bounds__(256) void colsum_stage1(const bf16* __restrict__ d16, const float* __restrict__ d32,
@@ -132,15 +132,15 @@ __global__ __launch_bounds__(256) void colsum_stage1(const bf16* __restrict__ d1
                                                      long long h_stride, const float* __restrict__ mean,
                                                      const float* __restrict__ rstd, float* __restrict__ partials,
                                                      int rows, int cols) {
-  __shared__ float red[8][256];
-  const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
-  const int c0 = blockIdx.x * 256 + cx * 8;
+  __shared__ float red[32][CS_COLS + 1];
+  const int cx = threadIdx.x & 7, ry = threadIdx.x >> 3;
+  const int c0 = blockIdx.x * CS_COLS + cx * 8;
   const int r_begin = blockIdx.y * CS_ROWS, r_end = min(rows, r_begin + CS_ROWS);
   float acc[8];
 #pragma unroll
   for (int j = 0; j < 8; j++) acc[j] = 0.f;
   if (c0 < cols) {
-    for (int r = r_begin + ry; r < r_end; r += 8) {
+    for (int r = r_begin + ry; r < r_end; r += 32) {
       float v[8];
       if (F32IN) {
         const float4 a = *(const float4*)(d32 + (long long)r * d_stride + c0);
@@ -165,12 +165,14 @@ __global__ __launch_bounds__(256) void colsum_stage1(const bf16* __restrict__ d1
 #pragma unroll
   for (int j = 0; j < 8; j++) red[ry][cx * 8 + j] = acc[j];
   __syncthreads();
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c < cols) {
-    float s = red[0][threadIdx.x];
+  if (threadIdx.x < CS_COLS) {
+    const int c = blockIdx.x * CS_COLS + threadIdx.x;
+    if (c < cols) {
+      float s = red[0][threadIdx.x];
 #pragma unroll
-    for (int k = 1; k < 8; k++) s += red[k][threadIdx.x];
-    partials[(long long)blockIdx.y * cols + c] = s;
+      for (int k = 1; k < 32; k++) s += red[k][threadIdx.x];
+      partials[(long long)blockIdx.y * cols + c] = s;
+    }
   }
 }
 
@@ -341,7 +343,7 @@ hipError_t colsum(const bf16* d, const float* d_f32, long long d_stride, const f
     return hipErrorInvalidValue;
   if ((d && !al16(d)) || (d_f32 && !al16(d_f32)) || (h && !al16(h))) return hipErrorInvalidValue;
   const int chunks = (rows + CS_ROWS - 1) / CS_ROWS;
-  dim3 grid((cols + 255) / 256, chunks), block(256);
+  dim3 grid((cols + CS_COLS - 1) / CS_COLS, chunks), block(256);
   if (d_f32) {
     if (h)
       hipLaunchKernelGGL((colsum_stage1<true, true>), grid, block, 0, s, d, d_f32, d_stride, h, h_stride, mean, rstd,

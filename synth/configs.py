@@ -61,6 +61,10 @@ CONFIGS = {
     # spans several GEMM tiles with ragged tails in every dimension
     "vit_small": ViTConfig("vit_small", 3, 197, 200, 192, 3, 320, 2, 56),
     "vit_mid": ViTConfig("vit_mid", 5, 197, 768, 384, 6, 1536, 3, 200),
+    # more tokens than the fused attention kernels take: exercises the unfused attention path
+    "vit_t230": ViTConfig("vit_t230", 2, 230, 64, 128, 2, 256, 1, 16),
+    # fewer tokens: one and two key tiles in the fused attention kernels
+    "vit_t40": ViTConfig("vit_t40", 3, 40, 64, 128, 2, 256, 2, 16),
 }
 
 

@@ -52,7 +52,8 @@ def test_mlp_all_16_masks():
     s.close()
 
 
-@pytest.mark.parametrize("name,seed", [("vit_small", 0), ("vit_small", 1), ("vit_mid", 2)])
+@pytest.mark.parametrize("name,seed", [("vit_small", 0), ("vit_small", 1), ("vit_mid", 2), ("vit_t230", 3),
+                                       ("vit_t40", 4)])
 def test_vit_masks_match_oracle(name, seed):
     cfg = CONFIGS[name]
     wl = make_workload(cfg, seed=seed, init="random")
