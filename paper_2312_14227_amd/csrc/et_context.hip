@@ -603,7 +603,7 @@ int vit_backward(et_ctx* c, const void* x, const uint8_t* mask) {
       Region r(c, PH_DW, t0 + 10);
       ET_G(linear_dw(c, c->dh16, v.D, b.ga, v.F, c->grad[t0 + 10], v.M, v.D, v.F));
     }
-    if (pass(t0 + 10)) {  // through fc2.W, then through the GELU
+    if (pass(t0 + 10)) {  // through fc2.W, then through the GELU (b.u holds gelu'(pre-activation))
       Region r(c, PH_DY, t0 + 10);
       et::GemmDesc g = linear_dx(c->dh16, W(t0 + 10), v.M, v.D, v.F);
       g.mode = et::EPI_GELU_BWD; g.U = b.u; g.C = c->du;

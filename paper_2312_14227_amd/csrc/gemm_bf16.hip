@@ -56,7 +56,7 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   p.sAo = d.sAo; p.sAi = d.sAi; p.sBo = d.sBo; p.sBi = d.sBi; p.sCo = d.sCo; p.sCi = d.sCi;
   p.split_k = 1; p.k_chunk = 0;
   p.alpha = d.alpha; p.bias = d.bias; p.residual = d.residual; p.ldr = d.ldr;
-  p.C = d.C; p.ldc = d.ldc; p.C2 = d.C2; p.U = d.U; p.no_store = d.no_store ? 1 : 0;
+  p.C = d.C; p.ldc = d.ldc; p.C2 = d.C2; p.U = d.U; p.no_store = d.no_store;
   int zdim = d.z_outer * d.z_inner;
   int epi;
   int k_per_block = d.K;

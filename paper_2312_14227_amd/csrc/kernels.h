@@ -21,8 +21,8 @@ typedef __bf16 bf16;
 // ------------------------------------------------------------------------------------------
 enum EpiMode : int {
   EPI_PLAIN = 0,     // C = v
-  EPI_GELU_FWD = 1,  // C = v (pre-activation, bf16), C2 = gelu(v) (bf16)
-  EPI_GELU_BWD = 2,  // C = v * gelu'(U)
+  EPI_GELU_FWD = 1,  // C = gelu'(v) (bf16, kept for the backward pass), C2 = gelu(v) (bf16)
+  EPI_GELU_BWD = 2,  // C = v * U, U = the stored gelu'(u)
 };
 
 struct GemmDesc {
@@ -50,7 +50,7 @@ struct GemmDesc {
   bf16* C2 = nullptr;              // EPI_GELU_FWD
   const bf16* U = nullptr;         // EPI_GELU_BWD, same leading dimension as C
   int tile = 0;                    // 0 = choose by shape; else a TileId (tuning/tests)
-  bool no_store = false;           // tuning aid: run the main loop, store nothing
+  int no_store = 0;                // tuning aids (bit 0: store nothing, bit 1: no loads, bit 2: one panel)
 };
 
 // returns hipSuccess, or hipErrorInvalidValue when a requirement above is violated
