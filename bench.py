@@ -128,9 +128,15 @@ def main():
     if gemm:
         dom = max(gemm, key=lambda c: gemm[c][1])
         n, ns, work = gemm[dom]
+        traffic = None
+        try:   # measured separately with rocprofv3 --pmc (bench.py cannot run the profiler on itself)
+            with open(os.path.join(ROOT, "paper_2312_14227_amd", "measured_traffic.json")) as fh:
+                traffic = json.load(fh).get(cfg.name, {}).get(GEMM_CLASS_NAMES[dom], {}).get("bytes_per_launch")
+        except OSError:
+            pass
         roofline = {"bound": "mfma", "kernel": GEMM_CLASS_NAMES[dom], "achieved": work / ns / 1e3,
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": work / ns / 1e3 / PEAK_BF16_TFLOPS,
-                    "traffic": None, "avg_launch_us": ns / n / 1e3, "flops_per_launch": work / n,
+                    "traffic": traffic, "avg_launch_us": ns / n / 1e3, "flops_per_launch": work / n,
                     "launches_per_step": n / a.steps}
         all_ns = sum(v[1] for v in gemm.values())
         all_work = sum(v[2] for v in gemm.values())
