@@ -133,6 +133,16 @@ int et_profile(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, int32_t war
 int et_importance(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, void* const* w_snapshot_dev /*[N]*/,
                   double* importance_host /*[N]*/);
 
+/* The same evaluation with full-precision weight updates, for ET_BF16 models: delta w is taken
+ * between float32 snapshots and the float32 master weights (optimizer state slot 0) instead of
+ * the bf16 copies, whose rounding step is of the size of a few low-learning-rate updates
+ * (Section 4 assumes updates proportional to a learning rate of 1e-4..1e-5).
+ * w_snapshot_f32_dev[i]: float32 [numel_i], a copy of the master weights taken earlier.
+ * Needs optimizer state bound; ET_ESTATE otherwise, ET_EINVAL for ET_F32 models (use
+ * et_importance there). */
+int et_importance_master(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, void* const* w_snapshot_f32_dev /*[N]*/,
+                         double* importance_host /*[N]*/);
+
 /* Tensor Selector (Eq. 3 solved exactly on integers; Sections 3.3 and 6).  Pure host code,
  * no context, no device.  Maximises the summed importance of the selected tensors subject to
  *   t_fwd + sum_{i selected} t_dw[i] + sum_{i > i*} t_dy[i] <= rho * T_full,

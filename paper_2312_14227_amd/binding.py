@@ -54,6 +54,7 @@ def _load():
         "et_bind": (C.c_int, [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), vp, C.c_size_t]),
         "et_profile": (C.c_int, [vp, vp, vp, i32, i32, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64)]),
         "et_importance": (C.c_int, [vp, vp, vp, C.POINTER(vp), C.POINTER(C.c_double)]),
+        "et_importance_master": (C.c_int, [vp, vp, vp, C.POINTER(vp), C.POINTER(C.c_double)]),
         "et_select": (C.c_int, [i32, C.POINTER(C.c_double), C.POINTER(u64), C.POINTER(u64), u64, C.c_uint32,
                                 C.c_uint32, C.POINTER(C.c_uint8), C.POINTER(u64)]),
         "et_train_step": (C.c_int, [vp, vp, vp, C.POINTER(C.c_uint8), C.POINTER(et_opt), C.POINTER(C.c_float)]),
@@ -73,7 +74,7 @@ def _load():
 
 _lib = _load()
 EXPORTS = ["et_create", "et_destroy", "et_num_tensors", "et_tensor_info", "et_workspace_bytes", "et_state_slots",
-           "et_bind", "et_profile", "et_importance", "et_select", "et_train_step", "et_last_launch_counts",
+           "et_bind", "et_profile", "et_importance", "et_importance_master", "et_select", "et_train_step", "et_last_launch_counts",
            "et_kernel_timing", "et_kernel_timing_read", "et_last_hip_error", "et_strerror", "et_debug_gemm_bf16", "et_debug_copy"]
 
 
@@ -164,6 +165,14 @@ def et_importance(ctx, x_dev, y_dev, w_snapshot_dev):
     out = (C.c_double * n)()
     _check(_lib.et_importance(ctx, C.c_void_p(x_dev), C.c_void_p(y_dev), _ptr_array(w_snapshot_dev), out),
            "et_importance", ctx=ctx)
+    return np.array(out[:], dtype=np.float64)
+
+
+def et_importance_master(ctx, x_dev, y_dev, w_snapshot_f32_dev):
+    n = et_num_tensors(ctx)
+    out = (C.c_double * n)()
+    _check(_lib.et_importance_master(ctx, C.c_void_p(x_dev), C.c_void_p(y_dev), _ptr_array(w_snapshot_f32_dev), out),
+           "et_importance_master", ctx=ctx)
     return np.array(out[:], dtype=np.float64)
 
 

@@ -77,7 +77,12 @@ class Session:
         return et.et_train_step(self.ctx, xt.data_ptr(), yt.data_ptr(), mask, opt, want_loss)
 
     def importance(self, xt, yt, snap):
+        """snap: list of device tensors in the model's storage type (e.g. clones of self.w)."""
         return et.et_importance(self.ctx, xt.data_ptr(), yt.data_ptr(), [s.data_ptr() for s in snap])
+
+    def importance_master(self, xt, yt, snap_f32):
+        """snap_f32: list of float32 device tensors (earlier copies of the master weights)."""
+        return et.et_importance_master(self.ctx, xt.data_ptr(), yt.data_ptr(), [s.data_ptr() for s in snap_f32])
 
     def profile(self, xt, yt, warmup=2, reps=5):
         return et.et_profile(self.ctx, xt.data_ptr(), yt.data_ptr(), warmup, reps)

@@ -126,3 +126,39 @@ def test_profile_and_select_bit_exact_on_device_inputs(name):
             assert list(mask) == list(want["mask"]), (rho, Tq)
             assert pred == want["predicted_ns"]
     s.close()
+
+
+def test_importance_from_master_weights():
+    """Full-precision weight updates: float32 snapshots against the float32 master weights."""
+    import torch
+    from paper_2312_14227_amd import binding as et
+    from paper_2312_14227_amd.session import make_opt
+    cfg = CONFIGS["vit_small"]
+    wl = make_workload(cfg, seed=2, init="random")
+    N = len(wl.weights)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    snap = [st[0].clone() for st in s.state]
+    ones = np.ones(N, dtype=np.uint8)
+    for step in (1, 2, 3):
+        s.train_step(xt, yt, ones, make_opt("adam", lr=1e-5, step=step))
+    I = s.importance_master(xt, yt, snap)
+    torch.cuda.synchronize()
+    g = [s.grads_host(k) for k in range(N)]
+    w = [s.state[k][0].cpu().numpy().astype(np.float64) for k in range(N)]
+    sn = [t.cpu().numpy().astype(np.float64) for t in snap]
+    I_ref = oimp.importance_from_grads(g, w, sn)
+    A_ref = oimp.abs_importance_from_grads(g, w, sn)
+    for k in range(N):
+        assert abs(I[k] - I_ref[k]) <= 1e-5 * A_ref[k] + 1e-300, (wl.names[k], I[k], I_ref[k])
+    assert (I > 0).sum() > N // 2                       # undoing descent steps raises the loss
+    # the bf16 copies barely move at this learning rate: their delta w is mostly rounding noise
+    I16 = s.importance(xt, yt, [t.to(torch.bfloat16) for t in snap])
+    assert np.abs(I16 - I).max() > 0
+    with pytest.raises(et.EtError):
+        mlp = CONFIGS["mlp"]
+        wl2 = make_workload(mlp, seed=0)
+        s2 = _session(mlp, wl2)
+        x2, y2 = s2.put_input(wl2.x, wl2.y)
+        s2.importance_master(x2, y2, [w.clone() for w in s2.w])
+    s.close()
