@@ -17,7 +17,9 @@ extern "C" {
  * C is fp32 if c_f32 else bf16, leading dimension ldc.  split_k > 1 needs c_f32, ldc == N and
  * `partials` with M*N*split_k floats.  A residual needs c_f32 and a_t = b_t = 0.  tile: 0 =
  * automatic, otherwise a tile id of the library (1, 3: register-staged 128x128, 128x64; 5, 7:
- * direct-to-LDS 256x256, 256x128); adding 256 runs the main loop without storing (tuning).
+ * direct-to-LDS 256x256, 256x128); adding 256 runs the main loop without storing (tuning); adding 2048 selects the GELU-forward
+ * epilogue (bf16 C = gelu'(v), second bf16 output gelu(v) through `partials`), adding 4096 the GELU-backward
+ * epilogue (C = v * U, U bf16 [M][ldc] through `partials`).
  * stream: hipStream_t.  Returns 0, or -1 for a rejected argument, -3 for a HIP error. */
 int et_debug_gemm_bf16(const void* A, const void* B, void* C, int M, int N, int K, int lda, int ldb, int ldc,
                        int a_t, int b_t, int c_f32, float alpha, const void* bias, const float* residual,

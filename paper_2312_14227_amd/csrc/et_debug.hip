@@ -13,6 +13,9 @@ extern "C" int et_debug_gemm_bf16(const void* A, const void* B, void* C, int M, 
   g.a_t = a_t != 0; g.b_t = b_t != 0; g.c_f32 = c_f32 != 0; g.alpha = alpha;
   g.bias = (const et::bf16*)bias; g.residual = residual; g.ldr = ldc;
   g.split_k = split_k < 1 ? 1 : split_k; g.partials = partials; g.tile = tile & 255; g.no_store = (tile >> 8) & 7;
+  const int mode = (tile >> 11) & 3;  // 1: GELU forward (partials = second output), 2: GELU backward (partials = U)
+  if (mode == 1) { g.mode = et::EPI_GELU_FWD; g.C2 = (et::bf16*)partials; g.partials = nullptr; g.split_k = 1; }
+  if (mode == 2) { g.mode = et::EPI_GELU_BWD; g.U = (const et::bf16*)partials; g.partials = nullptr; g.split_k = 1; }
   const hipError_t e = et::gemm_bf16(g, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return ET_EINVAL;
   return e == hipSuccess ? ET_OK : ET_EHIP;

@@ -2,8 +2,9 @@
 benchmark workload, sampled so that the file stays small.  Calls only the oracle and the seeded
 generators.  Usage:  python tests/golden/make_full_size_golden.py vit_b [seed] [batch]
 
-Stored per tensor k: 512 seeded element indices idx_k, the oracle gradient at those elements
-g_k (all tensors selected; by the invariant of selective training these are also the values for
+Stored per tensor k: element indices idx_k (512 drawn uniformly with a fixed seed, plus the 512
+elements of largest magnitude, where the mass of the tensor's norm lies), the oracle gradient at
+those elements g_k (all tensors selected; by the invariant of selective training these are also the values for
 any mask that selects k), the gradient's L2 norm, and Eq. 2's importance with its magnitude sum
 for the workload's snapshot.  Also the loss and the logits.
 """
@@ -21,11 +22,14 @@ from synth import CONFIGS, make_workload  # noqa: E402
 SAMPLES = 512
 
 
-def sample_indices(k, numel, seed):
+def sample_indices(k, g, seed):
+    numel = g.size
     rng = np.random.default_rng([seed, 900 + k])
-    if numel <= SAMPLES:
+    if numel <= 2 * SAMPLES:
         return np.arange(numel, dtype=np.int64)
-    return np.sort(rng.choice(numel, size=SAMPLES, replace=False)).astype(np.int64)
+    uniform = rng.choice(numel, size=SAMPLES, replace=False)
+    largest = np.argpartition(np.abs(g.ravel()), numel - SAMPLES)[numel - SAMPLES:]
+    return np.unique(np.concatenate([uniform, largest])).astype(np.int64)
 
 
 def main():
@@ -40,7 +44,7 @@ def main():
                batch=np.int64(batch), seed=np.int64(seed),
                gnorm=np.array([np.linalg.norm(g.ravel()) for g in r["grads"]]))
     for k, g in enumerate(r["grads"]):
-        idx = sample_indices(k, g.size, seed)
+        idx = sample_indices(k, g, seed)
         out["idx_%d" % k] = idx.astype(np.int32)
         out["g_%d" % k] = g.ravel()[idx]
     tag = name if batch == cfg.batch else "%s_b%d" % (name, batch)

@@ -1,6 +1,7 @@
-"""Parity at the full size of the benchmark workload (ViT-B shape, batch 64), in the launch
-configuration bench.py times, against oracle values stored by tests/golden/make_full_size_golden.py
-(512 seeded gradient elements per tensor, gradient norms, loss, importance)."""
+"""Parity at the full size of the benchmark workloads (ViT-B shape at batch 64, ViT-L shape at batch
+32), in the launch configuration bench.py times, against oracle values stored by tests/golden/make_full_size_golden.py
+(per tensor 512 uniformly drawn gradient elements plus its 512 largest ones, gradient norms, loss,
+importance)."""
 import os
 
 import numpy as np
@@ -10,14 +11,15 @@ from gpu_util import rel_l2
 from synth import CONFIGS, make_workload
 
 pytestmark = pytest.mark.gpu
-GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "vit_b_seed0.npz")
+GOLD_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 
-def test_vit_b_full_size_gradients_importance_and_masks():
+@pytest.mark.parametrize("name,first", [("vit_b", 87), ("vit_l", 200)])
+def test_full_size_gradients_importance_and_masks(name, first):
     import torch
     from paper_2312_14227_amd.session import Session
-    G = np.load(GOLD)
-    cfg = CONFIGS["vit_b"]
+    G = np.load(os.path.join(GOLD_DIR, "%s_seed0.npz" % name))
+    cfg = CONFIGS[name]
     assert int(G["batch"]) == cfg.batch
     wl = make_workload(cfg, seed=int(G["seed"]))
     N = len(wl.weights)
@@ -25,6 +27,7 @@ def test_vit_b_full_size_gradients_importance_and_masks():
     xt, yt = s.put_input(wl.x, wl.y)
     snap = s.put_snapshot(wl.snapshot)
     tol = 2e-2
+    errs = {}
     I = s.importance(xt, yt, snap)                 # full backward, gradients stay in the buffers
     torch.cuda.synchronize()
     full = [g.clone() for g in s.grad]
@@ -34,7 +37,7 @@ def test_vit_b_full_size_gradients_importance_and_masks():
         got = full[k][idx].cpu().numpy()
         err = rel_l2(got, G["g_%d" % k])
         worst = max(worst, err)
-        assert err <= tol, (wl.names[k], err)
+        errs[wl.names[k]] = err
         nrm = float(torch.linalg.vector_norm(full[k].double()))
         assert abs(nrm - G["gnorm"][k]) <= tol * G["gnorm"][k], (wl.names[k], nrm, G["gnorm"][k])
         # a gradient within tol (relative L2) moves g.dw by at most tol |g| |dw| (Cauchy-Schwarz)
@@ -42,13 +45,17 @@ def test_vit_b_full_size_gradients_importance_and_masks():
         bound = tol * max(abs(G["importance"][k]), G["gnorm"][k] * dwn)
         worst_i = max(worst_i, abs(I[k] - G["importance"][k]) / bound)
         assert abs(I[k] - G["importance"][k]) <= bound, (wl.names[k], I[k], G["importance"][k])
+    top = sorted(errs.items(), key=lambda kv: -kv[1])[:6]
+    print("largest sampled gradient errors:", [(n, round(e, 4)) for n, e in top],
+          "| tensors above 2e-2:", sum(e > 2e-2 for e in errs.values()), "of", N)
+    assert top[0][1] <= tol, top
     print("worst sampled relative L2 gradient error at full size: %.3e; worst importance error / bound: %.3f"
           % (worst, worst_i))
     # a selective step: selected gradients are the very same numbers, the rest is not written
     rng = np.random.default_rng(0)
     mask = np.zeros(N, dtype=np.uint8)
-    mask[87:] = rng.random(N - 87) < 0.3
-    mask[87] = 1
+    mask[first:] = rng.random(N - first) < 0.3
+    mask[first] = 1
     for g in s.grad:
         g.fill_(float("nan"))
     loss = s.train_step(xt, yt, mask)
