@@ -290,8 +290,14 @@ def vit_step(cfg, weights, x, y, mask):
 
 
 def forward(cfg, weights, x, y):
+    if cfg.kind == "resnet":
+        from . import resnet
+        return resnet.resnet_forward(cfg, weights, x, y)
     return (mlp_forward if cfg.kind == "mlp" else vit_forward)(cfg, weights, x, y)
 
 
 def step(cfg, weights, x, y, mask):
+    if cfg.kind == "resnet":
+        from . import resnet
+        return resnet.resnet_step(cfg, weights, x, y, mask)
     return (mlp_step if cfg.kind == "mlp" else vit_step)(cfg, weights, x, y, mask)

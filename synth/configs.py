@@ -47,6 +47,28 @@ class ViTConfig:
         return self.batch * self.tokens
 
 
+@dataclass(frozen=True)
+class ResNetConfig:
+    """Bottleneck ResNet on NHWC images; BatchNorm folded into a per-channel affine (gain, shift).
+
+    Stem: 7x7/2 convolution, affine, ReLU, 3x3/2 max pooling.  Stage i has blocks[i] bottleneck
+    blocks of planes[i] -> 4*planes[i] channels (1x1, 3x3, 1x1 convolutions, each followed by an
+    affine; ReLU after the first two and after the residual sum); the 3x3 convolution of the first
+    block of stages 1.. has stride 2 and that block has a 1x1 projection shortcut (so has the
+    first block of stage 0, stride 1).  Global average pooling and a linear head follow.
+    Convolutions carry no bias.  Weights are stored [out, kh, kw, in]."""
+    name: str
+    batch: int
+    image: int
+    in_ch: int
+    stem: int
+    blocks: Tuple[int, ...]
+    planes: Tuple[int, ...]
+    classes: int
+    dtype: str = "bf16"
+    kind: str = "resnet"
+
+
 CONFIGS = {
     # BASELINE configs[0]: 4-layer ReLU MLP, fp32, batch 32
     "mlp": MLPConfig("mlp", (256, 256, 256, 256, 10), 32),
@@ -54,6 +76,10 @@ CONFIGS = {
     "vit_b": ViTConfig("vit_b", 64, 197, 768, 768, 12, 3072, 12, 200),
     # BASELINE configs[3]: ViT-L/16 shape, batch 32
     "vit_l": ViTConfig("vit_l", 32, 197, 768, 1024, 16, 4096, 24, 200),
+    # BASELINE configs[4]: ResNet-50 shape, batch 32
+    "resnet50": ResNetConfig("resnet50", 32, 224, 3, 64, (3, 4, 6, 3), (64, 128, 256, 512), 200),
+    "resnet_tiny": ResNetConfig("resnet_tiny", 2, 16, 3, 8, (1, 1), (8, 8), 8),
+    "resnet_small": ResNetConfig("resnet_small", 3, 64, 3, 16, (2, 1, 2, 1), (8, 16, 24, 32), 24),
     # small cases the oracle finishes in well under a second
     "mlp_tiny": MLPConfig("mlp_tiny", (8, 8, 8, 4), 4),
     "mlp5": MLPConfig("mlp5", (6, 6, 6, 6, 6, 3), 4),
@@ -84,5 +110,19 @@ def tensor_specs(cfg) -> List[Tuple[str, Tuple[int, ...]]]:
                     (p + "fc1.W", (F, D)), (p + "fc1.b", (F,)),
                     (p + "fc2.W", (D, F)), (p + "fc2.b", (D,))]
         out += [("lnf.g", (D,)), ("lnf.b", (D,)), ("head.W", (cfg.classes, D)), ("head.b", (cfg.classes,))]
+        return out
+    if cfg.kind == "resnet":
+        out = [("stem.W", (cfg.stem, 7, 7, cfg.in_ch)), ("stem.g", (cfg.stem,)), ("stem.b", (cfg.stem,))]
+        cin = cfg.stem
+        for si, (nb, p) in enumerate(zip(cfg.blocks, cfg.planes)):
+            for bi in range(nb):
+                n = "s%db%d." % (si, bi)
+                out += [(n + "c1.W", (p, 1, 1, cin)), (n + "c1.g", (p,)), (n + "c1.b", (p,)),
+                        (n + "c2.W", (p, 3, 3, p)), (n + "c2.g", (p,)), (n + "c2.b", (p,)),
+                        (n + "c3.W", (4 * p, 1, 1, p)), (n + "c3.g", (4 * p,)), (n + "c3.b", (4 * p,))]
+                if bi == 0:      # projection shortcut; in chain order it follows the main branch
+                    out += [(n + "sc.W", (4 * p, 1, 1, cin)), (n + "sc.g", (4 * p,)), (n + "sc.b", (4 * p,))]
+                cin = 4 * p
+        out += [("head.W", (cfg.classes, cin)), ("head.b", (cfg.classes,))]
         return out
     raise ValueError(cfg.kind)

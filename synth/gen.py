@@ -28,7 +28,7 @@ class Workload:
     names: List[str]
     weights: List[np.ndarray]    # float32, chain order; bf16-representable for bf16 configs
     snapshot: List[np.ndarray]   # weights + N(0, std 1e-3), same representation
-    x: np.ndarray                # MLP: [B, dims[0]]; ViT: [B, tokens-1, patch_dim]
+    x: np.ndarray                # MLP: [B, dims[0]]; ViT: [B, tokens-1, patch_dim]; ResNet: [B, H, W, C]
     y: np.ndarray                # int32 labels, uniform over the classes
 
 
@@ -63,6 +63,14 @@ def make_workload(cfg, seed: int = 0, init: str = "paper", batch: int = None) ->
         rng = _rng(seed, 100 + i)
         if cfg.kind == "mlp":
             w = rng.standard_normal(shape) * np.sqrt(2.0 / shape[1])        # Kaiming normal, fan-in
+        elif cfg.kind == "resnet":
+            leaf = name.split(".")[-1]
+            if leaf == "W":                                                  # He normal, fan-in
+                w = rng.standard_normal(shape) * np.sqrt(2.0 / int(np.prod(shape[1:])))
+            elif leaf == "g":
+                w = np.ones(shape) if init == "paper" else 1.0 + 0.1 * rng.standard_normal(shape)
+            else:
+                w = np.zeros(shape) if init == "paper" else 0.05 * rng.standard_normal(shape)
         else:
             leaf = name.split(".")[-1]
             if leaf == "W" or name in ("cls", "pos"):
@@ -78,6 +86,8 @@ def make_workload(cfg, seed: int = 0, init: str = "paper", batch: int = None) ->
         snapshot.append(s)
     if cfg.kind == "mlp":
         x = _rng(seed, 1).standard_normal((B, cfg.dims[0])).astype(np.float32)
+    elif cfg.kind == "resnet":
+        x = quant(_rng(seed, 1).standard_normal((B, cfg.image, cfg.image, cfg.in_ch)).astype(np.float32))
     else:
         x = quant(_rng(seed, 1).standard_normal((B, cfg.tokens - 1, cfg.patch_dim)).astype(np.float32))
     y = _rng(seed, 2).integers(0, cfg.classes, size=B).astype(np.int32)

@@ -1,0 +1,95 @@
+"""Pins of the oracle's ResNet forward/backward pass: finite differences, PyTorch CPU autograd over
+library convolution/pooling ops, and the executed-work invariants of selective training."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import nets, resnet
+from synth import CONFIGS, make_workload, tensor_specs
+
+
+def test_tensor_count_of_resnet50():
+    assert len(tensor_specs(CONFIGS["resnet50"])) == 161       # 53 convolutions x (W, gain, shift) + head W, b
+
+
+def test_gradients_match_finite_differences():
+    cfg = CONFIGS["resnet_tiny"]
+    wl = make_workload(cfg, seed=3, init="random")
+    N = len(wl.weights)
+    r = nets.step(cfg, wl.weights, wl.x, wl.y, [1] * N)
+    rng = np.random.default_rng(0)
+    h = 1e-6
+    checked = 0
+    for k in range(N):
+        g = r["grads"][k]
+        assert g.shape == wl.weights[k].shape
+        for _ in range(3):
+            idx = tuple(int(rng.integers(0, s)) for s in g.shape)
+            W = [w.astype(np.float64) for w in wl.weights]
+            W[k] = W[k].copy()
+            W[k][idx] += h
+            lp, _ = nets.forward(cfg, W, wl.x, wl.y)
+            W[k][idx] -= 2 * h
+            lm, _ = nets.forward(cfg, W, wl.x, wl.y)
+            fd = (lp - lm) / (2 * h)
+            # ReLU / max-pool kinks make single elements non-differentiable now and then
+            if abs(fd - g[idx]) <= 1e-5 * max(1.0, abs(fd)):
+                checked += 1
+    assert checked >= int(0.95 * 3 * N), checked
+
+
+def _torch_loss(cfg, W, x, y):
+    F = torch.nn.functional
+
+    def conv(h, w, stride):
+        k = w.shape[1]
+        return F.conv2d(h, w.permute(0, 3, 1, 2), stride=stride, padding=(k - 1) // 2)
+
+    def aff(z, g, b):
+        return z * g.view(1, -1, 1, 1) + b.view(1, -1, 1, 1)
+    h = x.permute(0, 3, 1, 2)
+    h = F.max_pool2d(torch.relu(aff(conv(h, W[0], 2), W[1], W[2])), 3, 2, 1)
+    layout, t_head = resnet.block_layout(cfg)
+    for (_, _, stride, proj, t) in layout:
+        y1 = torch.relu(aff(conv(h, W[t], 1), W[t + 1], W[t + 2]))
+        y2 = torch.relu(aff(conv(y1, W[t + 3], stride), W[t + 4], W[t + 5]))
+        m = aff(conv(y2, W[t + 6], 1), W[t + 7], W[t + 8])
+        sh = aff(conv(h, W[t + 9], stride), W[t + 10], W[t + 11]) if proj else h
+        h = torch.relu(m + sh)
+    p = h.mean(dim=(2, 3))
+    return F.cross_entropy(F.linear(p, W[t_head], W[t_head + 1]), y)
+
+
+@pytest.mark.parametrize("name", ["resnet_tiny", "resnet_small"])
+def test_matches_torch_autograd(name):
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg, seed=5, init="random")
+    N = len(wl.weights)
+    r = nets.step(cfg, wl.weights, wl.x, wl.y, [1] * N)
+    W = [torch.tensor(w, dtype=torch.float64, requires_grad=True) for w in wl.weights]
+    loss = _torch_loss(cfg, W, torch.tensor(wl.x, dtype=torch.float64), torch.tensor(wl.y, dtype=torch.long))
+    loss.backward()
+    assert abs(loss.item() - r["loss"]) <= 1e-12 * abs(loss.item())
+    for k in range(N):
+        ref = W[k].grad.numpy()
+        err = np.linalg.norm(r["grads"][k] - ref) / max(np.linalg.norm(ref), 1e-300)
+        assert err <= 1e-10, (wl.names[k], err)
+
+
+def test_executed_work_and_mask_invariants():
+    cfg = CONFIGS["resnet_tiny"]
+    wl = make_workload(cfg, seed=2, init="random")
+    N = len(wl.weights)
+    full = nets.step(cfg, wl.weights, wl.x, wl.y, [1] * N)
+    assert nets.step(cfg, wl.weights, wl.x, wl.y, [0] * N)["work"] == []
+    rng = np.random.default_rng(7)
+    for _ in range(20):
+        mask = (rng.random(N) < rng.choice([0.05, 0.3, 0.8])).astype(int)
+        if not mask.any():
+            mask[rng.integers(0, N)] = 1
+        r = nets.step(cfg, wl.weights, wl.x, wl.y, mask)
+        sel = [j for j in range(N) if mask[j]]
+        assert sorted(j for op, j in r["work"] if op == "dw") == sel
+        assert sorted(j for op, j in r["work"] if op == "dy") == list(range(sel[0] + 1, N))
+        for j in sel:
+            assert np.array_equal(r["grads"][j], full["grads"][j])
