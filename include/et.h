@@ -40,6 +40,7 @@ extern "C" {
 /* model kinds */
 #define ET_MLP 0 /* ReLU multi-layer perceptron without biases                      */
 #define ET_VIT 1 /* pre-LN vision transformer encoder on flattened patches          */
+#define ET_RESNET 2 /* bottleneck residual CNN, BatchNorm folded into per-channel affines */
 
 /* storage types of weights and activations */
 #define ET_F32 0  /* float32 everywhere                                             */
@@ -50,6 +51,7 @@ extern "C" {
 #define ET_SGDW 1
 
 #define ET_MAX_MLP_LAYERS 16
+#define ET_MAX_STAGES 4
 
 typedef struct et_ctx et_ctx;
 
@@ -61,15 +63,27 @@ typedef struct et_ctx et_ctx;
  *   fc1.W [mlp, width], fc1.b, fc2.W [width, mlp], fc2.b, then lnf.g, lnf.b,
  *   head.W [classes, width], head.b.  width, patch_dim, mlp, classes and the head size
  *   width/heads must be multiples of 8 (16-byte rows); tokens is arbitrary.
+ * ET_RESNET: x is [batch, image, image, in_ch] (NHWC), convolution weights are [out, kh, kw, in],
+ *   zero padding (k-1)/2.  Stem: 7x7/2 convolution to `stem` channels, affine, ReLU, 3x3/2 max
+ *   pooling.  Stage i has stage_blocks[i] bottleneck blocks (1x1 to planes[i], 3x3 to planes[i],
+ *   1x1 to 4 planes[i], an affine after each, ReLU after the first two and after the residual
+ *   sum); the 3x3 of the first block of stages 1.. has stride 2; the first block of every stage
+ *   has a 1x1 projection shortcut with the same stride.  Then global average pooling and a
+ *   linear head.  Tensors in chain order (a branched network is unrolled by execution order,
+ *   Section 5): stem.W, stem.g, stem.b; per block c1.W, c1.g, c1.b, c2.*, c3.*, then sc.W,
+ *   sc.g, sc.b for a projection block; head.W [classes, 4 planes[last]], head.b.  stem, planes
+ *   and classes must be multiples of 8.
  * Labels are int32 in [0, classes). The loss is the mean softmax cross-entropy. */
 typedef struct {
-  int32_t kind;  /* ET_MLP | ET_VIT */
-  int32_t dtype; /* ET_F32 (MLP) | ET_BF16 (ViT) */
+  int32_t kind;  /* ET_MLP | ET_VIT | ET_RESNET */
+  int32_t dtype; /* ET_F32 (MLP) | ET_BF16 (ViT, ResNet) */
   int32_t batch;
   int32_t n_layers;                    /* ET_MLP */
   int32_t dims[ET_MAX_MLP_LAYERS + 1]; /* ET_MLP */
   int32_t tokens, patch_dim, width, heads, mlp, blocks, classes; /* ET_VIT */
   float ln_eps;                        /* ET_VIT */
+  int32_t image, in_ch, stem, n_stages;               /* ET_RESNET (classes as above) */
+  int32_t stage_blocks[ET_MAX_STAGES], planes[ET_MAX_STAGES]; /* ET_RESNET */
 } et_model_desc;
 
 /* Optimizer hyper-parameters of one step; every constant is explicit.

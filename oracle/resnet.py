@@ -13,12 +13,34 @@ weights (ReLU, pooling) lies in the dy() of the tensor that has to be passed for
 
 BatchNorm is "folded" (BASELINE): a per-channel affine y = gain * z + shift without batch
 statistics.  Layout NHWC; convolution weights [out, kh, kw, in]; zero padding (k-1)/2.
+
+Storage precision.  With store=None everything is float64 (the plain definition; this is what the
+pins check).  The workload fixes bf16 storage for activations and error gradients; a ReLU network
+turns a rounding of a value next to zero into a dropped or passed gradient element, so on a deep
+network the exact result and ANY bf16 evaluation differ by far more than a rounding.  For the
+comparison with a bf16 evaluation, `store` (e.g. round_bf16) is applied to every tensor that such
+an evaluation keeps in memory between two operations: each convolution output except the stem's
+(kept in fp32 so that the pooling argmax is decided on unrounded values), each affine/ReLU
+output, the pooled features, the bf16 copy of the logit gradient that feeds the matrix products,
+and each error gradient handed from one backward operation to the next.  Arithmetic stays float64.
 """
 import numpy as np
 
 from .nets import _Tiny, _run_chain, softmax_xent
 
 _F = np.float64
+
+
+def round_bf16(a):
+    """Nearest bf16 (ties to even) of float64 values, returned as float64."""
+    f = np.ascontiguousarray(a, dtype=np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(f.shape).astype(_F)
+
+
+def _same(a):
+    return a
 
 
 # ----------------------------------------------------------------------------
@@ -54,20 +76,22 @@ def col2im(dcols, shape, kh, kw, stride, pad):
 class Conv:
     """One convolution with everything its backward operations need."""
 
-    def __init__(self, x, w, stride):
+    def __init__(self, x, w, stride, q=_same):
         self.x_shape = x.shape
         self.w = w
         O, self.kh, self.kw, _ = w.shape
         self.stride, self.pad = stride, (self.kh - 1) // 2
         self.cols = im2col(x, self.kh, self.kw, stride, self.pad)
         self.wm = w.reshape(O, -1)
-        self.out = self.cols @ self.wm.T
+        self.out = q(self.cols @ self.wm.T)
+        self.q = q
 
     def dw(self, d):
         return (d.reshape(-1, d.shape[-1]).T @ self.cols.reshape(-1, self.cols.shape[-1])).reshape(self.w.shape)
 
     def dx(self, d):
-        return col2im(d @ self.wm, self.x_shape, self.kh, self.kw, self.stride, self.pad)
+        dcols = self.q(d @ self.wm)         # the column gradient is a stored tensor
+        return col2im(dcols, self.x_shape, self.kh, self.kw, self.stride, self.pad)
 
 
 def maxpool_3x3_s2(x):
@@ -110,34 +134,36 @@ def block_layout(cfg):
     return out, t
 
 
-def resnet_forward(cfg, weights, x, y):
+def resnet_forward(cfg, weights, x, y, store=None):
+    q = store if store is not None else _same
     W = [np.asarray(w, dtype=_F) for w in weights]
     x = np.asarray(x, dtype=_F)
-    c = {"W": W}
-    stem = Conv(x, W[0], 2)
+    c = {"W": W, "q": q}
+    stem = Conv(x, W[0], 2)                                    # output not rounded (see the header)
     stem_y = np.maximum(stem.out * W[1] + W[2], 0.0)
-    pooled, arg = maxpool_3x3_s2(stem_y)
+    pooled, arg = maxpool_3x3_s2(stem_y)                       # argmax on the unrounded values
+    stem_y, pooled = q(stem_y), q(pooled)
     c.update(stem=stem, stem_y=stem_y, pool_arg=arg)
     blocks = []
     h = pooled
     layout, t_head = block_layout(cfg)
     for (si, bi, stride, proj, t) in layout:
         b = {"x": h, "t": t, "proj": proj}
-        b["c1"] = Conv(h, W[t], 1)
-        b["y1"] = np.maximum(b["c1"].out * W[t + 1] + W[t + 2], 0.0)
-        b["c2"] = Conv(b["y1"], W[t + 3], stride)
-        b["y2"] = np.maximum(b["c2"].out * W[t + 4] + W[t + 5], 0.0)
-        b["c3"] = Conv(b["y2"], W[t + 6], 1)
+        b["c1"] = Conv(h, W[t], 1, q)
+        b["y1"] = q(np.maximum(b["c1"].out * W[t + 1] + W[t + 2], 0.0))
+        b["c2"] = Conv(b["y1"], W[t + 3], stride, q)
+        b["y2"] = q(np.maximum(b["c2"].out * W[t + 4] + W[t + 5], 0.0))
+        b["c3"] = Conv(b["y2"], W[t + 6], 1, q)
         m = b["c3"].out * W[t + 7] + W[t + 8]
         if proj:
-            b["sc"] = Conv(h, W[t + 9], stride)
+            b["sc"] = Conv(h, W[t + 9], stride, q)
             sh = b["sc"].out * W[t + 10] + W[t + 11]
         else:
             sh = h
-        h = np.maximum(m + sh, 0.0)
+        h = q(np.maximum(m + sh, 0.0))
         b["y"] = h
         blocks.append(b)
-    p = h.mean(axis=(1, 2))
+    p = q(h.mean(axis=(1, 2)))
     logits = p @ W[t_head].T + W[t_head + 1]
     loss, dlogits = softmax_xent(logits, np.asarray(y))
     c.update(blocks=blocks, last=h, pooled_in=pooled, p=p, logits=logits, dlogits=dlogits, t_head=t_head)
@@ -147,14 +173,16 @@ def resnet_forward(cfg, weights, x, y):
 # ----------------------------------------------------------------------------
 # masked backward on the tensor-level chain
 # ----------------------------------------------------------------------------
-def resnet_step(cfg, weights, x, y, mask):
-    loss, c = resnet_forward(cfg, weights, x, y)
+def resnet_step(cfg, weights, x, y, mask, store=None):
+    loss, c = resnet_forward(cfg, weights, x, y, store)
+    q = c["q"]
     W, blocks, t_head = c["W"], c["blocks"], c["t_head"]
     N = len(W)
     # state: d    = gradient w.r.t. the output of the tiny layer being visited
     #        dsum = gradient w.r.t. the pre-ReLU sum at the end of the current block (both branches)
     #        dsc  = gradient w.r.t. the output of the current block's shortcut convolution
-    state = {"d": c["dlogits"], "dsum": None, "dsc": None}
+    #        dl   = the logit gradient as the matrix products read it
+    state = {"d": c["dlogits"], "dl": q(c["dlogits"]), "dsum": None, "dsc": None}
 
     def identity(s):
         pass
@@ -164,11 +192,11 @@ def resnet_step(cfg, weights, x, y, mask):
     # ---- head
     def head_dy(s):
         last = c["last"]
-        dp = s["d"] @ W[t_head]                                    # through the head matrix
+        dp = q(s["dl"] @ W[t_head])                                # through the head matrix
         d = np.broadcast_to(dp[:, None, None, :] / (last.shape[1] * last.shape[2]), last.shape)  # average pooling
-        s["d"] = d * (last > 0.0)                                  # ReLU closing the last block
+        s["d"] = q(d * (last > 0.0))                               # ReLU closing the last block
         s["dsum"] = s["d"]
-    chain[t_head] = _Tiny(lambda s: s["d"].T @ c["p"], head_dy)
+    chain[t_head] = _Tiny(lambda s: s["dl"].T @ c["p"], head_dy)
     chain[t_head + 1] = _Tiny(lambda s: s["d"].sum(axis=0), identity)
 
     # ---- blocks
@@ -181,7 +209,7 @@ def resnet_step(cfg, weights, x, y, mask):
                 return _sum_channels(s[key] * conv_out)
 
             def dy(s):
-                s[key if key == "d" else "dsc"] = s[key] * W[gidx]
+                s[key if key == "d" else "dsc"] = q(s[key] * W[gidx])
             return _Tiny(dw, dy)
 
         def shift(key):
@@ -192,7 +220,7 @@ def resnet_step(cfg, weights, x, y, mask):
             chain[t + 11] = shift("dsum")
 
             def sc_gain_dy(s, b=b, t=t):
-                s["dsc"] = s["dsum"] * W[t + 10]
+                s["dsc"] = q(s["dsum"] * W[t + 10])
             chain[t + 10] = _Tiny(lambda s, b=b: _sum_channels(s["dsum"] * b["sc"].out), sc_gain_dy)
             chain[t + 9] = _Tiny(lambda s, b=b: b["sc"].dw(s["dsc"]), identity)   # its dX is part of dy(c1.W)
         # main branch
@@ -200,13 +228,13 @@ def resnet_step(cfg, weights, x, y, mask):
         chain[t + 7] = gain(b["c3"].out, t + 7, "d")
 
         def c3_dy(s, b=b):
-            s["d"] = b["c3"].dx(s["d"]) * (b["y2"] > 0.0)
+            s["d"] = q(b["c3"].dx(s["d"]) * (b["y2"] > 0.0))
         chain[t + 6] = _Tiny(lambda s, b=b: b["c3"].dw(s["d"]), c3_dy)
         chain[t + 5] = shift("d")
         chain[t + 4] = gain(b["c2"].out, t + 4, "d")
 
         def c2_dy(s, b=b):
-            s["d"] = b["c2"].dx(s["d"]) * (b["y1"] > 0.0)
+            s["d"] = q(b["c2"].dx(s["d"]) * (b["y1"] > 0.0))
         chain[t + 3] = _Tiny(lambda s, b=b: b["c2"].dw(s["d"]), c2_dy)
         chain[t + 2] = shift("d")
         chain[t + 1] = gain(b["c1"].out, t + 1, "d")
@@ -215,9 +243,9 @@ def resnet_step(cfg, weights, x, y, mask):
             dx = b["c1"].dx(s["d"])
             dx = dx + (b["sc"].dx(s["dsc"]) if b["proj"] else s["dsum"])      # the two branches meet
             if prev_y is not None:
-                s["d"] = dx * (prev_y > 0.0)                                  # ReLU closing the previous block
+                s["d"] = q(dx * (prev_y > 0.0))                               # ReLU closing the previous block
             else:                                                             # max pooling, then the stem's ReLU
-                s["d"] = maxpool_3x3_s2_backward(dx, c["pool_arg"], c["stem_y"].shape) * (c["stem_y"] > 0.0)
+                s["d"] = q(maxpool_3x3_s2_backward(q(dx), c["pool_arg"], c["stem_y"].shape) * (c["stem_y"] > 0.0))
             s["dsum"] = s["d"]
         chain[t + 0] = _Tiny(lambda s, b=b: b["c1"].dw(s["d"]), c1_dy)
 
@@ -225,7 +253,7 @@ def resnet_step(cfg, weights, x, y, mask):
     chain[2] = _Tiny(lambda s: _sum_channels(s["d"]), identity)
 
     def stem_gain_dy(s):
-        s["d"] = s["d"] * W[1]
+        s["d"] = q(s["d"] * W[1])
     chain[1] = _Tiny(lambda s: _sum_channels(s["d"] * c["stem"].out), stem_gain_dy)
     chain[0] = _Tiny(lambda s: c["stem"].dw(s["d"]), None)
 

@@ -1,0 +1,431 @@
+// HBM-bound kernels of the convolutional workload (Section 5: every convolution weight, folded
+// BatchNorm gain and shift is one tensor of the chain).  Activations are NHWC bf16, so a
+// convolution is a matrix product over the rows of an im2col matrix [B*Ho*Wo][k*k*C] (column
+// order ky, kx, c — the order of the weights [out][ky][kx][c]); everything here moves 16-byte
+// vectors of 8 channels.  All sums have a fixed order.
+#include "kernels.h"
+
+namespace et {
+namespace {
+
+typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+__device__ __forceinline__ bf16x8 zero8() {
+  bf16x8 z;
+#pragma unroll
+  for (int j = 0; j < 8; j++) z[j] = (bf16)0.f;
+  return z;
+}
+
+// ---------------------------------------------------------------------------------------------
+// im2col, channels a multiple of 8: one thread per (row, tap, 8 channels)
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void im2col_vec_kernel(const bf16* __restrict__ x, bf16* __restrict__ cols,
+                                                         ConvGeom g, long long total) {
+  const int c8n = g.C >> 3, taps = g.k * g.k;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const int c8 = (int)(i % c8n);
+    const long long r = i / c8n;
+    const int t = (int)(r % taps);
+    const long long m = r / taps;
+    const int ow = (int)(m % g.Wo), oh = (int)((m / g.Wo) % g.Ho), b = (int)(m / ((long long)g.Wo * g.Ho));
+    const int h = oh * g.stride - g.pad + t / g.k, w = ow * g.stride - g.pad + t % g.k;
+    bf16x8 v = zero8();
+    if (h >= 0 && h < g.H && w >= 0 && w < g.W)
+      v = *(const bf16x8*)(x + (((long long)b * g.H + h) * g.W + w) * g.C + c8 * 8);
+    *(bf16x8*)(cols + m * g.Kc + (long long)t * g.C + c8 * 8) = v;
+  }
+}
+
+// any channel count (the 3-channel stem): one thread per 8 consecutive columns, scalar gathers;
+// columns from k*k*C up to Kc are zero
+__global__ __launch_bounds__(256) void im2col_any_kernel(const bf16* __restrict__ x, bf16* __restrict__ cols,
+                                                         ConvGeom g, long long total) {
+  const int k8n = g.Kc >> 3, K = g.k * g.k * g.C;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const int j8 = (int)(i % k8n);
+    const long long m = i / k8n;
+    const int ow = (int)(m % g.Wo), oh = (int)((m / g.Wo) % g.Ho), b = (int)(m / ((long long)g.Wo * g.Ho));
+    bf16x8 v;
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      const int col = j8 * 8 + e;
+      bf16 val = (bf16)0.f;
+      if (col < K) {
+        const int t = col / g.C, ch = col % g.C;
+        const int h = oh * g.stride - g.pad + t / g.k, w = ow * g.stride - g.pad + t % g.k;
+        if (h >= 0 && h < g.H && w >= 0 && w < g.W) val = x[(((long long)b * g.H + h) * g.W + w) * g.C + ch];
+      }
+      v[e] = val;
+    }
+    *(bf16x8*)(cols + m * g.Kc + j8 * 8) = v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// adjoint of im2col in gather form: every input pixel adds the (at most k*k) column entries that
+// were copied from it, taps in ascending order; then out = (sum + add) * (mask > 0)
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void col2im_kernel(const bf16* __restrict__ dcols, const bf16* __restrict__ add,
+                                                     const bf16* __restrict__ mask, bf16* __restrict__ out, ConvGeom g,
+                                                     long long total) {
+  const int c8n = g.C >> 3;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const int c8 = (int)(i % c8n);
+    const long long pix = i / c8n;
+    const int w = (int)(pix % g.W), h = (int)((pix / g.W) % g.H), b = (int)(pix / ((long long)g.W * g.H));
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) acc[j] = 0.f;
+    for (int ky = 0; ky < g.k; ky++) {
+      const int hh = h + g.pad - ky;
+      if (hh < 0 || hh % g.stride) continue;
+      const int oh = hh / g.stride;
+      if (oh >= g.Ho) continue;
+      for (int kx = 0; kx < g.k; kx++) {
+        const int ww = w + g.pad - kx;
+        if (ww < 0 || ww % g.stride) continue;
+        const int ow = ww / g.stride;
+        if (ow >= g.Wo) continue;
+        const bf16x8 v = *(const bf16x8*)(dcols + (((long long)b * g.Ho + oh) * g.Wo + ow) * g.Kc +
+                                          (long long)(ky * g.k + kx) * g.C + c8 * 8);
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[j] += (float)v[j];
+      }
+    }
+    const long long o = pix * g.C + c8 * 8;
+    if (add) {
+      const bf16x8 a = *(const bf16x8*)(add + o);
+#pragma unroll
+      for (int j = 0; j < 8; j++) acc[j] += (float)a[j];
+    }
+    bf16x8 r;
+    if (mask) {
+      const bf16x8 mk = *(const bf16x8*)(mask + o);
+#pragma unroll
+      for (int j = 0; j < 8; j++) r[j] = (float)mk[j] > 0.f ? (bf16)acc[j] : (bf16)0.f;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; j++) r[j] = (bf16)acc[j];
+    }
+    *(bf16x8*)(out + o) = r;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// folded BatchNorm: out = act(z1*g1 + b1 + [z2*g2 + b2 | z2]), act = ReLU or identity
+// ---------------------------------------------------------------------------------------------
+template <bool Z32>
+__global__ __launch_bounds__(256) void affine_kernel(const bf16* __restrict__ z1, const float* __restrict__ z1f,
+                                                     const bf16* __restrict__ g1, const bf16* __restrict__ b1,
+                                                     const bf16* __restrict__ z2, const bf16* __restrict__ g2,
+                                                     const bf16* __restrict__ b2, int relu, bf16* __restrict__ out,
+                                                     long long n8, int C) {
+  const int c8n = C >> 3;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (long long)gridDim.x * blockDim.x) {
+    const int c = (int)(i % c8n) * 8;
+    float v[8];
+    if (Z32) {
+      const float4 a = *(const float4*)(z1f + i * 8), b = *(const float4*)(z1f + i * 8 + 4);
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    } else {
+      const bf16x8 a = *(const bf16x8*)(z1 + i * 8);
+#pragma unroll
+      for (int j = 0; j < 8; j++) v[j] = (float)a[j];
+    }
+    const bf16x8 g = *(const bf16x8*)(g1 + c), s = *(const bf16x8*)(b1 + c);
+#pragma unroll
+    for (int j = 0; j < 8; j++) v[j] = v[j] * (float)g[j] + (float)s[j];
+    if (z2) {
+      const bf16x8 a = *(const bf16x8*)(z2 + i * 8);
+      if (g2) {
+        const bf16x8 gg = *(const bf16x8*)(g2 + c), ss = *(const bf16x8*)(b2 + c);
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] += (float)a[j] * (float)gg[j] + (float)ss[j];
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] += (float)a[j];
+      }
+    }
+    bf16x8 r;
+#pragma unroll
+    for (int j = 0; j < 8; j++) r[j] = (bf16)(relu ? fmaxf(v[j], 0.f) : v[j]);
+    *(bf16x8*)(out + i * 8) = r;
+  }
+}
+
+// out = d * gain[c]
+__global__ __launch_bounds__(256) void scale_cols_kernel(const bf16* __restrict__ d, const bf16* __restrict__ gain,
+                                                         bf16* __restrict__ out, long long n8, int C) {
+  const int c8n = C >> 3;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (long long)gridDim.x * blockDim.x) {
+    const bf16x8 a = *(const bf16x8*)(d + i * 8), g = *(const bf16x8*)(gain + (int)(i % c8n) * 8);
+    bf16x8 r;
+#pragma unroll
+    for (int j = 0; j < 8; j++) r[j] = (bf16)((float)a[j] * (float)g[j]);
+    *(bf16x8*)(out + i * 8) = r;
+  }
+}
+
+// out = (a + b) * (mask > 0); b may be null
+__global__ __launch_bounds__(256) void add_mask_kernel(const bf16* __restrict__ a, const bf16* __restrict__ b,
+                                                       const bf16* __restrict__ mask, bf16* __restrict__ out,
+                                                       long long n8) {
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (long long)gridDim.x * blockDim.x) {
+    const bf16x8 x = *(const bf16x8*)(a + i * 8), mk = *(const bf16x8*)(mask + i * 8);
+    bf16x8 r;
+    if (b) {
+      const bf16x8 y = *(const bf16x8*)(b + i * 8);
+#pragma unroll
+      for (int j = 0; j < 8; j++) r[j] = (float)mk[j] > 0.f ? (bf16)((float)x[j] + (float)y[j]) : (bf16)0.f;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; j++) r[j] = (float)mk[j] > 0.f ? x[j] : (bf16)0.f;
+    }
+    *(bf16x8*)(out + i * 8) = r;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// stem: y = relu(z*g + b) evaluated in fp32 from the fp32 convolution output, 3x3 / stride 2 /
+// pad 1 max pooling with the first maximum in (ky, kx) order; and its backward in gather form
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(const float* __restrict__ z, const bf16* __restrict__ gain,
+                                                          const bf16* __restrict__ shift, bf16* __restrict__ out,
+                                                          uint8_t* __restrict__ arg, int B, int H, int W, int C, int Ho,
+                                                          int Wo, long long total) {
+  const int c8n = C >> 3;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const int c8 = (int)(i % c8n);
+    const long long pix = i / c8n;
+    const int ow = (int)(pix % Wo), oh = (int)((pix / Wo) % Ho), b = (int)(pix / ((long long)Wo * Ho));
+    const bf16x8 g = *(const bf16x8*)(gain + c8 * 8), s = *(const bf16x8*)(shift + c8 * 8);
+    float best[8];
+    int bi[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) { best[j] = -INFINITY; bi[j] = 0; }
+    for (int ky = 0; ky < 3; ky++) {
+      const int h = oh * 2 - 1 + ky;
+      if (h < 0 || h >= H) continue;
+      for (int kx = 0; kx < 3; kx++) {
+        const int w = ow * 2 - 1 + kx;
+        if (w < 0 || w >= W) continue;
+        const float* p = z + (((long long)b * H + h) * W + w) * C + c8 * 8;
+        const float4 a = *(const float4*)p, bb = *(const float4*)(p + 4);
+        const float v[8] = {a.x, a.y, a.z, a.w, bb.x, bb.y, bb.z, bb.w};
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+          const float y = fmaxf(v[j] * (float)g[j] + (float)s[j], 0.f);
+          if (y > best[j]) { best[j] = y; bi[j] = ky * 3 + kx; }
+        }
+      }
+    }
+    bf16x8 r;
+    uint64_t packed = 0;
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      r[j] = (bf16)best[j];
+      packed |= (uint64_t)bi[j] << (8 * j);
+    }
+    *(bf16x8*)(out + pix * C + c8 * 8) = r;
+    *(uint64_t*)(arg + pix * C + c8 * 8) = packed;
+  }
+}
+
+// dx[b][h][w][c] = sum over the pooling windows that contain (h, w) and chose it of d, times (y > 0)
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(const bf16* __restrict__ d, const uint8_t* __restrict__ arg,
+                                                          const bf16* __restrict__ y, bf16* __restrict__ out, int B,
+                                                          int H, int W, int C, int Ho, int Wo, long long total) {
+  const int c8n = C >> 3;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const int c8 = (int)(i % c8n);
+    const long long pix = i / c8n;
+    const int w = (int)(pix % W), h = (int)((pix / W) % H), b = (int)(pix / ((long long)W * H));
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) acc[j] = 0.f;
+    for (int ky = 0; ky < 3; ky++) {
+      const int hh = h + 1 - ky;
+      if (hh < 0 || (hh & 1)) continue;
+      const int oh = hh >> 1;
+      if (oh >= Ho) continue;
+      for (int kx = 0; kx < 3; kx++) {
+        const int ww = w + 1 - kx;
+        if (ww < 0 || (ww & 1)) continue;
+        const int ow = ww >> 1;
+        if (ow >= Wo) continue;
+        const long long o = (((long long)b * Ho + oh) * Wo + ow) * C + c8 * 8;
+        const bf16x8 v = *(const bf16x8*)(d + o);
+        const uint64_t a = *(const uint64_t*)(arg + o);
+#pragma unroll
+        for (int j = 0; j < 8; j++)
+          if ((int)((a >> (8 * j)) & 0xff) == ky * 3 + kx) acc[j] += (float)v[j];
+      }
+    }
+    const bf16x8 yy = *(const bf16x8*)(y + pix * C + c8 * 8);
+    bf16x8 r;
+#pragma unroll
+    for (int j = 0; j < 8; j++) r[j] = (float)yy[j] > 0.f ? (bf16)acc[j] : (bf16)0.f;
+    *(bf16x8*)(out + pix * C + c8 * 8) = r;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// global average pooling and its backward (+ the ReLU closing the last block)
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void avgpool_fwd_kernel(const bf16* __restrict__ x, bf16* __restrict__ p, int B, int HW,
+                                                          int C) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * C) return;
+  const int b = i / C, c = i % C;
+  float s = 0.f;
+  for (int t = 0; t < HW; t++) s += (float)x[((long long)b * HW + t) * C + c];
+  p[i] = (bf16)(s / (float)HW);
+}
+
+__global__ __launch_bounds__(256) void avgpool_bwd_kernel(const bf16* __restrict__ dp, const bf16* __restrict__ y,
+                                                          bf16* __restrict__ out, int HW, int C, long long n8) {
+  const int c8n = C >> 3;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (long long)gridDim.x * blockDim.x) {
+    const int c8 = (int)(i % c8n);
+    const long long b = i / ((long long)c8n * HW);
+    const bf16x8 v = *(const bf16x8*)(dp + b * C + c8 * 8), yy = *(const bf16x8*)(y + i * 8);
+    bf16x8 r;
+#pragma unroll
+    for (int j = 0; j < 8; j++) r[j] = (float)yy[j] > 0.f ? (bf16)((float)v[j] / (float)HW) : (bf16)0.f;
+    *(bf16x8*)(out + i * 8) = r;
+  }
+}
+
+// rows of K elements -> rows of Kc >= K elements, tail zero (bf16); and back (fp32)
+__global__ void pad_rows_kernel(const bf16* __restrict__ in, bf16* __restrict__ out, int rows, int K, int Kc) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * Kc) return;
+  const int r = i / Kc, k = i % Kc;
+  out[i] = k < K ? in[r * K + k] : (bf16)0.f;
+}
+__global__ void strip_rows_kernel(const float* __restrict__ in, float* __restrict__ out, int rows, int K, int Kc) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * K) return;
+  out[i] = in[(i / K) * Kc + i % K];
+}
+
+inline unsigned grid_for(long long total) {
+  long long b = (total + 255) / 256;
+  return (unsigned)(b < 1 ? 1 : (b > 65536 ? 65536 : b));
+}
+
+bool geom_ok(const ConvGeom& g) {
+  if (g.B < 1 || g.H < 1 || g.W < 1 || g.C < 1 || g.k < 1 || g.stride < 1 || g.pad < 0 || g.Ho < 1 || g.Wo < 1) return false;
+  if (g.Ho != (g.H + 2 * g.pad - g.k) / g.stride + 1 || g.Wo != (g.W + 2 * g.pad - g.k) / g.stride + 1) return false;
+  if (g.Kc < g.k * g.k * g.C || (g.Kc & 7)) return false;
+  return true;
+}
+
+}  // namespace
+
+hipError_t im2col(const bf16* x, bf16* cols, const ConvGeom& g, hipStream_t s) {
+  if (!geom_ok(g) || !al16(x) || !al16(cols)) return hipErrorInvalidValue;
+  const long long M = (long long)g.B * g.Ho * g.Wo;
+  if ((g.C & 7) == 0 && g.Kc == g.k * g.k * g.C) {
+    const long long total = M * g.k * g.k * (g.C >> 3);
+    hipLaunchKernelGGL(im2col_vec_kernel, dim3(grid_for(total)), dim3(256), 0, s, x, cols, g, total);
+  } else {
+    const long long total = M * (g.Kc >> 3);
+    hipLaunchKernelGGL(im2col_any_kernel, dim3(grid_for(total)), dim3(256), 0, s, x, cols, g, total);
+  }
+  return hipGetLastError();
+}
+
+hipError_t col2im(const bf16* dcols, const bf16* add, const bf16* mask, bf16* out, const ConvGeom& g, hipStream_t s) {
+  if (!geom_ok(g) || (g.C & 7) || g.Kc != g.k * g.k * g.C) return hipErrorInvalidValue;
+  if (!al16(dcols) || !al16(out) || (add && !al16(add)) || (mask && !al16(mask))) return hipErrorInvalidValue;
+  const long long total = (long long)g.B * g.H * g.W * (g.C >> 3);
+  hipLaunchKernelGGL(col2im_kernel, dim3(grid_for(total)), dim3(256), 0, s, dcols, add, mask, out, g, total);
+  return hipGetLastError();
+}
+
+hipError_t affine_act(const bf16* z1, const float* z1_f32, const bf16* g1, const bf16* b1, const bf16* z2,
+                      const bf16* g2, const bf16* b2, bool relu, bf16* out, long long rows, int C, hipStream_t s) {
+  if (rows < 1 || C < 8 || (C & 7) || (!z1 && !z1_f32) || !g1 || !b1 || (g2 && !b2) || (g2 && !z2)) return hipErrorInvalidValue;
+  if ((z1 && !al16(z1)) || (z1_f32 && !al16(z1_f32)) || !al16(g1) || !al16(b1) || (z2 && !al16(z2)) ||
+      (g2 && (!al16(g2) || !al16(b2))) || !al16(out))
+    return hipErrorInvalidValue;
+  const long long n8 = rows * (C >> 3);
+  if (z1_f32)
+    hipLaunchKernelGGL((affine_kernel<true>), dim3(grid_for(n8)), dim3(256), 0, s, z1, z1_f32, g1, b1, z2, g2, b2,
+                       relu ? 1 : 0, out, n8, C);
+  else
+    hipLaunchKernelGGL((affine_kernel<false>), dim3(grid_for(n8)), dim3(256), 0, s, z1, z1_f32, g1, b1, z2, g2, b2,
+                       relu ? 1 : 0, out, n8, C);
+  return hipGetLastError();
+}
+
+hipError_t scale_cols(const bf16* d, const bf16* gain, bf16* out, long long rows, int C, hipStream_t s) {
+  if (rows < 1 || C < 8 || (C & 7) || !al16(d) || !al16(gain) || !al16(out)) return hipErrorInvalidValue;
+  const long long n8 = rows * (C >> 3);
+  hipLaunchKernelGGL(scale_cols_kernel, dim3(grid_for(n8)), dim3(256), 0, s, d, gain, out, n8, C);
+  return hipGetLastError();
+}
+
+hipError_t add_mask(const bf16* a, const bf16* b, const bf16* mask, bf16* out, long long n, hipStream_t s) {
+  if (n < 8 || (n & 7) || !a || !mask || !al16(a) || (b && !al16(b)) || !al16(mask) || !al16(out)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(add_mask_kernel, dim3(grid_for(n >> 3)), dim3(256), 0, s, a, b, mask, out, n >> 3);
+  return hipGetLastError();
+}
+
+hipError_t maxpool3x3s2_fwd(const float* z, const bf16* gain, const bf16* shift, bf16* out, uint8_t* arg, int B, int H,
+                            int W, int C, hipStream_t s) {
+  if (B < 1 || H < 1 || W < 1 || C < 8 || (C & 7) || !al16(z) || !al16(gain) || !al16(shift) || !al16(out) || !al16(arg))
+    return hipErrorInvalidValue;
+  const int Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1;
+  const long long total = (long long)B * Ho * Wo * (C >> 3);
+  hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid_for(total)), dim3(256), 0, s, z, gain, shift, out, arg, B, H, W, C, Ho,
+                     Wo, total);
+  return hipGetLastError();
+}
+
+hipError_t maxpool3x3s2_bwd(const bf16* d, const uint8_t* arg, const bf16* y, bf16* out, int B, int H, int W, int C,
+                            hipStream_t s) {
+  if (B < 1 || H < 1 || W < 1 || C < 8 || (C & 7) || !al16(d) || !al16(arg) || !al16(y) || !al16(out))
+    return hipErrorInvalidValue;
+  const int Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1;
+  const long long total = (long long)B * H * W * (C >> 3);
+  hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for(total)), dim3(256), 0, s, d, arg, y, out, B, H, W, C, Ho, Wo,
+                     total);
+  return hipGetLastError();
+}
+
+hipError_t avgpool_fwd(const bf16* x, bf16* p, int B, int HW, int C, hipStream_t s) {
+  if (B < 1 || HW < 1 || C < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(avgpool_fwd_kernel, dim3((B * C + 255) / 256), dim3(256), 0, s, x, p, B, HW, C);
+  return hipGetLastError();
+}
+
+hipError_t avgpool_bwd_relu(const bf16* dp, const bf16* y, bf16* out, int B, int HW, int C, hipStream_t s) {
+  if (B < 1 || HW < 1 || C < 8 || (C & 7) || !al16(dp) || !al16(y) || !al16(out)) return hipErrorInvalidValue;
+  const long long n8 = (long long)B * HW * (C >> 3);
+  hipLaunchKernelGGL(avgpool_bwd_kernel, dim3(grid_for(n8)), dim3(256), 0, s, dp, y, out, HW, C, n8);
+  return hipGetLastError();
+}
+
+hipError_t pad_rows(const bf16* in, bf16* out, int rows, int K, int Kc, hipStream_t s) {
+  if (rows < 1 || K < 1 || Kc < K) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(pad_rows_kernel, dim3((rows * Kc + 255) / 256), dim3(256), 0, s, in, out, rows, K, Kc);
+  return hipGetLastError();
+}
+
+hipError_t strip_rows(const float* in, float* out, int rows, int K, int Kc, hipStream_t s) {
+  if (rows < 1 || K < 1 || Kc < K) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(strip_rows_kernel, dim3((rows * K + 255) / 256), dim3(256), 0, s, in, out, rows, K, Kc);
+  return hipGetLastError();
+}
+
+}  // namespace et

@@ -9,181 +9,9 @@
 // selector's time model assumes.  Backward kernels of operations without weights (ReLU, GELU, the
 // attention core, residual additions) sit in the dy() of the tensor that has to be passed for them
 // to be needed; a LayerNorm's input-gradient kernel sits in dy(gain).
-#include <algorithm>
-#include <cmath>
-#include <cstdio>
-#include <cstring>
-#include <new>
-#include <string>
-#include <vector>
-
-#include "et.h"
-#include "kernels.h"
-
-using et::bf16;
+#include "context.h"
 
 namespace {
-
-constexpr uint32_t SEG_ELEMS = 16384;  // elements per chunk of the importance / update tables
-
-enum Phase { PH_FWD = 0, PH_DW = 1, PH_DY = 2, PH_UPD = 3 };
-
-struct TensorInfo {
-  std::string name;
-  size_t numel;
-  int32_t dtype;
-};
-
-struct Scope {  // one timed region of the profile
-  int phase, tensor;
-  hipEvent_t e0, e1;
-};
-
-struct KernelRecord {  // one timed kernel launch (measurement support)
-  int cls;
-  double work;
-  hipEvent_t e0, e1;
-};
-
-struct VitBlockBufs {
-  float *h_in, *h_mid, *mean1, *rstd1, *mean2, *rstd2, *lse;
-  bf16 *a1, *qkv, *p, *o, *a2, *u, *ga;
-};
-
-}  // namespace
-
-struct et_ctx {
-  et_model_desc desc;
-  hipStream_t stream = nullptr;
-  std::vector<TensorInfo> tensors;
-  int32_t state_slots = 0;
-  bool bf16_model = false;
-
-  // workspace plan (offsets in bytes)
-  size_t ws_bytes = 0;
-  std::vector<std::pair<void**, size_t>> plan;  // (where to store the pointer, offset)
-
-  // bound buffers
-  bool bound = false;
-  std::vector<void*> w;
-  std::vector<float*> grad;
-  std::vector<float*> state;
-  unsigned char* ws = nullptr;
-
-  // MLP buffers
-  std::vector<float*> act;  // act[i]: input of layer i (act[0] is x itself, not in the workspace)
-  float *logits = nullptr, *dlogits = nullptr, *loss = nullptr, *dbuf[2] = {nullptr, nullptr};
-
-  // ViT buffers
-  std::vector<VitBlockBufs> blk;
-  float *e = nullptr, *h_out = nullptr, *s_f32 = nullptr, *meanf = nullptr, *rstdf = nullptr, *dh = nullptr;
-  bf16 *zc = nullptr, *dl16 = nullptr, *dz = nullptr, *dh16 = nullptr, *da = nullptr, *du = nullptr, *dattn = nullptr,
-       *dqkv = nullptr, *ds = nullptr, *de = nullptr;
-  float *gemm_partials = nullptr, *colsum_partials = nullptr;
-  size_t gemm_partial_elems = 0;
-
-  // tables for importance / update
-  std::vector<uint32_t> seg_begin;  // [N+1]
-  uint32_t n_segs = 0;
-  et::TensorSeg* imp_segs_dev = nullptr;
-  et::UpdateSeg* upd_segs_dev = nullptr;
-  uint32_t* seg_begin_dev = nullptr;
-  double *imp_partial_dev = nullptr, *imp_out_dev = nullptr;
-  std::vector<et::UpdateSeg> upd_segs_host;
-  std::vector<et::TensorSeg> imp_segs_host;
-
-  // launch accounting and profiling
-  int32_t launches[4] = {0, 0, 0, 0};
-  int cur_phase = PH_FWD;
-  bool profiling = false;
-  std::vector<Scope> scopes;
-  std::vector<hipEvent_t> event_pool;
-  size_t events_used = 0;
-  hipError_t hip_err = hipSuccess;
-
-  // per-kernel-class timing
-  bool ktiming = false;
-  std::vector<KernelRecord> krecs;
-  std::vector<hipEvent_t> kevent_pool;
-  size_t kevents_used = 0;
-};
-
-namespace {
-
-#define ET_HIP(expr)                       \
-  do {                                     \
-    hipError_t e__ = (expr);               \
-    if (e__ != hipSuccess) {               \
-      c->hip_err = e__;                    \
-      return ET_EHIP;                      \
-    }                                      \
-  } while (0)
-
-// kernel launch through a wrapper that returns hipError_t; counts the launches
-#define ET_K(n, expr)                      \
-  do {                                     \
-    hipError_t e__ = (expr);               \
-    if (e__ != hipSuccess) {               \
-      c->hip_err = e__;                    \
-      return ET_EHIP;                      \
-    }                                      \
-    c->launches[c->cur_phase] += (n);      \
-  } while (0)
-
-inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-inline int round8(int v) { return (v + 7) & ~7; }
-
-template <typename T>
-void reserve(et_ctx* c, T** where, size_t bytes) {
-  c->plan.emplace_back(reinterpret_cast<void**>(where), c->ws_bytes);
-  c->ws_bytes += align_up(bytes, 256);
-}
-
-hipError_t get_event(et_ctx* c, hipEvent_t* ev) {
-  if (c->events_used == c->event_pool.size()) {
-    hipEvent_t e;
-    hipError_t r = hipEventCreate(&e);
-    if (r != hipSuccess) return r;
-    c->event_pool.push_back(e);
-  }
-  *ev = c->event_pool[c->events_used++];
-  return hipSuccess;
-}
-
-// timed region: events are recorded only while profiling
-struct Region {
-  et_ctx* c;
-  bool on;
-  size_t idx = 0;
-  Region(et_ctx* ctx, int phase, int tensor) : c(ctx), on(ctx->profiling) {
-    c->cur_phase = phase;
-    if (!on) return;
-    Scope s;
-    s.phase = phase;
-    s.tensor = tensor;
-    if (get_event(c, &s.e0) != hipSuccess || get_event(c, &s.e1) != hipSuccess) {
-      on = false;
-      c->hip_err = hipErrorOutOfMemory;
-      return;
-    }
-    (void)hipEventRecord(s.e0, c->stream);
-    idx = c->scopes.size();
-    c->scopes.push_back(s);
-  }
-  ~Region() {
-    if (on) (void)hipEventRecord(c->scopes[idx].e1, c->stream);
-  }
-};
-
-// split of the reduction dimension for a weight gradient [Mo][No] reduced over K rows: as many
-// chunks as keep one wave of 256x256 tiles on the 256 CUs, each chunk at least 4 slices of 64
-int split_for(int Mo, int No, int K) {
-  const int tiles = ((Mo + 255) / 256) * ((No + 255) / 256);
-  int s = 256 / tiles;
-  const int slices = (K + 63) / 64;
-  s = std::min(s, std::max(1, slices / 4));
-  return std::max(1, std::min(s, 64));
-}
 
 // -----------------------------------------------------------------------------------------------
 // model construction
@@ -359,72 +187,6 @@ VitDims vit_dims(const et_model_desc& d) {
   v.scale = 1.f / std::sqrt((float)v.dh);
   return v;
 }
-
-// Y[M][N] = X[M][K] W[N][K]^T (+ bias) ...
-et::GemmDesc linear_fwd(const bf16* X, const bf16* W, const bf16* bias, int M, int N, int K) {
-  et::GemmDesc g;
-  g.A = X; g.lda = K; g.B = W; g.ldb = K; g.M = M; g.N = N; g.K = K; g.bias = bias; g.ldc = N;
-  return g;
-}
-// dX[M][K] = dY[M][N] W[N][K]
-et::GemmDesc linear_dx(const bf16* dY, const bf16* W, int M, int N, int K) {
-  et::GemmDesc g;
-  g.A = dY; g.lda = N; g.B = W; g.b_t = true; g.ldb = K; g.M = M; g.N = K; g.K = N; g.ldc = K;
-  return g;
-}
-// dW[N][K] = dY[M][N]^T X[M][K], fp32, split over the rows
-et::GemmDesc linear_dw(et_ctx* c, const bf16* dY, int ldy, const bf16* X, int ldx, float* dW, int M, int N, int K) {
-  et::GemmDesc g;
-  g.A = dY; g.a_t = true; g.lda = ldy; g.B = X; g.b_t = true; g.ldb = ldx; g.M = N; g.N = K; g.K = M;
-  g.C = dW; g.ldc = K; g.c_f32 = true;
-  g.split_k = split_for(N, K, M);
-  g.partials = c->gemm_partials;
-  if (et::gemm_bf16_partial_elems(N, K, g.split_k) > c->gemm_partial_elems) g.split_k = 1;
-  return g;
-}
-
-// bracket a launch with events while per-kernel timing is on
-struct KernelTimer {
-  et_ctx* c;
-  bool on = false;
-  size_t idx = 0;
-  KernelTimer(et_ctx* ctx, int cls, double work) : c(ctx) {
-    if (!c->ktiming) return;
-    KernelRecord r;
-    r.cls = cls;
-    r.work = work;
-    for (hipEvent_t* ev : {&r.e0, &r.e1}) {
-      if (c->kevents_used == c->kevent_pool.size()) {
-        hipEvent_t e;
-        if (hipEventCreate(&e) != hipSuccess) { c->hip_err = hipErrorOutOfMemory; return; }
-        c->kevent_pool.push_back(e);
-      }
-      *ev = c->kevent_pool[c->kevents_used++];
-    }
-    (void)hipEventRecord(r.e0, c->stream);
-    idx = c->krecs.size();
-    c->krecs.push_back(r);
-    on = true;
-  }
-  ~KernelTimer() {
-    if (on) (void)hipEventRecord(c->krecs[idx].e1, c->stream);
-  }
-};
-
-int launch_gemm(et_ctx* c, const et::GemmDesc& g) {
-  int n = 0;
-  const int cls = g.a_t ? 2 : (g.b_t ? 1 : 0);
-  KernelTimer kt(c, cls, 2.0 * g.M * g.N * (double)g.K * g.z_outer * g.z_inner);
-  hipError_t e = et::gemm_bf16(g, c->stream, &n);
-  if (e != hipSuccess) { c->hip_err = e; return ET_EHIP; }
-  c->launches[c->cur_phase] += n;
-  return ET_OK;
-}
-#define ET_G(g)                            \
-  do {                                     \
-    int r__ = launch_gemm(c, (g));         \
-    if (r__ != ET_OK) return r__;          \
-  } while (0)
 
 int vit_forward(et_ctx* c, const void* x, const int32_t* y) {
   const VitDims v = vit_dims(c->desc);
@@ -709,10 +471,12 @@ int vit_backward(et_ctx* c, const void* x, const uint8_t* mask) {
 
 int run_forward(et_ctx* c, const void* x, const int32_t* y) {
   c->cur_phase = PH_FWD;
+  if (c->desc.kind == ET_RESNET) return resnet_forward(c, x, y);
   return c->desc.kind == ET_MLP ? mlp_forward(c, x, y) : vit_forward(c, x, y);
 }
 int run_backward(et_ctx* c, const void* x, const uint8_t* mask) {
   c->cur_phase = PH_DW;
+  if (c->desc.kind == ET_RESNET) return resnet_backward(c, x, mask);
   return c->desc.kind == ET_MLP ? mlp_backward(c, x, mask) : vit_backward(c, x, mask);
 }
 
@@ -781,6 +545,7 @@ int et_create(const et_model_desc* desc, void* hip_stream, et_ctx** out) {
     c->bf16_model = desc->dtype == ET_BF16;
     if (desc->kind == ET_MLP) rc = build_mlp(c);
     else if (desc->kind == ET_VIT) rc = build_vit(c);
+    else if (desc->kind == ET_RESNET) rc = build_resnet(c);
     else rc = ET_EINVAL;
     if (rc == ET_OK && c->tensors.size() > (size_t)et::MAX_TENSORS) rc = ET_EINVAL;
     if (rc == ET_OK) {

@@ -123,6 +123,44 @@ hipError_t fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t cast_bf16(const float* in, bf16* out, size_t n, hipStream_t s);
 
 // ------------------------------------------------------------------------------------------
+// convolutional workload: NHWC bf16 activations, a convolution is a GEMM over an im2col matrix
+// ------------------------------------------------------------------------------------------
+struct ConvGeom {
+  int B, H, W, C;      // input [B][H][W][C]
+  int k, stride, pad;  // square kernel
+  int Ho, Wo;          // output size, (H + 2 pad - k) / stride + 1
+  int Kc;              // row length of the column matrix: k*k*C rounded up to a multiple of 8
+};
+// cols[B*Ho*Wo][Kc], column order (ky, kx, c); out-of-image taps and the row tail are zero
+hipError_t im2col(const bf16* x, bf16* cols, const ConvGeom& g, hipStream_t s);
+// out[B][H][W][C] = (adjoint of im2col applied to dcols  + add) * (mask > 0); add, mask nullable; C % 8 == 0
+hipError_t col2im(const bf16* dcols, const bf16* add, const bf16* mask, bf16* out, const ConvGeom& g, hipStream_t s);
+// folded BatchNorm: out = act(z1*g1 + b1 + t), t = z2*g2 + b2 (g2 given), z2 (g2 null) or 0 (z2 null);
+// z1 is bf16, or fp32 when z1_f32 is given; rows x C, C % 8 == 0
+hipError_t affine_act(const bf16* z1, const float* z1_f32, const bf16* g1, const bf16* b1, const bf16* z2,
+                      const bf16* g2, const bf16* b2, bool relu, bf16* out, long long rows, int C, hipStream_t s);
+// out[r][c] = d[r][c] * gain[c]
+hipError_t scale_cols(const bf16* d, const bf16* gain, bf16* out, long long rows, int C, hipStream_t s);
+// out = (a + b) * (mask > 0), n elements (n % 8 == 0); b nullable; out may alias a or b
+hipError_t add_mask(const bf16* a, const bf16* b, const bf16* mask, bf16* out, long long n, hipStream_t s);
+// stem pooling: y = relu(z*gain + shift) in fp32, then 3x3 / stride 2 / pad 1 maximum, first maximum in
+// (ky, kx) order; arg holds the chosen tap (one byte per output element)
+hipError_t maxpool3x3s2_fwd(const float* z, const bf16* gain, const bf16* shift, bf16* out, uint8_t* arg, int B, int H,
+                            int W, int C, hipStream_t s);
+// out[B][H][W][C] = (d routed back to the chosen taps) * (y > 0)
+hipError_t maxpool3x3s2_bwd(const bf16* d, const uint8_t* arg, const bf16* y, bf16* out, int B, int H, int W, int C,
+                            hipStream_t s);
+// p[b][c] = mean over the HW positions; backward: out[b][t][c] = dp[b][c] / HW * (y[b][t][c] > 0)
+hipError_t avgpool_fwd(const bf16* x, bf16* p, int B, int HW, int C, hipStream_t s);
+hipError_t avgpool_bwd_relu(const bf16* dp, const bf16* y, bf16* out, int B, int HW, int C, hipStream_t s);
+// rows of K elements <-> rows of Kc >= K elements (zero tail)
+hipError_t pad_rows(const bf16* in, bf16* out, int rows, int K, int Kc, hipStream_t s);
+hipError_t strip_rows(const float* in, float* out, int rows, int K, int Kc, hipStream_t s);
+// out[c] = sum_r d[r][c] * z[r][c]   (z bf16, or fp32 when z_f32 is given); same two stages as colsum
+hipError_t colsum_mul(const bf16* d, const bf16* z, const float* z_f32, float* out, float* partials, int rows, int cols,
+                      hipStream_t s);
+
+// ------------------------------------------------------------------------------------------
 // importance (Eq. 2) and masked optimizer update over a table of tensors
 // ------------------------------------------------------------------------------------------
 struct TensorSeg {       // one chunk of one tensor

@@ -1,0 +1,394 @@
+// Bottleneck residual CNN on the tensor-level chain (Sections 2.3 and 5).  A branched network is
+// unrolled by execution order: per block c1.W, c1.g, c1.b, c2.*, c3.*, then the projection
+// shortcut sc.W, sc.g, sc.b.  From the output side the shortcut tensors of a block are therefore
+// visited first; they work on the gradient of the block's pre-ReLU sum.  Passing the gradient
+// through the shortcut convolution to the block input is needed exactly when something before
+// the block is selected, so it belongs to dy(c1.W), where the two branches meet.  BatchNorm is
+// folded into a per-channel affine, so a gain's dw() is a column sum of d * (convolution output)
+// and a shift's dw() a column sum of d.
+//
+// A convolution is a GEMM over the rows of an im2col matrix kept from the forward pass (a 1x1
+// stride-1 convolution reads the activation itself): forward cols * W^T, dw() d^T * cols (split
+// over the rows), dy() d * W followed by the gather-form adjoint of im2col fused with the branch
+// sum and the ReLU mask.  The stem's convolution output stays fp32 so that the max-pooling
+// argmax is decided on unrounded values.
+#include "context.h"
+
+namespace {
+
+et::ConvGeom geom(const et_ctx* c, const ConvUnit& u) {
+  et::ConvGeom g;
+  g.B = c->desc.batch; g.H = u.H; g.W = u.W; g.C = u.Cin; g.k = u.k; g.stride = u.stride; g.pad = (u.k - 1) / 2;
+  g.Ho = u.Ho; g.Wo = u.Wo; g.Kc = u.Kc;
+  return g;
+}
+
+void init_unit(ConvUnit& u, int t, int H, int W, int Cin, int Cout, int k, int stride) {
+  u.t = t; u.H = H; u.W = W; u.Cin = Cin; u.Cout = Cout; u.k = k; u.stride = stride;
+  const int pad = (k - 1) / 2;
+  u.Ho = (H + 2 * pad - k) / stride + 1;
+  u.Wo = (W + 2 * pad - k) / stride + 1;
+  u.Kc = round8(k * k * Cin);
+  u.in = nullptr; u.cols = nullptr; u.z = nullptr; u.y = nullptr;
+}
+
+inline size_t rows_of(const et_ctx* c, const ConvUnit& u) { return (size_t)c->desc.batch * u.Ho * u.Wo; }
+inline bool needs_cols(const ConvUnit& u) { return u.k > 1 || u.stride > 1; }
+
+// z = cols(in) * Wm^T
+int conv_forward(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16* Wm, void* z, bool z_f32) {
+  const bf16* A = in;
+  if (needs_cols(u)) {
+    ET_K(1, et::im2col(in, u.cols, geom(c, u), c->stream));
+    A = u.cols;
+  }
+  et::GemmDesc g = linear_fwd(A, Wm, nullptr, (int)rows_of(c, u), u.Cout, u.Kc);
+  g.C = z; g.c_f32 = z_f32;
+  ET_G(g);
+  return ET_OK;
+}
+
+int conv_dw(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16* d, float* dW) {
+  const bf16* A = needs_cols(u) ? u.cols : in;
+  ET_G(linear_dw(c, d, u.Cout, A, u.Kc, dW, (int)rows_of(c, u), u.Cout, u.Kc));
+  return ET_OK;
+}
+
+// gradient of the column matrix: dcols[M][Kc] = d[M][Cout] * Wm[Cout][Kc]
+int conv_dcols(et_ctx* c, const ConvUnit& u, const bf16* d, const bf16* Wm, bf16* dcols) {
+  et::GemmDesc g = linear_dx(d, Wm, (int)rows_of(c, u), u.Cout, u.Kc);
+  g.C = dcols;
+  ET_G(g);
+  return ET_OK;
+}
+
+}  // namespace
+
+int build_resnet(et_ctx* c) {
+  const et_model_desc& d = c->desc;
+  if (d.dtype != ET_BF16 || d.batch < 1 || d.image < 4 || d.in_ch < 1 || d.n_stages < 1 || d.n_stages > ET_MAX_STAGES)
+    return ET_EINVAL;
+  if (d.stem < 8 || (d.stem % 8) || d.classes < 8 || (d.classes % 8)) return ET_EINVAL;
+  int n_blocks = 0;
+  for (int s = 0; s < d.n_stages; s++) {
+    if (d.stage_blocks[s] < 1 || d.planes[s] < 8 || (d.planes[s] % 8)) return ET_EINVAL;
+    n_blocks += d.stage_blocks[s];
+  }
+  auto add = [&](const std::string& n, size_t numel) { c->tensors.push_back({n, numel, ET_BF16}); };
+  const size_t B = d.batch, b16 = sizeof(bf16), f32 = sizeof(float);
+
+  init_unit(c->stem, 0, d.image, d.image, d.in_ch, d.stem, 7, 2);
+  add("stem.W", (size_t)d.stem * 49 * d.in_ch); add("stem.g", d.stem); add("stem.b", d.stem);
+  const int Hs = c->stem.Ho, Ws = c->stem.Wo;
+  int H = (Hs - 1) / 2 + 1, W = (Ws - 1) / 2 + 1, Cin = d.stem;   // after max pooling
+  if (H < 1 || W < 1) return ET_EINVAL;
+
+  c->rblk.assign(n_blocks, ResBlockBufs());
+  int bi = 0, t = 3;
+  for (int s = 0; s < d.n_stages; s++)
+    for (int k = 0; k < d.stage_blocks[s]; k++, bi++) {
+      ResBlockBufs& b = c->rblk[bi];
+      const int p = d.planes[s], stride = (k == 0 && s > 0) ? 2 : 1;
+      b.t = t; b.proj = k == 0; b.x = nullptr; b.y = nullptr;
+      const std::string pre = "s" + std::to_string(s) + "b" + std::to_string(k) + ".";
+      init_unit(b.c1, t, H, W, Cin, p, 1, 1);
+      init_unit(b.c2, t + 3, H, W, p, p, 3, stride);
+      init_unit(b.c3, t + 6, b.c2.Ho, b.c2.Wo, p, 4 * p, 1, 1);
+      add(pre + "c1.W", (size_t)p * Cin); add(pre + "c1.g", p); add(pre + "c1.b", p);
+      add(pre + "c2.W", (size_t)p * 9 * p); add(pre + "c2.g", p); add(pre + "c2.b", p);
+      add(pre + "c3.W", (size_t)4 * p * p); add(pre + "c3.g", 4 * p); add(pre + "c3.b", 4 * p);
+      t += 9;
+      if (b.proj) {
+        init_unit(b.sc, t, H, W, Cin, 4 * p, 1, stride);
+        add(pre + "sc.W", (size_t)4 * p * Cin); add(pre + "sc.g", 4 * p); add(pre + "sc.b", 4 * p);
+        t += 3;
+      } else if (Cin != 4 * p || stride != 1) {
+        return ET_EINVAL;
+      }
+      H = b.c2.Ho; W = b.c2.Wo; Cin = 4 * p;
+    }
+  if (!c->rblk[0].proj) return ET_EINVAL;
+  const int Cf = Cin, C = d.classes, C8 = round8(d.classes);
+  add("head.W", (size_t)C * Cf); add("head.b", C);
+
+  // ---- workspace
+  size_t max_act = 0, max_cols = 0, max_cs = 0, pe = 0;
+  auto act = [&](size_t rows, size_t ch) {
+    max_act = std::max(max_act, rows * ch);
+    max_cs = std::max(max_cs, et::colsum_partial_elems((int)rows, (int)ch));
+  };
+  auto wg = [&](const ConvUnit& u) {
+    const int M = (int)rows_of(c, u);
+    pe = std::max(pe, et::gemm_bf16_partial_elems(u.Cout, u.Kc, split_for(u.Cout, u.Kc, M)));
+    max_cols = std::max(max_cols, (size_t)M * u.Kc);   // the column gradient of any unit fits rdcols
+  };
+  auto unit = [&](ConvUnit& u, bool with_y) {
+    const size_t M = rows_of(c, u);
+    if (needs_cols(u)) reserve(c, &u.cols, b16 * M * u.Kc);
+    reserve(c, &u.z, b16 * M * u.Cout);
+    if (with_y) reserve(c, &u.y, b16 * M * u.Cout);
+    act(M, u.Cout);
+    wg(u);
+  };
+  {
+    ConvUnit& u = c->stem;
+    const size_t M = rows_of(c, u);
+    reserve(c, &u.cols, b16 * M * u.Kc);
+    reserve(c, &c->stem_z32, f32 * M * u.Cout);
+    reserve(c, &c->pool_y, b16 * M * u.Cout);
+    reserve(c, &c->stem_w8, b16 * (size_t)u.Cout * u.Kc);
+    reserve(c, &c->stem_dw8, f32 * (size_t)u.Cout * u.Kc);
+    act(M, u.Cout);
+    pe = std::max(pe, et::gemm_bf16_partial_elems(u.Cout, u.Kc, split_for(u.Cout, u.Kc, (int)M)));
+    const size_t Mp = B * c->rblk[0].c1.H * c->rblk[0].c1.W;
+    reserve(c, &c->pooled, b16 * Mp * u.Cout);
+    reserve(c, &c->pool_arg, Mp * u.Cout);
+    act(Mp, u.Cout);
+  }
+  for (ResBlockBufs& b : c->rblk) {
+    unit(b.c1, true);
+    unit(b.c2, true);
+    unit(b.c3, false);
+    if (b.proj) unit(b.sc, false);
+    reserve(c, &b.y, b16 * rows_of(c, b.c3) * b.c3.Cout);
+  }
+  reserve(c, &c->zc, b16 * B * Cf);
+  reserve(c, &c->logits, f32 * B * C);
+  reserve(c, &c->dlogits, f32 * B * C);
+  reserve(c, &c->dl16, b16 * B * C8);
+  reserve(c, &c->loss, 256);
+  reserve(c, &c->dz, b16 * B * Cf);
+  max_cs = std::max(max_cs, et::colsum_partial_elems((int)B, C));
+  pe = std::max(pe, et::gemm_bf16_partial_elems(C, Cf, split_for(C, Cf, (int)B)));
+  for (int i = 0; i < 2; i++) reserve(c, &c->rd[i], b16 * max_act);
+  reserve(c, &c->rdsum, b16 * max_act);
+  reserve(c, &c->rdsc, b16 * max_act);
+  reserve(c, &c->rdcols, b16 * std::max<size_t>(max_cols, 8));
+  c->gemm_partial_elems = pe;
+  reserve(c, &c->gemm_partials, f32 * std::max<size_t>(pe, 64));
+  reserve(c, &c->colsum_partials, f32 * std::max<size_t>(max_cs, 64));
+  // every matrix dimension and element count below is handled as int by the GEMM
+  if (max_act > 0x7fffffffull || max_cols > 0x7fffffffull || rows_of(c, c->stem) * c->stem.Kc > 0x7fffffffull)
+    return ET_EINVAL;
+  return ET_OK;
+}
+
+int resnet_forward(et_ctx* c, const void* x, const int32_t* y) {
+  const et_model_desc& d = c->desc;
+  Region r(c, PH_FWD, -1);
+  hipStream_t s = c->stream;
+  auto Wt = [&](int i) { return (const bf16*)c->w[i]; };
+  const int B = d.batch;
+  {  // stem: convolution (fp32 result), affine + ReLU, max pooling
+    const ConvUnit& u = c->stem;
+    ET_K(1, et::pad_rows(Wt(0), c->stem_w8, u.Cout, 49 * u.Cin, u.Kc, s));
+    int rc = conv_forward(c, u, (const bf16*)x, c->stem_w8, c->stem_z32, true);
+    if (rc != ET_OK) return rc;
+    ET_K(1, et::affine_act(nullptr, c->stem_z32, Wt(1), Wt(2), nullptr, nullptr, nullptr, true, c->pool_y,
+                           (long long)rows_of(c, u), u.Cout, s));
+    ET_K(1, et::maxpool3x3s2_fwd(c->stem_z32, Wt(1), Wt(2), c->pooled, c->pool_arg, B, u.Ho, u.Wo, u.Cout, s));
+  }
+  const bf16* h = c->pooled;
+  for (ResBlockBufs& b : c->rblk) {
+    const int t = b.t;
+    b.x = h;
+    int rc = conv_forward(c, b.c1, h, Wt(t), b.c1.z, false);
+    if (rc != ET_OK) return rc;
+    ET_K(1, et::affine_act(b.c1.z, nullptr, Wt(t + 1), Wt(t + 2), nullptr, nullptr, nullptr, true, b.c1.y,
+                           (long long)rows_of(c, b.c1), b.c1.Cout, s));
+    rc = conv_forward(c, b.c2, b.c1.y, Wt(t + 3), b.c2.z, false);
+    if (rc != ET_OK) return rc;
+    ET_K(1, et::affine_act(b.c2.z, nullptr, Wt(t + 4), Wt(t + 5), nullptr, nullptr, nullptr, true, b.c2.y,
+                           (long long)rows_of(c, b.c2), b.c2.Cout, s));
+    rc = conv_forward(c, b.c3, b.c2.y, Wt(t + 6), b.c3.z, false);
+    if (rc != ET_OK) return rc;
+    if (b.proj) {
+      rc = conv_forward(c, b.sc, h, Wt(t + 9), b.sc.z, false);
+      if (rc != ET_OK) return rc;
+      ET_K(1, et::affine_act(b.c3.z, nullptr, Wt(t + 7), Wt(t + 8), b.sc.z, Wt(t + 10), Wt(t + 11), true, b.y,
+                             (long long)rows_of(c, b.c3), b.c3.Cout, s));
+    } else {
+      ET_K(1, et::affine_act(b.c3.z, nullptr, Wt(t + 7), Wt(t + 8), h, nullptr, nullptr, true, b.y,
+                             (long long)rows_of(c, b.c3), b.c3.Cout, s));
+    }
+    h = b.y;
+  }
+  const ResBlockBufs& last = c->rblk.back();
+  const int Cf = last.c3.Cout, N = (int)c->tensors.size();
+  ET_K(1, et::avgpool_fwd(h, c->zc, B, last.c3.Ho * last.c3.Wo, Cf, s));
+  {
+    et::GemmDesc g = linear_fwd(c->zc, Wt(N - 2), Wt(N - 1), B, d.classes, Cf);
+    g.C = c->logits; g.c_f32 = true;
+    ET_G(g);
+  }
+  ET_K(1, et::xent(c->logits, y, B, d.classes, c->loss, c->dlogits, c->dl16, round8(d.classes), s));
+  return ET_OK;
+}
+
+int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
+  const et_model_desc& md = c->desc;
+  const int N = (int)c->tensors.size(), B = md.batch;
+  int jstar = -1;
+  for (int j = 0; j < N; j++)
+    if (mask[j]) { jstar = j; break; }
+  if (jstar < 0) return ET_OK;
+  auto Wt = [&](int i) { return (const bf16*)c->w[i]; };
+  auto sel = [&](int j) { return mask[j] != 0; };
+  auto pass = [&](int j) { return j > jstar; };
+  hipStream_t s = c->stream;
+  float* cp = c->colsum_partials;
+  int rc;
+
+  // ---- head
+  const ResBlockBufs& last = c->rblk.back();
+  const int Cf = last.c3.Cout, C = md.classes, C8 = round8(md.classes), HWf = last.c3.Ho * last.c3.Wo;
+  if (sel(N - 1)) {
+    Region r(c, PH_DW, N - 1);
+    ET_K(2, et::colsum(nullptr, c->dlogits, C, nullptr, 0, nullptr, nullptr, c->grad[N - 1], cp, B, C, s));
+  }
+  if (sel(N - 2)) {
+    Region r(c, PH_DW, N - 2);
+    ET_G(linear_dw(c, c->dl16, C8, c->zc, Cf, c->grad[N - 2], B, C, Cf));
+  }
+  if (pass(N - 2)) {  // through the head matrix, the average pooling and the ReLU closing the last block
+    Region r(c, PH_DY, N - 2);
+    et::GemmDesc g = linear_dx(c->dl16, Wt(N - 2), B, C, Cf);
+    g.lda = C8; g.C = c->dz;
+    ET_G(g);
+    ET_K(1, et::avgpool_bwd_relu(c->dz, last.y, c->rdsum, B, HWf, Cf, s));
+  }
+
+  // ---- blocks, output side first.  On entry rdsum holds the gradient of the block's pre-ReLU sum.
+  for (int bi = (int)c->rblk.size() - 1; bi >= 0; bi--) {
+    const ResBlockBufs& b = c->rblk[bi];
+    const int t = b.t;
+    if (jstar > t + (b.proj ? 11 : 8)) break;
+    const long long M3 = (long long)rows_of(c, b.c3), M2 = (long long)rows_of(c, b.c2), M1 = (long long)rows_of(c, b.c1);
+    if (b.proj) {
+      if (sel(t + 11)) {
+        Region r(c, PH_DW, t + 11);
+        ET_K(2, et::colsum(c->rdsum, nullptr, b.sc.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 11], cp, (int)M3,
+                           b.sc.Cout, s));
+      }
+      if (sel(t + 10)) {
+        Region r(c, PH_DW, t + 10);
+        ET_K(2, et::colsum_mul(c->rdsum, b.sc.z, nullptr, c->grad[t + 10], cp, (int)M3, b.sc.Cout, s));
+      }
+      if (pass(t + 10)) {
+        Region r(c, PH_DY, t + 10);
+        ET_K(1, et::scale_cols(c->rdsum, Wt(t + 10), c->rdsc, M3, b.sc.Cout, s));
+      }
+      if (sel(t + 9)) {
+        Region r(c, PH_DW, t + 9);
+        if ((rc = conv_dw(c, b.sc, b.x, c->rdsc, c->grad[t + 9])) != ET_OK) return rc;
+      }
+    }
+    // main branch: c3
+    if (sel(t + 8)) {
+      Region r(c, PH_DW, t + 8);
+      ET_K(2, et::colsum(c->rdsum, nullptr, b.c3.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 8], cp, (int)M3,
+                         b.c3.Cout, s));
+    }
+    if (sel(t + 7)) {
+      Region r(c, PH_DW, t + 7);
+      ET_K(2, et::colsum_mul(c->rdsum, b.c3.z, nullptr, c->grad[t + 7], cp, (int)M3, b.c3.Cout, s));
+    }
+    if (pass(t + 7)) {
+      Region r(c, PH_DY, t + 7);
+      ET_K(1, et::scale_cols(c->rdsum, Wt(t + 7), c->rd[0], M3, b.c3.Cout, s));
+    }
+    if (sel(t + 6)) {
+      Region r(c, PH_DW, t + 6);
+      if ((rc = conv_dw(c, b.c3, b.c2.y, c->rd[0], c->grad[t + 6])) != ET_OK) return rc;
+    }
+    if (pass(t + 6)) {  // through the 1x1 convolution and the ReLU after c2
+      Region r(c, PH_DY, t + 6);
+      if ((rc = conv_dcols(c, b.c3, c->rd[0], Wt(t + 6), c->rd[1])) != ET_OK) return rc;
+      ET_K(1, et::add_mask(c->rd[1], nullptr, b.c2.y, c->rd[1], M2 * b.c2.Cout, s));
+    }
+    // c2
+    if (sel(t + 5)) {
+      Region r(c, PH_DW, t + 5);
+      ET_K(2, et::colsum(c->rd[1], nullptr, b.c2.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 5], cp, (int)M2,
+                         b.c2.Cout, s));
+    }
+    if (sel(t + 4)) {
+      Region r(c, PH_DW, t + 4);
+      ET_K(2, et::colsum_mul(c->rd[1], b.c2.z, nullptr, c->grad[t + 4], cp, (int)M2, b.c2.Cout, s));
+    }
+    if (pass(t + 4)) {
+      Region r(c, PH_DY, t + 4);
+      ET_K(1, et::scale_cols(c->rd[1], Wt(t + 4), c->rd[0], M2, b.c2.Cout, s));
+    }
+    if (sel(t + 3)) {
+      Region r(c, PH_DW, t + 3);
+      if ((rc = conv_dw(c, b.c2, b.c1.y, c->rd[0], c->grad[t + 3])) != ET_OK) return rc;
+    }
+    if (pass(t + 3)) {  // through the 3x3 convolution and the ReLU after c1
+      Region r(c, PH_DY, t + 3);
+      if ((rc = conv_dcols(c, b.c2, c->rd[0], Wt(t + 3), c->rdcols)) != ET_OK) return rc;
+      ET_K(1, et::col2im(c->rdcols, nullptr, b.c1.y, c->rd[1], geom(c, b.c2), s));
+    }
+    // c1
+    if (sel(t + 2)) {
+      Region r(c, PH_DW, t + 2);
+      ET_K(2, et::colsum(c->rd[1], nullptr, b.c1.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 2], cp, (int)M1,
+                         b.c1.Cout, s));
+    }
+    if (sel(t + 1)) {
+      Region r(c, PH_DW, t + 1);
+      ET_K(2, et::colsum_mul(c->rd[1], b.c1.z, nullptr, c->grad[t + 1], cp, (int)M1, b.c1.Cout, s));
+    }
+    if (pass(t + 1)) {
+      Region r(c, PH_DY, t + 1);
+      ET_K(1, et::scale_cols(c->rd[1], Wt(t + 1), c->rd[0], M1, b.c1.Cout, s));
+    }
+    if (sel(t)) {
+      Region r(c, PH_DW, t);
+      if ((rc = conv_dw(c, b.c1, b.x, c->rd[0], c->grad[t])) != ET_OK) return rc;
+    }
+    if (pass(t)) {
+      // through c1, joined by the shortcut branch (through the shortcut convolution, or the
+      // identity), then through the ReLU closing the previous block -- or, for the first block,
+      // the max pooling and the stem's ReLU
+      Region r(c, PH_DY, t);
+      if ((rc = conv_dcols(c, b.c1, c->rd[0], Wt(t), c->rd[1])) != ET_OK) return rc;
+      const bf16* prev_y = bi > 0 ? c->rblk[bi - 1].y : nullptr;
+      if (b.proj) {
+        if ((rc = conv_dcols(c, b.sc, c->rdsc, Wt(t + 9), c->rdcols)) != ET_OK) return rc;
+        ET_K(1, et::col2im(c->rdcols, c->rd[1], prev_y, prev_y ? c->rdsum : c->rd[0], geom(c, b.sc), s));
+      } else {
+        ET_K(1, et::add_mask(c->rd[1], c->rdsum, prev_y, c->rdsum, M1 * b.c1.Cin, s));
+      }
+      if (!prev_y) {
+        const ConvUnit& u = c->stem;
+        ET_K(1, et::maxpool3x3s2_bwd(c->rd[0], c->pool_arg, c->pool_y, c->rdsum, B, u.Ho, u.Wo, u.Cout, s));
+      }
+    }
+  }
+
+  // ---- stem
+  if (jstar <= 2) {
+    const ConvUnit& u = c->stem;
+    const long long M = (long long)rows_of(c, u);
+    if (sel(2)) {
+      Region r(c, PH_DW, 2);
+      ET_K(2, et::colsum(c->rdsum, nullptr, u.Cout, nullptr, 0, nullptr, nullptr, c->grad[2], cp, (int)M, u.Cout, s));
+    }
+    if (sel(1)) {
+      Region r(c, PH_DW, 1);
+      ET_K(2, et::colsum_mul(c->rdsum, nullptr, c->stem_z32, c->grad[1], cp, (int)M, u.Cout, s));
+    }
+    if (pass(1)) {
+      Region r(c, PH_DY, 1);
+      ET_K(1, et::scale_cols(c->rdsum, Wt(1), c->rd[0], M, u.Cout, s));
+    }
+    if (sel(0)) {
+      Region r(c, PH_DW, 0);
+      ET_G(linear_dw(c, c->rd[0], u.Cout, u.cols, u.Kc, c->stem_dw8, (int)M, u.Cout, u.Kc));
+      ET_K(1, et::strip_rows(c->stem_dw8, c->grad[0], u.Cout, 49 * u.Cin, u.Kc, s));
+    }
+  }
+  (void)x;
+  return ET_OK;
+}

@@ -176,6 +176,47 @@ __global__ __launch_bounds__(256) void colsum_stage1(const bf16* __restrict__ d1
   }
 }
 
+// same reduction with an element-wise multiplier: out[c] = sum_r d[r][c] * z[r][c]
+template <bool Z32>
+__global__ __launch_bounds__(256) void colsum_mul_stage1(const bf16* __restrict__ d, const bf16* __restrict__ z16,
+                                                         const float* __restrict__ z32, float* __restrict__ partials,
+                                                         int rows, int cols) {
+  __shared__ float red[32][CS_COLS + 1];
+  const int cx = threadIdx.x & 7, ry = threadIdx.x >> 3;
+  const int c0 = blockIdx.x * CS_COLS + cx * 8;
+  const int r_begin = blockIdx.y * CS_ROWS, r_end = min(rows, r_begin + CS_ROWS);
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; j++) acc[j] = 0.f;
+  if (c0 < cols) {
+    for (int r = r_begin + ry; r < r_end; r += 32) {
+      const bf16x8 a = *(const bf16x8*)(d + (long long)r * cols + c0);
+      if (Z32) {
+        const float4 p = *(const float4*)(z32 + (long long)r * cols + c0);
+        const float4 q = *(const float4*)(z32 + (long long)r * cols + c0 + 4);
+        acc[0] += (float)a[0] * p.x; acc[1] += (float)a[1] * p.y; acc[2] += (float)a[2] * p.z; acc[3] += (float)a[3] * p.w;
+        acc[4] += (float)a[4] * q.x; acc[5] += (float)a[5] * q.y; acc[6] += (float)a[6] * q.z; acc[7] += (float)a[7] * q.w;
+      } else {
+        const bf16x8 b = *(const bf16x8*)(z16 + (long long)r * cols + c0);
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[j] += (float)a[j] * (float)b[j];
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; j++) red[ry][cx * 8 + j] = acc[j];
+  __syncthreads();
+  if (threadIdx.x < CS_COLS) {
+    const int c = blockIdx.x * CS_COLS + threadIdx.x;
+    if (c < cols) {
+      float s = red[0][threadIdx.x];
+#pragma unroll
+      for (int k = 1; k < 32; k++) s += red[k][threadIdx.x];
+      partials[(long long)blockIdx.y * cols + c] = s;
+    }
+  }
+}
+
 __global__ void colsum_stage2(const float* __restrict__ partials, float* __restrict__ out, int chunks, int cols) {
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= cols) return;
@@ -359,6 +400,22 @@ hipError_t colsum(const bf16* d, const float* d_f32, long long d_stride, const f
       hipLaunchKernelGGL((colsum_stage1<false, false>), grid, block, 0, s, d, d_f32, d_stride, h, h_stride, mean, rstd,
                          partials, rows, cols);
   }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(colsum_stage2, dim3((cols + 255) / 256), dim3(256), 0, s, partials, out, chunks, cols);
+  return hipGetLastError();
+}
+
+hipError_t colsum_mul(const bf16* d, const bf16* z, const float* z_f32, float* out, float* partials, int rows, int cols,
+                      hipStream_t s) {
+  if (rows <= 0 || cols <= 0 || (cols & 7) || !d || (!z && !z_f32) || !partials) return hipErrorInvalidValue;
+  if (!al16(d) || (z && !al16(z)) || (z_f32 && !al16(z_f32))) return hipErrorInvalidValue;
+  const int chunks = (rows + CS_ROWS - 1) / CS_ROWS;
+  dim3 grid((cols + CS_COLS - 1) / CS_COLS, chunks), block(256);
+  if (z_f32)
+    hipLaunchKernelGGL((colsum_mul_stage1<true>), grid, block, 0, s, d, z, z_f32, partials, rows, cols);
+  else
+    hipLaunchKernelGGL((colsum_mul_stage1<false>), grid, block, 0, s, d, z, z_f32, partials, rows, cols);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(colsum_stage2, dim3((cols + 255) / 256), dim3(256), 0, s, partials, out, chunks, cols);

@@ -10,6 +10,9 @@ def desc_from_config(cfg, batch=None):
     B = cfg.batch if batch is None else batch
     if cfg.kind == "mlp":
         return et.make_desc(et.ET_MLP, et.ET_F32, B, dims=cfg.dims)
+    if cfg.kind == "resnet":
+        return et.make_desc(et.ET_RESNET, et.ET_BF16, B, classes=cfg.classes, image=cfg.image, in_ch=cfg.in_ch,
+                            stem=cfg.stem, stage_blocks=cfg.blocks, planes=cfg.planes)
     return et.make_desc(et.ET_VIT, et.ET_BF16, B, tokens=cfg.tokens, patch_dim=cfg.patch_dim, width=cfg.width,
                         heads=cfg.heads, mlp=cfg.mlp, blocks=cfg.blocks, classes=cfg.classes, ln_eps=cfg.ln_eps)
 

@@ -5,6 +5,7 @@ import pytest
 import torch
 
 from oracle import nets, resnet
+from oracle import resnet as R
 from synth import CONFIGS, make_workload, tensor_specs
 
 
@@ -93,3 +94,31 @@ def test_executed_work_and_mask_invariants():
         assert sorted(j for op, j in r["work"] if op == "dy") == list(range(sel[0] + 1, N))
         for j in sel:
             assert np.array_equal(r["grads"][j], full["grads"][j])
+
+
+# ----------------------------------------------------------------------------
+# storage-precision hook
+# ----------------------------------------------------------------------------
+def test_round_bf16_matches_torch():
+    rng = np.random.default_rng(0)
+    a = np.concatenate([rng.standard_normal(4096) * 10.0 ** rng.integers(-6, 6, 4096),
+                        np.array([0.0, -0.0, 1.0, 1.00390625, 1.001953125, 1.005859375, 3.0e38, -2.5e-40])])
+    want = torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(R.round_bf16(a), want)
+    assert np.array_equal(R.round_bf16(want), want)                 # idempotent
+
+
+def test_store_none_is_the_plain_definition_and_bf16_store_stays_close():
+    cfg = CONFIGS["resnet_tiny"]
+    wl = make_workload(cfg, seed=0, init="random")
+    N = len(wl.weights)
+    exact = R.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * N)
+    same = R.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * N, store=lambda a: a)
+    for a, b in zip(exact["grads"], same["grads"]):
+        assert np.array_equal(a, b)
+    stored = R.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * N, store=R.round_bf16)
+    assert stored["work"] == exact["work"]
+    errs = [np.linalg.norm(a - b) / np.linalg.norm(a) for a, b in zip(exact["grads"], stored["grads"])]
+    # a bf16 evaluation of a ReLU network is not a rounding of the exact gradient: per cent, not 2^-9
+    assert 1e-3 < max(errs) < 0.25
+    assert abs(stored["loss"] - exact["loss"]) < 2e-2 * abs(exact["loss"])
