@@ -67,7 +67,8 @@ def main():
     ap.add_argument("--config", default="vit_b")
     ap.add_argument("--rho", type=float, default=0.5)
     ap.add_argument("--tq", type=int, default=10000)
-    ap.add_argument("--cpu-sample-batch", type=int, default=64)
+    ap.add_argument("--cpu-sample-batch", type=int, default=None,
+                    help="batch of the oracle's timed step (default: 64 for the transformers, 4 for the ResNet)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB plain copy kernel (known traffic, for scaling hardware counters)")
@@ -113,7 +114,7 @@ def main():
     # ---- kernel classes inside the same selective steps, HIP events on the launch stream
     et.et_kernel_timing(s.ctx, 1)
     timed_steps(s, xt, yt, mask, mk, a.steps, 1)
-    classes = {c: et.et_kernel_timing_read(s.ctx, c) for c in range(7)}
+    classes = {c: et.et_kernel_timing_read(s.ctx, c) for c in range(8)}
     et.et_kernel_timing(s.ctx, 1)
     s.importance(xt, yt, snap)
     imp_n, imp_ns, imp_bytes = et.et_kernel_timing_read(s.ctx, 3)
@@ -151,8 +152,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": "%s: batch %d, %d tensors, rho=%.2g, Tq=%d, Adam lr 1e-4" % (
-            cfg.name, cfg.batch, N, a.rho, a.tq) if cfg.kind == "vit" else "%s: batch %d, %d tensors, rho=%.2g" % (
-            cfg.name, cfg.batch, N, a.rho)},
+            cfg.name, cfg.batch, N, a.rho, a.tq) if cfg.kind == "vit" else
+            "%s: batch %d, %d tensors, rho=%.2g, Tq=%d, SGD momentum 0.9 lr 1e-4 wd 5e-4" % (cfg.name, cfg.batch, N, a.rho, a.tq)},
         "roofline": roofline,
         "cpu_baseline": None,
         "selected_tensors": int(mask.sum()), "first_selected": int(np.argmax(mask)) if mask.any() else None,
@@ -168,6 +169,9 @@ def main():
         "attention": {name: ({"launches_per_step": classes[c][0] / a.steps, "avg_us": classes[c][1] / classes[c][0] / 1e3,
                               "tflops": classes[c][2] / classes[c][1] / 1e3} if classes[c][0] else None)
                       for name, c in (("forward", 5), ("backward", 6))},
+        "conv_data_movement": ({"launches_per_step": classes[7][0] / a.steps, "ms_per_step": classes[7][1] / a.steps / 1e6,
+                                "gbps": classes[7][2] / classes[7][1],
+                                "frac_of_hbm_peak": classes[7][2] / classes[7][1] / PEAK_HBM_GBS} if classes[7][0] else None),
         "update": {"gbps": upd_bytes / upd_ns if upd_ns else None, "us": upd_ns / max(upd_n, 1) / 1e3,
                    "frac_of_hbm_peak": upd_bytes / upd_ns / PEAK_HBM_GBS if upd_ns else None},
     }
@@ -178,7 +182,8 @@ def main():
         torch.cuda.synchronize()
     s.close()
     if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, mask, min(a.cpu_sample_batch, cfg.batch), opt_kind, hp)
+        sample = a.cpu_sample_batch if a.cpu_sample_batch else (4 if cfg.kind == "resnet" else 64)
+        out["cpu_baseline"] = cpu_baseline(cfg, mask, min(sample, cfg.batch), opt_kind, hp)
     print(json.dumps(out))
 
 

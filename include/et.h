@@ -195,12 +195,13 @@ int et_last_launch_counts(const et_ctx* ctx, int32_t* forward, int32_t* backward
  * duration of a kernel inside real training steps.  Classes:
  *   0 forward GEMM (X W^T), 1 gradient-passing GEMM (dY W), 2 weight-gradient GEMM (dY^T X,
  *   including its split-K reduction), 3 importance reduction, 4 masked optimizer update,
- *   5 fused attention forward, 6 fused attention backward.
+ *   5 fused attention forward, 6 fused attention backward, 7 the data-movement kernels of the
+ *   convolutional workload (im2col and its adjoint, affine, pooling, per-channel reductions).
  * et_kernel_timing_read waits for the stream and returns, for one class, the number of timed
  * launches since timing was enabled, their summed duration, and their summed algorithmic work
- * (floating-point operations for classes 0-2 and 5-6, bytes read plus written for classes 3-4).
+ * (floating-point operations for classes 0-2 and 5-6, bytes read plus written for classes 3-4, 7).
  * Enabling clears the records.  Outputs are host pointers and may be NULL. */
-#define ET_NUM_KERNEL_CLASSES 7
+#define ET_NUM_KERNEL_CLASSES 8
 int et_kernel_timing(et_ctx* ctx, int32_t enable);
 int et_kernel_timing_read(et_ctx* ctx, int32_t kernel_class, uint64_t* launches, double* total_ns, double* work);
 

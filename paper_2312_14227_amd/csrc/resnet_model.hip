@@ -16,6 +16,14 @@
 
 namespace {
 
+// launch of an HBM-bound kernel of this workload: counted, and timed as kernel class 7 with its
+// algorithmic bytes (operands read once, results written once)
+#define ET_KB(n, bytes, expr)              \
+  do {                                     \
+    KernelTimer kt__(c, 7, (double)(bytes)); \
+    ET_K(n, expr);                         \
+  } while (0)
+
 et::ConvGeom geom(const et_ctx* c, const ConvUnit& u) {
   et::ConvGeom g;
   g.B = c->desc.batch; g.H = u.H; g.W = u.W; g.C = u.Cin; g.k = u.k; g.stride = u.stride; g.pad = (u.k - 1) / 2;
@@ -39,7 +47,8 @@ inline bool needs_cols(const ConvUnit& u) { return u.k > 1 || u.stride > 1; }
 int conv_forward(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16* Wm, void* z, bool z_f32) {
   const bf16* A = in;
   if (needs_cols(u)) {
-    ET_K(1, et::im2col(in, u.cols, geom(c, u), c->stream));
+    ET_KB(1, 2.0 * ((double)c->desc.batch * u.H * u.W * u.Cin + (double)rows_of(c, u) * u.Kc),
+          et::im2col(in, u.cols, geom(c, u), c->stream));
     A = u.cols;
   }
   et::GemmDesc g = linear_fwd(A, Wm, nullptr, (int)rows_of(c, u), u.Cout, u.Kc);
@@ -184,9 +193,11 @@ int resnet_forward(et_ctx* c, const void* x, const int32_t* y) {
     ET_K(1, et::pad_rows(Wt(0), c->stem_w8, u.Cout, 49 * u.Cin, u.Kc, s));
     int rc = conv_forward(c, u, (const bf16*)x, c->stem_w8, c->stem_z32, true);
     if (rc != ET_OK) return rc;
-    ET_K(1, et::affine_act(nullptr, c->stem_z32, Wt(1), Wt(2), nullptr, nullptr, nullptr, true, c->pool_y,
-                           (long long)rows_of(c, u), u.Cout, s));
-    ET_K(1, et::maxpool3x3s2_fwd(c->stem_z32, Wt(1), Wt(2), c->pooled, c->pool_arg, B, u.Ho, u.Wo, u.Cout, s));
+    const double n = (double)rows_of(c, u) * u.Cout, np = (double)B * c->rblk[0].c1.H * c->rblk[0].c1.W * u.Cout;
+    ET_KB(1, 6.0 * n, et::affine_act(nullptr, c->stem_z32, Wt(1), Wt(2), nullptr, nullptr, nullptr, true, c->pool_y,
+                                     (long long)rows_of(c, u), u.Cout, s));
+    ET_KB(1, 4.0 * n + 3.0 * np,
+          et::maxpool3x3s2_fwd(c->stem_z32, Wt(1), Wt(2), c->pooled, c->pool_arg, B, u.Ho, u.Wo, u.Cout, s));
   }
   const bf16* h = c->pooled;
   for (ResBlockBufs& b : c->rblk) {
@@ -194,28 +205,32 @@ int resnet_forward(et_ctx* c, const void* x, const int32_t* y) {
     b.x = h;
     int rc = conv_forward(c, b.c1, h, Wt(t), b.c1.z, false);
     if (rc != ET_OK) return rc;
-    ET_K(1, et::affine_act(b.c1.z, nullptr, Wt(t + 1), Wt(t + 2), nullptr, nullptr, nullptr, true, b.c1.y,
-                           (long long)rows_of(c, b.c1), b.c1.Cout, s));
+    ET_KB(1, 4.0 * rows_of(c, b.c1) * b.c1.Cout,
+          et::affine_act(b.c1.z, nullptr, Wt(t + 1), Wt(t + 2), nullptr, nullptr, nullptr, true, b.c1.y,
+                         (long long)rows_of(c, b.c1), b.c1.Cout, s));
     rc = conv_forward(c, b.c2, b.c1.y, Wt(t + 3), b.c2.z, false);
     if (rc != ET_OK) return rc;
-    ET_K(1, et::affine_act(b.c2.z, nullptr, Wt(t + 4), Wt(t + 5), nullptr, nullptr, nullptr, true, b.c2.y,
-                           (long long)rows_of(c, b.c2), b.c2.Cout, s));
+    ET_KB(1, 4.0 * rows_of(c, b.c2) * b.c2.Cout,
+          et::affine_act(b.c2.z, nullptr, Wt(t + 4), Wt(t + 5), nullptr, nullptr, nullptr, true, b.c2.y,
+                         (long long)rows_of(c, b.c2), b.c2.Cout, s));
     rc = conv_forward(c, b.c3, b.c2.y, Wt(t + 6), b.c3.z, false);
     if (rc != ET_OK) return rc;
     if (b.proj) {
       rc = conv_forward(c, b.sc, h, Wt(t + 9), b.sc.z, false);
       if (rc != ET_OK) return rc;
-      ET_K(1, et::affine_act(b.c3.z, nullptr, Wt(t + 7), Wt(t + 8), b.sc.z, Wt(t + 10), Wt(t + 11), true, b.y,
-                             (long long)rows_of(c, b.c3), b.c3.Cout, s));
+      ET_KB(1, 6.0 * rows_of(c, b.c3) * b.c3.Cout,
+            et::affine_act(b.c3.z, nullptr, Wt(t + 7), Wt(t + 8), b.sc.z, Wt(t + 10), Wt(t + 11), true, b.y,
+                           (long long)rows_of(c, b.c3), b.c3.Cout, s));
     } else {
-      ET_K(1, et::affine_act(b.c3.z, nullptr, Wt(t + 7), Wt(t + 8), h, nullptr, nullptr, true, b.y,
-                             (long long)rows_of(c, b.c3), b.c3.Cout, s));
+      ET_KB(1, 6.0 * rows_of(c, b.c3) * b.c3.Cout,
+            et::affine_act(b.c3.z, nullptr, Wt(t + 7), Wt(t + 8), h, nullptr, nullptr, true, b.y,
+                           (long long)rows_of(c, b.c3), b.c3.Cout, s));
     }
     h = b.y;
   }
   const ResBlockBufs& last = c->rblk.back();
   const int Cf = last.c3.Cout, N = (int)c->tensors.size();
-  ET_K(1, et::avgpool_fwd(h, c->zc, B, last.c3.Ho * last.c3.Wo, Cf, s));
+  ET_KB(1, 2.0 * B * last.c3.Ho * last.c3.Wo * Cf, et::avgpool_fwd(h, c->zc, B, last.c3.Ho * last.c3.Wo, Cf, s));
   {
     et::GemmDesc g = linear_fwd(c->zc, Wt(N - 2), Wt(N - 1), B, d.classes, Cf);
     g.C = c->logits; g.c_f32 = true;
@@ -255,7 +270,7 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
     et::GemmDesc g = linear_dx(c->dl16, Wt(N - 2), B, C, Cf);
     g.lda = C8; g.C = c->dz;
     ET_G(g);
-    ET_K(1, et::avgpool_bwd_relu(c->dz, last.y, c->rdsum, B, HWf, Cf, s));
+    ET_KB(1, 4.0 * B * HWf * Cf, et::avgpool_bwd_relu(c->dz, last.y, c->rdsum, B, HWf, Cf, s));
   }
 
   // ---- blocks, output side first.  On entry rdsum holds the gradient of the block's pre-ReLU sum.
@@ -267,16 +282,16 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
     if (b.proj) {
       if (sel(t + 11)) {
         Region r(c, PH_DW, t + 11);
-        ET_K(2, et::colsum(c->rdsum, nullptr, b.sc.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 11], cp, (int)M3,
+        ET_KB(2, 2.0 * M3 * b.sc.Cout, et::colsum(c->rdsum, nullptr, b.sc.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 11], cp, (int)M3,
                            b.sc.Cout, s));
       }
       if (sel(t + 10)) {
         Region r(c, PH_DW, t + 10);
-        ET_K(2, et::colsum_mul(c->rdsum, b.sc.z, nullptr, c->grad[t + 10], cp, (int)M3, b.sc.Cout, s));
+        ET_KB(2, 4.0 * M3 * b.sc.Cout, et::colsum_mul(c->rdsum, b.sc.z, nullptr, c->grad[t + 10], cp, (int)M3, b.sc.Cout, s));
       }
       if (pass(t + 10)) {
         Region r(c, PH_DY, t + 10);
-        ET_K(1, et::scale_cols(c->rdsum, Wt(t + 10), c->rdsc, M3, b.sc.Cout, s));
+        ET_KB(1, 4.0 * M3 * b.sc.Cout, et::scale_cols(c->rdsum, Wt(t + 10), c->rdsc, M3, b.sc.Cout, s));
       }
       if (sel(t + 9)) {
         Region r(c, PH_DW, t + 9);
@@ -286,16 +301,16 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
     // main branch: c3
     if (sel(t + 8)) {
       Region r(c, PH_DW, t + 8);
-      ET_K(2, et::colsum(c->rdsum, nullptr, b.c3.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 8], cp, (int)M3,
+      ET_KB(2, 2.0 * M3 * b.c3.Cout, et::colsum(c->rdsum, nullptr, b.c3.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 8], cp, (int)M3,
                          b.c3.Cout, s));
     }
     if (sel(t + 7)) {
       Region r(c, PH_DW, t + 7);
-      ET_K(2, et::colsum_mul(c->rdsum, b.c3.z, nullptr, c->grad[t + 7], cp, (int)M3, b.c3.Cout, s));
+      ET_KB(2, 4.0 * M3 * b.c3.Cout, et::colsum_mul(c->rdsum, b.c3.z, nullptr, c->grad[t + 7], cp, (int)M3, b.c3.Cout, s));
     }
     if (pass(t + 7)) {
       Region r(c, PH_DY, t + 7);
-      ET_K(1, et::scale_cols(c->rdsum, Wt(t + 7), c->rd[0], M3, b.c3.Cout, s));
+      ET_KB(1, 4.0 * M3 * b.c3.Cout, et::scale_cols(c->rdsum, Wt(t + 7), c->rd[0], M3, b.c3.Cout, s));
     }
     if (sel(t + 6)) {
       Region r(c, PH_DW, t + 6);
@@ -304,21 +319,21 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
     if (pass(t + 6)) {  // through the 1x1 convolution and the ReLU after c2
       Region r(c, PH_DY, t + 6);
       if ((rc = conv_dcols(c, b.c3, c->rd[0], Wt(t + 6), c->rd[1])) != ET_OK) return rc;
-      ET_K(1, et::add_mask(c->rd[1], nullptr, b.c2.y, c->rd[1], M2 * b.c2.Cout, s));
+      ET_KB(1, 6.0 * M2 * b.c2.Cout, et::add_mask(c->rd[1], nullptr, b.c2.y, c->rd[1], M2 * b.c2.Cout, s));
     }
     // c2
     if (sel(t + 5)) {
       Region r(c, PH_DW, t + 5);
-      ET_K(2, et::colsum(c->rd[1], nullptr, b.c2.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 5], cp, (int)M2,
+      ET_KB(2, 2.0 * M2 * b.c2.Cout, et::colsum(c->rd[1], nullptr, b.c2.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 5], cp, (int)M2,
                          b.c2.Cout, s));
     }
     if (sel(t + 4)) {
       Region r(c, PH_DW, t + 4);
-      ET_K(2, et::colsum_mul(c->rd[1], b.c2.z, nullptr, c->grad[t + 4], cp, (int)M2, b.c2.Cout, s));
+      ET_KB(2, 4.0 * M2 * b.c2.Cout, et::colsum_mul(c->rd[1], b.c2.z, nullptr, c->grad[t + 4], cp, (int)M2, b.c2.Cout, s));
     }
     if (pass(t + 4)) {
       Region r(c, PH_DY, t + 4);
-      ET_K(1, et::scale_cols(c->rd[1], Wt(t + 4), c->rd[0], M2, b.c2.Cout, s));
+      ET_KB(1, 4.0 * M2 * b.c2.Cout, et::scale_cols(c->rd[1], Wt(t + 4), c->rd[0], M2, b.c2.Cout, s));
     }
     if (sel(t + 3)) {
       Region r(c, PH_DW, t + 3);
@@ -327,21 +342,21 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
     if (pass(t + 3)) {  // through the 3x3 convolution and the ReLU after c1
       Region r(c, PH_DY, t + 3);
       if ((rc = conv_dcols(c, b.c2, c->rd[0], Wt(t + 3), c->rdcols)) != ET_OK) return rc;
-      ET_K(1, et::col2im(c->rdcols, nullptr, b.c1.y, c->rd[1], geom(c, b.c2), s));
+      ET_KB(1, 2.0 * M2 * b.c2.Kc + 4.0 * M1 * b.c1.Cout, et::col2im(c->rdcols, nullptr, b.c1.y, c->rd[1], geom(c, b.c2), s));
     }
     // c1
     if (sel(t + 2)) {
       Region r(c, PH_DW, t + 2);
-      ET_K(2, et::colsum(c->rd[1], nullptr, b.c1.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 2], cp, (int)M1,
+      ET_KB(2, 2.0 * M1 * b.c1.Cout, et::colsum(c->rd[1], nullptr, b.c1.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 2], cp, (int)M1,
                          b.c1.Cout, s));
     }
     if (sel(t + 1)) {
       Region r(c, PH_DW, t + 1);
-      ET_K(2, et::colsum_mul(c->rd[1], b.c1.z, nullptr, c->grad[t + 1], cp, (int)M1, b.c1.Cout, s));
+      ET_KB(2, 4.0 * M1 * b.c1.Cout, et::colsum_mul(c->rd[1], b.c1.z, nullptr, c->grad[t + 1], cp, (int)M1, b.c1.Cout, s));
     }
     if (pass(t + 1)) {
       Region r(c, PH_DY, t + 1);
-      ET_K(1, et::scale_cols(c->rd[1], Wt(t + 1), c->rd[0], M1, b.c1.Cout, s));
+      ET_KB(1, 4.0 * M1 * b.c1.Cout, et::scale_cols(c->rd[1], Wt(t + 1), c->rd[0], M1, b.c1.Cout, s));
     }
     if (sel(t)) {
       Region r(c, PH_DW, t);
@@ -356,13 +371,15 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
       const bf16* prev_y = bi > 0 ? c->rblk[bi - 1].y : nullptr;
       if (b.proj) {
         if ((rc = conv_dcols(c, b.sc, c->rdsc, Wt(t + 9), c->rdcols)) != ET_OK) return rc;
-        ET_K(1, et::col2im(c->rdcols, c->rd[1], prev_y, prev_y ? c->rdsum : c->rd[0], geom(c, b.sc), s));
+        ET_KB(1, 2.0 * M3 * b.sc.Kc + (prev_y ? 6.0 : 4.0) * M1 * b.c1.Cin,
+              et::col2im(c->rdcols, c->rd[1], prev_y, prev_y ? c->rdsum : c->rd[0], geom(c, b.sc), s));
       } else {
-        ET_K(1, et::add_mask(c->rd[1], c->rdsum, prev_y, c->rdsum, M1 * b.c1.Cin, s));
+        ET_KB(1, 8.0 * M1 * b.c1.Cin, et::add_mask(c->rd[1], c->rdsum, prev_y, c->rdsum, M1 * b.c1.Cin, s));
       }
       if (!prev_y) {
         const ConvUnit& u = c->stem;
-        ET_K(1, et::maxpool3x3s2_bwd(c->rd[0], c->pool_arg, c->pool_y, c->rdsum, B, u.Ho, u.Wo, u.Cout, s));
+        ET_KB(1, 3.0 * M1 * b.c1.Cin + 4.0 * B * u.Ho * u.Wo * u.Cout,
+              et::maxpool3x3s2_bwd(c->rd[0], c->pool_arg, c->pool_y, c->rdsum, B, u.Ho, u.Wo, u.Cout, s));
       }
     }
   }
@@ -373,15 +390,15 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
     const long long M = (long long)rows_of(c, u);
     if (sel(2)) {
       Region r(c, PH_DW, 2);
-      ET_K(2, et::colsum(c->rdsum, nullptr, u.Cout, nullptr, 0, nullptr, nullptr, c->grad[2], cp, (int)M, u.Cout, s));
+      ET_KB(2, 2.0 * M * u.Cout, et::colsum(c->rdsum, nullptr, u.Cout, nullptr, 0, nullptr, nullptr, c->grad[2], cp, (int)M, u.Cout, s));
     }
     if (sel(1)) {
       Region r(c, PH_DW, 1);
-      ET_K(2, et::colsum_mul(c->rdsum, nullptr, c->stem_z32, c->grad[1], cp, (int)M, u.Cout, s));
+      ET_KB(2, 6.0 * M * u.Cout, et::colsum_mul(c->rdsum, nullptr, c->stem_z32, c->grad[1], cp, (int)M, u.Cout, s));
     }
     if (pass(1)) {
       Region r(c, PH_DY, 1);
-      ET_K(1, et::scale_cols(c->rdsum, Wt(1), c->rd[0], M, u.Cout, s));
+      ET_KB(1, 4.0 * M * u.Cout, et::scale_cols(c->rdsum, Wt(1), c->rd[0], M, u.Cout, s));
     }
     if (sel(0)) {
       Region r(c, PH_DW, 0);

@@ -217,12 +217,27 @@ __global__ __launch_bounds__(256) void colsum_mul_stage1(const bf16* __restrict_
   }
 }
 
-__global__ void colsum_stage2(const float* __restrict__ partials, float* __restrict__ out, int chunks, int cols) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= cols) return;
-  float s = partials[c];
-  for (int k = 1; k < chunks; k++) s += partials[(long long)k * cols + c];
-  out[c] = s;
+// stage 2: 16 threads per column each add every 16th row-chunk partial, then the 16 sums are added
+// in ascending order (a long serial loop per column would be bound by load latency)
+constexpr int S2_PARTS = 16, S2_COLS = 16;
+__global__ __launch_bounds__(256) void colsum_stage2(const float* __restrict__ partials, float* __restrict__ out,
+                                                     int chunks, int cols) {
+  __shared__ float red[S2_PARTS][S2_COLS + 1];
+  const int cx = threadIdx.x % S2_COLS, part = threadIdx.x / S2_COLS;
+  const int c = blockIdx.x * S2_COLS + cx;
+  float s = 0.f;
+  if (c < cols) {
+#pragma unroll 4
+    for (int k = part; k < chunks; k += S2_PARTS) s += partials[(long long)k * cols + c];
+  }
+  red[part][cx] = s;
+  __syncthreads();
+  if (threadIdx.x < S2_COLS && c < cols) {
+    float t = red[0][cx];
+#pragma unroll
+    for (int q = 1; q < S2_PARTS; q++) t += red[q][cx];
+    out[c] = t;
+  }
 }
 
 __global__ void batchsum_kernel(const float* __restrict__ d, float* __restrict__ out, int B, long long batch_stride,
@@ -402,7 +417,7 @@ hipError_t colsum(const bf16* d, const float* d_f32, long long d_stride, const f
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(colsum_stage2, dim3((cols + 255) / 256), dim3(256), 0, s, partials, out, chunks, cols);
+  hipLaunchKernelGGL(colsum_stage2, dim3((cols + S2_COLS - 1) / S2_COLS), dim3(256), 0, s, partials, out, chunks, cols);
   return hipGetLastError();
 }
 
@@ -418,7 +433,7 @@ hipError_t colsum_mul(const bf16* d, const bf16* z, const float* z_f32, float* o
     hipLaunchKernelGGL((colsum_mul_stage1<false>), grid, block, 0, s, d, z, z_f32, partials, rows, cols);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(colsum_stage2, dim3((cols + 255) / 256), dim3(256), 0, s, partials, out, chunks, cols);
+  hipLaunchKernelGGL(colsum_stage2, dim3((cols + S2_COLS - 1) / S2_COLS), dim3(256), 0, s, partials, out, chunks, cols);
   return hipGetLastError();
 }
 

@@ -38,7 +38,14 @@ def main():
     cfg = CONFIGS[name]
     batch = int(sys.argv[3]) if len(sys.argv) > 3 else cfg.batch
     wl = make_workload(cfg, seed=seed, batch=batch)
-    I, r = oimp.importance(cfg, wl.weights, wl.snapshot, wl.x, wl.y)
+    if cfg.kind == "resnet":
+        # a bf16 evaluation of a deep ReLU network is not a rounding of the exact gradient: the stored
+        # reference rounds the tensors the bf16 data layout keeps in memory (see oracle/resnet.py)
+        from oracle import resnet
+        r = resnet.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights), store=resnet.round_bf16)
+        I = oimp.importance_from_grads(r["grads"], wl.weights, wl.snapshot)
+    else:
+        I, r = oimp.importance(cfg, wl.weights, wl.snapshot, wl.x, wl.y)
     A = oimp.abs_importance_from_grads(r["grads"], wl.weights, wl.snapshot)
     out = dict(loss=np.float64(r["loss"]), logits=r["logits"], importance=I, abs_importance=A,
                batch=np.int64(batch), seed=np.int64(seed),

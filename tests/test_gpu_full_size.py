@@ -1,5 +1,5 @@
 """Parity at the full size of the benchmark workloads (ViT-B shape at batch 64, ViT-L shape at batch
-32), in the launch configuration bench.py times, against oracle values stored by tests/golden/make_full_size_golden.py
+32, ResNet-50 shape at batch 32), in the launch configuration bench.py times, against oracle values stored by tests/golden/make_full_size_golden.py
 (per tensor 512 uniformly drawn gradient elements plus its 512 largest ones, gradient norms, loss,
 importance)."""
 import os
@@ -14,8 +14,15 @@ pytestmark = pytest.mark.gpu
 GOLD_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 
-@pytest.mark.parametrize("name,first", [("vit_b", 87), ("vit_l", 200)])
-def test_full_size_gradients_importance_and_masks(name, first):
+# Tolerance.  ViT: the 2e-2 of the workload definition, against the exact oracle.  ResNet-50: the stored
+# reference is the oracle with bf16 storage rounding (see oracle/resnet.py); the kernels add in fp32 in
+# another order than the oracle's float64, which flips the bf16 rounding of about one activation in a
+# thousand per layer (forward noise of a few 1e-4 at the last block).  A ReLU turns a perturbation eps of
+# its input into a fraction ~eps of flipped mask bits, each of which drops or passes a whole gradient
+# element: a gradient error of sqrt(eps), i.e. 1-3 % here.  Two correct bf16 evaluations differ by that
+# much; the small ResNet cases, where no rounding flips, agree to 2e-6 (tests/test_gpu_resnet.py).
+@pytest.mark.parametrize("name,first,tol", [("vit_b", 87, 2e-2), ("vit_l", 200, 2e-2), ("resnet50", 80, 5e-2)])
+def test_full_size_gradients_importance_and_masks(name, first, tol):
     import torch
     from paper_2312_14227_amd.session import Session
     G = np.load(os.path.join(GOLD_DIR, "%s_seed0.npz" % name))
@@ -26,7 +33,6 @@ def test_full_size_gradients_importance_and_masks(name, first):
     s = Session(cfg, wl.weights, with_state=False)
     xt, yt = s.put_input(wl.x, wl.y)
     snap = s.put_snapshot(wl.snapshot)
-    tol = 2e-2
     errs = {}
     I = s.importance(xt, yt, snap)                 # full backward, gradients stay in the buffers
     torch.cuda.synchronize()
@@ -43,11 +49,12 @@ def test_full_size_gradients_importance_and_masks(name, first):
         # a gradient within tol (relative L2) moves g.dw by at most tol |g| |dw| (Cauchy-Schwarz)
         dwn = float(np.linalg.norm((wl.snapshot[k].astype(np.float64) - wl.weights[k].astype(np.float64)).ravel()))
         bound = tol * max(abs(G["importance"][k]), G["gnorm"][k] * dwn)
-        worst_i = max(worst_i, abs(I[k] - G["importance"][k]) / bound)
+        if bound > 0.0:
+            worst_i = max(worst_i, abs(I[k] - G["importance"][k]) / bound)
         assert abs(I[k] - G["importance"][k]) <= bound, (wl.names[k], I[k], G["importance"][k])
     top = sorted(errs.items(), key=lambda kv: -kv[1])[:6]
     print("largest sampled gradient errors:", [(n, round(e, 4)) for n, e in top],
-          "| tensors above 2e-2:", sum(e > 2e-2 for e in errs.values()), "of", N)
+          "| tensors above 2e-2:", sum(e > 2e-2 for e in errs.values()), "of", N, "| median %.4f" % float(np.median(list(errs.values()))))
     assert top[0][1] <= tol, top
     print("worst sampled relative L2 gradient error at full size: %.3e; worst importance error / bound: %.3f"
           % (worst, worst_i))
