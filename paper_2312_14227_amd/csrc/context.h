@@ -194,14 +194,11 @@ struct Region {
   }
 };
 
-// split of the reduction dimension for a weight gradient [Mo][No] reduced over K rows: as many
-// chunks as keep one wave of 256x256 tiles on the 256 CUs, each chunk at least 4 slices of 64
+// split of the reduction dimension for a weight gradient [Mo][No] reduced over K rows
 inline int split_for(int Mo, int No, int K) {
-  const int tiles = ((Mo + 255) / 256) * ((No + 255) / 256);
-  int s = 256 / tiles;
-  const int slices = (K + 63) / 64;
-  s = std::min(s, std::max(1, slices / 4));
-  return std::max(1, std::min(s, 64));
+  int tile, split;
+  et::gemm_bf16_plan_split(Mo, No, K, &tile, &split);
+  return split;
 }
 
 // Y[M][N] = X[M][K] W[N][K]^T (+ bias) ...
@@ -221,9 +218,9 @@ inline et::GemmDesc linear_dw(et_ctx* c, const bf16* dY, int ldy, const bf16* X,
   et::GemmDesc g;
   g.A = dY; g.a_t = true; g.lda = ldy; g.B = X; g.b_t = true; g.ldb = ldx; g.M = N; g.N = K; g.K = M;
   g.C = dW; g.ldc = K; g.c_f32 = true;
-  g.split_k = split_for(N, K, M);
+  et::gemm_bf16_plan_split(N, K, M, &g.tile, &g.split_k);
   g.partials = c->gemm_partials;
-  if (et::gemm_bf16_partial_elems(N, K, g.split_k) > c->gemm_partial_elems) g.split_k = 1;
+  if (et::gemm_bf16_partial_elems(N, K, g.split_k) > c->gemm_partial_elems) { g.split_k = 1; g.tile = 0; }
   return g;
 }
 

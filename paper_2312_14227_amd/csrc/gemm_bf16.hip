@@ -1,4 +1,6 @@
 // Host side of the bf16 MFMA GEMM: argument checks, tile choice, split-K reduction.
+#include <algorithm>
+
 #include "gemm_bf16_kernels.h"
 
 namespace et {
@@ -16,24 +18,70 @@ __global__ void splitk_reduce_kernel(const float4* __restrict__ part, float4* __
   out[i] = s;
 }
 
-enum TileId : int { T_AUTO = 0, T_128x128 = 1, T_128x64 = 3, T_DMA_256x256 = 5, T_DMA_256x128 = 7 };
+enum TileId : int { T_AUTO = 0, T_128x128 = 1, T_128x64 = 3, T_DMA_256x256 = 5, T_DMA_256x128 = 7, T_PP_256x256 = 11, T_PP_256x192 = 13 };
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// Cost model behind the tile and split choice for large problems (seconds, one launch):
+//   rounds of workgroups over the 256 CUs x time of one workgroup at the rate a CU sustains with
+//   that tile (measured on the ViT shapes: about 3.3 TFLOP/s per CU with the 256x256 two-group
+//   tile, 3.0 with 256x192), plus, for a split reduction, writing and re-reading the fp32 partials.
+struct Plan { int tile, split; double cost; };
+
+Plan plan_large(int M, int N, int K, bool may_split) {
+  Plan best = {T_AUTO, 1, 1e30};
+  const int slices = (K + gemm::PBK - 1) / gemm::PBK;
+  const int max_split = may_split ? std::max(1, std::min(64, slices / 4)) : 1;
+  const struct { int tile, bn; double rate; } cand[2] = {{T_PP_256x256, 256, 3.3e12}, {T_PP_256x192, 192, 3.0e12}};
+  for (const auto& c : cand) {
+    const long long tiles = (long long)((M + 255) / 256) * ((N + c.bn - 1) / c.bn);
+    for (int s = 1; s <= max_split; s++) {
+      const int per = (slices + s - 1) / s;
+      const int chunks = (slices + per - 1) / per;
+      if (chunks != s) continue;   // this split leaves empty chunks: the same work as a smaller one
+      const long long rounds = (tiles * s + 255) / 256;
+      double t = rounds * (2.0 * 256 * c.bn * per * gemm::PBK / c.rate);
+      if (s > 1) t += (2.0 * s + 1.0) * M * N * 4.0 / 3.5e12;
+      if (t < best.cost) best = {c.tile, s, t};
+    }
+  }
+  return best;
+}
+
 int choose_tile(const GemmDesc& d, int k_per_block) {
   const bool dma_ok = (d.K % gemm::DBK) == 0 && (k_per_block % gemm::DBK) == 0;
+  const bool pp_ok = (d.K % gemm::PBK) == 0 && (k_per_block % gemm::PBK) == 0;
+  if (d.tile == T_PP_256x256 || d.tile == T_PP_256x192) return pp_ok ? d.tile : (dma_ok ? T_DMA_256x256 : T_128x128);
   if (d.tile == T_DMA_256x256 || d.tile == T_DMA_256x128) return dma_ok ? d.tile : T_128x128;
   if (d.tile != T_AUTO) return d.tile;
   if (d.N <= 64) return T_128x64;
-  // large problems: direct-to-LDS tiles; the wider matrices did better with two 256x128
-  // workgroups per CU, the others with one 256x256 workgroup (measured on the ViT shapes)
-  if (dma_ok && d.M >= 512 && d.N >= 256 && k_per_block >= 4 * gemm::DBK) return d.N >= 2560 ? T_DMA_256x128 : T_DMA_256x256;
+  // large problems: a two-group tile where K comes in slices of 64 (4-20 % faster than either
+  // direct-to-LDS tile on every forward, passing and gradient product of the ViT shapes), else
+  // the direct-to-LDS tile with slices of 32
+  if (d.M >= 512 && d.N >= 256) {
+    if (pp_ok && k_per_block >= 4 * gemm::PBK) return plan_large(d.M, d.N, k_per_block, false).tile;
+    if (dma_ok && k_per_block >= 4 * gemm::DBK) return d.N >= 2560 ? T_DMA_256x128 : T_DMA_256x256;
+  }
   return T_128x128;
 }
 
 }  // namespace
 
 size_t gemm_bf16_partial_elems(int M, int N, int split_k) { return split_k > 1 ? (size_t)M * N * split_k : 0; }
+
+void gemm_bf16_plan_split(int M, int N, int K, int* tile, int* split_k) {
+  *tile = T_AUTO;
+  *split_k = 1;
+  if (M >= 256 && N >= 256 && (K % gemm::PBK) == 0 && K >= 4 * gemm::PBK) {
+    const Plan pl = plan_large(M, N, K, true);
+    *tile = pl.tile;
+    *split_k = pl.split;
+  } else {   // small outputs: as many chunks as keep the CUs busy, each at least 4 slices
+    const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
+    const int slices = (K + gemm::SBK - 1) / gemm::SBK;
+    *split_k = std::max(1, std::min(std::min(256 / std::max(tiles, 1), std::max(1, slices / 4)), 64));
+  }
+}
 
 hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   if (launches) *launches = 0;
@@ -96,6 +144,8 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
     case T_128x64: BM = 128; BN = 64; fn = gemm::staged_128x64(d.a_t, d.b_t, epi); break;
     case T_DMA_256x256: BM = 256; BN = 256; fn = gemm::dma_256x256(d.a_t, d.b_t, epi); break;
     case T_DMA_256x128: BM = 256; BN = 128; fn = gemm::dma_256x128(d.a_t, d.b_t, epi); break;
+    case T_PP_256x192: BM = 256; BN = 192; fn = gemm::pp_256x192(d.a_t, d.b_t, epi); break;
+    case T_PP_256x256: BM = 256; BN = 256; fn = gemm::pp_256x256(d.a_t, d.b_t, epi); break;
     default: BM = 128; BN = 128; fn = gemm::staged_128x128(d.a_t, d.b_t, epi); break;
   }
   if (!fn) return hipErrorInvalidValue;  // this (layout, epilogue) pair is not part of the training step

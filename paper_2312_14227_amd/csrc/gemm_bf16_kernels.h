@@ -17,12 +17,14 @@
 //     [k-rows][tile rows] and the lanes fetch their 2 x 4 k values with ds_read_b64_tr_b16, the
 //     LDS transpose read of gfx950: in every group of 16 lanes, lane 4c+a supplies the address of
 //     4 consecutive elements of k-row c, and lane i receives element i of k-rows 0..3.
-// Two main loops share this:
+// Three main loops share this:
 //   gemm_staged_kernel: K slices of 64 through two LDS buffers, the global loads of slice t+1 are
 //     issued into registers before the MFMAs of slice t (small tiles, several workgroups per CU;
 //     any K, with a predicated last slice);
 //   gemm_dma_kernel: K slices of 32 loaded with global_load_lds_dwordx4 straight into a ring of
-//     LDS stages, several slices in flight (large tiles; K a multiple of 32).
+//     LDS stages, several slices in flight (large tiles; K a multiple of 32);
+//   gemm_pp_kernel: K slices of 64 through registers into two LDS stages, the eight waves in two
+//     groups that alternate between MFMAs and memory work (256x256 tile; K a multiple of 64).
 // Rows beyond the matrix edge are clamped to valid addresses (their products are never stored).
 // Epilogue: every wave passes its accumulators through a private LDS area, 32 rows at a time, so
 // that each lane ends up with 4 consecutive columns of one row: bias, residual, GELU and the
@@ -30,6 +32,8 @@
 // Workgroup ids are remapped so that consecutive tiles run on the same XCD (ids are dealt
 // round-robin over the 8 XCDs, each with its own L2), in groups of 8 tile rows.
 #pragma once
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace et {
@@ -39,6 +43,7 @@ typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int NUM_XCD = 8;
 
@@ -144,7 +149,8 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
   const int l32 = lane & 31, khalf = lane >> 5;
   const int c4 = (lane % CPL) * 4, rsub = lane / CPL;
   const int col = col0 + c4;
-  const bool col_any = col < g.N, col_full = col + 3 < g.N;
+  // (when 64 is not a multiple of CPL the last lanes of the wave have no row of their own)
+  const bool col_any = col < g.N && rsub < RPI, col_full = col + 3 < g.N;
   const int ld = EPI == E_PARTIAL ? g.N : g.ldc;
   float bias[4] = {0.f, 0.f, 0.f, 0.f};
   if (EPI != E_PARTIAL && EPI != E_GELU_BWD && g.bias && col_any) {
@@ -165,7 +171,7 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
     // the same wave reads back: LDS operations of one wave complete in order
 #pragma unroll
     for (int it = 0; it < 32 / RPI; it++) {
-      const int rr = it * RPI + rsub;
+      const int rr = min(it * RPI + rsub, 31);
       const float4 raw = *(const float4*)(stage + rr * TN + c4);
       const int row = row0 + mi * 32 + rr;
       if (row >= g.M || !col_any) continue;
@@ -591,10 +597,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(Params g) {
     else wait_vmcnt<0>();
   };
 
+  bf16x8 a0[MI], b0[NI], a1[MI], b1[NI];
 #pragma unroll
   for (int sl = 0; sl < RING - 2; sl++)
     if (sl < nk) issue(sl);
-  bf16x8 a0[MI], b0[NI], a1[MI], b1[NI];
   if (nk > 0) {
     wait_slice(0);
     block_barrier();
@@ -611,7 +617,246 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(Params g) {
     if (kt + 1 < nk) load_frags(smem + ((kt + 1) % RING) * STAGE, 0, a0, b0);
     mma(a1, b1);
   }
-  if (g.no_store) return;
+  if (g.no_store & 7) return;
+  __syncthreads();  // every wave is done with the stages before they are reused for the epilogue
+  wave_epilogue<EPI, MI, NI>(g, acc, (float*)smem + wave * 32 * TN, m0 + wave_m * TM, n0 + wave_n * TN, c_off, lane);
+}
+
+// =================================================================================================
+// two-group kernel: K slices of 64 through registers into two LDS stages
+// =================================================================================================
+// Measured on this chip: a wave-wide load whose lanes cover 16 rows x 64 B costs 18 ns per CU
+// when every CU loads, one that covers 8 rows x 128 B (whole cache lines) 10 ns; with slices of 32
+// the operand loads of a 256x256 tile take longer than its MFMAs.  This kernel therefore loads
+// slices of 64 (128-byte row pieces), and since two 64 KiB stages are all that fits in LDS, the
+// third buffer of the pipeline is the register file: a slice is loaded into registers one slice
+// period before it is written to the stage that has just been read for the last time.
+//
+// Schedule.  The 8 waves form two groups with one wave on each SIMD; in every barrier interval
+// one group multiplies half a slice (16 MFMAs) while the other does its memory work, then they
+// swap, so the matrix pipe of a SIMD always has a wave with operands in registers:
+//   group 0:  M(0,0) | C(0,0) | M(0,1) | C(0,1) | M(1,0) | ...
+//   group 1:         | M(0,0) | C(0,0) | M(0,1) | C(0,1) | ...
+// M(t,h): write this wave's A (h=0) or B (h=1) pieces of slice t+1 from registers to stage
+// (t+1)%2, start the global loads of the same pieces of slice t+2 into those registers, read the
+// fragments of half h of slice t from stage t%2.  Stage (t+1)%2 held slice t-1, last read in
+// interval 4t-1; it is written in intervals 4t..4t+3 and first read in interval 4t+4.  Loads and
+// stores past the last slice are not skipped but repeat the last slice into a dead stage, which
+// keeps the loop free of branches.  Every wave executes the same number of barriers: group 1 one
+// extra before the loop, group 0 one extra after it.
+constexpr int PBK = 64;
+
+template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, int EPI>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
+  constexpr int NW = WGM * WGN;
+  constexpr int TM = BM / WGM, TN = BN / WGN;
+  constexpr int MI = TM / 32, NI = TN / 32;
+  constexpr int A_BYTES = BM * PBK * 2, B_BYTES = BN * PBK * 2, STAGE = A_BYTES + B_BYTES;
+  constexpr int A_LOADS = A_BYTES / 1024 / NW, B_LOADS = B_BYTES / 1024 / NW;  // wave-wide 1 KiB pieces per wave and slice
+  static_assert(NW == 8, "two groups of four waves");
+  static_assert(A_LOADS * 1024 * NW == A_BYTES && B_LOADS * 1024 * NW == B_BYTES, "tile/waves mismatch");
+  constexpr int EPI_BYTES = NW * 32 * TN * 4;
+  constexpr int SMEM = 2 * STAGE > EPI_BYTES ? 2 * STAGE : EPI_BYTES;
+  static_assert(SMEM <= 160 * 1024, "LDS");
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave / WGN, wave_n = wave % WGN;
+  int m0, n0;
+  tile_coords<BM, BN>(g, m0, n0);
+  if (g.no_store & 4) { m0 = 0; n0 = 0; }
+  const bf16* A;
+  const bf16* B;
+  long long c_off;
+  int k_begin, k_end;
+  batch_offsets(g, A, B, c_off, k_begin, k_end);
+  const int nk = (k_end - k_begin) / PBK;
+
+  // per-lane global source and LDS destination (within a stage) of each of this wave's pieces
+  const bf16* ga[A_LOADS];
+  const bf16* gb[B_LOADS];
+  int la[A_LOADS], lb[B_LOADS];
+#pragma unroll
+  for (int i = 0; i < A_LOADS; i++) {
+    const int q = wave * A_LOADS + i;
+    if (!AT) {  // 8 rows x 128 B; 16-byte chunk c of row r sits at chunk position c ^ ((r >> 1) & 7)
+      const int row = q * 8 + (lane >> 3), chunk = lane & 7;
+      ga[i] = A + (long long)min(m0 + row, g.M - 1) * g.lda + k_begin + chunk * 8;
+      la[i] = row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
+    } else {    // [64 k-rows][BM]; chunk j of k-row k sits at chunk position j ^ ((k & 3) << 1)
+      constexpr int CR = BM / 8;
+      const int pos = q * 64 + lane;
+      const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << 1);
+      int gi = m0 + j * 8;
+      if (gi + 8 > ((g.M + 7) & ~7)) gi = 0;
+      ga[i] = A + (long long)(k_begin + k) * g.lda + gi;
+      la[i] = pos * 16;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < B_LOADS; i++) {
+    const int q = wave * B_LOADS + i;
+    if (!BT) {
+      const int row = q * 8 + (lane >> 3), chunk = lane & 7;
+      gb[i] = B + (long long)min(n0 + row, g.N - 1) * g.ldb + k_begin + chunk * 8;
+      lb[i] = A_BYTES + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
+    } else {
+      constexpr int CR = BN / 8;
+      const int pos = q * 64 + lane;
+      const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << 1);
+      int gj = n0 + j * 8;
+      if (gj + 8 > ((g.N + 7) & ~7)) gj = 0;
+      gb[i] = B + (long long)(k_begin + k) * g.ldb + gj;
+      lb[i] = A_BYTES + pos * 16;
+    }
+  }
+  const long long a_step = AT ? (long long)PBK * g.lda : PBK;
+  const long long b_step = BT ? (long long)PBK * g.ldb : PBK;
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; mi++)
+#pragma unroll
+    for (int ni = 0; ni < NI; ni++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[mi][ni][r] = 0.f;
+
+  const int l32 = lane & 31, khalf = lane >> 5;
+  const int grp16 = lane >> 4, r16 = lane & 15;
+  const int tr_col = (grp16 & 1) * 16 + 4 * (r16 & 3);
+  const int tr_krow = (grp16 >> 1) * 8 + (r16 >> 2);
+  const int tr_swz = (r16 >> 2) << 1;
+
+  // fragment of k-step ks (16 k values, 0..3) of the slice in stage `st`
+  auto load_a = [&](const unsigned char* st, int ks, int mi) -> bf16x8 {
+    const int rbase = wave_m * TM + mi * 32;
+    if (!AT) {
+      const int row = rbase + l32, chunk = ks * 2 + khalf;
+      return *(const bf16x8*)(st + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
+    } else {
+      const int col = rbase + tr_col;
+      const unsigned char* p = st + (ks * 16 + tr_krow) * (BM * 2) + (((col >> 3) ^ tr_swz) << 4) + ((col >> 2) & 1) * 8;
+      bf16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * (BM * 2));
+      return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+  };
+  auto load_b = [&](const unsigned char* st, int ks, int ni) -> bf16x8 {
+    const unsigned char* sb = st + A_BYTES;
+    const int rbase = wave_n * TN + ni * 32;
+    if (!BT) {
+      const int row = rbase + l32, chunk = ks * 2 + khalf;
+      return *(const bf16x8*)(sb + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
+    } else {
+      const int col = rbase + tr_col;
+      const unsigned char* p = sb + (ks * 16 + tr_krow) * (BN * 2) + (((col >> 3) ^ tr_swz) << 4) + ((col >> 2) & 1) * 8;
+      bf16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * (BN * 2));
+      return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+  };
+  auto load_frags = [&](const unsigned char* st, int ks, bf16x8 (&af)[MI], bf16x8 (&bfr)[NI]) {
+#pragma unroll
+    for (int mi = 0; mi < MI; mi++) af[mi] = load_a(st, ks, mi);
+#pragma unroll
+    for (int ni = 0; ni < NI; ni++) bfr[ni] = load_b(st, ks, ni);
+  };
+  auto mma = [&](bf16x8 (&af)[MI], bf16x8 (&bfr)[NI]) {
+#pragma unroll
+    for (int mi = 0; mi < MI; mi++)
+#pragma unroll
+      for (int ni = 0; ni < NI; ni++)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+  };
+
+  u32x4 ra[A_LOADS], rb[B_LOADS];
+  // pointers always address a valid slice: they stop advancing at the last one
+  auto load_a_regs = [&](bool advance) {
+#pragma unroll
+    for (int i = 0; i < A_LOADS; i++) {
+      ra[i] = *(const u32x4*)ga[i];
+      ga[i] += advance ? a_step : 0;
+    }
+  };
+  auto load_b_regs = [&](bool advance) {
+#pragma unroll
+    for (int i = 0; i < B_LOADS; i++) {
+      rb[i] = *(const u32x4*)gb[i];
+      gb[i] += advance ? b_step : 0;
+    }
+  };
+  auto store_a = [&](unsigned char* st) {
+#pragma unroll
+    for (int i = 0; i < A_LOADS; i++) *(u32x4*)(st + la[i]) = ra[i];
+  };
+  auto store_b = [&](unsigned char* st) {
+#pragma unroll
+    for (int i = 0; i < B_LOADS; i++) *(u32x4*)(st + lb[i]) = rb[i];
+  };
+
+  const int group = wave >> 2;
+  bf16x8 a0[MI], b0[NI], a1[MI], b1[NI];
+  // prologue: slice 0 into stage 0, slice 1 (or slice 0 again) into the registers
+  load_a_regs(nk > 1);
+  load_b_regs(nk > 1);
+  store_a(smem);
+  store_b(smem);
+  load_a_regs(nk > 2);
+  load_b_regs(nk > 2);
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  block_barrier();
+  if (group == 1) block_barrier();
+  // one C phase: the MFMAs of two k-steps with this wave's global loads of one operand spread
+  // evenly between them, so that the loads of the four SIMDs reach
+  // the texture addresser evenly instead of in a burst that would stall the issuing waves
+  constexpr int P = MI * NI * 2;   // MFMAs of one C phase
+  auto c_phase = [&](auto loads_tag, auto&& load_one) {
+    constexpr int L = decltype(loads_tag)::value;
+    __builtin_amdgcn_s_setprio(1);
+    int n = 0;
+#pragma unroll
+    for (int half = 0; half < 2; half++)
+#pragma unroll
+      for (int mi = 0; mi < MI; mi++)
+#pragma unroll
+        for (int ni = 0; ni < NI; ni++) {
+          acc[mi][ni] = half == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mi], b0[ni], acc[mi][ni], 0, 0, 0)
+                                  : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[mi], b1[ni], acc[mi][ni], 0, 0, 0);
+          n++;
+#pragma unroll
+          for (int j = 0; j < L; j++)
+            if (n == ((2 * j + 1) * P) / (2 * L)) {   // load j goes in the middle of its share of the MFMAs
+              __builtin_amdgcn_sched_barrier(0);
+              load_one(j);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    __builtin_amdgcn_s_setprio(0);
+    block_barrier();
+  };
+  for (int kt = 0; kt < nk; kt++) {
+    unsigned char* cur = smem + (kt & 1) * STAGE;
+    unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
+    const bool adv = kt + 3 < nk;   // the registers are reloaded with slice min(kt + 2, nk - 1)
+    store_a(nxt);
+    load_frags(cur, 0, a0, b0);
+    load_frags(cur, 1, a1, b1);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    block_barrier();
+    c_phase(std::integral_constant<int, A_LOADS>(), [&](int i) {
+      ra[i] = *(const u32x4*)ga[i];
+      ga[i] += adv ? a_step : 0;
+    });
+    store_b(nxt);
+    load_frags(cur, 2, a0, b0);
+    load_frags(cur, 3, a1, b1);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    block_barrier();
+    c_phase(std::integral_constant<int, B_LOADS>(), [&](int i) {
+      rb[i] = *(const u32x4*)gb[i];
+      gb[i] += adv ? b_step : 0;
+    });
+  }
+  if (group == 0) block_barrier();
+  if (g.no_store & 7) return;
   __syncthreads();  // every wave is done with the stages before they are reused for the epilogue
   wave_epilogue<EPI, MI, NI>(g, acc, (float*)smem + wave * 32 * TN, m0 + wave_m * TM, n0 + wave_n * TN, c_off, lane);
 }
@@ -622,6 +867,8 @@ LaunchFn staged_128x128(bool a_t, bool b_t, int epi);
 LaunchFn staged_128x64(bool a_t, bool b_t, int epi);
 LaunchFn dma_256x256(bool a_t, bool b_t, int epi);
 LaunchFn dma_256x128(bool a_t, bool b_t, int epi);
+LaunchFn pp_256x256(bool a_t, bool b_t, int epi);
+LaunchFn pp_256x192(bool a_t, bool b_t, int epi);
 
 }  // namespace gemm
 }  // namespace et

@@ -58,6 +58,9 @@ struct GemmDesc {
 hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches = nullptr);
 // fp32 partial elements needed for a split-K call
 size_t gemm_bf16_partial_elems(int M, int N, int split_k);
+// tile and split for a weight gradient [M][N] reduced over K rows (a cost model over tile shapes
+// and split counts); pass both on in GemmDesc::tile and GemmDesc::split_k
+void gemm_bf16_plan_split(int M, int N, int K, int* tile, int* split_k);
 
 // ------------------------------------------------------------------------------------------
 // fp32 GEMM (true fp32 FMA), same operand convention, for the fp32 MLP workload
