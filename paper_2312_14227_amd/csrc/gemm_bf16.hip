@@ -59,6 +59,10 @@ int choose_tile(const GemmDesc& d, int k_per_block) {
   // direct-to-LDS tile on every forward, passing and gradient product of the ViT shapes), else
   // the direct-to-LDS tile with slices of 32
   if (d.M >= 512 && d.N >= 256) {
+    // the GELU epilogues (two outputs or an extra operand, transcendental math) take as long as a
+    // short main loop; two 256x128 workgroups per CU overlap one's epilogue with the other's MFMAs
+    // (measured in the ViT-B step: 121 us against 132 us with the two-group tile)
+    if (d.mode != EPI_PLAIN && dma_ok && d.N >= 2560 && k_per_block >= 4 * gemm::DBK) return T_DMA_256x128;
     if (pp_ok && k_per_block >= 4 * gemm::PBK) return plan_large(d.M, d.N, k_per_block, false).tile;
     if (dma_ok && k_per_block >= 4 * gemm::DBK) return d.N >= 2560 ? T_DMA_256x128 : T_DMA_256x256;
   }
