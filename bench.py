@@ -144,6 +144,16 @@ def main():
         roofline["all_gemm_tflops"] = all_work / all_ns / 1e3
         roofline["all_gemm_frac"] = all_work / all_ns / 1e3 / PEAK_BF16_TFLOPS
         roofline["gemm_ms_per_step"] = all_ns / a.steps / 1e6
+    # the convolutional workload spends more time in its HBM-bound data-movement kernels than in any one
+    # GEMM class: then that class is the dominant one and the roofline is the HBM one
+    cn, cns, cbytes = classes[7]
+    if cn and (not gemm or cns > max(v[1] for v in gemm.values())):
+        gemm_part = {k: roofline[k] for k in ("all_gemm_tflops", "all_gemm_frac", "gemm_ms_per_step")} if roofline else {}
+        roofline = {"bound": "hbm", "kernel": "convolution data-movement kernels (im2col and its adjoint, affine+ReLU, "
+                    "pooling, per-channel sums)", "achieved": cbytes / cns, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": cbytes / cns / PEAK_HBM_GBS, "traffic": None, "avg_launch_us": cns / cn / 1e3,
+                    "bytes_per_launch": cbytes / cn, "launches_per_step": cn / a.steps}
+        roofline.update(gemm_part)
     upd_n, upd_ns, upd_bytes = classes[4]
 
     out = {
