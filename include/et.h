@@ -157,6 +157,16 @@ int et_importance(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, void* co
 int et_importance_master(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, void* const* w_snapshot_f32_dev /*[N]*/,
                          double* importance_host /*[N]*/);
 
+/* The two importance metrics the ablation of Section 8 compares Eq. 2 with, evaluated per tensor by the
+ * same single segmented reduction (the paper names them only; the reading here is the L1 norm):
+ *   ET_METRIC_WEIGHT_L1: sum |w_i| over the tensor's current weights (x_dev, y_dev may be NULL);
+ *   ET_METRIC_GRAD_L1:   sum |dL/dw_i| after one full backward pass on the given batch.
+ * Neither is additive in the sense of Section 4; their values feed et_select like importances.
+ * metric_host: N doubles.  Synchronises the stream. */
+#define ET_METRIC_WEIGHT_L1 1
+#define ET_METRIC_GRAD_L1 2
+int et_tensor_metric(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, int32_t metric, double* metric_host /*[N]*/);
+
 /* Tensor Selector (Eq. 3 solved exactly on integers; Sections 3.3 and 6).  Pure host code,
  * no context, no device.  Maximises the summed importance of the selected tensors subject to
  *   t_fwd + sum_{i selected} t_dw[i] + sum_{i > i*} t_dy[i] <= rho * T_full,
@@ -174,6 +184,24 @@ int et_importance_master(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, v
 int et_select(int32_t n, const double* importance, const uint64_t* t_dw_ns, const uint64_t* t_dy_ns,
               uint64_t t_fwd_ns, uint32_t rho_ppm, uint32_t tq, uint8_t* mask_out /*[N]*/,
               uint64_t* predicted_ns);
+
+/* The same selection, plus the sizes of the dynamic-programming tables on the quantised times
+ * (Section 6.3, Figure 10: how much of the table the pruning of invalid and redundant cells
+ * leaves).  With depth d = 1..N counted from the output and T the quantised time axis:
+ *   backward_q:     quantised full backward time, budget_q: quantised budget;
+ *   cells_table:    N * (max(backward_q, budget_q) + 1), the paper's table without pruning;
+ *   cells_pruned:   sum over depths that fit the budget of (budget_q - reach_d + 1): cells that are
+ *                   neither invalid (t above the budget) nor redundant (t below the time reach_d of
+ *                   merely passing the gradient down to depth d);
+ *   cells_knapsack: N * (budget_q + 1), the table this library fills (one 0/1-knapsack row per
+ *                   depth serves every choice of the input-most selected tensor).
+ * counts must not be NULL; it is zeroed when the call returns ET_INFEASIBLE or an error. */
+typedef struct {
+  uint64_t backward_q, budget_q, cells_table, cells_pruned, cells_knapsack;
+} et_select_counts;
+int et_select_stats(int32_t n, const double* importance, const uint64_t* t_dw_ns, const uint64_t* t_dy_ns,
+                    uint64_t t_fwd_ns, uint32_t rho_ppm, uint32_t tq, uint8_t* mask_out /*[n]*/,
+                    uint64_t* predicted_ns, et_select_counts* counts);
 
 /* One elastic selective training iteration (Section 2.2): forward pass and loss; then, from
  * the output backwards, the weight gradient of every selected tensor and the error-gradient

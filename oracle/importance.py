@@ -35,3 +35,17 @@ def importance(cfg, weights, snapshot, x, y):
     """Full backward pass at the current weights (all tensors selected), then Eq. 2."""
     r = nets.step(cfg, weights, x, y, [1] * len(weights))
     return importance_from_grads(r["grads"], weights, snapshot), r
+
+
+# ----------------------------------------------------------------------------
+# the two metrics the ablation of Section 8 compares Eq. 2 with ("Weight", "Grad.")
+# ----------------------------------------------------------------------------
+# The paper names them only.  Reading: the L1 norm of the tensor's weights, and the L1 norm of its
+# gradient on the batch.  Neither is additive in the sense of Section 4 (summing magnitudes does not
+# estimate a loss change), which is the point of the ablation.
+def weight_magnitude(weights):
+    return np.array([np.abs(np.asarray(w, dtype=np.float64)).sum() for w in weights])
+
+
+def grad_magnitude(grads):
+    return np.array([np.abs(np.asarray(g, dtype=np.float64)).sum() for g in grads])

@@ -77,7 +77,7 @@ def _load():
 
 _lib = _load()
 EXPORTS = ["et_create", "et_destroy", "et_num_tensors", "et_tensor_info", "et_workspace_bytes", "et_state_slots",
-           "et_bind", "et_profile", "et_importance", "et_importance_master", "et_select", "et_train_step", "et_last_launch_counts",
+           "et_bind", "et_profile", "et_importance", "et_importance_master", "et_select", "et_select_stats", "et_tensor_metric", "et_train_step", "et_last_launch_counts",
            "et_kernel_timing", "et_kernel_timing_read", "et_last_hip_error", "et_strerror", "et_debug_gemm_bf16", "et_debug_copy"]
 
 
@@ -195,6 +195,38 @@ def et_select(importance, t_dw_ns, t_dy_ns, t_fwd_ns, rho_ppm, tq):
                         mask.ctypes.data_as(C.POINTER(C.c_uint8)), C.byref(pred))
     _check(st, "et_select", allow=(ET_INFEASIBLE,))
     return st, mask[:n].copy(), pred.value
+
+
+ET_METRIC_WEIGHT_L1, ET_METRIC_GRAD_L1 = 1, 2
+
+
+def et_tensor_metric(ctx, x_dev, y_dev, metric, n):
+    out = (C.c_double * n)()
+    _lib.et_tensor_metric.restype = C.c_int
+    _check(_lib.et_tensor_metric(ctx, C.c_void_p(x_dev), C.c_void_p(y_dev), C.c_int32(metric), out), "et_tensor_metric", ctx=ctx)
+    return np.array(out[:], dtype=np.float64)
+
+
+class et_select_counts(C.Structure):
+    _fields_ = [("backward_q", C.c_uint64), ("budget_q", C.c_uint64), ("cells_table", C.c_uint64),
+                ("cells_pruned", C.c_uint64), ("cells_knapsack", C.c_uint64)]
+
+
+def et_select_stats(importance, t_dw_ns, t_dy_ns, t_fwd_ns, rho_ppm, tq):
+    """Returns (status, mask uint8[N], predicted_ns, counts dict)."""
+    imp = np.ascontiguousarray(importance, dtype=np.float64)
+    dw = np.ascontiguousarray(t_dw_ns, dtype=np.uint64)
+    dy = np.ascontiguousarray(t_dy_ns, dtype=np.uint64)
+    n = imp.size
+    mask = np.zeros(max(n, 1), dtype=np.uint8)
+    pred = C.c_uint64()
+    cnt = et_select_counts()
+    _lib.et_select_stats.restype = C.c_int
+    st = _lib.et_select_stats(C.c_int32(n), imp.ctypes.data_as(C.POINTER(C.c_double)), dw.ctypes.data_as(C.POINTER(C.c_uint64)),
+                              dy.ctypes.data_as(C.POINTER(C.c_uint64)), C.c_uint64(int(t_fwd_ns)), C.c_uint32(int(rho_ppm)),
+                              C.c_uint32(int(tq)), mask.ctypes.data_as(C.POINTER(C.c_uint8)), C.byref(pred), C.byref(cnt))
+    _check(st, "et_select_stats", allow=(ET_INFEASIBLE,))
+    return st, mask[:n].copy(), pred.value, {k: int(getattr(cnt, k)) for k, _ in et_select_counts._fields_}
 
 
 def et_train_step(ctx, x_dev, y_dev, mask, opt=None, want_loss=True):

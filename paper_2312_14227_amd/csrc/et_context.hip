@@ -718,39 +718,44 @@ namespace {
 // full backward pass, then one segmented reduction of g * (snapshot - w) over all tensors;
 // master: both are float32 (snapshot of, and current, master weights)
 int importance_impl(et_ctx* c, const void* x_dev, const int32_t* y_dev, void* const* snapshot_dev,
-                    double* importance_host, bool master) {
-  if (!c || !x_dev || !y_dev || !snapshot_dev || !importance_host) return ET_EINVAL;
+                    double* importance_host, bool master, int metric = 0) {
+  if (!c || !importance_host || metric < 0 || metric > 2) return ET_EINVAL;
+  if (metric != 1 && (!x_dev || !y_dev)) return ET_EINVAL;   // the weight magnitude needs no pass over data
+  if (metric == 0 && !snapshot_dev) return ET_EINVAL;
   if (!c->bound) return ET_ESTATE;
   if (master && !c->bf16_model) return ET_EINVAL;
   if (master && c->state.empty()) return ET_ESTATE;
   const size_t N = c->tensors.size();
   const bool bf16_w = c->bf16_model && !master;
   const size_t wsize = bf16_w ? sizeof(bf16) : sizeof(float);
-  for (size_t i = 0; i < N; i++)
-    if (!snapshot_dev[i] || (reinterpret_cast<uintptr_t>(snapshot_dev[i]) & 15)) return ET_EINVAL;
+  if (metric == 0)
+    for (size_t i = 0; i < N; i++)
+      if (!snapshot_dev[i] || (reinterpret_cast<uintptr_t>(snapshot_dev[i]) & 15)) return ET_EINVAL;
   std::vector<uint8_t> ones(N, 1);
   c->launches[0] = c->launches[1] = c->launches[2] = c->launches[3] = 0;
-  int rc = run_forward(c, x_dev, y_dev);
-  if (rc != ET_OK) return rc;
-  rc = run_backward(c, x_dev, ones.data());
-  if (rc != ET_OK) return rc;
+  if (metric != 1) {
+    int rc = run_forward(c, x_dev, y_dev);
+    if (rc != ET_OK) return rc;
+    rc = run_backward(c, x_dev, ones.data());
+    if (rc != ET_OK) return rc;
+  }
   const int k = c->state_slots;
   for (size_t i = 0; i < N; i++)
     for (uint32_t sg = c->seg_begin[i]; sg < c->seg_begin[i + 1]; sg++) {
       const size_t off = (size_t)(sg - c->seg_begin[i]) * SEG_ELEMS;
       et::TensorSeg& t = c->imp_segs_host[sg];
       t.w = master ? (const void*)(c->state[i * k] + off) : (const void*)((const unsigned char*)c->w[i] + off * wsize);
-      t.w_snap = (const unsigned char*)snapshot_dev[i] + off * wsize;
+      t.w_snap = metric == 0 ? (const unsigned char*)snapshot_dev[i] + off * wsize : t.w;
     }
   ET_HIP(hipMemcpyAsync(c->imp_segs_dev, c->imp_segs_host.data(), sizeof(et::TensorSeg) * c->n_segs,
                         hipMemcpyHostToDevice, c->stream));
   c->cur_phase = PH_DW;
   double imp_bytes = 0.0;
-  for (size_t i = 0; i < N; i++) imp_bytes += (double)c->tensors[i].numel * (4.0 + 2.0 * wsize);
+  for (size_t i = 0; i < N; i++) imp_bytes += (double)c->tensors[i].numel * (metric == 0 ? 4.0 + 2.0 * wsize : (metric == 1 ? (double)wsize : 4.0));
   {
     KernelTimer kt(c, 3, imp_bytes);
     ET_K(2, et::importance_reduce(c->imp_segs_dev, (int)c->n_segs, c->seg_begin_dev, (int)N, bf16_w, c->imp_partial_dev,
-                                  c->imp_out_dev, c->stream));
+                                  c->imp_out_dev, c->stream, metric));
   }
   ET_HIP(hipMemcpyAsync(importance_host, c->imp_out_dev, sizeof(double) * N, hipMemcpyDeviceToHost, c->stream));
   ET_HIP(hipStreamSynchronize(c->stream));
@@ -766,6 +771,11 @@ int et_importance(et_ctx* c, const void* x_dev, const int32_t* y_dev, void* cons
 int et_importance_master(et_ctx* c, const void* x_dev, const int32_t* y_dev, void* const* w_snapshot_f32_dev,
                          double* importance_host) {
   return importance_impl(c, x_dev, y_dev, w_snapshot_f32_dev, importance_host, true);
+}
+
+int et_tensor_metric(et_ctx* c, const void* x_dev, const int32_t* y_dev, int32_t metric, double* metric_host) {
+  if (metric != ET_METRIC_WEIGHT_L1 && metric != ET_METRIC_GRAD_L1) return ET_EINVAL;
+  return importance_impl(c, x_dev, y_dev, nullptr, metric_host, false, metric);
 }
 
 int et_profile(et_ctx* c, const void* x_dev, const int32_t* y_dev, int32_t warmup, int32_t reps, uint64_t* t_fwd_ns,

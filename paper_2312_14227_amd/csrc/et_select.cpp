@@ -8,6 +8,7 @@
 // and one knapsack table built from the output side serves every i*: O(N T_q).  Same optimum,
 // same tie order (larger summed importance, then the smallest mask read as a binary number with
 // tensor 0 as the most significant bit).
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <new>
@@ -37,10 +38,11 @@ uint64_t time_model(int32_t n, const uint8_t* mask, const uint64_t* t_dw, const 
 
 }  // namespace
 
-extern "C" int et_select(int32_t n, const double* importance, const uint64_t* t_dw_ns, const uint64_t* t_dy_ns,
-                         uint64_t t_fwd_ns, uint32_t rho_ppm, uint32_t tq, uint8_t* mask_out,
-                         uint64_t* predicted_ns) {
+static int select_core(int32_t n, const double* importance, const uint64_t* t_dw_ns, const uint64_t* t_dy_ns,
+                uint64_t t_fwd_ns, uint32_t rho_ppm, uint32_t tq, uint8_t* mask_out, uint64_t* predicted_ns,
+                et_select_counts* counts) {
   if (n <= 0 || !importance || !t_dw_ns || !t_dy_ns || !mask_out) return ET_EINVAL;
+  if (counts) *counts = et_select_counts{0, 0, 0, 0, 0};
   for (int32_t i = 0; i < n; i++) mask_out[i] = 0;
   if (predicted_ns) *predicted_ns = t_fwd_ns;
   // no single time may push the 64-bit sums over the edge
@@ -81,6 +83,20 @@ extern "C" int et_select(int32_t n, const double* importance, const uint64_t* t_
       b[i] = scale ? muldiv(t_dy_ns[i], tq, t_b) : t_dy_ns[i];
     }
     if (scale) budget = muldiv(budget, tq, t_b);
+    if (counts) {
+      // Section 6.3 on the paper's table (depth d = 1..N from the output, time 0..T): a cell is invalid
+      // above the budget and redundant below the time of merely reaching depth d
+      uint64_t tb_q = 0, reach = 0;
+      for (int32_t i = 0; i < n; i++) tb_q += a[i] + (i >= 1 ? b[i] : 0);
+      counts->budget_q = budget;
+      counts->backward_q = tb_q;
+      counts->cells_table = (uint64_t)n * (std::max(tb_q, budget) + 1);
+      counts->cells_knapsack = (uint64_t)n * (budget + 1);
+      for (int32_t i = n - 1; i >= 0; i--) {          // depth d = n - i
+        if (reach + a[i] <= budget) counts->cells_pruned += budget - reach + 1;
+        reach += b[i];
+      }
+    }
     if ((u128)(budget + 1) * (u128)(n + 1) > ((u128)1 << 31)) return ET_ENOMEM;  // choose a coarser tq
     const size_t W = (size_t)budget + 1;
 
@@ -138,4 +154,17 @@ extern "C" int et_select(int32_t n, const double* importance, const uint64_t* t_
   }
   if (predicted_ns) *predicted_ns = time_model(n, mask_out, t_dw_ns, t_dy_ns, t_fwd_ns);
   return ET_OK;
+}
+
+extern "C" int et_select(int32_t n, const double* importance, const uint64_t* t_dw_ns, const uint64_t* t_dy_ns,
+                         uint64_t t_fwd_ns, uint32_t rho_ppm, uint32_t tq, uint8_t* mask_out,
+                         uint64_t* predicted_ns) {
+  return select_core(n, importance, t_dw_ns, t_dy_ns, t_fwd_ns, rho_ppm, tq, mask_out, predicted_ns, nullptr);
+}
+
+extern "C" int et_select_stats(int32_t n, const double* importance, const uint64_t* t_dw_ns, const uint64_t* t_dy_ns,
+                               uint64_t t_fwd_ns, uint32_t rho_ppm, uint32_t tq, uint8_t* mask_out,
+                               uint64_t* predicted_ns, et_select_counts* counts) {
+  if (!counts) return ET_EINVAL;
+  return select_core(n, importance, t_dw_ns, t_dy_ns, t_fwd_ns, rho_ppm, tq, mask_out, predicted_ns, counts);
 }

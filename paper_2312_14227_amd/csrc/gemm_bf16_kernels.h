@@ -646,7 +646,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(Params g) {
 // extra before the loop, group 0 one extra after it.
 constexpr int PBK = 64;
 
-template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, int EPI>
+template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, int EPI, int LOADS_IN_C = 1>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   constexpr int NW = WGM * WGN;
   constexpr int TM = BM / WGM, TN = BN / WGN;
@@ -839,18 +839,26 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
     store_a(nxt);
     load_frags(cur, 0, a0, b0);
     load_frags(cur, 1, a1, b1);
+    if (LOADS_IN_C == 0) {
+      __builtin_amdgcn_sched_barrier(0);
+      load_a_regs(adv);
+    }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     block_barrier();
-    c_phase(std::integral_constant<int, A_LOADS>(), [&](int i) {
+    c_phase(std::integral_constant<int, LOADS_IN_C ? A_LOADS : 0>(), [&](int i) {
       ra[i] = *(const u32x4*)ga[i];
       ga[i] += adv ? a_step : 0;
     });
     store_b(nxt);
     load_frags(cur, 2, a0, b0);
     load_frags(cur, 3, a1, b1);
+    if (LOADS_IN_C == 0) {
+      __builtin_amdgcn_sched_barrier(0);
+      load_b_regs(adv);
+    }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     block_barrier();
-    c_phase(std::integral_constant<int, B_LOADS>(), [&](int i) {
+    c_phase(std::integral_constant<int, LOADS_IN_C ? B_LOADS : 0>(), [&](int i) {
       rb[i] = *(const u32x4*)gb[i];
       gb[i] += adv ? b_step : 0;
     });
@@ -869,6 +877,7 @@ LaunchFn dma_256x256(bool a_t, bool b_t, int epi);
 LaunchFn dma_256x128(bool a_t, bool b_t, int epi);
 LaunchFn pp_256x256(bool a_t, bool b_t, int epi);
 LaunchFn pp_256x192(bool a_t, bool b_t, int epi);
+LaunchFn pp_256x256_m(bool a_t, bool b_t, int epi);
 
 }  // namespace gemm
 }  // namespace et

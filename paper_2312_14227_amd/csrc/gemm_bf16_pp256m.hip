@@ -1,0 +1,27 @@
+// Instantiations of the bf16 GEMM kernels for one tile shape (see gemm_bf16_kernels.h).
+#include "gemm_bf16_kernels.h"
+
+namespace et {
+namespace gemm {
+namespace {
+
+template <bool AT, bool BT, int E>
+hipError_t launch(const Params& p, dim3 grid, hipStream_t s) {
+  hipLaunchKernelGGL((gemm_pp_kernel<256, 256, 2, 4, AT, BT, E, 0>), grid, dim3(512), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+LaunchFn pp_256x256_m(bool a_t, bool b_t, int epi) {
+#define ET_PICK(AT, BT, E) \
+  if (a_t == AT && b_t == BT && epi == E) return launch<AT, BT, E>;
+  ET_PICK(false, false, E_BF16)
+  ET_PICK(false, true, E_BF16)
+  ET_PICK(true, true, E_PARTIAL)
+#undef ET_PICK
+  return nullptr;
+}
+
+}  // namespace gemm
+}  // namespace et

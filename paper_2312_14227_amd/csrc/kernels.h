@@ -174,8 +174,9 @@ struct TensorSeg {       // one chunk of one tensor
   uint32_t tensor;       // tensor index
 };
 // stage 1: one block per segment -> partial[seg]; stage 2: per tensor, fixed-order sum -> double
+// metric 0: sum g (w_snap - w) (Eq. 2); 1: sum |w|; 2: sum |g| (w_snap is not read for 1 and 2)
 hipError_t importance_reduce(const TensorSeg* segs_dev, int n_segs, const uint32_t* seg_begin_dev, int n_tensors,
-                             bool bf16_weights, double* partial_dev, double* out_dev, hipStream_t s);
+                             bool bf16_weights, double* partial_dev, double* out_dev, hipStream_t s, int metric = 0);
 
 struct UpdateSeg {
   const float* g;

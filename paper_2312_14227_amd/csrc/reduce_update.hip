@@ -23,7 +23,14 @@ __device__ __forceinline__ double wave_sum_d(double v) {
   return v;
 }
 
-template <bool BF16W>
+// METRIC 0: Eq. 2, g * (w_snap - w);  1: |w| (weight magnitude);  2: |g| (gradient magnitude) -- the two
+// non-additive metrics of the ablation in Section 8 go through the same segmented reduction
+template <int METRIC>
+__device__ __forceinline__ float metric_term(float g, float w, float ws) {
+  return METRIC == 0 ? g * (ws - w) : (METRIC == 1 ? fabsf(w) : fabsf(g));
+}
+
+template <bool BF16W, int METRIC>
 __global__ __launch_bounds__(256) void importance_stage1(const TensorSeg* __restrict__ segs,
                                                          double* __restrict__ partial) {
   __shared__ double red[4];
@@ -38,26 +45,31 @@ __global__ __launch_bounds__(256) void importance_stage1(const TensorSeg* __rest
     const uint32_t n8 = vec ? n / 8 : 0;
     for (uint32_t i = threadIdx.x; i < n8; i += 256) {
       const float4 g0 = ((const float4*)g)[2 * i], g1 = ((const float4*)g)[2 * i + 1];
-      const bf16x8 wv = ((const bf16x8*)w)[i], sv = ((const bf16x8*)ws)[i];
-      a0 += g0.x * ((float)sv[0] - (float)wv[0]) + g0.y * ((float)sv[1] - (float)wv[1]);
-      a1 += g0.z * ((float)sv[2] - (float)wv[2]) + g0.w * ((float)sv[3] - (float)wv[3]);
-      a2 += g1.x * ((float)sv[4] - (float)wv[4]) + g1.y * ((float)sv[5] - (float)wv[5]);
-      a3 += g1.z * ((float)sv[6] - (float)wv[6]) + g1.w * ((float)sv[7] - (float)wv[7]);
+      const bf16x8 wv = ((const bf16x8*)w)[i];
+      bf16x8 sv = wv;
+      if (METRIC == 0) sv = ((const bf16x8*)ws)[i];
+      a0 += metric_term<METRIC>(g0.x, (float)wv[0], (float)sv[0]) + metric_term<METRIC>(g0.y, (float)wv[1], (float)sv[1]);
+      a1 += metric_term<METRIC>(g0.z, (float)wv[2], (float)sv[2]) + metric_term<METRIC>(g0.w, (float)wv[3], (float)sv[3]);
+      a2 += metric_term<METRIC>(g1.x, (float)wv[4], (float)sv[4]) + metric_term<METRIC>(g1.y, (float)wv[5], (float)sv[5]);
+      a3 += metric_term<METRIC>(g1.z, (float)wv[6], (float)sv[6]) + metric_term<METRIC>(g1.w, (float)wv[7], (float)sv[7]);
     }
-    for (uint32_t i = n8 * 8 + threadIdx.x; i < n; i += 256) a0 += g[i] * ((float)ws[i] - (float)w[i]);
+    for (uint32_t i = n8 * 8 + threadIdx.x; i < n; i += 256)
+      a0 += metric_term<METRIC>(g[i], (float)w[i], METRIC == 0 ? (float)ws[i] : 0.f);
   } else {
     const float* __restrict__ w = (const float*)sg.w;
     const float* __restrict__ ws = (const float*)sg.w_snap;
     const bool vec = (((uintptr_t)g | (uintptr_t)w | (uintptr_t)ws) & 15) == 0;
     const uint32_t n4 = vec ? n / 4 : 0;
     for (uint32_t i = threadIdx.x; i < n4; i += 256) {
-      const float4 gv = ((const float4*)g)[i], wv = ((const float4*)w)[i], sv = ((const float4*)ws)[i];
-      a0 += gv.x * (sv.x - wv.x);
-      a1 += gv.y * (sv.y - wv.y);
-      a2 += gv.z * (sv.z - wv.z);
-      a3 += gv.w * (sv.w - wv.w);
+      const float4 gv = ((const float4*)g)[i], wv = ((const float4*)w)[i];
+      float4 sv = wv;
+      if (METRIC == 0) sv = ((const float4*)ws)[i];
+      a0 += metric_term<METRIC>(gv.x, wv.x, sv.x);
+      a1 += metric_term<METRIC>(gv.y, wv.y, sv.y);
+      a2 += metric_term<METRIC>(gv.z, wv.z, sv.z);
+      a3 += metric_term<METRIC>(gv.w, wv.w, sv.w);
     }
-    for (uint32_t i = n4 * 4 + threadIdx.x; i < n; i += 256) a0 += g[i] * (ws[i] - w[i]);
+    for (uint32_t i = n4 * 4 + threadIdx.x; i < n; i += 256) a0 += metric_term<METRIC>(g[i], w[i], METRIC == 0 ? ws[i] : 0.f);
   }
   double s = wave_sum_d(((double)a0 + (double)a1) + ((double)a2 + (double)a3));
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
@@ -114,12 +126,15 @@ __global__ __launch_bounds__(256) void masked_update_kernel(const UpdateSeg* __r
 }  // namespace
 
 hipError_t importance_reduce(const TensorSeg* segs_dev, int n_segs, const uint32_t* seg_begin_dev, int n_tensors,
-                             bool bf16_weights, double* partial_dev, double* out_dev, hipStream_t s) {
-  if (n_segs <= 0 || n_tensors <= 0) return hipErrorInvalidValue;
-  if (bf16_weights)
-    hipLaunchKernelGGL((importance_stage1<true>), dim3(n_segs), dim3(256), 0, s, segs_dev, partial_dev);
-  else
-    hipLaunchKernelGGL((importance_stage1<false>), dim3(n_segs), dim3(256), 0, s, segs_dev, partial_dev);
+                             bool bf16_weights, double* partial_dev, double* out_dev, hipStream_t s, int metric) {
+  if (n_segs <= 0 || n_tensors <= 0 || metric < 0 || metric > 2) return hipErrorInvalidValue;
+#define ET_IMP(B, M) hipLaunchKernelGGL((importance_stage1<B, M>), dim3(n_segs), dim3(256), 0, s, segs_dev, partial_dev)
+  if (bf16_weights) {
+    if (metric == 0) ET_IMP(true, 0); else if (metric == 1) ET_IMP(true, 1); else ET_IMP(true, 2);
+  } else {
+    if (metric == 0) ET_IMP(false, 0); else if (metric == 1) ET_IMP(false, 1); else ET_IMP(false, 2);
+  }
+#undef ET_IMP
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(importance_stage2, dim3((n_tensors + 63) / 64), dim3(64), 0, s, partial_dev, seg_begin_dev,

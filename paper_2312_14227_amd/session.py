@@ -87,6 +87,11 @@ class Session:
         """snap_f32: list of float32 device tensors (earlier copies of the master weights)."""
         return et.et_importance_master(self.ctx, xt.data_ptr(), yt.data_ptr(), [s.data_ptr() for s in snap_f32])
 
+    def tensor_metric(self, xt, yt, metric):
+        """metric: et.ET_METRIC_WEIGHT_L1 (xt, yt may be None) or et.ET_METRIC_GRAD_L1."""
+        return et.et_tensor_metric(self.ctx, xt.data_ptr() if xt is not None else None,
+                                   yt.data_ptr() if yt is not None else None, metric, self.n)
+
     def profile(self, xt, yt, warmup=2, reps=5):
         return et.et_profile(self.ctx, xt.data_ptr(), yt.data_ptr(), warmup, reps)
 

@@ -5,6 +5,7 @@ import pytest
 
 from gpu_util import rel_l2, tol_for
 from oracle import importance as oimp
+from oracle import nets
 from oracle import optim as oopt
 from oracle import select as osel
 from synth import CONFIGS, make_workload
@@ -161,4 +162,29 @@ def test_importance_from_master_weights():
         s2 = _session(mlp, wl2)
         x2, y2 = s2.put_input(wl2.x, wl2.y)
         s2.importance_master(x2, y2, [w.clone() for w in s2.w])
+    s.close()
+
+
+def test_weight_and_gradient_magnitude_metrics():
+    """The ablation's two metrics through the same segmented reduction, against the oracle's L1 norms."""
+    from oracle import importance as oimp
+    from paper_2312_14227_amd import binding as et
+    cfg = CONFIGS["vit_small"]
+    wl = make_workload(cfg, seed=4, init="random")
+    N = len(wl.weights)
+    ref = nets.step(cfg, wl.weights, wl.x, wl.y, [1] * N)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    wm = s.tensor_metric(None, None, et.ET_METRIC_WEIGHT_L1)
+    want = oimp.weight_magnitude(wl.weights)
+    assert np.all(np.abs(wm - want) <= 1e-5 * want + 1e-30), np.abs(wm / want - 1).max()   # same values, fp32 terms
+    gm = s.tensor_metric(xt, yt, et.ET_METRIC_GRAD_L1)
+    want = oimp.grad_magnitude(ref["grads"])
+    assert np.all(np.abs(gm - want) <= tol_for(cfg) * want), np.abs(gm / want - 1).max()
+    # selection runs on them like on importances
+    t_fwd, t_dw, t_dy = s.profile(xt, yt, warmup=1, reps=3)
+    for metric in (wm, gm):
+        st, mask, pred = et.et_select(metric, t_dw, t_dy, t_fwd, 600_000, 1000)
+        want_sel = osel.select(metric, [int(t) for t in t_dw], [int(t) for t in t_dy], int(t_fwd), 600_000, 1000)
+        assert st == want_sel["status"] and list(mask) == list(want_sel["mask"])
     s.close()

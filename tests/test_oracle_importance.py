@@ -64,3 +64,13 @@ def test_additivity_over_a_split_tensor():
     assert abs(whole - parts.sum()) <= 1e-12 * imp.abs_importance_from_grads([g], [w], [s])[0]
     perm = rng.permutation(1000)
     assert abs(whole - imp.importance_from_grads([g[perm]], [w[perm]], [s[perm]])[0]) <= 1e-11
+
+
+def test_magnitude_metrics_are_l1_norms():
+    rng = np.random.default_rng(5)
+    tensors = [rng.standard_normal((7, 5)), rng.standard_normal(11) * 3.0, np.zeros(4)]
+    want = [np.linalg.norm(t.ravel(), 1) for t in tensors]
+    assert np.allclose(imp.weight_magnitude(tensors), want, rtol=1e-14, atol=0)
+    assert np.allclose(imp.grad_magnitude(tensors), want, rtol=1e-14, atol=0)
+    # not additive in the sense of Section 4: the sign of an update does not matter to them
+    assert np.array_equal(imp.weight_magnitude([-t for t in tensors]), imp.weight_magnitude(tensors))

@@ -76,3 +76,27 @@ def test_error_paths():
     assert st == et.ET_OK and not mask.any()
     st, mask, _ = et.et_select([1.0, 2.0], [0, 0], [0, 0], 0, 500_000, 1000)
     assert st == et.ET_OK and list(mask) == [1, 1]
+
+
+@pytest.mark.parametrize("N,Tq", [(12, 50), (40, 500), (152, 1000)])
+def test_table_sizes_match_the_cells_the_recurrence_visits(N, Tq):
+    """et_select_stats: same mask as et_select, and the cell counts of Section 6.3 equal what the oracle's
+    recurrence actually evaluates with and without pruning."""
+    rng = np.random.default_rng(7 * N + Tq)
+    imp, t_dw, t_dy, t_fwd = _profile_like(rng, N, 1000)
+    for rho in (350_000, 500_000, 800_000):
+        pruned = osel.select_recurrence(imp, t_dw, t_dy, t_fwd, rho, Tq, prune=True)
+        full = osel.select_recurrence(imp, t_dw, t_dy, t_fwd, rho, Tq, prune=False)
+        st, mask, pred, cnt = et.et_select_stats(imp, t_dw, t_dy, t_fwd, rho, Tq)
+        st2, mask2, pred2 = et.et_select(imp, t_dw, t_dy, t_fwd, rho, Tq)
+        assert (st, list(mask), pred) == (st2, list(mask2), pred2)
+        assert list(mask) == list(pruned["mask"]) == list(full["mask"])
+        if st != et.ET_OK:
+            assert all(v == 0 for v in cnt.values())
+            continue
+        a, b, budget = osel.quantise_times(t_fwd, t_dw, t_dy, rho, Tq)
+        assert cnt["budget_q"] == budget and cnt["backward_q"] == sum(a) + sum(b[1:])
+        assert cnt["cells_pruned"] == pruned["cells"]
+        assert cnt["cells_table"] == full["cells"]
+        assert cnt["cells_knapsack"] == N * (budget + 1)
+        assert cnt["cells_pruned"] <= cnt["cells_knapsack"] <= cnt["cells_table"]
