@@ -18,7 +18,7 @@ __global__ void splitk_reduce_kernel(const float4* __restrict__ part, float4* __
   out[i] = s;
 }
 
-enum TileId : int { T_AUTO = 0, T_128x128 = 1, T_128x64 = 3, T_DMA_256x256 = 5, T_DMA_256x128 = 7, T_PP_256x256 = 11, T_PP_256x192 = 13, T_PP_256x256_M = 15 };
+enum TileId : int { T_AUTO = 0, T_128x128 = 1, T_128x64 = 3, T_DMA_256x256 = 5, T_DMA_256x128 = 7, T_PP_256x256 = 11, T_PP_256x192 = 13 };
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -51,7 +51,7 @@ Plan plan_large(int M, int N, int K, bool may_split) {
 int choose_tile(const GemmDesc& d, int k_per_block) {
   const bool dma_ok = (d.K % gemm::DBK) == 0 && (k_per_block % gemm::DBK) == 0;
   const bool pp_ok = (d.K % gemm::PBK) == 0 && (k_per_block % gemm::PBK) == 0;
-  if (d.tile == T_PP_256x256 || d.tile == T_PP_256x192 || d.tile == T_PP_256x256_M) return pp_ok ? d.tile : (dma_ok ? T_DMA_256x256 : T_128x128);
+  if (d.tile == T_PP_256x256 || d.tile == T_PP_256x192) return pp_ok ? d.tile : (dma_ok ? T_DMA_256x256 : T_128x128);
   if (d.tile == T_DMA_256x256 || d.tile == T_DMA_256x128) return dma_ok ? d.tile : T_128x128;
   if (d.tile != T_AUTO) return d.tile;
   if (d.N <= 64) return T_128x64;
@@ -149,7 +149,6 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
     case T_DMA_256x256: BM = 256; BN = 256; fn = gemm::dma_256x256(d.a_t, d.b_t, epi); break;
     case T_DMA_256x128: BM = 256; BN = 128; fn = gemm::dma_256x128(d.a_t, d.b_t, epi); break;
     case T_PP_256x192: BM = 256; BN = 192; fn = gemm::pp_256x192(d.a_t, d.b_t, epi); break;
-    case T_PP_256x256_M: BM = 256; BN = 256; fn = gemm::pp_256x256_m(d.a_t, d.b_t, epi); break;
     case T_PP_256x256: BM = 256; BN = 256; fn = gemm::pp_256x256(d.a_t, d.b_t, epi); break;
     default: BM = 128; BN = 128; fn = gemm::staged_128x128(d.a_t, d.b_t, epi); break;
   }

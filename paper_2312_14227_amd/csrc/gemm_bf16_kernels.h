@@ -646,7 +646,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(Params g) {
 // extra before the loop, group 0 one extra after it.
 constexpr int PBK = 64;
 
-template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, int EPI, int LOADS_IN_C = 1>
+template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, int EPI>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   constexpr int NW = WGM * WGN;
   constexpr int TM = BM / WGM, TN = BN / WGN;
@@ -808,60 +808,57 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   // evenly between them, so that the loads of the four SIMDs reach
   // the texture addresser evenly instead of in a burst that would stall the issuing waves
   constexpr int P = MI * NI * 2;   // MFMAs of one C phase
-  auto c_phase = [&](auto loads_tag, auto&& load_one) {
-    constexpr int L = decltype(loads_tag)::value;
-    __builtin_amdgcn_s_setprio(1);
-    int n = 0;
+  // load j is issued in the middle of its share of the phase's MFMAs (staggering the four SIMDs
+  // against each other as well was measured and is slower)
+  {
+    constexpr int S = 2;
+    auto c_phase = [&](auto loads_tag, auto&& load_one) {
+      constexpr int L = decltype(loads_tag)::value;
+      __builtin_amdgcn_s_setprio(1);
+      int n = 0;
 #pragma unroll
-    for (int half = 0; half < 2; half++)
+      for (int half = 0; half < 2; half++)
 #pragma unroll
-      for (int mi = 0; mi < MI; mi++)
+        for (int mi = 0; mi < MI; mi++)
 #pragma unroll
-        for (int ni = 0; ni < NI; ni++) {
-          acc[mi][ni] = half == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mi], b0[ni], acc[mi][ni], 0, 0, 0)
-                                  : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[mi], b1[ni], acc[mi][ni], 0, 0, 0);
-          n++;
+          for (int ni = 0; ni < NI; ni++) {
+            acc[mi][ni] = half == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mi], b0[ni], acc[mi][ni], 0, 0, 0)
+                                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[mi], b1[ni], acc[mi][ni], 0, 0, 0);
+            n++;
 #pragma unroll
-          for (int j = 0; j < L; j++)
-            if (n == ((2 * j + 1) * P) / (2 * L)) {   // load j goes in the middle of its share of the MFMAs
-              __builtin_amdgcn_sched_barrier(0);
-              load_one(j);
-              __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-    __builtin_amdgcn_s_setprio(0);
-    block_barrier();
-  };
-  for (int kt = 0; kt < nk; kt++) {
-    unsigned char* cur = smem + (kt & 1) * STAGE;
-    unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
-    const bool adv = kt + 3 < nk;   // the registers are reloaded with slice min(kt + 2, nk - 1)
-    store_a(nxt);
-    load_frags(cur, 0, a0, b0);
-    load_frags(cur, 1, a1, b1);
-    if (LOADS_IN_C == 0) {
-      __builtin_amdgcn_sched_barrier(0);
-      load_a_regs(adv);
+            for (int j = 0; j < L; j++)
+              if (n == 1 + (4 * j * P + S * P) / (4 * L)) {
+                __builtin_amdgcn_sched_barrier(0);
+                load_one(j);
+                __builtin_amdgcn_sched_barrier(0);
+              }
+          }
+      __builtin_amdgcn_s_setprio(0);
+      block_barrier();
+    };
+    for (int kt = 0; kt < nk; kt++) {
+      unsigned char* cur = smem + (kt & 1) * STAGE;
+      unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
+      const bool adv = kt + 3 < nk;   // the registers are reloaded with slice min(kt + 2, nk - 1)
+      store_a(nxt);
+      load_frags(cur, 0, a0, b0);
+      load_frags(cur, 1, a1, b1);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      block_barrier();
+      c_phase(std::integral_constant<int, A_LOADS>(), [&](int i) {
+        ra[i] = *(const u32x4*)ga[i];
+        ga[i] += adv ? a_step : 0;
+      });
+      store_b(nxt);
+      load_frags(cur, 2, a0, b0);
+      load_frags(cur, 3, a1, b1);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      block_barrier();
+      c_phase(std::integral_constant<int, B_LOADS>(), [&](int i) {
+        rb[i] = *(const u32x4*)gb[i];
+        gb[i] += adv ? b_step : 0;
+      });
     }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    block_barrier();
-    c_phase(std::integral_constant<int, LOADS_IN_C ? A_LOADS : 0>(), [&](int i) {
-      ra[i] = *(const u32x4*)ga[i];
-      ga[i] += adv ? a_step : 0;
-    });
-    store_b(nxt);
-    load_frags(cur, 2, a0, b0);
-    load_frags(cur, 3, a1, b1);
-    if (LOADS_IN_C == 0) {
-      __builtin_amdgcn_sched_barrier(0);
-      load_b_regs(adv);
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    block_barrier();
-    c_phase(std::integral_constant<int, LOADS_IN_C ? B_LOADS : 0>(), [&](int i) {
-      rb[i] = *(const u32x4*)gb[i];
-      gb[i] += adv ? b_step : 0;
-    });
   }
   if (group == 0) block_barrier();
   if (g.no_store & 7) return;
@@ -877,7 +874,6 @@ LaunchFn dma_256x256(bool a_t, bool b_t, int epi);
 LaunchFn dma_256x128(bool a_t, bool b_t, int epi);
 LaunchFn pp_256x256(bool a_t, bool b_t, int epi);
 LaunchFn pp_256x192(bool a_t, bool b_t, int epi);
-LaunchFn pp_256x256_m(bool a_t, bool b_t, int epi);
 
 }  // namespace gemm
 }  // namespace et
