@@ -30,7 +30,7 @@ int build_mlp(et_ctx* c) {
   for (int i = 1; i < d.n_layers; i++) reserve(c, &c->act[i], sizeof(float) * B * d.dims[i]);
   reserve(c, &c->logits, sizeof(float) * B * C);
   reserve(c, &c->dlogits, sizeof(float) * B * C);
-  reserve(c, &c->loss, 256);
+  reserve(c, &c->loss, 256 + sizeof(float) * (size_t)d.batch);
   reserve(c, &c->dbuf[0], sizeof(float) * B * maxdim);
   reserve(c, &c->dbuf[1], sizeof(float) * B * maxdim);
   return ET_OK;
@@ -81,7 +81,7 @@ int build_vit(et_ctx* c) {
   reserve(c, &c->logits, f32 * B * C);
   reserve(c, &c->dlogits, f32 * B * C);
   reserve(c, &c->dl16, b16 * B * C8);
-  reserve(c, &c->loss, 256);
+  reserve(c, &c->loss, 256 + sizeof(float) * (size_t)d.batch);
   reserve(c, &c->dz, b16 * B * D);
   reserve(c, &c->dh, f32 * M * D);
   reserve(c, &c->dh16, b16 * M * D);
@@ -133,7 +133,7 @@ int mlp_forward(et_ctx* c, const void* x, const int32_t* y) {
     g.relu_out = i + 1 < L;
     ET_K(1, et::gemm_f32(g, c->stream));
   }
-  ET_K(1, et::xent(c->logits, y, B, d.dims[L], c->loss, c->dlogits, nullptr, d.dims[L], c->stream));
+  ET_K(2, et::xent(c->logits, y, B, d.dims[L], c->loss, c->dlogits, nullptr, d.dims[L], c->stream));
   return ET_OK;
 }
 
@@ -258,7 +258,7 @@ int vit_forward(et_ctx* c, const void* x, const int32_t* y) {
     g.C = c->logits; g.c_f32 = true;
     ET_G(g);
   }
-  ET_K(1, et::xent(c->logits, y, v.B, v.C, c->loss, c->dlogits, c->dl16, v.C8, c->stream));
+  ET_K(2, et::xent(c->logits, y, v.B, v.C, c->loss, c->dlogits, c->dl16, v.C8, c->stream));
   return ET_OK;
 }
 

@@ -62,7 +62,8 @@ int choose_tile(const GemmDesc& d, int k_per_block) {
     // the GELU epilogues (two outputs or an extra operand, transcendental math) take as long as a
     // short main loop; two 256x128 workgroups per CU overlap one's epilogue with the other's MFMAs
     // (measured in the ViT-B step: 121 us against 132 us with the two-group tile)
-    if (d.mode != EPI_PLAIN && dma_ok && d.N >= 2560 && k_per_block >= 4 * gemm::DBK) return T_DMA_256x128;
+    if ((d.mode == EPI_GELU_FWD || d.mode == EPI_GELU_BWD) && dma_ok && d.N >= 2560 && k_per_block >= 4 * gemm::DBK)
+      return T_DMA_256x128;
     if (pp_ok && k_per_block >= 4 * gemm::PBK) return plan_large(d.M, d.N, k_per_block, false).tile;
     if (dma_ok && k_per_block >= 4 * gemm::DBK) return d.N >= 2560 ? T_DMA_256x128 : T_DMA_256x256;
   }
@@ -107,7 +108,7 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   p.z_inner = d.z_inner;
   p.sAo = d.sAo; p.sAi = d.sAi; p.sBo = d.sBo; p.sBi = d.sBi; p.sCo = d.sCo; p.sCi = d.sCi;
   p.split_k = 1; p.k_chunk = 0;
-  p.alpha = d.alpha; p.bias = d.bias; p.residual = d.residual; p.ldr = d.ldr;
+  p.alpha = d.alpha; p.bias = d.bias; p.gain = d.gain; p.residual = d.residual; p.ldr = d.ldr;
   p.C = d.C; p.ldc = d.ldc; p.C2 = d.C2; p.U = d.U; p.no_store = d.no_store;
   int zdim = d.z_outer * d.z_inner;
   int epi;
@@ -132,6 +133,9 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
     if (d.mode == EPI_GELU_FWD) {
       if (!d.C2 || d.c_f32 || d.residual || !aligned(d.C2, 8)) return hipErrorInvalidValue;
       epi = gemm::E_GELU_FWD;
+    } else if (d.mode == EPI_AFFINE_RELU) {
+      if (!d.C2 || !d.gain || !d.bias || d.c_f32 || d.residual || d.a_t || d.b_t || !aligned(d.C2, 8)) return hipErrorInvalidValue;
+      epi = gemm::E_AFFINE;
     } else if (d.mode == EPI_GELU_BWD) {
       if (!d.U || d.c_f32 || d.residual || d.bias || !aligned(d.U, 8)) return hipErrorInvalidValue;
       epi = gemm::E_GELU_BWD;

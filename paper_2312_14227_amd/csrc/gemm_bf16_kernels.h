@@ -55,6 +55,7 @@ enum Epi : int {
   E_GELU_FWD = 3,   // with u = v + bias: C bf16 = gelu'(u) (kept for the backward pass), C2 bf16 = gelu(u)
   E_GELU_BWD = 4,   // C bf16 = v * U, U = the stored gelu'(u)
   E_PARTIAL = 5,    // split-K partial: C fp32 [z][M][N] = v
+  E_AFFINE = 6,     // C bf16 = z = v, C2 bf16 = max(z * gain[j] + bias[j], 0) with z as rounded to bf16
 };
 
 struct Params {
@@ -67,6 +68,7 @@ struct Params {
   int split_k, k_chunk;  // split_k > 1: blockIdx.z picks [z*k_chunk, (z+1)*k_chunk)
   float alpha;
   const bf16* bias;
+  const bf16* gain;      // E_AFFINE: per output column
   const float* residual;
   int ldr;
   void* C;
@@ -153,6 +155,10 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
   const bool col_any = col < g.N && rsub < RPI, col_full = col + 3 < g.N;
   const int ld = EPI == E_PARTIAL ? g.N : g.ldc;
   float bias[4] = {0.f, 0.f, 0.f, 0.f};
+  float gain[4] = {1.f, 1.f, 1.f, 1.f};
+  if (EPI == E_AFFINE && col_any) {
+    for (int j = 0; j < 4 && col + j < g.N; j++) gain[j] = (float)g.gain[col + j];
+  }
   if (EPI != E_PARTIAL && EPI != E_GELU_BWD && g.bias && col_any) {
     if (col_full) {
       const bf16x4 b = *(const bf16x4*)(g.bias + col);
@@ -177,7 +183,10 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
       if (row >= g.M || !col_any) continue;
       float v[4] = {raw.x, raw.y, raw.z, raw.w};
       const long long ci = c_off + (long long)row * ld + col;
-      if (EPI != E_PARTIAL) {
+      if (EPI == E_AFFINE) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) v[j] *= g.alpha;
+      } else if (EPI != E_PARTIAL) {
 #pragma unroll
         for (int j = 0; j < 4; j++) v[j] = v[j] * g.alpha + bias[j];
       }
@@ -204,6 +213,15 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
           }
           *(bf16x4*)((bf16*)g.C + ci) = o;
           *(bf16x4*)(g.C2 + ci) = o2;
+        } else if (EPI == E_AFFINE) {
+          bf16x4 o, o2;
+#pragma unroll
+          for (int j = 0; j < 4; j++) {
+            o[j] = (bf16)v[j];
+            o2[j] = (bf16)fmaxf((float)o[j] * gain[j] + bias[j], 0.f);
+          }
+          *(bf16x4*)((bf16*)g.C + ci) = o;
+          *(bf16x4*)(g.C2 + ci) = o2;
         } else {
           bf16x4 o;
 #pragma unroll
@@ -222,6 +240,10 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
             gelu_both(x, gv, dgv);
             ((bf16*)g.C)[ci + j] = (bf16)dgv;
             g.C2[ci + j] = (bf16)gv;
+          } else if (EPI == E_AFFINE) {
+            const bf16 z = (bf16)x;
+            ((bf16*)g.C)[ci + j] = z;
+            g.C2[ci + j] = (bf16)fmaxf((float)z * gain[j] + bias[j], 0.f);
           } else {
             ((bf16*)g.C)[ci + j] = (bf16)x;
           }

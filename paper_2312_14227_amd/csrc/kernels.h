@@ -23,6 +23,7 @@ enum EpiMode : int {
   EPI_PLAIN = 0,     // C = v
   EPI_GELU_FWD = 1,  // C = gelu'(v) (bf16, kept for the backward pass), C2 = gelu(v) (bf16)
   EPI_GELU_BWD = 2,  // C = v * U, U = the stored gelu'(u)
+  EPI_AFFINE_RELU = 3,  // C = z = v (bf16), C2 = max(z * gain[j] + bias[j], 0) (bf16), z as rounded to bf16
 };
 
 struct GemmDesc {
@@ -41,6 +42,7 @@ struct GemmDesc {
   // epilogue: v = alpha * acc + bias[j] + residual[i][j]
   float alpha = 1.f;
   const bf16* bias = nullptr;      // per output column
+  const bf16* gain = nullptr;      // EPI_AFFINE_RELU, per output column
   const float* residual = nullptr; // fp32 [M][ldr]
   int ldr = 0;
   int mode = EPI_PLAIN;
@@ -112,7 +114,8 @@ hipError_t attention_fwd(const bf16* qkv, bf16* out, float* lse, int B, int T, i
 hipError_t attention_bwd(const bf16* qkv, const bf16* dout, const float* lse, bf16* dqkv, int B, int T, int H,
                          int head_dim, float scale, hipStream_t s);
 
-// mean softmax cross-entropy: loss (1 float), dlogits fp32 and (if not null) a bf16 copy [B][ld16], zero padded
+// mean softmax cross-entropy: dlogits fp32 and (if not null) a bf16 copy [B][ld16], zero padded; `loss` points to
+// 64 + B floats: the loss in element 0, the per-row terms from element 64 on (two launches)
 hipError_t xent(const float* logits, const int32_t* y, int B, int C, float* loss, float* dlogits, bf16* dlogits_bf16,
                 int ld16, hipStream_t s);
 

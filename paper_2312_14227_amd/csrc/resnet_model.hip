@@ -43,8 +43,9 @@ void init_unit(ConvUnit& u, int t, int H, int W, int Cin, int Cout, int k, int s
 inline size_t rows_of(const et_ctx* c, const ConvUnit& u) { return (size_t)c->desc.batch * u.Ho * u.Wo; }
 inline bool needs_cols(const ConvUnit& u) { return u.k > 1 || u.stride > 1; }
 
-// z = cols(in) * Wm^T
-int conv_forward(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16* Wm, void* z, bool z_f32) {
+// z = cols(in) * Wm^T; with gain/shift the GEMM epilogue also writes y = max(z * gain + shift, 0)
+int conv_forward(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16* Wm, void* z, bool z_f32,
+                 const bf16* gain = nullptr, const bf16* shift = nullptr, bf16* y = nullptr) {
   const bf16* A = in;
   if (needs_cols(u)) {
     ET_KB(1, 2.0 * ((double)c->desc.batch * u.H * u.W * u.Cin + (double)rows_of(c, u) * u.Kc),
@@ -53,6 +54,9 @@ int conv_forward(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16* Wm, v
   }
   et::GemmDesc g = linear_fwd(A, Wm, nullptr, (int)rows_of(c, u), u.Cout, u.Kc);
   g.C = z; g.c_f32 = z_f32;
+  if (gain) {
+    g.mode = et::EPI_AFFINE_RELU; g.gain = gain; g.bias = shift; g.C2 = y;
+  }
   ET_G(g);
   return ET_OK;
 }
@@ -165,7 +169,7 @@ int build_resnet(et_ctx* c) {
   reserve(c, &c->logits, f32 * B * C);
   reserve(c, &c->dlogits, f32 * B * C);
   reserve(c, &c->dl16, b16 * B * C8);
-  reserve(c, &c->loss, 256);
+  reserve(c, &c->loss, 256 + sizeof(float) * (size_t)d.batch);
   reserve(c, &c->dz, b16 * B * Cf);
   max_cs = std::max(max_cs, et::colsum_partial_elems((int)B, C));
   pe = std::max(pe, et::gemm_bf16_partial_elems(C, Cf, split_for(C, Cf, (int)B)));
@@ -203,16 +207,11 @@ int resnet_forward(et_ctx* c, const void* x, const int32_t* y) {
   for (ResBlockBufs& b : c->rblk) {
     const int t = b.t;
     b.x = h;
-    int rc = conv_forward(c, b.c1, h, Wt(t), b.c1.z, false);
+    // c1, c2: the affine + ReLU is the epilogue of the convolution's GEMM (z is kept for the gain's gradient)
+    int rc = conv_forward(c, b.c1, h, Wt(t), b.c1.z, false, Wt(t + 1), Wt(t + 2), b.c1.y);
     if (rc != ET_OK) return rc;
-    ET_KB(1, 4.0 * rows_of(c, b.c1) * b.c1.Cout,
-          et::affine_act(b.c1.z, nullptr, Wt(t + 1), Wt(t + 2), nullptr, nullptr, nullptr, true, b.c1.y,
-                         (long long)rows_of(c, b.c1), b.c1.Cout, s));
-    rc = conv_forward(c, b.c2, b.c1.y, Wt(t + 3), b.c2.z, false);
+    rc = conv_forward(c, b.c2, b.c1.y, Wt(t + 3), b.c2.z, false, Wt(t + 4), Wt(t + 5), b.c2.y);
     if (rc != ET_OK) return rc;
-    ET_KB(1, 4.0 * rows_of(c, b.c2) * b.c2.Cout,
-          et::affine_act(b.c2.z, nullptr, Wt(t + 4), Wt(t + 5), nullptr, nullptr, nullptr, true, b.c2.y,
-                         (long long)rows_of(c, b.c2), b.c2.Cout, s));
     rc = conv_forward(c, b.c3, b.c2.y, Wt(t + 6), b.c3.z, false);
     if (rc != ET_OK) return rc;
     if (b.proj) {
@@ -236,7 +235,7 @@ int resnet_forward(et_ctx* c, const void* x, const int32_t* y) {
     g.C = c->logits; g.c_f32 = true;
     ET_G(g);
   }
-  ET_K(1, et::xent(c->logits, y, B, d.classes, c->loss, c->dlogits, c->dl16, round8(d.classes), s));
+  ET_K(2, et::xent(c->logits, y, B, d.classes, c->loss, c->dlogits, c->dl16, round8(d.classes), s));
   return ET_OK;
 }
 

@@ -282,38 +282,40 @@ __global__ __launch_bounds__(256) void softmax_bwd_rows_kernel(const float* __re
 }
 
 // ---------------------------------------------------------------------------------------------
-// mean softmax cross-entropy and its gradient; one block, waves take rows in turn
+// mean softmax cross-entropy and its gradient: one wave per row (4 rows per block) writes the
+// gradient and the row's loss term; a second one-wave kernel adds the terms in ascending order
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void xent_kernel(const float* __restrict__ logits, const int32_t* __restrict__ y,
-                                                   int B, int C, float* __restrict__ loss, float* __restrict__ dl,
-                                                   bf16* __restrict__ dl16, int ld16) {
-  __shared__ float wsum[4];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  float acc = 0.f;  // meaningful in lane 0
+__global__ __launch_bounds__(256) void xent_rows_kernel(const float* __restrict__ logits, const int32_t* __restrict__ y,
+                                                        int B, int C, float* __restrict__ row_loss,
+                                                        float* __restrict__ dl, bf16* __restrict__ dl16, int ld16) {
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (r >= B) return;
   const float invB = 1.f / (float)B;
-  for (int r = wave; r < B; r += 4) {
-    const float* x = logits + (long long)r * C;
-    float mx = -INFINITY;
-    for (int i = lane; i < C; i += WAVE) mx = fmaxf(mx, x[i]);
-    mx = wave_max(mx);
-    float sum = 0.f;
-    for (int i = lane; i < C; i += WAVE) sum += expf(x[i] - mx);
-    sum = wave_sum(sum);
-    const float lse = logf(sum) + mx;
-    const int label = y[r];
-    acc += lse - x[label];
-    for (int i = lane; i < ld16; i += WAVE) {
-      float gval = 0.f;
-      if (i < C) {
-        gval = (expf(x[i] - lse) - (i == label ? 1.f : 0.f)) * invB;
-        dl[(long long)r * C + i] = gval;
-      }
-      if (dl16) dl16[(long long)r * ld16 + i] = (bf16)gval;
+  const float* x = logits + (long long)r * C;
+  float mx = -INFINITY;
+  for (int i = lane; i < C; i += WAVE) mx = fmaxf(mx, x[i]);
+  mx = wave_max(mx);
+  float sum = 0.f;
+  for (int i = lane; i < C; i += WAVE) sum += expf(x[i] - mx);
+  sum = wave_sum(sum);
+  const float lse = logf(sum) + mx;
+  const int label = y[r];
+  if (lane == 0) row_loss[r] = lse - x[label];
+  for (int i = lane; i < ld16; i += WAVE) {
+    float gval = 0.f;
+    if (i < C) {
+      gval = (expf(x[i] - lse) - (i == label ? 1.f : 0.f)) * invB;
+      dl[(long long)r * C + i] = gval;
     }
+    if (dl16) dl16[(long long)r * ld16 + i] = (bf16)gval;
   }
-  if (lane == 0) wsum[wave] = acc;
-  __syncthreads();
-  if (threadIdx.x == 0) *loss = ((wsum[0] + wsum[1]) + (wsum[2] + wsum[3])) * invB;
+}
+
+__global__ __launch_bounds__(64) void xent_loss_kernel(const float* __restrict__ row_loss, int B, float* __restrict__ loss) {
+  if (threadIdx.x != 0) return;
+  float acc = 0.f;
+  for (int r = 0; r < B; r++) acc += row_loss[r];
+  *loss = acc / (float)B;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -459,7 +461,12 @@ hipError_t softmax_bwd_rows(const float* dp, const bf16* p, bf16* ds, float scal
 hipError_t xent(const float* logits, const int32_t* y, int B, int C, float* loss, float* dlogits, bf16* dlogits_bf16,
                 int ld16, hipStream_t s) {
   if (B <= 0 || C <= 0 || ld16 < C) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(xent_kernel, dim3(1), dim3(256), 0, s, logits, y, B, C, loss, dlogits, dlogits_bf16, ld16);
+  float* row_loss = loss + 64;
+  hipLaunchKernelGGL(xent_rows_kernel, dim3((B + 3) / 4), dim3(256), 0, s, logits, y, B, C, row_loss, dlogits,
+                     dlogits_bf16, ld16);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(xent_loss_kernel, dim3(1), dim3(64), 0, s, row_loss, B, loss);
   return hipGetLastError();
 }
 

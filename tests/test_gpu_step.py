@@ -47,7 +47,7 @@ def test_mlp_all_16_masks():
         _check_step(s, cfg, wl, xt, yt, np.array(mask, dtype=np.uint8), ref, tol_for(cfg))
         fwd, bwd, upd = s.launch_counts()
         sel = [j for j in range(4) if mask[j]]
-        assert fwd == 5 and upd == 0
+        assert fwd == 6 and upd == 0      # 4 GEMMs + the two cross-entropy launches
         assert bwd == (len(sel) + (3 - sel[0]) if sel else 0)      # dw per selected + dy after the first selected
     s.close()
 
