@@ -108,7 +108,7 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   p.z_inner = d.z_inner;
   p.sAo = d.sAo; p.sAi = d.sAi; p.sBo = d.sBo; p.sBi = d.sBi; p.sCo = d.sCo; p.sCi = d.sCi;
   p.split_k = 1; p.k_chunk = 0;
-  p.alpha = d.alpha; p.bias = d.bias; p.gain = d.gain; p.residual = d.residual; p.ldr = d.ldr;
+  p.alpha = d.alpha; p.bias = d.bias; p.gain = d.gain; p.gain2 = d.gain2; p.bias2 = d.bias2; p.residual = d.residual; p.ldr = d.ldr;
   p.C = d.C; p.ldc = d.ldc; p.C2 = d.C2; p.U = d.U; p.no_store = d.no_store;
   int zdim = d.z_outer * d.z_inner;
   int epi;
@@ -136,6 +136,11 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
     } else if (d.mode == EPI_AFFINE_RELU) {
       if (!d.C2 || !d.gain || !d.bias || d.c_f32 || d.residual || d.a_t || d.b_t || !aligned(d.C2, 8)) return hipErrorInvalidValue;
       epi = gemm::E_AFFINE;
+    } else if (d.mode == EPI_AFFINE_ADD_RELU) {
+      if (!d.C2 || !d.gain || !d.bias || !d.U || (d.gain2 && !d.bias2) || d.c_f32 || d.residual || d.a_t || d.b_t ||
+          !aligned(d.C2, 8) || !aligned(d.U, 8))
+        return hipErrorInvalidValue;
+      epi = gemm::E_AFFINE_ADD;
     } else if (d.mode == EPI_GELU_BWD) {
       if (!d.U || d.c_f32 || d.residual || d.bias || !aligned(d.U, 8)) return hipErrorInvalidValue;
       epi = gemm::E_GELU_BWD;

@@ -56,6 +56,7 @@ enum Epi : int {
   E_GELU_BWD = 4,   // C bf16 = v * U, U = the stored gelu'(u)
   E_PARTIAL = 5,    // split-K partial: C fp32 [z][M][N] = v
   E_AFFINE = 6,     // C bf16 = z = v, C2 bf16 = max(z * gain[j] + bias[j], 0) with z as rounded to bf16
+  E_AFFINE_ADD = 7, // as E_AFFINE with a second branch inside the ReLU: + U * gain2[j] + bias2[j] (or + U if gain2 is null)
 };
 
 struct Params {
@@ -68,7 +69,9 @@ struct Params {
   int split_k, k_chunk;  // split_k > 1: blockIdx.z picks [z*k_chunk, (z+1)*k_chunk)
   float alpha;
   const bf16* bias;
-  const bf16* gain;      // E_AFFINE: per output column
+  const bf16* gain;      // E_AFFINE, E_AFFINE_ADD: per output column
+  const bf16* gain2;     // E_AFFINE_ADD (nullable), with bias2
+  const bf16* bias2;
   const float* residual;
   int ldr;
   void* C;
@@ -156,8 +159,14 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
   const int ld = EPI == E_PARTIAL ? g.N : g.ldc;
   float bias[4] = {0.f, 0.f, 0.f, 0.f};
   float gain[4] = {1.f, 1.f, 1.f, 1.f};
-  if (EPI == E_AFFINE && col_any) {
+  float gain2[4] = {1.f, 1.f, 1.f, 1.f}, bias2[4] = {0.f, 0.f, 0.f, 0.f};
+  if ((EPI == E_AFFINE || EPI == E_AFFINE_ADD) && col_any) {
     for (int j = 0; j < 4 && col + j < g.N; j++) gain[j] = (float)g.gain[col + j];
+    if (EPI == E_AFFINE_ADD && g.gain2)
+      for (int j = 0; j < 4 && col + j < g.N; j++) {
+        gain2[j] = (float)g.gain2[col + j];
+        bias2[j] = (float)g.bias2[col + j];
+      }
   }
   if (EPI != E_PARTIAL && EPI != E_GELU_BWD && g.bias && col_any) {
     if (col_full) {
@@ -183,7 +192,7 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
       if (row >= g.M || !col_any) continue;
       float v[4] = {raw.x, raw.y, raw.z, raw.w};
       const long long ci = c_off + (long long)row * ld + col;
-      if (EPI == E_AFFINE) {
+      if (EPI == E_AFFINE || EPI == E_AFFINE_ADD) {
 #pragma unroll
         for (int j = 0; j < 4; j++) v[j] *= g.alpha;
       } else if (EPI != E_PARTIAL) {
@@ -222,6 +231,16 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
           }
           *(bf16x4*)((bf16*)g.C + ci) = o;
           *(bf16x4*)(g.C2 + ci) = o2;
+        } else if (EPI == E_AFFINE_ADD) {
+          const bf16x4 u = *(const bf16x4*)(g.U + ci);
+          bf16x4 o, o2;
+#pragma unroll
+          for (int j = 0; j < 4; j++) {
+            o[j] = (bf16)v[j];
+            o2[j] = (bf16)fmaxf(((float)o[j] * gain[j] + bias[j]) + ((float)u[j] * gain2[j] + bias2[j]), 0.f);
+          }
+          *(bf16x4*)((bf16*)g.C + ci) = o;
+          *(bf16x4*)(g.C2 + ci) = o2;
         } else {
           bf16x4 o;
 #pragma unroll
@@ -244,6 +263,10 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
             const bf16 z = (bf16)x;
             ((bf16*)g.C)[ci + j] = z;
             g.C2[ci + j] = (bf16)fmaxf((float)z * gain[j] + bias[j], 0.f);
+          } else if (EPI == E_AFFINE_ADD) {
+            const bf16 z = (bf16)x;
+            ((bf16*)g.C)[ci + j] = z;
+            g.C2[ci + j] = (bf16)fmaxf(((float)z * gain[j] + bias[j]) + ((float)g.U[ci + j] * gain2[j] + bias2[j]), 0.f);
           } else {
             ((bf16*)g.C)[ci + j] = (bf16)x;
           }

@@ -24,6 +24,7 @@ enum EpiMode : int {
   EPI_GELU_FWD = 1,  // C = gelu'(v) (bf16, kept for the backward pass), C2 = gelu(v) (bf16)
   EPI_GELU_BWD = 2,  // C = v * U, U = the stored gelu'(u)
   EPI_AFFINE_RELU = 3,  // C = z = v (bf16), C2 = max(z * gain[j] + bias[j], 0) (bf16), z as rounded to bf16
+  EPI_AFFINE_ADD_RELU = 4,  // C = z, C2 = max(z * gain + bias + U * gain2 + bias2, 0); gain2 null: + U
 };
 
 struct GemmDesc {
@@ -42,7 +43,9 @@ struct GemmDesc {
   // epilogue: v = alpha * acc + bias[j] + residual[i][j]
   float alpha = 1.f;
   const bf16* bias = nullptr;      // per output column
-  const bf16* gain = nullptr;      // EPI_AFFINE_RELU, per output column
+  const bf16* gain = nullptr;      // EPI_AFFINE_RELU / EPI_AFFINE_ADD_RELU, per output column
+  const bf16* gain2 = nullptr;     // EPI_AFFINE_ADD_RELU (nullable, then bias2 is ignored too)
+  const bf16* bias2 = nullptr;
   const float* residual = nullptr; // fp32 [M][ldr]
   int ldr = 0;
   int mode = EPI_PLAIN;
@@ -50,7 +53,7 @@ struct GemmDesc {
   int ldc = 0;
   bool c_f32 = false;
   bf16* C2 = nullptr;              // EPI_GELU_FWD
-  const bf16* U = nullptr;         // EPI_GELU_BWD, same leading dimension as C
+  const bf16* U = nullptr;         // EPI_GELU_BWD, EPI_AFFINE_ADD_RELU: same leading dimension as C
   int tile = 0;                    // 0 = choose by shape; else a TileId (tuning/tests)
   int no_store = 0;                // tuning aids (bit 0: store nothing, bit 1: no loads, bit 2: one panel)
 };

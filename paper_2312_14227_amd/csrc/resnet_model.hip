@@ -45,7 +45,8 @@ inline bool needs_cols(const ConvUnit& u) { return u.k > 1 || u.stride > 1; }
 
 // z = cols(in) * Wm^T; with gain/shift the GEMM epilogue also writes y = max(z * gain + shift, 0)
 int conv_forward(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16* Wm, void* z, bool z_f32,
-                 const bf16* gain = nullptr, const bf16* shift = nullptr, bf16* y = nullptr) {
+                 const bf16* gain = nullptr, const bf16* shift = nullptr, bf16* y = nullptr, const bf16* branch = nullptr,
+                 const bf16* gain2 = nullptr, const bf16* shift2 = nullptr) {
   const bf16* A = in;
   if (needs_cols(u)) {
     ET_KB(1, 2.0 * ((double)c->desc.batch * u.H * u.W * u.Cin + (double)rows_of(c, u) * u.Kc),
@@ -56,6 +57,9 @@ int conv_forward(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16* Wm, v
   g.C = z; g.c_f32 = z_f32;
   if (gain) {
     g.mode = et::EPI_AFFINE_RELU; g.gain = gain; g.bias = shift; g.C2 = y;
+    if (branch) {   // the other branch of a block end, inside the same ReLU
+      g.mode = et::EPI_AFFINE_ADD_RELU; g.U = branch; g.gain2 = gain2; g.bias2 = shift2;
+    }
   }
   ET_G(g);
   return ET_OK;
@@ -212,19 +216,16 @@ int resnet_forward(et_ctx* c, const void* x, const int32_t* y) {
     if (rc != ET_OK) return rc;
     rc = conv_forward(c, b.c2, b.c1.y, Wt(t + 3), b.c2.z, false, Wt(t + 4), Wt(t + 5), b.c2.y);
     if (rc != ET_OK) return rc;
-    rc = conv_forward(c, b.c3, b.c2.y, Wt(t + 6), b.c3.z, false);
-    if (rc != ET_OK) return rc;
+    // block end: y = max(c3.z * g + b + shortcut, 0) is the epilogue of c3's GEMM; the projection
+    // shortcut's convolution runs first
     if (b.proj) {
       rc = conv_forward(c, b.sc, h, Wt(t + 9), b.sc.z, false);
       if (rc != ET_OK) return rc;
-      ET_KB(1, 6.0 * rows_of(c, b.c3) * b.c3.Cout,
-            et::affine_act(b.c3.z, nullptr, Wt(t + 7), Wt(t + 8), b.sc.z, Wt(t + 10), Wt(t + 11), true, b.y,
-                           (long long)rows_of(c, b.c3), b.c3.Cout, s));
+      rc = conv_forward(c, b.c3, b.c2.y, Wt(t + 6), b.c3.z, false, Wt(t + 7), Wt(t + 8), b.y, b.sc.z, Wt(t + 10), Wt(t + 11));
     } else {
-      ET_KB(1, 6.0 * rows_of(c, b.c3) * b.c3.Cout,
-            et::affine_act(b.c3.z, nullptr, Wt(t + 7), Wt(t + 8), h, nullptr, nullptr, true, b.y,
-                           (long long)rows_of(c, b.c3), b.c3.Cout, s));
+      rc = conv_forward(c, b.c3, b.c2.y, Wt(t + 6), b.c3.z, false, Wt(t + 7), Wt(t + 8), b.y, h);
     }
+    if (rc != ET_OK) return rc;
     h = b.y;
   }
   const ResBlockBufs& last = c->rblk.back();
