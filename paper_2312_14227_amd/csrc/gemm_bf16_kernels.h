@@ -177,8 +177,24 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
       for (int j = 0; j < 4 && col + j < g.N; j++) bias[j] = (float)g.bias[col + j];
     }
   }
+  constexpr bool HAS_RES = EPI == E_F32_RES;
+  constexpr bool HAS_U = EPI == E_GELU_BWD || EPI == E_AFFINE_ADD;
 #pragma unroll
   for (int mi = 0; mi < MI; mi++) {
+    // the second operands of this 32-row block are requested before the accumulators go through
+    // LDS, all at once: one memory latency per block instead of one per row group
+    float4 pre_res[HAS_RES ? 32 / RPI : 1];
+    bf16x4 pre_u[HAS_U ? 32 / RPI : 1];
+    if (HAS_RES || HAS_U) {
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; it++) {
+        const int row = row0 + mi * 32 + min(it * RPI + rsub, 31);
+        if (row < g.M && col_any && col_full) {
+          if (HAS_RES) pre_res[it] = *(const float4*)(g.residual + (long long)row * g.ldr + col);
+          if (HAS_U) pre_u[it] = *(const bf16x4*)(g.U + c_off + (long long)row * ld + col);
+        }
+      }
+    }
 #pragma unroll
     for (int ni = 0; ni < NI; ni++)
 #pragma unroll
@@ -201,11 +217,11 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
       }
       if (col_full) {
         if (EPI == E_F32_RES) {
-          const float4 rs = *(const float4*)(g.residual + (long long)row * g.ldr + col);
+          const float4 rs = pre_res[HAS_RES ? it : 0];
           v[0] += rs.x; v[1] += rs.y; v[2] += rs.z; v[3] += rs.w;
         }
         if (EPI == E_GELU_BWD) {
-          const bf16x4 u = *(const bf16x4*)(g.U + ci);
+          const bf16x4 u = pre_u[HAS_U ? it : 0];
 #pragma unroll
           for (int j = 0; j < 4; j++) v[j] *= (float)u[j];
         }
@@ -232,7 +248,7 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
           *(bf16x4*)((bf16*)g.C + ci) = o;
           *(bf16x4*)(g.C2 + ci) = o2;
         } else if (EPI == E_AFFINE_ADD) {
-          const bf16x4 u = *(const bf16x4*)(g.U + ci);
+          const bf16x4 u = pre_u[HAS_U ? it : 0];
           bf16x4 o, o2;
 #pragma unroll
           for (int j = 0; j < 4; j++) {
