@@ -271,5 +271,7 @@ inline int launch_gemm(et_ctx* c, const et::GemmDesc& g) {
 
 // per-model chains (each in its own file)
 int build_resnet(et_ctx* c);
-int resnet_forward(et_ctx* c, const void* x, const int32_t* y);
+// mask (nullable = keep everything): the forward pass stores a backward-only tensor only if the
+// masked backward pass will read it
+int resnet_forward(et_ctx* c, const void* x, const int32_t* y, const uint8_t* mask);
 int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask);

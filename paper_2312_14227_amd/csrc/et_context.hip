@@ -188,8 +188,15 @@ VitDims vit_dims(const et_model_desc& d) {
   return v;
 }
 
-int vit_forward(et_ctx* c, const void* x, const int32_t* y) {
+int vit_forward(et_ctx* c, const void* x, const int32_t* y, const uint8_t* mask) {
   const VitDims v = vit_dims(c->desc);
+  // input-most selected tensor: gelu'(u) of a block is read only when the gradient is passed through its fc2
+  int jstar = -1;
+  if (mask) {
+    jstar = (int)c->tensors.size();
+    for (int j = 0; j < (int)c->tensors.size(); j++)
+      if (mask[j]) { jstar = j; break; }
+  }
   Region r(c, PH_FWD, -1);
   auto W = [&](int i) { return (const bf16*)c->w[i]; };
   {
@@ -241,7 +248,11 @@ int vit_forward(et_ctx* c, const void* x, const int32_t* y) {
                               c->stream));
     {
       et::GemmDesc g = linear_fwd(b.a2, W(t0 + 8), W(t0 + 9), v.M, v.F, v.D);
-      g.mode = et::EPI_GELU_FWD; g.C = b.u; g.C2 = b.ga;
+      if (t0 + 10 > jstar) {   // also when mask is null (jstar = -1)
+        g.mode = et::EPI_GELU_FWD; g.C = b.u; g.C2 = b.ga;
+      } else {
+        g.mode = et::EPI_GELU_ONLY; g.C = b.ga;
+      }
       ET_G(g);
     }
     {
@@ -469,10 +480,12 @@ int vit_backward(et_ctx* c, const void* x, const uint8_t* mask) {
   return ET_OK;
 }
 
-int run_forward(et_ctx* c, const void* x, const int32_t* y) {
+// mask (nullable = keep everything): tensors that only the backward pass reads (the GELU derivative,
+// a convolution's output ahead of its affine) are stored only if the masked backward pass will read them
+int run_forward(et_ctx* c, const void* x, const int32_t* y, const uint8_t* mask = nullptr) {
   c->cur_phase = PH_FWD;
-  if (c->desc.kind == ET_RESNET) return resnet_forward(c, x, y);
-  return c->desc.kind == ET_MLP ? mlp_forward(c, x, y) : vit_forward(c, x, y);
+  if (c->desc.kind == ET_RESNET) return resnet_forward(c, x, y, mask);
+  return c->desc.kind == ET_MLP ? mlp_forward(c, x, y) : vit_forward(c, x, y, mask);
 }
 int run_backward(et_ctx* c, const void* x, const uint8_t* mask) {
   c->cur_phase = PH_DW;
@@ -663,7 +676,7 @@ int et_train_step(et_ctx* c, const void* x_dev, const int32_t* y_dev, const uint
   if (!c->bound) return ET_ESTATE;
   if (reinterpret_cast<uintptr_t>(x_dev) & 15) return ET_EINVAL;
   c->launches[0] = c->launches[1] = c->launches[2] = c->launches[3] = 0;
-  int rc = run_forward(c, x_dev, y_dev);
+  int rc = run_forward(c, x_dev, y_dev, mask_host);
   if (rc != ET_OK) return rc;
   rc = run_backward(c, x_dev, mask_host);
   if (rc != ET_OK) return rc;

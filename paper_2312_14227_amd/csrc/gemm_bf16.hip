@@ -62,7 +62,7 @@ int choose_tile(const GemmDesc& d, int k_per_block) {
     // the GELU epilogues (two outputs or an extra operand, transcendental math) take as long as a
     // short main loop; two 256x128 workgroups per CU overlap one's epilogue with the other's MFMAs
     // (measured in the ViT-B step: 121 us against 132 us with the two-group tile)
-    if ((d.mode == EPI_GELU_FWD || d.mode == EPI_GELU_BWD) && dma_ok && d.N >= 2560 && k_per_block >= 4 * gemm::DBK)
+    if ((d.mode == EPI_GELU_FWD || d.mode == EPI_GELU_BWD || d.mode == EPI_GELU_ONLY) && dma_ok && d.N >= 2560 && k_per_block >= 4 * gemm::DBK)
       return T_DMA_256x128;
     if (pp_ok && k_per_block >= 4 * gemm::PBK) return plan_large(d.M, d.N, k_per_block, false).tile;
     if (dma_ok && k_per_block >= 4 * gemm::DBK) return d.N >= 2560 ? T_DMA_256x128 : T_DMA_256x256;
@@ -90,7 +90,8 @@ void gemm_bf16_plan_split(int M, int N, int K, int* tile, int* split_k) {
 
 hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   if (launches) *launches = 0;
-  if (!d.A || !d.B || !d.C || d.M <= 0 || d.N <= 0 || d.K <= 0) return hipErrorInvalidValue;
+  const bool c_optional = d.mode == EPI_AFFINE_RELU || d.mode == EPI_AFFINE_ADD_RELU;
+  if (!d.A || !d.B || (!d.C && !c_optional) || d.M <= 0 || d.N <= 0 || d.K <= 0) return hipErrorInvalidValue;
   if (!aligned(d.A, 16) || !aligned(d.B, 16) || !aligned(d.C, 16) || (d.lda & 7) || (d.ldb & 7)) return hipErrorInvalidValue;
   if ((d.sAo | d.sAi | d.sBo | d.sBi) & 7) return hipErrorInvalidValue;
   if ((d.sCo | d.sCi) & 3) return hipErrorInvalidValue;
@@ -133,6 +134,9 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
     if (d.mode == EPI_GELU_FWD) {
       if (!d.C2 || d.c_f32 || d.residual || !aligned(d.C2, 8)) return hipErrorInvalidValue;
       epi = gemm::E_GELU_FWD;
+    } else if (d.mode == EPI_GELU_ONLY) {
+      if (d.c_f32 || d.residual || d.a_t || d.b_t) return hipErrorInvalidValue;
+      epi = gemm::E_GELU_ONLY;
     } else if (d.mode == EPI_AFFINE_RELU) {
       if (!d.C2 || !d.gain || !d.bias || d.c_f32 || d.residual || d.a_t || d.b_t || !aligned(d.C2, 8)) return hipErrorInvalidValue;
       epi = gemm::E_AFFINE;

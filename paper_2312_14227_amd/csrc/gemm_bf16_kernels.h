@@ -56,6 +56,7 @@ enum Epi : int {
   E_GELU_BWD = 4,   // C bf16 = v * U, U = the stored gelu'(u)
   E_PARTIAL = 5,    // split-K partial: C fp32 [z][M][N] = v
   E_AFFINE = 6,     // C bf16 = z = v, C2 bf16 = max(z * gain[j] + bias[j], 0) with z as rounded to bf16
+  E_GELU_ONLY = 8,  // C bf16 = gelu(v + bias) (forward of a block whose backward will not run)
   E_AFFINE_ADD = 7, // as E_AFFINE with a second branch inside the ReLU: + U * gain2[j] + bias2[j] (or + U if gain2 is null)
 };
 
@@ -94,6 +95,14 @@ __device__ __forceinline__ void gelu_both(float u, float& g, float& dg) {
   const float phi = 0.5f * (1.f + copysignf(erf_abs, u));
   g = u * phi;
   dg = phi + u * e * 0.39894228040143268f;
+}
+
+__device__ __forceinline__ float gelu_only(float u) {
+  const float x = fabsf(u) * 0.70710678118654752f;
+  const float t = __frcp_rn(1.f + 0.3275911f * x);
+  const float e = __expf(-x * x);
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  return u * (0.5f * (1.f + copysignf(1.f - poly * e, u)));
 }
 
 __device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char* p) {
@@ -238,6 +247,11 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
           }
           *(bf16x4*)((bf16*)g.C + ci) = o;
           *(bf16x4*)(g.C2 + ci) = o2;
+        } else if (EPI == E_GELU_ONLY) {
+          bf16x4 o;
+#pragma unroll
+          for (int j = 0; j < 4; j++) o[j] = (bf16)gelu_only(v[j]);
+          *(bf16x4*)((bf16*)g.C + ci) = o;
         } else if (EPI == E_AFFINE) {
           bf16x4 o, o2;
 #pragma unroll
@@ -245,7 +259,7 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
             o[j] = (bf16)v[j];
             o2[j] = (bf16)fmaxf((float)o[j] * gain[j] + bias[j], 0.f);
           }
-          *(bf16x4*)((bf16*)g.C + ci) = o;
+          if (g.C) *(bf16x4*)((bf16*)g.C + ci) = o;   // z is kept only if the gain's gradient will be computed
           *(bf16x4*)(g.C2 + ci) = o2;
         } else if (EPI == E_AFFINE_ADD) {
           const bf16x4 u = pre_u[HAS_U ? it : 0];
@@ -255,7 +269,7 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
             o[j] = (bf16)v[j];
             o2[j] = (bf16)fmaxf(((float)o[j] * gain[j] + bias[j]) + ((float)u[j] * gain2[j] + bias2[j]), 0.f);
           }
-          *(bf16x4*)((bf16*)g.C + ci) = o;
+          if (g.C) *(bf16x4*)((bf16*)g.C + ci) = o;
           *(bf16x4*)(g.C2 + ci) = o2;
         } else {
           bf16x4 o;
@@ -266,6 +280,10 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
       } else {  // ragged right edge: element by element
         for (int j = 0; j < 4 && col + j < g.N; j++) {
           float x = v[j];
+          if (EPI == E_GELU_ONLY) {
+            ((bf16*)g.C)[ci + j] = (bf16)gelu_only(x);
+            continue;
+          }
           if (EPI == E_F32_RES) x += g.residual[(long long)row * g.ldr + col + j];
           if (EPI == E_GELU_BWD) x *= (float)g.U[ci + j];
           if (EPI == E_F32 || EPI == E_F32_RES || EPI == E_PARTIAL) {
@@ -277,11 +295,11 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
             g.C2[ci + j] = (bf16)gv;
           } else if (EPI == E_AFFINE) {
             const bf16 z = (bf16)x;
-            ((bf16*)g.C)[ci + j] = z;
+            if (g.C) ((bf16*)g.C)[ci + j] = z;
             g.C2[ci + j] = (bf16)fmaxf((float)z * gain[j] + bias[j], 0.f);
           } else if (EPI == E_AFFINE_ADD) {
             const bf16 z = (bf16)x;
-            ((bf16*)g.C)[ci + j] = z;
+            if (g.C) ((bf16*)g.C)[ci + j] = z;
             g.C2[ci + j] = (bf16)fmaxf(((float)z * gain[j] + bias[j]) + ((float)g.U[ci + j] * gain2[j] + bias2[j]), 0.f);
           } else {
             ((bf16*)g.C)[ci + j] = (bf16)x;

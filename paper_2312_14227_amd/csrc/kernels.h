@@ -24,6 +24,7 @@ enum EpiMode : int {
   EPI_GELU_FWD = 1,  // C = gelu'(v) (bf16, kept for the backward pass), C2 = gelu(v) (bf16)
   EPI_GELU_BWD = 2,  // C = v * U, U = the stored gelu'(u)
   EPI_AFFINE_RELU = 3,  // C = z = v (bf16), C2 = max(z * gain[j] + bias[j], 0) (bf16), z as rounded to bf16
+  EPI_GELU_ONLY = 5,    // C = gelu(v) (bf16): the forward of a layer whose backward will not run
   EPI_AFFINE_ADD_RELU = 4,  // C = z, C2 = max(z * gain + bias + U * gain2 + bias2, 0); gain2 null: + U
 };
 
@@ -49,7 +50,7 @@ struct GemmDesc {
   const float* residual = nullptr; // fp32 [M][ldr]
   int ldr = 0;
   int mode = EPI_PLAIN;
-  void* C = nullptr;               // bf16 or fp32 [M][ldc]
+  void* C = nullptr;               // bf16 or fp32 [M][ldc]; may be null for the AFFINE modes (z not kept)
   int ldc = 0;
   bool c_f32 = false;
   bf16* C2 = nullptr;              // EPI_GELU_FWD

@@ -190,7 +190,7 @@ int build_resnet(et_ctx* c) {
   return ET_OK;
 }
 
-int resnet_forward(et_ctx* c, const void* x, const int32_t* y) {
+int resnet_forward(et_ctx* c, const void* x, const int32_t* y, const uint8_t* mask) {
   const et_model_desc& d = c->desc;
   Region r(c, PH_FWD, -1);
   hipStream_t s = c->stream;
@@ -208,22 +208,24 @@ int resnet_forward(et_ctx* c, const void* x, const int32_t* y) {
           et::maxpool3x3s2_fwd(c->stem_z32, Wt(1), Wt(2), c->pooled, c->pool_arg, B, u.Ho, u.Wo, u.Cout, s));
   }
   const bf16* h = c->pooled;
+  // a convolution's output z is read again only by the gradient of its gain
+  auto keep = [&](bf16* z, int gain_index) -> bf16* { return (!mask || mask[gain_index]) ? z : nullptr; };
   for (ResBlockBufs& b : c->rblk) {
     const int t = b.t;
     b.x = h;
     // c1, c2: the affine + ReLU is the epilogue of the convolution's GEMM (z is kept for the gain's gradient)
-    int rc = conv_forward(c, b.c1, h, Wt(t), b.c1.z, false, Wt(t + 1), Wt(t + 2), b.c1.y);
+    int rc = conv_forward(c, b.c1, h, Wt(t), keep(b.c1.z, t + 1), false, Wt(t + 1), Wt(t + 2), b.c1.y);
     if (rc != ET_OK) return rc;
-    rc = conv_forward(c, b.c2, b.c1.y, Wt(t + 3), b.c2.z, false, Wt(t + 4), Wt(t + 5), b.c2.y);
+    rc = conv_forward(c, b.c2, b.c1.y, Wt(t + 3), keep(b.c2.z, t + 4), false, Wt(t + 4), Wt(t + 5), b.c2.y);
     if (rc != ET_OK) return rc;
     // block end: y = max(c3.z * g + b + shortcut, 0) is the epilogue of c3's GEMM; the projection
     // shortcut's convolution runs first
     if (b.proj) {
       rc = conv_forward(c, b.sc, h, Wt(t + 9), b.sc.z, false);
       if (rc != ET_OK) return rc;
-      rc = conv_forward(c, b.c3, b.c2.y, Wt(t + 6), b.c3.z, false, Wt(t + 7), Wt(t + 8), b.y, b.sc.z, Wt(t + 10), Wt(t + 11));
+      rc = conv_forward(c, b.c3, b.c2.y, Wt(t + 6), keep(b.c3.z, t + 7), false, Wt(t + 7), Wt(t + 8), b.y, b.sc.z, Wt(t + 10), Wt(t + 11));
     } else {
-      rc = conv_forward(c, b.c3, b.c2.y, Wt(t + 6), b.c3.z, false, Wt(t + 7), Wt(t + 8), b.y, h);
+      rc = conv_forward(c, b.c3, b.c2.y, Wt(t + 6), keep(b.c3.z, t + 7), false, Wt(t + 7), Wt(t + 8), b.y, h);
     }
     if (rc != ET_OK) return rc;
     h = b.y;
