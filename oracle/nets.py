@@ -290,6 +290,9 @@ def vit_step(cfg, weights, x, y, mask):
 
 
 def forward(cfg, weights, x, y):
+    if cfg.kind == "vgg":
+        from . import vgg
+        return vgg.vgg_forward(cfg, weights, x, y)
     if cfg.kind == "resnet":
         from . import resnet
         return resnet.resnet_forward(cfg, weights, x, y)
@@ -297,6 +300,9 @@ def forward(cfg, weights, x, y):
 
 
 def step(cfg, weights, x, y, mask):
+    if cfg.kind == "vgg":
+        from . import vgg
+        return vgg.vgg_step(cfg, weights, x, y, mask)
     if cfg.kind == "resnet":
         from . import resnet
         return resnet.resnet_step(cfg, weights, x, y, mask)

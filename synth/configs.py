@@ -69,6 +69,24 @@ class ResNetConfig:
     kind: str = "resnet"
 
 
+@dataclass(frozen=True)
+class VGGConfig:
+    """Plain convolution stack on NHWC images (VGG family): stage i has convs[i] 3x3 convolutions (stride 1,
+    padding 1, with bias, ReLU) to widths[i] channels followed by 2x2 / stride 2 max pooling; then the
+    flattened (h, w, c) features go through linear layers of fc[j] units with bias and ReLU and a linear
+    head.  Convolution weights are stored [out, kh, kw, in], linear ones [out, in]."""
+    name: str
+    batch: int
+    image: int
+    in_ch: int
+    widths: Tuple[int, ...]
+    convs: Tuple[int, ...]
+    fc: Tuple[int, ...]
+    classes: int
+    dtype: str = "bf16"
+    kind: str = "vgg"
+
+
 CONFIGS = {
     # BASELINE configs[0]: 4-layer ReLU MLP, fp32, batch 32
     "mlp": MLPConfig("mlp", (256, 256, 256, 256, 10), 32),
@@ -81,6 +99,10 @@ CONFIGS = {
     "resnet_tiny": ResNetConfig("resnet_tiny", 2, 16, 3, 8, (1, 1), (8, 8), 8),
     "resnet_small": ResNetConfig("resnet_small", 3, 64, 3, 16, (2, 1, 2, 1), (8, 16, 24, 32), 24),
     # small cases the oracle finishes in well under a second
+    # second CNN family of the paper's evaluation (Section 8): VGG16 shape, 200 classes
+    "vgg16": VGGConfig("vgg16", 32, 224, 3, (64, 128, 256, 512, 512), (2, 2, 3, 3, 3), (4096, 4096), 200),
+    "vgg_tiny": VGGConfig("vgg_tiny", 2, 8, 3, (8, 8), (1, 2), (16,), 8),
+    "vgg_small": VGGConfig("vgg_small", 3, 32, 3, (8, 16, 24), (2, 1, 2), (40, 24), 24),
     "mlp_tiny": MLPConfig("mlp_tiny", (8, 8, 8, 4), 4),
     "mlp5": MLPConfig("mlp5", (6, 6, 6, 6, 6, 3), 4),
     "vit_tiny": ViTConfig("vit_tiny", 2, 5, 12, 16, 2, 32, 2, 7),
@@ -124,5 +146,17 @@ def tensor_specs(cfg) -> List[Tuple[str, Tuple[int, ...]]]:
                     out += [(n + "sc.W", (4 * p, 1, 1, cin)), (n + "sc.g", (4 * p,)), (n + "sc.b", (4 * p,))]
                 cin = 4 * p
         out += [("head.W", (cfg.classes, cin)), ("head.b", (cfg.classes,))]
+        return out
+    if cfg.kind == "vgg":
+        out, cin, i = [], cfg.in_ch, 0
+        for w, n in zip(cfg.widths, cfg.convs):
+            for _ in range(n):
+                out += [("conv%d.W" % i, (w, 3, 3, cin)), ("conv%d.b" % i, (w,))]
+                cin, i = w, i + 1
+        side = cfg.image >> len(cfg.widths)
+        fin = side * side * cin
+        for j, f in enumerate(tuple(cfg.fc) + (cfg.classes,)):
+            out += [("fc%d.W" % j, (f, fin)), ("fc%d.b" % j, (f,))]
+            fin = f
         return out
     raise ValueError(cfg.kind)

@@ -28,7 +28,7 @@ class Workload:
     names: List[str]
     weights: List[np.ndarray]    # float32, chain order; bf16-representable for bf16 configs
     snapshot: List[np.ndarray]   # weights + N(0, std 1e-3), same representation
-    x: np.ndarray                # MLP: [B, dims[0]]; ViT: [B, tokens-1, patch_dim]; ResNet: [B, H, W, C]
+    x: np.ndarray                # MLP: [B, dims[0]]; ViT: [B, tokens-1, patch_dim]; ResNet, VGG: [B, H, W, C]
     y: np.ndarray                # int32 labels, uniform over the classes
 
 
@@ -63,6 +63,11 @@ def make_workload(cfg, seed: int = 0, init: str = "paper", batch: int = None) ->
         rng = _rng(seed, 100 + i)
         if cfg.kind == "mlp":
             w = rng.standard_normal(shape) * np.sqrt(2.0 / shape[1])        # Kaiming normal, fan-in
+        elif cfg.kind == "vgg":
+            if name.endswith(".W"):                                          # He normal, fan-in
+                w = rng.standard_normal(shape) * np.sqrt(2.0 / int(np.prod(shape[1:])))
+            else:
+                w = np.zeros(shape) if init == "paper" else 0.05 * rng.standard_normal(shape)
         elif cfg.kind == "resnet":
             leaf = name.split(".")[-1]
             if leaf == "W":                                                  # He normal, fan-in
@@ -86,7 +91,7 @@ def make_workload(cfg, seed: int = 0, init: str = "paper", batch: int = None) ->
         snapshot.append(s)
     if cfg.kind == "mlp":
         x = _rng(seed, 1).standard_normal((B, cfg.dims[0])).astype(np.float32)
-    elif cfg.kind == "resnet":
+    elif cfg.kind in ("resnet", "vgg"):
         x = quant(_rng(seed, 1).standard_normal((B, cfg.image, cfg.image, cfg.in_ch)).astype(np.float32))
     else:
         x = quant(_rng(seed, 1).standard_normal((B, cfg.tokens - 1, cfg.patch_dim)).astype(np.float32))
