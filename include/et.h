@@ -41,6 +41,7 @@ extern "C" {
 #define ET_MLP 0 /* ReLU multi-layer perceptron without biases                      */
 #define ET_VIT 1 /* pre-LN vision transformer encoder on flattened patches          */
 #define ET_RESNET 2 /* bottleneck residual CNN, BatchNorm folded into per-channel affines */
+#define ET_VGG 3 /* plain 3x3 convolution stack with biases, 2x2 max pooling, linear layers   */
 
 /* storage types of weights and activations */
 #define ET_F32 0  /* float32 everywhere                                             */
@@ -51,7 +52,7 @@ extern "C" {
 #define ET_SGDW 1
 
 #define ET_MAX_MLP_LAYERS 16
-#define ET_MAX_STAGES 4
+#define ET_MAX_STAGES 8
 
 typedef struct et_ctx et_ctx;
 
@@ -73,17 +74,24 @@ typedef struct et_ctx et_ctx;
  *   Section 5): stem.W, stem.g, stem.b; per block c1.W, c1.g, c1.b, c2.*, c3.*, then sc.W,
  *   sc.g, sc.b for a projection block; head.W [classes, 4 planes[last]], head.b.  stem, planes
  *   and classes must be multiples of 8.
+ * ET_VGG: x and the convolution weights are laid out as for ET_RESNET.  Stage i is stage_blocks[i]
+ *   3x3 / stride 1 / zero padding 1 convolutions to planes[i] channels, each followed by a bias and
+ *   a ReLU, then a 2x2 / stride 2 max pooling (image must be divisible by 2^n_stages).  The pooled
+ *   features, flattened in (h, w, c) order, pass through n_layers hidden linear layers of
+ *   dims[0..n_layers-1] units (bias, ReLU) and a linear layer to `classes` logits.  Every layer is
+ *   two tensors, Kernel and Bias (Section 5.1): conv{i}.W [out, 3, 3, in], conv{i}.b, ...,
+ *   fc{j}.W [out, in], fc{j}.b.  planes, dims and classes must be multiples of 8.
  * Labels are int32 in [0, classes). The loss is the mean softmax cross-entropy. */
 typedef struct {
-  int32_t kind;  /* ET_MLP | ET_VIT | ET_RESNET */
-  int32_t dtype; /* ET_F32 (MLP) | ET_BF16 (ViT, ResNet) */
+  int32_t kind;  /* ET_MLP | ET_VIT | ET_RESNET | ET_VGG */
+  int32_t dtype; /* ET_F32 (MLP) | ET_BF16 (ViT, ResNet, VGG) */
   int32_t batch;
-  int32_t n_layers;                    /* ET_MLP */
-  int32_t dims[ET_MAX_MLP_LAYERS + 1]; /* ET_MLP */
+  int32_t n_layers;                    /* ET_MLP, ET_VGG */
+  int32_t dims[ET_MAX_MLP_LAYERS + 1]; /* ET_MLP, ET_VGG */
   int32_t tokens, patch_dim, width, heads, mlp, blocks, classes; /* ET_VIT */
   float ln_eps;                        /* ET_VIT */
-  int32_t image, in_ch, stem, n_stages;               /* ET_RESNET (classes as above) */
-  int32_t stage_blocks[ET_MAX_STAGES], planes[ET_MAX_STAGES]; /* ET_RESNET */
+  int32_t image, in_ch, stem, n_stages;               /* ET_RESNET, ET_VGG (classes as above; stem: ET_RESNET only) */
+  int32_t stage_blocks[ET_MAX_STAGES], planes[ET_MAX_STAGES]; /* ET_RESNET, ET_VGG */
 } et_model_desc;
 
 /* Optimizer hyper-parameters of one step; every constant is explicit.

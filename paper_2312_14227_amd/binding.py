@@ -14,11 +14,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libet.so")
 
 ET_OK, ET_INFEASIBLE, ET_EINVAL, ET_ENOMEM, ET_EHIP, ET_ENAN, ET_ESTATE = 0, 1, -1, -2, -3, -4, -5
-ET_MLP, ET_VIT, ET_RESNET = 0, 1, 2
+ET_MLP, ET_VIT, ET_RESNET, ET_VGG = 0, 1, 2, 3
 ET_F32, ET_BF16 = 0, 1
 ET_ADAM, ET_SGDW = 0, 1
 ET_MAX_MLP_LAYERS = 16
-ET_MAX_STAGES = 4
+ET_MAX_STAGES = 8
 
 
 class et_model_desc(C.Structure):

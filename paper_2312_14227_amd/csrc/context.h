@@ -101,6 +101,15 @@ struct et_ctx {
   uint8_t* pool_arg = nullptr;
   float *stem_dw8 = nullptr, *stem_z32 = nullptr;
 
+  // plain convolution stack (VGG family): one unit per convolution (y: after bias + ReLU),
+  // per stage the pooled output and the chosen taps, the inputs of the linear layers
+  std::vector<ConvUnit> vconv;
+  std::vector<int> vstage;
+  std::vector<bf16*> vpool;
+  std::vector<uint8_t*> varg;
+  std::vector<bf16*> vact;
+  std::vector<int> vdims;           // vdims[j] -> vdims[j+1]: linear layer j
+
   // tables for importance / update
   std::vector<uint32_t> seg_begin;  // [N+1]
   uint32_t n_segs = 0;
@@ -275,3 +284,6 @@ int build_resnet(et_ctx* c);
 // masked backward pass will read it
 int resnet_forward(et_ctx* c, const void* x, const int32_t* y, const uint8_t* mask);
 int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask);
+int build_vgg(et_ctx* c);
+int vgg_forward(et_ctx* c, const void* x, const int32_t* y);
+int vgg_backward(et_ctx* c, const void* x, const uint8_t* mask);

@@ -277,6 +277,61 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(const bf16* __restrict
   }
 }
 
+// 2x2 / stride 2 max pooling (plain convolution stacks): first maximum in (dy, dx) order
+__global__ __launch_bounds__(256) void maxpool2_fwd_kernel(const bf16* __restrict__ y, bf16* __restrict__ out,
+                                                           uint8_t* __restrict__ arg, int H, int W, int C, long long total) {
+  const int c8n = C >> 3, Ho = H >> 1, Wo = W >> 1;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const int c8 = (int)(i % c8n);
+    const long long pix = i / c8n;
+    const int ow = (int)(pix % Wo), oh = (int)((pix / Wo) % Ho);
+    const long long b = pix / ((long long)Wo * Ho);
+    float best[8];
+    int bi[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) { best[j] = -INFINITY; bi[j] = 0; }
+#pragma unroll
+    for (int t = 0; t < 4; t++) {
+      const bf16x8 v = *(const bf16x8*)(y + ((b * H + oh * 2 + (t >> 1)) * W + ow * 2 + (t & 1)) * C + c8 * 8);
+#pragma unroll
+      for (int j = 0; j < 8; j++)
+        if ((float)v[j] > best[j]) { best[j] = (float)v[j]; bi[j] = t; }
+    }
+    bf16x8 r;
+    uint64_t packed = 0;
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      r[j] = (bf16)best[j];
+      packed |= (uint64_t)bi[j] << (8 * j);
+    }
+    *(bf16x8*)(out + pix * C + c8 * 8) = r;
+    *(uint64_t*)(arg + pix * C + c8 * 8) = packed;
+  }
+}
+
+__global__ __launch_bounds__(256) void maxpool2_bwd_kernel(const bf16* __restrict__ d, const uint8_t* __restrict__ arg,
+                                                           const bf16* __restrict__ y, bf16* __restrict__ out, int H, int W,
+                                                           int C, long long total) {
+  const int c8n = C >> 3, Ho = H >> 1, Wo = W >> 1;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const int c8 = (int)(i % c8n);
+    const long long pix = i / c8n;
+    const int w = (int)(pix % W), h = (int)((pix / W) % H);
+    const long long b = pix / ((long long)W * H);
+    const long long o = ((b * Ho + (h >> 1)) * Wo + (w >> 1)) * C + c8 * 8;
+    const bf16x8 dv = *(const bf16x8*)(d + o), yy = *(const bf16x8*)(y + pix * C + c8 * 8);
+    const uint64_t a = *(const uint64_t*)(arg + o);
+    const int tap = (h & 1) * 2 + (w & 1);
+    bf16x8 r;
+#pragma unroll
+    for (int j = 0; j < 8; j++)
+      r[j] = ((int)((a >> (8 * j)) & 0xff) == tap && (float)yy[j] > 0.f) ? dv[j] : (bf16)0.f;
+    *(bf16x8*)(out + pix * C + c8 * 8) = r;
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // global average pooling and its backward (+ the ReLU closing the last block)
 // ---------------------------------------------------------------------------------------------
@@ -400,6 +455,23 @@ hipError_t maxpool3x3s2_bwd(const bf16* d, const uint8_t* arg, const bf16* y, bf
   const long long total = (long long)B * H * W * (C >> 3);
   hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for(total)), dim3(256), 0, s, d, arg, y, out, B, H, W, C, Ho, Wo,
                      total);
+  return hipGetLastError();
+}
+
+hipError_t maxpool2x2_fwd(const bf16* y, bf16* out, uint8_t* arg, int B, int H, int W, int C, hipStream_t s) {
+  if (B < 1 || H < 2 || W < 2 || (H & 1) || (W & 1) || C < 8 || (C & 7) || !al16(y) || !al16(out) || !al16(arg))
+    return hipErrorInvalidValue;
+  const long long total = (long long)B * (H >> 1) * (W >> 1) * (C >> 3);
+  hipLaunchKernelGGL(maxpool2_fwd_kernel, dim3(grid_for(total)), dim3(256), 0, s, y, out, arg, H, W, C, total);
+  return hipGetLastError();
+}
+
+hipError_t maxpool2x2_bwd(const bf16* d, const uint8_t* arg, const bf16* y, bf16* out, int B, int H, int W, int C,
+                          hipStream_t s) {
+  if (B < 1 || H < 2 || W < 2 || (H & 1) || (W & 1) || C < 8 || (C & 7) || !al16(d) || !al16(arg) || !al16(y) || !al16(out))
+    return hipErrorInvalidValue;
+  const long long total = (long long)B * H * W * (C >> 3);
+  hipLaunchKernelGGL(maxpool2_bwd_kernel, dim3(grid_for(total)), dim3(256), 0, s, d, arg, y, out, H, W, C, total);
   return hipGetLastError();
 }
 

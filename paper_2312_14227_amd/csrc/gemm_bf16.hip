@@ -134,6 +134,9 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
     if (d.mode == EPI_GELU_FWD) {
       if (!d.C2 || d.c_f32 || d.residual || !aligned(d.C2, 8)) return hipErrorInvalidValue;
       epi = gemm::E_GELU_FWD;
+    } else if (d.mode == EPI_BIAS_RELU) {
+      if (d.c_f32 || d.residual || d.a_t || d.b_t) return hipErrorInvalidValue;
+      epi = gemm::E_BIAS_RELU;
     } else if (d.mode == EPI_GELU_ONLY) {
       if (d.c_f32 || d.residual || d.a_t || d.b_t) return hipErrorInvalidValue;
       epi = gemm::E_GELU_ONLY;

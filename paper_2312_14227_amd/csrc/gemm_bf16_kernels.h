@@ -56,6 +56,7 @@ enum Epi : int {
   E_GELU_BWD = 4,   // C bf16 = v * U, U = the stored gelu'(u)
   E_PARTIAL = 5,    // split-K partial: C fp32 [z][M][N] = v
   E_AFFINE = 6,     // C bf16 = z = v, C2 bf16 = max(z * gain[j] + bias[j], 0) with z as rounded to bf16
+  E_BIAS_RELU = 9,  // C bf16 = max(alpha*v + bias, 0)
   E_GELU_ONLY = 8,  // C bf16 = gelu(v + bias) (forward of a block whose backward will not run)
   E_AFFINE_ADD = 7, // as E_AFFINE with a second branch inside the ReLU: + U * gain2[j] + bias2[j] (or + U if gain2 is null)
 };
@@ -252,6 +253,11 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
 #pragma unroll
           for (int j = 0; j < 4; j++) o[j] = (bf16)gelu_only(v[j]);
           *(bf16x4*)((bf16*)g.C + ci) = o;
+        } else if (EPI == E_BIAS_RELU) {
+          bf16x4 o;
+#pragma unroll
+          for (int j = 0; j < 4; j++) o[j] = (bf16)fmaxf(v[j], 0.f);
+          *(bf16x4*)((bf16*)g.C + ci) = o;
         } else if (EPI == E_AFFINE) {
           bf16x4 o, o2;
 #pragma unroll
@@ -282,6 +288,10 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
           float x = v[j];
           if (EPI == E_GELU_ONLY) {
             ((bf16*)g.C)[ci + j] = (bf16)gelu_only(x);
+            continue;
+          }
+          if (EPI == E_BIAS_RELU) {
+            ((bf16*)g.C)[ci + j] = (bf16)fmaxf(x, 0.f);
             continue;
           }
           if (EPI == E_F32_RES) x += g.residual[(long long)row * g.ldr + col + j];

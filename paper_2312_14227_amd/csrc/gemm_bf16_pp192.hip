@@ -21,6 +21,7 @@ LaunchFn pp_256x192(bool a_t, bool b_t, int epi) {
   ET_PICK(false, false, E_BF16)
   ET_PICK(false, false, E_GELU_FWD)
   ET_PICK(false, false, E_GELU_ONLY)
+  ET_PICK(false, false, E_BIAS_RELU)
   ET_PICK(false, false, E_AFFINE)
   ET_PICK(false, false, E_AFFINE_ADD)
   ET_PICK(false, true, E_F32)

@@ -24,6 +24,7 @@ enum EpiMode : int {
   EPI_GELU_FWD = 1,  // C = gelu'(v) (bf16, kept for the backward pass), C2 = gelu(v) (bf16)
   EPI_GELU_BWD = 2,  // C = v * U, U = the stored gelu'(u)
   EPI_AFFINE_RELU = 3,  // C = z = v (bf16), C2 = max(z * gain[j] + bias[j], 0) (bf16), z as rounded to bf16
+  EPI_BIAS_RELU = 6,    // C = max(v + bias, 0) (bf16)
   EPI_GELU_ONLY = 5,    // C = gelu(v) (bf16): the forward of a layer whose backward will not run
   EPI_AFFINE_ADD_RELU = 4,  // C = z, C2 = max(z * gain + bias + U * gain2 + bias2, 0); gain2 null: + U
 };
@@ -163,6 +164,11 @@ hipError_t maxpool3x3s2_bwd(const bf16* d, const uint8_t* arg, const bf16* y, bf
 // p[b][c] = mean over the HW positions; backward: out[b][t][c] = dp[b][c] / HW * (y[b][t][c] > 0)
 hipError_t avgpool_fwd(const bf16* x, bf16* p, int B, int HW, int C, hipStream_t s);
 hipError_t avgpool_bwd_relu(const bf16* dp, const bf16* y, bf16* out, int B, int HW, int C, hipStream_t s);
+// 2x2 / stride 2 max pooling of y [B][H][W][C] (H, W even), first maximum in (dy, dx) order; arg: one byte per output
+hipError_t maxpool2x2_fwd(const bf16* y, bf16* out, uint8_t* arg, int B, int H, int W, int C, hipStream_t s);
+// out[B][H][W][C] = (d routed back to the chosen tap of its window) * (y > 0)
+hipError_t maxpool2x2_bwd(const bf16* d, const uint8_t* arg, const bf16* y, bf16* out, int B, int H, int W, int C,
+                          hipStream_t s);
 // rows of K elements <-> rows of Kc >= K elements (zero tail)
 hipError_t pad_rows(const bf16* in, bf16* out, int rows, int K, int Kc, hipStream_t s);
 hipError_t strip_rows(const float* in, float* out, int rows, int K, int Kc, hipStream_t s);

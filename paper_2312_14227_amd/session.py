@@ -13,6 +13,9 @@ def desc_from_config(cfg, batch=None):
     if cfg.kind == "resnet":
         return et.make_desc(et.ET_RESNET, et.ET_BF16, B, classes=cfg.classes, image=cfg.image, in_ch=cfg.in_ch,
                             stem=cfg.stem, stage_blocks=cfg.blocks, planes=cfg.planes)
+    if cfg.kind == "vgg":
+        return et.make_desc(et.ET_VGG, et.ET_BF16, B, dims=tuple(cfg.fc) + (cfg.classes,), classes=cfg.classes,
+                            image=cfg.image, in_ch=cfg.in_ch, stage_blocks=cfg.convs, planes=cfg.widths)
     return et.make_desc(et.ET_VIT, et.ET_BF16, B, tokens=cfg.tokens, patch_dim=cfg.patch_dim, width=cfg.width,
                         heads=cfg.heads, mlp=cfg.mlp, blocks=cfg.blocks, classes=cfg.classes, ln_eps=cfg.ln_eps)
 

@@ -1,0 +1,129 @@
+"""Parity of the HIP step of the plain convolution stack (VGG family) with the oracle, through the
+C ABI, on the same seeded inputs.  As for the residual network the parity reference is the oracle
+with its `store` hook set to bf16 rounding at the tensors the bf16 data layout keeps in memory
+(its arithmetic stays float64); the distance to the exact oracle is bounded by that of the
+bf16-storage oracle to the exact one."""
+import numpy as np
+import pytest
+
+from gpu_util import rel_l2, sample_masks, tol_for
+from oracle import resnet as R
+from oracle import vgg as V
+from synth import CONFIGS, make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def _session(cfg, wl, **kw):
+    from paper_2312_14227_amd.session import Session
+    return Session(cfg, wl.weights, **kw)
+
+
+def _run(s, xt, yt, mask):
+    import torch
+    for g in s.grad:
+        g.fill_(float("nan"))
+    loss = s.train_step(xt, yt, mask)
+    torch.cuda.synchronize()
+    return loss, [g.cpu().numpy() for g in s.grad]
+
+
+@pytest.mark.parametrize("name,seed,init", [("vgg_tiny", 0, "random"), ("vgg_tiny", 1, "paper"),
+                                            ("vgg_small", 2, "random"), ("vgg_small", 3, "paper")])
+def test_vgg_masks_match_oracle(name, seed, init):
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg, seed=seed, init=init)
+    N = len(wl.weights)
+    ones = [1] * N
+    ref = V.vgg_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16)
+    exact = V.vgg_step(cfg, wl.weights, wl.x, wl.y, ones)
+    s = _session(cfg, wl)
+    from paper_2312_14227_amd import binding as et
+    assert [et.et_tensor_info(s.ctx, i)[2] for i in range(N)] == list(wl.names)
+    xt, yt = s.put_input(wl.x, wl.y)
+    rng = np.random.default_rng(seed)
+    tol = 0.1 * tol_for(cfg)            # same rounding points on both sides: far inside the bf16 bound
+    worst = worst_exact = 0.0
+    convs, t_fc = V.layout(cfg)
+    # every stage boundary (a pooling layer in the gradient's way) and every linear layer
+    extra = [t for (t, _, first) in convs if first] + [t + 1 for (t, _, first) in convs if first] + \
+            list(range(t_fc, N))
+    for mask in sample_masks(N, rng, extra=extra):
+        loss, grads = _run(s, xt, yt, mask)
+        assert abs(loss - ref["loss"]) <= tol * abs(ref["loss"]), (loss, ref["loss"])
+        for j in range(N):
+            if mask[j]:
+                assert np.isfinite(grads[j]).all(), wl.names[j]
+                err = rel_l2(grads[j], ref["grads"][j])
+                worst = max(worst, err)
+                assert err <= tol, (wl.names[j], err, [int(m) for m in mask])
+                worst_exact = max(worst_exact, rel_l2(grads[j], exact["grads"][j]))
+            else:
+                assert np.isnan(grads[j]).all(), ("unselected gradient buffer was written", wl.names[j])
+    print("%s: worst relative L2 error %.3e against the bf16-storage oracle, %.3e against the exact one"
+          % (name, worst, worst_exact))
+    own = max(rel_l2(a, b) for a, b in zip(ref["grads"], exact["grads"]))
+    assert worst_exact <= 1.25 * own + tol, (worst_exact, own)
+    s.close()
+
+
+def test_vgg_launched_work_follows_the_time_model():
+    """A bias adds no dy() work (t_dy = 0, Section 5.1): selecting a layer's bias alone launches what
+    selecting its kernel alone launches, up to the dw() kernels themselves; nothing runs behind the
+    input-most selected tensor."""
+    cfg = CONFIGS["vgg_small"]
+    wl = make_workload(cfg, seed=0, init="random")
+    N = len(wl.weights)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    m = np.zeros(N, dtype=np.uint8)
+    s.train_step(xt, yt, m)
+    fwd0, bwd0, _ = s.launch_counts()
+    assert bwd0 == 0 and fwd0 > 0
+    counts = []
+    for j in range(N):
+        m = np.zeros(N, dtype=np.uint8)
+        m[j] = 1
+        s.train_step(xt, yt, m)
+        fwd, bwd, _ = s.launch_counts()
+        assert fwd == fwd0
+        counts.append(bwd)
+    assert counts[N - 1] < counts[0]
+    for t in range(0, N, 2):
+        assert abs(counts[t] - counts[t + 1]) <= 3, (t, counts)      # kernel vs bias of one layer
+    for t in range(0, N - 2, 2):
+        assert counts[t] > counts[t + 2], (t, counts)                # one more dy() per layer passed
+    s.close()
+
+
+def test_vgg_profile_and_selection_run():
+    """et_profile fills every tensor's t_dw, gives a bias t_dy = 0 and selection accepts the result."""
+    from paper_2312_14227_amd import binding as et
+    cfg = CONFIGS["vgg_small"]
+    wl = make_workload(cfg, seed=4, init="random")
+    N = len(wl.weights)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    t_fwd, t_dw, t_dy = s.profile(xt, yt, warmup=1, reps=2)
+    assert t_fwd > 0 and (t_dw > 0).all()
+    assert (t_dy[1::2] == 0).all() and (t_dy[2::2] > 0).all() and t_dy[0] == 0
+    imp = s.importance(xt, yt, [w.clone() for w in s.w])
+    assert np.isfinite(imp).all() and len(imp) == N
+    st, mask, pred = et.et_select(np.abs(imp) + 1e-12, t_dw, t_dy, t_fwd, 500000, 1000)
+    assert st == 0 and mask.any() and pred > 0
+    s.close()
+
+
+def test_vgg_determinism():
+    cfg = CONFIGS["vgg_small"]
+    wl = make_workload(cfg, seed=5, init="random")
+    N = len(wl.weights)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    mask = np.ones(N, dtype=np.uint8)
+    l1, g1 = _run(s, xt, yt, mask)
+    l2, g2 = _run(s, xt, yt, mask)
+    assert l1 == l2
+    for a, b in zip(g1, g2):
+        assert np.array_equal(a, b)
+    s.close()
