@@ -25,6 +25,15 @@ int et_debug_gemm_bf16(const void* A, const void* B, void* C, int M, int N, int 
                        int a_t, int b_t, int c_f32, float alpha, const void* bias, const float* residual,
                        int split_k, float* partials, int tile, void* stream);
 
+/* 3x3 / stride 1 / zero padding 1 convolution as an implicit GEMM (the im2col matrix of Section 5.1's
+ * convolution kernels is never written): out[b][h][w][n] = sum over (ky, kx, c) of
+ * x[b][h+ky-1][w+kx-1][c] * w[n][ky][kx][c].  x bf16 NHWC [batch][H][W][C], C a multiple of 64; w bf16
+ * [N][3][3][C]; out bf16 [batch*H*W][N], N a multiple of 4.  mode 0: plain; 1: out = max(v + bias[n], 0);
+ * 2: out = U > 0 ? v : 0 with U bf16 shaped like out.  tile: 0 = automatic, or 11, 13, 15, 17 for the
+ * 256x256, 256x192, 256x128, 512x64 tiles.  Device pointers, 16-byte aligned.  Returns 0, -1, -3 as above. */
+int et_debug_conv3x3(const void* x, const void* w, void* out, int batch, int H, int W, int C, int N,
+                     const void* bias, const void* U, int mode, int tile, void* stream);
+
 /* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16; 16-byte aligned device
  * pointers).  Used to calibrate hardware traffic counters against a known size. */
 int et_debug_copy(void* dst, const void* src, size_t bytes, void* stream);

@@ -21,6 +21,20 @@ extern "C" int et_debug_gemm_bf16(const void* A, const void* B, void* C, int M, 
   return e == hipSuccess ? ET_OK : ET_EHIP;
 }
 
+extern "C" int et_debug_conv3x3(const void* x, const void* w, void* out, int batch, int H, int W, int C, int N,
+                                const void* bias, const void* U, int mode, int tile, void* stream) {
+  et::GemmDesc g;
+  g.A = (const et::bf16*)x; g.B = (const et::bf16*)w; g.C = out;
+  g.M = batch * H * W; g.N = N; g.K = 9 * C; g.lda = 9 * C; g.ldb = 9 * C; g.ldc = N;
+  g.conv_h = H; g.conv_w = W; g.conv_c = C; g.tile = tile;
+  if (mode == 1) { g.mode = et::EPI_BIAS_RELU; g.bias = (const et::bf16*)bias; }
+  if (mode == 2) { g.mode = et::EPI_RELU_MASK; g.U = (const et::bf16*)U; }
+  if (batch < 1 || H < 1 || W < 1 || (long long)batch * H * W > 0x7fffffffll) return ET_EINVAL;
+  const hipError_t e = et::gemm_bf16(g, (hipStream_t)stream);
+  if (e == hipErrorInvalidValue) return ET_EINVAL;
+  return e == hipSuccess ? ET_OK : ET_EHIP;
+}
+
 namespace {
 __global__ void et_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;

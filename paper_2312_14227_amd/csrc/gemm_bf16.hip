@@ -18,7 +18,8 @@ __global__ void splitk_reduce_kernel(const float4* __restrict__ part, float4* __
   out[i] = s;
 }
 
-enum TileId : int { T_AUTO = 0, T_128x128 = 1, T_128x64 = 3, T_DMA_256x256 = 5, T_DMA_256x128 = 7, T_PP_256x256 = 11, T_PP_256x192 = 13 };
+enum TileId : int { T_AUTO = 0, T_128x128 = 1, T_128x64 = 3, T_DMA_256x256 = 5, T_DMA_256x128 = 7, T_PP_256x256 = 11, T_PP_256x192 = 13,
+              T_PP_256x128 = 15, T_PP_512x64 = 17 };
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -48,10 +49,22 @@ Plan plan_large(int M, int N, int K, bool may_split) {
   return best;
 }
 
+// implicit convolution: two-group tiles only; narrow outputs take the narrow tiles
+int choose_conv_tile(const GemmDesc& d) {
+  if (d.tile == T_PP_256x256 || d.tile == T_PP_256x192 || d.tile == T_PP_256x128 || d.tile == T_PP_512x64) return d.tile;
+  if (d.N <= 64) return T_PP_512x64;
+  if (d.N <= 128) return T_PP_256x128;
+  // few tiles: the narrower tile fills more CUs
+  const long long t256 = (long long)((d.M + 255) / 256) * ((d.N + 255) / 256);
+  if (t256 < 200) return T_PP_256x128;
+  return plan_large(d.M, d.N, d.K, false).tile;
+}
+
 int choose_tile(const GemmDesc& d, int k_per_block) {
   const bool dma_ok = (d.K % gemm::DBK) == 0 && (k_per_block % gemm::DBK) == 0;
   const bool pp_ok = (d.K % gemm::PBK) == 0 && (k_per_block % gemm::PBK) == 0;
   if (d.tile == T_PP_256x256 || d.tile == T_PP_256x192) return pp_ok ? d.tile : (dma_ok ? T_DMA_256x256 : T_128x128);
+  if (d.tile == T_PP_256x128 || d.tile == T_PP_512x64) return pp_ok ? d.tile : T_128x128;
   if (d.tile == T_DMA_256x256 || d.tile == T_DMA_256x128) return dma_ok ? d.tile : T_128x128;
   if (d.tile != T_AUTO) return d.tile;
   if (d.N <= 64) return T_128x64;
@@ -97,11 +110,17 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   if ((d.sCo | d.sCi) & 3) return hipErrorInvalidValue;
   if (d.z_outer < 1 || d.z_inner < 1) return hipErrorInvalidValue;
   // rows must be long enough for the 16-byte loads of the contiguous index
-  if (!d.a_t && d.lda < ((d.K + 7) & ~7)) return hipErrorInvalidValue;
+  if (!d.a_t && d.conv_c <= 0 && d.lda < ((d.K + 7) & ~7)) return hipErrorInvalidValue;
   if (!d.b_t && d.ldb < ((d.K + 7) & ~7)) return hipErrorInvalidValue;
   if (d.a_t && d.lda < ((d.M + 7) & ~7)) return hipErrorInvalidValue;
   if (d.b_t && d.ldb < ((d.N + 7) & ~7)) return hipErrorInvalidValue;
   if (d.bias && !aligned(d.bias, 8)) return hipErrorInvalidValue;
+  const bool conv = d.conv_c > 0;
+  if (conv) {
+    if ((d.conv_c % gemm::PBK) || d.conv_h < 1 || d.conv_w < 1 || d.K != 9 * d.conv_c || (d.M % (d.conv_h * d.conv_w)) ||
+        d.a_t || d.b_t || d.split_k > 1 || d.z_outer != 1 || d.z_inner != 1)
+      return hipErrorInvalidValue;
+  }
   if (d.residual && (d.ldr < d.N || (d.ldr & 3) || !aligned(d.residual, 16))) return hipErrorInvalidValue;
 
   gemm::Params p;
@@ -111,6 +130,7 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   p.split_k = 1; p.k_chunk = 0;
   p.alpha = d.alpha; p.bias = d.bias; p.gain = d.gain; p.gain2 = d.gain2; p.bias2 = d.bias2; p.residual = d.residual; p.ldr = d.ldr;
   p.C = d.C; p.ldc = d.ldc; p.C2 = d.C2; p.U = d.U; p.no_store = d.no_store;
+  p.cH = d.conv_h; p.cW = d.conv_w; p.cC = d.conv_c;
   int zdim = d.z_outer * d.z_inner;
   int epi;
   int k_per_block = d.K;
@@ -148,6 +168,9 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
           !aligned(d.C2, 8) || !aligned(d.U, 8))
         return hipErrorInvalidValue;
       epi = gemm::E_AFFINE_ADD;
+    } else if (d.mode == EPI_RELU_MASK) {
+      if (!d.U || d.c_f32 || d.residual || d.bias || !aligned(d.U, 8)) return hipErrorInvalidValue;
+      epi = gemm::E_RELU_MASK;
     } else if (d.mode == EPI_GELU_BWD) {
       if (!d.U || d.c_f32 || d.residual || d.bias || !aligned(d.U, 8)) return hipErrorInvalidValue;
       epi = gemm::E_GELU_BWD;
@@ -160,7 +183,17 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   }
   int BM, BN;
   gemm::LaunchFn fn;
+  if (conv) {
+    switch (choose_conv_tile(d)) {
+      case T_PP_512x64: BM = 512; BN = 64; fn = gemm::pp_conv_512x64(epi); break;
+      case T_PP_256x128: BM = 256; BN = 128; fn = gemm::pp_conv_256x128(epi); break;
+      case T_PP_256x192: BM = 256; BN = 192; fn = gemm::pp_conv_256x192(epi); break;
+      default: BM = 256; BN = 256; fn = gemm::pp_conv_256x256(epi); break;
+    }
+  } else
   switch (choose_tile(d, k_per_block)) {
+    case T_PP_512x64: BM = 512; BN = 64; fn = gemm::pp_512x64(d.a_t, d.b_t, epi); break;
+    case T_PP_256x128: BM = 256; BN = 128; fn = gemm::pp_256x128(d.a_t, d.b_t, epi); break;
     case T_128x64: BM = 128; BN = 64; fn = gemm::staged_128x64(d.a_t, d.b_t, epi); break;
     case T_DMA_256x256: BM = 256; BN = 256; fn = gemm::dma_256x256(d.a_t, d.b_t, epi); break;
     case T_DMA_256x128: BM = 256; BN = 128; fn = gemm::dma_256x128(d.a_t, d.b_t, epi); break;

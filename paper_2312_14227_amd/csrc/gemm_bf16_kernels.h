@@ -57,6 +57,7 @@ enum Epi : int {
   E_PARTIAL = 5,    // split-K partial: C fp32 [z][M][N] = v
   E_AFFINE = 6,     // C bf16 = z = v, C2 bf16 = max(z * gain[j] + bias[j], 0) with z as rounded to bf16
   E_BIAS_RELU = 9,  // C bf16 = max(alpha*v + bias, 0)
+  E_RELU_MASK = 10, // C bf16 = U > 0 ? v : 0 (gradient through a ReLU whose output U was stored)
   E_GELU_ONLY = 8,  // C bf16 = gelu(v + bias) (forward of a block whose backward will not run)
   E_AFFINE_ADD = 7, // as E_AFFINE with a second branch inside the ReLU: + U * gain2[j] + bias2[j] (or + U if gain2 is null)
 };
@@ -80,6 +81,7 @@ struct Params {
   int ldc;
   bf16* C2;
   const bf16* U;
+  int cH, cW, cC;        // implicit 3x3 convolution (gemm_pp_kernel<.., CONV>): input height, width, channels
   int no_store;          // tuning aids: 1 run the main loop, store nothing; 2 also issue no loads; 4 all tiles load the same panels
 };
 
@@ -178,7 +180,7 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
         bias2[j] = (float)g.bias2[col + j];
       }
   }
-  if (EPI != E_PARTIAL && EPI != E_GELU_BWD && g.bias && col_any) {
+  if (EPI != E_PARTIAL && EPI != E_GELU_BWD && EPI != E_RELU_MASK && g.bias && col_any) {
     if (col_full) {
       const bf16x4 b = *(const bf16x4*)(g.bias + col);
 #pragma unroll
@@ -188,7 +190,7 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
     }
   }
   constexpr bool HAS_RES = EPI == E_F32_RES;
-  constexpr bool HAS_U = EPI == E_GELU_BWD || EPI == E_AFFINE_ADD;
+  constexpr bool HAS_U = EPI == E_GELU_BWD || EPI == E_AFFINE_ADD || EPI == E_RELU_MASK;
 #pragma unroll
   for (int mi = 0; mi < MI; mi++) {
     // the second operands of this 32-row block are requested before the accumulators go through
@@ -234,6 +236,11 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
           const bf16x4 u = pre_u[HAS_U ? it : 0];
 #pragma unroll
           for (int j = 0; j < 4; j++) v[j] *= (float)u[j];
+        }
+        if (EPI == E_RELU_MASK) {
+          const bf16x4 u = pre_u[HAS_U ? it : 0];
+#pragma unroll
+          for (int j = 0; j < 4; j++) v[j] = (float)u[j] > 0.f ? v[j] : 0.f;
         }
         if (EPI == E_F32 || EPI == E_F32_RES || EPI == E_PARTIAL) {
           *(float4*)((float*)g.C + ci) = make_float4(v[0], v[1], v[2], v[3]);
@@ -296,6 +303,7 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
           }
           if (EPI == E_F32_RES) x += g.residual[(long long)row * g.ldr + col + j];
           if (EPI == E_GELU_BWD) x *= (float)g.U[ci + j];
+          if (EPI == E_RELU_MASK) x = (float)g.U[ci + j] > 0.f ? x : 0.f;
           if (EPI == E_F32 || EPI == E_F32_RES || EPI == E_PARTIAL) {
             ((float*)g.C)[ci + j] = x;
           } else if (EPI == E_GELU_FWD) {
@@ -735,7 +743,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(Params g) {
 // extra before the loop, group 0 one extra after it.
 constexpr int PBK = 64;
 
-template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, int EPI>
+//
+// CONV = 1: the A operand is the im2col matrix of a 3x3 / stride 1 / zero padding 1 convolution
+// that is never written: row m is output pixel m of an NHWC activation [.., cH, cW, cC] (g.A),
+// column (tap, c) is input channel c at the pixel shifted by the tap.  cC is a multiple of 64, so
+// a K slice is 64 channels of one tap: the same 128-byte row pieces as in a stored matrix, read
+// from the shifted pixel, or replaced by zeros outside the image.
+template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, int EPI, int CONV = 0>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   constexpr int NW = WGM * WGN;
   constexpr int TM = BM / WGM, TN = BN / WGN;
@@ -765,10 +779,19 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   const bf16* ga[A_LOADS];
   const bf16* gb[B_LOADS];
   int la[A_LOADS], lb[B_LOADS];
+  static_assert(!CONV || (!AT && !BT), "implicit convolution: row-major operands");
+  int coh[CONV ? A_LOADS : 1], cow[CONV ? A_LOADS : 1];   // CONV: output pixel (h, w) of each piece's row
 #pragma unroll
   for (int i = 0; i < A_LOADS; i++) {
     const int q = wave * A_LOADS + i;
-    if (!AT) {  // 8 rows x 128 B; 16-byte chunk c of row r sits at chunk position c ^ ((r >> 1) & 7)
+    if (CONV) {  // centre tap of the row's pixel
+      const int row = q * 8 + (lane >> 3), chunk = lane & 7;
+      const int m = min(m0 + row, g.M - 1);
+      cow[i] = m % g.cW;
+      coh[i] = (m / g.cW) % g.cH;
+      ga[i] = A + (long long)m * g.cC + chunk * 8;
+      la[i] = row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
+    } else if (!AT) {  // 8 rows x 128 B; 16-byte chunk c of row r sits at chunk position c ^ ((r >> 1) & 7)
       const int row = q * 8 + (lane >> 3), chunk = lane & 7;
       ga[i] = A + (long long)min(m0 + row, g.M - 1) * g.lda + k_begin + chunk * 8;
       la[i] = row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
@@ -857,13 +880,38 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   };
 
   u32x4 ra[A_LOADS], rb[B_LOADS];
+  // CONV: tap (dy, dx) and channel offset of the next slice to load (uniform), the element offset
+  // of that slice from the centre tap, and per lane one bit per piece: "the registers hold data"
+  // (as opposed to a pixel outside the image, stored as zeros)
+  int c_dy = -1, c_dx = -1, c_sub = 0;
+  long long c_off_a = CONV ? -(long long)(g.cW + 1) * g.cC : 0;
+  unsigned c_ok = 0;
+  auto conv_load = [&](int i) {
+    const bool ok = (unsigned)(coh[CONV ? i : 0] + c_dy) < (unsigned)g.cH && (unsigned)(cow[CONV ? i : 0] + c_dx) < (unsigned)g.cW;
+    ra[i] = *(const u32x4*)(ga[i] + (ok ? c_off_a : 0));
+    c_ok = ok ? (c_ok | (1u << i)) : (c_ok & ~(1u << i));
+  };
+  auto conv_advance = [&](bool advance) {
+    if (!advance) return;
+    c_sub += PBK;
+    if (c_sub == g.cC) {
+      c_sub = 0;
+      if (++c_dx == 2) { c_dx = -1; c_dy++; }
+    }
+    c_off_a = (long long)(c_dy * g.cW + c_dx) * g.cC + c_sub;
+  };
   // pointers always address a valid slice: they stop advancing at the last one
   auto load_a_regs = [&](bool advance) {
 #pragma unroll
     for (int i = 0; i < A_LOADS; i++) {
-      ra[i] = *(const u32x4*)ga[i];
-      ga[i] += advance ? a_step : 0;
+      if (CONV) {
+        conv_load(i);
+      } else {
+        ra[i] = *(const u32x4*)ga[i];
+        ga[i] += advance ? a_step : 0;
+      }
     }
+    if (CONV) conv_advance(advance);
   };
   auto load_b_regs = [&](bool advance) {
 #pragma unroll
@@ -874,7 +922,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   };
   auto store_a = [&](unsigned char* st) {
 #pragma unroll
-    for (int i = 0; i < A_LOADS; i++) *(u32x4*)(st + la[i]) = ra[i];
+    for (int i = 0; i < A_LOADS; i++) {
+      if (CONV) {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        *(u32x4*)(st + la[i]) = ((c_ok >> i) & 1u) ? ra[i] : zero;
+      } else {
+        *(u32x4*)(st + la[i]) = ra[i];
+      }
+    }
   };
   auto store_b = [&](unsigned char* st) {
 #pragma unroll
@@ -935,8 +990,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       block_barrier();
       c_phase(std::integral_constant<int, A_LOADS>(), [&](int i) {
-        ra[i] = *(const u32x4*)ga[i];
-        ga[i] += adv ? a_step : 0;
+        if (CONV) {
+          conv_load(i);
+          if (i == A_LOADS - 1) conv_advance(adv);
+        } else {
+          ra[i] = *(const u32x4*)ga[i];
+          ga[i] += adv ? a_step : 0;
+        }
       });
       store_b(nxt);
       load_frags(cur, 2, a0, b0);
@@ -963,6 +1023,13 @@ LaunchFn dma_256x256(bool a_t, bool b_t, int epi);
 LaunchFn dma_256x128(bool a_t, bool b_t, int epi);
 LaunchFn pp_256x256(bool a_t, bool b_t, int epi);
 LaunchFn pp_256x192(bool a_t, bool b_t, int epi);
+LaunchFn pp_256x128(bool a_t, bool b_t, int epi);
+LaunchFn pp_512x64(bool a_t, bool b_t, int epi);
+// implicit 3x3 convolution (A gathered from the activation), row-major operands
+LaunchFn pp_conv_256x256(int epi);
+LaunchFn pp_conv_256x192(int epi);
+LaunchFn pp_conv_256x128(int epi);
+LaunchFn pp_conv_512x64(int epi);
 
 }  // namespace gemm
 }  // namespace et

@@ -1,0 +1,30 @@
+// Instantiations of the two-group bf16 GEMM kernel for one tile shape (see gemm_bf16_kernels.h):
+// the plain product and the implicit 3x3 convolution.
+#include "gemm_bf16_kernels.h"
+
+namespace et {
+namespace gemm {
+namespace {
+
+template <bool AT, bool BT, int E, int CONV>
+hipError_t launch(const Params& p, dim3 grid, hipStream_t s) {
+  hipLaunchKernelGGL((gemm_pp_kernel<256, 192, 4, 2, AT, BT, E, CONV>), grid, dim3(512), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+
+LaunchFn pp_conv_256x192(int epi) {
+#define ET_PICK(E) \
+  if (epi == E) return launch<false, false, E, 1>;
+  ET_PICK(E_BF16)
+  ET_PICK(E_BIAS_RELU)
+  ET_PICK(E_AFFINE)
+  ET_PICK(E_RELU_MASK)
+#undef ET_PICK
+  return nullptr;
+}
+
+}  // namespace gemm
+}  // namespace et

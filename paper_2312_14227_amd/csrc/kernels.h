@@ -25,6 +25,7 @@ enum EpiMode : int {
   EPI_GELU_BWD = 2,  // C = v * U, U = the stored gelu'(u)
   EPI_AFFINE_RELU = 3,  // C = z = v (bf16), C2 = max(z * gain[j] + bias[j], 0) (bf16), z as rounded to bf16
   EPI_BIAS_RELU = 6,    // C = max(v + bias, 0) (bf16)
+  EPI_RELU_MASK = 7,    // C = U > 0 ? v : 0 (bf16): gradient through a ReLU whose output U was stored
   EPI_GELU_ONLY = 5,    // C = gelu(v) (bf16): the forward of a layer whose backward will not run
   EPI_AFFINE_ADD_RELU = 4,  // C = z, C2 = max(z * gain + bias + U * gain2 + bias2, 0); gain2 null: + U
 };
@@ -55,7 +56,11 @@ struct GemmDesc {
   int ldc = 0;
   bool c_f32 = false;
   bf16* C2 = nullptr;              // EPI_GELU_FWD
-  const bf16* U = nullptr;         // EPI_GELU_BWD, EPI_AFFINE_ADD_RELU: same leading dimension as C
+  const bf16* U = nullptr;         // EPI_GELU_BWD, EPI_AFFINE_ADD_RELU, EPI_RELU_MASK: same leading dimension as C
+  // implicit 3x3 / stride 1 / zero padding 1 convolution (conv_c > 0): A is the NHWC activation
+  // [M / (conv_h conv_w), conv_h, conv_w, conv_c] itself, standing for its im2col matrix [M][9 conv_c]
+  // (K = 9 conv_c, column (tap, c)); conv_c must be a multiple of 64; row-major operands, no batching, no split
+  int conv_h = 0, conv_w = 0, conv_c = 0;
   int tile = 0;                    // 0 = choose by shape; else a TileId (tuning/tests)
   int no_store = 0;                // tuning aids (bit 0: store nothing, bit 1: no loads, bit 2: one panel)
 };

@@ -79,11 +79,14 @@ __global__ __launch_bounds__(256) void importance_stage1(const TensorSeg* __rest
 
 __global__ void importance_stage2(const double* __restrict__ partial, const uint32_t* __restrict__ seg_begin,
                                   int n_tensors, double* __restrict__ out) {
-  const int k = blockIdx.x * blockDim.x + threadIdx.x;
+  // one wave per tensor: lane l adds the chunks l, l+64, ... in order, then a fixed butterfly
+  const int k = blockIdx.x;
   if (k >= n_tensors) return;
   double s = 0.0;
-  for (uint32_t i = seg_begin[k]; i < seg_begin[k + 1]; i++) s += partial[i];
-  out[k] = s;
+  for (uint32_t i = seg_begin[k] + threadIdx.x; i < seg_begin[k + 1]; i += 64) s += partial[i];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  if (threadIdx.x == 0) out[k] = s;
 }
 
 template <bool BF16W>
@@ -137,7 +140,7 @@ hipError_t importance_reduce(const TensorSeg* segs_dev, int n_segs, const uint32
 #undef ET_IMP
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(importance_stage2, dim3((n_tensors + 63) / 64), dim3(64), 0, s, partial_dev, seg_begin_dev,
+  hipLaunchKernelGGL(importance_stage2, dim3(n_tensors), dim3(64), 0, s, partial_dev, seg_begin_dev,
                      n_tensors, out_dev);
   return hipGetLastError();
 }

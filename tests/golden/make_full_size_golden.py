@@ -32,6 +32,23 @@ def sample_indices(k, g, seed):
     return np.unique(np.concatenate([uniform, largest])).astype(np.int64)
 
 
+def vgg_in_chunks(cfg, wl, chunk):
+    """The oracle's float64 column matrices of a whole VGG16 batch do not fit this machine's memory.
+    No operation of the network mixes samples, so the gradient of the batch-mean loss is the mean of the
+    chunks' gradients; the batch size enters only through the factor 1/B of the logit gradient, and a
+    ratio of batch sizes that is a power of two commutes with the bf16 storage rounding.  The identity
+    is pinned at a small size in tests/test_oracle_vgg.py."""
+    from oracle import resnet, vgg
+    B = wl.x.shape[0]
+    assert B % chunk == 0 and ((B // chunk) & (B // chunk - 1)) == 0
+    parts = [vgg.vgg_step(cfg, wl.weights, wl.x[i:i + chunk], wl.y[i:i + chunk], [1] * len(wl.weights),
+                          store=resnet.round_bf16) for i in range(0, B, chunk)]
+    n = len(parts)
+    return dict(loss=sum(p["loss"] for p in parts) / n,
+                grads=[sum(p["grads"][k] for p in parts) / n for k in range(len(wl.weights))],
+                logits=np.concatenate([p["logits"] for p in parts], axis=0))
+
+
 def main():
     name = sys.argv[1]
     seed = int(sys.argv[2]) if len(sys.argv) > 2 else 0
@@ -43,6 +60,9 @@ def main():
         # reference rounds the tensors the bf16 data layout keeps in memory (see oracle/resnet.py)
         from oracle import resnet
         r = resnet.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights), store=resnet.round_bf16)
+        I = oimp.importance_from_grads(r["grads"], wl.weights, wl.snapshot)
+    elif cfg.kind == "vgg":
+        r = vgg_in_chunks(cfg, wl, 8)
         I = oimp.importance_from_grads(r["grads"], wl.weights, wl.snapshot)
     else:
         I, r = oimp.importance(cfg, wl.weights, wl.snapshot, wl.x, wl.y)

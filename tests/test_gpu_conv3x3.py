@@ -1,0 +1,65 @@
+"""Implicit-GEMM 3x3 convolution kernel (the im2col matrix is gathered from the activation, never written)
+against the oracle's convolution (explicit im2col and a float64 matrix product) on the same bf16 inputs,
+through the C ABI; all four tile shapes, images smaller and larger than a tile, ragged row and column tails."""
+import numpy as np
+import pytest
+
+from oracle import resnet as R
+from synth import bf16_round
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(batch, H, W, C, N, mode, tile, seed):
+    import torch
+    from paper_2312_14227_amd import binding as et
+    rng = np.random.default_rng(seed)
+    x = bf16_round(rng.standard_normal((batch, H, W, C)).astype(np.float32))
+    w = bf16_round((rng.standard_normal((N, 3, 3, C)) / np.sqrt(9 * C)).astype(np.float32))
+    bias = bf16_round(rng.standard_normal(N).astype(np.float32))
+    u = bf16_round(rng.standard_normal((batch * H * W, N)).astype(np.float32))
+    cv = R.Conv(x.astype(np.float64), w.astype(np.float64), 1)
+    ref = cv.out.reshape(batch * H * W, N)
+    scale = (np.abs(cv.cols.reshape(batch * H * W, -1)) @ np.abs(cv.wm).T)
+    if mode == 1:
+        ref = np.maximum(ref + bias.astype(np.float64), 0.0)
+    if mode == 2:
+        ref = ref * (u > 0)
+    dev = "cuda:0"
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(torch.bfloat16)
+    xt, wt, bt, ut = to(x), to(w), to(bias), to(u)
+    out = torch.full((batch * H * W, N), float("nan"), device=dev, dtype=torch.bfloat16)
+    st = et.et_debug_conv3x3(xt.data_ptr(), wt.data_ptr(), out.data_ptr(), batch, H, W, C, N, bt.data_ptr(), ut.data_ptr(),
+                             mode, tile, torch.cuda.current_stream().cuda_stream)
+    assert st == 0
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    # fp32 accumulation of exact bf16 products, then one rounding of the output
+    bound = 2e-6 * scale * np.sqrt(9 * C) + 1e-6 + 2.0 ** -8 * np.abs(ref)
+    if mode == 1:
+        bound = bound + 2.0 ** -8 * np.abs(bias)
+    bad = np.abs(got - ref) > bound
+    assert not bad.any(), (int(bad.sum()), float(np.abs(got - ref).max()))
+
+
+@pytest.mark.parametrize("tile", [0, 11, 13, 15, 17])
+@pytest.mark.parametrize("batch,H,W,C,N", [(2, 14, 14, 64, 64), (1, 28, 28, 128, 72), (3, 7, 9, 64, 264), (1, 40, 24, 192, 128)])
+def test_conv3x3_plain(batch, H, W, C, N, tile):
+    _case(batch, H, W, C, N, 0, tile, seed=tile + H)
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("batch,H,W,C,N,tile", [(2, 14, 14, 64, 64, 17), (1, 28, 28, 128, 128, 15), (3, 7, 9, 64, 264, 11),
+                                                (2, 16, 16, 64, 200, 13), (2, 16, 16, 256, 512, 0)])
+def test_conv3x3_epilogues(batch, H, W, C, N, tile, mode):
+    _case(batch, H, W, C, N, mode, tile, seed=mode * 100 + tile)
+
+
+def test_conv3x3_rejects_bad_arguments():
+    import torch
+    from paper_2312_14227_amd import binding as et
+    t = torch.zeros(1 << 16, device="cuda:0", dtype=torch.bfloat16)
+    p = t.data_ptr()
+    assert et.et_debug_conv3x3(p, p, p, 1, 8, 8, 48, 64) == -1        # channels not a multiple of 64
+    assert et.et_debug_conv3x3(p, p, p, 0, 8, 8, 64, 64) == -1
+    assert et.et_debug_conv3x3(p + 2, p, p, 1, 8, 8, 64, 64) == -1    # misaligned

@@ -1,5 +1,5 @@
 """Parity at the full size of the benchmark workloads (ViT-B shape at batch 64, ViT-L shape at batch
-32, ResNet-50 shape at batch 32), in the launch configuration bench.py times, against oracle values stored by tests/golden/make_full_size_golden.py
+32, ResNet-50 shape at batch 32, VGG16 shape at batch 32), in the launch configuration bench.py times, against oracle values stored by tests/golden/make_full_size_golden.py
 (per tensor 512 uniformly drawn gradient elements plus its 512 largest ones, gradient norms, loss,
 importance)."""
 import os
@@ -21,7 +21,10 @@ GOLD_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 # its input into a fraction ~eps of flipped mask bits, each of which drops or passes a whole gradient
 # element: a gradient error of sqrt(eps), i.e. 1-3 % here.  Two correct bf16 evaluations differ by that
 # much; the small ResNet cases, where no rounding flips, agree to 2e-6 (tests/test_gpu_resnet.py).
-@pytest.mark.parametrize("name,first,tol", [("vit_b", 87, 2e-2), ("vit_l", 200, 2e-2), ("resnet50", 80, 5e-2)])
+# VGG16: the same kind of reference and the same mechanism (13 ReLU convolutions, reductions over up to
+# 25 088 terms); its small cases agree to 1e-7 (tests/test_gpu_vgg.py).
+@pytest.mark.parametrize("name,first,tol", [("vit_b", 87, 2e-2), ("vit_l", 200, 2e-2), ("resnet50", 80, 5e-2),
+                                            ("vgg16", 11, 5e-2)])
 def test_full_size_gradients_importance_and_masks(name, first, tol):
     import torch
     from paper_2312_14227_amd.session import Session

@@ -96,14 +96,14 @@ def test_gemm_direct_to_lds_tiles(M, N, K, a_t, b_t, tile):
 @pytest.mark.parametrize("M,N,K,a_t,b_t", [(700, 520, 192, 0, 0), (700, 192, 512, 0, 1), (520, 264, 704, 1, 1),
                                            (1000, 768, 768, 0, 0), (200, 768, 64, 1, 1), (3, 8, 64, 0, 0),
                                            (513, 300, 128, 0, 0), (260, 257, 256, 0, 1)])
-@pytest.mark.parametrize("tile", [11, 13])
+@pytest.mark.parametrize("tile", [11, 13, 15, 17])
 def test_gemm_two_group_tile(M, N, K, a_t, b_t, tile):
     """Slices of 64 through registers into two LDS stages: one, two, three and many slices."""
     _run(M, N, K, a_t, b_t, 1, True, a_t == 0 and b_t == 0, 1, tile, seed=tile + M)
     _run(M, N, K, a_t, b_t, 0, True, False, 1, tile, seed=tile + N)
 
 
-@pytest.mark.parametrize("tile", [11, 13])
+@pytest.mark.parametrize("tile", [11, 13, 15, 17])
 def test_gemm_two_group_tile_split_k(tile):
     _run(768, 520, 4992, 1, 1, 1, False, False, 6, tile, seed=3)
 

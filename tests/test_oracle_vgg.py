@@ -118,3 +118,17 @@ def test_maxpool_takes_the_first_maximum():
     d = np.ones((1, 1, 1, 2))
     back = V.maxpool_2x2_backward(d, arg, x.shape)
     assert back[0, :, :, 0].tolist() == [[1.0, 0.0], [0.0, 0.0]] and back[0, :, :, 1].tolist() == [[0.0, 1.0], [0.0, 0.0]]
+
+
+def test_batch_mean_gradient_is_the_mean_over_chunks_also_with_storage_rounding():
+    """Used by the full-size golden writer: chunks of a batch (count a power of two) average to the batch result."""
+    cfg = CONFIGS["vgg_small"]
+    wl = make_workload(cfg, seed=11, init="random", batch=4)
+    N = len(wl.weights)
+    for store in (None, R.round_bf16):
+        whole = V.vgg_step(cfg, wl.weights, wl.x, wl.y, [1] * N, store=store)
+        parts = [V.vgg_step(cfg, wl.weights, wl.x[i:i + 2], wl.y[i:i + 2], [1] * N, store=store) for i in (0, 2)]
+        assert abs(whole["loss"] - 0.5 * (parts[0]["loss"] + parts[1]["loss"])) < 1e-13
+        for k in range(N):
+            np.testing.assert_allclose(whole["grads"][k], 0.5 * (parts[0]["grads"][k] + parts[1]["grads"][k]),
+                                       rtol=1e-11, atol=1e-15)
