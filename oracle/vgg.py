@@ -14,7 +14,9 @@ Layout NHWC; convolution weights [out, kh, kw, in] with zero padding 1; the line
 pooled features flattened in (h, w, c) order.  `store` is the storage-precision hook described in
 oracle/resnet.py: applied to every tensor a bf16 evaluation keeps in memory (activations after
 bias + ReLU, pooled features, column gradients, error gradients); a layer's pre-activation is not
-such a tensor here (bias and ReLU are applied to the unrounded sum).
+such a tensor here (bias and ReLU are applied to the unrounded sum).  Whether the column gradient
+of a convolution (d @ W, before the adjoint of im2col sums it into the input gradient) is a stored
+tensor depends on the layout under test: `cols_stored(cin, cout)` says so per convolution.
 """
 import numpy as np
 
@@ -83,7 +85,7 @@ def vgg_forward(cfg, weights, x, y, store=None):
     return loss, c
 
 
-def vgg_step(cfg, weights, x, y, mask, store=None):
+def vgg_step(cfg, weights, x, y, mask, store=None, cols_stored=lambda cin, cout: True):
     loss, c = vgg_forward(cfg, weights, x, y, store)
     W, q, units, pools, acts = c["W"], c["q"], c["units"], c["pools"], c["acts"]
     t_fc, n_fc = c["t_fc"], c["n_fc"]
@@ -131,8 +133,9 @@ def vgg_step(cfg, weights, x, y, mask, store=None):
             s["d"] = q(dx * (prev["y"] > 0.0))
         chain[t] = _Tiny(lambda s, u=u: u["conv"].dw(s["d"]), conv_dy if i > 0 else None)
         chain[t + 1] = _Tiny(lambda s: s["d"].reshape(-1, s["d"].shape[-1]).sum(axis=0), identity)
-    # the column gradient of a convolution is a stored tensor: give each Conv the hook
+    # where the column gradient of a convolution is a stored tensor, give its Conv the hook
     for u in units:
-        u["conv"].q = q
+        cout, _, _, cin = W[u["t"]].shape
+        u["conv"].q = q if cols_stored(cin, cout) else _same
     grads, work = _run_chain(chain, mask, state)
     return dict(loss=loss, grads=grads, work=work, logits=c["logits"])

@@ -109,6 +109,8 @@ struct et_ctx {
   std::vector<uint8_t*> varg;
   std::vector<bf16*> vact;
   std::vector<int> vdims;           // vdims[j] -> vdims[j+1]: linear layer j
+  bf16* wflip = nullptr;            // mirrored weight of the convolution whose dy() is running
+  float* fc_z32 = nullptr;          // reduced sum of a linear layer's split forward product
 
   // tables for importance / update
   std::vector<uint32_t> seg_begin;  // [N+1]

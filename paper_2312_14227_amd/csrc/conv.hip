@@ -9,6 +9,7 @@ namespace et {
 namespace {
 
 typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
@@ -188,6 +189,22 @@ __global__ __launch_bounds__(256) void add_mask_kernel(const bf16* __restrict__ 
       for (int j = 0; j < 8; j++) r[j] = (float)mk[j] > 0.f ? x[j] : (bf16)0.f;
     }
     *(bf16x8*)(out + i * 8) = r;
+  }
+}
+
+// out = max(z + bias, 0) from an fp32 matrix [rows][N] (a split product's reduced sum); N % 4 == 0
+__global__ __launch_bounds__(256) void bias_relu_rows_kernel(const float4* __restrict__ z, const bf16* __restrict__ bias,
+                                                             bf16* __restrict__ out, int n4, long long total) {
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const int c = (int)(i % n4) * 4;
+    const float4 v = z[i];
+    const bf16x4 b = *(const bf16x4*)(bias + c);
+    bf16x4 r;
+    r[0] = (bf16)fmaxf(v.x + (float)b[0], 0.f);
+    r[1] = (bf16)fmaxf(v.y + (float)b[1], 0.f);
+    r[2] = (bf16)fmaxf(v.z + (float)b[2], 0.f);
+    r[3] = (bf16)fmaxf(v.w + (float)b[3], 0.f);
+    *(bf16x4*)(out + i * 4) = r;
   }
 }
 
@@ -372,6 +389,15 @@ __global__ void strip_rows_kernel(const float* __restrict__ in, float* __restric
   out[i] = in[(i / K) * Kc + i % K];
 }
 
+// out[c][8 - tap][o] = w[o][tap][c]: the weight of the convolution that carries a 3x3 convolution's output
+// gradient back to its input (taps mirrored, channel roles exchanged)
+__global__ void flip3x3_kernel(const bf16* __restrict__ w, bf16* __restrict__ out, int O, int C) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;   // index into out: (c, tap', o)
+  if (i >= O * 9 * C) return;
+  const int o = i % O, tp = (i / O) % 9, c = i / (9 * O);
+  out[i] = w[((long long)o * 9 + (8 - tp)) * C + c];
+}
+
 inline unsigned grid_for(long long total) {
   long long b = (total + 255) / 256;
   return (unsigned)(b < 1 ? 1 : (b > 65536 ? 65536 : b));
@@ -427,6 +453,14 @@ hipError_t scale_cols(const bf16* d, const bf16* gain, bf16* out, long long rows
   if (rows < 1 || C < 8 || (C & 7) || !al16(d) || !al16(gain) || !al16(out)) return hipErrorInvalidValue;
   const long long n8 = rows * (C >> 3);
   hipLaunchKernelGGL(scale_cols_kernel, dim3(grid_for(n8)), dim3(256), 0, s, d, gain, out, n8, C);
+  return hipGetLastError();
+}
+
+hipError_t bias_relu_rows(const float* z, const bf16* bias, bf16* out, int rows, int N, hipStream_t s) {
+  if (rows < 1 || N < 4 || (N & 3) || !al16(z) || !bias || (reinterpret_cast<uintptr_t>(bias) & 7) || (reinterpret_cast<uintptr_t>(out) & 7))
+    return hipErrorInvalidValue;
+  const long long total = (long long)rows * (N >> 2);
+  hipLaunchKernelGGL(bias_relu_rows_kernel, dim3(grid_for(total)), dim3(256), 0, s, (const float4*)z, bias, out, N >> 2, total);
   return hipGetLastError();
 }
 
@@ -491,6 +525,12 @@ hipError_t avgpool_bwd_relu(const bf16* dp, const bf16* y, bf16* out, int B, int
 hipError_t pad_rows(const bf16* in, bf16* out, int rows, int K, int Kc, hipStream_t s) {
   if (rows < 1 || K < 1 || Kc < K) return hipErrorInvalidValue;
   hipLaunchKernelGGL(pad_rows_kernel, dim3((rows * Kc + 255) / 256), dim3(256), 0, s, in, out, rows, K, Kc);
+  return hipGetLastError();
+}
+
+hipError_t flip3x3(const bf16* w, bf16* out, int O, int C, hipStream_t s) {
+  if (O < 1 || C < 1 || (long long)O * 9 * C > 0x7fffffffll) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(flip3x3_kernel, dim3((O * 9 * C + 255) / 256), dim3(256), 0, s, w, out, O, C);
   return hipGetLastError();
 }
 

@@ -18,6 +18,7 @@ LaunchFn staged_128x128(bool a_t, bool b_t, int epi) {
   if (a_t == AT && b_t == BT && epi == E) return launch<AT, BT, E>;
   ET_PICK(false, false, E_F32)
   ET_PICK(false, false, E_F32_RES)
+  ET_PICK(false, false, E_PARTIAL)
   ET_PICK(false, false, E_BF16)
   ET_PICK(false, false, E_GELU_FWD)
   ET_PICK(false, false, E_GELU_ONLY)

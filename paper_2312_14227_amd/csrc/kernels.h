@@ -175,6 +175,11 @@ hipError_t maxpool2x2_fwd(const bf16* y, bf16* out, uint8_t* arg, int B, int H, 
 hipError_t maxpool2x2_bwd(const bf16* d, const uint8_t* arg, const bf16* y, bf16* out, int B, int H, int W, int C,
                           hipStream_t s);
 // rows of K elements <-> rows of Kc >= K elements (zero tail)
+// out[rows][N] (bf16) = max(z[rows][N] + bias[N], 0), z fp32; N % 4 == 0
+hipError_t bias_relu_rows(const float* z, const bf16* bias, bf16* out, int rows, int N, hipStream_t s);
+// out[C][3][3][O] = w[O][3][3][C] with mirrored taps: the weight of the 3x3 convolution that maps an output
+// gradient to the input gradient
+hipError_t flip3x3(const bf16* w, bf16* out, int O, int C, hipStream_t s);
 hipError_t pad_rows(const bf16* in, bf16* out, int rows, int K, int Kc, hipStream_t s);
 hipError_t strip_rows(const float* in, float* out, int rows, int K, int Kc, hipStream_t s);
 // out[c] = sum_r d[r][c] * z[r][c]   (z bf16, or fp32 when z_f32 is given); same two stages as colsum

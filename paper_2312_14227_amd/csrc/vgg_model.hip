@@ -7,6 +7,13 @@
 //
 // Bias and ReLU are the epilogue of the layer's GEMM, applied to the unrounded sum; the
 // pre-activation itself is never stored (the ReLU mask is read from the stored activation).
+//
+// A convolution whose input channels come in multiples of 64 runs as an implicit GEMM: the
+// forward product gathers the im2col rows from the activation, and dy() is the same kind of
+// convolution of the output gradient with the mirrored weight, its epilogue applying the ReLU
+// mask of the previous layer; only dw() materialises the im2col matrix (inside its own timed
+// region, in a buffer shared by all layers).  Other convolutions (the first one) keep the
+// matrix from the forward pass and pass the gradient through d * W and the adjoint of im2col.
 #include "conv_chain.h"
 
 namespace {
@@ -15,6 +22,20 @@ namespace {
 inline const bf16* conv_matrix(const et_ctx* c, size_t i) {
   const ConvUnit& u = c->vconv[i];
   return u.Kc == 9 * u.Cin ? (const bf16*)c->w[u.t] : c->stem_w8;
+}
+
+// implicit forward product / implicit dy() of a unit
+inline bool implicit_fwd(const ConvUnit& u) { return (u.Cin % 64) == 0; }
+inline bool implicit_dy(const ConvUnit& u) { return (u.Cout % 64) == 0 && (u.Cin % 8) == 0; }
+
+// A hidden linear layer on a small batch is one row of output tiles streaming the whole weight
+// matrix: split over the input features so that every CU streams a part, then reduce, add the
+// bias and apply the ReLU (the same single rounding as the fused epilogue).
+inline int fc_split(int batch, int out, int in) {
+  if (batch > 128) return 1;
+  int tile, split;
+  et::gemm_bf16_plan_split(batch, out, in, &tile, &split);
+  return split;
 }
 
 }  // namespace
@@ -56,13 +77,14 @@ int build_vgg(et_ctx* c) {
   }
 
   // ---- workspace
-  size_t max_act = 0, max_cols = 0, max_cs = 0, pe = 0;
+  size_t max_act = 0, max_cols = 0, max_cs = 0, pe = 0, max_flip = 8;
   c->vpool.assign(d.n_stages, nullptr);
   c->varg.assign(d.n_stages, nullptr);
   for (size_t i = 0; i < c->vconv.size(); i++) {
     ConvUnit& u = c->vconv[i];
     const size_t M = rows_of(c, u);
-    reserve(c, &u.cols, b16 * M * u.Kc);
+    if (!implicit_fwd(u)) reserve(c, &u.cols, b16 * M * u.Kc);
+    if (implicit_dy(u)) max_flip = std::max(max_flip, (size_t)u.Cout * 9 * u.Cin);
     reserve(c, &u.y, b16 * M * u.Cout);
     max_act = std::max(max_act, std::max(M * u.Cout, M * round8(u.Cin)));
     max_cols = std::max(max_cols, M * u.Kc);
@@ -81,6 +103,15 @@ int build_vgg(et_ctx* c) {
   }
   c->vact.assign(n_fc, nullptr);   // vact[0]: the last pooled output (set by the forward pass)
   for (int j = 1; j < n_fc; j++) reserve(c, &c->vact[j], b16 * B * c->vdims[j]);
+  size_t max_fc = 8;
+  for (int j = 0; j + 1 < n_fc; j++) {
+    const int sp = fc_split(d.batch, c->vdims[j + 1], c->vdims[j]);
+    if (sp > 1) {
+      max_fc = std::max(max_fc, B * (size_t)c->vdims[j + 1]);
+      pe = std::max(pe, et::gemm_bf16_partial_elems(d.batch, c->vdims[j + 1], sp));
+    }
+  }
+  reserve(c, &c->fc_z32, f32 * max_fc);
   for (int j = 0; j < n_fc; j++) {
     max_act = std::max(max_act, B * (size_t)std::max(c->vdims[j], c->vdims[j + 1]));
     max_cs = std::max(max_cs, et::colsum_partial_elems((int)B, c->vdims[j + 1]));
@@ -93,6 +124,7 @@ int build_vgg(et_ctx* c) {
   reserve(c, &c->loss, 256 + sizeof(float) * (size_t)d.batch);
   for (int i = 0; i < 3; i++) reserve(c, &c->rd[i], b16 * max_act);
   reserve(c, &c->rdcols, b16 * std::max<size_t>(max_cols, 8));
+  reserve(c, &c->wflip, b16 * max_flip);
   c->gemm_partial_elems = pe;
   reserve(c, &c->gemm_partials, f32 * std::max<size_t>(pe, 64));
   reserve(c, &c->colsum_partials, f32 * std::max<size_t>(max_cs, 64));
@@ -113,8 +145,12 @@ int vgg_forward(et_ctx* c, const void* x, const int32_t* y) {
     const size_t M = rows_of(c, u);
     u.in = h;
     if (u.Kc != 9 * u.Cin) ET_K(1, et::pad_rows(Wt(u.t), c->stem_w8, u.Cout, 9 * u.Cin, u.Kc, s));
-    ET_KB(1, 2.0 * ((double)M * u.Cin + (double)M * u.Kc), et::im2col(h, u.cols, geom(c, u), s));
     et::GemmDesc g = linear_fwd(u.cols, conv_matrix(c, i), Wt(u.t + 1), (int)M, u.Cout, u.Kc);
+    if (implicit_fwd(u)) {
+      g.A = h; g.conv_h = u.H; g.conv_w = u.W; g.conv_c = u.Cin;
+    } else {
+      ET_KB(1, 2.0 * ((double)M * u.Cin + (double)M * u.Kc), et::im2col(h, u.cols, geom(c, u), s));
+    }
     g.mode = et::EPI_BIAS_RELU; g.C = u.y;
     ET_G(g);
     h = u.y;
@@ -128,6 +164,13 @@ int vgg_forward(et_ctx* c, const void* x, const int32_t* y) {
   const int n_fc = (int)c->vdims.size() - 1, t_fc = 2 * (int)c->vconv.size();
   for (int j = 0; j < n_fc; j++) {
     et::GemmDesc g = linear_fwd(c->vact[j], Wt(t_fc + 2 * j), Wt(t_fc + 2 * j + 1), B, c->vdims[j + 1], c->vdims[j]);
+    const int sp = j + 1 < n_fc ? fc_split(B, c->vdims[j + 1], c->vdims[j]) : 1;
+    if (sp > 1 && et::gemm_bf16_partial_elems(B, c->vdims[j + 1], sp) <= c->gemm_partial_elems) {
+      g.bias = nullptr; g.C = c->fc_z32; g.c_f32 = true; g.split_k = sp; g.partials = c->gemm_partials;
+      ET_G(g);
+      ET_K(1, et::bias_relu_rows(c->fc_z32, Wt(t_fc + 2 * j + 1), c->vact[j + 1], B, c->vdims[j + 1], s));
+      continue;
+    }
     if (j + 1 < n_fc) {
       g.mode = et::EPI_BIAS_RELU; g.C = c->vact[j + 1];
     } else {
@@ -203,7 +246,10 @@ int vgg_backward(et_ctx* c, const void* x, const uint8_t* mask) {
     }
     if (sel(t)) {
       Region r(c, PH_DW, t);
-      if (u.Kc == 9 * u.Cin) {
+      if (implicit_fwd(u)) {   // the im2col matrix exists only here
+        ET_KB(1, 2.0 * ((double)M * u.Cin + (double)M * u.Kc), et::im2col(u.in, c->rdcols, geom(c, u), s));
+        ET_G(linear_dw(c, dcur, u.Cout, c->rdcols, u.Kc, c->grad[t], (int)M, u.Cout, u.Kc));
+      } else if (u.Kc == 9 * u.Cin) {
         if ((rc = conv_dw(c, u, u.in, dcur, c->grad[t])) != ET_OK) return rc;
       } else {
         if ((rc = conv_dw(c, u, u.in, dcur, c->stem_dw8)) != ET_OK) return rc;
@@ -213,10 +259,27 @@ int vgg_backward(et_ctx* c, const void* x, const uint8_t* mask) {
     if (pass(t)) {   // i > 0 here: tensor 0 is never passed
       Region r(c, PH_DY, t);
       const ConvUnit& p = c->vconv[i - 1];
-      if ((rc = conv_dcols(c, u, dcur, conv_matrix(c, i), c->rdcols)) != ET_OK) return rc;
       bf16* dn = next_buf();
       const double nin = (double)M * u.Cin;
-      if (c->vstage[i - 1] == c->vstage[i]) {
+      const bool same_stage = c->vstage[i - 1] == c->vstage[i];
+      if (implicit_dy(u)) {
+        // input gradient = 3x3 convolution of d with the mirrored weight [Cin][3][3][Cout]
+        ET_K(1, et::flip3x3(Wt(t), c->wflip, u.Cout, u.Cin, s));
+        et::GemmDesc g = linear_fwd(dcur, c->wflip, nullptr, (int)M, u.Cin, 9 * u.Cout);
+        g.conv_h = u.H; g.conv_w = u.W; g.conv_c = u.Cout;
+        if (same_stage) {
+          g.mode = et::EPI_RELU_MASK; g.U = p.y; g.C = dn;
+        } else {
+          g.C = c->rd[2];
+        }
+        ET_G(g);
+        if (!same_stage)
+          ET_KB(1, 3.0 * nin + 16.0 * nin, et::maxpool2x2_bwd(c->rd[2], c->varg[c->vstage[i - 1]], p.y, dn, B, p.Ho, p.Wo, p.Cout, s));
+        dcur = dn;
+        continue;
+      }
+      if ((rc = conv_dcols(c, u, dcur, conv_matrix(c, i), c->rdcols)) != ET_OK) return rc;
+      if (same_stage) {
         ET_KB(1, 2.0 * M * u.Kc + 4.0 * nin, et::col2im(c->rdcols, nullptr, p.y, dn, geom(c, u), s));
       } else {       // a pooling layer sits in between
         ET_KB(1, 2.0 * M * u.Kc + 2.0 * nin, et::col2im(c->rdcols, nullptr, nullptr, c->rd[2], geom(c, u), s));

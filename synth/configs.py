@@ -98,11 +98,13 @@ CONFIGS = {
     "resnet50": ResNetConfig("resnet50", 32, 224, 3, 64, (3, 4, 6, 3), (64, 128, 256, 512), 200),
     "resnet_tiny": ResNetConfig("resnet_tiny", 2, 16, 3, 8, (1, 1), (8, 8), 8),
     "resnet_small": ResNetConfig("resnet_small", 3, 64, 3, 16, (2, 1, 2, 1), (8, 16, 24, 32), 24),
-    # small cases the oracle finishes in well under a second
     # second CNN family of the paper's evaluation (Section 8): VGG16 shape, 200 classes
     "vgg16": VGGConfig("vgg16", 32, 224, 3, (64, 128, 256, 512, 512), (2, 2, 3, 3, 3), (4096, 4096), 200),
     "vgg_tiny": VGGConfig("vgg_tiny", 2, 8, 3, (8, 8), (1, 2), (16,), 8),
     "vgg_small": VGGConfig("vgg_small", 3, 32, 3, (8, 16, 24), (2, 1, 2), (40, 24), 24),
+    # channel counts in multiples of 64, as in VGG16: the convolutions that run as implicit GEMMs
+    "vgg_c64": VGGConfig("vgg_c64", 2, 16, 3, (64, 128), (2, 2), (64,), 16),
+    # small cases the oracle finishes in well under a second
     "mlp_tiny": MLPConfig("mlp_tiny", (8, 8, 8, 4), 4),
     "mlp5": MLPConfig("mlp5", (6, 6, 6, 6, 6, 3), 4),
     "vit_tiny": ViTConfig("vit_tiny", 2, 5, 12, 16, 2, 32, 2, 7),

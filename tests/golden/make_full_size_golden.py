@@ -41,8 +41,10 @@ def vgg_in_chunks(cfg, wl, chunk):
     from oracle import resnet, vgg
     B = wl.x.shape[0]
     assert B % chunk == 0 and ((B // chunk) & (B // chunk - 1)) == 0
+    # the bf16 data layout stores no column gradient for convolutions with 64 k output channels (implicit GEMM)
     parts = [vgg.vgg_step(cfg, wl.weights, wl.x[i:i + chunk], wl.y[i:i + chunk], [1] * len(wl.weights),
-                          store=resnet.round_bf16) for i in range(0, B, chunk)]
+                          store=resnet.round_bf16, cols_stored=lambda cin, cout: cout % 64 != 0 or cin % 8 != 0)
+             for i in range(0, B, chunk)]
     n = len(parts)
     return dict(loss=sum(p["loss"] for p in parts) / n,
                 grads=[sum(p["grads"][k] for p in parts) / n for k in range(len(wl.weights))],

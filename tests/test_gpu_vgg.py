@@ -28,21 +28,31 @@ def _run(s, xt, yt, mask):
     return loss, [g.cpu().numpy() for g in s.grad]
 
 
-@pytest.mark.parametrize("name,seed,init", [("vgg_tiny", 0, "random"), ("vgg_tiny", 1, "paper"),
-                                            ("vgg_small", 2, "random"), ("vgg_small", 3, "paper")])
-def test_vgg_masks_match_oracle(name, seed, init):
+def _cols_stored(cin, cout):
+    """Data layout of the HIP path: a convolution with 64 k output channels passes the gradient to its input as
+    an implicit GEMM and never stores the column gradient."""
+    return cout % 64 != 0 or cin % 8 != 0
+
+
+# vgg_c64 reduces over 576 and 1152 terms: now and then fp32 and float64 sums round to different bf16
+# values, and one flipped ReLU decision among the 32 768 activations of a layer moves a gradient by
+# a few 1e-3.  Its bound is the workload tolerance itself; the cases without flips keep a tenth of it.
+@pytest.mark.parametrize("name,seed,init,factor", [("vgg_tiny", 0, "random", 0.1), ("vgg_tiny", 1, "paper", 0.1),
+                                                   ("vgg_small", 2, "random", 0.1), ("vgg_small", 3, "paper", 0.1),
+                                                   ("vgg_c64", 4, "random", 1.0), ("vgg_c64", 5, "paper", 1.0)])
+def test_vgg_masks_match_oracle(name, seed, init, factor):
     cfg = CONFIGS[name]
     wl = make_workload(cfg, seed=seed, init=init)
     N = len(wl.weights)
     ones = [1] * N
-    ref = V.vgg_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16)
+    ref = V.vgg_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16, cols_stored=_cols_stored)
     exact = V.vgg_step(cfg, wl.weights, wl.x, wl.y, ones)
     s = _session(cfg, wl)
     from paper_2312_14227_amd import binding as et
     assert [et.et_tensor_info(s.ctx, i)[2] for i in range(N)] == list(wl.names)
     xt, yt = s.put_input(wl.x, wl.y)
     rng = np.random.default_rng(seed)
-    tol = 0.1 * tol_for(cfg)            # same rounding points on both sides: far inside the bf16 bound
+    tol = factor * tol_for(cfg)         # same rounding points on both sides: far inside the bf16 bound
     worst = worst_exact = 0.0
     convs, t_fc = V.layout(cfg)
     # every stage boundary (a pooling layer in the gradient's way) and every linear layer
