@@ -35,6 +35,22 @@ extern "C" int et_debug_conv3x3(const void* x, const void* w, void* out, int bat
   return e == hipSuccess ? ET_OK : ET_EHIP;
 }
 
+extern "C" int et_debug_conv3x3_dw(const void* x, const void* d, float* dw, int batch, int H, int W, int C, int N,
+                                   int split_k, float* partials, int tile, void* stream) {
+  if (batch < 1 || H < 1 || W < 1 || (long long)batch * H * W > 0x7fffffffll) return ET_EINVAL;
+  et::GemmDesc g;
+  g.A = (const et::bf16*)d; g.a_t = true; g.lda = N;
+  g.B = (const et::bf16*)x; g.b_t = true; g.ldb = 9 * C;
+  g.M = N; g.N = 9 * C; g.K = batch * H * W;
+  g.C = dw; g.ldc = 9 * C; g.c_f32 = true;
+  g.conv_h = H; g.conv_w = W; g.conv_c = C; g.tile = tile;
+  g.split_k = split_k < 1 ? 1 : split_k; g.partials = partials;
+  if (split_k == 0) et::gemm_bf16_plan_conv_dw(g.M, g.N, g.K, &g.tile, &g.split_k);
+  const hipError_t e = et::gemm_bf16(g, (hipStream_t)stream);
+  if (e == hipErrorInvalidValue) return ET_EINVAL;
+  return e == hipSuccess ? ET_OK : ET_EHIP;
+}
+
 namespace {
 __global__ void et_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;

@@ -19,7 +19,7 @@ __global__ void splitk_reduce_kernel(const float4* __restrict__ part, float4* __
 }
 
 enum TileId : int { T_AUTO = 0, T_128x128 = 1, T_128x64 = 3, T_DMA_256x256 = 5, T_DMA_256x128 = 7, T_PP_256x256 = 11, T_PP_256x192 = 13,
-              T_PP_256x128 = 15, T_PP_512x64 = 17 };
+              T_PP_256x128 = 15, T_PP_512x64 = 17, T_PP_128x256 = 19, T_PP_64x512 = 21 };
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -29,24 +29,39 @@ inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintp
 //   tile, 3.0 with 256x192), plus, for a split reduction, writing and re-reading the fp32 partials.
 struct Plan { int tile, split; double cost; };
 
-Plan plan_large(int M, int N, int K, bool may_split) {
+struct TileRate { int tile, bm, bn; double rate; };
+
+Plan plan_tiles(int M, int N, int K, bool may_split, const TileRate* cand, int n_cand) {
   Plan best = {T_AUTO, 1, 1e30};
   const int slices = (K + gemm::PBK - 1) / gemm::PBK;
   const int max_split = may_split ? std::max(1, std::min(64, slices / 4)) : 1;
-  const struct { int tile, bn; double rate; } cand[2] = {{T_PP_256x256, 256, 3.3e12}, {T_PP_256x192, 192, 3.0e12}};
-  for (const auto& c : cand) {
-    const long long tiles = (long long)((M + 255) / 256) * ((N + c.bn - 1) / c.bn);
+  for (int ci = 0; ci < n_cand; ci++) {
+    const TileRate& c = cand[ci];
+    const long long tiles = (long long)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
     for (int s = 1; s <= max_split; s++) {
       const int per = (slices + s - 1) / s;
       const int chunks = (slices + per - 1) / per;
       if (chunks != s) continue;   // this split leaves empty chunks: the same work as a smaller one
       const long long rounds = (tiles * s + 255) / 256;
-      double t = rounds * (2.0 * 256 * c.bn * per * gemm::PBK / c.rate);
+      double t = rounds * (2.0 * c.bm * c.bn * per * gemm::PBK / c.rate);
       if (s > 1) t += (2.0 * s + 1.0) * M * N * 4.0 / 3.5e12;
       if (t < best.cost) best = {c.tile, s, t};
     }
   }
   return best;
+}
+
+Plan plan_large(int M, int N, int K, bool may_split) {
+  static const TileRate cand[2] = {{T_PP_256x256, 256, 256, 3.3e12}, {T_PP_256x192, 256, 192, 3.0e12}};
+  return plan_tiles(M, N, K, may_split, cand, 2);
+}
+
+// weight gradient of a convolution, [M = output channels][N = 9 input channels] reduced over the pixels:
+// few output channels take the tiles that are narrow in M (rates measured on the VGG16 shapes)
+Plan plan_conv_dw(int M, int N, int K) {
+  static const TileRate cand[4] = {{T_PP_256x256, 256, 256, 3.3e12}, {T_PP_256x192, 256, 192, 3.0e12},
+                                   {T_PP_128x256, 128, 256, 2.4e12}, {T_PP_64x512, 64, 512, 1.6e12}};
+  return plan_tiles(M, N, K, true, cand, 4);
 }
 
 // implicit convolution: two-group tiles only; narrow outputs take the narrow tiles
@@ -64,7 +79,7 @@ int choose_tile(const GemmDesc& d, int k_per_block) {
   const bool dma_ok = (d.K % gemm::DBK) == 0 && (k_per_block % gemm::DBK) == 0;
   const bool pp_ok = (d.K % gemm::PBK) == 0 && (k_per_block % gemm::PBK) == 0;
   if (d.tile == T_PP_256x256 || d.tile == T_PP_256x192) return pp_ok ? d.tile : (dma_ok ? T_DMA_256x256 : T_128x128);
-  if (d.tile == T_PP_256x128 || d.tile == T_PP_512x64) return pp_ok ? d.tile : T_128x128;
+  if (d.tile == T_PP_256x128 || d.tile == T_PP_512x64 || d.tile == T_PP_128x256 || d.tile == T_PP_64x512) return pp_ok ? d.tile : T_128x128;
   if (d.tile == T_DMA_256x256 || d.tile == T_DMA_256x128) return dma_ok ? d.tile : T_128x128;
   if (d.tile != T_AUTO) return d.tile;
   if (d.N <= 64) return T_128x64;
@@ -86,6 +101,12 @@ int choose_tile(const GemmDesc& d, int k_per_block) {
 }  // namespace
 
 size_t gemm_bf16_partial_elems(int M, int N, int split_k) { return split_k > 1 ? (size_t)M * N * split_k : 0; }
+
+void gemm_bf16_plan_conv_dw(int M, int N, int K, int* tile, int* split_k) {
+  const Plan pl = plan_conv_dw(M, N, K);
+  *tile = pl.tile;
+  *split_k = pl.split;
+}
 
 void gemm_bf16_plan_split(int M, int N, int K, int* tile, int* split_k) {
   *tile = T_AUTO;
@@ -113,10 +134,15 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   if (!d.a_t && d.conv_c <= 0 && d.lda < ((d.K + 7) & ~7)) return hipErrorInvalidValue;
   if (!d.b_t && d.ldb < ((d.K + 7) & ~7)) return hipErrorInvalidValue;
   if (d.a_t && d.lda < ((d.M + 7) & ~7)) return hipErrorInvalidValue;
-  if (d.b_t && d.ldb < ((d.N + 7) & ~7)) return hipErrorInvalidValue;
+  if (d.b_t && !(d.conv_c > 0 && d.a_t) && d.ldb < ((d.N + 7) & ~7)) return hipErrorInvalidValue;
   if (d.bias && !aligned(d.bias, 8)) return hipErrorInvalidValue;
   const bool conv = d.conv_c > 0;
-  if (conv) {
+  const bool conv_dw = conv && d.a_t && d.b_t;
+  if (conv_dw) {   // B is the activation; the reduction runs over its pixels
+    if ((d.conv_c & 7) || d.conv_h < 1 || d.conv_w < 1 || d.conv_h > 4095 || d.conv_w > 4095 || d.N != 9 * d.conv_c ||
+        (d.K % (d.conv_h * d.conv_w)) || (d.K % gemm::PBK) || d.z_outer != 1 || d.z_inner != 1 || !d.c_f32)
+      return hipErrorInvalidValue;
+  } else if (conv) {
     if ((d.conv_c % gemm::PBK) || d.conv_h < 1 || d.conv_w < 1 || d.K != 9 * d.conv_c || (d.M % (d.conv_h * d.conv_w)) ||
         d.a_t || d.b_t || d.split_k > 1 || d.z_outer != 1 || d.z_inner != 1)
       return hipErrorInvalidValue;
@@ -183,7 +209,17 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   }
   int BM, BN;
   gemm::LaunchFn fn;
-  if (conv) {
+  if (conv_dw) {
+    int tile = d.tile;
+    if (tile != T_PP_256x256 && tile != T_PP_256x192 && tile != T_PP_128x256 && tile != T_PP_64x512)
+      tile = plan_conv_dw(d.M, d.N, k_per_block).tile;
+    switch (tile) {
+      case T_PP_64x512: BM = 64; BN = 512; fn = gemm::pp_convdw_64x512(epi); break;
+      case T_PP_128x256: BM = 128; BN = 256; fn = gemm::pp_convdw_128x256(epi); break;
+      case T_PP_256x192: BM = 256; BN = 192; fn = gemm::pp_convdw_256x192(epi); break;
+      default: BM = 256; BN = 256; fn = gemm::pp_convdw_256x256(epi); break;
+    }
+  } else if (conv) {
     switch (choose_conv_tile(d)) {
       case T_PP_512x64: BM = 512; BN = 64; fn = gemm::pp_conv_512x64(epi); break;
       case T_PP_256x128: BM = 256; BN = 128; fn = gemm::pp_conv_256x128(epi); break;
@@ -192,6 +228,8 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
     }
   } else
   switch (choose_tile(d, k_per_block)) {
+    case T_PP_64x512: BM = 64; BN = 512; fn = gemm::pp_64x512(d.a_t, d.b_t, epi); break;
+    case T_PP_128x256: BM = 128; BN = 256; fn = gemm::pp_128x256(d.a_t, d.b_t, epi); break;
     case T_PP_512x64: BM = 512; BN = 64; fn = gemm::pp_512x64(d.a_t, d.b_t, epi); break;
     case T_PP_256x128: BM = 256; BN = 128; fn = gemm::pp_256x128(d.a_t, d.b_t, epi); break;
     case T_128x64: BM = 128; BN = 64; fn = gemm::staged_128x64(d.a_t, d.b_t, epi); break;

@@ -749,6 +749,9 @@ constexpr int PBK = 64;
 // column (tap, c) is input channel c at the pixel shifted by the tap.  cC is a multiple of 64, so
 // a K slice is 64 channels of one tap: the same 128-byte row pieces as in a stored matrix, read
 // from the shifted pixel, or replaced by zeros outside the image.
+// CONV = 2 (weight gradient, AT = BT = true): the B operand [pixel][(tap, c)] is that same matrix,
+// gathered from the activation g.B; the reduction runs over the pixels, 64 per slice, and each
+// 16-byte piece (8 channels of one tap, fixed for a lane) comes from the pixel shifted by its tap.
 template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, int EPI, int CONV = 0>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   constexpr int NW = WGM * WGN;
@@ -779,12 +782,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   const bf16* ga[A_LOADS];
   const bf16* gb[B_LOADS];
   int la[A_LOADS], lb[B_LOADS];
-  static_assert(!CONV || (!AT && !BT), "implicit convolution: row-major operands");
-  int coh[CONV ? A_LOADS : 1], cow[CONV ? A_LOADS : 1];   // CONV: output pixel (h, w) of each piece's row
+  static_assert(CONV != 1 || (!AT && !BT), "implicit convolution, forward: row-major operands");
+  static_assert(CONV != 2 || (AT && BT), "implicit convolution, weight gradient: both operands reduce over rows");
+  int coh[CONV == 1 ? A_LOADS : 1], cow[CONV == 1 ? A_LOADS : 1];   // CONV 1: output pixel (h, w) of each piece's row
 #pragma unroll
   for (int i = 0; i < A_LOADS; i++) {
     const int q = wave * A_LOADS + i;
-    if (CONV) {  // centre tap of the row's pixel
+    if (CONV == 1) {  // centre tap of the row's pixel
       const int row = q * 8 + (lane >> 3), chunk = lane & 7;
       const int m = min(m0 + row, g.M - 1);
       cow[i] = m % g.cW;
@@ -805,10 +809,26 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
       la[i] = pos * 16;
     }
   }
+  // CONV 2: per piece, (dy + 1) << 26 | (dx + 1) << 24 | h << 12 | w for its tap and the pixel (h, w) of its k-row
+  // (cH, cW < 4096), and the tap's element offset
+  int bpix[CONV == 2 ? B_LOADS : 1], boff[CONV == 2 ? B_LOADS : 1];
 #pragma unroll
   for (int i = 0; i < B_LOADS; i++) {
     const int q = wave * B_LOADS + i;
-    if (!BT) {
+    if (CONV == 2) {
+      constexpr int CR = BN / 8;
+      const int pos = q * 64 + lane;
+      const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << 1);
+      int gj = n0 + j * 8;
+      if (gj + 8 > g.N) gj = 0;                 // N = 9 cC is a multiple of 8
+      const int tap = gj / g.cC, ch = gj % g.cC;
+      const int dy = tap / 3 - 1, dx = tap % 3 - 1;
+      const int pix = k_begin + k;
+      bpix[i] = ((dy + 1) << 26) | ((dx + 1) << 24) | (((pix / g.cW) % g.cH) << 12) | (pix % g.cW);
+      boff[i] = (dy * g.cW + dx) * g.cC;
+      gb[i] = B + (long long)pix * g.cC + ch;   // centre tap
+      lb[i] = A_BYTES + pos * 16;
+    } else if (!BT) {
       const int row = q * 8 + (lane >> 3), chunk = lane & 7;
       gb[i] = B + (long long)min(n0 + row, g.N - 1) * g.ldb + k_begin + chunk * 8;
       lb[i] = A_BYTES + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
@@ -823,7 +843,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
     }
   }
   const long long a_step = AT ? (long long)PBK * g.lda : PBK;
-  const long long b_step = BT ? (long long)PBK * g.ldb : PBK;
+  const long long b_step = CONV == 2 ? (long long)PBK * g.cC : (BT ? (long long)PBK * g.ldb : PBK);
+  // CONV 2: a slice moves every piece 64 pixels on: (h, w) advance by (64 / cW, 64 % cW) with carries
+  const int b_sw = CONV == 2 ? PBK % g.cW : 0, b_sh = CONV == 2 ? (PBK / g.cW) % g.cH : 0;
 
   f32x16 acc[MI][NI];
 #pragma unroll
@@ -884,10 +906,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   // of that slice from the centre tap, and per lane one bit per piece: "the registers hold data"
   // (as opposed to a pixel outside the image, stored as zeros)
   int c_dy = -1, c_dx = -1, c_sub = 0;
-  long long c_off_a = CONV ? -(long long)(g.cW + 1) * g.cC : 0;
+  long long c_off_a = CONV == 1 ? -(long long)(g.cW + 1) * g.cC : 0;
   unsigned c_ok = 0;
   auto conv_load = [&](int i) {
-    const bool ok = (unsigned)(coh[CONV ? i : 0] + c_dy) < (unsigned)g.cH && (unsigned)(cow[CONV ? i : 0] + c_dx) < (unsigned)g.cW;
+    const bool ok = (unsigned)(coh[CONV == 1 ? i : 0] + c_dy) < (unsigned)g.cH && (unsigned)(cow[CONV == 1 ? i : 0] + c_dx) < (unsigned)g.cW;
     ra[i] = *(const u32x4*)(ga[i] + (ok ? c_off_a : 0));
     c_ok = ok ? (c_ok | (1u << i)) : (c_ok & ~(1u << i));
   };
@@ -904,26 +926,47 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   auto load_a_regs = [&](bool advance) {
 #pragma unroll
     for (int i = 0; i < A_LOADS; i++) {
-      if (CONV) {
+      if (CONV == 1) {
         conv_load(i);
       } else {
         ra[i] = *(const u32x4*)ga[i];
         ga[i] += advance ? a_step : 0;
       }
     }
-    if (CONV) conv_advance(advance);
+    if (CONV == 1) conv_advance(advance);
+  };
+  unsigned b_ok = 0;   // CONV 2: per lane one bit per piece, "the registers hold data"
+  auto conv_load_b = [&](int i, bool advance) {
+    const int k = CONV == 2 ? i : 0;
+    const int dy = (bpix[k] >> 26) - 1, dx = ((bpix[k] >> 24) & 3) - 1;
+    int h = (bpix[k] >> 12) & 4095, w = bpix[k] & 4095;
+    const bool ok = (unsigned)(h + dy) < (unsigned)g.cH && (unsigned)(w + dx) < (unsigned)g.cW;
+    rb[i] = *(const u32x4*)(gb[i] + (ok ? boff[k] : 0));
+    b_ok = ok ? (b_ok | (1u << i)) : (b_ok & ~(1u << i));
+    if (advance) {
+      gb[i] += b_step;
+      w += b_sw;
+      h += b_sh;
+      if (w >= g.cW) { w -= g.cW; h++; }
+      if (h >= g.cH) h -= g.cH;
+      bpix[k] = (bpix[k] & ~0xffffff) | (h << 12) | w;
+    }
   };
   auto load_b_regs = [&](bool advance) {
 #pragma unroll
     for (int i = 0; i < B_LOADS; i++) {
-      rb[i] = *(const u32x4*)gb[i];
-      gb[i] += advance ? b_step : 0;
+      if (CONV == 2) {
+        conv_load_b(i, advance);
+      } else {
+        rb[i] = *(const u32x4*)gb[i];
+        gb[i] += advance ? b_step : 0;
+      }
     }
   };
   auto store_a = [&](unsigned char* st) {
 #pragma unroll
     for (int i = 0; i < A_LOADS; i++) {
-      if (CONV) {
+      if (CONV == 1) {
         const u32x4 zero = {0u, 0u, 0u, 0u};
         *(u32x4*)(st + la[i]) = ((c_ok >> i) & 1u) ? ra[i] : zero;
       } else {
@@ -933,7 +976,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   };
   auto store_b = [&](unsigned char* st) {
 #pragma unroll
-    for (int i = 0; i < B_LOADS; i++) *(u32x4*)(st + lb[i]) = rb[i];
+    for (int i = 0; i < B_LOADS; i++) {
+      if (CONV == 2) {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        *(u32x4*)(st + lb[i]) = ((b_ok >> i) & 1u) ? rb[i] : zero;
+      } else {
+        *(u32x4*)(st + lb[i]) = rb[i];
+      }
+    }
   };
 
   const int group = wave >> 2;
@@ -990,7 +1040,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       block_barrier();
       c_phase(std::integral_constant<int, A_LOADS>(), [&](int i) {
-        if (CONV) {
+        if (CONV == 1) {
           conv_load(i);
           if (i == A_LOADS - 1) conv_advance(adv);
         } else {
@@ -1004,8 +1054,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       block_barrier();
       c_phase(std::integral_constant<int, B_LOADS>(), [&](int i) {
-        rb[i] = *(const u32x4*)gb[i];
-        gb[i] += adv ? b_step : 0;
+        if (CONV == 2) {
+          conv_load_b(i, adv);
+        } else {
+          rb[i] = *(const u32x4*)gb[i];
+          gb[i] += adv ? b_step : 0;
+        }
       });
     }
   }
@@ -1030,6 +1084,13 @@ LaunchFn pp_conv_256x256(int epi);
 LaunchFn pp_conv_256x192(int epi);
 LaunchFn pp_conv_256x128(int epi);
 LaunchFn pp_conv_512x64(int epi);
+// tiles for weight gradients with few output rows, and the implicit weight gradient of a 3x3 convolution
+LaunchFn pp_128x256(bool a_t, bool b_t, int epi);
+LaunchFn pp_64x512(bool a_t, bool b_t, int epi);
+LaunchFn pp_convdw_256x256(int epi);
+LaunchFn pp_convdw_256x192(int epi);
+LaunchFn pp_convdw_128x256(int epi);
+LaunchFn pp_convdw_64x512(int epi);
 
 }  // namespace gemm
 }  // namespace et

@@ -1,5 +1,5 @@
 // Instantiations of the two-group bf16 GEMM kernel for one tile shape (see gemm_bf16_kernels.h):
-// the plain product and the implicit 3x3 convolution.
+// the plain product and the implicit 3x3 convolution (forward / gradient passing, weight gradient).
 #include "gemm_bf16_kernels.h"
 
 namespace et {

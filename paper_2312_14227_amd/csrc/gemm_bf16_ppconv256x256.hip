@@ -1,5 +1,5 @@
 // Instantiations of the two-group bf16 GEMM kernel for one tile shape (see gemm_bf16_kernels.h):
-// the plain product and the implicit 3x3 convolution.
+// the plain product and the implicit 3x3 convolution (forward / gradient passing, weight gradient).
 #include "gemm_bf16_kernels.h"
 
 namespace et {
@@ -14,7 +14,6 @@ hipError_t launch(const Params& p, dim3 grid, hipStream_t s) {
 
 }  // namespace
 
-
 LaunchFn pp_conv_256x256(int epi) {
 #define ET_PICK(E) \
   if (epi == E) return launch<false, false, E, 1>;
@@ -23,6 +22,12 @@ LaunchFn pp_conv_256x256(int epi) {
   ET_PICK(E_AFFINE)
   ET_PICK(E_RELU_MASK)
 #undef ET_PICK
+  return nullptr;
+}
+
+LaunchFn pp_convdw_256x256(int epi) {
+  if (epi == E_F32) return launch<true, true, E_F32, 2>;
+  if (epi == E_PARTIAL) return launch<true, true, E_PARTIAL, 2>;
   return nullptr;
 }
 

@@ -11,9 +11,10 @@
 // A convolution whose input channels come in multiples of 64 runs as an implicit GEMM: the
 // forward product gathers the im2col rows from the activation, and dy() is the same kind of
 // convolution of the output gradient with the mirrored weight, its epilogue applying the ReLU
-// mask of the previous layer; only dw() materialises the im2col matrix (inside its own timed
-// region, in a buffer shared by all layers).  Other convolutions (the first one) keep the
-// matrix from the forward pass and pass the gradient through d * W and the adjoint of im2col.
+// mask of the previous layer; dw() gathers the same rows as the B operand of d^T * cols, reduced
+// over the pixels.  The im2col matrix of such a layer is never written.  Other convolutions (the
+// first one) keep the matrix from the forward pass and pass the gradient through d * W and the
+// adjoint of im2col.
 #include "conv_chain.h"
 
 namespace {
@@ -27,6 +28,23 @@ inline const bf16* conv_matrix(const et_ctx* c, size_t i) {
 // implicit forward product / implicit dy() of a unit
 inline bool implicit_fwd(const ConvUnit& u) { return (u.Cin % 64) == 0; }
 inline bool implicit_dy(const ConvUnit& u) { return (u.Cout % 64) == 0 && (u.Cin % 8) == 0; }
+inline bool implicit_dw(const et_ctx* c, const ConvUnit& u) {
+  return (u.Cin % 8) == 0 && ((size_t)c->desc.batch * u.H * u.W) % 64 == 0 && u.H < 4096 && u.W < 4096;
+}
+
+// dw() of a convolution whose im2col matrix is not stored
+inline et::GemmDesc conv_dw_implicit(et_ctx* c, const ConvUnit& u, const bf16* d, float* dW) {
+  const int M = (int)((size_t)c->desc.batch * u.H * u.W);
+  et::GemmDesc g;
+  g.A = d; g.a_t = true; g.lda = u.Cout; g.B = u.in; g.b_t = true; g.ldb = 9 * u.Cin;
+  g.M = u.Cout; g.N = 9 * u.Cin; g.K = M;
+  g.C = dW; g.ldc = 9 * u.Cin; g.c_f32 = true;
+  g.conv_h = u.H; g.conv_w = u.W; g.conv_c = u.Cin;
+  et::gemm_bf16_plan_conv_dw(g.M, g.N, g.K, &g.tile, &g.split_k);
+  g.partials = c->gemm_partials;
+  if (et::gemm_bf16_partial_elems(g.M, g.N, g.split_k) > c->gemm_partial_elems) g.split_k = 1;
+  return g;
+}
 
 // A hidden linear layer on a small batch is one row of output tiles streaming the whole weight
 // matrix: split over the input features so that every CU streams a part, then reduce, add the
@@ -87,9 +105,15 @@ int build_vgg(et_ctx* c) {
     if (implicit_dy(u)) max_flip = std::max(max_flip, (size_t)u.Cout * 9 * u.Cin);
     reserve(c, &u.y, b16 * M * u.Cout);
     max_act = std::max(max_act, std::max(M * u.Cout, M * round8(u.Cin)));
-    max_cols = std::max(max_cols, M * u.Kc);
+    if (!implicit_dw(c, u) || !implicit_dy(u)) max_cols = std::max(max_cols, M * u.Kc);
     max_cs = std::max(max_cs, et::colsum_partial_elems((int)M, u.Cout));
-    pe = std::max(pe, et::gemm_bf16_partial_elems(u.Cout, u.Kc, split_for(u.Cout, u.Kc, (int)M)));
+    if (implicit_dw(c, u)) {
+      int tile, split;
+      et::gemm_bf16_plan_conv_dw(u.Cout, 9 * u.Cin, (int)M, &tile, &split);
+      pe = std::max(pe, et::gemm_bf16_partial_elems(u.Cout, 9 * u.Cin, split));
+    } else {
+      pe = std::max(pe, et::gemm_bf16_partial_elems(u.Cout, u.Kc, split_for(u.Cout, u.Kc, (int)M)));
+    }
     const bool last_of_stage = i + 1 == c->vconv.size() || c->vstage[i + 1] != c->vstage[i];
     if (last_of_stage) {
       reserve(c, &c->vpool[c->vstage[i]], b16 * (M / 4) * u.Cout);
@@ -246,7 +270,9 @@ int vgg_backward(et_ctx* c, const void* x, const uint8_t* mask) {
     }
     if (sel(t)) {
       Region r(c, PH_DW, t);
-      if (implicit_fwd(u)) {   // the im2col matrix exists only here
+      if (implicit_dw(c, u)) {
+        ET_G(conv_dw_implicit(c, u, dcur, c->grad[t]));
+      } else if (implicit_fwd(u)) {   // the im2col matrix exists only here
         ET_KB(1, 2.0 * ((double)M * u.Cin + (double)M * u.Kc), et::im2col(u.in, c->rdcols, geom(c, u), s));
         ET_G(linear_dw(c, dcur, u.Cout, c->rdcols, u.Kc, c->grad[t], (int)M, u.Cout, u.Kc));
       } else if (u.Kc == 9 * u.Cin) {

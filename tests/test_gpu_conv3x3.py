@@ -63,3 +63,49 @@ def test_conv3x3_rejects_bad_arguments():
     assert et.et_debug_conv3x3(p, p, p, 1, 8, 8, 48, 64) == -1        # channels not a multiple of 64
     assert et.et_debug_conv3x3(p, p, p, 0, 8, 8, 64, 64) == -1
     assert et.et_debug_conv3x3(p + 2, p, p, 1, 8, 8, 64, 64) == -1    # misaligned
+
+
+def _case_dw(batch, H, W, C, N, split, tile, seed):
+    import torch
+    from paper_2312_14227_amd import binding as et
+    rng = np.random.default_rng(seed)
+    x = bf16_round(rng.standard_normal((batch, H, W, C)).astype(np.float32))
+    d = bf16_round(rng.standard_normal((batch, H, W, N)).astype(np.float32))
+    cv = R.Conv(x.astype(np.float64), np.zeros((N, 3, 3, C)), 1)
+    ref = cv.dw(d.astype(np.float64)).reshape(N, 9 * C)
+    scale = np.abs(d.reshape(-1, N).astype(np.float64)).T @ np.abs(cv.cols.reshape(batch * H * W, -1))
+    dev = "cuda:0"
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(torch.bfloat16)
+    xt, dt = to(x), to(d)
+    out = torch.full((N, 9 * C), float("nan"), device=dev, dtype=torch.float32)
+    part = torch.empty(N * 9 * C * 64, device=dev, dtype=torch.float32)
+    st = et.et_debug_conv3x3_dw(xt.data_ptr(), dt.data_ptr(), out.data_ptr(), batch, H, W, C, N, split, part.data_ptr(),
+                                tile, torch.cuda.current_stream().cuda_stream)
+    assert st == 0
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    bound = 2e-6 * scale * np.sqrt(batch * H * W) + 1e-6
+    bad = ~(np.abs(got - ref) <= bound)
+    assert not bad.any(), (int(bad.sum()), float(np.nanmax(np.abs(got - ref))))
+
+
+@pytest.mark.parametrize("tile", [11, 13, 19, 21])
+@pytest.mark.parametrize("batch,H,W,C,N,split", [(1, 8, 8, 8, 8, 1), (2, 16, 16, 64, 64, 1), (4, 8, 8, 24, 40, 2), (1, 32, 24, 64, 128, 3),
+                                                 (2, 14, 16, 128, 264, 1), (3, 7, 64, 16, 520, 5)])
+def test_conv3x3_weight_gradient(batch, H, W, C, N, split, tile):
+    _case_dw(batch, H, W, C, N, split, tile, seed=tile + H + N)
+
+
+@pytest.mark.parametrize("batch,H,W,C,N", [(2, 32, 32, 64, 64), (2, 16, 16, 128, 128), (4, 16, 16, 256, 512)])
+def test_conv3x3_weight_gradient_planned(batch, H, W, C, N):
+    _case_dw(batch, H, W, C, N, 0, 0, seed=C + N)
+
+
+def test_conv3x3_weight_gradient_rejects_bad_arguments():
+    import torch
+    from paper_2312_14227_amd import binding as et
+    t = torch.zeros(1 << 20, device="cuda:0", dtype=torch.float32)
+    p = t.data_ptr()
+    assert et.et_debug_conv3x3_dw(p, p, p, 1, 8, 8, 12, 64) == -1     # channels not a multiple of 8
+    assert et.et_debug_conv3x3_dw(p, p, p, 1, 5, 5, 8, 64) == -1      # pixels not a multiple of 64
+    assert et.et_debug_conv3x3_dw(p, p, p, 1, 8, 8, 8, 64, 2, 0) == -1  # split without partials

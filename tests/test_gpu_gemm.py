@@ -103,7 +103,7 @@ def test_gemm_two_group_tile(M, N, K, a_t, b_t, tile):
     _run(M, N, K, a_t, b_t, 0, True, False, 1, tile, seed=tile + N)
 
 
-@pytest.mark.parametrize("tile", [11, 13, 15, 17])
+@pytest.mark.parametrize("tile", [11, 13, 15, 17, 19, 21])
 def test_gemm_two_group_tile_split_k(tile):
     _run(768, 520, 4992, 1, 1, 1, False, False, 6, tile, seed=3)
 
