@@ -136,6 +136,6 @@ def vgg_step(cfg, weights, x, y, mask, store=None, cols_stored=lambda cin, cout:
     # where the column gradient of a convolution is a stored tensor, give its Conv the hook
     for u in units:
         cout, _, _, cin = W[u["t"]].shape
-        u["conv"].q = q if cols_stored(cin, cout) else _same
+        u["conv"].q_cols = q if cols_stored(cin, cout) else _same
     grads, work = _run_chain(chain, mask, state)
     return dict(loss=loss, grads=grads, work=work, logits=c["logits"])

@@ -1,7 +1,9 @@
 // Convolution units shared by the convolutional chains: a convolution is a GEMM over the rows of
-// an im2col matrix kept from the forward pass (a 1x1 stride-1 convolution reads the activation
-// itself): forward cols * W^T, dw() d^T * cols (split over the rows), dy() d * W followed by the
-// gather-form adjoint of im2col.
+// an im2col matrix (a 1x1 stride-1 convolution reads the activation itself): forward cols * W^T,
+// dw() d^T * cols (split over the rows), dy() d * W followed by the gather-form adjoint of im2col.
+// A 3x3 / stride 1 convolution with channel counts in multiples of 64 never writes that matrix:
+// the forward product and dw() gather its rows from the activation inside the GEMM, and dy() is
+// the same kind of convolution of the output gradient with the mirrored weight.
 #pragma once
 #include "context.h"
 
@@ -33,18 +35,35 @@ inline void init_unit(ConvUnit& u, int t, int H, int W, int Cin, int Cout, int k
 
 inline size_t rows_of(const et_ctx* c, const ConvUnit& u) { return (size_t)c->desc.batch * u.Ho * u.Wo; }
 inline bool needs_cols(const ConvUnit& u) { return u.k > 1 || u.stride > 1; }
+// which of the three products of a unit run as implicit GEMMs
+inline bool implicit_fwd(const ConvUnit& u) { return u.k == 3 && u.stride == 1 && (u.Cin % 64) == 0; }
+inline bool implicit_dy(const ConvUnit& u) { return u.k == 3 && u.stride == 1 && (u.Cout % 64) == 0 && (u.Cin % 8) == 0; }
+inline bool implicit_dw(const et_ctx* c, const ConvUnit& u) {
+  return u.k == 3 && u.stride == 1 && (u.Cin % 8) == 0 && ((size_t)c->desc.batch * u.H * u.W) % 64 == 0 && u.H < 4096 && u.W < 4096;
+}
+// fp32 partial elements of a unit's weight gradient with the split its plan chooses
+inline size_t conv_dw_partials(const et_ctx* c, const ConvUnit& u) {
+  const int M = (int)rows_of(c, u);
+  int tile, split;
+  if (implicit_dw(c, u)) {
+    et::gemm_bf16_plan_conv_dw(u.Cout, 9 * u.Cin, M, &tile, &split);
+    return et::gemm_bf16_partial_elems(u.Cout, 9 * u.Cin, split);
+  }
+  return et::gemm_bf16_partial_elems(u.Cout, u.Kc, split_for(u.Cout, u.Kc, M));
+}
 
 // z = cols(in) * Wm^T; with gain/shift the GEMM epilogue also writes y = max(z * gain + shift, 0)
 inline int conv_forward(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16* Wm, void* z, bool z_f32,
                  const bf16* gain = nullptr, const bf16* shift = nullptr, bf16* y = nullptr, const bf16* branch = nullptr,
                  const bf16* gain2 = nullptr, const bf16* shift2 = nullptr) {
   const bf16* A = in;
-  if (needs_cols(u)) {
+  if (needs_cols(u) && !implicit_fwd(u)) {
     ET_KB(1, 2.0 * ((double)c->desc.batch * u.H * u.W * u.Cin + (double)rows_of(c, u) * u.Kc),
           et::im2col(in, u.cols, geom(c, u), c->stream));
     A = u.cols;
   }
   et::GemmDesc g = linear_fwd(A, Wm, nullptr, (int)rows_of(c, u), u.Cout, u.Kc);
+  if (implicit_fwd(u)) { g.conv_h = u.H; g.conv_w = u.W; g.conv_c = u.Cin; }
   g.C = z; g.c_f32 = z_f32;
   if (gain) {
     g.mode = et::EPI_AFFINE_RELU; g.gain = gain; g.bias = shift; g.C2 = y;
@@ -57,6 +76,24 @@ inline int conv_forward(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16
 }
 
 inline int conv_dw(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16* d, float* dW) {
+  if (implicit_dw(c, u)) {   // B operand: the activation standing for its im2col matrix
+    et::GemmDesc g;
+    g.A = d; g.a_t = true; g.lda = u.Cout; g.B = in; g.b_t = true; g.ldb = 9 * u.Cin;
+    g.M = u.Cout; g.N = 9 * u.Cin; g.K = (int)rows_of(c, u);
+    g.C = dW; g.ldc = 9 * u.Cin; g.c_f32 = true;
+    g.conv_h = u.H; g.conv_w = u.W; g.conv_c = u.Cin;
+    et::gemm_bf16_plan_conv_dw(g.M, g.N, g.K, &g.tile, &g.split_k);
+    g.partials = c->gemm_partials;
+    if (et::gemm_bf16_partial_elems(g.M, g.N, g.split_k) > c->gemm_partial_elems) g.split_k = 1;
+    ET_G(g);
+    return ET_OK;
+  }
+  if (implicit_fwd(u)) {     // the im2col matrix exists only here, in the shared column buffer
+    ET_KB(1, 2.0 * ((double)c->desc.batch * u.H * u.W * u.Cin + (double)rows_of(c, u) * u.Kc),
+          et::im2col(in, c->rdcols, geom(c, u), c->stream));
+    ET_G(linear_dw(c, d, u.Cout, c->rdcols, u.Kc, dW, (int)rows_of(c, u), u.Cout, u.Kc));
+    return ET_OK;
+  }
   const bf16* A = needs_cols(u) ? u.cols : in;
   ET_G(linear_dw(c, d, u.Cout, A, u.Kc, dW, (int)rows_of(c, u), u.Cout, u.Kc));
   return ET_OK;
@@ -70,5 +107,17 @@ inline int conv_dcols(et_ctx* c, const ConvUnit& u, const bf16* d, const bf16* W
   return ET_OK;
 }
 
+
+// dy() of a 3x3 / stride 1 unit as an implicit GEMM: out = (convolution of d with the mirrored weight), times
+// the ReLU mask (relu_y > 0) if given; c->wflip receives the mirrored weight [Cin][3][3][Cout]
+inline int conv_dy_implicit(et_ctx* c, const ConvUnit& u, const bf16* d, const bf16* W, const bf16* relu_y, bf16* out) {
+  ET_K(1, et::flip3x3(W, c->wflip, u.Cout, u.Cin, c->stream));
+  et::GemmDesc g = linear_fwd(d, c->wflip, nullptr, (int)rows_of(c, u), u.Cin, 9 * u.Cout);
+  g.conv_h = u.H; g.conv_w = u.W; g.conv_c = u.Cout;
+  g.C = out;
+  if (relu_y) { g.mode = et::EPI_RELU_MASK; g.U = relu_y; }
+  ET_G(g);
+  return ET_OK;
+}
 
 }  // namespace et_exec

@@ -10,8 +10,10 @@
 // A convolution is a GEMM over the rows of an im2col matrix kept from the forward pass (a 1x1
 // stride-1 convolution reads the activation itself): forward cols * W^T, dw() d^T * cols (split
 // over the rows), dy() d * W followed by the gather-form adjoint of im2col fused with the branch
-// sum and the ReLU mask.  The stem's convolution output stays fp32 so that the max-pooling
-// argmax is decided on unrounded values.
+// sum and the ReLU mask.  The 3x3 / stride 1 convolutions run as implicit GEMMs instead (the
+// matrix is gathered from the activation inside the kernel; dy() is a convolution with the
+// mirrored weight whose epilogue applies the ReLU mask).  The stem's convolution output stays
+// fp32 so that the max-pooling argmax is decided on unrounded values.
 #include "conv_chain.h"
 
 
@@ -63,19 +65,20 @@ int build_resnet(et_ctx* c) {
   add("head.W", (size_t)C * Cf); add("head.b", C);
 
   // ---- workspace
-  size_t max_act = 0, max_cols = 0, max_cs = 0, pe = 0;
+  size_t max_act = 0, max_cols = 0, max_cs = 0, pe = 0, max_flip = 8;
   auto act = [&](size_t rows, size_t ch) {
     max_act = std::max(max_act, rows * ch);
     max_cs = std::max(max_cs, et::colsum_partial_elems((int)rows, (int)ch));
   };
   auto wg = [&](const ConvUnit& u) {
     const int M = (int)rows_of(c, u);
-    pe = std::max(pe, et::gemm_bf16_partial_elems(u.Cout, u.Kc, split_for(u.Cout, u.Kc, M)));
+    pe = std::max(pe, conv_dw_partials(c, u));
     max_cols = std::max(max_cols, (size_t)M * u.Kc);   // the column gradient of any unit fits rdcols
+    if (implicit_dy(u)) max_flip = std::max(max_flip, (size_t)u.Cout * 9 * u.Cin);
   };
   auto unit = [&](ConvUnit& u, bool with_y) {
     const size_t M = rows_of(c, u);
-    if (needs_cols(u)) reserve(c, &u.cols, b16 * M * u.Kc);
+    if (needs_cols(u) && !implicit_fwd(u)) reserve(c, &u.cols, b16 * M * u.Kc);
     reserve(c, &u.z, b16 * M * u.Cout);
     if (with_y) reserve(c, &u.y, b16 * M * u.Cout);
     act(M, u.Cout);
@@ -115,6 +118,7 @@ int build_resnet(et_ctx* c) {
   reserve(c, &c->rdsum, b16 * max_act);
   reserve(c, &c->rdsc, b16 * max_act);
   reserve(c, &c->rdcols, b16 * std::max<size_t>(max_cols, 8));
+  reserve(c, &c->wflip, b16 * max_flip);
   c->gemm_partial_elems = pe;
   reserve(c, &c->gemm_partials, f32 * std::max<size_t>(pe, 64));
   reserve(c, &c->colsum_partials, f32 * std::max<size_t>(max_cs, 64));
@@ -277,8 +281,12 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
     }
     if (pass(t + 3)) {  // through the 3x3 convolution and the ReLU after c1
       Region r(c, PH_DY, t + 3);
-      if ((rc = conv_dcols(c, b.c2, c->rd[0], Wt(t + 3), c->rdcols)) != ET_OK) return rc;
-      ET_KB(1, 2.0 * M2 * b.c2.Kc + 4.0 * M1 * b.c1.Cout, et::col2im(c->rdcols, nullptr, b.c1.y, c->rd[1], geom(c, b.c2), s));
+      if (implicit_dy(b.c2)) {
+        if ((rc = conv_dy_implicit(c, b.c2, c->rd[0], Wt(t + 3), b.c1.y, c->rd[1])) != ET_OK) return rc;
+      } else {
+        if ((rc = conv_dcols(c, b.c2, c->rd[0], Wt(t + 3), c->rdcols)) != ET_OK) return rc;
+        ET_KB(1, 2.0 * M2 * b.c2.Kc + 4.0 * M1 * b.c1.Cout, et::col2im(c->rdcols, nullptr, b.c1.y, c->rd[1], geom(c, b.c2), s));
+      }
     }
     // c1
     if (sel(t + 2)) {

@@ -25,27 +25,6 @@ inline const bf16* conv_matrix(const et_ctx* c, size_t i) {
   return u.Kc == 9 * u.Cin ? (const bf16*)c->w[u.t] : c->stem_w8;
 }
 
-// implicit forward product / implicit dy() of a unit
-inline bool implicit_fwd(const ConvUnit& u) { return (u.Cin % 64) == 0; }
-inline bool implicit_dy(const ConvUnit& u) { return (u.Cout % 64) == 0 && (u.Cin % 8) == 0; }
-inline bool implicit_dw(const et_ctx* c, const ConvUnit& u) {
-  return (u.Cin % 8) == 0 && ((size_t)c->desc.batch * u.H * u.W) % 64 == 0 && u.H < 4096 && u.W < 4096;
-}
-
-// dw() of a convolution whose im2col matrix is not stored
-inline et::GemmDesc conv_dw_implicit(et_ctx* c, const ConvUnit& u, const bf16* d, float* dW) {
-  const int M = (int)((size_t)c->desc.batch * u.H * u.W);
-  et::GemmDesc g;
-  g.A = d; g.a_t = true; g.lda = u.Cout; g.B = u.in; g.b_t = true; g.ldb = 9 * u.Cin;
-  g.M = u.Cout; g.N = 9 * u.Cin; g.K = M;
-  g.C = dW; g.ldc = 9 * u.Cin; g.c_f32 = true;
-  g.conv_h = u.H; g.conv_w = u.W; g.conv_c = u.Cin;
-  et::gemm_bf16_plan_conv_dw(g.M, g.N, g.K, &g.tile, &g.split_k);
-  g.partials = c->gemm_partials;
-  if (et::gemm_bf16_partial_elems(g.M, g.N, g.split_k) > c->gemm_partial_elems) g.split_k = 1;
-  return g;
-}
-
 // A hidden linear layer on a small batch is one row of output tiles streaming the whole weight
 // matrix: split over the input features so that every CU streams a part, then reduce, add the
 // bias and apply the ReLU (the same single rounding as the fused epilogue).
@@ -107,13 +86,7 @@ int build_vgg(et_ctx* c) {
     max_act = std::max(max_act, std::max(M * u.Cout, M * round8(u.Cin)));
     if (!implicit_dw(c, u) || !implicit_dy(u)) max_cols = std::max(max_cols, M * u.Kc);
     max_cs = std::max(max_cs, et::colsum_partial_elems((int)M, u.Cout));
-    if (implicit_dw(c, u)) {
-      int tile, split;
-      et::gemm_bf16_plan_conv_dw(u.Cout, 9 * u.Cin, (int)M, &tile, &split);
-      pe = std::max(pe, et::gemm_bf16_partial_elems(u.Cout, 9 * u.Cin, split));
-    } else {
-      pe = std::max(pe, et::gemm_bf16_partial_elems(u.Cout, u.Kc, split_for(u.Cout, u.Kc, (int)M)));
-    }
+    pe = std::max(pe, conv_dw_partials(c, u));
     const bool last_of_stage = i + 1 == c->vconv.size() || c->vstage[i + 1] != c->vstage[i];
     if (last_of_stage) {
       reserve(c, &c->vpool[c->vstage[i]], b16 * (M / 4) * u.Cout);
@@ -270,12 +243,7 @@ int vgg_backward(et_ctx* c, const void* x, const uint8_t* mask) {
     }
     if (sel(t)) {
       Region r(c, PH_DW, t);
-      if (implicit_dw(c, u)) {
-        ET_G(conv_dw_implicit(c, u, dcur, c->grad[t]));
-      } else if (implicit_fwd(u)) {   // the im2col matrix exists only here
-        ET_KB(1, 2.0 * ((double)M * u.Cin + (double)M * u.Kc), et::im2col(u.in, c->rdcols, geom(c, u), s));
-        ET_G(linear_dw(c, dcur, u.Cout, c->rdcols, u.Kc, c->grad[t], (int)M, u.Cout, u.Kc));
-      } else if (u.Kc == 9 * u.Cin) {
+      if (u.Kc == 9 * u.Cin) {
         if ((rc = conv_dw(c, u, u.in, dcur, c->grad[t])) != ET_OK) return rc;
       } else {
         if ((rc = conv_dw(c, u, u.in, dcur, c->stem_dw8)) != ET_OK) return rc;
@@ -290,15 +258,7 @@ int vgg_backward(et_ctx* c, const void* x, const uint8_t* mask) {
       const bool same_stage = c->vstage[i - 1] == c->vstage[i];
       if (implicit_dy(u)) {
         // input gradient = 3x3 convolution of d with the mirrored weight [Cin][3][3][Cout]
-        ET_K(1, et::flip3x3(Wt(t), c->wflip, u.Cout, u.Cin, s));
-        et::GemmDesc g = linear_fwd(dcur, c->wflip, nullptr, (int)M, u.Cin, 9 * u.Cout);
-        g.conv_h = u.H; g.conv_w = u.W; g.conv_c = u.Cout;
-        if (same_stage) {
-          g.mode = et::EPI_RELU_MASK; g.U = p.y; g.C = dn;
-        } else {
-          g.C = c->rd[2];
-        }
-        ET_G(g);
+        if ((rc = conv_dy_implicit(c, u, dcur, Wt(t), same_stage ? p.y : nullptr, same_stage ? dn : c->rd[2])) != ET_OK) return rc;
         if (!same_stage)
           ET_KB(1, 3.0 * nin + 16.0 * nin, et::maxpool2x2_bwd(c->rd[2], c->varg[c->vstage[i - 1]], p.y, dn, B, p.Ho, p.Wo, p.Cout, s));
         dcur = dn;

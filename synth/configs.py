@@ -98,6 +98,8 @@ CONFIGS = {
     "resnet50": ResNetConfig("resnet50", 32, 224, 3, 64, (3, 4, 6, 3), (64, 128, 256, 512), 200),
     "resnet_tiny": ResNetConfig("resnet_tiny", 2, 16, 3, 8, (1, 1), (8, 8), 8),
     "resnet_small": ResNetConfig("resnet_small", 3, 64, 3, 16, (2, 1, 2, 1), (8, 16, 24, 32), 24),
+    # bottleneck width 64: the 3x3 convolutions that run as implicit GEMMs (stride 1) next to a strided one
+    "resnet_c64": ResNetConfig("resnet_c64", 2, 32, 3, 64, (2, 1), (64, 128), 16),
     # second CNN family of the paper's evaluation (Section 8): VGG16 shape, 200 classes
     "vgg16": VGGConfig("vgg16", 32, 224, 3, (64, 128, 256, 512, 512), (2, 2, 3, 3, 3), (4096, 4096), 200),
     "vgg_tiny": VGGConfig("vgg_tiny", 2, 8, 3, (8, 8), (1, 2), (16,), 8),

@@ -61,7 +61,9 @@ def main():
         # a bf16 evaluation of a deep ReLU network is not a rounding of the exact gradient: the stored
         # reference rounds the tensors the bf16 data layout keeps in memory (see oracle/resnet.py)
         from oracle import resnet
-        r = resnet.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights), store=resnet.round_bf16)
+        # (no stored column gradient for the 3x3 / stride 1 convolutions, which pass gradients as implicit GEMMs)
+        r = resnet.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights), store=resnet.round_bf16,
+                               cols_stored=lambda cin, cout, stride: not (stride == 1 and cout % 64 == 0 and cin % 8 == 0))
         I = oimp.importance_from_grads(r["grads"], wl.weights, wl.snapshot)
     elif cfg.kind == "vgg":
         r = vgg_in_chunks(cfg, wl, 8)

@@ -30,19 +30,29 @@ def _run(s, xt, yt, mask):
     return loss, [g.cpu().numpy() for g in s.grad]
 
 
-@pytest.mark.parametrize("name,seed,init", [("resnet_tiny", 0, "random"), ("resnet_tiny", 1, "paper"),
-                                            ("resnet_small", 2, "random"), ("resnet_small", 3, "paper")])
-def test_resnet_masks_match_oracle(name, seed, init):
+def _cols_stored(cin, cout, stride):
+    """Data layout of the HIP path: a 3x3 / stride 1 convolution with 64 k output channels passes the gradient
+    to its input as an implicit GEMM and never stores the column gradient."""
+    return not (stride == 1 and cout % 64 == 0 and cin % 8 == 0)
+
+
+# resnet_c64 reduces over 576 and more terms: now and then fp32 and float64 sums round to different bf16
+# values, and one flipped ReLU decision moves a gradient by a few 1e-3; its bound is the workload
+# tolerance itself, the cases without flips keep a tenth of it.
+@pytest.mark.parametrize("name,seed,init,factor", [("resnet_tiny", 0, "random", 0.1), ("resnet_tiny", 1, "paper", 0.1),
+                                                   ("resnet_small", 2, "random", 0.1), ("resnet_small", 3, "paper", 0.1),
+                                                   ("resnet_c64", 4, "random", 1.0), ("resnet_c64", 5, "paper", 1.0)])
+def test_resnet_masks_match_oracle(name, seed, init, factor):
     cfg = CONFIGS[name]
     wl = make_workload(cfg, seed=seed, init=init)
     N = len(wl.weights)
     ones = [1] * N
-    ref = R.resnet_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16)
+    ref = R.resnet_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16, cols_stored=_cols_stored)
     exact = R.resnet_step(cfg, wl.weights, wl.x, wl.y, ones)
     s = _session(cfg, wl)
     xt, yt = s.put_input(wl.x, wl.y)
     rng = np.random.default_rng(seed)
-    tol = 0.1 * tol_for(cfg)            # same rounding points on both sides: far inside the bf16 bound
+    tol = factor * tol_for(cfg)         # same rounding points on both sides: far inside the bf16 bound
     worst = worst_exact = 0.0
     layout, t_head = R.block_layout(cfg)
     extra = [t for (_, _, _, proj, t) in layout] + [t + 9 for (_, _, _, proj, t) in layout if proj] + \
