@@ -132,3 +132,26 @@ def test_batch_mean_gradient_is_the_mean_over_chunks_also_with_storage_rounding(
         for k in range(N):
             np.testing.assert_allclose(whole["grads"][k], 0.5 * (parts[0]["grads"][k] + parts[1]["grads"][k]),
                                        rtol=1e-11, atol=1e-15)
+
+
+def test_rounding_noise_moves_the_gradients_of_a_deep_plain_stack_by_per_cent():
+    """Why the full-size VGG16 comparison allows 0.25: thirteen ReLU convolutions without shortcuts.  Noise of
+    3e-7 (fp32 summation order) ahead of the bf16 storage rounding flips some roundings; every flip perturbs all
+    later activations at the 2^-9 level, ReLU decisions next to zero flip with them, and each flipped decision
+    drops or passes a whole gradient element.  The disagreement grows from the output side to the input side."""
+    from synth.configs import VGGConfig
+    cfg = VGGConfig("vgg16_img32", 1, 32, 3, (64, 128, 256, 512, 512), (2, 2, 3, 3, 3), (256,), 40)
+    wl = make_workload(cfg, seed=0)
+    N = len(wl.weights)
+    rng = np.random.default_rng(123)
+
+    def noisy(a):
+        a = np.asarray(a, dtype=np.float64)
+        return R.round_bf16(a * (1.0 + 3e-7 * rng.standard_normal(a.shape)))
+
+    a = V.vgg_step(cfg, wl.weights, wl.x, wl.y, [1] * N, store=R.round_bf16)
+    b = V.vgg_step(cfg, wl.weights, wl.x, wl.y, [1] * N, store=noisy)
+    diff = [np.linalg.norm((a["grads"][k] - b["grads"][k]).ravel()) / np.linalg.norm(a["grads"][k].ravel())
+            for k in range(N)]
+    assert diff[0] > 0.03, diff[0]                 # conv0.W: several per cent from 3e-7 of noise
+    assert diff[N - 2] < 0.5 * diff[0]             # the last linear layer sees far less of it
