@@ -38,7 +38,7 @@ int et_debug_conv3x3(const void* x, const void* w, void* out, int batch, int H, 
  * d[b][h][w][n] * x[b][h+ky-1][w+kx-1][c].  x bf16 NHWC, C a multiple of 8; d bf16 [batch*H*W][N], N a multiple of 8;
  * dw fp32 [N][9 C]; batch*H*W a multiple of 64; H, W < 4096.  split_k > 1 reduces over that many pixel ranges
  * through `partials` (N * 9 C * split_k floats); split_k = 0 lets the library plan tile and split (then `partials`
- * must hold 64 such copies).  tile: 0 = automatic, or 11, 13, 19, 21 for the 256x256, 256x192, 128x256, 64x512
+ * must hold 256 such copies).  tile: 0 = automatic, or 11, 13, 19, 21 for the 256x256, 256x192, 128x256, 64x512
  * tiles.  Returns 0, -1, -3 as above. */
 int et_debug_conv3x3_dw(const void* x, const void* d, float* dw, int batch, int H, int W, int C, int N, int split_k,
                         float* partials, int tile, void* stream);

@@ -34,7 +34,7 @@ struct TileRate { int tile, bm, bn; double rate; };
 Plan plan_tiles(int M, int N, int K, bool may_split, const TileRate* cand, int n_cand) {
   Plan best = {T_AUTO, 1, 1e30};
   const int slices = (K + gemm::PBK - 1) / gemm::PBK;
-  const int max_split = may_split ? std::max(1, std::min(64, slices / 4)) : 1;
+  const int max_split = may_split ? std::max(1, std::min(256, slices / 4)) : 1;
   for (int ci = 0; ci < n_cand; ci++) {
     const TileRate& c = cand[ci];
     const long long tiles = (long long)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
@@ -118,7 +118,7 @@ void gemm_bf16_plan_split(int M, int N, int K, int* tile, int* split_k) {
   } else {   // small outputs: as many chunks as keep the CUs busy, each at least 4 slices
     const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
     const int slices = (K + gemm::SBK - 1) / gemm::SBK;
-    *split_k = std::max(1, std::min(std::min(256 / std::max(tiles, 1), std::max(1, slices / 4)), 64));
+    *split_k = std::max(1, std::min(std::min(256 / std::max(tiles, 1), std::max(1, slices / 4)), 256));
   }
 }
 

@@ -78,7 +78,7 @@ def _case_dw(batch, H, W, C, N, split, tile, seed):
     to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(torch.bfloat16)
     xt, dt = to(x), to(d)
     out = torch.full((N, 9 * C), float("nan"), device=dev, dtype=torch.float32)
-    part = torch.empty(N * 9 * C * 64, device=dev, dtype=torch.float32)
+    part = torch.empty(N * 9 * C * 256, device=dev, dtype=torch.float32)
     st = et.et_debug_conv3x3_dw(xt.data_ptr(), dt.data_ptr(), out.data_ptr(), batch, H, W, C, N, split, part.data_ptr(),
                                 tile, torch.cuda.current_stream().cuda_stream)
     assert st == 0
