@@ -290,6 +290,9 @@ def vit_step(cfg, weights, x, y, mask):
 
 
 def forward(cfg, weights, x, y):
+    if cfg.kind == "mobilenet":
+        from . import mobilenet
+        return mobilenet.mobilenet_forward(cfg, weights, x, y)
     if cfg.kind == "vgg":
         from . import vgg
         return vgg.vgg_forward(cfg, weights, x, y)
@@ -300,6 +303,9 @@ def forward(cfg, weights, x, y):
 
 
 def step(cfg, weights, x, y, mask):
+    if cfg.kind == "mobilenet":
+        from . import mobilenet
+        return mobilenet.mobilenet_step(cfg, weights, x, y, mask)
     if cfg.kind == "vgg":
         from . import vgg
         return vgg.vgg_step(cfg, weights, x, y, mask)

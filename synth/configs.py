@@ -87,6 +87,39 @@ class VGGConfig:
     kind: str = "vgg"
 
 
+@dataclass(frozen=True)
+class MobileNetConfig:
+    """Inverted-residual network on NHWC images (MobileNetV2 family); BatchNorm folded into a per-channel
+    affine.  Stem: 3x3 / stride 2 convolution to `stem` channels, affine, ReLU6.  Each entry (t, c, n, s) of
+    `settings` is n blocks to c channels with expansion factor t, the first of stride s: a 1x1 expansion to
+    t * c_in channels (affine, ReLU6; absent when t = 1), a 3x3 depthwise convolution (stride s or 1, affine,
+    ReLU6), a 1x1 projection to c channels (affine, no activation); a block of stride 1 whose input has c
+    channels adds its input to its output.  Then a 1x1 convolution to `last` channels (affine, ReLU6), global
+    average pooling and a linear head.  Convolution weights are stored [out, kh, kw, in], the depthwise ones
+    [channels, 3, 3, 1]; convolutions carry no bias."""
+    name: str
+    batch: int
+    image: int
+    in_ch: int
+    stem: int
+    settings: Tuple[Tuple[int, int, int, int], ...]
+    last: int
+    classes: int
+    dtype: str = "bf16"
+    kind: str = "mobilenet"
+
+
+def mobilenet_blocks(cfg):
+    """[(c_in, hidden, c_out, stride, has_expansion, has_shortcut)] in forward order."""
+    out, cin = [], cfg.stem
+    for (t, c, n, s) in cfg.settings:
+        for i in range(n):
+            stride = s if i == 0 else 1
+            out.append((cin, cin * t, c, stride, t != 1, stride == 1 and cin == c))
+            cin = c
+    return out
+
+
 CONFIGS = {
     # BASELINE configs[0]: 4-layer ReLU MLP, fp32, batch 32
     "mlp": MLPConfig("mlp", (256, 256, 256, 256, 10), 32),
@@ -106,6 +139,11 @@ CONFIGS = {
     "vgg_small": VGGConfig("vgg_small", 3, 32, 3, (8, 16, 24), (2, 1, 2), (40, 24), 24),
     # channel counts in multiples of 64, as in VGG16: the convolutions that run as implicit GEMMs
     "vgg_c64": VGGConfig("vgg_c64", 2, 16, 3, (64, 128), (2, 2), (64,), 16),
+    # third CNN family of the paper's evaluation (Section 8): MobileNetV2 shape (width 1.0), 200 classes
+    "mobilenetv2": MobileNetConfig("mobilenetv2", 32, 224, 3, 32, ((1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2),
+                                                                  (6, 96, 3, 1), (6, 160, 3, 2), (6, 320, 1, 1)), 1280, 200),
+    "mobilenet_tiny": MobileNetConfig("mobilenet_tiny", 2, 16, 3, 8, ((1, 8, 1, 1), (2, 8, 2, 2)), 16, 8),
+    "mobilenet_small": MobileNetConfig("mobilenet_small", 3, 32, 3, 8, ((1, 8, 1, 1), (6, 16, 2, 2), (6, 24, 2, 2), (4, 24, 1, 1)), 64, 24),
     # small cases the oracle finishes in well under a second
     "mlp_tiny": MLPConfig("mlp_tiny", (8, 8, 8, 4), 4),
     "mlp5": MLPConfig("mlp5", (6, 6, 6, 6, 6, 3), 4),
@@ -150,6 +188,18 @@ def tensor_specs(cfg) -> List[Tuple[str, Tuple[int, ...]]]:
                     out += [(n + "sc.W", (4 * p, 1, 1, cin)), (n + "sc.g", (4 * p,)), (n + "sc.b", (4 * p,))]
                 cin = 4 * p
         out += [("head.W", (cfg.classes, cin)), ("head.b", (cfg.classes,))]
+        return out
+    if cfg.kind == "mobilenet":
+        out = [("stem.W", (cfg.stem, 3, 3, cfg.in_ch)), ("stem.g", (cfg.stem,)), ("stem.b", (cfg.stem,))]
+        for i, (cin, hid, cout, stride, expand, shortcut) in enumerate(mobilenet_blocks(cfg)):
+            n = "b%d." % i
+            if expand:
+                out += [(n + "exp.W", (hid, 1, 1, cin)), (n + "exp.g", (hid,)), (n + "exp.b", (hid,))]
+            out += [(n + "dw.W", (hid, 3, 3, 1)), (n + "dw.g", (hid,)), (n + "dw.b", (hid,)),
+                    (n + "proj.W", (cout, 1, 1, hid)), (n + "proj.g", (cout,)), (n + "proj.b", (cout,))]
+        c_last = mobilenet_blocks(cfg)[-1][2]
+        out += [("last.W", (cfg.last, 1, 1, c_last)), ("last.g", (cfg.last,)), ("last.b", (cfg.last,)),
+                ("head.W", (cfg.classes, cfg.last)), ("head.b", (cfg.classes,))]
         return out
     if cfg.kind == "vgg":
         out, cin, i = [], cfg.in_ch, 0

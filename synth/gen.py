@@ -68,7 +68,7 @@ def make_workload(cfg, seed: int = 0, init: str = "paper", batch: int = None) ->
                 w = rng.standard_normal(shape) * np.sqrt(2.0 / int(np.prod(shape[1:])))
             else:
                 w = np.zeros(shape) if init == "paper" else 0.05 * rng.standard_normal(shape)
-        elif cfg.kind == "resnet":
+        elif cfg.kind in ("resnet", "mobilenet"):
             leaf = name.split(".")[-1]
             if leaf == "W":                                                  # He normal, fan-in
                 w = rng.standard_normal(shape) * np.sqrt(2.0 / int(np.prod(shape[1:])))
@@ -91,7 +91,7 @@ def make_workload(cfg, seed: int = 0, init: str = "paper", batch: int = None) ->
         snapshot.append(s)
     if cfg.kind == "mlp":
         x = _rng(seed, 1).standard_normal((B, cfg.dims[0])).astype(np.float32)
-    elif cfg.kind in ("resnet", "vgg"):
+    elif cfg.kind in ("resnet", "vgg", "mobilenet"):
         x = quant(_rng(seed, 1).standard_normal((B, cfg.image, cfg.image, cfg.in_ch)).astype(np.float32))
     else:
         x = quant(_rng(seed, 1).standard_normal((B, cfg.tokens - 1, cfg.patch_dim)).astype(np.float32))
