@@ -42,6 +42,7 @@ extern "C" {
 #define ET_VIT 1 /* pre-LN vision transformer encoder on flattened patches          */
 #define ET_RESNET 2 /* bottleneck residual CNN, BatchNorm folded into per-channel affines */
 #define ET_VGG 3 /* plain 3x3 convolution stack with biases, 2x2 max pooling, linear layers   */
+#define ET_MOBILENET 4 /* inverted residual blocks: 1x1 expansion, 3x3 depthwise, 1x1 projection   */
 
 /* storage types of weights and activations */
 #define ET_F32 0  /* float32 everywhere                                             */
@@ -81,17 +82,29 @@ typedef struct et_ctx et_ctx;
  *   dims[0..n_layers-1] units (bias, ReLU) and a linear layer to `classes` logits.  Every layer is
  *   two tensors, Kernel and Bias (Section 5.1): conv{i}.W [out, 3, 3, in], conv{i}.b, ...,
  *   fc{j}.W [out, in], fc{j}.b.  planes, dims and classes must be multiples of 8.
+ * ET_MOBILENET: x and the dense convolution weights as for ET_RESNET; depthwise weights [channels, 3, 3, 1];
+ *   every convolution is followed by a per-channel affine (folded BatchNorm) and contributes three
+ *   tensors W, g, b.  Stem: 3x3 / stride 2 convolution to `stem` channels, ReLU6.  Entry i of the
+ *   settings is stage_blocks[i] blocks to planes[i] channels with expansion factor expand[i], the
+ *   first of stride strides[i] (1 or 2): 1x1 expansion to expand[i] * c_in channels with ReLU6
+ *   (absent when expand[i] = 1), 3x3 depthwise convolution with ReLU6, 1x1 projection without
+ *   activation; a stride-1 block whose input has planes[i] channels adds its input to its output.
+ *   Then a 1x1 convolution to `last` channels with ReLU6, global average pooling and a linear
+ *   head.  Tensors in chain order: stem.W, stem.g, stem.b; per block [exp.W, exp.g, exp.b,] dw.W,
+ *   dw.g, dw.b, proj.W, proj.g, proj.b; last.W, last.g, last.b; head.W [classes, last], head.b.
+ *   All channel counts and classes must be multiples of 8.
  * Labels are int32 in [0, classes). The loss is the mean softmax cross-entropy. */
 typedef struct {
-  int32_t kind;  /* ET_MLP | ET_VIT | ET_RESNET | ET_VGG */
-  int32_t dtype; /* ET_F32 (MLP) | ET_BF16 (ViT, ResNet, VGG) */
+  int32_t kind;  /* ET_MLP | ET_VIT | ET_RESNET | ET_VGG | ET_MOBILENET */
+  int32_t dtype; /* ET_F32 (MLP) | ET_BF16 (all others) */
   int32_t batch;
   int32_t n_layers;                    /* ET_MLP, ET_VGG */
   int32_t dims[ET_MAX_MLP_LAYERS + 1]; /* ET_MLP, ET_VGG */
   int32_t tokens, patch_dim, width, heads, mlp, blocks, classes; /* ET_VIT */
   float ln_eps;                        /* ET_VIT */
-  int32_t image, in_ch, stem, n_stages;               /* ET_RESNET, ET_VGG (classes as above; stem: ET_RESNET only) */
-  int32_t stage_blocks[ET_MAX_STAGES], planes[ET_MAX_STAGES]; /* ET_RESNET, ET_VGG */
+  int32_t image, in_ch, stem, n_stages;               /* ET_RESNET, ET_VGG, ET_MOBILENET (classes as above; stem: not ET_VGG) */
+  int32_t stage_blocks[ET_MAX_STAGES], planes[ET_MAX_STAGES]; /* ET_RESNET, ET_VGG, ET_MOBILENET */
+  int32_t expand[ET_MAX_STAGES], strides[ET_MAX_STAGES], last;  /* ET_MOBILENET */
 } et_model_desc;
 
 /* Optimizer hyper-parameters of one step; every constant is explicit.

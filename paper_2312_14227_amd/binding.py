@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libet.so")
 
 ET_OK, ET_INFEASIBLE, ET_EINVAL, ET_ENOMEM, ET_EHIP, ET_ENAN, ET_ESTATE = 0, 1, -1, -2, -3, -4, -5
-ET_MLP, ET_VIT, ET_RESNET, ET_VGG = 0, 1, 2, 3
+ET_MLP, ET_VIT, ET_RESNET, ET_VGG, ET_MOBILENET = 0, 1, 2, 3, 4
 ET_F32, ET_BF16 = 0, 1
 ET_ADAM, ET_SGDW = 0, 1
 ET_MAX_MLP_LAYERS = 16
@@ -27,7 +27,8 @@ class et_model_desc(C.Structure):
                 ("tokens", C.c_int32), ("patch_dim", C.c_int32), ("width", C.c_int32), ("heads", C.c_int32),
                 ("mlp", C.c_int32), ("blocks", C.c_int32), ("classes", C.c_int32), ("ln_eps", C.c_float),
                 ("image", C.c_int32), ("in_ch", C.c_int32), ("stem", C.c_int32), ("n_stages", C.c_int32),
-                ("stage_blocks", C.c_int32 * ET_MAX_STAGES), ("planes", C.c_int32 * ET_MAX_STAGES)]
+                ("stage_blocks", C.c_int32 * ET_MAX_STAGES), ("planes", C.c_int32 * ET_MAX_STAGES),
+                ("expand", C.c_int32 * ET_MAX_STAGES), ("strides", C.c_int32 * ET_MAX_STAGES), ("last", C.c_int32)]
 
 
 class et_opt(C.Structure):
@@ -108,7 +109,7 @@ def _ptr_array(ptrs):
 
 
 def make_desc(kind, dtype, batch, dims=(), tokens=0, patch_dim=0, width=0, heads=0, mlp=0, blocks=0, classes=0,
-              ln_eps=1e-6, image=0, in_ch=0, stem=0, stage_blocks=(), planes=()):
+              ln_eps=1e-6, image=0, in_ch=0, stem=0, stage_blocks=(), planes=(), expand=(), strides=(), last=0):
     d = et_model_desc()
     d.kind, d.dtype, d.batch = kind, dtype, batch
     d.n_layers = max(len(dims) - 1, 0)
@@ -119,6 +120,9 @@ def make_desc(kind, dtype, batch, dims=(), tokens=0, patch_dim=0, width=0, heads
     d.image, d.in_ch, d.stem, d.n_stages = image, in_ch, stem, len(stage_blocks)
     for i, (nb, pl) in enumerate(zip(stage_blocks, planes)):
         d.stage_blocks[i], d.planes[i] = nb, pl
+    for i, (e, st) in enumerate(zip(expand, strides)):
+        d.expand[i], d.strides[i] = e, st
+    d.last = last
     return d
 
 

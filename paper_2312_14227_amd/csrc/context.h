@@ -60,6 +60,17 @@ struct ResBlockBufs {
   bf16* y;                    // block output (after the closing ReLU)
 };
 
+// activations kept by one inverted-residual block (MobileNetV2 family)
+struct MbBlockBufs {
+  int t, t_dw;                 // tensor index of the block's first weight and of its depthwise weight
+  int Cin, hid, Cout, stride, H, W, Ho, Wo;
+  bool expand, shortcut;
+  const bf16* x;               // block input [B,H,W,Cin]
+  bf16 *z_exp, *y_exp;         // expansion: convolution output, after affine + ReLU6   [B,H,W,hid]
+  bf16 *z_dw, *y_dw;           // depthwise: the same                                   [B,Ho,Wo,hid]
+  bf16 *z_proj, *y;            // projection output and the block output                [B,Ho,Wo,Cout]
+};
+
 }  // namespace et_exec
 using namespace et_exec;
 
@@ -111,6 +122,11 @@ struct et_ctx {
   std::vector<int> vdims;           // vdims[j] -> vdims[j+1]: linear layer j
   bf16* wflip = nullptr;            // mirrored weight of the convolution whose dy() is running
   float* fc_z32 = nullptr;          // reduced sum of a linear layer's split forward product
+
+  // inverted-residual network: blocks; the stem and the last convolution are ConvUnits (`stem`, `mlast`)
+  std::vector<MbBlockBufs> mblk;
+  ConvUnit mlast;
+  float* dw_part = nullptr;         // partial sums of a depthwise weight gradient
 
   // tables for importance / update
   std::vector<uint32_t> seg_begin;  // [N+1]
@@ -286,6 +302,9 @@ int build_resnet(et_ctx* c);
 // masked backward pass will read it
 int resnet_forward(et_ctx* c, const void* x, const int32_t* y, const uint8_t* mask);
 int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask);
+int build_mobilenet(et_ctx* c);
+int mobilenet_forward(et_ctx* c, const void* x, const int32_t* y, const uint8_t* mask);
+int mobilenet_backward(et_ctx* c, const void* x, const uint8_t* mask);
 int build_vgg(et_ctx* c);
 int vgg_forward(et_ctx* c, const void* x, const int32_t* y);
 int vgg_backward(et_ctx* c, const void* x, const uint8_t* mask);

@@ -173,23 +173,156 @@ __global__ __launch_bounds__(256) void scale_cols_kernel(const bf16* __restrict_
   }
 }
 
-// out = (a + b) * (mask > 0); b may be null
+// out = (a + b) * (0 < mask < hi); b may be null; mask may be null (plain sum)
 __global__ __launch_bounds__(256) void add_mask_kernel(const bf16* __restrict__ a, const bf16* __restrict__ b,
                                                        const bf16* __restrict__ mask, bf16* __restrict__ out,
-                                                       long long n8) {
+                                                       long long n8, float hi) {
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (long long)gridDim.x * blockDim.x) {
-    const bf16x8 x = *(const bf16x8*)(a + i * 8), mk = *(const bf16x8*)(mask + i * 8);
-    bf16x8 r;
+    const bf16x8 x = *(const bf16x8*)(a + i * 8);
+    bf16x8 r = x;
     if (b) {
       const bf16x8 y = *(const bf16x8*)(b + i * 8);
 #pragma unroll
-      for (int j = 0; j < 8; j++) r[j] = (float)mk[j] > 0.f ? (bf16)((float)x[j] + (float)y[j]) : (bf16)0.f;
-    } else {
+      for (int j = 0; j < 8; j++) r[j] = (bf16)((float)x[j] + (float)y[j]);
+    }
+    if (mask) {
+      const bf16x8 mk = *(const bf16x8*)(mask + i * 8);
 #pragma unroll
-      for (int j = 0; j < 8; j++) r[j] = (float)mk[j] > 0.f ? x[j] : (bf16)0.f;
+      for (int j = 0; j < 8; j++) r[j] = ((float)mk[j] > 0.f && (float)mk[j] < hi) ? r[j] : (bf16)0.f;
     }
     *(bf16x8*)(out + i * 8) = r;
   }
+}
+
+// ---------------------------------------------------------------------------------------------
+// 3x3 depthwise convolution (zero padding 1, stride 1 or 2) on NHWC, 8 channels per thread; weights
+// [C][9].  Forward: z = sum over taps (fp32), stored rounded; y = clamp(z * gain + shift, 0, 6)
+// from the rounded z.  Input gradient in gather form: every input pixel sums the output
+// gradients of the windows it belongs to; then + add (nullable), times the ReLU6 mask of the
+// activation in front of the convolution (nullable).
+// ---------------------------------------------------------------------------------------------
+struct DwGeom { int B, H, W, C, stride, Ho, Wo; };
+
+__global__ __launch_bounds__(256) void depthwise_fwd_kernel(const bf16* __restrict__ x, const bf16* __restrict__ w,
+                                                            const bf16* __restrict__ gain, const bf16* __restrict__ shift,
+                                                            bf16* __restrict__ z, bf16* __restrict__ y, DwGeom g,
+                                                            long long total) {
+  const int c8n = g.C >> 3;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const int c0 = (int)(i % c8n) * 8;
+    const long long pix = i / c8n;
+    const int wo = (int)(pix % g.Wo), ho = (int)((pix / g.Wo) % g.Ho);
+    const long long b = pix / ((long long)g.Wo * g.Ho);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ky = 0; ky < 3; ky++) {
+      const int h = ho * g.stride + ky - 1;
+      if ((unsigned)h >= (unsigned)g.H) continue;
+#pragma unroll
+      for (int kx = 0; kx < 3; kx++) {
+        const int ww = wo * g.stride + kx - 1;
+        if ((unsigned)ww >= (unsigned)g.W) continue;
+        const bf16x8 v = *(const bf16x8*)(x + ((b * g.H + h) * g.W + ww) * g.C + c0);
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[j] += (float)v[j] * (float)w[(c0 + j) * 9 + ky * 3 + kx];
+      }
+    }
+    const bf16x8 gn = *(const bf16x8*)(gain + c0), sh = *(const bf16x8*)(shift + c0);
+    bf16x8 zr, yr;
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      zr[j] = (bf16)acc[j];
+      yr[j] = (bf16)fminf(fmaxf((float)zr[j] * (float)gn[j] + (float)sh[j], 0.f), 6.f);
+    }
+    if (z) *(bf16x8*)(z + pix * g.C + c0) = zr;
+    *(bf16x8*)(y + pix * g.C + c0) = yr;
+  }
+}
+
+__global__ __launch_bounds__(256) void depthwise_dx_kernel(const bf16* __restrict__ d, const bf16* __restrict__ w,
+                                                           const bf16* __restrict__ add, const bf16* __restrict__ mask,
+                                                           bf16* __restrict__ out, DwGeom g, long long total) {
+  const int c8n = g.C >> 3;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const int c0 = (int)(i % c8n) * 8;
+    const long long pix = i / c8n;
+    const int ww = (int)(pix % g.W), h = (int)((pix / g.W) % g.H);
+    const long long b = pix / ((long long)g.W * g.H);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ky = 0; ky < 3; ky++) {
+      const int hn = h + 1 - ky;                 // = ho * stride
+      if (hn < 0 || hn % g.stride) continue;
+      const int ho = hn / g.stride;
+      if (ho >= g.Ho) continue;
+#pragma unroll
+      for (int kx = 0; kx < 3; kx++) {
+        const int wn = ww + 1 - kx;
+        if (wn < 0 || wn % g.stride) continue;
+        const int wo = wn / g.stride;
+        if (wo >= g.Wo) continue;
+        const bf16x8 v = *(const bf16x8*)(d + ((b * g.Ho + ho) * g.Wo + wo) * g.C + c0);
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[j] += (float)v[j] * (float)w[(c0 + j) * 9 + ky * 3 + kx];
+      }
+    }
+    if (add) {
+      const bf16x8 v = *(const bf16x8*)(add + pix * g.C + c0);
+#pragma unroll
+      for (int j = 0; j < 8; j++) acc[j] += (float)v[j];
+    }
+    bf16x8 r;
+    if (mask) {
+      const bf16x8 mk = *(const bf16x8*)(mask + pix * g.C + c0);
+#pragma unroll
+      for (int j = 0; j < 8; j++) r[j] = ((float)mk[j] > 0.f && (float)mk[j] < 6.f) ? (bf16)acc[j] : (bf16)0.f;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; j++) r[j] = (bf16)acc[j];
+    }
+    *(bf16x8*)(out + pix * g.C + c0) = r;
+  }
+}
+
+// Weight gradient, first stage: worker r (one thread per 8 channels) adds d * x over the output pixels
+// r, r + R, r + 2R, ... in that order and writes its 72 sums to part[r][c * 9 + tap]; a column sum over the
+// R rows finishes the reduction in a fixed order.
+__global__ __launch_bounds__(256) void depthwise_dw_kernel(const bf16* __restrict__ d, const bf16* __restrict__ x,
+                                                           float* __restrict__ part, DwGeom g, int R, long long total) {
+  const int c8n = g.C >> 3;
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int c0 = (int)(i % c8n) * 8;
+  const int r = (int)(i / c8n);
+  const long long pixels = (long long)g.B * g.Ho * g.Wo;
+  float acc[9][8];
+#pragma unroll
+  for (int t = 0; t < 9; t++)
+#pragma unroll
+    for (int j = 0; j < 8; j++) acc[t][j] = 0.f;
+  for (long long pix = r; pix < pixels; pix += R) {
+    const int wo = (int)(pix % g.Wo), ho = (int)((pix / g.Wo) % g.Ho);
+    const long long b = pix / ((long long)g.Wo * g.Ho);
+    const bf16x8 dv = *(const bf16x8*)(d + pix * g.C + c0);
+#pragma unroll
+    for (int ky = 0; ky < 3; ky++) {
+      const int h = ho * g.stride + ky - 1;
+      if ((unsigned)h >= (unsigned)g.H) continue;
+#pragma unroll
+      for (int kx = 0; kx < 3; kx++) {
+        const int ww = wo * g.stride + kx - 1;
+        if ((unsigned)ww >= (unsigned)g.W) continue;
+        const bf16x8 v = *(const bf16x8*)(x + ((b * g.H + h) * g.W + ww) * g.C + c0);
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[ky * 3 + kx][j] += (float)dv[j] * (float)v[j];
+      }
+    }
+  }
+  float* o = part + (long long)r * g.C * 9 + c0 * 9;
+#pragma unroll
+  for (int j = 0; j < 8; j++)
+#pragma unroll
+    for (int t = 0; t < 9; t++) o[j * 9 + t] = acc[t][j];
 }
 
 // out = max(z + bias, 0) from an fp32 matrix [rows][N] (a split product's reduced sum); N % 4 == 0
@@ -363,7 +496,7 @@ __global__ __launch_bounds__(256) void avgpool_fwd_kernel(const bf16* __restrict
 }
 
 __global__ __launch_bounds__(256) void avgpool_bwd_kernel(const bf16* __restrict__ dp, const bf16* __restrict__ y,
-                                                          bf16* __restrict__ out, int HW, int C, long long n8) {
+                                                          bf16* __restrict__ out, int HW, int C, long long n8, float hi) {
   const int c8n = C >> 3;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (long long)gridDim.x * blockDim.x) {
     const int c8 = (int)(i % c8n);
@@ -371,7 +504,7 @@ __global__ __launch_bounds__(256) void avgpool_bwd_kernel(const bf16* __restrict
     const bf16x8 v = *(const bf16x8*)(dp + b * C + c8 * 8), yy = *(const bf16x8*)(y + i * 8);
     bf16x8 r;
 #pragma unroll
-    for (int j = 0; j < 8; j++) r[j] = (float)yy[j] > 0.f ? (bf16)((float)v[j] / (float)HW) : (bf16)0.f;
+    for (int j = 0; j < 8; j++) r[j] = ((float)yy[j] > 0.f && (float)yy[j] < hi) ? (bf16)((float)v[j] / (float)HW) : (bf16)0.f;
     *(bf16x8*)(out + i * 8) = r;
   }
 }
@@ -464,9 +597,57 @@ hipError_t bias_relu_rows(const float* z, const bf16* bias, bf16* out, int rows,
   return hipGetLastError();
 }
 
-hipError_t add_mask(const bf16* a, const bf16* b, const bf16* mask, bf16* out, long long n, hipStream_t s) {
-  if (n < 8 || (n & 7) || !a || !mask || !al16(a) || (b && !al16(b)) || !al16(mask) || !al16(out)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(add_mask_kernel, dim3(grid_for(n >> 3)), dim3(256), 0, s, a, b, mask, out, n >> 3);
+hipError_t add_mask(const bf16* a, const bf16* b, const bf16* mask, bf16* out, long long n, hipStream_t s, float mask_hi) {
+  if (n < 8 || (n & 7) || !a || (!mask && !b) || !al16(a) || (b && !al16(b)) || (mask && !al16(mask)) || !al16(out))
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(add_mask_kernel, dim3(grid_for(n >> 3)), dim3(256), 0, s, a, b, mask, out, n >> 3, mask_hi);
+  return hipGetLastError();
+}
+
+namespace {
+bool dw_geom(DwGeom& g, int B, int H, int W, int C, int stride) {
+  if (B < 1 || H < 1 || W < 1 || C < 8 || (C & 7) || (stride != 1 && stride != 2)) return false;
+  g.B = B; g.H = H; g.W = W; g.C = C; g.stride = stride;
+  g.Ho = (H - 1) / stride + 1;
+  g.Wo = (W - 1) / stride + 1;
+  return true;
+}
+}  // namespace
+
+hipError_t depthwise3x3_fwd(const bf16* x, const bf16* w, const bf16* gain, const bf16* shift, bf16* z, bf16* y, int B, int H,
+                            int W, int C, int stride, hipStream_t s) {
+  DwGeom g;
+  if (!dw_geom(g, B, H, W, C, stride) || !al16(x) || !w || !al16(gain) || !al16(shift) || (z && !al16(z)) || !al16(y))
+    return hipErrorInvalidValue;
+  const long long total = (long long)B * g.Ho * g.Wo * (C >> 3);
+  hipLaunchKernelGGL(depthwise_fwd_kernel, dim3(grid_for(total)), dim3(256), 0, s, x, w, gain, shift, z, y, g, total);
+  return hipGetLastError();
+}
+
+hipError_t depthwise3x3_dx(const bf16* d, const bf16* w, const bf16* add, const bf16* relu6_y, bf16* out, int B, int H, int W,
+                           int C, int stride, hipStream_t s) {
+  DwGeom g;
+  if (!dw_geom(g, B, H, W, C, stride) || !al16(d) || !w || (add && !al16(add)) || (relu6_y && !al16(relu6_y)) || !al16(out))
+    return hipErrorInvalidValue;
+  const long long total = (long long)B * H * W * (C >> 3);
+  hipLaunchKernelGGL(depthwise_dx_kernel, dim3(grid_for(total)), dim3(256), 0, s, d, w, add, relu6_y, out, g, total);
+  return hipGetLastError();
+}
+
+int depthwise3x3_dw_rows(int B, int H, int W, int C, int stride) {
+  const long long pixels = (long long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
+  long long r = 65536 / (C >> 3);
+  if (r < 64) r = 64;
+  if (r > pixels) r = pixels;
+  return (int)r;
+}
+
+hipError_t depthwise3x3_dw(const bf16* d, const bf16* x, float* part, int B, int H, int W, int C, int stride, hipStream_t s) {
+  DwGeom g;
+  if (!dw_geom(g, B, H, W, C, stride) || !al16(d) || !al16(x) || !al16(part)) return hipErrorInvalidValue;
+  const int R = depthwise3x3_dw_rows(B, H, W, C, stride);
+  const long long total = (long long)R * (C >> 3);
+  hipLaunchKernelGGL(depthwise_dw_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, d, x, part, g, R, total);
   return hipGetLastError();
 }
 
@@ -515,10 +696,10 @@ hipError_t avgpool_fwd(const bf16* x, bf16* p, int B, int HW, int C, hipStream_t
   return hipGetLastError();
 }
 
-hipError_t avgpool_bwd_relu(const bf16* dp, const bf16* y, bf16* out, int B, int HW, int C, hipStream_t s) {
+hipError_t avgpool_bwd_relu(const bf16* dp, const bf16* y, bf16* out, int B, int HW, int C, hipStream_t s, float mask_hi) {
   if (B < 1 || HW < 1 || C < 8 || (C & 7) || !al16(dp) || !al16(y) || !al16(out)) return hipErrorInvalidValue;
   const long long n8 = (long long)B * HW * (C >> 3);
-  hipLaunchKernelGGL(avgpool_bwd_kernel, dim3(grid_for(n8)), dim3(256), 0, s, dp, y, out, HW, C, n8);
+  hipLaunchKernelGGL(avgpool_bwd_kernel, dim3(grid_for(n8)), dim3(256), 0, s, dp, y, out, HW, C, n8, mask_hi);
   return hipGetLastError();
 }
 

@@ -486,12 +486,14 @@ int run_forward(et_ctx* c, const void* x, const int32_t* y, const uint8_t* mask 
   c->cur_phase = PH_FWD;
   if (c->desc.kind == ET_RESNET) return resnet_forward(c, x, y, mask);
   if (c->desc.kind == ET_VGG) return vgg_forward(c, x, y);
+  if (c->desc.kind == ET_MOBILENET) return mobilenet_forward(c, x, y, mask);
   return c->desc.kind == ET_MLP ? mlp_forward(c, x, y) : vit_forward(c, x, y, mask);
 }
 int run_backward(et_ctx* c, const void* x, const uint8_t* mask) {
   c->cur_phase = PH_DW;
   if (c->desc.kind == ET_RESNET) return resnet_backward(c, x, mask);
   if (c->desc.kind == ET_VGG) return vgg_backward(c, x, mask);
+  if (c->desc.kind == ET_MOBILENET) return mobilenet_backward(c, x, mask);
   return c->desc.kind == ET_MLP ? mlp_backward(c, x, mask) : vit_backward(c, x, mask);
 }
 
@@ -562,6 +564,7 @@ int et_create(const et_model_desc* desc, void* hip_stream, et_ctx** out) {
     else if (desc->kind == ET_VIT) rc = build_vit(c);
     else if (desc->kind == ET_RESNET) rc = build_resnet(c);
     else if (desc->kind == ET_VGG) rc = build_vgg(c);
+    else if (desc->kind == ET_MOBILENET) rc = build_mobilenet(c);
     else rc = ET_EINVAL;
     if (rc == ET_OK && c->tensors.size() > (size_t)et::MAX_TENSORS) rc = ET_EINVAL;
     if (rc == ET_OK) {

@@ -157,6 +157,7 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   p.alpha = d.alpha; p.bias = d.bias; p.gain = d.gain; p.gain2 = d.gain2; p.bias2 = d.bias2; p.residual = d.residual; p.ldr = d.ldr;
   p.C = d.C; p.ldc = d.ldc; p.C2 = d.C2; p.U = d.U; p.no_store = d.no_store;
   p.cH = d.conv_h; p.cW = d.conv_w; p.cC = d.conv_c;
+  p.act_lo = d.act_lo; p.act_hi = d.act_hi; p.mask_hi = d.mask_hi;
   int zdim = d.z_outer * d.z_inner;
   int epi;
   int k_per_block = d.K;

@@ -81,6 +81,8 @@ struct Params {
   int ldc;
   bf16* C2;
   const bf16* U;
+  float act_lo, act_hi;  // E_AFFINE, E_AFFINE_ADD: the activation is a clamp to [act_lo, act_hi] (0, +inf: ReLU; 0, 6: ReLU6; -inf, +inf: none)
+  float mask_hi;         // E_RELU_MASK passes where 0 < U < mask_hi
   int cH, cW, cC;        // implicit 3x3 convolution (gemm_pp_kernel<.., CONV>): input height, width, channels
   int no_store;          // tuning aids: 1 run the main loop, store nothing; 2 also issue no loads; 4 all tiles load the same panels
 };
@@ -240,7 +242,7 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
         if (EPI == E_RELU_MASK) {
           const bf16x4 u = pre_u[HAS_U ? it : 0];
 #pragma unroll
-          for (int j = 0; j < 4; j++) v[j] = (float)u[j] > 0.f ? v[j] : 0.f;
+          for (int j = 0; j < 4; j++) v[j] = ((float)u[j] > 0.f && (float)u[j] < g.mask_hi) ? v[j] : 0.f;
         }
         if (EPI == E_F32 || EPI == E_F32_RES || EPI == E_PARTIAL) {
           *(float4*)((float*)g.C + ci) = make_float4(v[0], v[1], v[2], v[3]);
@@ -270,7 +272,7 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
 #pragma unroll
           for (int j = 0; j < 4; j++) {
             o[j] = (bf16)v[j];
-            o2[j] = (bf16)fmaxf((float)o[j] * gain[j] + bias[j], 0.f);
+            o2[j] = (bf16)fminf(fmaxf((float)o[j] * gain[j] + bias[j], g.act_lo), g.act_hi);
           }
           if (g.C) *(bf16x4*)((bf16*)g.C + ci) = o;   // z is kept only if the gain's gradient will be computed
           *(bf16x4*)(g.C2 + ci) = o2;
@@ -280,7 +282,7 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
 #pragma unroll
           for (int j = 0; j < 4; j++) {
             o[j] = (bf16)v[j];
-            o2[j] = (bf16)fmaxf(((float)o[j] * gain[j] + bias[j]) + ((float)u[j] * gain2[j] + bias2[j]), 0.f);
+            o2[j] = (bf16)fminf(fmaxf(((float)o[j] * gain[j] + bias[j]) + ((float)u[j] * gain2[j] + bias2[j]), g.act_lo), g.act_hi);
           }
           if (g.C) *(bf16x4*)((bf16*)g.C + ci) = o;
           *(bf16x4*)(g.C2 + ci) = o2;
@@ -303,7 +305,7 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
           }
           if (EPI == E_F32_RES) x += g.residual[(long long)row * g.ldr + col + j];
           if (EPI == E_GELU_BWD) x *= (float)g.U[ci + j];
-          if (EPI == E_RELU_MASK) x = (float)g.U[ci + j] > 0.f ? x : 0.f;
+          if (EPI == E_RELU_MASK) x = ((float)g.U[ci + j] > 0.f && (float)g.U[ci + j] < g.mask_hi) ? x : 0.f;
           if (EPI == E_F32 || EPI == E_F32_RES || EPI == E_PARTIAL) {
             ((float*)g.C)[ci + j] = x;
           } else if (EPI == E_GELU_FWD) {
@@ -314,11 +316,11 @@ __device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI]
           } else if (EPI == E_AFFINE) {
             const bf16 z = (bf16)x;
             if (g.C) ((bf16*)g.C)[ci + j] = z;
-            g.C2[ci + j] = (bf16)fmaxf((float)z * gain[j] + bias[j], 0.f);
+            g.C2[ci + j] = (bf16)fminf(fmaxf((float)z * gain[j] + bias[j], g.act_lo), g.act_hi);
           } else if (EPI == E_AFFINE_ADD) {
             const bf16 z = (bf16)x;
             if (g.C) ((bf16*)g.C)[ci + j] = z;
-            g.C2[ci + j] = (bf16)fmaxf(((float)z * gain[j] + bias[j]) + ((float)g.U[ci + j] * gain2[j] + bias2[j]), 0.f);
+            g.C2[ci + j] = (bf16)fminf(fmaxf(((float)z * gain[j] + bias[j]) + ((float)g.U[ci + j] * gain2[j] + bias2[j]), g.act_lo), g.act_hi);
           } else {
             ((bf16*)g.C)[ci + j] = (bf16)x;
           }

@@ -52,6 +52,9 @@ struct GemmDesc {
   const float* residual = nullptr; // fp32 [M][ldr]
   int ldr = 0;
   int mode = EPI_PLAIN;
+  // the AFFINE modes' activation is a clamp to [act_lo, act_hi] (defaults: ReLU; 0, 6: ReLU6; -inf, +inf: none);
+  // EPI_RELU_MASK passes where 0 < U < mask_hi
+  float act_lo = 0.f, act_hi = __builtin_inff(), mask_hi = __builtin_inff();
   void* C = nullptr;               // bf16 or fp32 [M][ldc]; may be null for the AFFINE modes (z not kept)
   int ldc = 0;
   bool c_f32 = false;
@@ -162,7 +165,8 @@ hipError_t affine_act(const bf16* z1, const float* z1_f32, const bf16* g1, const
 // out[r][c] = d[r][c] * gain[c]
 hipError_t scale_cols(const bf16* d, const bf16* gain, bf16* out, long long rows, int C, hipStream_t s);
 // out = (a + b) * (mask > 0), n elements (n % 8 == 0); b nullable; out may alias a or b
-hipError_t add_mask(const bf16* a, const bf16* b, const bf16* mask, bf16* out, long long n, hipStream_t s);
+hipError_t add_mask(const bf16* a, const bf16* b, const bf16* mask, bf16* out, long long n, hipStream_t s,
+                    float mask_hi = __builtin_inff());
 // stem pooling: y = relu(z*gain + shift) in fp32, then 3x3 / stride 2 / pad 1 maximum, first maximum in
 // (ky, kx) order; arg holds the chosen tap (one byte per output element)
 hipError_t maxpool3x3s2_fwd(const float* z, const bf16* gain, const bf16* shift, bf16* out, uint8_t* arg, int B, int H,
@@ -172,13 +176,25 @@ hipError_t maxpool3x3s2_bwd(const bf16* d, const uint8_t* arg, const bf16* y, bf
                             hipStream_t s);
 // p[b][c] = mean over the HW positions; backward: out[b][t][c] = dp[b][c] / HW * (y[b][t][c] > 0)
 hipError_t avgpool_fwd(const bf16* x, bf16* p, int B, int HW, int C, hipStream_t s);
-hipError_t avgpool_bwd_relu(const bf16* dp, const bf16* y, bf16* out, int B, int HW, int C, hipStream_t s);
+hipError_t avgpool_bwd_relu(const bf16* dp, const bf16* y, bf16* out, int B, int HW, int C, hipStream_t s,
+                            float mask_hi = __builtin_inff());
 // 2x2 / stride 2 max pooling of y [B][H][W][C] (H, W even), first maximum in (dy, dx) order; arg: one byte per output
 hipError_t maxpool2x2_fwd(const bf16* y, bf16* out, uint8_t* arg, int B, int H, int W, int C, hipStream_t s);
 // out[B][H][W][C] = (d routed back to the chosen tap of its window) * (y > 0)
 hipError_t maxpool2x2_bwd(const bf16* d, const uint8_t* arg, const bf16* y, bf16* out, int B, int H, int W, int C,
                           hipStream_t s);
 // rows of K elements <-> rows of Kc >= K elements (zero tail)
+// 3x3 depthwise convolution, zero padding 1, stride 1 or 2, NHWC, C % 8 == 0, weights [C][9] (bf16):
+//   fwd: z (nullable: not kept) = the convolution, rounded; y = clamp(z * gain + shift, 0, 6)
+//   dx:  out[B][H][W][C] = (adjoint applied to d [B][Ho][Wo][C] + add) * (0 < relu6_y < 6); add, relu6_y nullable
+//   dw:  part[R][C * 9] fp32 partial sums over R = depthwise3x3_dw_rows(..) interleaved pixel subsets; their
+//        column sum (colsum over R rows) is the gradient [C][9]
+hipError_t depthwise3x3_fwd(const bf16* x, const bf16* w, const bf16* gain, const bf16* shift, bf16* z, bf16* y, int B, int H,
+                            int W, int C, int stride, hipStream_t s);
+hipError_t depthwise3x3_dx(const bf16* d, const bf16* w, const bf16* add, const bf16* relu6_y, bf16* out, int B, int H, int W,
+                           int C, int stride, hipStream_t s);
+int depthwise3x3_dw_rows(int B, int H, int W, int C, int stride);
+hipError_t depthwise3x3_dw(const bf16* d, const bf16* x, float* part, int B, int H, int W, int C, int stride, hipStream_t s);
 // out[rows][N] (bf16) = max(z[rows][N] + bias[N], 0), z fp32; N % 4 == 0
 hipError_t bias_relu_rows(const float* z, const bf16* bias, bf16* out, int rows, int N, hipStream_t s);
 // out[C][3][3][O] = w[O][3][3][C] with mirrored taps: the weight of the 3x3 convolution that maps an output

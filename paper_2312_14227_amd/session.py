@@ -13,6 +13,11 @@ def desc_from_config(cfg, batch=None):
     if cfg.kind == "resnet":
         return et.make_desc(et.ET_RESNET, et.ET_BF16, B, classes=cfg.classes, image=cfg.image, in_ch=cfg.in_ch,
                             stem=cfg.stem, stage_blocks=cfg.blocks, planes=cfg.planes)
+    if cfg.kind == "mobilenet":
+        return et.make_desc(et.ET_MOBILENET, et.ET_BF16, B, classes=cfg.classes, image=cfg.image, in_ch=cfg.in_ch,
+                            stem=cfg.stem, stage_blocks=[n for (_, _, n, _) in cfg.settings],
+                            planes=[c for (_, c, _, _) in cfg.settings], expand=[t for (t, _, _, _) in cfg.settings],
+                            strides=[s for (_, _, _, s) in cfg.settings], last=cfg.last)
     if cfg.kind == "vgg":
         return et.make_desc(et.ET_VGG, et.ET_BF16, B, dims=tuple(cfg.fc) + (cfg.classes,), classes=cfg.classes,
                             image=cfg.image, in_ch=cfg.in_ch, stage_blocks=cfg.convs, planes=cfg.widths)

@@ -1,0 +1,124 @@
+"""Parity of the HIP step of the inverted-residual network (MobileNetV2 family) with the oracle, through the C
+ABI, on the same seeded inputs.  The parity reference is the oracle with its `store` hook set to bf16 rounding at
+the tensors the bf16 data layout keeps in memory (its arithmetic stays float64); the distance to the exact oracle
+is bounded by that of the bf16-storage oracle to the exact one."""
+import numpy as np
+import pytest
+
+from gpu_util import rel_l2, sample_masks, tol_for
+from oracle import mobilenet as MB
+from oracle import resnet as R
+from synth import CONFIGS, make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def _session(cfg, wl, **kw):
+    from paper_2312_14227_amd.session import Session
+    return Session(cfg, wl.weights, **kw)
+
+
+def _run(s, xt, yt, mask):
+    import torch
+    for g in s.grad:
+        g.fill_(float("nan"))
+    loss = s.train_step(xt, yt, mask)
+    torch.cuda.synchronize()
+    return loss, [g.cpu().numpy() for g in s.grad]
+
+
+@pytest.mark.parametrize("name,seed,init", [("mobilenet_tiny", 0, "random"), ("mobilenet_tiny", 1, "paper"),
+                                            ("mobilenet_small", 2, "random"), ("mobilenet_small", 3, "paper")])
+def test_mobilenet_masks_match_oracle(name, seed, init):
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg, seed=seed, init=init)
+    N = len(wl.weights)
+    ones = [1] * N
+    ref = MB.mobilenet_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16)
+    exact = MB.mobilenet_step(cfg, wl.weights, wl.x, wl.y, ones)
+    s = _session(cfg, wl)
+    from paper_2312_14227_amd import binding as et
+    assert [et.et_tensor_info(s.ctx, i)[2] for i in range(N)] == list(wl.names)
+    xt, yt = s.put_input(wl.x, wl.y)
+    rng = np.random.default_rng(seed)
+    tol = 0.1 * tol_for(cfg)            # same rounding points on both sides: far inside the bf16 bound
+    worst = worst_exact = 0.0
+    layout, t_last = MB.block_layout(cfg)
+    # every tensor of the first two blocks and the first tensor of every block (where shortcuts join)
+    extra = list(range(0, min(N, 16))) + [t for (*_, t) in layout] + [t_last, t_last + 1, t_last + 2]
+    for mask in sample_masks(N, rng, extra=extra):
+        loss, grads = _run(s, xt, yt, mask)
+        assert abs(loss - ref["loss"]) <= tol * abs(ref["loss"]), (loss, ref["loss"])
+        for j in range(N):
+            if mask[j]:
+                assert np.isfinite(grads[j]).all(), wl.names[j]
+                err = rel_l2(grads[j], ref["grads"][j])
+                worst = max(worst, err)
+                assert err <= tol, (wl.names[j], err, [int(m) for m in mask])
+                worst_exact = max(worst_exact, rel_l2(grads[j], exact["grads"][j]))
+            else:
+                assert np.isnan(grads[j]).all(), ("unselected gradient buffer was written", wl.names[j])
+    print("%s: worst relative L2 error %.3e against the bf16-storage oracle, %.3e against the exact one"
+          % (name, worst, worst_exact))
+    own = max(rel_l2(a, b) for a, b in zip(ref["grads"], exact["grads"]))
+    assert worst_exact <= 1.25 * own + tol, (worst_exact, own)
+    s.close()
+
+
+def test_mobilenet_launched_work_follows_the_time_model():
+    """Nothing runs behind the input-most selected tensor; the forward pass does not depend on the mask's
+    backward reach; selecting an earlier tensor alone never launches less."""
+    cfg = CONFIGS["mobilenet_small"]
+    wl = make_workload(cfg, seed=0, init="random")
+    N = len(wl.weights)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    m = np.zeros(N, dtype=np.uint8)
+    s.train_step(xt, yt, m)
+    fwd0, bwd0, _ = s.launch_counts()
+    assert bwd0 == 0 and fwd0 > 0
+    counts = []
+    for j in range(N):
+        m = np.zeros(N, dtype=np.uint8)
+        m[j] = 1
+        s.train_step(xt, yt, m)
+        fwd, bwd, _ = s.launch_counts()
+        assert fwd == fwd0
+        counts.append(bwd)
+    assert counts[N - 1] < counts[0]
+    assert all(counts[j] >= counts[j + 1] - 3 for j in range(N - 1))   # dw kernels differ by at most a few launches
+    s.close()
+
+
+def test_mobilenet_profile_importance_and_selection_run():
+    from paper_2312_14227_amd import binding as et
+    cfg = CONFIGS["mobilenet_small"]
+    wl = make_workload(cfg, seed=4, init="random")
+    N = len(wl.weights)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    t_fwd, t_dw, t_dy = s.profile(xt, yt, warmup=1, reps=2)
+    assert t_fwd > 0 and (t_dw > 0).all() and t_dy[0] == 0
+    names = wl.names
+    assert all(t_dy[k] == 0 for k in range(N) if names[k].endswith(".b"))      # a shift passes the gradient unchanged
+    assert all(t_dy[k] > 0 for k in range(1, N) if not names[k].endswith(".b"))
+    imp = s.importance(xt, yt, [w.clone() for w in s.w])
+    assert np.isfinite(imp).all() and len(imp) == N
+    st, mask, pred = et.et_select(np.abs(imp) + 1e-12, t_dw, t_dy, t_fwd, 500000, 1000)
+    assert st == 0 and mask.any() and pred > 0
+    s.close()
+
+
+def test_mobilenet_determinism():
+    cfg = CONFIGS["mobilenet_small"]
+    wl = make_workload(cfg, seed=5, init="random")
+    N = len(wl.weights)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    mask = np.ones(N, dtype=np.uint8)
+    l1, g1 = _run(s, xt, yt, mask)
+    l2, g2 = _run(s, xt, yt, mask)
+    assert l1 == l2
+    for a, b in zip(g1, g2):
+        assert np.array_equal(a, b)
+    s.close()
