@@ -68,7 +68,7 @@ def main():
     ap.add_argument("--rho", type=float, default=0.5)
     ap.add_argument("--tq", type=int, default=10000)
     ap.add_argument("--cpu-sample-batch", type=int, default=None,
-                    help="batch of the oracle's timed step (default: 64 for the transformers, 4 for the ResNet, 2 for VGG16)")
+                    help="batch of the oracle's timed step (default: 64 for the transformers, 4 for the ResNet, 2 for VGG16, 8 for MobileNetV2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB plain copy kernel (known traffic, for scaling hardware counters)")
@@ -150,7 +150,7 @@ def main():
     if cn and (not gemm or cns > max(v[1] for v in gemm.values())):
         gemm_part = {k: roofline[k] for k in ("all_gemm_tflops", "all_gemm_frac", "gemm_ms_per_step")} if roofline else {}
         roofline = {"bound": "hbm", "kernel": "convolution data-movement kernels (im2col and its adjoint, affine / ReLU masks, "
-                    "pooling, per-channel sums)", "achieved": cbytes / cns, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "depthwise convolutions, pooling, per-channel sums)", "achieved": cbytes / cns, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": cbytes / cns / PEAK_HBM_GBS, "traffic": None, "avg_launch_us": cns / cn / 1e3,
                     "bytes_per_launch": cbytes / cn, "launches_per_step": cn / a.steps}
         roofline.update(gemm_part)
@@ -192,7 +192,7 @@ def main():
         torch.cuda.synchronize()
     s.close()
     if not a.no_cpu_baseline:
-        sample = a.cpu_sample_batch if a.cpu_sample_batch else {"resnet": 4, "vgg": 2}.get(cfg.kind, 64)
+        sample = a.cpu_sample_batch if a.cpu_sample_batch else {"resnet": 4, "vgg": 2, "mobilenet": 8}.get(cfg.kind, 64)
         out["cpu_baseline"] = cpu_baseline(cfg, mask, min(sample, cfg.batch), opt_kind, hp)
     print(json.dumps(out))
 

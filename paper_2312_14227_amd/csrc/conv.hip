@@ -203,6 +203,16 @@ __global__ __launch_bounds__(256) void add_mask_kernel(const bf16* __restrict__ 
 // ---------------------------------------------------------------------------------------------
 struct DwGeom { int B, H, W, C, stride, Ho, Wo; };
 
+// the 72 weights of 8 consecutive channels, [channel][tap]: nine 16-byte loads (c0 is a multiple of 8)
+struct DwWeights {
+  bf16x8 v[9];
+  __device__ __forceinline__ void load(const bf16* __restrict__ w, int c0) {
+#pragma unroll
+    for (int i = 0; i < 9; i++) v[i] = *(const bf16x8*)(w + c0 * 9 + i * 8);
+  }
+  __device__ __forceinline__ float at(int j, int tap) const { return (float)v[(j * 9 + tap) >> 3][(j * 9 + tap) & 7]; }
+};
+
 __global__ __launch_bounds__(256) void depthwise_fwd_kernel(const bf16* __restrict__ x, const bf16* __restrict__ w,
                                                             const bf16* __restrict__ gain, const bf16* __restrict__ shift,
                                                             bf16* __restrict__ z, bf16* __restrict__ y, DwGeom g,
@@ -214,6 +224,8 @@ __global__ __launch_bounds__(256) void depthwise_fwd_kernel(const bf16* __restri
     const int wo = (int)(pix % g.Wo), ho = (int)((pix / g.Wo) % g.Ho);
     const long long b = pix / ((long long)g.Wo * g.Ho);
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    DwWeights wt;
+    wt.load(w, c0);
 #pragma unroll
     for (int ky = 0; ky < 3; ky++) {
       const int h = ho * g.stride + ky - 1;
@@ -224,7 +236,7 @@ __global__ __launch_bounds__(256) void depthwise_fwd_kernel(const bf16* __restri
         if ((unsigned)ww >= (unsigned)g.W) continue;
         const bf16x8 v = *(const bf16x8*)(x + ((b * g.H + h) * g.W + ww) * g.C + c0);
 #pragma unroll
-        for (int j = 0; j < 8; j++) acc[j] += (float)v[j] * (float)w[(c0 + j) * 9 + ky * 3 + kx];
+        for (int j = 0; j < 8; j++) acc[j] += (float)v[j] * wt.at(j, ky * 3 + kx);
       }
     }
     const bf16x8 gn = *(const bf16x8*)(gain + c0), sh = *(const bf16x8*)(shift + c0);
@@ -249,6 +261,8 @@ __global__ __launch_bounds__(256) void depthwise_dx_kernel(const bf16* __restric
     const int ww = (int)(pix % g.W), h = (int)((pix / g.W) % g.H);
     const long long b = pix / ((long long)g.W * g.H);
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    DwWeights wt;
+    wt.load(w, c0);
 #pragma unroll
     for (int ky = 0; ky < 3; ky++) {
       const int hn = h + 1 - ky;                 // = ho * stride
@@ -263,7 +277,7 @@ __global__ __launch_bounds__(256) void depthwise_dx_kernel(const bf16* __restric
         if (wo >= g.Wo) continue;
         const bf16x8 v = *(const bf16x8*)(d + ((b * g.Ho + ho) * g.Wo + wo) * g.C + c0);
 #pragma unroll
-        for (int j = 0; j < 8; j++) acc[j] += (float)v[j] * (float)w[(c0 + j) * 9 + ky * 3 + kx];
+        for (int j = 0; j < 8; j++) acc[j] += (float)v[j] * wt.at(j, ky * 3 + kx);
       }
     }
     if (add) {
@@ -617,7 +631,7 @@ bool dw_geom(DwGeom& g, int B, int H, int W, int C, int stride) {
 hipError_t depthwise3x3_fwd(const bf16* x, const bf16* w, const bf16* gain, const bf16* shift, bf16* z, bf16* y, int B, int H,
                             int W, int C, int stride, hipStream_t s) {
   DwGeom g;
-  if (!dw_geom(g, B, H, W, C, stride) || !al16(x) || !w || !al16(gain) || !al16(shift) || (z && !al16(z)) || !al16(y))
+  if (!dw_geom(g, B, H, W, C, stride) || !al16(x) || !al16(w) || !al16(gain) || !al16(shift) || (z && !al16(z)) || !al16(y))
     return hipErrorInvalidValue;
   const long long total = (long long)B * g.Ho * g.Wo * (C >> 3);
   hipLaunchKernelGGL(depthwise_fwd_kernel, dim3(grid_for(total)), dim3(256), 0, s, x, w, gain, shift, z, y, g, total);
@@ -627,7 +641,7 @@ hipError_t depthwise3x3_fwd(const bf16* x, const bf16* w, const bf16* gain, cons
 hipError_t depthwise3x3_dx(const bf16* d, const bf16* w, const bf16* add, const bf16* relu6_y, bf16* out, int B, int H, int W,
                            int C, int stride, hipStream_t s) {
   DwGeom g;
-  if (!dw_geom(g, B, H, W, C, stride) || !al16(d) || !w || (add && !al16(add)) || (relu6_y && !al16(relu6_y)) || !al16(out))
+  if (!dw_geom(g, B, H, W, C, stride) || !al16(d) || !al16(w) || (add && !al16(add)) || (relu6_y && !al16(relu6_y)) || !al16(out))
     return hipErrorInvalidValue;
   const long long total = (long long)B * H * W * (C >> 3);
   hipLaunchKernelGGL(depthwise_dx_kernel, dim3(grid_for(total)), dim3(256), 0, s, d, w, add, relu6_y, out, g, total);

@@ -18,6 +18,31 @@ __global__ void splitk_reduce_kernel(const float4* __restrict__ part, float4* __
   out[i] = s;
 }
 
+// many chunks, few outputs: 16 lanes share one output vector, lane g adds the chunks g, g + 16, ... in
+// order, then the 16 sums are added in lane order (through LDS): again the same order on every run
+__global__ __launch_bounds__(256) void splitk_reduce_wide_kernel(const float4* __restrict__ part, float4* __restrict__ out,
+                                                                 size_t n4, int splits) {
+  __shared__ float4 sh[16][16];
+  const int o = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const size_t i = blockIdx.x * (size_t)16 + o;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < n4)
+    for (int z = grp; z < splits; z += 16) {
+      const float4 p = part[(size_t)z * n4 + i];
+      s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    }
+  sh[grp][o] = s;
+  __syncthreads();
+  if (grp == 0 && i < n4) {
+    float4 t = sh[0][o];
+    for (int k = 1; k < 16; k++) {
+      const float4 p = sh[k][o];
+      t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+    }
+    out[i] = t;
+  }
+}
+
 enum TileId : int { T_AUTO = 0, T_128x128 = 1, T_128x64 = 3, T_DMA_256x256 = 5, T_DMA_256x128 = 7, T_PP_256x256 = 11, T_PP_256x192 = 13,
               T_PP_256x128 = 15, T_PP_512x64 = 17, T_PP_128x256 = 19, T_PP_64x512 = 21 };
 
@@ -247,8 +272,12 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   if (launches) *launches = 1;
   if (p.split_k > 1) {
     const size_t n4 = (size_t)d.M * d.N / 4;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s,
-                       (const float4*)d.partials, (float4*)d.C, n4, p.split_k);
+    if (p.split_k > 32)
+      hipLaunchKernelGGL(splitk_reduce_wide_kernel, dim3((unsigned)((n4 + 15) / 16)), dim3(256), 0, s,
+                         (const float4*)d.partials, (float4*)d.C, n4, p.split_k);
+    else
+      hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s,
+                         (const float4*)d.partials, (float4*)d.C, n4, p.split_k);
     e = hipGetLastError();
     if (launches) *launches = 2;
   }

@@ -65,6 +65,10 @@ def main():
         r = resnet.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights), store=resnet.round_bf16,
                                cols_stored=lambda cin, cout, stride: not (stride == 1 and cout % 64 == 0 and cin % 8 == 0))
         I = oimp.importance_from_grads(r["grads"], wl.weights, wl.snapshot)
+    elif cfg.kind == "mobilenet":
+        from oracle import mobilenet, resnet
+        r = mobilenet.mobilenet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights), store=resnet.round_bf16)
+        I = oimp.importance_from_grads(r["grads"], wl.weights, wl.snapshot)
     elif cfg.kind == "vgg":
         r = vgg_in_chunks(cfg, wl, 8)
         I = oimp.importance_from_grads(r["grads"], wl.weights, wl.snapshot)
