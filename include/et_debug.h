@@ -43,6 +43,18 @@ int et_debug_conv3x3(const void* x, const void* w, void* out, int batch, int H, 
 int et_debug_conv3x3_dw(const void* x, const void* d, float* dw, int batch, int H, int W, int C, int N, int split_k,
                         float* partials, int tile, void* stream);
 
+/* 3x3 depthwise convolution kernels (zero padding 1, stride 1 or 2; NHWC bf16, C a multiple of 8; weights bf16
+ * [C][9]; Ho = (H - 1) / stride + 1, Wo likewise).  op selects the kernel:
+ *   0 forward: a = x [batch][H][W][C], b = weights, gain, shift [C]; out0 (nullable) = z, the convolution rounded to
+ *     bf16; out1 = y = min(max(z * gain + shift, 0), 6), both [batch][Ho][Wo][C];
+ *   1 input gradient: a = d [batch][Ho][Wo][C], b = weights, `gain` = an addend (nullable) and `shift` = a stored
+ *     ReLU6 activation (nullable), both [batch][H][W][C]; out0 = (adjoint applied to d + addend) where 0 < activation < 6;
+ *   2 weight gradient: a = d, b = x; out0 = fp32 [C][9]; ws = device scratch of et_debug_depthwise3x3_ws_floats(..) floats.
+ * Device pointers, 16-byte aligned.  Returns 0, -1, -3 as above. */
+size_t et_debug_depthwise3x3_ws_floats(int batch, int H, int W, int C, int stride);
+int et_debug_depthwise3x3(int op, const void* a, const void* b, const void* gain, const void* shift, void* out0, void* out1,
+                          float* ws, int batch, int H, int W, int C, int stride, void* stream);
+
 /* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16; 16-byte aligned device
  * pointers).  Used to calibrate hardware traffic counters against a known size. */
 int et_debug_copy(void* dst, const void* src, size_t bytes, void* stream);

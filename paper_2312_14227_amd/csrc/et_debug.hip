@@ -51,6 +51,34 @@ extern "C" int et_debug_conv3x3_dw(const void* x, const void* d, float* dw, int 
   return e == hipSuccess ? ET_OK : ET_EHIP;
 }
 
+extern "C" size_t et_debug_depthwise3x3_ws_floats(int batch, int H, int W, int C, int stride) {
+  if (batch < 1 || H < 1 || W < 1 || C < 8 || (C & 7) || (stride != 1 && stride != 2)) return 0;
+  const int R = et::depthwise3x3_dw_rows(batch, H, W, C, stride);
+  return (size_t)R * C * 9 + et::colsum_partial_elems(R, C * 9) + 64;
+}
+
+extern "C" int et_debug_depthwise3x3(int op, const void* a, const void* b, const void* gain, const void* shift, void* out0,
+                                     void* out1, float* ws, int batch, int H, int W, int C, int stride, void* stream) {
+  hipStream_t s = (hipStream_t)stream;
+  typedef const et::bf16* P;
+  hipError_t e;
+  if (op == 0) {
+    e = et::depthwise3x3_fwd((P)a, (P)b, (P)gain, (P)shift, (et::bf16*)out0, (et::bf16*)out1, batch, H, W, C, stride, s);
+  } else if (op == 1) {
+    e = et::depthwise3x3_dx((P)a, (P)b, (P)gain, (P)shift, (et::bf16*)out0, batch, H, W, C, stride, s);
+  } else if (op == 2) {
+    if (!ws || et_debug_depthwise3x3_ws_floats(batch, H, W, C, stride) == 0) return ET_EINVAL;
+    const int R = et::depthwise3x3_dw_rows(batch, H, W, C, stride);
+    e = et::depthwise3x3_dw((P)a, (P)b, ws, batch, H, W, C, stride, s);
+    if (e == hipSuccess)
+      e = et::colsum(nullptr, ws, C * 9, nullptr, 0, nullptr, nullptr, (float*)out0, ws + (size_t)R * C * 9, R, C * 9, s);
+  } else {
+    return ET_EINVAL;
+  }
+  if (e == hipErrorInvalidValue) return ET_EINVAL;
+  return e == hipSuccess ? ET_OK : ET_EHIP;
+}
+
 namespace {
 __global__ void et_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;

@@ -28,8 +28,16 @@ GOLD_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 # error of order one; the kernels themselves are compared element by element, layer by layer, in
 # tests/test_gpu_conv3x3.py and tests/test_gpu_gemm.py, and the small cases, where no rounding flips, agree
 # to 1e-7 (tests/test_gpu_vgg.py).
+# MobileNetV2: 52 convolutions, ReLU6 clamping on both sides, random weights without normalisation: the same
+# mechanism makes two correct bf16 evaluations agree to 0.3-2 % over the last eight tensors and disagree by
+# 30-55 % from the middle of the network to its input (CPU pin: noise of 3e-7 on the oracle alone gives 26-85 % at
+# batch 2, tests/test_oracle_mobilenet.py).  The end-to-end comparison at full size is therefore informative only
+# at the output side (bound 5e-2 there; 0.75 elsewhere, which still rejects zero, sign-flipped or unrelated
+# gradients); the depthwise kernels are compared with the oracle at the full-size shapes in
+# tests/test_gpu_depthwise.py, the GEMMs in tests/test_gpu_gemm.py, and the small cases agree to 1e-7
+# (tests/test_gpu_mobilenet.py).
 @pytest.mark.parametrize("name,first,tol", [("vit_b", 87, 2e-2), ("vit_l", 200, 2e-2), ("resnet50", 80, 5e-2),
-                                            ("vgg16", 11, 0.25)])
+                                            ("vgg16", 11, 0.25), ("mobilenetv2", 60, 0.75)])
 def test_full_size_gradients_importance_and_masks(name, first, tol):
     import torch
     from paper_2312_14227_amd.session import Session
@@ -60,8 +68,14 @@ def test_full_size_gradients_importance_and_masks(name, first, tol):
         if bound > 0.0:
             worst_i = max(worst_i, abs(I[k] - G["importance"][k]) / bound)
         assert abs(I[k] - G["importance"][k]) <= bound, (wl.names[k], I[k], G["importance"][k])
-    if name == "vgg16":
+    if name in ("vgg16", "mobilenetv2"):
         print("per tensor:", [(n, round(e, 4)) for n, e in errs.items()])
+    if name == "mobilenetv2":
+        # 52 convolutions with ReLU6 on random weights: two correct bf16 evaluations agree only near the output
+        # (CPU pin in tests/test_oracle_mobilenet.py); there the workload-level agreement is required
+        print("output side:", [(n, round(e, 4)) for n, e in list(errs.items())[-8:]])
+        assert all(e <= 5e-2 for e in list(errs.values())[-8:]), list(errs.items())[-8:]
+    if name == "vgg16":
         # the linear layers, which see the least of the disagreement, keep the workload tolerance
         assert all(e <= 2e-2 for n, e in errs.items() if n.startswith("fc")), errs
     top = sorted(errs.items(), key=lambda kv: -kv[1])[:6]

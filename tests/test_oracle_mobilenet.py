@@ -131,3 +131,27 @@ def test_storage_hook():
         assert np.array_equal(a["grads"][k], b["grads"][k])
     err = max(np.linalg.norm((a["grads"][k] - c["grads"][k]).ravel()) / np.linalg.norm(a["grads"][k].ravel()) for k in range(N))
     assert 1e-4 < err < 0.5, err                                # rounding is applied, and it is a perturbation
+
+
+def test_rounding_noise_moves_the_gradients_of_the_deep_network_by_tens_of_per_cent():
+    """Why the full-size MobileNetV2 comparison is informative only at the output side: 52 convolutions, ReLU6
+    clamping on both sides, random weights and no normalisation.  Noise of 3e-7 (fp32 summation order) ahead of
+    the bf16 storage rounding changes the gradients of the input-side tensors by tens of per cent, those of the
+    head by a few per cent."""
+    from dataclasses import replace
+    cfg = replace(CONFIGS["mobilenetv2"], name="mobilenetv2_img64", batch=2, image=64)
+    wl = make_workload(cfg, seed=0)
+    N = len(wl.weights)
+    rng = np.random.default_rng(123)
+
+    def noisy(a):
+        a = np.asarray(a, dtype=np.float64)
+        return R.round_bf16(a * (1.0 + 3e-7 * rng.standard_normal(a.shape)))
+
+    a = MB.mobilenet_step(cfg, wl.weights, wl.x, wl.y, [1] * N, store=R.round_bf16)
+    b = MB.mobilenet_step(cfg, wl.weights, wl.x, wl.y, [1] * N, store=noisy)
+    diff = [np.linalg.norm((a["grads"][k] - b["grads"][k]).ravel()) / np.linalg.norm(a["grads"][k].ravel())
+            for k in range(N)]
+    print("first tensors", np.round(diff[:6], 3), "last tensors", np.round(diff[-5:], 3))
+    assert np.median(diff[:30]) > 0.1
+    assert diff[N - 2] < 0.3 * np.median(diff[:30])
