@@ -14,7 +14,8 @@
 // reduction slots meaning keys (e/4)*8 + (l/32)*4 + e%4 of a 16-key group; the matching B operand
 // (V with the same key order, one column d per lane) is what two ds_read_b64_tr_b16 deliver from
 // V stored [key][d].  No shuffle or LDS round trip between the two matrix products.
-// The backward pass uses the mirrored trick (S = Q K^T, a lane holds one key) for dK and dV.
+// The backward pass uses the mirrored trick (S = Q K^T, a lane holds one key) for dK and dV, and takes
+// rowsum(P * dP) of a query from the stored forward output: it equals dO . O.
 #include "kernels.h"
 
 namespace et {
@@ -105,31 +106,19 @@ __global__ __launch_bounds__(NTHREADS) void attention_fwd_kernel(const bf16* __r
       return acc;
     };
 
-    // sweep 1: running maximum and sum of exponentials over this lane's keys
-    float mx = -INFINITY, sum = 0.f;
+    // sweep 1: maximum over this lane's keys (no exponentials yet); the other half of the keys lives in lane l^32
+    float mx = -INFINITY;
 #pragma unroll 1
     for (int kt = 0; kt < KT; kt++) {
       const f32x16 st = scores(kt);
-      float tmax = st[0];
 #pragma unroll
-      for (int r = 1; r < 16; r++) tmax = fmaxf(tmax, st[r]);
-      const float nmx = fmaxf(mx, tmax);
-      if (nmx != -INFINITY) {
-        float part = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; r++) part += __expf(st[r] - nmx);
-        sum = sum * __expf(mx - nmx) + part;
-        mx = nmx;
-      }
+      for (int r = 0; r < 16; r++) mx = fmaxf(mx, st[r]);
     }
-    // the other half of the keys lives in lane l^32
-    const float omx = __shfl_xor(mx, 32, 64), osum = __shfl_xor(sum, 32, 64);
-    const float M = fmaxf(mx, omx);
-    const float S = sum * __expf(mx - M) + osum * __expf(omx - M);
-    const float inv = 1.f / S;
-    if (khalf == 0 && qt * 32 + l32 < T) lse[((long long)b * H + h) * T + qt * 32 + l32] = M + logf(S);
+    const float M = fmaxf(mx, __shfl_xor(mx, 32, 64));   // finite: key 0 is never masked
 
-    // sweep 2: O = P V; the probabilities of a tile are already an A operand
+    // sweep 2: O = exp(S - M) V with unnormalised probabilities, which are already an A operand; their sum
+    // per query is collected on the way and divides the result afterwards
+    float sum = 0.f;
     f32x16 o[2];
 #pragma unroll
     for (int dt = 0; dt < 2; dt++)
@@ -142,11 +131,25 @@ __global__ __launch_bounds__(NTHREADS) void attention_fwd_kernel(const bf16* __r
       for (int j = 0; j < 2; j++) {
         bf16x8 pf;
 #pragma unroll
-        for (int e = 0; e < 8; e++) pf[e] = (bf16)(__expf(st[j * 8 + e] - M) * inv);
+        for (int e = 0; e < 8; e++) {
+          const float p = __expf(st[j * 8 + e] - M);
+          sum += p;
+          pf[e] = (bf16)p;
+        }
 #pragma unroll
         for (int dt = 0; dt < 2; dt++)
           o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, frag_rows_tr(sv, kt * 32 + j * 16, dt * 32, lane), o[dt], 0, 0, 0);
       }
+    }
+    const float S = sum + __shfl_xor(sum, 32, 64);
+    const float inv = 1.f / S;
+    if (khalf == 0 && qt * 32 + l32 < T) lse[((long long)b * H + h) * T + qt * 32 + l32] = M + logf(S);
+    // the rows of the result tile are other lanes' queries: fetch their 1/S (lane q holds query q's)
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const float f = __shfl(inv, tile_row(r, lane), 64);
+      o[0][r] *= f;
+      o[1][r] *= f;
     }
     // result tile: lane holds column d = dt*32 + l%32, rows = queries
 #pragma unroll
@@ -163,9 +166,9 @@ __global__ __launch_bounds__(NTHREADS) void attention_fwd_kernel(const bf16* __r
 // backward: dS = P * (dP - rowsum(P*dP)) / sqrt(d);  dQ = dS K,  dK = dS^T Q,  dV = P^T dO
 // -------------------------------------------------------------------------------------------------
 template <int KT>
-__global__ __launch_bounds__(NTHREADS) void attention_bwd_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
-                                                            const float* __restrict__ lse, bf16* __restrict__ dqkv,
-                                                            int T, int H, float scale) {
+__global__ __launch_bounds__(NTHREADS) void attention_bwd_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ out,
+                                                            const bf16* __restrict__ dout, const float* __restrict__ lse,
+                                                            bf16* __restrict__ dqkv, int T, int H, float scale) {
   constexpr int TP = KT * 32;
   __shared__ __attribute__((aligned(16))) unsigned char sq[TP * PITCH];
   __shared__ __attribute__((aligned(16))) unsigned char sk[TP * PITCH];
@@ -188,7 +191,8 @@ __global__ __launch_bounds__(NTHREADS) void attention_bwd_kernel(const bf16* __r
 
   const int l32 = lane & 31, khalf = lane >> 5;
 
-  // ---- pass A: a wave owns 32 queries (one per lane pair); first the row dot products, then dQ
+  // ---- pass A: a wave owns 32 queries (one per lane pair).  rowsum(P * dP) of a query equals dO . O (O = P V is
+  // the stored forward output), so it needs no sweep over the keys of its own; then dQ
   for (int qt = wave; qt < KT; qt += NWAVES) {
     bf16x8 qf[4], dof[4];
 #pragma unroll
@@ -198,58 +202,54 @@ __global__ __launch_bounds__(NTHREADS) void attention_bwd_kernel(const bf16* __r
     }
     const float my_lse = s_lse[qt * 32 + l32];
     float dot = 0.f;
-#pragma unroll 1
-    for (int sweep = 0; sweep < 2; sweep++) {
-      f32x16 dq[2];
+    {
+      const int qrow = min(qt * 32 + l32, T - 1);
+      const bf16* orow = out + ((long long)b * T + qrow) * D + h * DH;
 #pragma unroll
-      for (int dt = 0; dt < 2; dt++)
+      for (int ks = 0; ks < 4; ks++) {
+        const bf16x8 of = *(const bf16x8*)(orow + ks * 16 + khalf * 8);
 #pragma unroll
-        for (int r = 0; r < 16; r++) dq[dt][r] = 0.f;
-      const float my_dot = dot;  // complete (both lane halves) in the second sweep
-#pragma unroll 1
-      for (int kt = 0; kt < KT; kt++) {
-        f32x16 st, dp;
-#pragma unroll
-        for (int r = 0; r < 16; r++) { st[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-        for (int ks = 0; ks < 4; ks++) {
-          st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct(sk, kt * 32, ks, lane), qf[ks], st, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct(sv, kt * 32, ks, lane), dof[ks], dp, 0, 0, 0);
-        }
-        float pr[16];
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-          const int key = kt * 32 + tile_row(r, lane);
-          pr[r] = key < T ? __expf(st[r] * scale - my_lse) : 0.f;
-        }
-        if (sweep == 0) {
-#pragma unroll
-          for (int r = 0; r < 16; r++) dot += pr[r] * dp[r];
-        } else {
-#pragma unroll
-          for (int j = 0; j < 2; j++) {
-            bf16x8 dsf;
-#pragma unroll
-            for (int e = 0; e < 8; e++) dsf[e] = (bf16)(pr[j * 8 + e] * (dp[j * 8 + e] - my_dot) * scale);
-#pragma unroll
-            for (int dt = 0; dt < 2; dt++)
-              dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, frag_rows_tr(sk, kt * 32 + j * 16, dt * 32, lane), dq[dt], 0, 0, 0);
-          }
-        }
+        for (int e = 0; e < 8; e++) dot += (float)of[e] * (float)dof[ks][e];
       }
-      if (sweep == 0) {
-        dot += __shfl_xor(dot, 32, 64);
-        if (khalf == 0) s_dot[qt * 32 + l32] = dot;
-      } else {
+      dot += __shfl_xor(dot, 32, 64);
+      if (khalf == 0) s_dot[qt * 32 + l32] = dot;
+    }
+    f32x16 dq[2];
+#pragma unroll
+    for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) dq[dt][r] = 0.f;
+#pragma unroll 1
+    for (int kt = 0; kt < KT; kt++) {
+      f32x16 st, dp;
+#pragma unroll
+      for (int r = 0; r < 16; r++) { st[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < 4; ks++) {
+        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct(sk, kt * 32, ks, lane), qf[ks], st, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct(sv, kt * 32, ks, lane), dof[ks], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int j = 0; j < 2; j++) {
+        bf16x8 dsf;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+          const int r = j * 8 + e;
+          const float p = kt * 32 + tile_row(r, lane) < T ? __expf(st[r] * scale - my_lse) : 0.f;
+          dsf[e] = (bf16)(p * (dp[r] - dot) * scale);
+        }
 #pragma unroll
         for (int dt = 0; dt < 2; dt++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) {
-            const int row = qt * 32 + tile_row(r, lane);
-            if (row < T) dqkv[((long long)b * T + row) * ld + h * DH + dt * 32 + l32] = (bf16)dq[dt][r];
-          }
+          dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, frag_rows_tr(sk, kt * 32 + j * 16, dt * 32, lane), dq[dt], 0, 0, 0);
       }
     }
+#pragma unroll
+    for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int row = qt * 32 + tile_row(r, lane);
+        if (row < T) dqkv[((long long)b * T + row) * ld + h * DH + dt * 32 + l32] = (bf16)dq[dt][r];
+      }
   }
   __syncthreads();
 
@@ -324,9 +324,9 @@ hipError_t launch_fwd(const bf16* qkv, bf16* out, float* lse, int B, int T, int 
   return hipGetLastError();
 }
 template <int KT>
-hipError_t launch_bwd(const bf16* qkv, const bf16* dout, const float* lse, bf16* dqkv, int B, int T, int H, float scale,
-                      hipStream_t s) {
-  hipLaunchKernelGGL((attention_bwd_kernel<KT>), dim3(B * H), dim3(NTHREADS), 0, s, qkv, dout, lse, dqkv, T, H, scale);
+hipError_t launch_bwd(const bf16* qkv, const bf16* out, const bf16* dout, const float* lse, bf16* dqkv, int B, int T, int H,
+                      float scale, hipStream_t s) {
+  hipLaunchKernelGGL((attention_bwd_kernel<KT>), dim3(B * H), dim3(NTHREADS), 0, s, qkv, out, dout, lse, dqkv, T, H, scale);
   return hipGetLastError();
 }
 
@@ -348,17 +348,17 @@ hipError_t attention_fwd(const bf16* qkv, bf16* out, float* lse, int B, int T, i
   }
 }
 
-hipError_t attention_bwd(const bf16* qkv, const bf16* dout, const float* lse, bf16* dqkv, int B, int T, int H,
+hipError_t attention_bwd(const bf16* qkv, const bf16* out, const bf16* dout, const float* lse, bf16* dqkv, int B, int T, int H,
                          int head_dim, float scale, hipStream_t s) {
-  if (!attention_fused_supported(T, head_dim) || B < 1 || H < 1) return hipErrorInvalidValue;
+  if (!attention_fused_supported(T, head_dim) || B < 1 || H < 1 || !out) return hipErrorInvalidValue;
   switch ((T + 31) / 32) {
-    case 1: return launch_bwd<1>(qkv, dout, lse, dqkv, B, T, H, scale, s);
-    case 2: return launch_bwd<2>(qkv, dout, lse, dqkv, B, T, H, scale, s);
-    case 3: return launch_bwd<3>(qkv, dout, lse, dqkv, B, T, H, scale, s);
-    case 4: return launch_bwd<4>(qkv, dout, lse, dqkv, B, T, H, scale, s);
-    case 5: return launch_bwd<5>(qkv, dout, lse, dqkv, B, T, H, scale, s);
-    case 6: return launch_bwd<6>(qkv, dout, lse, dqkv, B, T, H, scale, s);
-    default: return launch_bwd<7>(qkv, dout, lse, dqkv, B, T, H, scale, s);
+    case 1: return launch_bwd<1>(qkv, out, dout, lse, dqkv, B, T, H, scale, s);
+    case 2: return launch_bwd<2>(qkv, out, dout, lse, dqkv, B, T, H, scale, s);
+    case 3: return launch_bwd<3>(qkv, out, dout, lse, dqkv, B, T, H, scale, s);
+    case 4: return launch_bwd<4>(qkv, out, dout, lse, dqkv, B, T, H, scale, s);
+    case 5: return launch_bwd<5>(qkv, out, dout, lse, dqkv, B, T, H, scale, s);
+    case 6: return launch_bwd<6>(qkv, out, dout, lse, dqkv, B, T, H, scale, s);
+    default: return launch_bwd<7>(qkv, out, dout, lse, dqkv, B, T, H, scale, s);
   }
 }
 

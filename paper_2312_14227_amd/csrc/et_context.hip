@@ -276,7 +276,7 @@ int vit_forward(et_ctx* c, const void* x, const int32_t* y, const uint8_t* mask)
 int vit_attention_backward(et_ctx* c, const VitDims& v, VitBlockBufs& b) {
   if (et::attention_fused_supported(v.T, v.dh)) {
     KernelTimer kt(c, 6, 8.0 * v.B * v.H * (double)v.T * v.T * v.dh);
-    ET_K(1, et::attention_bwd(b.qkv, c->dattn, b.lse, c->dqkv, v.B, v.T, v.H, v.dh, v.scale, c->stream));
+    ET_K(1, et::attention_bwd(b.qkv, b.o, c->dattn, b.lse, c->dqkv, v.B, v.T, v.H, v.dh, v.scale, c->stream));
     return ET_OK;
   }
   const long long sQo = (long long)v.T * 3 * v.D, sPo = (long long)v.H * v.T * v.ldT, sPi = (long long)v.T * v.ldT;

@@ -124,11 +124,12 @@ hipError_t softmax_bwd_rows(const float* dp, const bf16* p, bf16* ds, float scal
 
 // fused attention core (tokens <= 224, head size 64), one workgroup per (batch, head):
 //   forward: out[b][t][h*64+d] = softmax(Q K^T * scale) V, lse[b][h][t] = log-sum-exp of the scaled scores
-//   backward: dqkv (same layout as qkv) from dout, recomputing the probabilities from lse
+//   backward: dqkv (same layout as qkv) from dout, recomputing the probabilities from lse; `out` is the stored
+//   forward output (rowsum(P * dP) = dout . out)
 bool attention_fused_supported(int T, int head_dim);
 hipError_t attention_fwd(const bf16* qkv, bf16* out, float* lse, int B, int T, int H, int head_dim, float scale,
                          hipStream_t s);
-hipError_t attention_bwd(const bf16* qkv, const bf16* dout, const float* lse, bf16* dqkv, int B, int T, int H,
+hipError_t attention_bwd(const bf16* qkv, const bf16* out, const bf16* dout, const float* lse, bf16* dqkv, int B, int T, int H,
                          int head_dim, float scale, hipStream_t s);
 
 // mean softmax cross-entropy: dlogits fp32 and (if not null) a bf16 copy [B][ld16], zero padded; `loss` points to
