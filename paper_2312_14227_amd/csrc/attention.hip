@@ -35,16 +35,29 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char* p) {
   return __builtin_bit_cast(bf16x4, v);
 }
 
-// rows [0, T) of a [T][64] bf16 matrix (row stride ld elements) into LDS rows of PITCH bytes; rows
-// [T, rows_pad) are zero-filled
-__device__ __forceinline__ void stage_rows(unsigned char* dst, const bf16* src, long long ld, int T, int rows_pad,
-                                           int tid, int nthreads) {
-  for (int v = tid; v < rows_pad * 8; v += nthreads) {
-    const int row = v >> 3, c = v & 7;
-    uint4 val = make_uint4(0, 0, 0, 0);
-    if (row < T) val = *(const uint4*)(src + (long long)row * ld + c * 8);
-    *(uint4*)(dst + row * PITCH + c * 16) = val;
-  }
+// rows [0, T) of NM [T][64] bf16 matrices (row stride ld[m] elements) into LDS rows of PITCH bytes; rows
+// [T, TP) are zero-filled.  All loads are issued before the first store, so the matrices arrive
+// after one memory latency instead of one per 16-byte piece.
+template <int TP, int NM>
+__device__ __forceinline__ void stage_rows(unsigned char* const (&dst)[NM], const bf16* const (&src)[NM],
+                                           const long long (&ld)[NM], int T, int tid) {
+  constexpr int PER = (TP * 8 + NTHREADS - 1) / NTHREADS;
+  uint4 val[NM][PER];
+#pragma unroll
+  for (int m = 0; m < NM; m++)
+#pragma unroll
+    for (int i = 0; i < PER; i++) {
+      const int v = tid + i * NTHREADS, row = v >> 3, c = v & 7;
+      val[m][i] = make_uint4(0, 0, 0, 0);
+      if (row < T) val[m][i] = *(const uint4*)(src[m] + (long long)row * ld[m] + c * 8);
+    }
+#pragma unroll
+  for (int m = 0; m < NM; m++)
+#pragma unroll
+    for (int i = 0; i < PER; i++) {
+      const int v = tid + i * NTHREADS, row = v >> 3, c = v & 7;
+      if (v < TP * 8) *(uint4*)(dst[m] + row * PITCH + c * 16) = val[m][i];
+    }
 }
 
 // A- or B-operand fragment of rows [row0, row0+32) for reduction slice ks (16 of the 64 columns):
@@ -81,8 +94,12 @@ __global__ __launch_bounds__(NTHREADS) void attention_fwd_kernel(const bf16* __r
   const bf16* q = qkv + (long long)b * T * ld + h * DH;
   const bf16* k = q + D;
   const bf16* v = q + 2 * D;
-  stage_rows(sk, k, ld, T, TP, tid, NTHREADS);
-  stage_rows(sv, v, ld, T, TP, tid, NTHREADS);
+  {
+    unsigned char* const dst[2] = {sk, sv};
+    const bf16* const src[2] = {k, v};
+    const long long lds[2] = {ld, ld};
+    stage_rows<TP, 2>(dst, src, lds, T, tid);
+  }
   __syncthreads();
 
   const int l32 = lane & 31, khalf = lane >> 5;
@@ -181,10 +198,12 @@ __global__ __launch_bounds__(NTHREADS) void attention_bwd_kernel(const bf16* __r
   const int D = H * DH;
   const long long ld = 3LL * D;
   const bf16* q = qkv + (long long)b * T * ld + h * DH;
-  stage_rows(sq, q, ld, T, TP, tid, NTHREADS);
-  stage_rows(sk, q + D, ld, T, TP, tid, NTHREADS);
-  stage_rows(sv, q + 2 * D, ld, T, TP, tid, NTHREADS);
-  stage_rows(sdo, dout + (long long)b * T * D + h * DH, D, T, TP, tid, NTHREADS);
+  {
+    unsigned char* const dst[4] = {sq, sk, sv, sdo};
+    const bf16* const src[4] = {q, q + D, q + 2 * D, dout + (long long)b * T * D + h * DH};
+    const long long lds[4] = {ld, ld, ld, (long long)D};
+    stage_rows<TP, 4>(dst, src, lds, T, tid);
+  }
   // padded queries get lse = +inf, so their probabilities vanish
   for (int i = tid; i < TP; i += NTHREADS) s_lse[i] = i < T ? lse[((long long)b * H + h) * T + i] : INFINITY;
   __syncthreads();
