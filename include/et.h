@@ -155,6 +155,9 @@ int et_bind(et_ctx* ctx, void* const* w_dev, void* const* opt_state_dev, void* c
  *               are charged to the tensor that must be passed for them to run (Section 5.3);
  *               a LayerNorm's input-gradient kernel is charged to its gain (Section 5.2);
  *   t_fwd_ns:   the whole forward pass including the loss and its gradient.
+ * Every timed iteration is followed by the same iteration without events, timed as a whole; the
+ * excess of the instrumented one is the measurement's own overhead and is taken off the regions
+ * in equal parts (at most half of a region's own time).
  * Host outputs; waits for the stream. */
 int et_profile(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, int32_t warmup, int32_t reps,
                uint64_t* t_fwd_ns, uint64_t* t_dw_ns /*[N]*/, uint64_t* t_dy_ns /*[N]*/);

@@ -823,12 +823,36 @@ int et_profile(et_ctx* c, const void* x_dev, const int32_t* y_dev, int32_t warmu
     ET_HIP(hipStreamSynchronize(c->stream));
     if (c->hip_err != hipSuccess) return ET_EHIP;
     if (!timed) continue;
+    // the same iteration without regions, timed as a whole: the instrumented one is slower by the
+    // measurement's own overhead, which is taken off the regions in equal parts (a region never
+    // loses more than half of what it measured)
+    hipEvent_t p0, p1;
+    ET_HIP(get_event(c, &p0));
+    ET_HIP(get_event(c, &p1));
+    ET_HIP(hipEventRecord(p0, c->stream));
+    rc = run_forward(c, x_dev, y_dev);
+    if (rc == ET_OK) rc = run_backward(c, x_dev, ones.data());
+    if (rc == ET_OK && with_update) rc = run_update(c, ones.data(), &opt, true);
+    if (rc != ET_OK) return rc;
+    ET_HIP(hipEventRecord(p1, c->stream));
+    ET_HIP(hipStreamSynchronize(c->stream));
+    if (c->hip_err != hipSuccess) return ET_EHIP;
+    float plain_ms = 0.f;
+    ET_HIP(hipEventElapsedTime(&plain_ms, p0, p1));
+    double instrumented = 0.0;
+    for (const Scope& sc : c->scopes) {
+      float ms = 0.f;
+      ET_HIP(hipEventElapsedTime(&ms, sc.e0, sc.e1));
+      instrumented += (double)ms * 1e6;
+    }
+    const double overhead = c->scopes.empty() ? 0.0 : std::max(0.0, (instrumented - (double)plain_ms * 1e6) / (double)c->scopes.size());
     std::vector<double> sdw(N, 0.0), sdy(N, 0.0);
     double sf = 0.0, su = 0.0;
     for (const Scope& sc : c->scopes) {
       float ms = 0.f;
       ET_HIP(hipEventElapsedTime(&ms, sc.e0, sc.e1));
-      const double ns = (double)ms * 1e6;
+      double ns = (double)ms * 1e6;
+      ns -= std::min(overhead, 0.5 * ns);
       if (sc.phase == PH_FWD) sf += ns;
       else if (sc.phase == PH_UPD) su += ns;
       else if (sc.phase == PH_DW) sdw[sc.tensor] += ns;
