@@ -55,6 +55,19 @@ def test_conv3x3_epilogues(batch, H, W, C, N, tile, mode):
     _case(batch, H, W, C, N, mode, tile, seed=mode * 100 + tile)
 
 
+# layer shapes of the VGG16 and ResNet-50 workloads (a few images; the weight gradient needs a multiple of 64 pixels)
+REAL = [(2, 224, 224, 64, 64), (2, 112, 112, 128, 128), (2, 56, 56, 256, 256), (4, 28, 28, 512, 512), (16, 14, 14, 512, 512),
+        (2, 56, 56, 64, 64), (16, 14, 14, 256, 256)]
+
+
+@pytest.mark.parametrize("batch,H,W,C,N", REAL)
+def test_conv3x3_workload_shapes(batch, H, W, C, N):
+    """Forward with bias + ReLU, gradient passing with the ReLU mask, weight gradient with the planned tile and split."""
+    _case(batch, H, W, C, N, 1, 0, seed=H + C)
+    _case(batch, H, W, C, N, 2, 0, seed=H + C + 1)
+    _case_dw(batch, H, W, C, N, 0, 0, seed=H + C + 2)
+
+
 def test_conv3x3_rejects_bad_arguments():
     import torch
     from paper_2312_14227_amd import binding as et
