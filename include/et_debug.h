@@ -55,6 +55,15 @@ size_t et_debug_depthwise3x3_ws_floats(int batch, int H, int W, int C, int strid
 int et_debug_depthwise3x3(int op, const void* a, const void* b, const void* gain, const void* shift, void* out0, void* out1,
                           float* ws, int batch, int H, int W, int C, int stride, void* stream);
 
+/* Device address and element count (bf16) of an activation the last forward pass of a bound context stored,
+ * so that a test can check one layer at a time against the layer's definition applied to the stored input.
+ * ET_VGG: "conv<i>.in" [batch][H][W][Cin], "conv<i>.y" (after bias + ReLU), "fc<j>.in" [batch][features];
+ * ET_MOBILENET: "stem.y", "b<i>.x" (block input), "b<i>.y_exp" (after the expansion's ReLU6; the block input
+ * when the block has no expansion), "b<i>.y_dw", "b<i>.y" (block output), "last.y".
+ * Returns 0, -1 for an unknown name or model kind, -5 before the first forward pass. */
+struct et_ctx;
+int et_debug_activation(const struct et_ctx* ctx, const char* name, const void** dev, size_t* numel);
+
 /* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16; 16-byte aligned device
  * pointers).  Used to calibrate hardware traffic counters against a known size. */
 int et_debug_copy(void* dst, const void* src, size_t bytes, void* stream);

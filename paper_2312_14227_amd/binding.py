@@ -68,6 +68,7 @@ def _load():
         "et_last_hip_error": (C.c_char_p, [vp]),
         "et_strerror": (C.c_char_p, [C.c_int]),
         "et_debug_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
+        "et_debug_activation": (C.c_int, [vp, C.c_char_p, C.POINTER(vp), C.POINTER(C.c_size_t)]),
         "et_debug_depthwise3x3_ws_floats": (C.c_size_t, [C.c_int] * 5),
         "et_debug_depthwise3x3": (C.c_int, [C.c_int] + [vp] * 7 + [C.c_int] * 5 + [vp]),
         "et_debug_conv3x3_dw": (C.c_int, [vp, vp, vp] + [C.c_int] * 6 + [vp, C.c_int, vp]),
@@ -84,7 +85,8 @@ _lib = _load()
 EXPORTS = ["et_create", "et_destroy", "et_num_tensors", "et_tensor_info", "et_workspace_bytes", "et_state_slots",
            "et_bind", "et_profile", "et_importance", "et_importance_master", "et_select", "et_select_stats", "et_tensor_metric", "et_train_step", "et_last_launch_counts",
            "et_kernel_timing", "et_kernel_timing_read", "et_last_hip_error", "et_strerror", "et_debug_gemm_bf16", "et_debug_copy", "et_debug_conv3x3",
-           "et_debug_conv3x3_dw", "et_debug_depthwise3x3", "et_debug_depthwise3x3_ws_floats"]
+           "et_debug_conv3x3_dw", "et_debug_depthwise3x3", "et_debug_depthwise3x3_ws_floats",
+           "et_debug_activation"]
 
 
 def strerror(status):
@@ -279,6 +281,13 @@ def et_debug_conv3x3(x, w, out, batch, H, W, Cin, N, bias=0, U=0, mode=0, tile=0
 def et_debug_conv3x3_dw(x, d, dw, batch, H, W, Cin, N, split_k=1, partials=0, tile=0, stream=0):
     return _lib.et_debug_conv3x3_dw(C.c_void_p(x), C.c_void_p(d), C.c_void_p(dw), batch, H, W, Cin, N, split_k,
                                     C.c_void_p(partials), tile, C.c_void_p(stream))
+
+
+def et_debug_activation(ctx, name):
+    """(device address, element count) of a stored bf16 activation."""
+    p, n = C.c_void_p(), C.c_size_t()
+    _check(_lib.et_debug_activation(ctx, name.encode(), C.byref(p), C.byref(n)), "et_debug_activation")
+    return p.value, n.value
 
 
 def et_debug_depthwise3x3(op, a, b, gain, shift, out0, out1, ws, batch, H, W, Cch, stride, stream=0):

@@ -705,6 +705,37 @@ int et_last_launch_counts(const et_ctx* c, int32_t* forward, int32_t* backward, 
   return ET_OK;
 }
 
+int et_debug_activation(const et_ctx* c, const char* name, const void** dev, size_t* numel) {
+  if (!c || !name || !dev || !numel || !c->bound) return ET_EINVAL;
+  const std::string n(name);
+  const size_t B = c->desc.batch;
+  *dev = nullptr;
+  *numel = 0;
+  auto give = [&](const void* p, size_t count) { *dev = p; *numel = count; return p ? ET_OK : ET_ESTATE; };
+  if (c->desc.kind == ET_VGG) {
+    for (size_t i = 0; i < c->vconv.size(); i++) {
+      const ConvUnit& u = c->vconv[i];
+      const std::string pre = "conv" + std::to_string(i);
+      if (n == pre + ".in") return give(u.in, B * u.H * u.W * u.Cin);
+      if (n == pre + ".y") return give(u.y, B * u.Ho * u.Wo * u.Cout);
+    }
+    for (size_t j = 0; j < c->vact.size(); j++)
+      if (n == "fc" + std::to_string(j) + ".in") return give(c->vact[j], B * c->vdims[j]);
+  } else if (c->desc.kind == ET_MOBILENET) {
+    if (n == "stem.y") return give(c->stem.y, B * c->stem.Ho * c->stem.Wo * c->stem.Cout);
+    if (n == "last.y") return give(c->mlast.y, B * c->mlast.Ho * c->mlast.Wo * c->mlast.Cout);
+    for (size_t i = 0; i < c->mblk.size(); i++) {
+      const MbBlockBufs& b = c->mblk[i];
+      const std::string pre = "b" + std::to_string(i);
+      if (n == pre + ".x") return give(b.x, B * b.H * b.W * b.Cin);
+      if (n == pre + ".y_exp") return give(b.expand ? b.y_exp : b.x, B * b.H * b.W * b.hid);
+      if (n == pre + ".y_dw") return give(b.y_dw, B * b.Ho * b.Wo * b.hid);
+      if (n == pre + ".y") return give(b.y, B * b.Ho * b.Wo * b.Cout);
+    }
+  }
+  return ET_EINVAL;
+}
+
 int et_kernel_timing(et_ctx* c, int32_t enable) {
   if (!c) return ET_EINVAL;
   ET_HIP(hipStreamSynchronize(c->stream));

@@ -103,6 +103,15 @@ class Session:
     def profile(self, xt, yt, warmup=2, reps=5):
         return et.et_profile(self.ctx, xt.data_ptr(), yt.data_ptr(), warmup, reps)
 
+    def activation(self, name, shape):
+        """View (no copy) of a bf16 activation the last forward pass stored in the workspace."""
+        ptr, numel = et.et_debug_activation(self.ctx, name)
+        assert numel == int(np.prod(shape)), (name, numel, shape)
+        if ptr >= self.ws_ptr and ptr + 2 * numel <= self.ws_ptr + self.ws_bytes:
+            off = ptr - self.ws.data_ptr()
+            return self.ws[off:off + 2 * numel].view(torch.bfloat16).view(*shape)
+        return None     # the network input itself: not in the workspace
+
     def launch_counts(self):
         return et.et_last_launch_counts(self.ctx)
 

@@ -1,0 +1,162 @@
+"""Layer-by-layer parity of the forward pass at the full size of the VGG16 and MobileNetV2 workloads.
+
+End to end, two correct bf16 evaluations of these deep ReLU networks disagree by far more than a rounding
+(tests/test_gpu_full_size.py explains and bounds that).  Here every layer is checked on its own: the layer's
+definition is applied, in float64, to the input activation the HIP path itself stored, at sampled output
+positions, and compared with the output activation the HIP path stored.  No error is carried from one layer to
+the next, so the bound is one accumulation in fp32 (3e-5 of the sum of the absolute products: several standard deviations for
+up to 25 088 terms) plus the bf16 roundings of that layer."""
+import numpy as np
+import pytest
+
+from synth import CONFIGS, make_workload, mobilenet_blocks
+
+pytestmark = pytest.mark.gpu
+SAMPLES = 48
+EPS = 2.0 ** -8
+
+
+def _forward_only(cfg):
+    import torch
+    from paper_2312_14227_amd.session import Session
+    wl = make_workload(cfg, seed=0)
+    s = Session(cfg, wl.weights, with_state=False)
+    xt, yt = s.put_input(wl.x, wl.y)
+    s.train_step(xt, yt, np.zeros(len(wl.weights), dtype=np.uint8))     # forward and loss only
+    torch.cuda.synchronize()
+    return wl, s, xt
+
+
+def _patches(act, pos, stride=1):
+    """act [B,H,W,C] (device, bf16); pos [n,3] output positions -> float64 [n,3,3,C], zero outside the image."""
+    import torch
+    B, H, W, C = act.shape
+    out = np.zeros((len(pos), 3, 3, C))
+    b = torch.as_tensor(pos[:, 0], device=act.device)
+    for ky in range(3):
+        for kx in range(3):
+            h = pos[:, 1] * stride + ky - 1
+            w = pos[:, 2] * stride + kx - 1
+            ok = (h >= 0) & (h < H) & (w >= 0) & (w < W)
+            hh = torch.as_tensor(np.clip(h, 0, H - 1), device=act.device)
+            ww = torch.as_tensor(np.clip(w, 0, W - 1), device=act.device)
+            v = act[b, hh, ww, :].float().cpu().numpy().astype(np.float64)
+            out[:, ky, kx, :] = v * ok[:, None]
+    return out
+
+
+def _rows(act, pos):
+    import torch
+    i = [torch.as_tensor(pos[:, k], device=act.device) for k in range(3)]
+    return act[i[0], i[1], i[2], :].float().cpu().numpy().astype(np.float64)
+
+
+def _positions(rng, B, H, W):
+    pos = np.stack([rng.integers(0, B, SAMPLES), rng.integers(0, H, SAMPLES), rng.integers(0, W, SAMPLES)], axis=1)
+    pos[0, 1:] = 0                 # corners and an edge: the zero padding
+    pos[1, 1:] = (H - 1, W - 1)
+    pos[2, 1:] = (0, W // 2)
+    return pos
+
+
+def test_vgg16_forward_layer_by_layer():
+    import torch
+    cfg = CONFIGS["vgg16"]
+    wl, s, xt = _forward_only(cfg)
+    W = [w.astype(np.float64) for w in wl.weights]
+    rng = np.random.default_rng(0)
+    B, H, cin, t, i = cfg.batch, cfg.image, cfg.in_ch, 0, 0
+    worst = 0.0
+    prev_y = None
+    for width, n in zip(cfg.widths, cfg.convs):
+        for k in range(n):
+            xin = s.activation("conv%d.in" % i, (B, H, H, cin))
+            if xin is None:
+                xin = xt.view(B, H, H, cin)
+            if k == 0 and prev_y is not None:      # the pooled tensor: exactly the 2x2 maximum of the previous activation
+                pooled = torch.nn.functional.max_pool2d(prev_y.float().permute(0, 3, 1, 2), 2).permute(0, 2, 3, 1)
+                assert torch.equal(pooled, xin.float())
+            y = s.activation("conv%d.y" % i, (B, H, H, width))
+            pos = _positions(rng, B, H, H)
+            p = _patches(xin, pos).reshape(SAMPLES, -1)
+            wm = W[t].reshape(width, -1)
+            ref = np.maximum(p @ wm.T + W[t + 1], 0.0)
+            bound = EPS * np.abs(ref) + 3e-5 * (np.abs(p) @ np.abs(wm).T + np.abs(W[t + 1])) + 1e-6
+            err = np.abs(_rows(y, pos) - ref)
+            assert (err <= bound).all(), ("conv%d" % i, float((err / bound).max()))
+            worst = max(worst, float((err / bound).max()))
+            prev_y, cin, t, i = y, width, t + 2, i + 1
+        H //= 2
+    # linear layers: sampled output units of every hidden layer
+    feat = H * H * cin
+    dims = [feat] + list(cfg.fc)
+    for j in range(len(cfg.fc)):
+        a = s.activation("fc%d.in" % j, (B, 1, 1, dims[j])).view(B, dims[j]).float().cpu().numpy().astype(np.float64)
+        nxt = s.activation("fc%d.in" % (j + 1), (B, 1, 1, dims[j + 1])).view(B, dims[j + 1]).float().cpu().numpy().astype(np.float64)
+        cols = rng.integers(0, dims[j + 1], 64)
+        ref = np.maximum(a @ W[t][cols].T + W[t + 1][cols], 0.0)
+        bound = EPS * np.abs(ref) + 3e-5 * (np.abs(a) @ np.abs(W[t][cols]).T) + 1e-6
+        err = np.abs(nxt[:, cols] - ref)
+        assert (err <= bound).all(), ("fc%d" % j, float((err / bound).max()))
+        t += 2
+    print("VGG16 forward, layer by layer at full size: worst error / bound %.3f" % worst)
+    s.close()
+
+
+def test_mobilenetv2_forward_layer_by_layer():
+    cfg = CONFIGS["mobilenetv2"]
+    wl, s, xt = _forward_only(cfg)
+    W = [w.astype(np.float64) for w in wl.weights]
+    rng = np.random.default_rng(1)
+    B = cfg.batch
+    relu6 = lambda a: np.minimum(np.maximum(a, 0.0), 6.0)
+    worst = [0.0]
+
+    def check(name, got, z, zabs, g, b, lo, hi, add=None):
+        """got = clamp(bf16(z) * g + b [+ add]): one rounding of z, one of the result, fp32 accumulation."""
+        ref = z * g + b + (0.0 if add is None else add)
+        ref = np.minimum(np.maximum(ref, lo), hi)
+        bound = EPS * (np.abs(z * g) + np.abs(ref)) + 3e-5 * zabs * np.abs(g) + 1e-6
+        err = np.abs(got - ref)
+        assert (err <= bound).all(), (name, float((err / bound).max()))
+        worst[0] = max(worst[0], float((err / bound).max()))
+
+    # stem: 3x3 / stride 2 on the input images
+    Hs = (cfg.image - 1) // 2 + 1
+    stem_y = s.activation("stem.y", (B, Hs, Hs, cfg.stem))
+    pos = _positions(rng, B, Hs, Hs)
+    p = _patches(xt.view(B, cfg.image, cfg.image, cfg.in_ch), pos, stride=2).reshape(SAMPLES, -1)
+    wm = W[0].reshape(cfg.stem, -1)
+    check("stem", _rows(stem_y, pos), p @ wm.T, np.abs(p) @ np.abs(wm).T, W[1], W[2], 0.0, 6.0)
+    H, t = Hs, 3
+    for i, (cin, hid, cout, stride, expand, shortcut) in enumerate(mobilenet_blocks(cfg)):
+        Ho = (H - 1) // stride + 1
+        x = s.activation("b%d.x" % i, (B, H, H, cin))
+        y_exp = s.activation("b%d.y_exp" % i, (B, H, H, hid))
+        y_dw = s.activation("b%d.y_dw" % i, (B, Ho, Ho, hid))
+        y = s.activation("b%d.y" % i, (B, Ho, Ho, cout))
+        if expand:
+            pos = _positions(rng, B, H, H)
+            xr = _rows(x, pos)
+            wm = W[t].reshape(hid, cin)
+            check("b%d.exp" % i, _rows(y_exp, pos), xr @ wm.T, np.abs(xr) @ np.abs(wm).T, W[t + 1], W[t + 2], 0.0, 6.0)
+            t += 3
+        pos = _positions(rng, B, Ho, Ho)
+        p = _patches(y_exp, pos, stride=stride)                      # [n,3,3,hid]
+        wd = W[t].reshape(hid, 3, 3).transpose(1, 2, 0)               # [3,3,hid]
+        check("b%d.dw" % i, _rows(y_dw, pos), (p * wd).sum(axis=(1, 2)), (np.abs(p) * np.abs(wd)).sum(axis=(1, 2)),
+              W[t + 1], W[t + 2], 0.0, 6.0)
+        a = _rows(y_dw, pos)
+        wm = W[t + 3].reshape(cout, hid)
+        check("b%d.proj" % i, _rows(y, pos), a @ wm.T, np.abs(a) @ np.abs(wm).T, W[t + 4], W[t + 5], -np.inf, np.inf,
+              add=_rows(x, pos) if shortcut else None)
+        t += 6
+        H = Ho
+    last_y = s.activation("last.y", (B, H, H, cfg.last))
+    c_last = mobilenet_blocks(cfg)[-1][2]
+    pos = _positions(rng, B, H, H)
+    a = _rows(s.activation("b%d.y" % (len(mobilenet_blocks(cfg)) - 1), (B, H, H, c_last)), pos)
+    wm = W[t].reshape(cfg.last, c_last)
+    check("last", _rows(last_y, pos), a @ wm.T, np.abs(a) @ np.abs(wm).T, W[t + 1], W[t + 2], 0.0, 6.0)
+    print("MobileNetV2 forward, layer by layer at full size: worst error / bound %.3f" % worst[0])
+    s.close()
