@@ -99,30 +99,55 @@ __global__ __launch_bounds__(256) void masked_update_kernel(const UpdateSeg* __r
   float* __restrict__ v = sg.v;
   float* __restrict__ wf = BF16W ? sg.master : (float*)sg.w;
   bf16* __restrict__ wb = (bf16*)sg.w;
-  for (uint32_t i = threadIdx.x; i < sg.n; i += 256) {
-    const float gi = g[i];
-    const float w_old = wf[i];
-    float w = w_old;
+  // one element: returns the new weight, updates the moments in place (unless dry)
+  auto one = [&](float gi, float w_old, float& mi, float& vi) -> float {
     if (p.kind == 0) {
-      const float m_old = m[i], v_old = v[i];
-      const float mi = p.beta1 * m_old + (1.f - p.beta1) * gi;
-      const float vi = p.beta2 * v_old + (1.f - p.beta2) * gi * gi;
-      m[i] = p.dry ? m_old : mi;
-      v[i] = p.dry ? v_old : vi;
-      w -= p.lr * (mi / p.bc1) / (sqrtf(vi / p.bc2) + p.eps);
-    } else {
-      const float m_old = m[i];
-      const float mi = p.momentum * m_old + gi;
-      m[i] = p.dry ? m_old : mi;
-      w = w - p.lr * mi - p.lr * p.wd * w;
+      const float m_new = p.beta1 * mi + (1.f - p.beta1) * gi;
+      const float v_new = p.beta2 * vi + (1.f - p.beta2) * gi * gi;
+      const float w = w_old - p.lr * (m_new / p.bc1) / (sqrtf(v_new / p.bc2) + p.eps);
+      if (!p.dry) { mi = m_new; vi = v_new; }
+      return w;
     }
-    if (p.dry) {
-      wf[i] = w_old;
-      if (BF16W) wb[i] = wb[i];
-    } else {
-      wf[i] = w;
-      if (BF16W) wb[i] = (bf16)w;
+    const float m_new = p.momentum * mi + gi;
+    const float w = w_old - p.lr * m_new - p.lr * p.wd * w_old;
+    if (!p.dry) mi = m_new;
+    return w;
+  };
+  // chunks start at multiples of 16 384 elements of 256-byte aligned tensors: 16-byte vectors of 4 elements
+  const uint32_t n4 = sg.n >> 2;
+  for (uint32_t i = threadIdx.x; i < n4; i += 256) {
+    const float4 g4 = ((const float4*)g)[i];
+    float4 w4 = ((const float4*)wf)[i];
+    float4 m4 = ((const float4*)m)[i];
+    float4 v4 = p.kind == 0 ? ((const float4*)v)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    const float4 w_old = w4;
+    w4.x = one(g4.x, w4.x, m4.x, v4.x);
+    w4.y = one(g4.y, w4.y, m4.y, v4.y);
+    w4.z = one(g4.z, w4.z, m4.z, v4.z);
+    w4.w = one(g4.w, w4.w, m4.w, v4.w);
+    // a dry run (profiling) moves the same bytes and leaves every value as it was
+    ((float4*)m)[i] = m4;
+    if (p.kind == 0) ((float4*)v)[i] = v4;
+    ((float4*)wf)[i] = p.dry ? w_old : w4;
+    if (BF16W) {
+      typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+      bf16x4 o;
+      if (p.dry) {
+        o = ((const bf16x4*)wb)[i];
+      } else {
+        o[0] = (bf16)w4.x; o[1] = (bf16)w4.y; o[2] = (bf16)w4.z; o[3] = (bf16)w4.w;
+      }
+      ((bf16x4*)wb)[i] = o;
     }
+  }
+  for (uint32_t i = (n4 << 2) + threadIdx.x; i < sg.n; i += 256) {   // at most three elements
+    float mi = m[i], vi = p.kind == 0 ? v[i] : 0.f;
+    const float w_old = wf[i];
+    const float w = one(g[i], w_old, mi, vi);
+    m[i] = mi;
+    if (p.kind == 0) v[i] = vi;
+    wf[i] = p.dry ? w_old : w;
+    if (BF16W) wb[i] = p.dry ? wb[i] : (bf16)w;
   }
 }
 
