@@ -58,6 +58,8 @@ int et_debug_depthwise3x3(int op, const void* a, const void* b, const void* gain
 /* Device address and element count (bf16) of an activation the last forward pass of a bound context stored,
  * so that a test can check one layer at a time against the layer's definition applied to the stored input.
  * ET_VGG: "conv<i>.in" [batch][H][W][Cin], "conv<i>.y" (after bias + ReLU), "fc<j>.in" [batch][features];
+ * ET_RESNET: "stem.y" (after affine + ReLU, before pooling), "pooled", per block in forward order "blk<i>.x"
+ * (block input), "blk<i>.y1", "blk<i>.y2" (after the first / second convolution's affine + ReLU), "blk<i>.y";
  * ET_MOBILENET: "stem.y", "b<i>.x" (block input), "b<i>.y_exp" (after the expansion's ReLU6; the block input
  * when the block has no expansion), "b<i>.y_dw", "b<i>.y" (block output), "last.y".
  * Returns 0, -1 for an unknown name or model kind, -5 before the first forward pass. */

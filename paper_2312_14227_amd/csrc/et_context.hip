@@ -721,6 +721,18 @@ int et_debug_activation(const et_ctx* c, const char* name, const void** dev, siz
     }
     for (size_t j = 0; j < c->vact.size(); j++)
       if (n == "fc" + std::to_string(j) + ".in") return give(c->vact[j], B * c->vdims[j]);
+  } else if (c->desc.kind == ET_RESNET) {
+    const ConvUnit& st = c->stem;
+    if (n == "stem.y") return give(c->pool_y, B * st.Ho * st.Wo * st.Cout);
+    if (n == "pooled") return give(c->pooled, B * c->rblk[0].c1.H * c->rblk[0].c1.W * st.Cout);
+    for (size_t i = 0; i < c->rblk.size(); i++) {
+      const ResBlockBufs& b = c->rblk[i];
+      const std::string pre = "blk" + std::to_string(i);
+      if (n == pre + ".x") return give(b.x, B * b.c1.H * b.c1.W * b.c1.Cin);
+      if (n == pre + ".y1") return give(b.c1.y, B * b.c1.Ho * b.c1.Wo * b.c1.Cout);
+      if (n == pre + ".y2") return give(b.c2.y, B * b.c2.Ho * b.c2.Wo * b.c2.Cout);
+      if (n == pre + ".y") return give(b.y, B * b.c3.Ho * b.c3.Wo * b.c3.Cout);
+    }
   } else if (c->desc.kind == ET_MOBILENET) {
     if (n == "stem.y") return give(c->stem.y, B * c->stem.Ho * c->stem.Wo * c->stem.Cout);
     if (n == "last.y") return give(c->mlast.y, B * c->mlast.Ho * c->mlast.Wo * c->mlast.Cout);

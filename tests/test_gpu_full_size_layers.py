@@ -160,3 +160,87 @@ def test_mobilenetv2_forward_layer_by_layer():
     check("last", _rows(last_y, pos), a @ wm.T, np.abs(a) @ np.abs(wm).T, W[t + 1], W[t + 2], 0.0, 6.0)
     print("MobileNetV2 forward, layer by layer at full size: worst error / bound %.3f" % worst[0])
     s.close()
+
+
+def test_resnet50_forward_layer_by_layer():
+    import torch
+    from oracle import resnet as R
+    cfg = CONFIGS["resnet50"]
+    wl, s, xt = _forward_only(cfg)
+    W = [w.astype(np.float64) for w in wl.weights]
+    rng = np.random.default_rng(2)
+    B = cfg.batch
+    worst = [0.0]
+
+    def check(name, got, parts, b_sum):
+        """got = max(sum over parts of bf16(z) * g + shifts, 0); parts: [(z, sum of |products|, gain)]."""
+        ref = sum(z * g for z, _, g in parts) + b_sum
+        ref = np.maximum(ref, 0.0)
+        bound = EPS * (sum(np.abs(z * g) for z, _, g in parts) + np.abs(ref)) + 3e-5 * sum(za * np.abs(g) for _, za, g in parts) + 1e-6
+        err = np.abs(got - ref)
+        assert (err <= bound).all(), (name, float((err / bound).max()))
+        worst[0] = max(worst[0], float((err / bound).max()))
+
+    def conv_at(act, pos, w, stride):
+        """z and the sum of absolute products of a 1x1 or 3x3 convolution (stride as given) at output positions pos."""
+        O, k, _, C = w.shape
+        if k == 1:
+            src = pos.copy()
+            src[:, 1:] *= stride
+            p = _rows(act, src)
+        else:
+            p = _patches(act, pos, stride=stride).reshape(len(pos), -1)
+        wm = w.reshape(O, -1)
+        return p @ wm.T, np.abs(p) @ np.abs(wm).T
+
+    # stem: 7x7 / stride 2 on the images; its convolution output stays fp32, so only the output rounding counts
+    Hs = (cfg.image + 6 - 7) // 2 + 1
+    stem_y = s.activation("stem.y", (B, Hs, Hs, cfg.stem))
+    pos = _positions(rng, B, Hs, Hs)
+    x = xt.view(B, cfg.image, cfg.image, cfg.in_ch)
+    p = np.zeros((SAMPLES, 7, 7, cfg.in_ch))
+    bi = torch.as_tensor(pos[:, 0], device=x.device)
+    for ky in range(7):
+        for kx in range(7):
+            h, w_ = pos[:, 1] * 2 + ky - 3, pos[:, 2] * 2 + kx - 3
+            ok = (h >= 0) & (h < cfg.image) & (w_ >= 0) & (w_ < cfg.image)
+            v = x[bi, torch.as_tensor(np.clip(h, 0, cfg.image - 1), device=x.device),
+                  torch.as_tensor(np.clip(w_, 0, cfg.image - 1), device=x.device), :].float().cpu().numpy().astype(np.float64)
+            p[:, ky, kx, :] = v * ok[:, None]
+    p = p.reshape(SAMPLES, -1)
+    wm = W[0].reshape(cfg.stem, -1)
+    z = p @ wm.T
+    ref = np.maximum(z * W[1] + W[2], 0.0)
+    err = np.abs(_rows(stem_y, pos) - ref)
+    bound = EPS * np.abs(ref) + 3e-5 * (np.abs(p) @ np.abs(wm).T) * np.abs(W[1]) + 1e-6
+    assert (err <= bound).all(), ("stem", float((err / bound).max()))
+    Hp = (Hs - 1) // 2 + 1
+    pooled = s.activation("pooled", (B, Hp, Hp, cfg.stem))
+    ref_pool = torch.nn.functional.max_pool2d(stem_y.float().permute(0, 3, 1, 2), 3, stride=2, padding=1).permute(0, 2, 3, 1)
+    assert torch.equal(ref_pool, pooled.float())        # pooling decided on unrounded values gives the same maxima
+    H = Hp
+    layout, t_head = R.block_layout(cfg)
+    cin = cfg.stem
+    for i, (si, bj, stride, proj, t) in enumerate(layout):
+        pl = cfg.planes[si]
+        Ho = (H - 1) // stride + 1
+        xb = s.activation("blk%d.x" % i, (B, H, H, cin))
+        y1 = s.activation("blk%d.y1" % i, (B, H, H, pl))
+        y2 = s.activation("blk%d.y2" % i, (B, Ho, Ho, pl))
+        y = s.activation("blk%d.y" % i, (B, Ho, Ho, 4 * pl))
+        pos = _positions(rng, B, H, H)
+        z, za = conv_at(xb, pos, W[t], 1)
+        check("blk%d.c1" % i, _rows(y1, pos), [(z, za, W[t + 1])], W[t + 2])
+        pos = _positions(rng, B, Ho, Ho)
+        z, za = conv_at(y1, pos, W[t + 3], stride)
+        check("blk%d.c2" % i, _rows(y2, pos), [(z, za, W[t + 4])], W[t + 5])
+        z, za = conv_at(y2, pos, W[t + 6], 1)
+        if proj:
+            zs, zsa = conv_at(xb, pos, W[t + 9], stride)
+            check("blk%d.end" % i, _rows(y, pos), [(z, za, W[t + 7]), (zs, zsa, W[t + 10])], W[t + 8] + W[t + 11])
+        else:
+            xr = _rows(xb, pos)
+            check("blk%d.end" % i, _rows(y, pos), [(z, za, W[t + 7]), (xr, 0.0 * xr, np.ones(4 * pl))], W[t + 8])
+        H, cin = Ho, 4 * pl
+    print("ResNet-50 forward, layer by layer at full size: worst error / bound %.3f" % worst[0])
+    s.close()
