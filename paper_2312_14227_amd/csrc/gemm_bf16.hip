@@ -85,19 +85,18 @@ Plan plan_large(int M, int N, int K, bool may_split) {
 // few output channels take the tiles that are narrow in M (rates measured on the VGG16 shapes)
 Plan plan_conv_dw(int M, int N, int K) {
   static const TileRate cand[4] = {{T_PP_256x256, 256, 256, 3.3e12}, {T_PP_256x192, 256, 192, 3.0e12},
-                                   {T_PP_128x256, 128, 256, 2.4e12}, {T_PP_64x512, 64, 512, 1.6e12}};
+                                   {T_PP_128x256, 128, 256, 2.4e12}, {T_PP_64x512, 64, 512, 2.0e12}};
   return plan_tiles(M, N, K, true, cand, 4);
 }
 
-// implicit convolution: two-group tiles only; narrow outputs take the narrow tiles
+// implicit convolution (forward, gradient passing): the same cost model over the four tiles, with the rates a
+// CU sustains on the VGG16 layer shapes (the shifted rows of the nine taps hit in the L2, so the wide tiles
+// run faster here than on a stored matrix)
 int choose_conv_tile(const GemmDesc& d) {
   if (d.tile == T_PP_256x256 || d.tile == T_PP_256x192 || d.tile == T_PP_256x128 || d.tile == T_PP_512x64) return d.tile;
-  if (d.N <= 64) return T_PP_512x64;
-  if (d.N <= 128) return T_PP_256x128;
-  // few tiles: the narrower tile fills more CUs
-  const long long t256 = (long long)((d.M + 255) / 256) * ((d.N + 255) / 256);
-  if (t256 < 200) return T_PP_256x128;
-  return plan_large(d.M, d.N, d.K, false).tile;
+  static const TileRate cand[4] = {{T_PP_256x256, 256, 256, 4.5e12}, {T_PP_256x192, 256, 192, 4.0e12},
+                                   {T_PP_256x128, 256, 128, 3.3e12}, {T_PP_512x64, 512, 64, 2.6e12}};
+  return plan_tiles(d.M, d.N, d.K, false, cand, 4).tile;
 }
 
 int choose_tile(const GemmDesc& d, int k_per_block) {
