@@ -110,6 +110,15 @@ int choose_tile(const GemmDesc& d, int k_per_block) {
   // large problems: a two-group tile where K comes in slices of 64 (4-20 % faster than either
   // direct-to-LDS tile on every forward, passing and gradient product of the ViT shapes), else
   // the direct-to-LDS tile with slices of 32
+  // too few 256x256 tiles to fill the 256 CUs: products of more than 8 GFLOP (a ViT-L layer at batch 32) take the
+  // 256x128 two-group tile (13 % faster there than 256x192), smaller ones (late ResNet / MobileNet stages: a few
+  // thousand rows) the register-staged tiles, several workgroups per CU, which are up to twice as fast there
+  const long long big_tiles = (long long)((d.M + 255) / 256) * ((d.N + 255) / 256) * d.z_outer * d.z_inner;
+  if (d.M >= 512 && d.N >= 256 && big_tiles < 128 && d.mode != EPI_GELU_FWD && d.mode != EPI_GELU_BWD && d.mode != EPI_GELU_ONLY) {
+    if (pp_ok && k_per_block >= 4 * gemm::PBK && 2.0 * d.M * d.N * (double)k_per_block >= 8e9 && d.z_outer * d.z_inner == 1)
+      return T_PP_256x128;
+    return (long long)((d.M + 127) / 128) * ((d.N + 127) / 128) >= 256 ? T_128x128 : T_128x64;
+  }
   if (d.M >= 512 && d.N >= 256) {
     // the GELU epilogues (two outputs or an extra operand, transcendental math) take as long as a
     // short main loop; two 256x128 workgroups per CU overlap one's epilogue with the other's MFMAs
