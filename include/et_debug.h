@@ -34,6 +34,15 @@ int et_debug_gemm_bf16(const void* A, const void* B, void* C, int M, int N, int 
 int et_debug_conv3x3(const void* x, const void* w, void* out, int batch, int H, int W, int C, int N,
                      const void* bias, const void* U, int mode, int tile, void* stream);
 
+/* The same convolution with its reduction over (tap, channel) split into split_k ranges (layers with few
+ * pixels): fp32 parts go to `partials` (batch*H*W * N * split_k floats), a second kernel adds them in
+ * ascending order and applies the epilogue.  mode 0, 1, 2 as above; 3: z_out (nullable) = the convolution
+ * rounded to bf16, out = min(max(z * gain[n] + bias[n], 0), 6).  split_k = 0 lets the library plan tile and
+ * split (then `partials` must hold 18 such copies).  N a multiple of 4. */
+int et_debug_conv3x3_split(const void* x, const void* w, void* out, void* z_out, int batch, int H, int W, int C, int N,
+                           const void* bias, const void* gain, const void* U, int mode, int split_k, float* partials, int tile,
+                           void* stream);
+
 /* Weight gradient of that convolution as an implicit GEMM: dw[n][ky][kx][c] = sum over pixels (b, h, w) of
  * d[b][h][w][n] * x[b][h+ky-1][w+kx-1][c].  x bf16 NHWC, C a multiple of 8; d bf16 [batch*H*W][N], N a multiple of 8;
  * dw fp32 [N][9 C]; batch*H*W a multiple of 64; H, W < 4096.  split_k > 1 reduces over that many pixel ranges

@@ -71,6 +71,7 @@ def _load():
         "et_debug_activation": (C.c_int, [vp, C.c_char_p, C.POINTER(vp), C.POINTER(C.c_size_t)]),
         "et_debug_depthwise3x3_ws_floats": (C.c_size_t, [C.c_int] * 5),
         "et_debug_depthwise3x3": (C.c_int, [C.c_int] + [vp] * 7 + [C.c_int] * 5 + [vp]),
+        "et_debug_conv3x3_split": (C.c_int, [vp, vp, vp, vp] + [C.c_int] * 5 + [vp, vp, vp, C.c_int, C.c_int, vp, C.c_int, vp]),
         "et_debug_conv3x3_dw": (C.c_int, [vp, vp, vp] + [C.c_int] * 6 + [vp, C.c_int, vp]),
         "et_debug_conv3x3": (C.c_int, [vp, vp, vp] + [C.c_int] * 5 + [vp, vp, C.c_int, C.c_int, vp]),
         "et_debug_gemm_bf16": (C.c_int, [vp, vp, vp] + [C.c_int] * 9 + [C.c_float, vp, vp, C.c_int, vp, C.c_int, vp]),
@@ -86,7 +87,7 @@ EXPORTS = ["et_create", "et_destroy", "et_num_tensors", "et_tensor_info", "et_wo
            "et_bind", "et_profile", "et_importance", "et_importance_master", "et_select", "et_select_stats", "et_tensor_metric", "et_train_step", "et_last_launch_counts",
            "et_kernel_timing", "et_kernel_timing_read", "et_last_hip_error", "et_strerror", "et_debug_gemm_bf16", "et_debug_copy", "et_debug_conv3x3",
            "et_debug_conv3x3_dw", "et_debug_depthwise3x3", "et_debug_depthwise3x3_ws_floats",
-           "et_debug_activation"]
+           "et_debug_activation", "et_debug_conv3x3_split"]
 
 
 def strerror(status):
@@ -276,6 +277,13 @@ def et_debug_gemm_bf16(A, B, Cp, M, N, K, lda, ldb, ldc, a_t, b_t, c_f32, alpha=
 def et_debug_conv3x3(x, w, out, batch, H, W, Cin, N, bias=0, U=0, mode=0, tile=0, stream=0):
     return _lib.et_debug_conv3x3(C.c_void_p(x), C.c_void_p(w), C.c_void_p(out), batch, H, W, Cin, N, C.c_void_p(bias),
                                  C.c_void_p(U), mode, tile, C.c_void_p(stream))
+
+
+def et_debug_conv3x3_split(x, w, out, z_out, batch, H, W, Cin, N, bias=0, gain=0, U=0, mode=0, split_k=0, partials=0, tile=0,
+                           stream=0):
+    return _lib.et_debug_conv3x3_split(C.c_void_p(x), C.c_void_p(w), C.c_void_p(out), C.c_void_p(z_out), batch, H, W, Cin, N,
+                                       C.c_void_p(bias), C.c_void_p(gain), C.c_void_p(U), mode, split_k, C.c_void_p(partials), tile,
+                                       C.c_void_p(stream))
 
 
 def et_debug_conv3x3_dw(x, d, dw, batch, H, W, Cin, N, split_k=1, partials=0, tile=0, stream=0):

@@ -41,6 +41,26 @@ inline bool implicit_dy(const ConvUnit& u) { return u.k == 3 && u.stride == 1 &&
 inline bool implicit_dw(const et_ctx* c, const ConvUnit& u) {
   return u.k == 3 && u.stride == 1 && (u.Cin % 8) == 0 && ((size_t)c->desc.batch * u.H * u.W) % 64 == 0 && u.H < 4096 && u.W < 4096;
 }
+// tile and split of a unit's implicit forward (or, with the channel roles exchanged, gradient-passing) product
+inline void plan_implicit(et_ctx* c, et::GemmDesc& g) {
+  et::gemm_bf16_plan_conv(g.M, g.N, g.K, &g.tile, &g.split_k);
+  g.partials = c->gemm_partials;
+  if (et::gemm_bf16_partial_elems(g.M, g.N, g.split_k) > c->gemm_partial_elems) g.split_k = 1;
+}
+inline size_t conv_split_partials(const et_ctx* c, const ConvUnit& u) {
+  size_t n = 0;
+  int tile, split;
+  const int M = (int)rows_of(c, u);
+  if (implicit_fwd(u)) {
+    et::gemm_bf16_plan_conv(M, u.Cout, 9 * u.Cin, &tile, &split);
+    n = std::max(n, et::gemm_bf16_partial_elems(M, u.Cout, split));
+  }
+  if (implicit_dy(u)) {
+    et::gemm_bf16_plan_conv(M, u.Cin, 9 * u.Cout, &tile, &split);
+    n = std::max(n, et::gemm_bf16_partial_elems(M, u.Cin, split));
+  }
+  return n;
+}
 // fp32 partial elements of a unit's weight gradient with the split its plan chooses
 inline size_t conv_dw_partials(const et_ctx* c, const ConvUnit& u) {
   const int M = (int)rows_of(c, u);
@@ -71,6 +91,7 @@ inline int conv_forward(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16
       g.mode = et::EPI_AFFINE_ADD_RELU; g.U = branch; g.gain2 = gain2; g.bias2 = shift2;
     }
   }
+  if (implicit_fwd(u) && !z_f32 && !branch) plan_implicit(c, g);
   ET_G(g);
   return ET_OK;
 }
@@ -116,6 +137,7 @@ inline int conv_dy_implicit(et_ctx* c, const ConvUnit& u, const bf16* d, const b
   g.conv_h = u.H; g.conv_w = u.W; g.conv_c = u.Cout;
   g.C = out;
   if (relu_y) { g.mode = et::EPI_RELU_MASK; g.U = relu_y; }
+  plan_implicit(c, g);
   ET_G(g);
   return ET_OK;
 }

@@ -35,6 +35,27 @@ extern "C" int et_debug_conv3x3(const void* x, const void* w, void* out, int bat
   return e == hipSuccess ? ET_OK : ET_EHIP;
 }
 
+extern "C" int et_debug_conv3x3_split(const void* x, const void* w, void* out, void* z_out, int batch, int H, int W, int C, int N,
+                                      const void* bias, const void* gain, const void* U, int mode, int split_k, float* partials,
+                                      int tile, void* stream) {
+  if (batch < 1 || H < 1 || W < 1 || (long long)batch * H * W > 0x7fffffffll) return ET_EINVAL;
+  et::GemmDesc g;
+  g.A = (const et::bf16*)x; g.B = (const et::bf16*)w; g.C = out;
+  g.M = batch * H * W; g.N = N; g.K = 9 * C; g.lda = 9 * C; g.ldb = 9 * C; g.ldc = N;
+  g.conv_h = H; g.conv_w = W; g.conv_c = C; g.tile = tile;
+  if (mode == 1) { g.mode = et::EPI_BIAS_RELU; g.bias = (const et::bf16*)bias; }
+  if (mode == 2) { g.mode = et::EPI_RELU_MASK; g.U = (const et::bf16*)U; }
+  if (mode == 3) {
+    g.mode = et::EPI_AFFINE_RELU; g.bias = (const et::bf16*)bias; g.gain = (const et::bf16*)gain;
+    g.C = z_out; g.C2 = (et::bf16*)out; g.act_hi = 6.f;
+  }
+  g.split_k = split_k; g.partials = partials;
+  if (split_k == 0) { et::gemm_bf16_plan_conv(g.M, g.N, g.K, &g.tile, &g.split_k); }
+  const hipError_t e = et::gemm_bf16(g, (hipStream_t)stream);
+  if (e == hipErrorInvalidValue) return ET_EINVAL;
+  return e == hipSuccess ? ET_OK : ET_EHIP;
+}
+
 extern "C" int et_debug_conv3x3_dw(const void* x, const void* d, float* dw, int batch, int H, int W, int C, int N,
                                    int split_k, float* partials, int tile, void* stream) {
   if (batch < 1 || H < 1 || W < 1 || (long long)batch * H * W > 0x7fffffffll) return ET_EINVAL;

@@ -43,6 +43,56 @@ __global__ __launch_bounds__(256) void splitk_reduce_wide_kernel(const float4* _
   }
 }
 
+// Split implicit convolution: out = epilogue(sum_z part[z]), z ascending.  mode: 0 bf16 copy, 1 max(v + bias, 0),
+// 2 0 < U < mask_hi ? v : 0, 3 z = bf16(v) (kept if zout), y = clamp(z * gain + bias, lo, hi)
+struct ReduceEpi {
+  const float4* part;
+  size_t n4;
+  int splits, N, mode;
+  const bf16* bias;
+  const bf16* gain;
+  const bf16* U;
+  bf16* out;
+  bf16* zout;
+  float lo, hi, mask_hi;
+};
+
+__global__ __launch_bounds__(256) void splitk_reduce_epilogue_kernel(ReduceEpi e) {
+  typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i >= e.n4) return;
+  float4 s = e.part[i];
+  for (int z = 1; z < e.splits; z++) {
+    const float4 p = e.part[(size_t)z * e.n4 + i];
+    s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+  }
+  float v[4] = {s.x, s.y, s.z, s.w};
+  const int col = (int)((i * 4) % (size_t)e.N);
+  bf16x4 o;
+  if (e.mode == 1) {
+    const bf16x4 b = *(const bf16x4*)(e.bias + col);
+#pragma unroll
+    for (int j = 0; j < 4; j++) o[j] = (bf16)fmaxf(v[j] + (float)b[j], 0.f);
+  } else if (e.mode == 2) {
+    const bf16x4 u = ((const bf16x4*)e.U)[i];
+#pragma unroll
+    for (int j = 0; j < 4; j++) o[j] = ((float)u[j] > 0.f && (float)u[j] < e.mask_hi) ? (bf16)v[j] : (bf16)0.f;
+  } else if (e.mode == 3) {
+    const bf16x4 g = *(const bf16x4*)(e.gain + col), b = *(const bf16x4*)(e.bias + col);
+    bf16x4 z;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      z[j] = (bf16)v[j];
+      o[j] = (bf16)fminf(fmaxf((float)z[j] * (float)g[j] + (float)b[j], e.lo), e.hi);
+    }
+    if (e.zout) ((bf16x4*)e.zout)[i] = z;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; j++) o[j] = (bf16)v[j];
+  }
+  ((bf16x4*)e.out)[i] = o;
+}
+
 enum TileId : int { T_AUTO = 0, T_128x128 = 1, T_128x64 = 3, T_DMA_256x256 = 5, T_DMA_256x128 = 7, T_PP_256x256 = 11, T_PP_256x192 = 13,
               T_PP_256x128 = 15, T_PP_512x64 = 17, T_PP_128x256 = 19, T_PP_64x512 = 21 };
 
@@ -69,7 +119,7 @@ Plan plan_tiles(int M, int N, int K, bool may_split, const TileRate* cand, int n
       if (chunks != s) continue;   // this split leaves empty chunks: the same work as a smaller one
       const long long rounds = (tiles * s + 255) / 256;
       double t = rounds * (2.0 * c.bm * c.bn * per * gemm::PBK / c.rate);
-      if (s > 1) t += (2.0 * s + 1.0) * M * N * 4.0 / 3.5e12;
+      if (s > 1) t += (2.0 * s + 1.0) * M * N * 4.0 / 3.5e12 + 4e-6;   // partial traffic and one more launch
       if (t < best.cost) best = {c.tile, s, t};
     }
   }
@@ -135,6 +185,14 @@ int choose_tile(const GemmDesc& d, int k_per_block) {
 
 size_t gemm_bf16_partial_elems(int M, int N, int split_k) { return split_k > 1 ? (size_t)M * N * split_k : 0; }
 
+void gemm_bf16_plan_conv(int M, int N, int K, int* tile, int* split_k) {
+  static const TileRate cand[4] = {{T_PP_256x256, 256, 256, 4.5e12}, {T_PP_256x192, 256, 192, 4.0e12},
+                                   {T_PP_256x128, 256, 128, 3.3e12}, {T_PP_512x64, 512, 64, 2.6e12}};
+  const Plan pl = plan_tiles(M, N, K, (N & 3) == 0, cand, 4);
+  *tile = pl.tile;
+  *split_k = pl.split;
+}
+
 void gemm_bf16_plan_conv_dw(int M, int N, int K, int* tile, int* split_k) {
   const Plan pl = plan_conv_dw(M, N, K);
   *tile = pl.tile;
@@ -177,9 +235,18 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
       return hipErrorInvalidValue;
   } else if (conv) {
     if ((d.conv_c % gemm::PBK) || d.conv_h < 1 || d.conv_w < 1 || d.K != 9 * d.conv_c || (d.M % (d.conv_h * d.conv_w)) ||
-        d.a_t || d.b_t || d.split_k > 1 || d.z_outer != 1 || d.z_inner != 1)
+        d.a_t || d.b_t || d.z_outer != 1 || d.z_inner != 1)
+      return hipErrorInvalidValue;
+    // a split reduction finishes in a second kernel that applies the epilogue: outputs without padding
+    if (d.split_k > 1 && (!d.partials || !aligned(d.partials, 16) || d.ldc != d.N || (d.N & 3) || d.c_f32 || d.residual ||
+                          d.alpha != 1.f || d.mode == EPI_AFFINE_ADD_RELU || d.mode == EPI_GELU_FWD || d.mode == EPI_GELU_BWD ||
+                          d.mode == EPI_GELU_ONLY || (d.mode == EPI_PLAIN && d.bias)))
+      return hipErrorInvalidValue;
+    if (d.split_k > 1 && ((d.mode == EPI_AFFINE_RELU && (!d.C2 || !d.gain || !d.bias || !aligned(d.C2, 8) || !aligned(d.gain, 8))) ||
+                          (d.mode == EPI_RELU_MASK && (!d.U || !aligned(d.U, 8))) || (d.mode == EPI_BIAS_RELU && !d.bias)))
       return hipErrorInvalidValue;
   }
+  const bool conv_split = conv && !conv_dw && d.split_k > 1;
   if (d.residual && (d.ldr < d.N || (d.ldr & 3) || !aligned(d.residual, 16))) return hipErrorInvalidValue;
 
   gemm::Params p;
@@ -195,8 +262,8 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   int epi;
   int k_per_block = d.K;
   if (d.split_k > 1) {
-    if (zdim != 1 || !d.partials || !d.c_f32 || d.bias || d.residual || d.mode != EPI_PLAIN || d.alpha != 1.f ||
-        d.ldc != d.N || (d.N & 3) || !aligned(d.partials, 16))
+    if (!conv_split && (zdim != 1 || !d.partials || !d.c_f32 || d.bias || d.residual || d.mode != EPI_PLAIN || d.alpha != 1.f ||
+                        d.ldc != d.N || (d.N & 3) || !aligned(d.partials, 16)))
       return hipErrorInvalidValue;
     const int slices = (d.K + gemm::SBK - 1) / gemm::SBK;
     const int per = (slices + d.split_k - 1) / d.split_k;
@@ -278,7 +345,18 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   hipError_t e = fn(p, dim3(tiles, 1, zdim), s);
   if (e != hipSuccess) return e;
   if (launches) *launches = 1;
-  if (p.split_k > 1) {
+  if (p.split_k > 1 && conv_split) {
+    ReduceEpi r;
+    r.part = (const float4*)d.partials; r.n4 = (size_t)d.M * d.N / 4; r.splits = p.split_k; r.N = d.N;
+    r.mode = d.mode == EPI_BIAS_RELU ? 1 : d.mode == EPI_RELU_MASK ? 2 : d.mode == EPI_AFFINE_RELU ? 3 : 0;
+    r.bias = d.bias; r.gain = d.gain; r.U = d.U;
+    r.out = d.mode == EPI_AFFINE_RELU ? d.C2 : (bf16*)d.C;
+    r.zout = d.mode == EPI_AFFINE_RELU ? (bf16*)d.C : nullptr;
+    r.lo = d.act_lo; r.hi = d.act_hi; r.mask_hi = d.mask_hi;
+    hipLaunchKernelGGL(splitk_reduce_epilogue_kernel, dim3((unsigned)((r.n4 + 255) / 256)), dim3(256), 0, s, r);
+    e = hipGetLastError();
+    if (launches) *launches = 2;
+  } else if (p.split_k > 1) {
     const size_t n4 = (size_t)d.M * d.N / 4;
     if (p.split_k > 32)
       hipLaunchKernelGGL(splitk_reduce_wide_kernel, dim3((unsigned)((n4 + 15) / 16)), dim3(256), 0, s,

@@ -907,8 +907,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   // CONV: tap (dy, dx) and channel offset of the next slice to load (uniform), the element offset
   // of that slice from the centre tap, and per lane one bit per piece: "the registers hold data"
   // (as opposed to a pixel outside the image, stored as zeros)
+  // (a split reduction starts at column k_begin = (tap, channel offset) of the matrix)
   int c_dy = -1, c_dx = -1, c_sub = 0;
-  long long c_off_a = CONV == 1 ? -(long long)(g.cW + 1) * g.cC : 0;
+  if (CONV == 1) {
+    const int tap0 = k_begin / g.cC;
+    c_sub = k_begin % g.cC;
+    c_dy = tap0 / 3 - 1;
+    c_dx = tap0 % 3 - 1;
+  }
+  long long c_off_a = CONV == 1 ? (long long)(c_dy * g.cW + c_dx) * g.cC + c_sub : 0;
   unsigned c_ok = 0;
   auto conv_load = [&](int i) {
     const bool ok = (unsigned)(coh[CONV == 1 ? i : 0] + c_dy) < (unsigned)g.cH && (unsigned)(cow[CONV == 1 ? i : 0] + c_dx) < (unsigned)g.cW;

@@ -39,6 +39,7 @@ LaunchFn pp_conv_256x128(int epi) {
   ET_PICK(E_BIAS_RELU)
   ET_PICK(E_AFFINE)
   ET_PICK(E_RELU_MASK)
+  ET_PICK(E_PARTIAL)
 #undef ET_PICK
   return nullptr;
 }

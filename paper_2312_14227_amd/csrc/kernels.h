@@ -62,7 +62,9 @@ struct GemmDesc {
   const bf16* U = nullptr;         // EPI_GELU_BWD, EPI_AFFINE_ADD_RELU, EPI_RELU_MASK: same leading dimension as C
   // implicit 3x3 / stride 1 / zero padding 1 convolution (conv_c > 0): A is the NHWC activation
   // [M / (conv_h conv_w), conv_h, conv_w, conv_c] itself, standing for its im2col matrix [M][9 conv_c]
-  // (K = 9 conv_c, column (tap, c)); conv_c must be a multiple of 64; row-major operands, no batching, no split.
+  // (K = 9 conv_c, column (tap, c)); conv_c must be a multiple of 64; row-major operands, no batching; split_k > 1
+  // (with `partials`, ldc == N, bf16 outputs, not with the ADD / GELU modes) reduces in a second kernel that also
+  // applies the epilogue.
   // With a_t and b_t (weight gradient): B is the activation standing for [K pixels][N = 9 conv_c]; conv_c % 8 == 0,
   // K a multiple of 64, fp32 output, split allowed
   int conv_h = 0, conv_w = 0, conv_c = 0;
@@ -78,6 +80,9 @@ size_t gemm_bf16_partial_elems(int M, int N, int split_k);
 // tile and split for a weight gradient [M][N] reduced over K rows (a cost model over tile shapes
 // and split counts); pass both on in GemmDesc::tile and GemmDesc::split_k
 void gemm_bf16_plan_split(int M, int N, int K, int* tile, int* split_k);
+// the same for the implicit forward / gradient-passing 3x3 convolution [M pixels][N channels], K = 9 input channels:
+// layers with few pixels split the reduction, and a second kernel sums the parts and applies the epilogue
+void gemm_bf16_plan_conv(int M, int N, int K, int* tile, int* split_k);
 // the same for the implicit weight gradient of a 3x3 convolution (M output channels, N = 9 input channels, K pixels)
 void gemm_bf16_plan_conv_dw(int M, int N, int K, int* tile, int* split_k);
 

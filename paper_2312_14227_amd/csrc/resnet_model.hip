@@ -72,7 +72,7 @@ int build_resnet(et_ctx* c) {
   };
   auto wg = [&](const ConvUnit& u) {
     const int M = (int)rows_of(c, u);
-    pe = std::max(pe, conv_dw_partials(c, u));
+    pe = std::max(pe, std::max(conv_dw_partials(c, u), conv_split_partials(c, u)));
     max_cols = std::max(max_cols, (size_t)M * u.Kc);   // the column gradient of any unit fits rdcols
     if (implicit_dy(u)) max_flip = std::max(max_flip, (size_t)u.Cout * 9 * u.Cin);
   };

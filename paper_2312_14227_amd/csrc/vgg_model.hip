@@ -86,7 +86,7 @@ int build_vgg(et_ctx* c) {
     max_act = std::max(max_act, std::max(M * u.Cout, M * round8(u.Cin)));
     if (!implicit_dw(c, u) || !implicit_dy(u)) max_cols = std::max(max_cols, M * u.Kc);
     max_cs = std::max(max_cs, et::colsum_partial_elems((int)M, u.Cout));
-    pe = std::max(pe, conv_dw_partials(c, u));
+    pe = std::max(pe, std::max(conv_dw_partials(c, u), conv_split_partials(c, u)));
     const bool last_of_stage = i + 1 == c->vconv.size() || c->vstage[i + 1] != c->vstage[i];
     if (last_of_stage) {
       reserve(c, &c->vpool[c->vstage[i]], b16 * (M / 4) * u.Cout);
@@ -143,12 +143,13 @@ int vgg_forward(et_ctx* c, const void* x, const int32_t* y) {
     u.in = h;
     if (u.Kc != 9 * u.Cin) ET_K(1, et::pad_rows(Wt(u.t), c->stem_w8, u.Cout, 9 * u.Cin, u.Kc, s));
     et::GemmDesc g = linear_fwd(u.cols, conv_matrix(c, i), Wt(u.t + 1), (int)M, u.Cout, u.Kc);
+    g.mode = et::EPI_BIAS_RELU; g.C = u.y;
     if (implicit_fwd(u)) {
       g.A = h; g.conv_h = u.H; g.conv_w = u.W; g.conv_c = u.Cin;
+      plan_implicit(c, g);
     } else {
       ET_KB(1, 2.0 * ((double)M * u.Cin + (double)M * u.Kc), et::im2col(h, u.cols, geom(c, u), s));
     }
-    g.mode = et::EPI_BIAS_RELU; g.C = u.y;
     ET_G(g);
     h = u.y;
     if (i + 1 == c->vconv.size() || c->vstage[i + 1] != c->vstage[i]) {

@@ -122,3 +122,52 @@ def test_conv3x3_weight_gradient_rejects_bad_arguments():
     assert et.et_debug_conv3x3_dw(p, p, p, 1, 8, 8, 12, 64) == -1     # channels not a multiple of 8
     assert et.et_debug_conv3x3_dw(p, p, p, 1, 5, 5, 8, 64) == -1      # pixels not a multiple of 64
     assert et.et_debug_conv3x3_dw(p, p, p, 1, 8, 8, 8, 64, 2, 0) == -1  # split without partials
+
+
+def _case_split(batch, H, W, C, N, mode, split, tile, seed):
+    import torch
+    from paper_2312_14227_amd import binding as et
+    rng = np.random.default_rng(seed)
+    x = bf16_round(rng.standard_normal((batch, H, W, C)).astype(np.float32))
+    w = bf16_round((rng.standard_normal((N, 3, 3, C)) / np.sqrt(9 * C)).astype(np.float32))
+    bias = bf16_round(rng.standard_normal(N).astype(np.float32))
+    gain = bf16_round((1.0 + 0.3 * rng.standard_normal(N)).astype(np.float32))
+    u = bf16_round(rng.standard_normal((batch * H * W, N)).astype(np.float32))
+    cv = R.Conv(x.astype(np.float64), w.astype(np.float64), 1)
+    z = cv.out.reshape(batch * H * W, N)
+    scale = (np.abs(cv.cols.reshape(batch * H * W, -1)) @ np.abs(cv.wm).T)
+    dev = "cuda:0"
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(torch.bfloat16)
+    xt, wt, bt, gt, ut = to(x), to(w), to(bias), to(gain), to(u)
+    out = torch.full((batch * H * W, N), float("nan"), device=dev, dtype=torch.bfloat16)
+    zt = torch.full_like(out, float("nan"))
+    part = torch.empty(batch * H * W * N * 18, device=dev, dtype=torch.float32)
+    st = et.et_debug_conv3x3_split(xt.data_ptr(), wt.data_ptr(), out.data_ptr(), zt.data_ptr() if mode == 3 else 0, batch, H, W, C, N,
+                                   bt.data_ptr(), gt.data_ptr(), ut.data_ptr(), mode, split, part.data_ptr(), tile,
+                                   torch.cuda.current_stream().cuda_stream)
+    assert st == 0
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    acc = 2e-6 * scale * np.sqrt(9 * C) + 1e-6
+    if mode == 0:
+        ref, bound = z, acc + 2.0 ** -8 * np.abs(z)
+    elif mode == 1:
+        ref = np.maximum(z + bias, 0.0)
+        bound = acc + 2.0 ** -8 * (np.abs(ref) + np.abs(bias))
+    elif mode == 2:
+        ref = z * (u > 0)
+        bound = acc + 2.0 ** -8 * np.abs(ref)
+    else:
+        zg = zt.float().cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(zg - z) <= acc + 2.0 ** -8 * np.abs(z))
+        ref = np.minimum(np.maximum(zg * gain + bias, 0.0), 6.0)        # from the rounded z the kernel stored
+        bound = 2.0 ** -8 * np.abs(ref) + 1e-6
+    bad = ~(np.abs(got - ref) <= bound)
+    assert not bad.any(), (int(bad.sum()), float(np.nanmax(np.abs(got - ref))))
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+@pytest.mark.parametrize("batch,H,W,C,N,split,tile", [(2, 7, 7, 64, 64, 3, 17), (2, 7, 7, 128, 72, 9, 15), (3, 14, 14, 64, 264, 2, 11),
+                                                      (2, 7, 9, 192, 128, 5, 13), (32, 7, 7, 512, 512, 0, 0), (32, 14, 14, 256, 256, 0, 0)])
+def test_conv3x3_split_reduction(batch, H, W, C, N, split, tile, mode):
+    _case_split(batch, H, W, C, N, mode, split, tile, seed=mode * 31 + H + N)
