@@ -91,23 +91,22 @@ struct Params {
 //   erf(|x|) = 1 - (a1 t + .. + a5 t^5) exp(-x^2),  t = 1 / (1 + p |x|)   (Abramowitz-Stegun 7.1.26,
 //   absolute error < 1.5e-7, far below the bf16 rounding of the results)
 //   gelu(u) = u Phi(u),  gelu'(u) = Phi(u) + u exp(-u^2/2) / sqrt(2 pi),  Phi(u) = (1 + erf(x)) / 2
+// (t from the hardware reciprocal, 1 ulp: a correctly rounded division costs eleven instructions here)
 __device__ __forceinline__ void gelu_both(float u, float& g, float& dg) {
-  const float x = fabsf(u) * 0.70710678118654752f;
-  const float t = __frcp_rn(1.f + 0.3275911f * x);
-  const float e = __expf(-x * x);
+  // constants folded: p / sqrt(2) for t, -log2(e) / 2 for exp(-x^2) = 2^(-u^2 log2(e) / 2)
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.23164189f, fabsf(u), 1.f));
+  const float e = __builtin_amdgcn_exp2f(u * u * -0.72134752f);
   const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
-  const float erf_abs = 1.f - poly * e;
-  const float phi = 0.5f * (1.f + copysignf(erf_abs, u));
+  const float phi = fmaf(0.5f, copysignf(fmaf(-poly, e, 1.f), u), 0.5f);
   g = u * phi;
-  dg = phi + u * e * 0.39894228040143268f;
+  dg = fmaf(u * e, 0.39894228040143268f, phi);
 }
 
 __device__ __forceinline__ float gelu_only(float u) {
-  const float x = fabsf(u) * 0.70710678118654752f;
-  const float t = __frcp_rn(1.f + 0.3275911f * x);
-  const float e = __expf(-x * x);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.23164189f, fabsf(u), 1.f));
+  const float e = __builtin_amdgcn_exp2f(u * u * -0.72134752f);
   const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
-  return u * (0.5f * (1.f + copysignf(1.f - poly * e, u)));
+  return u * fmaf(0.5f, copysignf(fmaf(-poly, e, 1.f), u), 0.5f);
 }
 
 __device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char* p) {
