@@ -122,9 +122,17 @@ __global__ __launch_bounds__(256) void layernorm_bwd_dx_kernel(const bf16* __res
 
 // ---------------------------------------------------------------------------------------------
 // column sums, stage 1: a block of 8 column-threads (8 columns each) x 32 row-threads sums
-// CS_ROWS rows of 64 columns; stage 2 adds the row-chunk partials in ascending order
+// cs_rows() rows of 64 columns; stage 2 adds the row-chunk partials in ascending order
 // ---------------------------------------------------------------------------------------------
-constexpr int CS_ROWS = 512, CS_COLS = 64;
+constexpr int CS_COLS = 64;
+// rows per chunk: about 2048 workgroups per launch (a multiple of 32 rows, 64 to 1024), so that a tall narrow
+// matrix and a short wide one both fill the chip; the same function sizes the partial buffer
+__host__ __device__ inline int cs_rows(int rows, int cols) {
+  const int col_blocks = (cols + CS_COLS - 1) / CS_COLS;
+  const int chunks_wanted = 2048 / col_blocks > 0 ? 2048 / col_blocks : 1;
+  int per = ((rows + chunks_wanted - 1) / chunks_wanted + 31) & ~31;
+  return per < 64 ? 64 : (per > 1024 ? 1024 : per);
+}
 
 template <bool F32IN, bool XHAT>
 __global__ __launch_bounds__(256) void colsum_stage1(const bf16* __restrict__ d16, const float* __restrict__ d32,
@@ -135,7 +143,8 @@ __global__ __launch_bounds__(256) void colsum_stage1(const bf16* __restrict__ d1
   __shared__ float red[32][CS_COLS + 1];
   const int cx = threadIdx.x & 7, ry = threadIdx.x >> 3;
   const int c0 = blockIdx.x * CS_COLS + cx * 8;
-  const int r_begin = blockIdx.y * CS_ROWS, r_end = min(rows, r_begin + CS_ROWS);
+  const int chunk_rows = cs_rows(rows, cols);
+  const int r_begin = blockIdx.y * chunk_rows, r_end = min(rows, r_begin + chunk_rows);
   float acc[8];
 #pragma unroll
   for (int j = 0; j < 8; j++) acc[j] = 0.f;
@@ -184,7 +193,8 @@ __global__ __launch_bounds__(256) void colsum_mul_stage1(const bf16* __restrict_
   __shared__ float red[32][CS_COLS + 1];
   const int cx = threadIdx.x & 7, ry = threadIdx.x >> 3;
   const int c0 = blockIdx.x * CS_COLS + cx * 8;
-  const int r_begin = blockIdx.y * CS_ROWS, r_end = min(rows, r_begin + CS_ROWS);
+  const int chunk_rows = cs_rows(rows, cols);
+  const int r_begin = blockIdx.y * chunk_rows, r_end = min(rows, r_begin + chunk_rows);
   float acc[8];
 #pragma unroll
   for (int j = 0; j < 8; j++) acc[j] = 0.f;
@@ -392,7 +402,10 @@ hipError_t layernorm_bwd_dx(const bf16* d, const float* h, long long in_stride, 
   return hipGetLastError();
 }
 
-size_t colsum_partial_elems(int rows, int cols) { return (size_t)((rows + CS_ROWS - 1) / CS_ROWS) * cols; }
+size_t colsum_partial_elems(int rows, int cols) {
+  const int per = cs_rows(rows, cols);
+  return (size_t)((rows + per - 1) / per) * cols;
+}
 
 hipError_t colsum(const bf16* d, const float* d_f32, long long d_stride, const float* h, long long h_stride,
                   const float* mean, const float* rstd, float* out, float* partials, int rows, int cols,
@@ -400,7 +413,7 @@ hipError_t colsum(const bf16* d, const float* d_f32, long long d_stride, const f
   if (rows <= 0 || cols <= 0 || (cols & 7) || (d_stride & 7) || (h && (h_stride & 3)) || (!d && !d_f32) || !partials)
     return hipErrorInvalidValue;
   if ((d && !al16(d)) || (d_f32 && !al16(d_f32)) || (h && !al16(h))) return hipErrorInvalidValue;
-  const int chunks = (rows + CS_ROWS - 1) / CS_ROWS;
+  const int chunks = (rows + cs_rows(rows, cols) - 1) / cs_rows(rows, cols);
   dim3 grid((cols + CS_COLS - 1) / CS_COLS, chunks), block(256);
   if (d_f32) {
     if (h)
@@ -427,7 +440,7 @@ hipError_t colsum_mul(const bf16* d, const bf16* z, const float* z_f32, float* o
                       hipStream_t s) {
   if (rows <= 0 || cols <= 0 || (cols & 7) || !d || (!z && !z_f32) || !partials) return hipErrorInvalidValue;
   if (!al16(d) || (z && !al16(z)) || (z_f32 && !al16(z_f32))) return hipErrorInvalidValue;
-  const int chunks = (rows + CS_ROWS - 1) / CS_ROWS;
+  const int chunks = (rows + cs_rows(rows, cols) - 1) / cs_rows(rows, cols);
   dim3 grid((cols + CS_COLS - 1) / CS_COLS, chunks), block(256);
   if (z_f32)
     hipLaunchKernelGGL((colsum_mul_stage1<true>), grid, block, 0, s, d, z, z_f32, partials, rows, cols);
