@@ -188,3 +188,79 @@ def test_weight_and_gradient_magnitude_metrics():
         want_sel = osel.select(metric, [int(t) for t in t_dw], [int(t) for t in t_dy], int(t_fwd), 600_000, 1000)
         assert st == want_sel["status"] and list(mask) == list(want_sel["mask"])
     s.close()
+
+
+def _bf16_storage_step(cfg, wl):
+    """Oracle step with bf16 storage rounding for the convolutional families (see tests/test_gpu_resnet.py)."""
+    from oracle import mobilenet as MB
+    from oracle import resnet as R
+    from oracle import vgg as V
+    ones = [1] * len(wl.weights)
+    if cfg.kind == "resnet":
+        return R.resnet_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16,
+                             cols_stored=lambda cin, cout, stride: not (stride == 1 and cout % 64 == 0 and cin % 8 == 0))
+    if cfg.kind == "vgg":
+        return V.vgg_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16,
+                          cols_stored=lambda cin, cout: cout % 64 != 0 or cin % 8 != 0)
+    return MB.mobilenet_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16)
+
+
+@pytest.mark.parametrize("name", ["resnet_small", "vgg_small", "mobilenet_small"])
+def test_importance_profile_and_selection_on_the_convolutional_families(name):
+    """Eq. 2 importance against the oracle's (same storage rounding on both sides), the attribution of the profiled
+    times (shifts and biases pass gradients for free) and bit-exact selection from the device's own numbers."""
+    from paper_2312_14227_amd import binding as et
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg, seed=7, init="random")
+    N = len(wl.weights)
+    r = _bf16_storage_step(cfg, wl)
+    I_ref = oimp.importance_from_grads(r["grads"], wl.weights, wl.snapshot)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    snap = s.put_snapshot(wl.snapshot)
+    I = s.importance(xt, yt, snap)
+    tol = 0.1 * tol_for(cfg)
+    for k in range(N):
+        gn = np.linalg.norm(r["grads"][k].ravel())
+        dwn = np.linalg.norm((wl.snapshot[k].astype(np.float64) - wl.weights[k].astype(np.float64)).ravel())
+        assert abs(I[k] - I_ref[k]) <= tol * max(abs(I_ref[k]), gn * dwn), (wl.names[k], I[k], I_ref[k])
+    t_fwd, t_dw, t_dy = s.profile(xt, yt, warmup=1, reps=3)
+    assert t_fwd > 0 and (t_dw > 0).all() and t_dy[0] == 0
+    for k in range(N):
+        if wl.names[k].endswith(".b"):
+            assert t_dy[k] == 0, wl.names[k]
+    for rho in (400_000, 500_000, 700_000, 1_000_000):
+        st, mask, pred = et.et_select(I, t_dw, t_dy, t_fwd, rho, 10_000)
+        want = osel.select(I, t_dw, t_dy, t_fwd, rho, 10_000)
+        assert st == want["status"] and list(mask) == list(want["mask"]) and pred == want["predicted_ns"], rho
+    s.close()
+
+
+def test_masked_update_sgd_on_a_convolutional_model():
+    import torch
+    from paper_2312_14227_amd.session import make_opt
+    cfg = CONFIGS["mobilenet_small"]
+    wl = make_workload(cfg, seed=3, init="random")
+    N = len(wl.weights)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    rng = np.random.default_rng(9)
+    mask = (rng.random(N) < 0.5).astype(np.uint8)
+    mask[N - 1] = 1
+    hp = {k: float(np.float32(v)) for k, v in dict(lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8, momentum=0.9, wd=5e-3).items()}
+    w_ref = [w.astype(np.float64) for w in wl.weights]
+    st_ref = [(np.zeros(w.shape),) for w in wl.weights]
+    for step in (1, 2):
+        before = [w.clone() for w in s.w]
+        s.train_step(xt, yt, mask, make_opt("sgdw", step=step, **hp))
+        torch.cuda.synchronize()
+        grads = [s.grads_host(k).reshape(wl.weights[k].shape) if mask[k] else None for k in range(N)]
+        w_ref, st_ref = oopt.masked_update("sgdw", mask, w_ref, st_ref, grads, step=step, **hp)
+        for k in range(N):
+            if not mask[k]:
+                assert torch.equal(s.w[k], before[k]), wl.names[k]
+                continue
+            fp = s.state[k][0].cpu().numpy().astype(np.float64).reshape(w_ref[k].shape)
+            np.testing.assert_allclose(fp, w_ref[k], rtol=2e-6, atol=step * 2e-3 * hp["lr"], err_msg=wl.names[k])
+            assert torch.equal(s.w[k].reshape(-1), s.state[k][0].to(torch.bfloat16)), wl.names[k]
+    s.close()
