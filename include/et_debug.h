@@ -64,6 +64,17 @@ size_t et_debug_depthwise3x3_ws_floats(int batch, int H, int W, int C, int strid
 int et_debug_depthwise3x3(int op, const void* a, const void* b, const void* gain, const void* shift, void* out0, void* out1,
                           float* ws, int batch, int H, int W, int C, int stride, void* stream);
 
+/* Fused attention core of one layer for sequences of at most 224 tokens and head size 64 (Section 5.4 counts the
+ * attention operations among the layers without weights; their backward time is charged to the tensor whose
+ * gradient passing needs them).  qkv bf16 [B][T][3 D], D = 64 H, holding Q | K | V of every token; scale = 1/sqrt(64).
+ *   op 0 forward: out bf16 [B][T][D] = softmax(Q K^T * scale) V per (batch, head); lse fp32 [B][H][T] = log-sum-exp
+ *     of each query's scaled scores;
+ *   op 1 backward: given out and lse of the forward pass and dout bf16 [B][T][D], dqkv bf16 [B][T][3 D] = gradients
+ *     w.r.t. Q | K | V.
+ * Device pointers, 16-byte aligned.  Returns 0, -1 (T > 224, bad sizes or pointers), -3 as above. */
+int et_debug_attention(int op, const void* qkv, void* out, float* lse, const void* dout, void* dqkv, int B, int T, int H,
+                       void* stream);
+
 /* Device address and element count (bf16) of an activation the last forward pass of a bound context stored,
  * so that a test can check one layer at a time against the layer's definition applied to the stored input.
  * ET_VGG: "conv<i>.in" [batch][H][W][Cin], "conv<i>.y" (after bias + ReLU), "fc<j>.in" [batch][features];

@@ -103,6 +103,8 @@ __global__ __launch_bounds__(NTHREADS) void attention_fwd_kernel(const bf16* __r
   __syncthreads();
 
   const int l32 = lane & 31, khalf = lane >> 5;
+  // exp(scale * x) = 2^(c x): the scale is folded into the exponent, scores stay as the MFMA leaves them
+  const float c = scale * 1.44269504088896341f;
   for (int qt = wave; qt < KT; qt += NWAVES) {
     // Q fragments straight from memory (B operand: row = query, 8 consecutive d)
     const int qrow = min(qt * 32 + l32, T - 1);
@@ -110,7 +112,8 @@ __global__ __launch_bounds__(NTHREADS) void attention_fwd_kernel(const bf16* __r
 #pragma unroll
     for (int ks = 0; ks < 4; ks++) qf[ks] = *(const bf16x8*)(q + (long long)qrow * ld + ks * 16 + khalf * 8);
 
-    // S^T tile kt: lane holds query l%32 and keys kt*32 + tile_row(r); scaled, masked beyond T
+    // S^T tile kt (unscaled): lane holds query l%32 and keys kt*32 + tile_row(r); only the last tile has keys
+    // beyond T, which get -inf
     auto scores = [&](int kt) -> f32x16 {
       f32x16 acc;
 #pragma unroll
@@ -118,8 +121,10 @@ __global__ __launch_bounds__(NTHREADS) void attention_fwd_kernel(const bf16* __r
 #pragma unroll
       for (int ks = 0; ks < 4; ks++)
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct(sk, kt * 32, ks, lane), qf[ks], acc, 0, 0, 0);
+      if (kt == KT - 1) {
 #pragma unroll
-      for (int r = 0; r < 16; r++) acc[r] = kt * 32 + tile_row(r, lane) < T ? acc[r] * scale : -INFINITY;
+        for (int r = 0; r < 16; r++) acc[r] = kt * 32 + tile_row(r, lane) < T ? acc[r] : -INFINITY;
+      }
       return acc;
     };
 
@@ -132,9 +137,11 @@ __global__ __launch_bounds__(NTHREADS) void attention_fwd_kernel(const bf16* __r
       for (int r = 0; r < 16; r++) mx = fmaxf(mx, st[r]);
     }
     const float M = fmaxf(mx, __shfl_xor(mx, 32, 64));   // finite: key 0 is never masked
+    const float mc = -M * c;
 
-    // sweep 2: O = exp(S - M) V with unnormalised probabilities, which are already an A operand; their sum
-    // per query is collected on the way and divides the result afterwards
+    // sweep 2: O^T = V^T exp(scale (S - M))^T with unnormalised probabilities, which are already an MFMA operand
+    // (query l%32, 8 keys per lane); the result tile has lane = query as well, so the sum of a query's
+    // probabilities, collected on the way, divides its own registers afterwards
     float sum = 0.f;
     f32x16 o[2];
 #pragma unroll
@@ -149,33 +156,32 @@ __global__ __launch_bounds__(NTHREADS) void attention_fwd_kernel(const bf16* __r
         bf16x8 pf;
 #pragma unroll
         for (int e = 0; e < 8; e++) {
-          const float p = __expf(st[j * 8 + e] - M);
+          const float p = __builtin_amdgcn_exp2f(fmaf(st[j * 8 + e], c, mc));
           sum += p;
           pf[e] = (bf16)p;
         }
 #pragma unroll
         for (int dt = 0; dt < 2; dt++)
-          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, frag_rows_tr(sv, kt * 32 + j * 16, dt * 32, lane), o[dt], 0, 0, 0);
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_tr(sv, kt * 32 + j * 16, dt * 32, lane), pf, o[dt], 0, 0, 0);
       }
     }
     const float S = sum + __shfl_xor(sum, 32, 64);
     const float inv = 1.f / S;
-    if (khalf == 0 && qt * 32 + l32 < T) lse[((long long)b * H + h) * T + qt * 32 + l32] = M + logf(S);
-    // the rows of the result tile are other lanes' queries: fetch their 1/S (lane q holds query q's)
+    const int row = qt * 32 + l32;
+    if (khalf == 0 && row < T) lse[((long long)b * H + h) * T + row] = M * scale + logf(S);
+    // result tile: lane holds query l%32 and d = dt*32 + tile_row(r): four consecutive d per register quad
+    if (row < T) {
+      bf16* orow = out + ((long long)b * T + row) * D + h * DH;
 #pragma unroll
-    for (int r = 0; r < 16; r++) {
-      const float f = __shfl(inv, tile_row(r, lane), 64);
-      o[0][r] *= f;
-      o[1][r] *= f;
+      for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+        for (int a = 0; a < 4; a++) {
+          bf16x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; e++) v[e] = (bf16)(o[dt][a * 4 + e] * inv);
+          *(bf16x4*)(orow + dt * 32 + a * 8 + khalf * 4) = v;
+        }
     }
-    // result tile: lane holds column d = dt*32 + l%32, rows = queries
-#pragma unroll
-    for (int dt = 0; dt < 2; dt++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const int row = qt * 32 + tile_row(r, lane);
-        if (row < T) out[((long long)b * T + row) * D + h * DH + dt * 32 + l32] = (bf16)o[dt][r];
-      }
   }
 }
 
@@ -204,14 +210,18 @@ __global__ __launch_bounds__(NTHREADS) void attention_bwd_kernel(const bf16* __r
     const long long lds[4] = {ld, ld, ld, (long long)D};
     stage_rows<TP, 4>(dst, src, lds, T, tid);
   }
-  // padded queries get lse = +inf, so their probabilities vanish
-  for (int i = tid; i < TP; i += NTHREADS) s_lse[i] = i < T ? lse[((long long)b * H + h) * T + i] : INFINITY;
+  // exp(scale * s - lse) = 2^(c s - lse log2(e)): both factors are folded in here; padded queries get
+  // lse = +inf, so their probabilities vanish.  Padded keys need no mask: their K and V rows are zero, so they
+  // add nothing to dQ, and their own dK / dV rows are never stored.
+  const float c = scale * 1.44269504088896341f;
+  for (int i = tid; i < TP; i += NTHREADS) s_lse[i] = i < T ? lse[((long long)b * H + h) * T + i] * 1.44269504088896341f : INFINITY;
   __syncthreads();
 
   const int l32 = lane & 31, khalf = lane >> 5;
 
   // ---- pass A: a wave owns 32 queries (one per lane pair).  rowsum(P * dP) of a query equals dO . O (O = P V is
-  // the stored forward output), so it needs no sweep over the keys of its own; then dQ
+  // the stored forward output), so it needs no sweep over the keys of its own; then dQ^T = K^T dS^T, whose
+  // result tile has lane = query again (the factor 1/sqrt(d) of dS is applied once at the end)
   for (int qt = wave; qt < KT; qt += NWAVES) {
     bf16x8 qf[4], dof[4];
 #pragma unroll
@@ -254,25 +264,32 @@ __global__ __launch_bounds__(NTHREADS) void attention_bwd_kernel(const bf16* __r
 #pragma unroll
         for (int e = 0; e < 8; e++) {
           const int r = j * 8 + e;
-          const float p = kt * 32 + tile_row(r, lane) < T ? __expf(st[r] * scale - my_lse) : 0.f;
-          dsf[e] = (bf16)(p * (dp[r] - dot) * scale);
+          const float p = __builtin_amdgcn_exp2f(fmaf(st[r], c, -my_lse));
+          dsf[e] = (bf16)(p * (dp[r] - dot));
         }
 #pragma unroll
         for (int dt = 0; dt < 2; dt++)
-          dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, frag_rows_tr(sk, kt * 32 + j * 16, dt * 32, lane), dq[dt], 0, 0, 0);
+          dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_tr(sk, kt * 32 + j * 16, dt * 32, lane), dsf, dq[dt], 0, 0, 0);
       }
     }
+    const int row = qt * 32 + l32;
+    if (row < T) {
+      bf16* drow = dqkv + ((long long)b * T + row) * ld + h * DH;
 #pragma unroll
-    for (int dt = 0; dt < 2; dt++)
+      for (int dt = 0; dt < 2; dt++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const int row = qt * 32 + tile_row(r, lane);
-        if (row < T) dqkv[((long long)b * T + row) * ld + h * DH + dt * 32 + l32] = (bf16)dq[dt][r];
-      }
+        for (int a = 0; a < 4; a++) {
+          bf16x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; e++) v[e] = (bf16)(dq[dt][a * 4 + e] * scale);
+          *(bf16x4*)(drow + dt * 32 + a * 8 + khalf * 4) = v;
+        }
+    }
   }
   __syncthreads();
 
-  // ---- pass B: a wave owns 32 keys (one per lane pair): S = Q K^T tiles with lane = key
+  // ---- pass B: a wave owns 32 keys (one per lane pair): S = Q K^T tiles with lane = key; dV^T = dO^T P and
+  // dK^T = Q^T dS keep lane = key in their result tiles
   for (int kt = wave; kt < KT; kt += NWAVES) {
     bf16x8 kf[4], vf[4];
 #pragma unroll
@@ -280,7 +297,6 @@ __global__ __launch_bounds__(NTHREADS) void attention_bwd_kernel(const bf16* __r
       kf[ks] = frag_direct(sk, kt * 32, ks, lane);
       vf[ks] = frag_direct(sv, kt * 32, ks, lane);
     }
-    const bool key_ok = kt * 32 + l32 < T;
     f32x16 dk[2], dv[2];
 #pragma unroll
     for (int dt = 0; dt < 2; dt++)
@@ -304,11 +320,11 @@ __global__ __launch_bounds__(NTHREADS) void attention_bwd_kernel(const bf16* __r
         const float4 d4 = *(const float4*)(s_dot + qt * 32 + a * 8 + khalf * 4);
         const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-        for (int c = 0; c < 4; c++) {
-          const int r = a * 4 + c;
-          const float p = key_ok ? __expf(st[r] * scale - lv[c]) : 0.f;
+        for (int e = 0; e < 4; e++) {
+          const int r = a * 4 + e;
+          const float p = __builtin_amdgcn_exp2f(fmaf(st[r], c, -lv[e]));
           pr[r] = p;
-          ds[r] = p * (dp[r] - dv4[c]) * scale;
+          ds[r] = p * (dp[r] - dv4[e]);
         }
       }
 #pragma unroll
@@ -318,22 +334,28 @@ __global__ __launch_bounds__(NTHREADS) void attention_bwd_kernel(const bf16* __r
         for (int e = 0; e < 8; e++) { pf[e] = (bf16)pr[j * 8 + e]; dsf[e] = (bf16)ds[j * 8 + e]; }
 #pragma unroll
         for (int dt = 0; dt < 2; dt++) {
-          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, frag_rows_tr(sdo, qt * 32 + j * 16, dt * 32, lane), dv[dt], 0, 0, 0);
-          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, frag_rows_tr(sq, qt * 32 + j * 16, dt * 32, lane), dk[dt], 0, 0, 0);
+          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_tr(sdo, qt * 32 + j * 16, dt * 32, lane), pf, dv[dt], 0, 0, 0);
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_tr(sq, qt * 32 + j * 16, dt * 32, lane), dsf, dk[dt], 0, 0, 0);
         }
       }
     }
+    const int row = kt * 32 + l32;
+    if (row < T) {
+      bf16* drow = dqkv + ((long long)b * T + row) * ld + h * DH;
 #pragma unroll
-    for (int dt = 0; dt < 2; dt++)
+      for (int dt = 0; dt < 2; dt++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const int row = kt * 32 + tile_row(r, lane);
-        if (row < T) {
-          const long long base = ((long long)b * T + row) * ld + h * DH + dt * 32 + l32;
-          dqkv[base + D] = (bf16)dk[dt][r];
-          dqkv[base + 2 * D] = (bf16)dv[dt][r];
+        for (int a = 0; a < 4; a++) {
+          bf16x4 vk, vv;
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            vk[e] = (bf16)(dk[dt][a * 4 + e] * scale);
+            vv[e] = (bf16)dv[dt][a * 4 + e];
+          }
+          *(bf16x4*)(drow + D + dt * 32 + a * 8 + khalf * 4) = vk;
+          *(bf16x4*)(drow + 2 * D + dt * 32 + a * 8 + khalf * 4) = vv;
         }
-      }
+    }
   }
 }
 

@@ -100,6 +100,26 @@ extern "C" int et_debug_depthwise3x3(int op, const void* a, const void* b, const
   return e == hipSuccess ? ET_OK : ET_EHIP;
 }
 
+extern "C" int et_debug_attention(int op, const void* qkv, void* out, float* lse, const void* dout, void* dqkv, int B, int T,
+                                  int H, void* stream) {
+  if (!qkv || !out || !lse || B < 1 || H < 1 || !et::attention_fused_supported(T, 64)) return ET_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(qkv) | reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(lse) |
+       reinterpret_cast<uintptr_t>(dout) | reinterpret_cast<uintptr_t>(dqkv)) & 15)
+    return ET_EINVAL;
+  hipError_t e;
+  if (op == 0) {
+    e = et::attention_fwd((const et::bf16*)qkv, (et::bf16*)out, lse, B, T, H, 64, 0.125f, (hipStream_t)stream);
+  } else if (op == 1) {
+    if (!dout || !dqkv) return ET_EINVAL;
+    e = et::attention_bwd((const et::bf16*)qkv, (const et::bf16*)out, (const et::bf16*)dout, lse, (et::bf16*)dqkv, B, T, H, 64,
+                          0.125f, (hipStream_t)stream);
+  } else {
+    return ET_EINVAL;
+  }
+  if (e == hipErrorInvalidValue) return ET_EINVAL;
+  return e == hipSuccess ? ET_OK : ET_EHIP;
+}
+
 namespace {
 __global__ void et_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
