@@ -37,6 +37,21 @@ def timed_steps(s, xt, yt, mask, make_opt_fn, n, first_step):
     return time.perf_counter() - t0
 
 
+def step_percentiles(s, xt, yt, mask, make_opt_fn, n, first_step):
+    """p10 / p50 / p90 of single selective steps (ms), from events recorded on the session's stream between steps."""
+    import torch
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    torch.cuda.synchronize()
+    ev[0].record(s.stream)
+    for i in range(n):
+        s.train_step(xt, yt, mask, make_opt_fn(first_step + i), want_loss=False)
+        ev[i + 1].record(s.stream)
+    torch.cuda.synchronize()
+    ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(n))
+    pick = lambda q: ms[min(n - 1, int(q * n))]
+    return {"p10": pick(0.1), "p50": pick(0.5), "p90": pick(0.9)}
+
+
 def cpu_baseline(cfg, mask, sample_batch, opt_kind, hp):
     """The oracle, as it stands, on a smaller batch of the same workload (seeded like the bench)."""
     from oracle import nets, optim
@@ -62,8 +77,8 @@ def cpu_baseline(cfg, mask, sample_batch, opt_kind, hp):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="vit_b")
     ap.add_argument("--rho", type=float, default=0.5)
     ap.add_argument("--tq", type=int, default=10000)
@@ -106,6 +121,7 @@ def main():
     timed_steps(s, xt, yt, mask, mk, a.warmup, 1)
     dt = timed_steps(s, xt, yt, mask, mk, a.steps, 1 + a.warmup)
     ms_per_step = dt / a.steps * 1e3
+    spread = step_percentiles(s, xt, yt, mask, mk, a.steps, 1 + a.warmup + a.steps)
     # full training for the ratio (same protocol)
     timed_steps(s, xt, yt, ones, mk, max(2, a.warmup // 2), 1)
     dt_full = timed_steps(s, xt, yt, ones, mk, a.steps, 1)
@@ -168,7 +184,7 @@ def main():
         "cpu_baseline": None,
         "selected_tensors": int(mask.sum()), "first_selected": int(np.argmax(mask)) if mask.any() else None,
         "select_status": int(status), "t_select_ms": t_select_ms,
-        "full_ms_per_step": full_ms, "selective_over_full": ms_per_step / full_ms,
+        "step_ms_percentiles": spread, "full_ms_per_step": full_ms, "selective_over_full": ms_per_step / full_ms,
         "predicted_ms": predicted_ns / 1e6, "predicted_full_ms": t_full_model_ns / 1e6,
         "measured_over_predicted": ms_per_step / (predicted_ns / 1e6),
         "full_measured_over_predicted": full_ms / (t_full_model_ns / 1e6),

@@ -69,7 +69,7 @@ struct Params {
   int lda, ldb;
   int z_inner;
   long long sAo, sAi, sBo, sBi, sCo, sCi;
-  int split_k, k_chunk;  // split_k > 1: blockIdx.z picks [z*k_chunk, (z+1)*k_chunk)
+  int split_k, k_chunk;  // split_k > 1: chunk z of the reduction is [z*k_chunk, (z+1)*k_chunk)
   float alpha;
   const bf16* bias;
   const bf16* gain;      // E_AFFINE, E_AFFINE_ADD: per output column
@@ -114,16 +114,32 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char* p) {
   return __builtin_bit_cast(bf16x4, v);
 }
 
-// tile coordinates of this workgroup
+// tile coordinates of this workgroup and its index z along the grid's third dimension (batch or reduction chunk).
+// Workgroups are dealt to the 8 XCDs (one L2 each) round-robin in launch order, x fastest; the mapping below undoes
+// that so that an XCD works on consecutive tiles, which share operand panels.  In a split reduction only the tiles
+// of ONE chunk share anything, so there the unit of the dealing is (chunk, tile): an XCD gets a run of consecutive
+// tiles of one chunk (then of the next) instead of the same few tiles of every chunk.
 template <int BM, int BN>
-__device__ __forceinline__ void tile_coords(const Params& g, int& m0, int& n0) {
+__device__ __forceinline__ void tile_coords(const Params& g, int& m0, int& n0, int& z) {
   const int tiles_n = (g.N + BN - 1) / BN;
   const int tiles_m = (g.M + BM - 1) / BM;
-  const int nt = tiles_m * tiles_n;
-  const int w = blockIdx.x;
-  const int xcd = w % NUM_XCD, idx = w / NUM_XCD;
-  const int per = nt / NUM_XCD, rem = nt % NUM_XCD;
-  const int t = xcd * per + (xcd < rem ? xcd : rem) + idx;  // undo the round-robin XCD dealing
+  const int nt = tiles_m * tiles_n;     // = gridDim.x
+  int t;
+  if (g.split_k > 1) {
+    const int total = nt * g.split_k;   // gridDim.z = split_k
+    const int w = blockIdx.z * nt + blockIdx.x;
+    const int xcd = w % NUM_XCD, idx = w / NUM_XCD;
+    const int per = total / NUM_XCD, rem = total % NUM_XCD;
+    const int u = xcd * per + (xcd < rem ? xcd : rem) + idx;
+    z = u / nt;
+    t = u % nt;
+  } else {
+    const int w = blockIdx.x;
+    const int xcd = w % NUM_XCD, idx = w / NUM_XCD;
+    const int per = nt / NUM_XCD, rem = nt % NUM_XCD;
+    t = xcd * per + (xcd < rem ? xcd : rem) + idx;  // undo the round-robin XCD dealing
+    z = blockIdx.z;
+  }
   constexpr int GROUP = 8;                                   // 8 tile rows, walked column by column
   const int gsz = GROUP * tiles_n;
   const int grp = t / gsz, in = t % gsz;
@@ -134,9 +150,8 @@ __device__ __forceinline__ void tile_coords(const Params& g, int& m0, int& n0) {
 }
 
 // batch / split-K bookkeeping
-__device__ __forceinline__ void batch_offsets(const Params& g, const bf16*& A, const bf16*& B, long long& c_off,
+__device__ __forceinline__ void batch_offsets(const Params& g, int z, const bf16*& A, const bf16*& B, long long& c_off,
                                               int& k_begin, int& k_end) {
-  const int z = blockIdx.z;
   A = g.A;
   B = g.B;
   k_begin = 0;
@@ -356,13 +371,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_staged_kernel(Params g) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave / WGN, wave_n = wave % WGN;
-  int m0, n0;
-  tile_coords<BM, BN>(g, m0, n0);
+  int m0, n0, z;
+  tile_coords<BM, BN>(g, m0, n0, z);
   const bf16* A;
   const bf16* B;
   long long c_off;
   int k_begin, k_end;
-  batch_offsets(g, A, B, c_off, k_begin, k_end);
+  batch_offsets(g, z, A, B, c_off, k_begin, k_end);
   const int k_end_pad = min((g.K + 7) & ~7, ((k_end + 7) & ~7));
   const int nk = (k_end - k_begin + SBK - 1) / SBK;
 
@@ -562,14 +577,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(Params g) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave / WGN, wave_n = wave % WGN;
-  int m0, n0;
-  tile_coords<BM, BN>(g, m0, n0);
+  int m0, n0, z;
+  tile_coords<BM, BN>(g, m0, n0, z);
   if (g.no_store & 4) { m0 = 0; n0 = 0; }
   const bf16* A;
   const bf16* B;
   long long c_off;
   int k_begin, k_end;
-  batch_offsets(g, A, B, c_off, k_begin, k_end);
+  batch_offsets(g, z, A, B, c_off, k_begin, k_end);
   const int nk = (k_end - k_begin) / DBK;
 
   // per-lane global source of each of this wave's loads (slice 0)
@@ -769,14 +784,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave / WGN, wave_n = wave % WGN;
-  int m0, n0;
-  tile_coords<BM, BN>(g, m0, n0);
+  int m0, n0, z;
+  tile_coords<BM, BN>(g, m0, n0, z);
   if (g.no_store & 4) { m0 = 0; n0 = 0; }
   const bf16* A;
   const bf16* B;
   long long c_off;
   int k_begin, k_end;
-  batch_offsets(g, A, B, c_off, k_begin, k_end);
+  batch_offsets(g, z, A, B, c_off, k_begin, k_end);
   const int nk = (k_end - k_begin) / PBK;
 
   // per-lane global source and LDS destination (within a stage) of each of this wave's pieces
