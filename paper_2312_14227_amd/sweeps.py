@@ -55,8 +55,9 @@ def main():
     t_full_model = int(t_fwd) + int(t_dw.sum()) + int(t_dy[1:].sum())
     # (the schedule sweep compares importances of identical weights, so it trains only at its end)
     full_ms = _timed(s, xt, yt, ones, mk, a.steps) if a.what != "schedule" else float("nan")
-    print("# %s: batch %d, %d tensors; profiled T_fwd %.3f ms, T_full (model) %.3f ms, measured full step %.3f ms"
-          % (cfg.name, cfg.batch, N, t_fwd / 1e6, t_full_model / 1e6, full_ms))
+    print("# %s: batch %d, %d tensors; profiled T_fwd %.3f ms, T_full (model) %.3f ms%s"
+          % (cfg.name, cfg.batch, N, t_fwd / 1e6, t_full_model / 1e6,
+             "" if a.what == "schedule" else ", measured full step %.3f ms" % full_ms))
 
     if a.what == "tq":
         print("%8s %5s %9s %12s %12s %12s %9s %8s %10s %10s %9s" % (
