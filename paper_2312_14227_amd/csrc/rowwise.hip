@@ -168,6 +168,62 @@ __global__ __launch_bounds__(256) void layernorm_bwd_dx_kernel(const bf16* __res
   }
 }
 
+// The same for rows of V * 256 elements, held in registers between the two passes (same sums, same order)
+template <int V>
+__global__ __launch_bounds__(256) void layernorm_bwd_dx_regs_kernel(const bf16* __restrict__ d, const float* __restrict__ h,
+                                                                    long long in_stride, const float* __restrict__ mean,
+                                                                    const float* __restrict__ rstd,
+                                                                    const bf16* __restrict__ gain,
+                                                                    const float* __restrict__ skip, float* __restrict__ dh,
+                                                                    bf16* __restrict__ dh16, long long out_stride, int rows) {
+  constexpr int D = V * 256;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const float4* x = (const float4*)(h + (long long)row * in_stride);
+  const bf16x4* d4 = (const bf16x4*)(d + (long long)row * D);
+  const float4* sk = skip ? (const float4*)(skip + (long long)row * out_stride) : nullptr;
+  float4 v[V], k[V];
+  bf16x4 dv[V], g[V];
+#pragma unroll
+  for (int j = 0; j < V; j++) {
+    v[j] = x[lane + j * WAVE];
+    dv[j] = d4[lane + j * WAVE];
+    g[j] = ((const bf16x4*)gain)[lane + j * WAVE];
+    if (sk) k[j] = sk[lane + j * WAVE];
+  }
+  const float mu = mean[row], rs = rstd[row];
+  float t[V][4];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int j = 0; j < V; j++) {
+#pragma unroll
+    for (int e = 0; e < 4; e++) t[j][e] = (float)dv[j][e] * (float)g[j][e];
+    s1 += (t[j][0] + t[j][1]) + (t[j][2] + t[j][3]);
+    s2 += (t[j][0] * ((v[j].x - mu) * rs) + t[j][1] * ((v[j].y - mu) * rs)) +
+          (t[j][2] * ((v[j].z - mu) * rs) + t[j][3] * ((v[j].w - mu) * rs));
+  }
+  const float m1 = wave_sum(s1) / (float)D, m2 = wave_sum(s2) / (float)D;
+  float4* o = (float4*)(dh + (long long)row * out_stride);
+  bf16x4* o16 = dh16 ? (bf16x4*)(dh16 + (long long)row * out_stride) : nullptr;
+#pragma unroll
+  for (int j = 0; j < V; j++) {
+    float4 r;
+    r.x = rs * (t[j][0] - m1 - (v[j].x - mu) * rs * m2);
+    r.y = rs * (t[j][1] - m1 - (v[j].y - mu) * rs * m2);
+    r.z = rs * (t[j][2] - m1 - (v[j].z - mu) * rs * m2);
+    r.w = rs * (t[j][3] - m1 - (v[j].w - mu) * rs * m2);
+    if (sk) {
+      r.x += k[j].x; r.y += k[j].y; r.z += k[j].z; r.w += k[j].w;
+    }
+    o[lane + j * WAVE] = r;
+    if (o16) {
+      bf16x4 q;
+      q[0] = (bf16)r.x; q[1] = (bf16)r.y; q[2] = (bf16)r.z; q[3] = (bf16)r.w;
+      o16[lane + j * WAVE] = q;
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // column sums, stage 1: a block of 8 column-threads (8 columns each) x 32 row-threads sums
 // cs_rows() rows of 64 columns; stage 2 adds the row-chunk partials in ascending order
@@ -452,8 +508,15 @@ hipError_t layernorm_bwd_dx(const bf16* d, const float* h, long long in_stride, 
   if (rows <= 0 || D <= 0 || (D & 3) || (in_stride & 3) || (out_stride & 3) || !al16(h) || !al8(d) || !al8(gain) ||
       !al16(dh) || (skip && !al16(skip)) || (dh16 && !al8(dh16)))
     return hipErrorInvalidValue;
-  hipLaunchKernelGGL(layernorm_bwd_dx_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, d, h, in_stride, mean, rstd, gain,
-                     skip, dh, dh16, out_stride, rows, D);
+  const dim3 grid((rows + 3) / 4), block(256);
+  switch ((D & 255) ? 0 : D / 256) {
+#define ET_LN_REGS(V) \
+    case V: hipLaunchKernelGGL(layernorm_bwd_dx_regs_kernel<V>, grid, block, 0, s, d, h, in_stride, mean, rstd, gain, skip, dh, dh16, out_stride, rows); break;
+    ET_LN_REGS(1) ET_LN_REGS(2) ET_LN_REGS(3) ET_LN_REGS(4) ET_LN_REGS(5) ET_LN_REGS(6)
+#undef ET_LN_REGS
+    default:
+      hipLaunchKernelGGL(layernorm_bwd_dx_kernel, grid, block, 0, s, d, h, in_stride, mean, rstd, gain, skip, dh, dh16, out_stride, rows, D);
+  }
   return hipGetLastError();
 }
 
