@@ -1012,12 +1012,33 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   const int group = wave >> 2;
   bf16x8 a0[MI], b0[NI], a1[MI], b1[NI];
   // prologue: slice 0 into stage 0, slice 1 (or slice 0 again) into the registers
-  load_a_regs(nk > 1);
-  load_b_regs(nk > 1);
-  store_a(smem);
-  store_b(smem);
-  load_a_regs(nk > 2);
-  load_b_regs(nk > 2);
+  if (CONV == 0) {
+    // both slices are requested before the first is stored: one memory latency instead of two
+    u32x4 ra0[A_LOADS], rb0[B_LOADS];
+#pragma unroll
+    for (int i = 0; i < A_LOADS; i++) {
+      ra0[i] = *(const u32x4*)ga[i];
+      ga[i] += nk > 1 ? a_step : 0;
+    }
+#pragma unroll
+    for (int i = 0; i < B_LOADS; i++) {
+      rb0[i] = *(const u32x4*)gb[i];
+      gb[i] += nk > 1 ? b_step : 0;
+    }
+    load_a_regs(nk > 2);
+    load_b_regs(nk > 2);
+#pragma unroll
+    for (int i = 0; i < A_LOADS; i++) *(u32x4*)(smem + la[i]) = ra0[i];
+#pragma unroll
+    for (int i = 0; i < B_LOADS; i++) *(u32x4*)(smem + lb[i]) = rb0[i];
+  } else {
+    load_a_regs(nk > 1);
+    load_b_regs(nk > 1);
+    store_a(smem);
+    store_b(smem);
+    load_a_regs(nk > 2);
+    load_b_regs(nk > 2);
+  }
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   block_barrier();
   if (group == 1) block_barrier();
