@@ -776,6 +776,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   constexpr int A_BYTES = BM * PBK * 2, B_BYTES = BN * PBK * 2, STAGE = A_BYTES + B_BYTES;
   constexpr int A_LOADS = A_BYTES / 1024 / NW, B_LOADS = B_BYTES / 1024 / NW;  // wave-wide 1 KiB pieces per wave and slice
   static_assert(NW == 8, "two groups of four waves");
+  // transposed operands ([64 k-rows][tile width] in LDS, read with ds_read_b64_tr_b16): the 16-byte chunks of a k-row
+  // are XORed with (k & 3) << TSH.  Sixteen lanes read 32 bytes of each of four k-rows; with rows of 256 or 512
+  // bytes (a multiple of the 256-byte bank span) a shift of 2 spreads the two 16-lane groups that share a clock
+  // over all 64 banks, where a shift of 1 would put them on the same 32; widths that are not a multiple of 128
+  // elements (192) keep the shift of 1, their rows being offset by half a bank span anyway.
+  constexpr int TSH_A = (BM % 128 == 0) ? 2 : 1, TSH_B = (BN % 128 == 0) ? 2 : 1;
   static_assert(A_LOADS * 1024 * NW == A_BYTES && B_LOADS * 1024 * NW == B_BYTES, "tile/waves mismatch");
   constexpr int EPI_BYTES = NW * 32 * TN * 4;
   constexpr int SMEM = 2 * STAGE > EPI_BYTES ? 2 * STAGE : EPI_BYTES;
@@ -815,10 +821,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
       const int row = q * 8 + (lane >> 3), chunk = lane & 7;
       ga[i] = A + (long long)min(m0 + row, g.M - 1) * g.lda + k_begin + chunk * 8;
       la[i] = row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
-    } else {    // [64 k-rows][BM]; chunk j of k-row k sits at chunk position j ^ ((k & 3) << 1)
+    } else {    // [64 k-rows][BM]; chunk j of k-row k sits at chunk position j ^ ((k & 3) << TSH_A)
       constexpr int CR = BM / 8;
       const int pos = q * 64 + lane;
-      const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << 1);
+      const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << TSH_A);
       int gi = m0 + j * 8;
       if (gi + 8 > ((g.M + 7) & ~7)) gi = 0;
       ga[i] = A + (long long)(k_begin + k) * g.lda + gi;
@@ -834,7 +840,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
     if (CONV == 2) {
       constexpr int CR = BN / 8;
       const int pos = q * 64 + lane;
-      const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << 1);
+      const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << TSH_B);
       int gj = n0 + j * 8;
       if (gj + 8 > g.N) gj = 0;                 // N = 9 cC is a multiple of 8
       const int tap = gj / g.cC, ch = gj % g.cC;
@@ -851,7 +857,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
     } else {
       constexpr int CR = BN / 8;
       const int pos = q * 64 + lane;
-      const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << 1);
+      const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << TSH_B);
       int gj = n0 + j * 8;
       if (gj + 8 > ((g.N + 7) & ~7)) gj = 0;
       gb[i] = B + (long long)(k_begin + k) * g.ldb + gj;
@@ -875,7 +881,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   const int grp16 = lane >> 4, r16 = lane & 15;
   const int tr_col = (grp16 & 1) * 16 + 4 * (r16 & 3);
   const int tr_krow = (grp16 >> 1) * 8 + (r16 >> 2);
-  const int tr_swz = (r16 >> 2) << 1;
+  const int tr_row = r16 >> 2;   // k & 3 of the lane's k-row, the same for both halves of the 8 k values
 
   // fragment of k-step ks (16 k values, 0..3) of the slice in stage `st`
   auto load_a = [&](const unsigned char* st, int ks, int mi) -> bf16x8 {
@@ -885,7 +891,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
       return *(const bf16x8*)(st + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
     } else {
       const int col = rbase + tr_col;
-      const unsigned char* p = st + (ks * 16 + tr_krow) * (BM * 2) + (((col >> 3) ^ tr_swz) << 4) + ((col >> 2) & 1) * 8;
+      const unsigned char* p = st + (ks * 16 + tr_krow) * (BM * 2) + (((col >> 3) ^ (tr_row << TSH_A)) << 4) + ((col >> 2) & 1) * 8;
       bf16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * (BM * 2));
       return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
@@ -898,7 +904,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
       return *(const bf16x8*)(sb + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
     } else {
       const int col = rbase + tr_col;
-      const unsigned char* p = sb + (ks * 16 + tr_krow) * (BN * 2) + (((col >> 3) ^ tr_swz) << 4) + ((col >> 2) & 1) * 8;
+      const unsigned char* p = sb + (ks * 16 + tr_krow) * (BN * 2) + (((col >> 3) ^ (tr_row << TSH_B)) << 4) + ((col >> 2) & 1) * 8;
       bf16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * (BN * 2));
       return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
