@@ -156,7 +156,7 @@ int choose_tile(const GemmDesc& d, int k_per_block) {
   if (d.tile == T_PP_256x128 || d.tile == T_PP_512x64 || d.tile == T_PP_128x256 || d.tile == T_PP_64x512) return pp_ok ? d.tile : T_128x128;
   if (d.tile == T_DMA_256x256 || d.tile == T_DMA_256x128) return dma_ok ? d.tile : T_128x128;
   if (d.tile != T_AUTO) return d.tile;
-  if (d.N <= 64) return T_128x64;
+  if (d.N <= 64 || d.K <= 64) return T_128x64;   // one K slice: a stream over the rows, more workgroups in flight win
   // large problems: a two-group tile where K comes in slices of 64 (4-20 % faster than either
   // direct-to-LDS tile on every forward, passing and gradient product of the ViT shapes), else
   // the direct-to-LDS tile with slices of 32
