@@ -155,6 +155,12 @@ CONFIGS = {
     "vit_t230": ViTConfig("vit_t230", 2, 230, 64, 128, 2, 256, 1, 16),
     # fewer tokens: one and two key tiles in the fused attention kernels
     "vit_t40": ViTConfig("vit_t40", 3, 40, 64, 128, 2, 256, 2, 16),
+    # widths that are multiples of 256 (rows the LayerNorm kernels keep in registers): one block each, few tokens
+    "vit_w256": ViTConfig("vit_w256", 2, 9, 64, 256, 4, 256, 1, 16),
+    "vit_w512": ViTConfig("vit_w512", 2, 9, 64, 512, 8, 256, 1, 16),
+    "vit_w1280": ViTConfig("vit_w1280", 1, 7, 64, 1280, 20, 256, 1, 16),
+    "vit_w1536": ViTConfig("vit_w1536", 1, 7, 64, 1536, 24, 256, 1, 16),
+    "vit_w2048": ViTConfig("vit_w2048", 1, 7, 64, 2048, 32, 256, 1, 16),
 }
 
 

@@ -53,7 +53,8 @@ def test_mlp_all_16_masks():
 
 
 @pytest.mark.parametrize("name,seed", [("vit_small", 0), ("vit_small", 1), ("vit_mid", 2), ("vit_t230", 3),
-                                       ("vit_t40", 4)])
+                                       ("vit_t40", 4), ("vit_w256", 5), ("vit_w512", 6), ("vit_w1280", 7),
+                                       ("vit_w1536", 8), ("vit_w2048", 9)])
 def test_vit_masks_match_oracle(name, seed):
     cfg = CONFIGS[name]
     wl = make_workload(cfg, seed=seed, init="random")
