@@ -18,6 +18,8 @@
 // rowsum(P * dP) of a query from the stored forward output: it equals dO . O.
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace et {
 namespace {
 
@@ -114,25 +116,32 @@ __global__ __launch_bounds__(NTHREADS) void attention_fwd_kernel(const bf16* __r
 
     // S^T tile kt (unscaled): lane holds query l%32 and keys kt*32 + tile_row(r); only the last tile has keys
     // beyond T, which get -inf
-    auto scores = [&](int kt) -> f32x16 {
+    auto scores = [&](int kt, auto last) -> f32x16 {
       f32x16 acc;
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < 4; ks++)
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct(sk, kt * 32, ks, lane), qf[ks], acc, 0, 0, 0);
-      if (kt == KT - 1) {
+      if (decltype(last)::value) {   // the last tile is handled outside the loops, so the others carry no selects
 #pragma unroll
         for (int r = 0; r < 16; r++) acc[r] = kt * 32 + tile_row(r, lane) < T ? acc[r] : -INFINITY;
       }
       return acc;
     };
+    typedef std::integral_constant<bool, false> Inner;
+    typedef std::integral_constant<bool, true> Last;
 
     // sweep 1: maximum over this lane's keys (no exponentials yet); the other half of the keys lives in lane l^32
     float mx = -INFINITY;
 #pragma unroll 1
-    for (int kt = 0; kt < KT; kt++) {
-      const f32x16 st = scores(kt);
+    for (int kt = 0; kt < KT - 1; kt++) {
+      const f32x16 st = scores(kt, Inner());
+#pragma unroll
+      for (int r = 0; r < 16; r++) mx = fmaxf(mx, st[r]);
+    }
+    {
+      const f32x16 st = scores(KT - 1, Last());
 #pragma unroll
       for (int r = 0; r < 16; r++) mx = fmaxf(mx, st[r]);
     }
@@ -148,9 +157,7 @@ __global__ __launch_bounds__(NTHREADS) void attention_fwd_kernel(const bf16* __r
     for (int dt = 0; dt < 2; dt++)
 #pragma unroll
       for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
-#pragma unroll 1
-    for (int kt = 0; kt < KT; kt++) {
-      const f32x16 st = scores(kt);
+    auto accumulate = [&](int kt, const f32x16& st) {
 #pragma unroll
       for (int j = 0; j < 2; j++) {
         bf16x8 pf;
@@ -164,7 +171,10 @@ __global__ __launch_bounds__(NTHREADS) void attention_fwd_kernel(const bf16* __r
         for (int dt = 0; dt < 2; dt++)
           o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_tr(sv, kt * 32 + j * 16, dt * 32, lane), pf, o[dt], 0, 0, 0);
       }
-    }
+    };
+#pragma unroll 1
+    for (int kt = 0; kt < KT - 1; kt++) accumulate(kt, scores(kt, Inner()));
+    accumulate(KT - 1, scores(KT - 1, Last()));
     const float S = sum + __shfl_xor(sum, 32, 64);
     const float inv = 1.f / S;
     const int row = qt * 32 + l32;
