@@ -12,7 +12,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 @pytest.mark.skipif(shutil.which("g++") is None, reason="no host compiler")
 def test_selector_is_clean_under_asan_and_ubsan(tmp_path):
     exe = str(tmp_path / "fuzz_select")
-    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-static-libasan",
            "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(ROOT, "paper_2312_14227_amd", "csrc"),
            "-o", exe, os.path.join(ROOT, "tests", "host", "fuzz_select.cpp")]
     subprocess.run(cmd, check=True, capture_output=True, text=True)
