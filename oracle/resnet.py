@@ -23,9 +23,11 @@ an evaluation keeps in memory between two operations: each convolution output ex
 (kept in fp32 so that the pooling argmax is decided on unrounded values), each affine/ReLU
 output, the pooled features, the bf16 copy of the logit gradient that feeds the matrix products,
 and each error gradient handed from one backward operation to the next.  Arithmetic stays float64.
-Whether the column gradient of a 3x3 convolution (d @ W, before the adjoint of im2col sums it into
-the input gradient) is such a tensor depends on the layout under test: `cols_stored(cin, cout,
-stride)` says so for the blocks' 3x3 convolutions (default: stored).
+The column gradient of a convolution with a kernel larger than 1x1 (d @ W, before the adjoint of
+im2col sums its shifted copies into the input gradient) is NOT such a tensor: the storage contract
+of the bf16 workloads (stated with the model description of the C ABI) keeps it in float32, so the
+input gradient is rounded once, after the sum.  For a 1x1 convolution the product is the input
+gradient itself and is rounded like any other stored product.
 """
 import numpy as np
 
@@ -79,7 +81,7 @@ def col2im(dcols, shape, kh, kw, stride, pad):
 class Conv:
     """One convolution with everything its backward operations need."""
 
-    def __init__(self, x, w, stride, q=_same, q_cols=None):
+    def __init__(self, x, w, stride, q=_same):
         self.x_shape = x.shape
         self.w = w
         O, self.kh, self.kw, _ = w.shape
@@ -87,13 +89,15 @@ class Conv:
         self.cols = im2col(x, self.kh, self.kw, stride, self.pad)
         self.wm = w.reshape(O, -1)
         self.out = q(self.cols @ self.wm.T)
-        self.q_cols = q if q_cols is None else q_cols      # storage hook of the column gradient
+        self.q = q
 
     def dw(self, d):
         return (d.reshape(-1, d.shape[-1]).T @ self.cols.reshape(-1, self.cols.shape[-1])).reshape(self.w.shape)
 
     def dx(self, d):
-        dcols = self.q_cols(d @ self.wm)    # the column gradient: a stored tensor in most layouts
+        dcols = d @ self.wm
+        if self.kh == 1 and self.kw == 1:   # the product is the input gradient itself: a stored tensor
+            dcols = self.q(dcols)
         return col2im(dcols, self.x_shape, self.kh, self.kw, self.stride, self.pad)
 
 
@@ -137,7 +141,7 @@ def block_layout(cfg):
     return out, t
 
 
-def resnet_forward(cfg, weights, x, y, store=None, cols_stored=lambda cin, cout, stride: True):
+def resnet_forward(cfg, weights, x, y, store=None):
     q = store if store is not None else _same
     W = [np.asarray(w, dtype=_F) for w in weights]
     x = np.asarray(x, dtype=_F)
@@ -154,8 +158,7 @@ def resnet_forward(cfg, weights, x, y, store=None, cols_stored=lambda cin, cout,
         b = {"x": h, "t": t, "proj": proj}
         b["c1"] = Conv(h, W[t], 1, q)
         b["y1"] = q(np.maximum(b["c1"].out * W[t + 1] + W[t + 2], 0.0))
-        p_out, _, _, p_in = W[t + 3].shape
-        b["c2"] = Conv(b["y1"], W[t + 3], stride, q, q if cols_stored(p_in, p_out, stride) else _same)
+        b["c2"] = Conv(b["y1"], W[t + 3], stride, q)
         b["y2"] = q(np.maximum(b["c2"].out * W[t + 4] + W[t + 5], 0.0))
         b["c3"] = Conv(b["y2"], W[t + 6], 1, q)
         m = b["c3"].out * W[t + 7] + W[t + 8]
@@ -177,8 +180,8 @@ def resnet_forward(cfg, weights, x, y, store=None, cols_stored=lambda cin, cout,
 # ----------------------------------------------------------------------------
 # masked backward on the tensor-level chain
 # ----------------------------------------------------------------------------
-def resnet_step(cfg, weights, x, y, mask, store=None, cols_stored=lambda cin, cout, stride: True):
-    loss, c = resnet_forward(cfg, weights, x, y, store, cols_stored)
+def resnet_step(cfg, weights, x, y, mask, store=None):
+    loss, c = resnet_forward(cfg, weights, x, y, store)
     q = c["q"]
     W, blocks, t_head = c["W"], c["blocks"], c["t_head"]
     N = len(W)

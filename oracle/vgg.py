@@ -13,10 +13,10 @@ to the pre-activation of the previous layer.
 Layout NHWC; convolution weights [out, kh, kw, in] with zero padding 1; the linear layers read the
 pooled features flattened in (h, w, c) order.  `store` is the storage-precision hook described in
 oracle/resnet.py: applied to every tensor a bf16 evaluation keeps in memory (activations after
-bias + ReLU, pooled features, column gradients, error gradients); a layer's pre-activation is not
-such a tensor here (bias and ReLU are applied to the unrounded sum).  Whether the column gradient
-of a convolution (d @ W, before the adjoint of im2col sums it into the input gradient) is a stored
-tensor depends on the layout under test: `cols_stored(cin, cout)` says so per convolution.
+bias + ReLU, pooled features, error gradients); a layer's pre-activation is not such a tensor
+here (bias and ReLU are applied to the unrounded sum), and neither is the column gradient of a
+3x3 convolution (d @ W, before the adjoint of im2col sums it into the input gradient, which is
+rounded once).
 """
 import numpy as np
 
@@ -85,7 +85,7 @@ def vgg_forward(cfg, weights, x, y, store=None):
     return loss, c
 
 
-def vgg_step(cfg, weights, x, y, mask, store=None, cols_stored=lambda cin, cout: True):
+def vgg_step(cfg, weights, x, y, mask, store=None):
     loss, c = vgg_forward(cfg, weights, x, y, store)
     W, q, units, pools, acts = c["W"], c["q"], c["units"], c["pools"], c["acts"]
     t_fc, n_fc = c["t_fc"], c["n_fc"]
@@ -133,9 +133,5 @@ def vgg_step(cfg, weights, x, y, mask, store=None, cols_stored=lambda cin, cout:
             s["d"] = q(dx * (prev["y"] > 0.0))
         chain[t] = _Tiny(lambda s, u=u: u["conv"].dw(s["d"]), conv_dy if i > 0 else None)
         chain[t + 1] = _Tiny(lambda s: s["d"].reshape(-1, s["d"].shape[-1]).sum(axis=0), identity)
-    # where the column gradient of a convolution is a stored tensor, give its Conv the hook
-    for u in units:
-        cout, _, _, cin = W[u["t"]].shape
-        u["conv"].q_cols = q if cols_stored(cin, cout) else _same
     grads, work = _run_chain(chain, mask, state)
     return dict(loss=loss, grads=grads, work=work, logits=c["logits"])

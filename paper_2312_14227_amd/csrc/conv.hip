@@ -71,7 +71,10 @@ __global__ __launch_bounds__(256) void im2col_any_kernel(const bf16* __restrict_
 // adjoint of im2col in gather form: every input pixel adds the (at most k*k) column entries that
 // were copied from it, taps in ascending order; then out = (sum + add) * (mask > 0)
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void col2im_kernel(const bf16* __restrict__ dcols, const bf16* __restrict__ add,
+// The column matrix is float32 for kernels larger than 1x1 (the taps are summed before the one
+// rounding of the input gradient) and bf16 for a strided 1x1 convolution (a pure scatter).
+template <typename TC>
+__global__ __launch_bounds__(256) void col2im_kernel(const TC* __restrict__ dcols, const bf16* __restrict__ add,
                                                      const bf16* __restrict__ mask, bf16* __restrict__ out, ConvGeom g,
                                                      long long total) {
   const int c8n = g.C >> 3;
@@ -93,10 +96,16 @@ __global__ __launch_bounds__(256) void col2im_kernel(const bf16* __restrict__ dc
         if (ww < 0 || ww % g.stride) continue;
         const int ow = ww / g.stride;
         if (ow >= g.Wo) continue;
-        const bf16x8 v = *(const bf16x8*)(dcols + (((long long)b * g.Ho + oh) * g.Wo + ow) * g.Kc +
-                                          (long long)(ky * g.k + kx) * g.C + c8 * 8);
+        const TC* src = dcols + (((long long)b * g.Ho + oh) * g.Wo + ow) * g.Kc + (long long)(ky * g.k + kx) * g.C + c8 * 8;
+        if constexpr (sizeof(TC) == 4) {
+          const float4 v0 = *(const float4*)src, v1 = *(const float4*)(src + 4);
+          acc[0] += v0.x; acc[1] += v0.y; acc[2] += v0.z; acc[3] += v0.w;
+          acc[4] += v1.x; acc[5] += v1.y; acc[6] += v1.z; acc[7] += v1.w;
+        } else {
+          const bf16x8 v = *(const bf16x8*)src;
 #pragma unroll
-        for (int j = 0; j < 8; j++) acc[j] += (float)v[j];
+          for (int j = 0; j < 8; j++) acc[j] += (float)v[j];
+        }
       }
     }
     const long long o = pix * g.C + c8 * 8;
@@ -572,11 +581,15 @@ hipError_t im2col(const bf16* x, bf16* cols, const ConvGeom& g, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t col2im(const bf16* dcols, const bf16* add, const bf16* mask, bf16* out, const ConvGeom& g, hipStream_t s) {
+hipError_t col2im(const void* dcols, bool dcols_f32, const bf16* add, const bf16* mask, bf16* out, const ConvGeom& g,
+                  hipStream_t s) {
   if (!geom_ok(g) || (g.C & 7) || g.Kc != g.k * g.k * g.C) return hipErrorInvalidValue;
   if (!al16(dcols) || !al16(out) || (add && !al16(add)) || (mask && !al16(mask))) return hipErrorInvalidValue;
   const long long total = (long long)g.B * g.H * g.W * (g.C >> 3);
-  hipLaunchKernelGGL(col2im_kernel, dim3(grid_for(total)), dim3(256), 0, s, dcols, add, mask, out, g, total);
+  if (dcols_f32)
+    hipLaunchKernelGGL(col2im_kernel<float>, dim3(grid_for(total)), dim3(256), 0, s, (const float*)dcols, add, mask, out, g, total);
+  else
+    hipLaunchKernelGGL(col2im_kernel<bf16>, dim3(grid_for(total)), dim3(256), 0, s, (const bf16*)dcols, add, mask, out, g, total);
   return hipGetLastError();
 }
 

@@ -120,10 +120,16 @@ inline int conv_dw(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16* d, 
   return ET_OK;
 }
 
-// gradient of the column matrix: dcols[M][Kc] = d[M][Cout] * Wm[Cout][Kc]
-inline int conv_dcols(et_ctx* c, const ConvUnit& u, const bf16* d, const bf16* Wm, bf16* dcols) {
+// Gradient of the column matrix: dcols[M][Kc] = d[M][Cout] * Wm[Cout][Kc].  For a 1x1 convolution this is the
+// input gradient itself, stored as bf16 like every tensor handed from one operation to the next.  For a larger
+// kernel it is an intermediate whose shifted copies the adjoint of im2col has yet to add: it stays float32, so
+// that the input gradient is rounded once, after the sum, as in the implicit-GEMM form of the same operation.
+inline bool dcols_f32(const ConvUnit& u) { return u.k > 1; }
+inline size_t dcols_bytes(const et_ctx* c, const ConvUnit& u) { return rows_of(c, u) * u.Kc * (dcols_f32(u) ? 4 : 2); }
+inline int conv_dcols(et_ctx* c, const ConvUnit& u, const bf16* d, const bf16* Wm, void* dcols) {
   et::GemmDesc g = linear_dx(d, Wm, (int)rows_of(c, u), u.Cout, u.Kc);
   g.C = dcols;
+  g.c_f32 = dcols_f32(u);
   ET_G(g);
   return ET_OK;
 }

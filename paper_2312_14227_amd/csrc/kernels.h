@@ -162,8 +162,10 @@ struct ConvGeom {
 };
 // cols[B*Ho*Wo][Kc], column order (ky, kx, c); out-of-image taps and the row tail are zero
 hipError_t im2col(const bf16* x, bf16* cols, const ConvGeom& g, hipStream_t s);
-// out[B][H][W][C] = (adjoint of im2col applied to dcols  + add) * (mask > 0); add, mask nullable; C % 8 == 0
-hipError_t col2im(const bf16* dcols, const bf16* add, const bf16* mask, bf16* out, const ConvGeom& g, hipStream_t s);
+// out[B][H][W][C] = (adjoint of im2col applied to dcols  + add) * (mask > 0); add, mask nullable; C % 8 == 0;
+// dcols is float32 [B*Ho*Wo][Kc] (dcols_f32) or bf16; the taps are added in float32, the result is rounded once
+hipError_t col2im(const void* dcols, bool dcols_f32, const bf16* add, const bf16* mask, bf16* out, const ConvGeom& g,
+                  hipStream_t s);
 // folded BatchNorm: out = act(z1*g1 + b1 + t), t = z2*g2 + b2 (g2 given), z2 (g2 null) or 0 (z2 null);
 // z1 is bf16, or fp32 when z1_f32 is given; rows x C, C % 8 == 0
 hipError_t affine_act(const bf16* z1, const float* z1_f32, const bf16* g1, const bf16* b1, const bf16* z2,

@@ -65,7 +65,7 @@ int build_resnet(et_ctx* c) {
   add("head.W", (size_t)C * Cf); add("head.b", C);
 
   // ---- workspace
-  size_t max_act = 0, max_cols = 0, max_cs = 0, pe = 0, max_flip = 8;
+  size_t max_act = 0, max_cols = 0, max_cs = 0, pe = 0, max_flip = 8, dcols_b = 16;
   auto act = [&](size_t rows, size_t ch) {
     max_act = std::max(max_act, rows * ch);
     max_cs = std::max(max_cs, et::colsum_partial_elems((int)rows, (int)ch));
@@ -73,7 +73,8 @@ int build_resnet(et_ctx* c) {
   auto wg = [&](const ConvUnit& u) {
     const int M = (int)rows_of(c, u);
     pe = std::max(pe, std::max(conv_dw_partials(c, u), conv_split_partials(c, u)));
-    max_cols = std::max(max_cols, (size_t)M * u.Kc);   // the column gradient of any unit fits rdcols
+    max_cols = std::max(max_cols, (size_t)M * u.Kc);   // the column matrix of any unit fits rdcols,
+    dcols_b = std::max(dcols_b, dcols_bytes(c, u));     // and so does its column gradient
     if (implicit_dy(u)) max_flip = std::max(max_flip, (size_t)u.Cout * 9 * u.Cin);
   };
   auto unit = [&](ConvUnit& u, bool with_y) {
@@ -117,7 +118,7 @@ int build_resnet(et_ctx* c) {
   for (int i = 0; i < 2; i++) reserve(c, &c->rd[i], b16 * max_act);
   reserve(c, &c->rdsum, b16 * max_act);
   reserve(c, &c->rdsc, b16 * max_act);
-  reserve(c, &c->rdcols, b16 * std::max<size_t>(max_cols, 8));
+  reserve(c, &c->rdcols, std::max(b16 * std::max<size_t>(max_cols, 8), dcols_b));
   reserve(c, &c->wflip, b16 * max_flip);
   c->gemm_partial_elems = pe;
   reserve(c, &c->gemm_partials, f32 * std::max<size_t>(pe, 64));
@@ -285,7 +286,7 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
         if ((rc = conv_dy_implicit(c, b.c2, c->rd[0], Wt(t + 3), b.c1.y, c->rd[1])) != ET_OK) return rc;
       } else {
         if ((rc = conv_dcols(c, b.c2, c->rd[0], Wt(t + 3), c->rdcols)) != ET_OK) return rc;
-        ET_KB(1, 2.0 * M2 * b.c2.Kc + 4.0 * M1 * b.c1.Cout, et::col2im(c->rdcols, nullptr, b.c1.y, c->rd[1], geom(c, b.c2), s));
+        ET_KB(1, (dcols_f32(b.c2) ? 4.0 : 2.0) * M2 * b.c2.Kc + 4.0 * M1 * b.c1.Cout, et::col2im(c->rdcols, dcols_f32(b.c2), nullptr, b.c1.y, c->rd[1], geom(c, b.c2), s));
       }
     }
     // c1
@@ -316,7 +317,7 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
       if (b.proj) {
         if ((rc = conv_dcols(c, b.sc, c->rdsc, Wt(t + 9), c->rdcols)) != ET_OK) return rc;
         ET_KB(1, 2.0 * M3 * b.sc.Kc + (prev_y ? 6.0 : 4.0) * M1 * b.c1.Cin,
-              et::col2im(c->rdcols, c->rd[1], prev_y, prev_y ? c->rdsum : c->rd[0], geom(c, b.sc), s));
+              et::col2im(c->rdcols, dcols_f32(b.sc), c->rd[1], prev_y, prev_y ? c->rdsum : c->rd[0], geom(c, b.sc), s));
       } else {
         ET_KB(1, 8.0 * M1 * b.c1.Cin, et::add_mask(c->rd[1], c->rdsum, prev_y, c->rdsum, M1 * b.c1.Cin, s));
       }

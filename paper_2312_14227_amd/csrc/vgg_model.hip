@@ -74,7 +74,7 @@ int build_vgg(et_ctx* c) {
   }
 
   // ---- workspace
-  size_t max_act = 0, max_cols = 0, max_cs = 0, pe = 0, max_flip = 8;
+  size_t max_act = 0, max_cols = 0, max_cs = 0, pe = 0, max_flip = 8, dcols_b = 16;
   c->vpool.assign(d.n_stages, nullptr);
   c->varg.assign(d.n_stages, nullptr);
   for (size_t i = 0; i < c->vconv.size(); i++) {
@@ -85,6 +85,7 @@ int build_vgg(et_ctx* c) {
     reserve(c, &u.y, b16 * M * u.Cout);
     max_act = std::max(max_act, std::max(M * u.Cout, M * round8(u.Cin)));
     if (!implicit_dw(c, u) || !implicit_dy(u)) max_cols = std::max(max_cols, M * u.Kc);
+    if (i > 0 && !implicit_dy(u)) dcols_b = std::max(dcols_b, dcols_bytes(c, u));   // conv0 passes nothing on
     max_cs = std::max(max_cs, et::colsum_partial_elems((int)M, u.Cout));
     pe = std::max(pe, std::max(conv_dw_partials(c, u), conv_split_partials(c, u)));
     const bool last_of_stage = i + 1 == c->vconv.size() || c->vstage[i + 1] != c->vstage[i];
@@ -120,7 +121,7 @@ int build_vgg(et_ctx* c) {
   reserve(c, &c->dl16, b16 * B * C);
   reserve(c, &c->loss, 256 + sizeof(float) * (size_t)d.batch);
   for (int i = 0; i < 3; i++) reserve(c, &c->rd[i], b16 * max_act);
-  reserve(c, &c->rdcols, b16 * std::max<size_t>(max_cols, 8));
+  reserve(c, &c->rdcols, std::max(b16 * std::max<size_t>(max_cols, 8), dcols_b));
   reserve(c, &c->wflip, b16 * max_flip);
   c->gemm_partial_elems = pe;
   reserve(c, &c->gemm_partials, f32 * std::max<size_t>(pe, 64));
@@ -267,9 +268,9 @@ int vgg_backward(et_ctx* c, const void* x, const uint8_t* mask) {
       }
       if ((rc = conv_dcols(c, u, dcur, conv_matrix(c, i), c->rdcols)) != ET_OK) return rc;
       if (same_stage) {
-        ET_KB(1, 2.0 * M * u.Kc + 4.0 * nin, et::col2im(c->rdcols, nullptr, p.y, dn, geom(c, u), s));
+        ET_KB(1, (dcols_f32(u) ? 4.0 : 2.0) * M * u.Kc + 4.0 * nin, et::col2im(c->rdcols, dcols_f32(u), nullptr, p.y, dn, geom(c, u), s));
       } else {       // a pooling layer sits in between
-        ET_KB(1, 2.0 * M * u.Kc + 2.0 * nin, et::col2im(c->rdcols, nullptr, nullptr, c->rd[2], geom(c, u), s));
+        ET_KB(1, (dcols_f32(u) ? 4.0 : 2.0) * M * u.Kc + 2.0 * nin, et::col2im(c->rdcols, dcols_f32(u), nullptr, nullptr, c->rd[2], geom(c, u), s));
         ET_KB(1, 3.0 * nin + 16.0 * nin, et::maxpool2x2_bwd(c->rd[2], c->varg[c->vstage[i - 1]], p.y, dn, B, p.Ho, p.Wo, p.Cout, s));
       }
       dcur = dn;

@@ -73,7 +73,21 @@ def make_workload(cfg, seed: int = 0, init: str = "paper", batch: int = None) ->
             if leaf == "W":                                                  # He normal, fan-in
                 w = rng.standard_normal(shape) * np.sqrt(2.0 / int(np.prod(shape[1:])))
             elif leaf == "g":
-                w = np.ones(shape) if init == "paper" else 1.0 + 0.1 * rng.standard_normal(shape)
+                # A folded BatchNorm gain carries the 1/sigma of the statistics it absorbed.  He-normal
+                # kernels keep the second moment through convolution + ReLU, but every residual sum adds
+                # the branch's to the stream's: the gains closing a ResNet block (last main convolution,
+                # projection shortcut) are therefore below one, so that the stream stays O(1) through
+                # the 16 blocks (0.25^2 + 0.9^2 ~ 0.9 where two zero-mean branches meet under a ReLU), and
+                # the stem's gain brings the stream to a root mean square of about one (logits of a few
+                # units, loss 6.6 at the full size).
+                base = 1.0
+                if cfg.kind == "resnet" and name.endswith("c3.g"):
+                    base = 0.25
+                elif cfg.kind == "resnet" and name.endswith("sc.g"):
+                    base = 0.9
+                elif cfg.kind == "resnet" and name == "stem.g":
+                    base = 0.4
+                w = base * (np.ones(shape) if init == "paper" else 1.0 + 0.1 * rng.standard_normal(shape))
             else:
                 w = np.zeros(shape) if init == "paper" else 0.05 * rng.standard_normal(shape)
         else:

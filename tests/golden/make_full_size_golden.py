@@ -41,9 +41,8 @@ def vgg_in_chunks(cfg, wl, chunk):
     from oracle import resnet, vgg
     B = wl.x.shape[0]
     assert B % chunk == 0 and ((B // chunk) & (B // chunk - 1)) == 0
-    # the bf16 data layout stores no column gradient for convolutions with 64 k output channels (implicit GEMM)
     parts = [vgg.vgg_step(cfg, wl.weights, wl.x[i:i + chunk], wl.y[i:i + chunk], [1] * len(wl.weights),
-                          store=resnet.round_bf16, cols_stored=lambda cin, cout: cout % 64 != 0 or cin % 8 != 0)
+                          store=resnet.round_bf16)
              for i in range(0, B, chunk)]
     n = len(parts)
     return dict(loss=sum(p["loss"] for p in parts) / n,
@@ -61,9 +60,7 @@ def main():
         # a bf16 evaluation of a deep ReLU network is not a rounding of the exact gradient: the stored
         # reference rounds the tensors the bf16 data layout keeps in memory (see oracle/resnet.py)
         from oracle import resnet
-        # (no stored column gradient for the 3x3 / stride 1 convolutions, which pass gradients as implicit GEMMs)
-        r = resnet.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights), store=resnet.round_bf16,
-                               cols_stored=lambda cin, cout, stride: not (stride == 1 and cout % 64 == 0 and cin % 8 == 0))
+        r = resnet.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights), store=resnet.round_bf16)
         I = oimp.importance_from_grads(r["grads"], wl.weights, wl.snapshot)
     elif cfg.kind == "mobilenet":
         from oracle import mobilenet, resnet

@@ -197,11 +197,9 @@ def _bf16_storage_step(cfg, wl):
     from oracle import vgg as V
     ones = [1] * len(wl.weights)
     if cfg.kind == "resnet":
-        return R.resnet_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16,
-                             cols_stored=lambda cin, cout, stride: not (stride == 1 and cout % 64 == 0 and cin % 8 == 0))
+        return R.resnet_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16)
     if cfg.kind == "vgg":
-        return V.vgg_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16,
-                          cols_stored=lambda cin, cout: cout % 64 != 0 or cin % 8 != 0)
+        return V.vgg_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16)
     return MB.mobilenet_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16)
 
 

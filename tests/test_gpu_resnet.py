@@ -30,12 +30,6 @@ def _run(s, xt, yt, mask):
     return loss, [g.cpu().numpy() for g in s.grad]
 
 
-def _cols_stored(cin, cout, stride):
-    """Data layout of the HIP path: a 3x3 / stride 1 convolution with 64 k output channels passes the gradient
-    to its input as an implicit GEMM and never stores the column gradient."""
-    return not (stride == 1 and cout % 64 == 0 and cin % 8 == 0)
-
-
 # resnet_c64 reduces over 576 and more terms: now and then fp32 and float64 sums round to different bf16
 # values, and one flipped ReLU decision moves a gradient by a few 1e-3; its bound is the workload
 # tolerance itself, the cases without flips keep a tenth of it.
@@ -47,7 +41,7 @@ def test_resnet_masks_match_oracle(name, seed, init, factor):
     wl = make_workload(cfg, seed=seed, init=init)
     N = len(wl.weights)
     ones = [1] * N
-    ref = R.resnet_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16, cols_stored=_cols_stored)
+    ref = R.resnet_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16)
     exact = R.resnet_step(cfg, wl.weights, wl.x, wl.y, ones)
     s = _session(cfg, wl)
     xt, yt = s.put_input(wl.x, wl.y)
