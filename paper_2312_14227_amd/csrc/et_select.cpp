@@ -97,41 +97,56 @@ static int select_core(int32_t n, const double* importance, const uint64_t* t_dw
         reach += b[i];
       }
     }
-    if ((u128)(budget + 1) * (u128)(n + 1) > ((u128)1 << 31)) return ET_ENOMEM;  // choose a coarser tq
+    // The table is kept as two rolling value rows plus one take/skip bit per cell for the walk back: 1/64 of
+    // the memory of a full value table, so nanosecond resolution (tq = 0) on a profile of a few
+    // milliseconds stays usable (Section 6.3 wants the selector far below 1 % of the training time).
+    if ((u128)(budget + 1) * (u128)(n + 1) > ((u128)1 << 32)) return ET_ENOMEM;  // 512 MiB of bits: choose a coarser tq
     const size_t W = (size_t)budget + 1;
+    const size_t WB = (W + 63) / 64;                       // 64-bit words per row of bits
 
-    // ---- knapsack from the output side: row d uses the d output-most tensors (depth <= d)
-    std::vector<int64_t> knap((size_t)(n + 1) * W, 0);
+    // ---- the capacity each candidate input-most tensor i* = i leaves for the tensors output-side of it
+    //      (reach = sum of b over those tensors); deeper tensors only cost more to reach
+    std::vector<uint64_t> cap(n, 0);
+    std::vector<uint8_t> fits(n, 0);
+    {
+      uint64_t reach = 0;
+      for (int32_t i = n - 1; i >= 0; i--) {
+        if (reach > budget) break;
+        if (reach + a[i] <= budget) { fits[i] = 1; cap[i] = budget - reach - a[i]; }
+        reach += b[i];
+      }
+    }
+
+    // ---- knapsack from the output side: row d uses the d output-most tensors (depth <= d); row d - 1 is what
+    //      candidate i* = n - d reads, just before tensor n - d itself enters as row d.  Scanning from the output keeps, among equal values, the mask with the
+    //      most leading zeros.
+    std::vector<int64_t> row0(W, 0), row1(W, 0);
+    std::vector<uint64_t> took((size_t)(n + 1) * WB, 0);   // bit (d, t): row d differs from row d - 1 at t
+    int64_t best = 0;  // the empty mask
+    int32_t best_first = -1;
+    uint64_t best_cap = 0;
+    int64_t* prev = row0.data();
+    int64_t* cur = row1.data();
     for (int32_t d = 1; d <= n; d++) {
-      const int32_t i = n - d;
-      const int64_t* prev = &knap[(size_t)(d - 1) * W];
-      int64_t* cur = &knap[(size_t)d * W];
+      const int32_t i = n - d;                             // candidate i* = i: its output side is row d - 1 = prev
+      if (fits[i]) {
+        const int64_t v = iq[i] + prev[cap[i]];
+        if (v > best) { best = v; best_first = i; best_cap = cap[i]; }
+      }
       const uint64_t w = a[i];
+      uint64_t* bits = &took[(size_t)d * WB];
       for (size_t t = 0; t < W; t++) {
         int64_t v = prev[t];
         if (t >= w) {
           const int64_t take = prev[t - w] + iq[i];
-          if (take > v) v = take;
+          if (take > v) {
+            v = take;
+            bits[t >> 6] |= (uint64_t)1 << (t & 63);
+          }
         }
         cur[t] = v;
       }
-    }
-
-    // ---- choose the input-most selected tensor; scanning from the output keeps, among equal
-    //      values, the mask with the most leading zeros
-    int64_t best = 0;  // the empty mask
-    int32_t best_first = -1;
-    uint64_t best_cap = 0;
-    uint64_t reach = 0;  // sum of b over tensors output-side of i
-    for (int32_t i = n - 1; i >= 0; i--) {
-      const uint64_t need = reach + a[i];
-      if (reach > budget) break;  // deeper tensors only cost more to reach
-      if (need <= budget) {
-        const uint64_t cap = budget - need;
-        const int64_t v = iq[i] + knap[(size_t)(n - 1 - i) * W + cap];
-        if (v > best) { best = v; best_first = i; best_cap = cap; }
-      }
-      reach += b[i];
+      std::swap(prev, cur);
     }
     if (best_first >= 0) {
       mask_out[best_first] = 1;
@@ -140,9 +155,7 @@ static int select_core(int32_t n, const double* importance, const uint64_t* t_dw
       // value is reachable without it
       for (int32_t i = best_first + 1; i < n; i++) {
         const int32_t d = n - i;
-        const int64_t with_row = knap[(size_t)d * W + t];
-        const int64_t without = knap[(size_t)(d - 1) * W + t];
-        if (with_row != without) {
+        if ((took[(size_t)d * WB + (t >> 6)] >> (t & 63)) & 1) {
           mask_out[i] = 1;
           t -= a[i];
         }

@@ -129,3 +129,40 @@ def test_importance_quantisation():
     assert q == [3 * 2 ** 38, 2, 2, -4]
     with pytest.raises(ValueError):
         sel.quantise_importance([1.0, float("nan")])
+
+
+def test_time_quantisation_by_hand():
+    """Eq. 8 with every integer worked out by hand: t~ = floor(t * T_q / T_b), T_b the full backward time, in which
+    the input-most tensor's gradient passing is never charged (Section 2.2, Eq. 7)."""
+    t_dw, t_dy, t_fwd = [7, 13, 5, 11], [1000, 9, 17, 3], 20
+    # T_b = (7 + 13 + 5 + 11) + (9 + 17 + 3) = 65, not 1065; T_full = 85
+    assert sel.t_full(t_fwd, t_dw, t_dy) == 85
+    # rho = 0.7: floor(59.5) - 20 = 39 ns (a ceiling would give 40)
+    a, b, budget = sel.quantise_times(t_fwd, t_dw, t_dy, 700_000, 0)
+    assert (a, b, budget) == (t_dw, t_dy, 39)
+    # T_q = 10: 70/65, 130/65, 50/65, 110/65 -> 1, 2, 0, 1 (ceilings: 2, 2, 1, 2; with t_dy[0] in T_b all four
+    # would be 0); 10000/65, 90/65, 170/65, 30/65 -> 153, 1, 2, 0; budget 390/65 = 6 exactly
+    a, b, budget = sel.quantise_times(t_fwd, t_dw, t_dy, 700_000, 10)
+    assert (a, b, budget) == ([1, 2, 0, 1], [153, 1, 2, 0], 6)
+    # rho = 0.69: floor(58.65) - 20 = 38 -> 380/65 = 5.85 -> 5
+    assert sel.quantise_times(t_fwd, t_dw, t_dy, 690_000, 10)[2] == 5
+    # T_q = 64 is still below T_b = 65: 448/65, 832/65, 320/65, 704/65 -> 6, 12, 4, 10
+    a, b, budget = sel.quantise_times(t_fwd, t_dw, t_dy, 700_000, 64)
+    assert (a, b[1:], budget) == ([6, 12, 4, 10], [8, 16, 2], 38)
+    # T_q >= T_b keeps nanoseconds
+    for Tq in (65, 66, 10_000):
+        assert sel.quantise_times(t_fwd, t_dw, t_dy, 700_000, Tq) == (t_dw, t_dy, 39)
+    # the budget: rho * T_full below T_fwd is infeasible; exactly T_fwd leaves a budget of zero
+    assert sel.quantise_times(t_fwd, t_dw, t_dy, 235_294, 10)[2] == -1     # floor(19.99999) = 19 < 20
+    assert sel.quantise_times(t_fwd, t_dw, t_dy, 235_295, 10)[2] == 0      # floor(20.000075) = 20
+    assert sel.quantise_times(t_fwd, t_dw, t_dy, 235_295, 0)[2] == 0
+    # and the search uses exactly these integers: at T_q = 10 and budget 6 tensors 1 and 2 (a = 2 + 0, passing
+    # b[2] + b[3] = 2) fit together with tensor 3 (a = 1): cost 2 + 0 + 1 + 2 = 5 <= 6, while adding tensor 0 would
+    # charge b[1] = 1 and a[0] = 1 more: 7 > 6
+    imp = [1.0, 1.0, 1.0, 1.0]
+    for method in ("enumerate", "recurrence"):
+        r = sel.select(imp, t_dw, t_dy, t_fwd, 700_000, 10, method=method)
+        assert list(r["mask"]) == [0, 1, 1, 1] and r["status"] == sel.OK
+        # in nanoseconds tensor 1..3 cost 13 + 5 + 11 + 17 + 3 = 49 > 39: the unquantised search must drop some
+        r0 = sel.select(imp, t_dw, t_dy, t_fwd, 700_000, 0, method=method)
+        assert sel.t_selective(r0["mask"], 0, t_dw, t_dy) <= 39 and int(r0["mask"].sum()) == 2

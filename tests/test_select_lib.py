@@ -100,3 +100,24 @@ def test_table_sizes_match_the_cells_the_recurrence_visits(N, Tq):
         assert cnt["cells_table"] == full["cells"]
         assert cnt["cells_knapsack"] == N * (budget + 1)
         assert cnt["cells_pruned"] <= cnt["cells_knapsack"] <= cnt["cells_table"]
+
+
+def test_time_quantisation_by_hand():
+    """The library's Eq. 8 integers for the instance worked out by hand in tests/test_oracle_select.py: the
+    quantised full backward time and budget as et_select_stats reports them, and the masks that follow."""
+    t_dw, t_dy, t_fwd = [7, 13, 5, 11], [1000, 9, 17, 3], 20
+    imp = [1.0, 1.0, 1.0, 1.0]
+    st, mask, pred, counts = et.et_select_stats(imp, t_dw, t_dy, t_fwd, 700_000, 10)
+    # a = 1, 2, 0, 1 and b[1:] = 1, 2, 0: backward 7, budget floor(39 * 10 / 65) = 6
+    assert st == 0 and counts["backward_q"] == 7 and counts["budget_q"] == 6
+    assert list(mask) == [0, 1, 1, 1] and pred == 20 + 13 + 5 + 11 + 17 + 3
+    st, mask, pred, counts = et.et_select_stats(imp, t_dw, t_dy, t_fwd, 700_000, 0)
+    assert st == 0 and counts["backward_q"] == 65 and counts["budget_q"] == 39 and pred <= 20 + 39
+    st, mask, pred, counts = et.et_select_stats(imp, t_dw, t_dy, t_fwd, 700_000, 64)
+    assert counts["backward_q"] == 6 + 12 + 4 + 10 + 8 + 16 + 2 and counts["budget_q"] == 38
+    assert et.et_select(imp, t_dw, t_dy, t_fwd, 235_294, 10)[0] == 1      # ET_INFEASIBLE
+    # budget 0: at T_q = 10 tensor 2 costs a[2] + b[3] = 0 + 0 and is selected; in nanoseconds nothing is free
+    st, mask, _ = et.et_select(imp, t_dw, t_dy, t_fwd, 235_295, 10)
+    assert st == 0 and list(mask) == [0, 0, 1, 0]
+    st, mask, _ = et.et_select(imp, t_dw, t_dy, t_fwd, 235_295, 0)
+    assert st == 0 and not any(mask)
