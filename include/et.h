@@ -191,6 +191,25 @@ int et_importance_master(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, v
 #define ET_METRIC_GRAD_L1 2
 int et_tensor_metric(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, int32_t metric, double* metric_host /*[N]*/);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the reduction of et_importance on its own,
+ *   importance_dev[i] = sum_e grad_dev[i][e] * (w_snapshot_dev[i][e] - w_dev[i][e]),   i = 0 .. n-1,
+ * with the same kernels, chunking and summation order (bit-identical to et_importance on the same gradients),
+ * but with the chunk table and the partial sums in a fixed device array inside the library instead of a
+ * caller's workspace.  It allocates nothing, on the device or through the HIP runtime, copies nothing from host
+ * memory and does not wait: a few kernel launches on `hip_stream` (NULL = the default stream).
+ *   grad_dev[i]: float32 [numel[i]]; w_dev[i], w_snapshot_dev[i]: `dtype` (ET_F32 | ET_BF16) [numel[i]]; the three
+ *   arrays of pointers and numel are host arrays, read before the call returns; importance_dev: n doubles in
+ *   device memory, written on the stream.  16-byte aligned tensors take the vector path.
+ * Limits: n <= ET_STATIC_MAX_TENSORS and sum_i ceil(numel[i] / 16384) <= ET_STATIC_MAX_CHUNKS (about 1e9
+ * elements), else ET_ENOMEM and nothing is launched; the array takes 2.6 MB on every GPU the library runs on,
+ * until the process ends.  All calls on one GPU share that GPU's array, which keeps the last call's contents
+ * (no entry has to start at zero): calls that overlap on one GPU race. */
+#define ET_STATIC_MAX_TENSORS 1024
+#define ET_STATIC_MAX_CHUNKS 65536
+int et_importance_reduce_static(int32_t n, void* const* grad_dev, void* const* w_dev, void* const* w_snapshot_dev,
+                                const uint64_t* numel, int32_t dtype, void* hip_stream, double* importance_dev);
+
 /* Tensor Selector (Eq. 3 solved exactly on integers; Sections 3.3 and 6).  Pure host code,
  * no context, no device.  Maximises the summed importance of the selected tensors subject to
  *   t_fwd + sum_{i selected} t_dw[i] + sum_{i > i*} t_dy[i] <= rho * T_full,

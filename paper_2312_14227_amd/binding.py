@@ -85,7 +85,7 @@ def _load():
 
 _lib = _load()
 EXPORTS = ["et_create", "et_destroy", "et_num_tensors", "et_tensor_info", "et_workspace_bytes", "et_state_slots",
-           "et_bind", "et_profile", "et_importance", "et_importance_master", "et_select", "et_select_stats", "et_tensor_metric", "et_train_step", "et_last_launch_counts",
+           "et_bind", "et_profile", "et_importance", "et_importance_master", "et_importance_reduce_static", "et_select", "et_select_stats", "et_tensor_metric", "et_train_step", "et_last_launch_counts",
            "et_kernel_timing", "et_kernel_timing_read", "et_last_hip_error", "et_strerror", "et_debug_gemm_bf16", "et_debug_copy", "et_debug_conv3x3",
            "et_debug_conv3x3_dw", "et_debug_depthwise3x3", "et_debug_depthwise3x3_ws_floats",
            "et_debug_activation", "et_debug_conv3x3_split", "et_debug_attention"]
@@ -193,6 +193,15 @@ def et_importance_master(ctx, x_dev, y_dev, w_snapshot_f32_dev):
     _check(_lib.et_importance_master(ctx, C.c_void_p(x_dev), C.c_void_p(y_dev), _ptr_array(w_snapshot_f32_dev), out),
            "et_importance_master", ctx=ctx)
     return np.array(out[:], dtype=np.float64)
+
+
+def et_importance_reduce_static(grad_dev, w_dev, w_snapshot_dev, numel, dtype, stream, importance_dev):
+    """Enqueues the allocation-free Eq. 2 reduction; importance_dev is a device address of len(numel) doubles."""
+    n = len(numel)
+    sizes = (C.c_uint64 * max(n, 1))(*[int(v) for v in numel])
+    _check(_lib.et_importance_reduce_static(C.c_int32(n), _ptr_array(grad_dev), _ptr_array(w_dev), _ptr_array(w_snapshot_dev),
+                                            sizes, C.c_int32(dtype), C.c_void_p(stream), C.c_void_p(importance_dev)),
+           "et_importance_reduce_static")
 
 
 def et_select(importance, t_dw_ns, t_dy_ns, t_fwd_ns, rho_ppm, tq):
