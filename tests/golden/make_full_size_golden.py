@@ -6,7 +6,9 @@ Stored per tensor k: element indices idx_k (512 drawn uniformly with a fixed see
 elements of largest magnitude, where the mass of the tensor's norm lies), the oracle gradient at
 those elements g_k (all tensors selected; by the invariant of selective training these are also the values for
 any mask that selects k), the gradient's L2 norm, and Eq. 2's importance with its magnitude sum
-for the workload's snapshot.  Also the loss and the logits.
+for the workload's snapshot.  Also the loss and the logits.  For the ResNet workload, whose reference
+rounds stored tensors to bf16, also the same samples of the exact float64 gradient (gx_k) and per tensor the
+distance between two bf16-storage evaluations that differ by summation-order noise (spread).
 """
 import os
 import sys
@@ -56,12 +58,28 @@ def main():
     cfg = CONFIGS[name]
     batch = int(sys.argv[3]) if len(sys.argv) > 3 else cfg.batch
     wl = make_workload(cfg, seed=seed, batch=batch)
+    extra = {}
     if cfg.kind == "resnet":
         # a bf16 evaluation of a deep ReLU network is not a rounding of the exact gradient: the stored
         # reference rounds the tensors the bf16 data layout keeps in memory (see oracle/resnet.py)
         from oracle import resnet
         r = resnet.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights), store=resnet.round_bf16)
         I = oimp.importance_from_grads(r["grads"], wl.weights, wl.snapshot)
+        # How far apart are two correct bf16-storage evaluations of this network?  A second one whose stored values
+        # carry relative noise of 3e-7 ahead of the rounding (what a float32 sum in another order differs by from
+        # the float64 one) flips a few roundings; behind a flip everything is perturbed at the 2^-9 level, and a
+        # ReLU mask bit that changes drops or passes a whole gradient element.  Per tensor the relative L2
+        # distance between the two is stored as `spread`; the exact (unrounded) gradient is stored beside both.
+        rng = np.random.default_rng([seed, 777])
+        r2 = resnet.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights),
+                                store=lambda a: resnet.round_bf16(a * (1.0 + 3e-7 * rng.standard_normal(a.shape))))
+        extra["spread"] = np.array([np.linalg.norm((a - b).ravel()) / max(np.linalg.norm(a.ravel()), 1e-300)
+                                    for a, b in zip(r["grads"], r2["grads"])])
+        del r2
+        rx = resnet.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights))
+        extra["exact_grads"] = rx["grads"]
+        extra["exact_loss"] = np.float64(rx["loss"])
+        del rx
     elif cfg.kind == "mobilenet":
         from oracle import mobilenet, resnet
         r = mobilenet.mobilenet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights), store=resnet.round_bf16)
@@ -79,6 +97,12 @@ def main():
         idx = sample_indices(k, g, seed)
         out["idx_%d" % k] = idx.astype(np.int32)
         out["g_%d" % k] = g.ravel()[idx]
+        if "exact_grads" in extra:
+            out["gx_%d" % k] = extra["exact_grads"][k].ravel()[idx]
+    if "exact_grads" in extra:
+        out["exact_gnorm"] = np.array([np.linalg.norm(g.ravel()) for g in extra["exact_grads"]])
+        out["exact_loss"] = extra["exact_loss"]
+        out["spread"] = extra["spread"]
     tag = name if batch == cfg.batch else "%s_b%d" % (name, batch)
     path = os.path.join(ROOT, "tests", "golden", "%s_seed%d.npz" % (tag, seed))
     np.savez_compressed(path, **out)

@@ -262,3 +262,44 @@ def test_masked_update_sgd_on_a_convolutional_model():
             np.testing.assert_allclose(fp, w_ref[k], rtol=2e-6, atol=step * 2e-3 * hp["lr"], err_msg=wl.names[k])
             assert torch.equal(s.w[k].reshape(-1), s.state[k][0].to(torch.bfloat16)), wl.names[k]
     s.close()
+
+
+@pytest.mark.parametrize("name,micro", [("vit_small", 1), ("mlp", 4), ("mlp", 8)])
+def test_importance_aggregated_over_micro_batches(name, micro):
+    """Section 4: the importance may be evaluated on micro-batches and aggregated.  The loss is a mean over the
+    samples, so Eq. 2 is additive: the mean of et_importance over the micro-batches of a batch must be the oracle's
+    importance of the whole batch, at the importance tolerance, and must select the same tensors."""
+    from paper_2312_14227_amd import binding as et
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg, seed=11, init="random")
+    N, B = len(wl.weights), cfg.batch
+    assert B % micro == 0
+    I_ref, r = oimp.importance(cfg, wl.weights, wl.snapshot, wl.x, wl.y)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    t_fwd, t_dw, t_dy = s.profile(xt, yt, warmup=1, reps=3)
+    I_full = s.importance(xt, yt, s.put_snapshot(wl.snapshot))
+    sm = _session(cfg, wl, batch=micro, with_state=False)
+    snap = sm.put_snapshot(wl.snapshot)
+    agg = np.zeros(N)
+    for i in range(0, B, micro):
+        xm, ym = sm.put_input(wl.x[i:i + micro], wl.y[i:i + micro])
+        agg += sm.importance(xm, ym, snap)
+    agg /= B // micro
+    tol = tol_for(cfg)
+    worst = 0.0
+    for k in range(N):
+        gn = np.linalg.norm(r["grads"][k].ravel())
+        dwn = np.linalg.norm((wl.snapshot[k].astype(np.float64) - wl.weights[k].astype(np.float64)).ravel())
+        bound = tol * max(abs(I_ref[k]), gn * dwn)
+        worst = max(worst, abs(agg[k] - I_ref[k]) / bound)
+        assert abs(agg[k] - I_ref[k]) <= bound, (wl.names[k], agg[k], I_ref[k])
+    print("aggregated over %d micro-batches of %d: worst importance error / bound %.3f; max |agg - full| / max |I| %.2e"
+          % (B // micro, micro, worst, np.abs(agg - I_full).max() / np.abs(I_full).max()))
+    # Eq. 3 on the aggregated importances: the library and the oracle agree bit for bit on identical inputs
+    for rho in (400_000, 600_000, 800_000):
+        st, mask, pred = et.et_select(agg, t_dw, t_dy, t_fwd, rho, 10_000)
+        want = osel.select(agg, [int(t) for t in t_dw], [int(t) for t in t_dy], int(t_fwd), rho, 10_000)
+        assert st == want["status"] and list(mask) == list(want["mask"]) and pred == want["predicted_ns"]
+    sm.close()
+    s.close()

@@ -139,3 +139,30 @@ def test_one_rounding_flip_moves_the_gradient_by_per_cent():
     errs = [np.linalg.norm(a - b) / np.linalg.norm(a) for a, b in zip(ref["grads"], noisy["grads"])]
     assert 5e-3 < float(np.median(errs)) < 0.5
     assert abs(noisy["loss"] - ref["loss"]) < 2e-2 * abs(ref["loss"])
+
+
+def test_two_bf16_evaluations_of_the_full_depth_network_differ_by_per_cent():
+    """The ResNet-50 workload at its own depth and resolution (batch 2 to bound the time): two bf16-storage
+    evaluations whose stored values differ by relative noise of 3e-7 ahead of the rounding -- what a float32 sum
+    in another order differs by from the float64 one -- end up several per cent apart in the gradients of the
+    input-side tensors, and as far from each other as either is from the exact gradient.  The size of the noise
+    does not matter (1e-6 gives the same spread): one flipped rounding perturbs everything behind it at the 2^-9
+    level, which flips further roundings and ReLU mask bits.  This is why the full-size GPU test bounds a tensor by
+    the spread stored with the golden values where that exceeds the workload tolerance."""
+    cfg = CONFIGS["resnet50"]
+    wl = make_workload(cfg, seed=0, batch=2)
+    N = len(wl.weights)
+    ones = [1] * N
+    ref = R.resnet_step(cfg, wl.weights, wl.x, wl.y, ones, store=R.round_bf16)
+    spreads = []
+    for eps in (3e-7, 1e-6):
+        rng = np.random.default_rng(0)
+        noisy = R.resnet_step(cfg, wl.weights, wl.x, wl.y, ones,
+                              store=lambda a: R.round_bf16(a * (1.0 + eps * rng.standard_normal(a.shape))))
+        spreads.append(np.array([np.linalg.norm(a - b) / np.linalg.norm(a) for a, b in zip(ref["grads"], noisy["grads"])]))
+        assert abs(noisy["loss"] - ref["loss"]) < 2e-2 * abs(ref["loss"])
+    for sp in spreads:
+        assert 1e-2 < float(np.median(sp)) < 0.2
+        assert sp[wl.names.index("stem.W")] > 5e-2           # the tensor behind every ReLU of the network
+        assert sp[wl.names.index("head.W")] < 2e-3           # nothing lies between the head and the loss
+    assert 0.5 < float(np.median(spreads[0]) / np.median(spreads[1])) < 2.0
