@@ -17,13 +17,14 @@ extern "C" {
  * C is fp32 if c_f32 else bf16, leading dimension ldc.  split_k > 1 needs c_f32, ldc == N and
  * `partials` with M*N*split_k floats.  A residual needs c_f32 and a_t = b_t = 0.  tile: 0 =
  * automatic, otherwise a tile id of the library (1, 3: register-staged 128x128, 128x64; 5, 7:
- * direct-to-LDS 256x256, 256x128); adding 256 runs the main loop without storing (tuning); adding 2048 selects the GELU-forward
- * epilogue (bf16 C = gelu'(v), second bf16 output gelu(v) through `partials`), adding 4096 the GELU-backward
- * epilogue (C = v * U, U bf16 [M][ldc] through `partials`).
- * stream: hipStream_t.  Returns 0, or -1 for a rejected argument, -3 for a HIP error. */
+ * direct-to-LDS 256x256, 256x128; 11, 13, 15, 17, 19, 21: the two-group tiles 256x256, 256x192, 256x128, 512x64,
+ * 128x256, 64x512).  epilogue: 0 the plain one above; 1 GELU forward, with u = the value above: bf16 C = gelu'(u) and
+ * a second bf16 output aux [M][ldc] = gelu(u); 2 GELU backward: bf16 C = value * aux, aux bf16 [M][ldc] the stored
+ * gelu'(u) (b_t = 1 only); 3 bf16 C = gelu(u), aux unused.  stream: hipStream_t.
+ * Returns 0, or -1 for a rejected argument, -3 for a HIP error. */
 int et_debug_gemm_bf16(const void* A, const void* B, void* C, int M, int N, int K, int lda, int ldb, int ldc,
                        int a_t, int b_t, int c_f32, float alpha, const void* bias, const float* residual,
-                       int split_k, float* partials, int tile, void* stream);
+                       int split_k, float* partials, int tile, int epilogue, void* aux, void* stream);
 
 /* 3x3 / stride 1 / zero padding 1 convolution as an implicit GEMM (the im2col matrix of Section 5.1's
  * convolution kernels is never written): out[b][h][w][n] = sum over (ky, kx, c) of

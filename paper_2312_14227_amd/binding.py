@@ -75,7 +75,7 @@ def _load():
         "et_debug_conv3x3_split": (C.c_int, [vp, vp, vp, vp] + [C.c_int] * 5 + [vp, vp, vp, C.c_int, C.c_int, vp, C.c_int, vp]),
         "et_debug_conv3x3_dw": (C.c_int, [vp, vp, vp] + [C.c_int] * 6 + [vp, C.c_int, vp]),
         "et_debug_conv3x3": (C.c_int, [vp, vp, vp] + [C.c_int] * 5 + [vp, vp, C.c_int, C.c_int, vp]),
-        "et_debug_gemm_bf16": (C.c_int, [vp, vp, vp] + [C.c_int] * 9 + [C.c_float, vp, vp, C.c_int, vp, C.c_int, vp]),
+        "et_debug_gemm_bf16": (C.c_int, [vp, vp, vp] + [C.c_int] * 9 + [C.c_float, vp, vp, C.c_int, vp, C.c_int, C.c_int, vp, vp]),
     }
     for name, (res, args) in sig.items():
         f = getattr(lib, name)
@@ -278,10 +278,10 @@ def et_kernel_timing_read(ctx, kernel_class):
 
 
 def et_debug_gemm_bf16(A, B, Cp, M, N, K, lda, ldb, ldc, a_t, b_t, c_f32, alpha=1.0, bias=0, residual=0, split_k=1,
-                       partials=0, tile=0, stream=0):
+                       partials=0, tile=0, stream=0, epilogue=0, aux=0):
     return _lib.et_debug_gemm_bf16(C.c_void_p(A), C.c_void_p(B), C.c_void_p(Cp), M, N, K, lda, ldb, ldc, int(a_t),
                                    int(b_t), int(c_f32), alpha, C.c_void_p(bias), C.c_void_p(residual), split_k,
-                                   C.c_void_p(partials), tile, C.c_void_p(stream))
+                                   C.c_void_p(partials), tile, int(epilogue), C.c_void_p(aux), C.c_void_p(stream))
 
 
 def et_debug_conv3x3(x, w, out, batch, H, W, Cin, N, bias=0, U=0, mode=0, tile=0, stream=0):

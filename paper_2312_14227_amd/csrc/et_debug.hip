@@ -6,16 +6,17 @@
 
 extern "C" int et_debug_gemm_bf16(const void* A, const void* B, void* C, int M, int N, int K, int lda, int ldb, int ldc,
                                   int a_t, int b_t, int c_f32, float alpha, const void* bias, const float* residual,
-                                  int split_k, float* partials, int tile, void* stream) {
+                                  int split_k, float* partials, int tile, int epilogue, void* aux, void* stream) {
   et::GemmDesc g;
   g.A = (const et::bf16*)A; g.B = (const et::bf16*)B; g.C = C;
   g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
   g.a_t = a_t != 0; g.b_t = b_t != 0; g.c_f32 = c_f32 != 0; g.alpha = alpha;
   g.bias = (const et::bf16*)bias; g.residual = residual; g.ldr = ldc;
-  g.split_k = split_k < 1 ? 1 : split_k; g.partials = partials; g.tile = tile & 255; g.no_store = (tile >> 8) & 7;
-  const int mode = (tile >> 11) & 3;  // 1: GELU forward (partials = second output), 2: GELU backward (partials = U)
-  if (mode == 1) { g.mode = et::EPI_GELU_FWD; g.C2 = (et::bf16*)partials; g.partials = nullptr; g.split_k = 1; }
-  if (mode == 2) { g.mode = et::EPI_GELU_BWD; g.U = (const et::bf16*)partials; g.partials = nullptr; g.split_k = 1; }
+  g.split_k = split_k < 1 ? 1 : split_k; g.partials = partials; g.tile = tile;
+  if (epilogue < 0 || epilogue > 3 || (epilogue != 0 && epilogue != 3 && !aux)) return ET_EINVAL;
+  if (epilogue == 1) { g.mode = et::EPI_GELU_FWD; g.C2 = (et::bf16*)aux; }
+  if (epilogue == 2) { g.mode = et::EPI_GELU_BWD; g.U = (const et::bf16*)aux; }
+  if (epilogue == 3) g.mode = et::EPI_GELU_ONLY;
   const hipError_t e = et::gemm_bf16(g, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return ET_EINVAL;
   return e == hipSuccess ? ET_OK : ET_EHIP;

@@ -96,6 +96,20 @@ __global__ __launch_bounds__(256) void splitk_reduce_epilogue_kernel(ReduceEpi e
 enum TileId : int { T_AUTO = 0, T_128x128 = 1, T_128x64 = 3, T_DMA_256x256 = 5, T_DMA_256x128 = 7, T_PP_256x256 = 11, T_PP_256x192 = 13,
               T_PP_256x128 = 15, T_PP_512x64 = 17, T_PP_128x256 = 19, T_PP_64x512 = 21 };
 
+// number of compute units of the current device (256 on an MI355X), looked up once per device; a multiple of 8
+// (one share per XCD) as the resident kernels' unit order assumes whenever a workgroup takes a second unit
+int compute_units() {
+  static int cus[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cus[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+    cus[dev] = n & ~7;
+  }
+  return cus[dev];
+}
+
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 // Cost model behind the tile and split choice for large problems (seconds, one launch):
@@ -170,12 +184,9 @@ int choose_tile(const GemmDesc& d, int k_per_block) {
     return (long long)((d.M + 127) / 128) * ((d.N + 127) / 128) >= 256 ? T_128x128 : T_128x64;
   }
   if (d.M >= 512 && d.N >= 256) {
-    // the GELU forward epilogues (transcendental math, two outputs) take as long as a short main loop; two
-    // 256x128 workgroups per CU overlap one's epilogue with the other's MFMAs (measured in the ViT-B step: as
-    // fast as the two-group tile since the epilogue math was shortened, kept).  The backward epilogue is one
-    // multiplication with a stored operand: there the two-group tile is 4 % faster in the step.
-    if ((d.mode == EPI_GELU_FWD || d.mode == EPI_GELU_ONLY) && dma_ok && d.N >= 2560 && k_per_block >= 4 * gemm::DBK)
-      return T_DMA_256x128;
+    // (the GELU forward epilogues, 20 instructions per element, cost a 256x256 tile as much as half its main loop;
+    // two 256x128 direct-to-LDS workgroups per CU that overlap one's epilogue with the other's MFMAs run no
+    // faster than the resident two-group tile: 101.7 against 101.3 us for the ViT-B fc1 product)
     if (pp_ok && k_per_block >= 4 * gemm::PBK) return plan_large(d.M, d.N, k_per_block, false).tile;
     if (dma_ok && k_per_block >= 4 * gemm::DBK) return d.N >= 2560 ? T_DMA_256x128 : T_DMA_256x256;
   }
@@ -256,7 +267,7 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   p.sAo = d.sAo; p.sAi = d.sAi; p.sBo = d.sBo; p.sBi = d.sBi; p.sCo = d.sCo; p.sCi = d.sCi;
   p.split_k = 1; p.k_chunk = 0;
   p.alpha = d.alpha; p.bias = d.bias; p.gain = d.gain; p.gain2 = d.gain2; p.bias2 = d.bias2; p.residual = d.residual; p.ldr = d.ldr;
-  p.C = d.C; p.ldc = d.ldc; p.C2 = d.C2; p.U = d.U; p.no_store = d.no_store;
+  p.C = d.C; p.ldc = d.ldc; p.C2 = d.C2; p.U = d.U;
   p.cH = d.conv_h; p.cW = d.conv_w; p.cC = d.conv_c;
   p.act_lo = d.act_lo; p.act_hi = d.act_hi; p.mask_hi = d.mask_hi;
   int zdim = d.z_outer * d.z_inner;
@@ -311,6 +322,7 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   }
   int BM, BN;
   gemm::LaunchFn fn;
+  bool resident = true;   // the two-group kernels keep one workgroup per CU that walks over the tiles
   if (conv_dw) {
     int tile = d.tile;
     if (tile != T_PP_256x256 && tile != T_PP_256x192 && tile != T_PP_128x256 && tile != T_PP_64x512)
@@ -334,16 +346,18 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
     case T_PP_128x256: BM = 128; BN = 256; fn = gemm::pp_128x256(d.a_t, d.b_t, epi); break;
     case T_PP_512x64: BM = 512; BN = 64; fn = gemm::pp_512x64(d.a_t, d.b_t, epi); break;
     case T_PP_256x128: BM = 256; BN = 128; fn = gemm::pp_256x128(d.a_t, d.b_t, epi); break;
-    case T_128x64: BM = 128; BN = 64; fn = gemm::staged_128x64(d.a_t, d.b_t, epi); break;
-    case T_DMA_256x256: BM = 256; BN = 256; fn = gemm::dma_256x256(d.a_t, d.b_t, epi); break;
-    case T_DMA_256x128: BM = 256; BN = 128; fn = gemm::dma_256x128(d.a_t, d.b_t, epi); break;
+    case T_128x64: BM = 128; BN = 64; fn = gemm::staged_128x64(d.a_t, d.b_t, epi); resident = false; break;
+    case T_DMA_256x256: BM = 256; BN = 256; fn = gemm::dma_256x256(d.a_t, d.b_t, epi); resident = false; break;
+    case T_DMA_256x128: BM = 256; BN = 128; fn = gemm::dma_256x128(d.a_t, d.b_t, epi); resident = false; break;
     case T_PP_256x192: BM = 256; BN = 192; fn = gemm::pp_256x192(d.a_t, d.b_t, epi); break;
     case T_PP_256x256: BM = 256; BN = 256; fn = gemm::pp_256x256(d.a_t, d.b_t, epi); break;
-    default: BM = 128; BN = 128; fn = gemm::staged_128x128(d.a_t, d.b_t, epi); break;
+    default: BM = 128; BN = 128; fn = gemm::staged_128x128(d.a_t, d.b_t, epi); resident = false; break;
   }
   if (!fn) return hipErrorInvalidValue;  // this (layout, epilogue) pair is not part of the training step
   const int tiles = ((d.M + BM - 1) / BM) * ((d.N + BN - 1) / BN);
-  hipError_t e = fn(p, dim3(tiles, 1, zdim), s);
+  if ((long long)tiles * zdim >= (1ll << 23)) return hipErrorInvalidValue;   // (the resident kernels' unit arithmetic)
+  p.units = tiles * zdim;
+  hipError_t e = resident ? fn(p, dim3(std::min(p.units, compute_units()), 1, 1), s) : fn(p, dim3(tiles, 1, zdim), s);
   if (e != hipSuccess) return e;
   if (launches) *launches = 1;
   if (p.split_k > 1 && conv_split) {

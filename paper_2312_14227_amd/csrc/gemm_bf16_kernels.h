@@ -70,6 +70,7 @@ struct Params {
   int z_inner;
   long long sAo, sAi, sBo, sBi, sCo, sCi;
   int split_k, k_chunk;  // split_k > 1: chunk z of the reduction is [z*k_chunk, (z+1)*k_chunk)
+  int units;             // gemm_pp_kernel: tiles x (batch entries or reduction chunks), the work its resident workgroups loop over
   float alpha;
   const bf16* bias;
   const bf16* gain;      // E_AFFINE, E_AFFINE_ADD: per output column
@@ -84,7 +85,6 @@ struct Params {
   float act_lo, act_hi;  // E_AFFINE, E_AFFINE_ADD: the activation is a clamp to [act_lo, act_hi] (0, +inf: ReLU; 0, 6: ReLU6; -inf, +inf: none)
   float mask_hi;         // E_RELU_MASK passes where 0 < U < mask_hi
   int cH, cW, cC;        // implicit 3x3 convolution (gemm_pp_kernel<.., CONV>): input height, width, channels
-  int no_store;          // tuning aids: 1 run the main loop, store nothing; 2 also issue no loads; 4 all tiles load the same panels
 };
 
 // GELU (exact erf form) and its derivative from one exponential: with x = u / sqrt(2),
@@ -149,6 +149,40 @@ __device__ __forceinline__ void tile_coords(const Params& g, int& m0, int& n0, i
   n0 = (in / gm) * BN;
 }
 
+// The same for a resident workgroup that loops over units of work (gemm_pp_kernel): unit w = blockIdx.x + round *
+// gridDim.x runs on XCD w % 8 in every round (the grid is a multiple of 8 whenever there is a second round), and the
+// units of one XCD are consecutive (chunk or batch entry, tile) pairs in the walk above.
+// Quotient and remainder of 0 <= u < 2^23 by d >= 1 through a float reciprocal (exact after one correction step:
+// the float product is off by less than one unit).  The kernels divide by the same few divisors for every unit.
+__device__ __forceinline__ void divmod_small(int u, int d, float rcp_d, int& q, int& r) {
+  q = (int)((float)u * rcp_d);
+  r = u - q * d;
+  if (r < 0) { q--; r += d; }
+  if (r >= d) { q++; r -= d; }
+}
+
+template <int BM, int BN>
+__device__ __forceinline__ void unit_coords(const Params& g, int w, int& m0, int& n0, int& z) {
+  const int tiles_n = (g.N + BN - 1) / BN;
+  const int tiles_m = (g.M + BM - 1) / BM;
+  const int nt = tiles_m * tiles_n;
+  const int xcd = w % NUM_XCD, idx = w / NUM_XCD;
+  const int per = g.units / NUM_XCD, rem = g.units % NUM_XCD;
+  const int u = xcd * per + (xcd < rem ? xcd : rem) + idx;
+  int t;
+  divmod_small(u, nt, 1.0f / (float)nt, z, t);
+  constexpr int GROUP = 8;
+  const int gsz = GROUP * tiles_n;
+  int grp, in;
+  divmod_small(t, gsz, 1.0f / (float)gsz, grp, in);
+  const int first = grp * GROUP;
+  const int gm = min(tiles_m - first, GROUP);
+  int qn, rm;
+  divmod_small(in, gm, 1.0f / (float)gm, qn, rm);   // gm <= 8
+  m0 = (first + rm) * BM;
+  n0 = qn * BN;
+}
+
 // batch / split-K bookkeeping
 __device__ __forceinline__ void batch_offsets(const Params& g, int z, const bf16*& A, const bf16*& B, long long& c_off,
                                               int& k_begin, int& k_end) {
@@ -169,179 +203,293 @@ __device__ __forceinline__ void batch_offsets(const Params& g, int z, const bf16
 }
 
 // -------------------------------------------------------------------------------------------------
-// Epilogue of one wave.  acc[mi][ni][r] holds element (mi*32 + (r/4)*8 + (lane/32)*4 + r%4,
-// ni*32 + lane%32) of the wave's TM x TN sub-tile whose top-left corner is (row0, col0).
-// `stage` is this wave's private LDS area of 32 * TN floats.
+// Epilogue of one wave.  The kernels multiply with the operands exchanged (MFMA of the B fragment by the A
+// fragment), so a lane owns ROWS: acc[mi][ni][r] holds element
+//   (mi*32 + lane%32,  ni*32 + (r/4)*8 + (lane/32)*4 + r%4)
+// of the wave's TM x TN sub-tile whose top-left corner is (row0, col0): four consecutive columns per register
+// quadruple.  The sub-tile goes through the wave's private LDS area 32 rows at a time and comes back with
+// consecutive lanes on consecutive columns of a row, so that global stores (and the row-major second operands)
+// are whole 128-byte lines:
+//   - bf16 outputs that need only per-column parameters (bias, folded-BN gain and shift) are finished in the
+//     registers (bias, GELU, affine + clamp), packed to bf16 and staged with 8-byte LDS writes, read back and
+//     stored 16 bytes per lane (two staged outputs for GELU forward and the affine pair);
+//   - everything else (fp32 outputs, residual, a second operand U) is staged as fp32 with 16-byte LDS writes and
+//     finished after the read-back, 4 columns per lane.
+// Row pitches are padded (8 bytes for bf16 rows, 16 for fp32 rows) so that the 32 rows written by one
+// instruction fall into distinct banks.  `mid(mi)` is called before every 32-row block but the first: the
+// accumulators of the blocks before it have been stored and their registers are free (a resident kernel
+// requests the first slices of its next tile there).
 // -------------------------------------------------------------------------------------------------
-template <int EPI, int MI, int NI>
-__device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI][NI], float* stage, int row0, int col0,
-                                              long long c_off, int lane) {
+struct NoMid {
+  __device__ __forceinline__ void operator()(int) const {}
+};
+template <int TN>
+constexpr int epi_wave_bytes() { return 32 * (TN + 4) * 4; }   // fp32 rows of TN + 4; two bf16 areas of rows of 2 TN + 8 bytes
+
+template <int EPI>
+constexpr bool epi_pre() {
+  return EPI == E_BF16 || EPI == E_GELU_FWD || EPI == E_GELU_ONLY || EPI == E_BIAS_RELU || EPI == E_AFFINE;
+}
+
+// FULL: the wave's whole sub-tile lies inside the matrix and every store address is 16-byte aligned: no per-lane
+// bounds checks, no ragged paths (all but the last row and column of tiles take this variant).
+template <int EPI, int MI, int NI, bool FULL, typename Mid>
+__device__ __forceinline__ void wave_epilogue_impl(const Params& g, f32x16 (&acc)[MI][NI], unsigned char* stage, int row0, int col0,
+                                                   long long c_off, int lane, Mid&& mid) {
   constexpr int TN = NI * 32;
-  constexpr int CPL = TN / 4;    // lanes per row when reading back 4 columns each
-  constexpr int RPI = 64 / CPL;  // rows covered by one wave-wide read
   const int l32 = lane & 31, khalf = lane >> 5;
-  const int c4 = (lane % CPL) * 4, rsub = lane / CPL;
-  const int col = col0 + c4;
-  // (when 64 is not a multiple of CPL the last lanes of the wave have no row of their own)
-  const bool col_any = col < g.N && rsub < RPI, col_full = col + 3 < g.N;
   const int ld = EPI == E_PARTIAL ? g.N : g.ldc;
-  float bias[4] = {0.f, 0.f, 0.f, 0.f};
-  float gain[4] = {1.f, 1.f, 1.f, 1.f};
-  float gain2[4] = {1.f, 1.f, 1.f, 1.f}, bias2[4] = {0.f, 0.f, 0.f, 0.f};
-  if ((EPI == E_AFFINE || EPI == E_AFFINE_ADD) && col_any) {
-    for (int j = 0; j < 4 && col + j < g.N; j++) gain[j] = (float)g.gain[col + j];
-    if (EPI == E_AFFINE_ADD && g.gain2)
-      for (int j = 0; j < 4 && col + j < g.N; j++) {
-        gain2[j] = (float)g.gain2[col + j];
-        bias2[j] = (float)g.bias2[col + j];
-      }
-  }
-  if (EPI != E_PARTIAL && EPI != E_GELU_BWD && EPI != E_RELU_MASK && g.bias && col_any) {
-    if (col_full) {
-      const bf16x4 b = *(const bf16x4*)(g.bias + col);
-#pragma unroll
-      for (int j = 0; j < 4; j++) bias[j] = (float)b[j];
-    } else {
-      for (int j = 0; j < 4 && col + j < g.N; j++) bias[j] = (float)g.bias[col + j];
-    }
-  }
-  constexpr bool HAS_RES = EPI == E_F32_RES;
-  constexpr bool HAS_U = EPI == E_GELU_BWD || EPI == E_AFFINE_ADD || EPI == E_RELU_MASK;
-#pragma unroll
-  for (int mi = 0; mi < MI; mi++) {
-    // the second operands of this 32-row block are requested before the accumulators go through
-    // LDS, all at once: one memory latency per block instead of one per row group
-    float4 pre_res[HAS_RES ? 32 / RPI : 1];
-    bf16x4 pre_u[HAS_U ? 32 / RPI : 1];
-    if (HAS_RES || HAS_U) {
-#pragma unroll
-      for (int it = 0; it < 32 / RPI; it++) {
-        const int row = row0 + mi * 32 + min(it * RPI + rsub, 31);
-        if (row < g.M && col_any && col_full) {
-          if (HAS_RES) pre_res[it] = *(const float4*)(g.residual + (long long)row * g.ldr + col);
-          if (HAS_U) pre_u[it] = *(const bf16x4*)(g.U + c_off + (long long)row * ld + col);
-        }
-      }
-    }
+  if constexpr (epi_pre<EPI>()) {
+    constexpr bool TWO = EPI == E_GELU_FWD || EPI == E_AFFINE;
+    constexpr int PITCH = TN * 2 + 8;                 // bytes per staged bf16 row
+    constexpr int AREA = 32 * PITCH;
+    static_assert(2 * AREA <= epi_wave_bytes<TN>(), "staging area");
+    constexpr int V = (64 % (TN / 8) == 0) ? 8 : 4;   // columns per lane when reading back (16 or 8 bytes)
+    constexpr int CPL = TN / V;                       // lanes per row
+    constexpr int RPI = 64 / CPL;                     // rows covered by one wave-wide read
+    constexpr int ITERS = (32 + RPI - 1) / RPI;
+    typedef bf16 bf16xv __attribute__((ext_vector_type(V)));
+    // per-column parameters of this lane's column quadruples
+    bf16x4 bias_q[NI][4], gain_q[EPI == E_AFFINE ? NI : 1][4];
+    const bool has_bias = g.bias != nullptr;
 #pragma unroll
     for (int ni = 0; ni < NI; ni++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) stage[((r >> 2) * 8 + khalf * 4 + (r & 3)) * TN + ni * 32 + l32] = acc[mi][ni][r];
-    // the same wave reads back: LDS operations of one wave complete in order
+      for (int q = 0; q < 4; q++) {
+        const int col = col0 + ni * 32 + q * 8 + khalf * 4;
+        bf16x4 b, gn;
 #pragma unroll
-    for (int it = 0; it < 32 / RPI; it++) {
-      const int rr = min(it * RPI + rsub, 31);
-      const float4 raw = *(const float4*)(stage + rr * TN + c4);
-      const int row = row0 + mi * 32 + rr;
-      if (row >= g.M || !col_any) continue;
-      float v[4] = {raw.x, raw.y, raw.z, raw.w};
-      const long long ci = c_off + (long long)row * ld + col;
-      if (EPI == E_AFFINE || EPI == E_AFFINE_ADD) {
-#pragma unroll
-        for (int j = 0; j < 4; j++) v[j] *= g.alpha;
-      } else if (EPI != E_PARTIAL) {
-#pragma unroll
-        for (int j = 0; j < 4; j++) v[j] = v[j] * g.alpha + bias[j];
-      }
-      if (col_full) {
-        if (EPI == E_F32_RES) {
-          const float4 rs = pre_res[HAS_RES ? it : 0];
-          v[0] += rs.x; v[1] += rs.y; v[2] += rs.z; v[3] += rs.w;
-        }
-        if (EPI == E_GELU_BWD) {
-          const bf16x4 u = pre_u[HAS_U ? it : 0];
-#pragma unroll
-          for (int j = 0; j < 4; j++) v[j] *= (float)u[j];
-        }
-        if (EPI == E_RELU_MASK) {
-          const bf16x4 u = pre_u[HAS_U ? it : 0];
-#pragma unroll
-          for (int j = 0; j < 4; j++) v[j] = ((float)u[j] > 0.f && (float)u[j] < g.mask_hi) ? v[j] : 0.f;
-        }
-        if (EPI == E_F32 || EPI == E_F32_RES || EPI == E_PARTIAL) {
-          *(float4*)((float*)g.C + ci) = make_float4(v[0], v[1], v[2], v[3]);
-        } else if (EPI == E_GELU_FWD) {
-          bf16x4 o, o2;
-#pragma unroll
-          for (int j = 0; j < 4; j++) {
-            float gv, dgv;
-            gelu_both(v[j], gv, dgv);
-            o[j] = (bf16)dgv;
-            o2[j] = (bf16)gv;
-          }
-          *(bf16x4*)((bf16*)g.C + ci) = o;
-          *(bf16x4*)(g.C2 + ci) = o2;
-        } else if (EPI == E_GELU_ONLY) {
-          bf16x4 o;
-#pragma unroll
-          for (int j = 0; j < 4; j++) o[j] = (bf16)gelu_only(v[j]);
-          *(bf16x4*)((bf16*)g.C + ci) = o;
-        } else if (EPI == E_BIAS_RELU) {
-          bf16x4 o;
-#pragma unroll
-          for (int j = 0; j < 4; j++) o[j] = (bf16)fmaxf(v[j], 0.f);
-          *(bf16x4*)((bf16*)g.C + ci) = o;
-        } else if (EPI == E_AFFINE) {
-          bf16x4 o, o2;
-#pragma unroll
-          for (int j = 0; j < 4; j++) {
-            o[j] = (bf16)v[j];
-            o2[j] = (bf16)fminf(fmaxf((float)o[j] * gain[j] + bias[j], g.act_lo), g.act_hi);
-          }
-          if (g.C) *(bf16x4*)((bf16*)g.C + ci) = o;   // z is kept only if the gain's gradient will be computed
-          *(bf16x4*)(g.C2 + ci) = o2;
-        } else if (EPI == E_AFFINE_ADD) {
-          const bf16x4 u = pre_u[HAS_U ? it : 0];
-          bf16x4 o, o2;
-#pragma unroll
-          for (int j = 0; j < 4; j++) {
-            o[j] = (bf16)v[j];
-            o2[j] = (bf16)fminf(fmaxf(((float)o[j] * gain[j] + bias[j]) + ((float)u[j] * gain2[j] + bias2[j]), g.act_lo), g.act_hi);
-          }
-          if (g.C) *(bf16x4*)((bf16*)g.C + ci) = o;
-          *(bf16x4*)(g.C2 + ci) = o2;
+        for (int j = 0; j < 4; j++) { b[j] = (bf16)0.f; gn[j] = (bf16)1.f; }
+        if (FULL || col + 3 < g.N) {
+          if (has_bias) b = *(const bf16x4*)(g.bias + col);
+          if (EPI == E_AFFINE) gn = *(const bf16x4*)(g.gain + col);
         } else {
-          bf16x4 o;
+          for (int j = 0; j < 4 && col + j < g.N; j++) {
+            if (has_bias) b[j] = g.bias[col + j];
+            if (EPI == E_AFFINE) gn[j] = g.gain[col + j];
+          }
+        }
+        bias_q[ni][q] = b;
+        if (EPI == E_AFFINE) gain_q[ni][q] = gn;
+      }
+    // read-back coordinates: V columns of one row per lane
+    const int cv = (lane % CPL) * V, rsub = lane / CPL;
+    const int colr = col0 + cv;
+    const bool lane_on = rsub < RPI && (FULL || colr < g.N);
+    const bool wide = FULL || (colr + V - 1 < g.N && (ld & 7) == 0 && (c_off & 7) == 0 && ((uintptr_t)g.C & 15) == 0 &&
+                               (!TWO || ((uintptr_t)g.C2 & 15) == 0));
+    const bool keep_c = !(EPI == E_AFFINE) || g.C != nullptr;    // z is kept only if the gain's gradient will be computed
+    long long ci = c_off + (long long)(row0 + rsub) * ld + colr;  // element index of this lane's piece, first row group
+    const long long ci_step = (long long)RPI * ld;
 #pragma unroll
-          for (int j = 0; j < 4; j++) o[j] = (bf16)v[j];
-          *(bf16x4*)((bf16*)g.C + ci) = o;
+    for (int mi = 0; mi < MI; mi++) {
+      if (mi > 0) mid(mi);
+#pragma unroll
+      for (int ni = 0; ni < NI; ni++)
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+          bf16x4 o, o2;
+#pragma unroll
+          for (int j = 0; j < 4; j++) {
+            const float a = acc[mi][ni][q * 4 + j];
+            if (EPI == E_AFFINE) {
+              o[j] = (bf16)(a * g.alpha);
+              o2[j] = (bf16)fminf(fmaxf((float)o[j] * (float)gain_q[EPI == E_AFFINE ? ni : 0][q][j] + (float)bias_q[ni][q][j], g.act_lo), g.act_hi);
+            } else {
+              const float v = a * g.alpha + (float)bias_q[ni][q][j];
+              if (EPI == E_GELU_FWD) {
+                float gv, dgv;
+                gelu_both(v, gv, dgv);
+                o[j] = (bf16)dgv;
+                o2[j] = (bf16)gv;
+              } else if (EPI == E_GELU_ONLY) {
+                o[j] = (bf16)gelu_only(v);
+              } else if (EPI == E_BIAS_RELU) {
+                o[j] = (bf16)fmaxf(v, 0.f);
+              } else {
+                o[j] = (bf16)v;
+              }
+            }
+          }
+          unsigned char* p = stage + l32 * PITCH + (ni * 32 + q * 8 + khalf * 4) * 2;
+          *(bf16x4*)p = o;
+          if (TWO) *(bf16x4*)(p + AREA) = o2;
         }
-      } else {  // ragged right edge: element by element
-        for (int j = 0; j < 4 && col + j < g.N; j++) {
-          float x = v[j];
-          if (EPI == E_GELU_ONLY) {
-            ((bf16*)g.C)[ci + j] = (bf16)gelu_only(x);
-            continue;
-          }
-          if (EPI == E_BIAS_RELU) {
-            ((bf16*)g.C)[ci + j] = (bf16)fmaxf(x, 0.f);
-            continue;
-          }
-          if (EPI == E_F32_RES) x += g.residual[(long long)row * g.ldr + col + j];
-          if (EPI == E_GELU_BWD) x *= (float)g.U[ci + j];
-          if (EPI == E_RELU_MASK) x = ((float)g.U[ci + j] > 0.f && (float)g.U[ci + j] < g.mask_hi) ? x : 0.f;
-          if (EPI == E_F32 || EPI == E_F32_RES || EPI == E_PARTIAL) {
-            ((float*)g.C)[ci + j] = x;
-          } else if (EPI == E_GELU_FWD) {
-            float gv, dgv;
-            gelu_both(x, gv, dgv);
-            ((bf16*)g.C)[ci + j] = (bf16)dgv;
-            g.C2[ci + j] = (bf16)gv;
-          } else if (EPI == E_AFFINE) {
-            const bf16 z = (bf16)x;
-            if (g.C) ((bf16*)g.C)[ci + j] = z;
-            g.C2[ci + j] = (bf16)fminf(fmaxf((float)z * gain[j] + bias[j], g.act_lo), g.act_hi);
-          } else if (EPI == E_AFFINE_ADD) {
-            const bf16 z = (bf16)x;
-            if (g.C) ((bf16*)g.C)[ci + j] = z;
-            g.C2[ci + j] = (bf16)fminf(fmaxf(((float)z * gain[j] + bias[j]) + ((float)g.U[ci + j] * gain2[j] + bias2[j]), g.act_lo), g.act_hi);
+      // the same wave reads back: LDS operations of one wave complete in order
+      bf16xv rd[ITERS], rd2[TWO ? ITERS : 1];
+#pragma unroll
+      for (int it = 0; it < ITERS; it++) {
+        const unsigned char* p = stage + min(it * RPI + rsub, 31) * PITCH + cv * 2;
+        rd[it] = *(const bf16xv*)p;
+        if (TWO) rd2[TWO ? it : 0] = *(const bf16xv*)(p + AREA);
+      }
+      if (lane_on) {
+#pragma unroll
+        for (int it = 0; it < ITERS; it++, ci += ci_step) {
+          const int rr = it * RPI + rsub;
+          if ((32 % RPI != 0 && rr >= 32) || (!FULL && row0 + mi * 32 + rr >= g.M)) continue;
+          if (wide) {
+            if (keep_c) *(bf16xv*)((bf16*)g.C + ci) = rd[it];
+            if (TWO) *(bf16xv*)(g.C2 + ci) = rd2[TWO ? it : 0];
           } else {
-            ((bf16*)g.C)[ci + j] = (bf16)x;
+            for (int j = 0; j < V && colr + j < g.N; j++) {
+              if (keep_c) ((bf16*)g.C)[ci + j] = rd[it][j];
+              if (TWO) g.C2[ci + j] = rd2[TWO ? it : 0][j];
+            }
           }
         }
+        ci += (32 - ITERS * RPI) * (long long)ld;   // (zero when RPI divides 32)
       }
     }
+  } else {
+    constexpr int PITCH = TN + 4;    // floats per staged row
+    float* stf = (float*)stage;
+    constexpr int CPL = TN / 4;      // lanes per row when reading back 4 columns each
+    constexpr int RPI = 64 / CPL;    // rows covered by one wave-wide read
+    constexpr int ITERS = (32 + RPI - 1) / RPI;
+    const int c4 = (lane % CPL) * 4, rsub = lane / CPL;
+    const int col = col0 + c4;
+    // (when 64 is not a multiple of CPL the last lanes of the wave have no row of their own)
+    const bool col_any = (FULL || col < g.N) && rsub < RPI, col_full = FULL || col + 3 < g.N;
+    float bias[4] = {0.f, 0.f, 0.f, 0.f};
+    float gain[4] = {1.f, 1.f, 1.f, 1.f};
+    float gain2[4] = {1.f, 1.f, 1.f, 1.f}, bias2[4] = {0.f, 0.f, 0.f, 0.f};
+    if (EPI == E_AFFINE_ADD && col_any) {
+      for (int j = 0; j < 4 && col + j < g.N; j++) gain[j] = (float)g.gain[col + j];
+      if (g.gain2)
+        for (int j = 0; j < 4 && col + j < g.N; j++) {
+          gain2[j] = (float)g.gain2[col + j];
+          bias2[j] = (float)g.bias2[col + j];
+        }
+    }
+    if (EPI != E_PARTIAL && EPI != E_GELU_BWD && EPI != E_RELU_MASK && g.bias && col_any) {
+      if (col_full) {
+        const bf16x4 b = *(const bf16x4*)(g.bias + col);
+#pragma unroll
+        for (int j = 0; j < 4; j++) bias[j] = (float)b[j];
+      } else {
+        for (int j = 0; j < 4 && col + j < g.N; j++) bias[j] = (float)g.bias[col + j];
+      }
+    }
+    constexpr bool HAS_RES = EPI == E_F32_RES;
+    constexpr bool HAS_U = EPI == E_GELU_BWD || EPI == E_AFFINE_ADD || EPI == E_RELU_MASK;
+    long long ci0 = c_off + (long long)(row0 + rsub) * ld + col;               // this lane's piece, first row group
+    long long ri0 = HAS_RES ? (long long)(row0 + rsub) * g.ldr + col : 0;      // the same in the residual
+    const long long ci_step = (long long)RPI * ld, ri_step = HAS_RES ? (long long)RPI * g.ldr : 0;
+#pragma unroll
+    for (int mi = 0; mi < MI; mi++) {
+      if (mi > 0) mid(mi);
+      // the second operands of this 32-row block are requested before the accumulators go through
+      // LDS, all at once: one memory latency per block instead of one per row group
+      float4 pre_res[HAS_RES ? ITERS : 1];
+      bf16x4 pre_u[HAS_U ? ITERS : 1];
+      if ((HAS_RES || HAS_U) && col_any && col_full) {
+        long long ci = ci0, ri = ri0;
+#pragma unroll
+        for (int it = 0; it < ITERS; it++, ci += ci_step, ri += ri_step) {
+          const int rr = it * RPI + rsub;
+          if ((32 % RPI != 0 && rr >= 32) || (!FULL && row0 + mi * 32 + rr >= g.M)) continue;
+          if (HAS_RES) pre_res[HAS_RES ? it : 0] = *(const float4*)(g.residual + ri);
+          if (HAS_U) pre_u[HAS_U ? it : 0] = *(const bf16x4*)(g.U + ci);
+        }
+      }
+#pragma unroll
+      for (int ni = 0; ni < NI; ni++)
+#pragma unroll
+        for (int q = 0; q < 4; q++)
+          *(float4*)(stf + l32 * PITCH + ni * 32 + q * 8 + khalf * 4) =
+              make_float4(acc[mi][ni][q * 4], acc[mi][ni][q * 4 + 1], acc[mi][ni][q * 4 + 2], acc[mi][ni][q * 4 + 3]);
+      // the same wave reads back: LDS operations of one wave complete in order
+      float4 rd[ITERS];
+#pragma unroll
+      for (int it = 0; it < ITERS; it++) rd[it] = *(const float4*)(stf + min(it * RPI + rsub, 31) * PITCH + c4);
+      if (col_any) {
+        long long ci = ci0;
+#pragma unroll
+        for (int it = 0; it < ITERS; it++, ci += ci_step) {
+          const int rr = it * RPI + rsub;
+          if ((32 % RPI != 0 && rr >= 32) || (!FULL && row0 + mi * 32 + rr >= g.M)) continue;
+          const float4 raw = rd[it];
+          float v[4] = {raw.x, raw.y, raw.z, raw.w};
+          if (EPI == E_AFFINE_ADD) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) v[j] *= g.alpha;
+          } else if (EPI != E_PARTIAL) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) v[j] = v[j] * g.alpha + bias[j];
+          }
+          if (col_full) {
+            if (EPI == E_F32_RES) {
+              const float4 rs = pre_res[HAS_RES ? it : 0];
+              v[0] += rs.x; v[1] += rs.y; v[2] += rs.z; v[3] += rs.w;
+            }
+            if (EPI == E_GELU_BWD) {
+              const bf16x4 u = pre_u[HAS_U ? it : 0];
+#pragma unroll
+              for (int j = 0; j < 4; j++) v[j] *= (float)u[j];
+            }
+            if (EPI == E_RELU_MASK) {
+              const bf16x4 u = pre_u[HAS_U ? it : 0];
+#pragma unroll
+              for (int j = 0; j < 4; j++) v[j] = ((float)u[j] > 0.f && (float)u[j] < g.mask_hi) ? v[j] : 0.f;
+            }
+            if (EPI == E_F32 || EPI == E_F32_RES || EPI == E_PARTIAL) {
+              *(float4*)((float*)g.C + ci) = make_float4(v[0], v[1], v[2], v[3]);
+            } else if (EPI == E_AFFINE_ADD) {
+              const bf16x4 u = pre_u[HAS_U ? it : 0];
+              bf16x4 o, o2;
+#pragma unroll
+              for (int j = 0; j < 4; j++) {
+                o[j] = (bf16)v[j];
+                o2[j] = (bf16)fminf(fmaxf(((float)o[j] * gain[j] + bias[j]) + ((float)u[j] * gain2[j] + bias2[j]), g.act_lo), g.act_hi);
+              }
+              if (g.C) *(bf16x4*)((bf16*)g.C + ci) = o;
+              *(bf16x4*)(g.C2 + ci) = o2;
+            } else {
+              bf16x4 o;
+#pragma unroll
+              for (int j = 0; j < 4; j++) o[j] = (bf16)v[j];
+              *(bf16x4*)((bf16*)g.C + ci) = o;
+            }
+          } else {  // ragged right edge: element by element
+            const long long ri = (long long)(row0 + mi * 32 + rr) * g.ldr + col;
+            for (int j = 0; j < 4 && col + j < g.N; j++) {
+              float x = v[j];
+              if (EPI == E_F32_RES) x += g.residual[ri + j];
+              if (EPI == E_GELU_BWD) x *= (float)g.U[ci + j];
+              if (EPI == E_RELU_MASK) x = ((float)g.U[ci + j] > 0.f && (float)g.U[ci + j] < g.mask_hi) ? x : 0.f;
+              if (EPI == E_F32 || EPI == E_F32_RES || EPI == E_PARTIAL) {
+                ((float*)g.C)[ci + j] = x;
+              } else if (EPI == E_AFFINE_ADD) {
+                const bf16 z = (bf16)x;
+                if (g.C) ((bf16*)g.C)[ci + j] = z;
+                g.C2[ci + j] = (bf16)fminf(fmaxf(((float)z * gain[j] + bias[j]) + ((float)g.U[ci + j] * gain2[j] + bias2[j]), g.act_lo), g.act_hi);
+              } else {
+                ((bf16*)g.C)[ci + j] = (bf16)x;
+              }
+            }
+          }
+        }
+      }
+      ci0 += 32 * (long long)ld;
+      ri0 += HAS_RES ? 32 * (long long)g.ldr : 0;
+    }
   }
+}
+
+template <int EPI, int MI, int NI, typename Mid = NoMid>
+__device__ __forceinline__ void wave_epilogue(const Params& g, f32x16 (&acc)[MI][NI], unsigned char* stage, int row0, int col0,
+                                              long long c_off, int lane, Mid&& mid = NoMid()) {
+  constexpr int TN = NI * 32;
+  const int ld = EPI == E_PARTIAL ? g.N : g.ldc;
+  // uniform over the wave: the whole sub-tile inside the matrix, every vector access aligned
+  bool full = row0 + MI * 32 <= g.M && col0 + TN <= g.N;
+  if (epi_pre<EPI>())
+    full = full && (ld & 7) == 0 && (c_off & 7) == 0 && ((uintptr_t)g.C & 15) == 0 && ((uintptr_t)g.C2 & 15) == 0;
+  if (full)
+    wave_epilogue_impl<EPI, MI, NI, true>(g, acc, stage, row0, col0, c_off, lane, mid);
+  else
+    wave_epilogue_impl<EPI, MI, NI, false>(g, acc, stage, row0, col0, c_off, lane, mid);
 }
 
 // =================================================================================================
@@ -365,7 +513,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_staged_kernel(Params g) {
   typedef StagedLds<BM, AT> LA;
   typedef StagedLds<BN, BT> LB;
   constexpr int STAGE = LA::BYTES + LB::BYTES;
-  constexpr int EPI_BYTES = WGM * WGN * 32 * TN * 4;
+  constexpr int EPI_BYTES = WGM * WGN * epi_wave_bytes<TN>();
   constexpr int SMEM = 2 * STAGE > EPI_BYTES ? 2 * STAGE : EPI_BYTES;
   __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
 
@@ -515,7 +663,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_staged_kernel(Params g) {
       for (int mi = 0; mi < MI; mi++)
 #pragma unroll
         for (int ni = 0; ni < NI; ni++)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ni], af[mi], acc[mi][ni], 0, 0, 0);
     }
   };
 
@@ -530,8 +678,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_staged_kernel(Params g) {
       __syncthreads();
     }
   }
-  if (g.no_store) return;
-  wave_epilogue<EPI, MI, NI>(g, acc, (float*)smem + wave * 32 * TN, m0 + wave_m * TM, n0 + wave_n * TN, c_off, lane);
+  wave_epilogue<EPI, MI, NI>(g, acc, smem + wave * epi_wave_bytes<TN>(), m0 + wave_m * TM, n0 + wave_n * TN, c_off, lane);
 }
 
 // =================================================================================================
@@ -572,14 +719,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(Params g) {
   constexpr int LOADS = A_LOADS + B_LOADS;
   static_assert(A_LOADS * 16 * NW == BM && B_LOADS * 16 * NW == BN, "tile/waves mismatch");
   static_assert(RING >= 3 && RING * STAGE <= 160 * 1024, "LDS ring too large");
-  static_assert(NW * 32 * TN * 4 <= RING * STAGE, "epilogue staging does not fit");
+  static_assert(NW * epi_wave_bytes<TN>() <= RING * STAGE, "epilogue staging does not fit");
   __shared__ __attribute__((aligned(1024))) unsigned char smem[RING * STAGE];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave / WGN, wave_n = wave % WGN;
   int m0, n0, z;
   tile_coords<BM, BN>(g, m0, n0, z);
-  if (g.no_store & 4) { m0 = 0; n0 = 0; }
   const bf16* A;
   const bf16* B;
   long long c_off;
@@ -627,7 +773,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(Params g) {
   const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) unsigned char*)smem;
 
   auto issue = [&](int stage) {
-    if (g.no_store & 2) return;
     const unsigned sa = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + wave * A_LOADS * 1024);
     const unsigned sb = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + A_BYTES + wave * B_LOADS * 1024);
 #pragma unroll
@@ -700,7 +845,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(Params g) {
     for (int mi = 0; mi < MI; mi++)
 #pragma unroll
       for (int ni = 0; ni < NI; ni++)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ni], af[mi], acc[mi][ni], 0, 0, 0);
   };
   // wait until slice `s` has landed: slices s+1 .. min(s + RING - 3, nk - 1) may stay in flight
   auto wait_slice = [&](int sl) {
@@ -730,9 +875,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(Params g) {
     if (kt + 1 < nk) load_frags(smem + ((kt + 1) % RING) * STAGE, 0, a0, b0);
     mma(a1, b1);
   }
-  if (g.no_store & 7) return;
   __syncthreads();  // every wave is done with the stages before they are reused for the epilogue
-  wave_epilogue<EPI, MI, NI>(g, acc, (float*)smem + wave * 32 * TN, m0 + wave_m * TM, n0 + wave_n * TN, c_off, lane);
+  wave_epilogue<EPI, MI, NI>(g, acc, smem + wave * epi_wave_bytes<TN>(), m0 + wave_m * TM, n0 + wave_n * TN, c_off, lane);
 }
 
 // =================================================================================================
@@ -783,99 +927,128 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   // elements (192) keep the shift of 1, their rows being offset by half a bank span anyway.
   constexpr int TSH_A = (BM % 128 == 0) ? 2 : 1, TSH_B = (BN % 128 == 0) ? 2 : 1;
   static_assert(A_LOADS * 1024 * NW == A_BYTES && B_LOADS * 1024 * NW == B_BYTES, "tile/waves mismatch");
-  constexpr int EPI_BYTES = NW * 32 * TN * 4;
+  constexpr int EPI_BYTES = NW * epi_wave_bytes<TN>();
   constexpr int SMEM = 2 * STAGE > EPI_BYTES ? 2 * STAGE : EPI_BYTES;
   static_assert(SMEM <= 160 * 1024, "LDS");
   __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave / WGN, wave_n = wave % WGN;
+  static_assert(CONV != 1 || (!AT && !BT), "implicit convolution, forward: row-major operands");
+  static_assert(CONV != 2 || (AT && BT), "implicit convolution, weight gradient: both operands reduce over rows");
+
+  // ---- state of the unit of work (tile, and batch entry or reduction chunk) being computed
   int m0, n0, z;
-  tile_coords<BM, BN>(g, m0, n0, z);
-  if (g.no_store & 4) { m0 = 0; n0 = 0; }
   const bf16* A;
   const bf16* B;
   long long c_off;
-  int k_begin, k_end;
-  batch_offsets(g, z, A, B, c_off, k_begin, k_end);
-  const int nk = (k_end - k_begin) / PBK;
-
-  // per-lane global source and LDS destination (within a stage) of each of this wave's pieces
+  int k_begin, k_end, nk;
+  // per-lane global source of each of this wave's pieces; CONV 1: output pixel (h, w) of each piece's row;
+  // CONV 2: per piece, (dy + 1) << 26 | (dx + 1) << 24 | h << 12 | w for its tap and the pixel (h, w) of its k-row
+  // (cH, cW < 4096), and the tap's element offset
   const bf16* ga[A_LOADS];
   const bf16* gb[B_LOADS];
+  int coh[CONV == 1 ? A_LOADS : 1], cow[CONV == 1 ? A_LOADS : 1];
+  int bpix[CONV == 2 ? B_LOADS : 1], boff[CONV == 2 ? B_LOADS : 1];
+  // CONV 1: tap (dy, dx) and channel offset of the next slice to load (uniform), the element offset of that
+  // slice from the centre tap (a split reduction starts at column k_begin = (tap, channel offset) of the matrix)
+  int c_dy = -1, c_dx = -1, c_sub = 0;
+  long long c_off_a = 0;
+
+  // LDS destination (within a stage) of each piece: the same for every unit
   int la[A_LOADS], lb[B_LOADS];
-  static_assert(CONV != 1 || (!AT && !BT), "implicit convolution, forward: row-major operands");
-  static_assert(CONV != 2 || (AT && BT), "implicit convolution, weight gradient: both operands reduce over rows");
-  int coh[CONV == 1 ? A_LOADS : 1], cow[CONV == 1 ? A_LOADS : 1];   // CONV 1: output pixel (h, w) of each piece's row
 #pragma unroll
   for (int i = 0; i < A_LOADS; i++) {
     const int q = wave * A_LOADS + i;
-    if (CONV == 1) {  // centre tap of the row's pixel
+    if (CONV == 1 || !AT) {  // 8 rows x 128 B; 16-byte chunk c of row r sits at chunk position c ^ ((r >> 1) & 7)
       const int row = q * 8 + (lane >> 3), chunk = lane & 7;
-      const int m = min(m0 + row, g.M - 1);
-      cow[i] = m % g.cW;
-      coh[i] = (m / g.cW) % g.cH;
-      ga[i] = A + (long long)m * g.cC + chunk * 8;
       la[i] = row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
-    } else if (!AT) {  // 8 rows x 128 B; 16-byte chunk c of row r sits at chunk position c ^ ((r >> 1) & 7)
-      const int row = q * 8 + (lane >> 3), chunk = lane & 7;
-      ga[i] = A + (long long)min(m0 + row, g.M - 1) * g.lda + k_begin + chunk * 8;
-      la[i] = row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
-    } else {    // [64 k-rows][BM]; chunk j of k-row k sits at chunk position j ^ ((k & 3) << TSH_A)
-      constexpr int CR = BM / 8;
-      const int pos = q * 64 + lane;
-      const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << TSH_A);
-      int gi = m0 + j * 8;
-      if (gi + 8 > ((g.M + 7) & ~7)) gi = 0;
-      ga[i] = A + (long long)(k_begin + k) * g.lda + gi;
-      la[i] = pos * 16;
+    } else {                 // [64 k-rows][BM]; chunk j of k-row k sits at chunk position j ^ ((k & 3) << TSH_A)
+      la[i] = (q * 64 + lane) * 16;
     }
   }
-  // CONV 2: per piece, (dy + 1) << 26 | (dx + 1) << 24 | h << 12 | w for its tap and the pixel (h, w) of its k-row
-  // (cH, cW < 4096), and the tap's element offset
-  int bpix[CONV == 2 ? B_LOADS : 1], boff[CONV == 2 ? B_LOADS : 1];
 #pragma unroll
   for (int i = 0; i < B_LOADS; i++) {
     const int q = wave * B_LOADS + i;
-    if (CONV == 2) {
-      constexpr int CR = BN / 8;
-      const int pos = q * 64 + lane;
-      const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << TSH_B);
-      int gj = n0 + j * 8;
-      if (gj + 8 > g.N) gj = 0;                 // N = 9 cC is a multiple of 8
-      const int tap = gj / g.cC, ch = gj % g.cC;
-      const int dy = tap / 3 - 1, dx = tap % 3 - 1;
-      const int pix = k_begin + k;
-      bpix[i] = ((dy + 1) << 26) | ((dx + 1) << 24) | (((pix / g.cW) % g.cH) << 12) | (pix % g.cW);
-      boff[i] = (dy * g.cW + dx) * g.cC;
-      gb[i] = B + (long long)pix * g.cC + ch;   // centre tap
-      lb[i] = A_BYTES + pos * 16;
-    } else if (!BT) {
+    if (CONV != 2 && !BT) {
       const int row = q * 8 + (lane >> 3), chunk = lane & 7;
-      gb[i] = B + (long long)min(n0 + row, g.N - 1) * g.ldb + k_begin + chunk * 8;
       lb[i] = A_BYTES + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
     } else {
-      constexpr int CR = BN / 8;
-      const int pos = q * 64 + lane;
-      const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << TSH_B);
-      int gj = n0 + j * 8;
-      if (gj + 8 > ((g.N + 7) & ~7)) gj = 0;
-      gb[i] = B + (long long)(k_begin + k) * g.ldb + gj;
-      lb[i] = A_BYTES + pos * 16;
+      lb[i] = A_BYTES + (q * 64 + lane) * 16;
     }
   }
+
+  auto setup = [&](int w) {
+    // (lane-dependent values of the address computation come from an opaque copy of the thread index: they are
+    // recomputed per unit instead of occupying registers throughout the main loop)
+    int s_tid = tid;
+    asm volatile("" : "+v"(s_tid));
+    const int lane = s_tid & 63, wave = s_tid >> 6;
+    unit_coords<BM, BN>(g, w, m0, n0, z);
+    batch_offsets(g, z, A, B, c_off, k_begin, k_end);
+    nk = (k_end - k_begin) / PBK;
+#pragma unroll
+    for (int i = 0; i < A_LOADS; i++) {
+      const int q = wave * A_LOADS + i;
+      if (CONV == 1) {  // centre tap of the row's pixel
+        const int row = q * 8 + (lane >> 3), chunk = lane & 7;
+        const int m = min(m0 + row, g.M - 1);
+        cow[CONV == 1 ? i : 0] = m % g.cW;
+        coh[CONV == 1 ? i : 0] = (m / g.cW) % g.cH;
+        ga[i] = A + (long long)m * g.cC + chunk * 8;
+      } else if (!AT) {
+        const int row = q * 8 + (lane >> 3), chunk = lane & 7;
+        ga[i] = A + (long long)min(m0 + row, g.M - 1) * g.lda + k_begin + chunk * 8;
+      } else {
+        constexpr int CR = BM / 8;
+        const int pos = q * 64 + lane;
+        const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << TSH_A);
+        int gi = m0 + j * 8;
+        if (gi + 8 > ((g.M + 7) & ~7)) gi = 0;
+        ga[i] = A + (long long)(k_begin + k) * g.lda + gi;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < B_LOADS; i++) {
+      const int q = wave * B_LOADS + i;
+      if (CONV == 2) {
+        constexpr int CR = BN / 8;
+        const int pos = q * 64 + lane;
+        const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << TSH_B);
+        int gj = n0 + j * 8;
+        if (gj + 8 > g.N) gj = 0;                 // N = 9 cC is a multiple of 8
+        const int tap = gj / g.cC, ch = gj % g.cC;
+        const int dy = tap / 3 - 1, dx = tap % 3 - 1;
+        const int pix = k_begin + k;
+        bpix[CONV == 2 ? i : 0] = ((dy + 1) << 26) | ((dx + 1) << 24) | (((pix / g.cW) % g.cH) << 12) | (pix % g.cW);
+        boff[CONV == 2 ? i : 0] = (dy * g.cW + dx) * g.cC;
+        gb[i] = B + (long long)pix * g.cC + ch;   // centre tap
+      } else if (!BT) {
+        const int row = q * 8 + (lane >> 3), chunk = lane & 7;
+        gb[i] = B + (long long)min(n0 + row, g.N - 1) * g.ldb + k_begin + chunk * 8;
+      } else {
+        constexpr int CR = BN / 8;
+        const int pos = q * 64 + lane;
+        const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << TSH_B);
+        int gj = n0 + j * 8;
+        if (gj + 8 > ((g.N + 7) & ~7)) gj = 0;
+        gb[i] = B + (long long)(k_begin + k) * g.ldb + gj;
+      }
+    }
+    if (CONV == 1) {
+      const int tap0 = k_begin / g.cC;
+      c_sub = k_begin % g.cC;
+      c_dy = tap0 / 3 - 1;
+      c_dx = tap0 % 3 - 1;
+      c_off_a = (long long)(c_dy * g.cW + c_dx) * g.cC + c_sub;
+    }
+  };
   const long long a_step = AT ? (long long)PBK * g.lda : PBK;
   const long long b_step = CONV == 2 ? (long long)PBK * g.cC : (BT ? (long long)PBK * g.ldb : PBK);
   // CONV 2: a slice moves every piece 64 pixels on: (h, w) advance by (64 / cW, 64 % cW) with carries
   const int b_sw = CONV == 2 ? PBK % g.cW : 0, b_sh = CONV == 2 ? (PBK / g.cW) % g.cH : 0;
 
   f32x16 acc[MI][NI];
-#pragma unroll
-  for (int mi = 0; mi < MI; mi++)
-#pragma unroll
-    for (int ni = 0; ni < NI; ni++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) acc[mi][ni][r] = 0.f;
 
   const int l32 = lane & 31, khalf = lane >> 5;
   const int grp16 = lane >> 4, r16 = lane & 15;
@@ -915,27 +1088,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
 #pragma unroll
     for (int ni = 0; ni < NI; ni++) bfr[ni] = load_b(st, ks, ni);
   };
-  auto mma = [&](bf16x8 (&af)[MI], bf16x8 (&bfr)[NI]) {
-#pragma unroll
-    for (int mi = 0; mi < MI; mi++)
-#pragma unroll
-      for (int ni = 0; ni < NI; ni++)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
-  };
 
   u32x4 ra[A_LOADS], rb[B_LOADS];
-  // CONV: tap (dy, dx) and channel offset of the next slice to load (uniform), the element offset
-  // of that slice from the centre tap, and per lane one bit per piece: "the registers hold data"
-  // (as opposed to a pixel outside the image, stored as zeros)
-  // (a split reduction starts at column k_begin = (tap, channel offset) of the matrix)
-  int c_dy = -1, c_dx = -1, c_sub = 0;
-  if (CONV == 1) {
-    const int tap0 = k_begin / g.cC;
-    c_sub = k_begin % g.cC;
-    c_dy = tap0 / 3 - 1;
-    c_dx = tap0 % 3 - 1;
-  }
-  long long c_off_a = CONV == 1 ? (long long)(c_dy * g.cW + c_dx) * g.cC + c_sub : 0;
+  // per lane one bit per piece: "the registers hold data" (as opposed to a pixel outside the image, stored as zeros)
   unsigned c_ok = 0;
   auto conv_load = [&](int i) {
     const bool ok = (unsigned)(coh[CONV == 1 ? i : 0] + c_dy) < (unsigned)g.cH && (unsigned)(cow[CONV == 1 ? i : 0] + c_dx) < (unsigned)g.cW;
@@ -1017,69 +1172,93 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
 
   const int group = wave >> 2;
   bf16x8 a0[MI], b0[NI], a1[MI], b1[NI];
-  // prologue: slice 0 into stage 0, slice 1 (or slice 0 again) into the registers
-  if (CONV == 0) {
-    // both slices are requested before the first is stored: one memory latency instead of two
-    u32x4 ra0[A_LOADS], rb0[B_LOADS];
+  // Start of a unit, plain product: slices 0 and 1 are both requested before the first is stored (one memory
+  // latency instead of two), and, from the second unit on, before the epilogue of the unit just finished: the
+  // loads travel while the accumulators pass through LDS and the stores of that tile drain.
+  u32x4 ra0[CONV == 0 ? A_LOADS : 1], rb0[CONV == 0 ? B_LOADS : 1];
+  auto first_loads = [&]() {
 #pragma unroll
     for (int i = 0; i < A_LOADS; i++) {
-      ra0[i] = *(const u32x4*)ga[i];
+      ra0[CONV == 0 ? i : 0] = *(const u32x4*)ga[i];
       ga[i] += nk > 1 ? a_step : 0;
     }
 #pragma unroll
     for (int i = 0; i < B_LOADS; i++) {
-      rb0[i] = *(const u32x4*)gb[i];
+      rb0[CONV == 0 ? i : 0] = *(const u32x4*)gb[i];
       gb[i] += nk > 1 ? b_step : 0;
     }
+  };
+  auto second_loads = [&]() {
     load_a_regs(nk > 2);
     load_b_regs(nk > 2);
-#pragma unroll
-    for (int i = 0; i < A_LOADS; i++) *(u32x4*)(smem + la[i]) = ra0[i];
-#pragma unroll
-    for (int i = 0; i < B_LOADS; i++) *(u32x4*)(smem + lb[i]) = rb0[i];
-  } else {
-    load_a_regs(nk > 1);
-    load_b_regs(nk > 1);
-    store_a(smem);
-    store_b(smem);
-    load_a_regs(nk > 2);
-    load_b_regs(nk > 2);
-  }
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  block_barrier();
-  if (group == 1) block_barrier();
+  };
+  // barrier between phases that exchange data through LDS only: the wave's own LDS operations are complete,
+  // outstanding global loads and stores are left in flight (a __syncthreads would wait for them too)
+  auto lds_barrier = [&]() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    block_barrier();
+  };
   // one C phase: the MFMAs of two k-steps with this wave's global loads of one operand spread
   // evenly between them, so that the loads of the four SIMDs reach
   // the texture addresser evenly instead of in a burst that would stall the issuing waves
   constexpr int P = MI * NI * 2;   // MFMAs of one C phase
   // load j is issued in the middle of its share of the phase's MFMAs (staggering the four SIMDs
   // against each other as well was measured and is slower)
-  {
-    constexpr int S = 2;
-    auto c_phase = [&](auto loads_tag, auto&& load_one) {
-      constexpr int L = decltype(loads_tag)::value;
-      __builtin_amdgcn_s_setprio(1);
-      int n = 0;
+  constexpr int S = 2;
+  auto c_phase = [&](auto loads_tag, auto&& load_one) {
+    constexpr int L = decltype(loads_tag)::value;
+    __builtin_amdgcn_s_setprio(1);
+    int n = 0;
 #pragma unroll
-      for (int half = 0; half < 2; half++)
+    for (int half = 0; half < 2; half++)
 #pragma unroll
-        for (int mi = 0; mi < MI; mi++)
+      for (int mi = 0; mi < MI; mi++)
 #pragma unroll
-          for (int ni = 0; ni < NI; ni++) {
-            acc[mi][ni] = half == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mi], b0[ni], acc[mi][ni], 0, 0, 0)
-                                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[mi], b1[ni], acc[mi][ni], 0, 0, 0);
-            n++;
+        for (int ni = 0; ni < NI; ni++) {
+          acc[mi][ni] = half == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0[ni], a0[mi], acc[mi][ni], 0, 0, 0)
+                                  : __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1[ni], a1[mi], acc[mi][ni], 0, 0, 0);
+          n++;
 #pragma unroll
-            for (int j = 0; j < L; j++)
-              if (n == 1 + (4 * j * P + S * P) / (4 * L)) {
-                __builtin_amdgcn_sched_barrier(0);
-                load_one(j);
-                __builtin_amdgcn_sched_barrier(0);
-              }
-          }
-      __builtin_amdgcn_s_setprio(0);
-      block_barrier();
-    };
+          for (int j = 0; j < L; j++)
+            if (n == 1 + (4 * j * P + S * P) / (4 * L)) {
+              __builtin_amdgcn_sched_barrier(0);
+              load_one(j);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    __builtin_amdgcn_s_setprio(0);
+    block_barrier();
+  };
+
+  // The workgroup stays resident and walks over units w = blockIdx.x, + gridDim.x, ...: the launch cost of a
+  // workgroup is paid once, and the stores of a tile drain while the next tile's first slices arrive.
+  int w = blockIdx.x;
+  setup(w);
+  if (CONV == 0) { first_loads(); second_loads(); }
+  for (;;) {
+#pragma unroll
+    for (int mi = 0; mi < MI; mi++)
+#pragma unroll
+      for (int ni = 0; ni < NI; ni++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc[mi][ni][r] = 0.f;
+    // slice 0 into stage 0, slice 1 (or slice 0 again) into the registers
+    if (CONV == 0) {
+#pragma unroll
+      for (int i = 0; i < A_LOADS; i++) *(u32x4*)(smem + la[i]) = ra0[CONV == 0 ? i : 0];
+#pragma unroll
+      for (int i = 0; i < B_LOADS; i++) *(u32x4*)(smem + lb[i]) = rb0[CONV == 0 ? i : 0];
+    } else {
+      load_a_regs(nk > 1);
+      load_b_regs(nk > 1);
+      store_a(smem);
+      store_b(smem);
+      load_a_regs(nk > 2);
+      load_b_regs(nk > 2);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    block_barrier();
+    if (group == 1) block_barrier();
     for (int kt = 0; kt < nk; kt++) {
       unsigned char* cur = smem + (kt & 1) * STAGE;
       unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
@@ -1112,11 +1291,41 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
         }
       });
     }
+    if (group == 0) block_barrier();
+    // where this tile goes; then the next unit's coordinates and first loads, ahead of the epilogue
+    const int m0e = m0, n0e = n0;
+    const long long e_off = c_off;
+    const int w_next = w + (int)gridDim.x;
+    const bool more = w_next < g.units;
+    lds_barrier();    // every wave is done with the stages before they are reused for the epilogue
+    // The next unit's coordinates and its first slice are requested from inside the epilogue, once half of the
+    // accumulator registers are free: the loads travel while the second half is stored.  (After the last unit
+    // the same unit's first slice is requested once more and dropped: an unconditional request leaves no path on
+    // which the registers of the previous request would have to survive the main loop.)
+    // (not where the epilogue needs the registers itself: prefetched residual rows, two sets of per-column parameters)
+    constexpr bool MID_PREFETCH = CONV == 0 && MI > 1 && EPI != E_F32_RES && EPI != E_AFFINE;
+    auto mid = [&](int mi) {
+      if (MID_PREFETCH && mi == (MI + 1) / 2) {   // slice 0, once half of the accumulators are stored
+        setup(more ? w_next : w);
+        first_loads();
+      }
+      if (MID_PREFETCH && mi == MI - 1) second_loads();   // slice 1 before the last block
+    };
+    // (the epilogue's own lane-dependent values are derived from an opaque copy of the thread index, so that they
+    // are computed here and not kept in registers across the main loop of every unit)
+    int e_tid = tid;
+    asm volatile("" : "+v"(e_tid));
+    const int e_lane = e_tid & 63, e_wave = e_tid >> 6;
+    wave_epilogue<EPI, MI, NI>(g, acc, smem + e_wave * epi_wave_bytes<TN>(), m0e + (e_wave / WGN) * TM, n0e + (e_wave % WGN) * TN, e_off,
+                               e_lane, mid);
+    if (!more) break;
+    w = w_next;
+    if (!MID_PREFETCH) {
+      setup(w_next);
+      if (CONV == 0) { first_loads(); second_loads(); }
+    }
+    lds_barrier();    // and done with the epilogue's staging area before the next unit's first slice is stored
   }
-  if (group == 0) block_barrier();
-  if (g.no_store & 7) return;
-  __syncthreads();  // every wave is done with the stages before they are reused for the epilogue
-  wave_epilogue<EPI, MI, NI>(g, acc, (float*)smem + wave * 32 * TN, m0 + wave_m * TM, n0 + wave_n * TN, c_off, lane);
 }
 
 // host side: pick the instantiation for (layout, epilogue); returns false if that pair is not built

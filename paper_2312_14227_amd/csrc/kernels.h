@@ -69,7 +69,6 @@ struct GemmDesc {
   // K a multiple of 64, fp32 output, split allowed
   int conv_h = 0, conv_w = 0, conv_c = 0;
   int tile = 0;                    // 0 = choose by shape; else a TileId (tuning/tests)
-  int no_store = 0;                // tuning aids (bit 0: store nothing, bit 1: no loads, bit 2: one panel)
 };
 
 // returns hipSuccess, or hipErrorInvalidValue when a requirement above is violated

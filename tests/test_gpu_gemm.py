@@ -52,7 +52,7 @@ def _run(M, N, K, a_t, b_t, c_f32, bias, residual, split_k, tile, seed):
     st = et.et_debug_gemm_bf16(At.data_ptr(), Bt.data_ptr(), Ct.data_ptr(), M, N, K, A.shape[1], B.shape[1], ldc, a_t,
                                b_t, c_f32, 1.0, bias_t.data_ptr() if bias else 0, res_t.data_ptr() if residual else 0,
                                split_k, part.data_ptr() if part is not None else 0, tile,
-                               torch.cuda.current_stream().cuda_stream)
+                               torch.cuda.current_stream().cuda_stream)   # (plain epilogue)
     assert st == 0
     torch.cuda.synchronize()
     got = Ct.float().cpu().numpy().astype(np.float64)[:, :N]
@@ -126,3 +126,54 @@ def test_gemm_rejects_bad_arguments():
     assert et.et_debug_gemm_bf16(t.data_ptr() + 2, t.data_ptr(), c.data_ptr(), 16, 16, 16, 16, 16, 16, 0, 0, 1) == et.ET_EINVAL
     assert et.et_debug_gemm_bf16(t.data_ptr(), t.data_ptr(), c.data_ptr(), 16, 16, 16, 16, 16, 16, 1, 0, 1) == et.ET_EINVAL
     assert et.et_debug_gemm_bf16(0, t.data_ptr(), c.data_ptr(), 16, 16, 16, 16, 16, 16, 0, 0, 1) == et.ET_EINVAL
+
+
+@pytest.mark.parametrize("tile", [0, 1, 7, 11, 13])
+@pytest.mark.parametrize("M,N,K", [(700, 520, 192), (1000, 768, 768), (513, 300, 128), (77, 136, 64)])
+def test_gemm_gelu_epilogues(M, N, K, tile):
+    """The fused GELU epilogues against the oracle's erf-form GELU and its derivative: forward (two outputs), forward
+    without the derivative, and the backward product that multiplies by the stored derivative."""
+    import torch
+    from oracle import nets
+    from paper_2312_14227_amd import binding as et
+    rng = np.random.default_rng(1000 * tile + M)
+    N8 = (N + 7) // 8 * 8
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream().cuda_stream
+    A = bf16_round(rng.standard_normal((M, K)).astype(np.float32) * 0.3)
+    B = bf16_round(rng.standard_normal((N, K)).astype(np.float32) * 0.3)
+    b = bf16_round(rng.standard_normal(N).astype(np.float32))
+    At, Bt = torch.from_numpy(A).to(dev).to(torch.bfloat16), torch.from_numpy(B).to(dev).to(torch.bfloat16)
+    bt = torch.from_numpy(b).to(dev).to(torch.bfloat16)
+    u = A.astype(np.float64) @ B.astype(np.float64).T + b.astype(np.float64)
+    slack = 2e-6 * (np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64).T) * np.sqrt(K) + 1e-5   # fp32 sum, erf approximation
+    for epi in (1, 3):
+        C1 = torch.full((M, N8), float("nan"), device=dev, dtype=torch.bfloat16)
+        C2 = torch.full((M, N8), float("nan"), device=dev, dtype=torch.bfloat16)
+        st = et.et_debug_gemm_bf16(At.data_ptr(), Bt.data_ptr(), C1.data_ptr(), M, N, K, K, K, N8, 0, 0, 0, 1.0, bt.data_ptr(), 0, 1, 0,
+                                   tile, stream, epilogue=epi, aux=C2.data_ptr() if epi == 1 else 0)
+        assert st == 0
+        torch.cuda.synchronize()
+        got1 = C1.float().cpu().numpy().astype(np.float64)[:, :N]
+        want1 = nets.gelu_grad(u) if epi == 1 else nets.gelu(u)
+        # |d gelu / du| <= 1.13 and |d gelu' / du| <= 1: an error of the sum passes through at most unchanged
+        assert (np.abs(got1 - want1) <= 1.2 * slack + 2.0 ** -8 * np.abs(want1)).all(), float(np.abs(got1 - want1).max())
+        if epi == 1:
+            got2 = C2.float().cpu().numpy().astype(np.float64)[:, :N]
+            assert (np.abs(got2 - nets.gelu(u)) <= 1.2 * slack + 2.0 ** -8 * np.abs(nets.gelu(u))).all()
+            if N8 > N:
+                assert torch.isnan(C2[:, N:].float()).all() and torch.isnan(C1[:, N:].float()).all()
+    # backward: dU = (dY W) * gelu'(u) with the stored derivative as second operand; here A [M][K] W [K][N] (b_t)
+    W = bf16_round(rng.standard_normal((K, N8)).astype(np.float32) * 0.3)
+    W[:, N:] = 0
+    U = bf16_round(rng.standard_normal((M, N8)).astype(np.float32))
+    Wt, Ut = torch.from_numpy(W).to(dev).to(torch.bfloat16), torch.from_numpy(U).to(dev).to(torch.bfloat16)
+    C3 = torch.full((M, N8), float("nan"), device=dev, dtype=torch.bfloat16)
+    st = et.et_debug_gemm_bf16(At.data_ptr(), Wt.data_ptr(), C3.data_ptr(), M, N, K, K, N8, N8, 0, 1, 0, 1.0, 0, 0, 1, 0, tile, stream,
+                               epilogue=2, aux=Ut.data_ptr())
+    assert st == 0
+    torch.cuda.synchronize()
+    want = (A.astype(np.float64) @ W[:, :N].astype(np.float64)) * U[:, :N].astype(np.float64)
+    sl = (2e-6 * (np.abs(A).astype(np.float64) @ np.abs(W[:, :N]).astype(np.float64)) * np.sqrt(K) + 1e-6) * np.abs(U[:, :N])
+    got = C3.float().cpu().numpy().astype(np.float64)[:, :N]
+    assert (np.abs(got - want) <= sl + 2.0 ** -8 * np.abs(want)).all(), float(np.abs(got - want).max())
