@@ -165,7 +165,8 @@ int et_profile(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, int32_t war
 /* Tensor Importance Evaluator (Eq. 2, with the gradient at the current weights, Eq. 5 at c=0):
  * one full backward pass on (x, y) without update, then
  *   importance[i] = sum_e grad_i[e] * (w_snapshot_i[e] - w_i[e])
- * for every tensor in ONE reduction launch.  w_snapshot_dev[i] has the model's storage type
+ * for every tensor in one segmented reduction (a launch over all chunks of all tensors, then a tiny launch
+ * that adds each tensor's chunk sums in a fixed order).  w_snapshot_dev[i] has the model's storage type
  * and tensor i's size: the weights that undoing the recent update would restore.  Leaves
  * the gradients of all tensors in grad_dev.  Host output; waits for the stream. */
 int et_importance(et_ctx* ctx, const void* x_dev, const int32_t* y_dev, void* const* w_snapshot_dev /*[N]*/,

@@ -134,6 +134,9 @@ struct et_ctx {
   et::TensorSeg* imp_segs_dev = nullptr;
   et::UpdateSeg* upd_segs_dev = nullptr;
   uint32_t* seg_begin_dev = nullptr;
+  uint32_t* upd_selected_dev = nullptr;   // indices of the chunks of the tensors selected by upd_mask
+  std::vector<uint32_t> upd_selected;
+  std::vector<uint8_t> upd_mask;          // the mask upd_selected_dev was built for
   double *imp_partial_dev = nullptr, *imp_out_dev = nullptr;
   std::vector<et::UpdateSeg> upd_segs_host;
   std::vector<et::TensorSeg> imp_segs_host;

@@ -111,6 +111,7 @@ void build_tables_plan(et_ctx* c) {
   c->n_segs = c->seg_begin[N];
   reserve(c, &c->imp_segs_dev, sizeof(et::TensorSeg) * c->n_segs);
   reserve(c, &c->upd_segs_dev, sizeof(et::UpdateSeg) * c->n_segs);
+  reserve(c, &c->upd_selected_dev, sizeof(uint32_t) * c->n_segs);
   reserve(c, &c->seg_begin_dev, sizeof(uint32_t) * (N + 1));
   reserve(c, &c->imp_partial_dev, sizeof(double) * c->n_segs);
   reserve(c, &c->imp_out_dev, sizeof(double) * N);
@@ -502,12 +503,20 @@ int run_update(et_ctx* c, const uint8_t* mask, const et_opt* opt, bool dry) {
   if (c->state.empty()) return ET_ESTATE;
   if (opt->kind != ET_ADAM && opt->kind != ET_SGDW) return ET_EINVAL;
   if (opt->kind == ET_ADAM && opt->step < 1) return ET_EINVAL;
-  et::SelectionBits sel;
-  std::memset(&sel, 0, sizeof(sel));
-  bool any = false;
-  for (size_t i = 0; i < N; i++)
-    if (mask[i]) { sel.bits[i >> 6] |= 1ull << (i & 63); any = true; }
-  if (!any) return ET_OK;
+  // the chunks of the selected tensors, listed on the device; rebuilt only when the mask changes
+  std::vector<uint8_t> norm(N);
+  for (size_t i = 0; i < N; i++) norm[i] = mask[i] ? 1 : 0;
+  if (c->upd_mask != norm) {
+    c->upd_mask = norm;
+    c->upd_selected.clear();
+    for (size_t i = 0; i < N; i++)
+      if (mask[i])
+        for (uint32_t sg = c->seg_begin[i]; sg < c->seg_begin[i + 1]; sg++) c->upd_selected.push_back(sg);
+    if (!c->upd_selected.empty())
+      ET_HIP(hipMemcpyAsync(c->upd_selected_dev, c->upd_selected.data(), sizeof(uint32_t) * c->upd_selected.size(),
+                            hipMemcpyHostToDevice, c->stream));
+  }
+  if (c->upd_selected.empty()) return ET_OK;
   et::OptParams p;
   p.kind = opt->kind == ET_ADAM ? 0 : 1;
   p.lr = opt->lr; p.beta1 = opt->beta1; p.beta2 = opt->beta2; p.eps = opt->eps; p.momentum = opt->momentum; p.wd = opt->wd;
@@ -522,7 +531,7 @@ int run_update(et_ctx* c, const uint8_t* mask, const et_opt* opt, bool dry) {
   // bytes per selected element: read g + fp32 weight + moments, write fp32 weight + moments (+ bf16 copy)
   const double per_elem = (opt->kind == ET_ADAM ? 28.0 : 20.0) + (c->bf16_model ? 2.0 : 0.0);
   KernelTimer kt(c, 4, sel_elems * per_elem);
-  ET_K(1, et::masked_update(c->upd_segs_dev, (int)c->n_segs, c->bf16_model, sel, p, c->stream));
+  ET_K(1, et::masked_update(c->upd_segs_dev, c->upd_selected_dev, (int)c->upd_selected.size(), c->bf16_model, p, c->stream));
   return ET_OK;
 }
 
@@ -566,7 +575,6 @@ int et_create(const et_model_desc* desc, void* hip_stream, et_ctx** out) {
     else if (desc->kind == ET_VGG) rc = build_vgg(c);
     else if (desc->kind == ET_MOBILENET) rc = build_mobilenet(c);
     else rc = ET_EINVAL;
-    if (rc == ET_OK && c->tensors.size() > (size_t)et::MAX_TENSORS) rc = ET_EINVAL;
     if (rc == ET_OK) {
       c->state_slots = c->bf16_model ? 3 : 2;
       build_tables_plan(c);
@@ -628,6 +636,8 @@ int et_bind(et_ctx* c, void* const* w_dev, void* const* opt_state_dev, void* con
   }
   try {
     c->bound = false;
+    c->upd_mask.clear();          // the device list of selected chunks lives in the (new) workspace
+    c->upd_selected.clear();
     c->w.assign(w_dev, w_dev + N);
     c->grad.resize(N);
     for (size_t i = 0; i < N; i++) c->grad[i] = (float*)grad_dev[i];

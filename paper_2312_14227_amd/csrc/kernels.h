@@ -237,18 +237,15 @@ struct UpdateSeg {
   uint32_t n;
   uint32_t tensor;
 };
-constexpr int MAX_TENSORS = 1024;
-struct SelectionBits {   // bit i set: tensor i is selected; passed by value as a kernel argument
-  uint64_t bits[MAX_TENSORS / 64];
-};
 struct OptParams {
   int kind;       // 0 Adam, 1 SGDW
   float lr, beta1, beta2, eps, momentum, wd;
   float bc1, bc2; // 1 - beta1^t, 1 - beta2^t
   int dry;        // 1: compute, then store the values that were loaded (timing without side effects)
 };
-// segs_dev lists the chunks of ALL tensors; chunks of tensors outside `sel` exit immediately
-hipError_t masked_update(const UpdateSeg* segs_dev, int n_segs, bool bf16_weights, const SelectionBits& sel,
+// segs_dev lists the chunks of ALL tensors, selected_dev the indices of the n_selected chunks that belong to
+// selected tensors: one workgroup per listed chunk, nothing else is touched
+hipError_t masked_update(const UpdateSeg* segs_dev, const uint32_t* selected_dev, int n_selected, bool bf16_weights,
                          OptParams p, hipStream_t s);
 
 }  // namespace et

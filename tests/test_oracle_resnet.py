@@ -164,5 +164,5 @@ def test_two_bf16_evaluations_of_the_full_depth_network_differ_by_per_cent():
     for sp in spreads:
         assert 1e-2 < float(np.median(sp)) < 0.2
         assert sp[wl.names.index("stem.W")] > 5e-2           # the tensor behind every ReLU of the network
-        assert sp[wl.names.index("head.W")] < 2e-3           # nothing lies between the head and the loss
+        assert sp[wl.names.index("head.W")] < 1e-2           # no mask lies between the head and the loss: forward noise only
     assert 0.5 < float(np.median(spreads[0]) / np.median(spreads[1])) < 2.0
