@@ -30,7 +30,16 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int DH = 64;
 constexpr int NWAVES = 8, NTHREADS = NWAVES * 64;
-constexpr int PITCH = 160;  // bytes per LDS row of 64 bf16: 128 + 32 keeps 4 consecutive rows in distinct banks
+// LDS rows are the 128 bytes of 64 bf16 without padding; the 16-byte chunk c of row r sits at chunk position
+// c ^ swz(r).  Every tile is read two ways and both must spread over the 64 banks:
+//   - row-major fragments (ds_read_b128, 16 consecutive rows x one chunk per 16 lanes): rows alternate between the
+//     two 128-byte halves of the 256-byte bank span, so the 8 even rows of a group need 8 different positions;
+//   - transposing fragments (ds_read_b64_tr_b16, 4 consecutive rows x 64 contiguous bytes per 32 lanes): rows
+//     r and r + 2 share a half, so their 64-byte pieces must land in different quarters.
+// swz(r) = bit 1 of r as the high bit, bits 2..3 of r as the low bits, does both (a plain (r >> 1) & 7 leaves the
+// transposing reads two-way conflicted, as did padded rows of 160 bytes: 41-45 % conflict cycles measured).
+constexpr int PITCH = 128;
+__device__ __forceinline__ int swz(int row) { return (((row >> 1) & 1) << 2) | ((row >> 2) & 3); }
 
 __device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char* p) {
   s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
@@ -58,22 +67,28 @@ __device__ __forceinline__ void stage_rows(unsigned char* const (&dst)[NM], cons
 #pragma unroll
     for (int i = 0; i < PER; i++) {
       const int v = tid + i * NTHREADS, row = v >> 3, c = v & 7;
-      if (v < TP * 8) *(uint4*)(dst[m] + row * PITCH + c * 16) = val[m][i];
+      if (v < TP * 8) *(uint4*)(dst[m] + row * PITCH + ((c ^ swz(row)) << 4)) = val[m][i];
     }
 }
 
 // A- or B-operand fragment of rows [row0, row0+32) for reduction slice ks (16 of the 64 columns):
 // lane l gets row row0 + l%32, columns ks*16 + (l/32)*8 .. +7
 __device__ __forceinline__ bf16x8 frag_direct(const unsigned char* m, int row0, int ks, int lane) {
-  return *(const bf16x8*)(m + (row0 + (lane & 31)) * PITCH + (ks * 2 + (lane >> 5)) * 16);
+  const int row = row0 + (lane & 31);
+  return *(const bf16x8*)(m + row * PITCH + (((ks * 2 + (lane >> 5)) ^ swz(row)) << 4));
 }
 
 // B-operand fragment for a reduction over ROWS of a matrix stored [row][64]: lane l gets column
 // col0 + l%32 and the 8 rows  row0 + (e/4)*8 + (l/32)*4 + e%4  (e = 0..7)
 __device__ __forceinline__ bf16x8 frag_rows_tr(const unsigned char* m, int row0, int col0, int lane) {
   const int g = lane >> 4, r16 = lane & 15;
-  const unsigned char* p = m + (row0 + (g >> 1) * 4 + (r16 >> 2)) * PITCH + (col0 + (g & 1) * 16 + 4 * (r16 & 3)) * 2;
-  const bf16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 8 * PITCH);
+  // (rows r and r + 8 differ in bit 3, which is bit 1 of swz: the second address is computed on its own)
+  const int row = row0 + (g >> 1) * 4 + (r16 >> 2);
+  const int byte = (col0 + (g & 1) * 16 + 4 * (r16 & 3)) * 2;      // 8-byte piece inside the logical row
+  const int chunk = byte >> 4, half = byte & 8;
+  const unsigned char* p = m + row * PITCH + ((chunk ^ swz(row)) << 4) + half;
+  const unsigned char* p8 = m + (row + 8) * PITCH + ((chunk ^ swz(row + 8)) << 4) + half;
+  const bf16x4 lo = lds_read_tr(p), hi = lds_read_tr(p8);
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
