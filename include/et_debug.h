@@ -53,6 +53,15 @@ int et_debug_conv3x3_split(const void* x, const void* w, void* out, void* z_out,
 int et_debug_conv3x3_dw(const void* x, const void* d, float* dw, int batch, int H, int W, int C, int N, int split_k,
                         float* partials, int tile, void* stream);
 
+/* The gathered (implicit im2col) convolution products in general form: taps = 3 (zero padding 1) or 1 (no padding),
+ * stride 1 or 2, Ho = (H - 1) / stride + 1, Wo likewise.  x bf16 NHWC [batch][H][W][C].
+ *   op 0 forward: w_or_d = weights bf16 [N][taps][taps][C], C a multiple of 64; out bf16 [batch*Ho*Wo][N];
+ *   op 1 weight gradient: w_or_d = d bf16 [batch*Ho*Wo][N]; out fp32 [N][taps*taps*C]; C a multiple of 8,
+ *     batch*Ho*Wo a multiple of 64.
+ * split_k, partials, tile as in the two 3x3 entries above (split_k = 0 plans tile and split).  Returns 0, -1, -3. */
+int et_debug_conv_gathered(int op, const void* x, const void* w_or_d, void* out, int batch, int H, int W, int C, int N,
+                           int taps, int stride, int split_k, float* partials, int tile, void* stream);
+
 /* 3x3 depthwise convolution kernels (zero padding 1, stride 1 or 2; NHWC bf16, C a multiple of 8; weights bf16
  * [C][9]; Ho = (H - 1) / stride + 1, Wo likewise).  op selects the kernel:
  *   0 forward: a = x [batch][H][W][C], b = weights, gain, shift [C]; out0 (nullable) = z, the convolution rounded to

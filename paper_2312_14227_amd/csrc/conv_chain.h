@@ -1,9 +1,10 @@
 // Convolution units shared by the convolutional chains: a convolution is a GEMM over the rows of
 // an im2col matrix (a 1x1 stride-1 convolution reads the activation itself): forward cols * W^T,
 // dw() d^T * cols (split over the rows), dy() d * W followed by the gather-form adjoint of im2col.
-// A 3x3 / stride 1 convolution with channel counts in multiples of 64 never writes that matrix:
-// the forward product and dw() gather its rows from the activation inside the GEMM, and dy() is
-// the same kind of convolution of the output gradient with the mirrored weight.
+// A 3x3 convolution of stride 1 or 2 (and a strided 1x1 one) with channel counts in multiples of 64 never
+// writes that matrix: the forward product and dw() gather its rows from the activation inside the GEMM; dy()
+// of a stride-1 3x3 convolution is the same kind of convolution of the output gradient with the mirrored
+// weight, dy() of the strided ones goes through a float32 column gradient and the adjoint of im2col.
 #pragma once
 #include "context.h"
 
@@ -36,10 +37,12 @@ inline void init_unit(ConvUnit& u, int t, int H, int W, int Cin, int Cout, int k
 inline size_t rows_of(const et_ctx* c, const ConvUnit& u) { return (size_t)c->desc.batch * u.Ho * u.Wo; }
 inline bool needs_cols(const ConvUnit& u) { return u.k > 1 || u.stride > 1; }
 // which of the three products of a unit run as implicit GEMMs
-inline bool implicit_fwd(const ConvUnit& u) { return u.k == 3 && u.stride == 1 && (u.Cin % 64) == 0; }
+// (3x3 of stride 1 or 2 and strided 1x1 convolutions gather their rows inside the GEMM)
+inline bool gathered_kind(const ConvUnit& u) { return (u.k == 3 && (u.stride == 1 || u.stride == 2)) || (u.k == 1 && u.stride == 2); }
+inline bool implicit_fwd(const ConvUnit& u) { return gathered_kind(u) && (u.Cin % 64) == 0; }
 inline bool implicit_dy(const ConvUnit& u) { return u.k == 3 && u.stride == 1 && (u.Cout % 64) == 0 && (u.Cin % 8) == 0; }
 inline bool implicit_dw(const et_ctx* c, const ConvUnit& u) {
-  return u.k == 3 && u.stride == 1 && (u.Cin % 8) == 0 && ((size_t)c->desc.batch * u.H * u.W) % 64 == 0 && u.H < 4096 && u.W < 4096;
+  return gathered_kind(u) && (u.Cin % 8) == 0 && ((size_t)c->desc.batch * u.Ho * u.Wo) % 64 == 0 && u.H < 4096 && u.W < 4096;
 }
 // tile and split of a unit's implicit forward (or, with the channel roles exchanged, gradient-passing) product
 inline void plan_implicit(et_ctx* c, et::GemmDesc& g) {
@@ -52,7 +55,7 @@ inline size_t conv_split_partials(const et_ctx* c, const ConvUnit& u) {
   int tile, split;
   const int M = (int)rows_of(c, u);
   if (implicit_fwd(u)) {
-    et::gemm_bf16_plan_conv(M, u.Cout, 9 * u.Cin, &tile, &split);
+    et::gemm_bf16_plan_conv(M, u.Cout, u.k * u.k * u.Cin, &tile, &split);
     n = std::max(n, et::gemm_bf16_partial_elems(M, u.Cout, split));
   }
   if (implicit_dy(u)) {
@@ -66,8 +69,8 @@ inline size_t conv_dw_partials(const et_ctx* c, const ConvUnit& u) {
   const int M = (int)rows_of(c, u);
   int tile, split;
   if (implicit_dw(c, u)) {
-    et::gemm_bf16_plan_conv_dw(u.Cout, 9 * u.Cin, M, &tile, &split);
-    return et::gemm_bf16_partial_elems(u.Cout, 9 * u.Cin, split);
+    et::gemm_bf16_plan_conv_dw(u.Cout, u.k * u.k * u.Cin, M, &tile, &split);
+    return et::gemm_bf16_partial_elems(u.Cout, u.k * u.k * u.Cin, split);
   }
   return et::gemm_bf16_partial_elems(u.Cout, u.Kc, split_for(u.Cout, u.Kc, M));
 }
@@ -83,7 +86,7 @@ inline int conv_forward(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16
     A = u.cols;
   }
   et::GemmDesc g = linear_fwd(A, Wm, nullptr, (int)rows_of(c, u), u.Cout, u.Kc);
-  if (implicit_fwd(u)) { g.conv_h = u.H; g.conv_w = u.W; g.conv_c = u.Cin; }
+  if (implicit_fwd(u)) { g.conv_h = u.H; g.conv_w = u.W; g.conv_c = u.Cin; g.conv_taps = u.k; g.conv_stride = u.stride; }
   g.C = z; g.c_f32 = z_f32;
   if (gain) {
     g.mode = et::EPI_AFFINE_RELU; g.gain = gain; g.bias = shift; g.C2 = y;
@@ -99,10 +102,11 @@ inline int conv_forward(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16
 inline int conv_dw(et_ctx* c, const ConvUnit& u, const bf16* in, const bf16* d, float* dW) {
   if (implicit_dw(c, u)) {   // B operand: the activation standing for its im2col matrix
     et::GemmDesc g;
-    g.A = d; g.a_t = true; g.lda = u.Cout; g.B = in; g.b_t = true; g.ldb = 9 * u.Cin;
-    g.M = u.Cout; g.N = 9 * u.Cin; g.K = (int)rows_of(c, u);
-    g.C = dW; g.ldc = 9 * u.Cin; g.c_f32 = true;
-    g.conv_h = u.H; g.conv_w = u.W; g.conv_c = u.Cin;
+    const int kk = u.k * u.k * u.Cin;
+    g.A = d; g.a_t = true; g.lda = u.Cout; g.B = in; g.b_t = true; g.ldb = kk;
+    g.M = u.Cout; g.N = kk; g.K = (int)rows_of(c, u);
+    g.C = dW; g.ldc = kk; g.c_f32 = true;
+    g.conv_h = u.H; g.conv_w = u.W; g.conv_c = u.Cin; g.conv_taps = u.k; g.conv_stride = u.stride;
     et::gemm_bf16_plan_conv_dw(g.M, g.N, g.K, &g.tile, &g.split_k);
     g.partials = c->gemm_partials;
     if (et::gemm_bf16_partial_elems(g.M, g.N, g.split_k) > c->gemm_partial_elems) g.split_k = 1;

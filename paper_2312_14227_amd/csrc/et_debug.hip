@@ -73,6 +73,32 @@ extern "C" int et_debug_conv3x3_dw(const void* x, const void* d, float* dw, int 
   return e == hipSuccess ? ET_OK : ET_EHIP;
 }
 
+extern "C" int et_debug_conv_gathered(int op, const void* x, const void* w_or_d, void* out, int batch, int H, int W, int C, int N,
+                                      int taps, int stride, int split_k, float* partials, int tile, void* stream) {
+  if (batch < 1 || H < 1 || W < 1 || (taps != 1 && taps != 3) || (stride != 1 && stride != 2)) return ET_EINVAL;
+  const int Ho = (H - 1) / stride + 1, Wo = (W - 1) / stride + 1;
+  if ((long long)batch * Ho * Wo > 0x7fffffffll) return ET_EINVAL;
+  const int kk = taps * taps * C, rows = batch * Ho * Wo;
+  et::GemmDesc g;
+  g.conv_h = H; g.conv_w = W; g.conv_c = C; g.conv_taps = taps; g.conv_stride = stride; g.tile = tile;
+  g.split_k = split_k < 1 ? 1 : split_k; g.partials = partials;
+  if (op == 0) {
+    g.A = (const et::bf16*)x; g.B = (const et::bf16*)w_or_d; g.C = out;
+    g.M = rows; g.N = N; g.K = kk; g.lda = kk; g.ldb = kk; g.ldc = N;
+    if (split_k == 0) et::gemm_bf16_plan_conv(g.M, g.N, g.K, &g.tile, &g.split_k);
+  } else if (op == 1) {
+    g.A = (const et::bf16*)w_or_d; g.a_t = true; g.lda = N;
+    g.B = (const et::bf16*)x; g.b_t = true; g.ldb = kk;
+    g.M = N; g.N = kk; g.K = rows; g.C = out; g.ldc = kk; g.c_f32 = true;
+    if (split_k == 0) et::gemm_bf16_plan_conv_dw(g.M, g.N, g.K, &g.tile, &g.split_k);
+  } else {
+    return ET_EINVAL;
+  }
+  const hipError_t e = et::gemm_bf16(g, (hipStream_t)stream);
+  if (e == hipErrorInvalidValue) return ET_EINVAL;
+  return e == hipSuccess ? ET_OK : ET_EHIP;
+}
+
 extern "C" size_t et_debug_depthwise3x3_ws_floats(int batch, int H, int W, int C, int stride) {
   if (batch < 1 || H < 1 || W < 1 || C < 8 || (C & 7) || (stride != 1 && stride != 2)) return 0;
   const int R = et::depthwise3x3_dw_rows(batch, H, W, C, stride);

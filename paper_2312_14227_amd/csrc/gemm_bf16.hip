@@ -241,13 +241,22 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   if (d.bias && !aligned(d.bias, 8)) return hipErrorInvalidValue;
   const bool conv = d.conv_c > 0;
   const bool conv_dw = conv && d.a_t && d.b_t;
-  if (conv_dw) {   // B is the activation; the reduction runs over its pixels
-    if ((d.conv_c & 7) || d.conv_h < 1 || d.conv_w < 1 || d.conv_h > 4095 || d.conv_w > 4095 || d.N != 9 * d.conv_c ||
-        (d.K % (d.conv_h * d.conv_w)) || (d.K % gemm::PBK) || d.z_outer != 1 || d.z_inner != 1 || !d.c_f32)
+  const int taps2 = d.conv_taps * d.conv_taps;
+  int conv_ho = 0, conv_wo = 0;
+  if (conv) {
+    if ((d.conv_taps != 1 && d.conv_taps != 3) || (d.conv_stride != 1 && d.conv_stride != 2) || d.conv_h < 1 || d.conv_w < 1 ||
+        d.conv_h > 4095 || d.conv_w > 4095)
+      return hipErrorInvalidValue;
+    conv_ho = (d.conv_h - 1) / d.conv_stride + 1;
+    conv_wo = (d.conv_w - 1) / d.conv_stride + 1;
+  }
+  if (conv_dw) {   // B is the activation; the reduction runs over the output pixels
+    if ((d.conv_c & 7) || d.N != taps2 * d.conv_c || (d.K % (conv_ho * conv_wo)) || (d.K % gemm::PBK) || d.z_outer != 1 ||
+        d.z_inner != 1 || !d.c_f32)
       return hipErrorInvalidValue;
   } else if (conv) {
-    if ((d.conv_c % gemm::PBK) || d.conv_h < 1 || d.conv_w < 1 || d.K != 9 * d.conv_c || (d.M % (d.conv_h * d.conv_w)) ||
-        d.a_t || d.b_t || d.z_outer != 1 || d.z_inner != 1)
+    if ((d.conv_c % gemm::PBK) || d.K != taps2 * d.conv_c || (d.M % (conv_ho * conv_wo)) || d.a_t || d.b_t || d.z_outer != 1 ||
+        d.z_inner != 1)
       return hipErrorInvalidValue;
     // a split reduction finishes in a second kernel that applies the epilogue: outputs without padding
     if (d.split_k > 1 && (!d.partials || !aligned(d.partials, 16) || d.ldc != d.N || (d.N & 3) || d.c_f32 || d.residual ||
@@ -269,6 +278,7 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   p.alpha = d.alpha; p.bias = d.bias; p.gain = d.gain; p.gain2 = d.gain2; p.bias2 = d.bias2; p.residual = d.residual; p.ldr = d.ldr;
   p.C = d.C; p.ldc = d.ldc; p.C2 = d.C2; p.U = d.U;
   p.cH = d.conv_h; p.cW = d.conv_w; p.cC = d.conv_c;
+  p.cT = d.conv_taps; p.cS = d.conv_stride; p.cHo = conv_ho; p.cWo = conv_wo;
   p.act_lo = d.act_lo; p.act_hi = d.act_hi; p.mask_hi = d.mask_hi;
   int zdim = d.z_outer * d.z_inner;
   int epi;

@@ -84,7 +84,8 @@ struct Params {
   const bf16* U;
   float act_lo, act_hi;  // E_AFFINE, E_AFFINE_ADD: the activation is a clamp to [act_lo, act_hi] (0, +inf: ReLU; 0, 6: ReLU6; -inf, +inf: none)
   float mask_hi;         // E_RELU_MASK passes where 0 < U < mask_hi
-  int cH, cW, cC;        // implicit 3x3 convolution (gemm_pp_kernel<.., CONV>): input height, width, channels
+  int cH, cW, cC;        // implicit convolution (gemm_pp_kernel<.., CONV>): input height, width, channels;
+  int cT, cS, cHo, cWo;  // taps per side (3, or 1 for a strided 1x1), stride, output height and width
 };
 
 // GELU (exact erf form) and its derivative from one exponential: with x = u / sqrt(2),
@@ -904,14 +905,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(Params g) {
 constexpr int PBK = 64;
 
 //
-// CONV = 1: the A operand is the im2col matrix of a 3x3 / stride 1 / zero padding 1 convolution
-// that is never written: row m is output pixel m of an NHWC activation [.., cH, cW, cC] (g.A),
-// column (tap, c) is input channel c at the pixel shifted by the tap.  cC is a multiple of 64, so
-// a K slice is 64 channels of one tap: the same 128-byte row pieces as in a stored matrix, read
-// from the shifted pixel, or replaced by zeros outside the image.
-// CONV = 2 (weight gradient, AT = BT = true): the B operand [pixel][(tap, c)] is that same matrix,
-// gathered from the activation g.B; the reduction runs over the pixels, 64 per slice, and each
-// 16-byte piece (8 channels of one tap, fixed for a lane) comes from the pixel shifted by its tap.
+// CONV = 1: the A operand is the im2col matrix of a 3x3 / zero padding 1 convolution of stride 1 or 2 (or of a
+// strided 1x1 convolution) that is never written: row m is output pixel m, column (tap, c) is input channel c of
+// the NHWC activation [.., cH, cW, cC] (g.A) at the pixel that tap reads.  cC is a multiple of 64, so a K slice
+// is 64 channels of one tap: the same 128-byte row pieces as in a stored matrix, read from the shifted pixel,
+// or replaced by zeros outside the image.
+// CONV = 2 (weight gradient, AT = BT = true): the B operand [output pixel][(tap, c)] is that same matrix,
+// gathered from the activation g.B; the reduction runs over the output pixels, 64 per slice, and each
+// 16-byte piece (8 channels of one tap, fixed for a lane) comes from the input pixel its tap reads.
 template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, int EPI, int CONV = 0>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   constexpr int NW = WGM * WGN;
@@ -993,9 +994,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
       if (CONV == 1) {  // centre tap of the row's pixel
         const int row = q * 8 + (lane >> 3), chunk = lane & 7;
         const int m = min(m0 + row, g.M - 1);
-        cow[CONV == 1 ? i : 0] = m % g.cW;
-        coh[CONV == 1 ? i : 0] = (m / g.cW) % g.cH;
-        ga[i] = A + (long long)m * g.cC + chunk * 8;
+        const int wo = m % g.cWo, t = m / g.cWo, ho = t % g.cHo, img = t / g.cHo;
+        cow[CONV == 1 ? i : 0] = wo * g.cS;           // input coordinates of the centre tap
+        coh[CONV == 1 ? i : 0] = ho * g.cS;
+        ga[i] = A + ((long long)(img * g.cH + ho * g.cS) * g.cW + wo * g.cS) * g.cC + chunk * 8;
       } else if (!AT) {
         const int row = q * 8 + (lane >> 3), chunk = lane & 7;
         ga[i] = A + (long long)min(m0 + row, g.M - 1) * g.lda + k_begin + chunk * 8;
@@ -1018,11 +1020,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
         int gj = n0 + j * 8;
         if (gj + 8 > g.N) gj = 0;                 // N = 9 cC is a multiple of 8
         const int tap = gj / g.cC, ch = gj % g.cC;
-        const int dy = tap / 3 - 1, dx = tap % 3 - 1;
-        const int pix = k_begin + k;
-        bpix[CONV == 2 ? i : 0] = ((dy + 1) << 26) | ((dx + 1) << 24) | (((pix / g.cW) % g.cH) << 12) | (pix % g.cW);
+        const int dy = tap / g.cT - (g.cT >> 1), dx = tap % g.cT - (g.cT >> 1);
+        const int pix = k_begin + k;               // output pixel of this k-row
+        const int wo = pix % g.cWo, t = pix / g.cWo, ho = t % g.cHo, img = t / g.cHo;
+        bpix[CONV == 2 ? i : 0] = ((dy + 1) << 26) | ((dx + 1) << 24) | (ho << 12) | wo;
         boff[CONV == 2 ? i : 0] = (dy * g.cW + dx) * g.cC;
-        gb[i] = B + (long long)pix * g.cC + ch;   // centre tap
+        gb[i] = B + ((long long)(img * g.cH + ho * g.cS) * g.cW + wo * g.cS) * g.cC + ch;   // centre tap
       } else if (!BT) {
         const int row = q * 8 + (lane >> 3), chunk = lane & 7;
         gb[i] = B + (long long)min(n0 + row, g.N - 1) * g.ldb + k_begin + chunk * 8;
@@ -1038,15 +1041,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
     if (CONV == 1) {
       const int tap0 = k_begin / g.cC;
       c_sub = k_begin % g.cC;
-      c_dy = tap0 / 3 - 1;
-      c_dx = tap0 % 3 - 1;
+      c_dy = tap0 / g.cT - (g.cT >> 1);
+      c_dx = tap0 % g.cT - (g.cT >> 1);
       c_off_a = (long long)(c_dy * g.cW + c_dx) * g.cC + c_sub;
     }
   };
   const long long a_step = AT ? (long long)PBK * g.lda : PBK;
-  const long long b_step = CONV == 2 ? (long long)PBK * g.cC : (BT ? (long long)PBK * g.ldb : PBK);
-  // CONV 2: a slice moves every piece 64 pixels on: (h, w) advance by (64 / cW, 64 % cW) with carries
-  const int b_sw = CONV == 2 ? PBK % g.cW : 0, b_sh = CONV == 2 ? (PBK / g.cW) % g.cH : 0;
+  const long long b_step = BT ? (long long)PBK * g.ldb : PBK;
+  // CONV 2: a slice moves every piece 64 output pixels on: (image, ho, wo) advance by (64 / (cHo cWo), (64 / cWo) % cHo,
+  // 64 % cWo) with carries, and the input pointer follows by the corresponding number of input pixels
+  const int b_sw = CONV == 2 ? PBK % g.cWo : 0, b_sh = CONV == 2 ? (PBK / g.cWo) % g.cHo : 0,
+            b_sb = CONV == 2 ? PBK / (g.cWo * g.cHo) : 0;
 
   f32x16 acc[MI][NI];
 
@@ -1102,7 +1107,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
     c_sub += PBK;
     if (c_sub == g.cC) {
       c_sub = 0;
-      if (++c_dx == 2) { c_dx = -1; c_dy++; }
+      if (++c_dx > (g.cT >> 1)) { c_dx = -(g.cT >> 1); c_dy++; }
     }
     c_off_a = (long long)(c_dy * g.cW + c_dx) * g.cC + c_sub;
   };
@@ -1124,16 +1129,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
     const int k = CONV == 2 ? i : 0;
     const int dy = (bpix[k] >> 26) - 1, dx = ((bpix[k] >> 24) & 3) - 1;
     int h = (bpix[k] >> 12) & 4095, w = bpix[k] & 4095;
-    const bool ok = (unsigned)(h + dy) < (unsigned)g.cH && (unsigned)(w + dx) < (unsigned)g.cW;
+    const bool ok = (unsigned)(h * g.cS + dy) < (unsigned)g.cH && (unsigned)(w * g.cS + dx) < (unsigned)g.cW;
     rb[i] = *(const u32x4*)(gb[i] + (ok ? boff[k] : 0));
     b_ok = ok ? (b_ok | (1u << i)) : (b_ok & ~(1u << i));
     if (advance) {
-      gb[i] += b_step;
-      w += b_sw;
-      h += b_sh;
-      if (w >= g.cW) { w -= g.cW; h++; }
-      if (h >= g.cH) h -= g.cH;
-      bpix[k] = (bpix[k] & ~0xffffff) | (h << 12) | w;
+      int w2 = w + b_sw, h2 = h + b_sh, img = b_sb;
+      if (w2 >= g.cWo) { w2 -= g.cWo; h2++; }
+      if (h2 >= g.cHo) { h2 -= g.cHo; img++; }
+      gb[i] += ((long long)(img * g.cH + (h2 - h) * g.cS) * g.cW + (w2 - w) * g.cS) * g.cC;
+      bpix[k] = (bpix[k] & ~0xffffff) | (h2 << 12) | w2;
     }
   };
   auto load_b_regs = [&](bool advance) {

@@ -60,14 +60,14 @@ struct GemmDesc {
   bool c_f32 = false;
   bf16* C2 = nullptr;              // EPI_GELU_FWD
   const bf16* U = nullptr;         // EPI_GELU_BWD, EPI_AFFINE_ADD_RELU, EPI_RELU_MASK: same leading dimension as C
-  // implicit 3x3 / stride 1 / zero padding 1 convolution (conv_c > 0): A is the NHWC activation
-  // [M / (conv_h conv_w), conv_h, conv_w, conv_c] itself, standing for its im2col matrix [M][9 conv_c]
-  // (K = 9 conv_c, column (tap, c)); conv_c must be a multiple of 64; row-major operands, no batching; split_k > 1
-  // (with `partials`, ldc == N, bf16 outputs, not with the ADD / GELU modes) reduces in a second kernel that also
-  // applies the epilogue.
-  // With a_t and b_t (weight gradient): B is the activation standing for [K pixels][N = 9 conv_c]; conv_c % 8 == 0,
-  // K a multiple of 64, fp32 output, split allowed
-  int conv_h = 0, conv_w = 0, conv_c = 0;
+  // implicit convolution (conv_c > 0), 3x3 with zero padding 1 (conv_taps = 3) or 1x1 (conv_taps = 1), stride
+  // conv_stride (1 or 2): A is the NHWC activation [batch, conv_h, conv_w, conv_c] itself, standing for its im2col
+  // matrix [M = batch Ho Wo][K = taps^2 conv_c] (column (tap, c); Ho = (conv_h - 1) / stride + 1); conv_c must be a
+  // multiple of 64; row-major operands, no batching; split_k > 1 (with `partials`, ldc == N, bf16 outputs, not with
+  // the ADD / GELU modes) reduces in a second kernel that also applies the epilogue.
+  // With a_t and b_t (weight gradient): B is the activation standing for [K = batch Ho Wo output pixels]
+  // [N = taps^2 conv_c]; conv_c % 8 == 0, K a multiple of 64, fp32 output, split allowed
+  int conv_h = 0, conv_w = 0, conv_c = 0, conv_taps = 3, conv_stride = 1;
   int tile = 0;                    // 0 = choose by shape; else a TileId (tuning/tests)
 };
 

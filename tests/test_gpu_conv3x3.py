@@ -171,3 +171,75 @@ def _case_split(batch, H, W, C, N, mode, split, tile, seed):
                                                       (2, 7, 9, 192, 128, 5, 13), (32, 7, 7, 512, 512, 0, 0), (32, 14, 14, 256, 256, 0, 0)])
 def test_conv3x3_split_reduction(batch, H, W, C, N, split, tile, mode):
     _case_split(batch, H, W, C, N, mode, split, tile, seed=mode * 31 + H + N)
+
+
+def _case_gathered(batch, H, W, C, N, taps, stride, tile, seed, split=1):
+    """Forward product and weight gradient of a gathered convolution with `taps` per side and `stride` against the
+    oracle's convolution (explicit im2col, float64)."""
+    import torch
+    from paper_2312_14227_amd import binding as et
+    rng = np.random.default_rng(seed)
+    x = bf16_round(rng.standard_normal((batch, H, W, C)).astype(np.float32))
+    w = bf16_round((rng.standard_normal((N, taps, taps, C)) / np.sqrt(taps * taps * C)).astype(np.float32))
+    cv = R.Conv(x.astype(np.float64), w.astype(np.float64), stride)
+    Ho, Wo = cv.out.shape[1:3]
+    assert (Ho, Wo) == ((H - 1) // stride + 1, (W - 1) // stride + 1)
+    rows, kk = batch * Ho * Wo, taps * taps * C
+    d = bf16_round(rng.standard_normal((batch, Ho, Wo, N)).astype(np.float32))
+    dev = "cuda:0"
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(torch.bfloat16)
+    xt, wt, dt = to(x), to(w), to(d)
+    stream = torch.cuda.current_stream().cuda_stream
+    cols = cv.cols.reshape(rows, kk)
+    if C % 64 == 0:
+        out = torch.full((rows, N), float("nan"), device=dev, dtype=torch.bfloat16)
+        assert et.et_debug_conv_gathered(0, xt.data_ptr(), wt.data_ptr(), out.data_ptr(), batch, H, W, C, N, taps, stride,
+                                         1, 0, tile, stream) == 0
+        torch.cuda.synchronize()
+        ref = cv.out.reshape(rows, N)
+        got = out.float().cpu().numpy().astype(np.float64)
+        bound = 2e-6 * (np.abs(cols) @ np.abs(cv.wm).T) * np.sqrt(kk) + 1e-6 + 2.0 ** -8 * np.abs(ref)
+        bad = ~(np.abs(got - ref) <= bound)
+        assert not bad.any(), ("forward", int(bad.sum()), float(np.nanmax(np.abs(got - ref))))
+    if rows % 64 == 0:
+        dw = torch.full((N, kk), float("nan"), device=dev, dtype=torch.float32)
+        part = torch.empty(N * kk * max(split, 1) if split else N * kk * 256, device=dev, dtype=torch.float32)
+        assert et.et_debug_conv_gathered(1, xt.data_ptr(), dt.data_ptr(), dw.data_ptr(), batch, H, W, C, N, taps, stride,
+                                         split, part.data_ptr(), tile if tile in (0, 11, 13) else 0, stream) == 0
+        torch.cuda.synchronize()
+        ref = cv.dw(d.astype(np.float64)).reshape(N, kk)
+        got = dw.cpu().numpy().astype(np.float64)
+        bound = 2e-6 * (np.abs(d.reshape(rows, N).astype(np.float64)).T @ np.abs(cols)) * np.sqrt(rows) + 1e-6
+        bad = ~(np.abs(got - ref) <= bound)
+        assert not bad.any(), ("dw", int(bad.sum()), float(np.nanmax(np.abs(got - ref))))
+
+
+# (batch, H, W, C, N, taps, stride): images smaller and larger than a 64-pixel slice, odd sizes (the last input row and
+# column are then read by the centre tap), output rows that do and do not divide a slice, the ResNet-50 stage shapes
+STRIDED = [(2, 16, 16, 64, 64, 3, 2), (1, 32, 32, 128, 72, 3, 2), (4, 15, 17, 64, 136, 3, 2), (2, 56, 56, 128, 128, 3, 2),
+           (8, 14, 14, 512, 512, 3, 2), (2, 16, 16, 64, 128, 1, 2), (4, 15, 17, 64, 264, 1, 2), (2, 56, 56, 256, 512, 1, 2),
+           (64, 3, 3, 64, 64, 3, 2), (2, 16, 16, 64, 64, 3, 1), (2, 16, 16, 8, 16, 3, 2), (2, 16, 16, 24, 16, 1, 2)]
+
+
+@pytest.mark.parametrize("batch,H,W,C,N,taps,stride", STRIDED)
+@pytest.mark.parametrize("tile", [0, 11, 13, 15])
+def test_gathered_convolution_with_stride(batch, H, W, C, N, taps, stride, tile):
+    _case_gathered(batch, H, W, C, N, taps, stride, tile, seed=H * 7 + C + taps + tile)
+
+
+@pytest.mark.parametrize("split", [0, 2, 3])
+def test_gathered_strided_weight_gradient_split(split):
+    _case_gathered(4, 28, 28, 64, 64, 3, 2, 0, seed=split, split=split)
+    _case_gathered(4, 28, 28, 64, 96, 1, 2, 0, seed=split + 10, split=split)
+
+
+def test_gathered_convolution_rejects_bad_arguments():
+    import torch
+    from paper_2312_14227_amd import binding as et
+    t = torch.zeros(1 << 18, device="cuda:0", dtype=torch.float32)
+    p = t.data_ptr()
+    assert et.et_debug_conv_gathered(0, p, p, p, 1, 8, 8, 64, 64, 2, 1) == -1     # taps
+    assert et.et_debug_conv_gathered(0, p, p, p, 1, 8, 8, 64, 64, 3, 3) == -1     # stride
+    assert et.et_debug_conv_gathered(0, p, p, p, 1, 8, 8, 48, 64, 3, 2) == -1     # channels
+    assert et.et_debug_conv_gathered(1, p, p, p, 1, 10, 10, 8, 64, 3, 2) == -1    # 25 output pixels
+    assert et.et_debug_conv_gathered(2, p, p, p, 1, 8, 8, 64, 64, 3, 2) == -1     # op
