@@ -62,6 +62,16 @@ int et_debug_conv3x3_dw(const void* x, const void* d, float* dw, int batch, int 
 int et_debug_conv_gathered(int op, const void* x, const void* w_or_d, void* out, int batch, int H, int W, int C, int N,
                            int taps, int stride, int split_k, float* partials, int tile, void* stream);
 
+/* Stem convolution (7x7, stride 2, zero padding 3, C <= 4 input channels) as a gathered GEMM over a padded copy of
+ * the image.  x bf16 NHWC [batch][H][W][C]; Ho = (H - 1) / 2 + 1, Wo likewise; N a multiple of 8.
+ *   op 0 forward: w_or_d = weights bf16 [N][7][7][C]; out fp32 [batch*Ho*Wo][N];
+ *   op 1 weight gradient: w_or_d = d bf16 [batch*Ho*Wo][N]; out fp32 [N][7][7][C]; batch*Ho*Wo a multiple of 64.
+ * ws = device scratch of et_debug_stem_ws_bytes(..) bytes (0 = arguments out of range), 256-byte aligned.
+ * Returns 0, -1, -3. */
+size_t et_debug_stem_ws_bytes(int batch, int H, int W, int C, int N);
+int et_debug_stem(int op, const void* x, const void* w_or_d, float* out, void* ws, int batch, int H, int W, int C, int N,
+                  void* stream);
+
 /* 3x3 depthwise convolution kernels (zero padding 1, stride 1 or 2; NHWC bf16, C a multiple of 8; weights bf16
  * [C][9]; Ho = (H - 1) / stride + 1, Wo likewise).  op selects the kernel:
  *   0 forward: a = x [batch][H][W][C], b = weights, gain, shift [C]; out0 (nullable) = z, the convolution rounded to

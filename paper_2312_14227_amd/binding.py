@@ -75,6 +75,8 @@ def _load():
         "et_debug_conv3x3_split": (C.c_int, [vp, vp, vp, vp] + [C.c_int] * 5 + [vp, vp, vp, C.c_int, C.c_int, vp, C.c_int, vp]),
         "et_debug_conv3x3_dw": (C.c_int, [vp, vp, vp] + [C.c_int] * 6 + [vp, C.c_int, vp]),
         "et_debug_conv_gathered": (C.c_int, [C.c_int, vp, vp, vp] + [C.c_int] * 8 + [vp, C.c_int, vp]),
+        "et_debug_stem_ws_bytes": (C.c_size_t, [C.c_int] * 5),
+        "et_debug_stem": (C.c_int, [C.c_int, vp, vp, vp, vp] + [C.c_int] * 5 + [vp]),
         "et_debug_conv3x3": (C.c_int, [vp, vp, vp] + [C.c_int] * 5 + [vp, vp, C.c_int, C.c_int, vp]),
         "et_debug_gemm_bf16": (C.c_int, [vp, vp, vp] + [C.c_int] * 9 + [C.c_float, vp, vp, C.c_int, vp, C.c_int, C.c_int, vp, vp]),
     }
@@ -90,7 +92,7 @@ EXPORTS = ["et_create", "et_destroy", "et_num_tensors", "et_tensor_info", "et_wo
            "et_kernel_timing", "et_kernel_timing_read", "et_last_hip_error", "et_strerror", "et_debug_gemm_bf16", "et_debug_copy", "et_debug_conv3x3",
            "et_debug_conv3x3_dw", "et_debug_depthwise3x3", "et_debug_depthwise3x3_ws_floats",
            "et_debug_activation", "et_debug_conv3x3_split", "et_debug_attention",
-           "et_debug_conv_gathered"]
+           "et_debug_conv_gathered", "et_debug_stem", "et_debug_stem_ws_bytes"]
 
 
 def strerror(status):
@@ -306,6 +308,15 @@ def et_debug_conv3x3_dw(x, d, dw, batch, H, W, Cin, N, split_k=1, partials=0, ti
 def et_debug_conv_gathered(op, x, w_or_d, out, batch, H, W, Cin, N, taps=3, stride=1, split_k=1, partials=0, tile=0, stream=0):
     return _lib.et_debug_conv_gathered(op, C.c_void_p(x), C.c_void_p(w_or_d), C.c_void_p(out), batch, H, W, Cin, N, taps, stride,
                                        split_k, C.c_void_p(partials), tile, C.c_void_p(stream))
+
+
+def et_debug_stem_ws_bytes(batch, H, W, Cin, N):
+    return int(_lib.et_debug_stem_ws_bytes(batch, H, W, Cin, N))
+
+
+def et_debug_stem(op, x, w_or_d, out, ws, batch, H, W, Cin, N, stream=0):
+    return _lib.et_debug_stem(op, C.c_void_p(x), C.c_void_p(w_or_d), C.c_void_p(out), C.c_void_p(ws), batch, H, W, Cin, N,
+                              C.c_void_p(stream))
 
 
 def et_debug_activation(ctx, name):

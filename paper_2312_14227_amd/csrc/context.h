@@ -111,6 +111,8 @@ struct et_ctx {
        *rdsc = nullptr, *rdcols = nullptr;
   uint8_t* pool_arg = nullptr;
   float *stem_dw8 = nullptr, *stem_z32 = nullptr;
+  bf16* stem_xpad = nullptr;   // ResNet stem as a gathered GEMM: the image padded to 4 channels and by the window
+  int stem_hp = 0, stem_wp = 0;
 
   // plain convolution stack (VGG family): one unit per convolution (y: after bias + ReLU),
   // per stage the pooled output and the chosen taps, the inputs of the linear layers

@@ -545,6 +545,37 @@ __global__ void strip_rows_kernel(const float* __restrict__ in, float* __restric
   out[i] = in[(i / K) * Kc + i % K];
 }
 
+// Operands of the stem convolution (7x7, stride 2, zero padding 3, at most 4 input channels) in the form its
+// gathered GEMM reads.  Image: [B][H][W][C] -> [B][Hp][Wp][4] with pixel (h, w) at (h + 3, w + 3) and zeros elsewhere,
+// one thread per padded pixel (8 bytes).  Weight: [O][7][7][C] -> [O][8][8][4], zero outside the 7x7xC window.
+// Weight gradient: float [O][8][8][4] -> [O][7][7][C].
+__global__ void stem_pad_image_kernel(const bf16* __restrict__ x, bf16* __restrict__ out, int H, int W, int C, int Hp, int Wp,
+                                      long long total) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int wp = (int)(i % Wp), hp = (int)((i / Wp) % Hp);
+  const long long b = i / ((long long)Wp * Hp);
+  const int h = hp - 3, w = wp - 3;
+  bf16x4 v = {(bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f};
+  if ((unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W) {
+    const bf16* src = x + ((b * H + h) * W + w) * C;
+    for (int c = 0; c < C; c++) v[c] = src[c];
+  }
+  *(bf16x4*)(out + i * 4) = v;
+}
+__global__ void stem_pack_weight_kernel(const bf16* __restrict__ w, bf16* __restrict__ out, int O, int C) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;   // index into out: (o, ky, kx, c)
+  if (i >= O * 256) return;
+  const int c = i & 3, kx = (i >> 2) & 7, ky = (i >> 5) & 7, o = i >> 8;
+  out[i] = (ky < 7 && kx < 7 && c < C) ? w[((o * 7 + ky) * 7 + kx) * C + c] : (bf16)0.f;
+}
+__global__ void stem_unpack_dw_kernel(const float* __restrict__ in, float* __restrict__ out, int O, int C) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;   // index into out: (o, ky, kx, c)
+  if (i >= O * 49 * C) return;
+  const int c = i % C, kx = (i / C) % 7, ky = (i / (7 * C)) % 7, o = i / (49 * C);
+  out[i] = in[o * 256 + ky * 32 + kx * 4 + c];
+}
+
 // out[c][8 - tap][o] = w[o][tap][c]: the weight of the convolution that carries a 3x3 convolution's output
 // gradient back to its input (taps mirrored, channel roles exchanged)
 __global__ void flip3x3_kernel(const bf16* __restrict__ w, bf16* __restrict__ out, int O, int C) {
@@ -739,6 +770,26 @@ hipError_t pad_rows(const bf16* in, bf16* out, int rows, int K, int Kc, hipStrea
 hipError_t flip3x3(const bf16* w, bf16* out, int O, int C, hipStream_t s) {
   if (O < 1 || C < 1 || (long long)O * 9 * C > 0x7fffffffll) return hipErrorInvalidValue;
   hipLaunchKernelGGL(flip3x3_kernel, dim3((O * 9 * C + 255) / 256), dim3(256), 0, s, w, out, O, C);
+  return hipGetLastError();
+}
+
+hipError_t stem_pad_image(const bf16* x, bf16* out, int B, int H, int W, int C, int Hp, int Wp, hipStream_t s) {
+  if (B < 1 || H < 1 || W < 1 || C < 1 || C > 4 || Hp < H + 3 || Wp < W + 3 || !al16(out)) return hipErrorInvalidValue;
+  const long long total = (long long)B * Hp * Wp;
+  if (total > 0x7fffffffll * 256) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(stem_pad_image_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, x, out, H, W, C, Hp, Wp, total);
+  return hipGetLastError();
+}
+
+hipError_t stem_pack_weight(const bf16* w, bf16* out, int O, int C, hipStream_t s) {
+  if (O < 1 || C < 1 || C > 4 || O > (1 << 20)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(stem_pack_weight_kernel, dim3(O), dim3(256), 0, s, w, out, O, C);
+  return hipGetLastError();
+}
+
+hipError_t stem_unpack_dw(const float* in, float* out, int O, int C, hipStream_t s) {
+  if (O < 1 || C < 1 || C > 4 || O > (1 << 20)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(stem_unpack_dw_kernel, dim3((O * 49 * C + 255) / 256), dim3(256), 0, s, in, out, O, C);
   return hipGetLastError();
 }
 

@@ -99,6 +99,60 @@ extern "C" int et_debug_conv_gathered(int op, const void* x, const void* w_or_d,
   return e == hipSuccess ? ET_OK : ET_EHIP;
 }
 
+namespace {
+struct StemPlan { int Ho, Wo, Hp, Wp, split; size_t off_w, off_dw, off_part, bytes; };
+bool stem_plan(int batch, int H, int W, int C, int N, StemPlan* p) {
+  if (batch < 1 || H < 1 || W < 1 || C < 1 || C > 4 || N < 8 || (N & 7)) return false;
+  p->Ho = (H - 1) / 2 + 1; p->Wo = (W - 1) / 2 + 1;
+  p->Hp = 2 * (p->Ho - 1) + 8; p->Wp = 2 * (p->Wo - 1) + 8;
+  if (p->Hp > 4095 || p->Wp > 4095 || (long long)batch * p->Ho * p->Wo > 0x7fffffffll) return false;
+  int tile;
+  et::gemm_bf16_plan_conv_dw(N, 256, batch * p->Ho * p->Wo, &tile, &p->split);
+  auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+  p->off_w = up((size_t)batch * p->Hp * p->Wp * 4 * 2);
+  p->off_dw = p->off_w + up((size_t)N * 256 * 2);
+  p->off_part = p->off_dw + up((size_t)N * 256 * 4);
+  p->bytes = p->off_part + up(et::gemm_bf16_partial_elems(N, 256, p->split) * 4 + 256);
+  return true;
+}
+}  // namespace
+
+extern "C" size_t et_debug_stem_ws_bytes(int batch, int H, int W, int C, int N) {
+  StemPlan p;
+  return stem_plan(batch, H, W, C, N, &p) ? p.bytes : 0;
+}
+
+extern "C" int et_debug_stem(int op, const void* x, const void* w_or_d, float* out, void* ws, int batch, int H, int W, int C,
+                             int N, void* stream) {
+  StemPlan p;
+  if (!x || !w_or_d || !out || !ws || !stem_plan(batch, H, W, C, N, &p)) return ET_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  et::bf16* xpad = (et::bf16*)ws;
+  et::bf16* w8 = (et::bf16*)((char*)ws + p.off_w);
+  float* dw8 = (float*)((char*)ws + p.off_dw);
+  hipError_t e = et::stem_pad_image((const et::bf16*)x, xpad, batch, H, W, C, p.Hp, p.Wp, s);
+  if (e != hipSuccess) return e == hipErrorInvalidValue ? ET_EINVAL : ET_EHIP;
+  et::GemmDesc g;
+  g.conv_h = p.Hp; g.conv_w = p.Wp; g.conv_c = 4; g.conv_taps = 7; g.conv_stride = 2; g.c_f32 = true;
+  const int rows = batch * p.Ho * p.Wo;
+  if (op == 0) {
+    e = et::stem_pack_weight((const et::bf16*)w_or_d, w8, N, C, s);
+    if (e != hipSuccess) return ET_EHIP;
+    g.A = xpad; g.B = w8; g.C = out; g.M = rows; g.N = N; g.K = 256; g.lda = 256; g.ldb = 256; g.ldc = N;
+    e = et::gemm_bf16(g, s);
+  } else if (op == 1) {
+    g.A = (const et::bf16*)w_or_d; g.a_t = true; g.lda = N; g.B = xpad; g.b_t = true; g.ldb = 256;
+    g.M = N; g.N = 256; g.K = rows; g.C = dw8; g.ldc = 256;
+    g.split_k = p.split; g.partials = (float*)((char*)ws + p.off_part);
+    e = et::gemm_bf16(g, s);
+    if (e == hipSuccess) e = et::stem_unpack_dw(dw8, out, N, C, s);
+  } else {
+    return ET_EINVAL;
+  }
+  if (e == hipErrorInvalidValue) return ET_EINVAL;
+  return e == hipSuccess ? ET_OK : ET_EHIP;
+}
+
 extern "C" size_t et_debug_depthwise3x3_ws_floats(int batch, int H, int W, int C, int stride) {
   if (batch < 1 || H < 1 || W < 1 || C < 8 || (C & 7) || (stride != 1 && stride != 2)) return 0;
   const int R = et::depthwise3x3_dw_rows(batch, H, W, C, stride);

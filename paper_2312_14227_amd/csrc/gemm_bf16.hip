@@ -243,14 +243,26 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   const bool conv_dw = conv && d.a_t && d.b_t;
   const int taps2 = d.conv_taps * d.conv_taps;
   int conv_ho = 0, conv_wo = 0;
-  if (conv) {
+  const bool stem = conv && d.conv_taps == 7;
+  if (stem) {   // padded image [.., conv_h, conv_w, 4]; the window is widened to 8 x 8
+    if (d.conv_c != 4 || d.conv_stride != 2 || d.conv_h < 8 || d.conv_w < 8 || (d.conv_w & 1) || d.conv_h > 4095 || d.conv_w > 4095 ||
+        d.z_outer != 1 || d.z_inner != 1)
+      return hipErrorInvalidValue;
+    conv_ho = (d.conv_h - 8) / 2 + 1;
+    conv_wo = (d.conv_w - 8) / 2 + 1;
+    if (conv_dw ? (d.N != 256 || (d.K % (conv_ho * conv_wo)) || (d.K % gemm::PBK) || !d.c_f32)
+                : (d.K != 256 || (d.M % (conv_ho * conv_wo)) || d.a_t || d.b_t || d.split_k > 1 || d.mode != EPI_PLAIN || !d.c_f32 ||
+                   d.residual))
+      return hipErrorInvalidValue;
+  } else if (conv) {
     if ((d.conv_taps != 1 && d.conv_taps != 3) || (d.conv_stride != 1 && d.conv_stride != 2) || d.conv_h < 1 || d.conv_w < 1 ||
         d.conv_h > 4095 || d.conv_w > 4095)
       return hipErrorInvalidValue;
     conv_ho = (d.conv_h - 1) / d.conv_stride + 1;
     conv_wo = (d.conv_w - 1) / d.conv_stride + 1;
   }
-  if (conv_dw) {   // B is the activation; the reduction runs over the output pixels
+  if (stem) {
+  } else if (conv_dw) {   // B is the activation; the reduction runs over the output pixels
     if ((d.conv_c & 7) || d.N != taps2 * d.conv_c || (d.K % (conv_ho * conv_wo)) || (d.K % gemm::PBK) || d.z_outer != 1 ||
         d.z_inner != 1 || !d.c_f32)
       return hipErrorInvalidValue;
@@ -278,7 +290,7 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   p.alpha = d.alpha; p.bias = d.bias; p.gain = d.gain; p.gain2 = d.gain2; p.bias2 = d.bias2; p.residual = d.residual; p.ldr = d.ldr;
   p.C = d.C; p.ldc = d.ldc; p.C2 = d.C2; p.U = d.U;
   p.cH = d.conv_h; p.cW = d.conv_w; p.cC = d.conv_c;
-  p.cT = d.conv_taps; p.cS = d.conv_stride; p.cHo = conv_ho; p.cWo = conv_wo;
+  p.cT = stem ? 8 : d.conv_taps; p.cS = d.conv_stride; p.cHo = conv_ho; p.cWo = conv_wo;
   p.act_lo = d.act_lo; p.act_hi = d.act_hi; p.mask_hi = d.mask_hi;
   int zdim = d.z_outer * d.z_inner;
   int epi;
@@ -343,6 +355,8 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
       case T_PP_256x192: BM = 256; BN = 192; fn = gemm::pp_convdw_256x192(epi); break;
       default: BM = 256; BN = 256; fn = gemm::pp_convdw_256x256(epi); break;
     }
+  } else if (stem) {   // few output channels, fp32 result
+    BM = 512; BN = 64; fn = gemm::pp_conv_512x64(epi);
   } else if (conv) {
     switch (choose_conv_tile(d)) {
       case T_PP_512x64: BM = 512; BN = 64; fn = gemm::pp_conv_512x64(epi); break;

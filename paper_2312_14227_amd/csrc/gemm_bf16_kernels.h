@@ -913,6 +913,10 @@ constexpr int PBK = 64;
 // CONV = 2 (weight gradient, AT = BT = true): the B operand [output pixel][(tap, c)] is that same matrix,
 // gathered from the activation g.B; the reduction runs over the output pixels, 64 per slice, and each
 // 16-byte piece (8 channels of one tap, fixed for a lane) comes from the input pixel its tap reads.
+// Stem form of both (cT == 8: a 7x7 / stride 2 / zero padding 3 convolution of an image with at most 4 channels):
+// the activation is the image padded to 4 channels and by 3 pixels at the top and left (zeros up to cH x cW with
+// cW even), the window is widened to 8 x 8 with zero weights, so K = 8 * 8 * 4 = 256 and a K slice is two window
+// rows of 64 contiguous bytes each, 16-byte aligned, that never leave the padded image: no validity test.
 template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, int EPI, int CONV = 0>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   constexpr int NW = WGM * WGN;
@@ -998,6 +1002,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
         cow[CONV == 1 ? i : 0] = wo * g.cS;           // input coordinates of the centre tap
         coh[CONV == 1 ? i : 0] = ho * g.cS;
         ga[i] = A + ((long long)(img * g.cH + ho * g.cS) * g.cW + wo * g.cS) * g.cC + chunk * 8;
+        if (g.cT == 8) {   // stem form: chunk = (row of the pair, pixel pair); nothing lies outside the padded image
+          cow[CONV == 1 ? i : 0] = 0;
+          coh[CONV == 1 ? i : 0] = 0;
+          ga[i] = A + ((long long)(img * g.cH + ho * 2 + (chunk >> 2)) * g.cW + wo * 2) * 4 + (chunk & 3) * 8;
+        }
       } else if (!AT) {
         const int row = q * 8 + (lane >> 3), chunk = lane & 7;
         ga[i] = A + (long long)min(m0 + row, g.M - 1) * g.lda + k_begin + chunk * 8;
@@ -1019,12 +1028,18 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
         const int k = pos / CR, j = (pos % CR) ^ ((k & 3) << TSH_B);
         int gj = n0 + j * 8;
         if (gj + 8 > g.N) gj = 0;                 // N = 9 cC is a multiple of 8
-        const int tap = gj / g.cC, ch = gj % g.cC;
-        const int dy = tap / g.cT - (g.cT >> 1), dx = tap % g.cT - (g.cT >> 1);
+        const int tap = gj / g.cC;
+        int ch = gj % g.cC;
+        int dy = tap / g.cT - (g.cT >> 1), dx = tap % g.cT - (g.cT >> 1);
+        int off = (dy * g.cW + dx) * g.cC;
+        if (g.cT == 8) {   // stem form: column = (row 0..7, pixel pair 0..3, 8 values), always inside the padded image
+          off = ((gj >> 5) * g.cW) * 4 + ((gj >> 3) & 3) * 8;
+          dy = dx = ch = 0;
+        }
         const int pix = k_begin + k;               // output pixel of this k-row
         const int wo = pix % g.cWo, t = pix / g.cWo, ho = t % g.cHo, img = t / g.cHo;
         bpix[CONV == 2 ? i : 0] = ((dy + 1) << 26) | ((dx + 1) << 24) | (ho << 12) | wo;
-        boff[CONV == 2 ? i : 0] = (dy * g.cW + dx) * g.cC;
+        boff[CONV == 2 ? i : 0] = off;
         gb[i] = B + ((long long)(img * g.cH + ho * g.cS) * g.cW + wo * g.cS) * g.cC + ch;   // centre tap
       } else if (!BT) {
         const int row = q * 8 + (lane >> 3), chunk = lane & 7;
@@ -1044,6 +1059,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
       c_dy = tap0 / g.cT - (g.cT >> 1);
       c_dx = tap0 % g.cT - (g.cT >> 1);
       c_off_a = (long long)(c_dy * g.cW + c_dx) * g.cC + c_sub;
+      if (g.cT == 8) {   // stem form: a slice is two rows of the 8 x 8 window
+        c_sub = c_dy = c_dx = 0;
+        c_off_a = (long long)(k_begin / PBK) * 2 * g.cW * 4;
+      }
     }
   };
   const long long a_step = AT ? (long long)PBK * g.lda : PBK;
@@ -1104,6 +1123,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   };
   auto conv_advance = [&](bool advance) {
     if (!advance) return;
+    if (g.cT == 8) {
+      c_off_a += 2 * g.cW * 4;
+      return;
+    }
     c_sub += PBK;
     if (c_sub == g.cC) {
       c_sub = 0;

@@ -35,6 +35,7 @@ LaunchFn pp_512x64(bool a_t, bool b_t, int epi) {
 LaunchFn pp_conv_512x64(int epi) {
 #define ET_PICK(E) \
   if (epi == E) return launch<false, false, E, 1>;
+  ET_PICK(E_F32)
   ET_PICK(E_BF16)
   ET_PICK(E_BIAS_RELU)
   ET_PICK(E_AFFINE)

@@ -209,6 +209,12 @@ hipError_t bias_relu_rows(const float* z, const bf16* bias, bf16* out, int rows,
 hipError_t flip3x3(const bf16* w, bf16* out, int O, int C, hipStream_t s);
 hipError_t pad_rows(const bf16* in, bf16* out, int rows, int K, int Kc, hipStream_t s);
 hipError_t strip_rows(const float* in, float* out, int rows, int K, int Kc, hipStream_t s);
+// operands of the stem convolution (7x7 / stride 2 / zero padding 3, C <= 4 input channels) for its gathered GEMM:
+// the image padded to [B][Hp][Wp][4] (pixel (h, w) at (h + 3, w + 3)), the weight widened to [O][8][8][4], and the
+// float32 weight gradient [O][8][8][4] brought back to [O][7][7][C]
+hipError_t stem_pad_image(const bf16* x, bf16* out, int B, int H, int W, int C, int Hp, int Wp, hipStream_t s);
+hipError_t stem_pack_weight(const bf16* w, bf16* out, int O, int C, hipStream_t s);
+hipError_t stem_unpack_dw(const float* in, float* out, int O, int C, hipStream_t s);
 // out[c] = sum_r d[r][c] * z[r][c]   (z bf16, or fp32 when z_f32 is given); same two stages as colsum
 hipError_t colsum_mul(const bf16* d, const bf16* z, const float* z_f32, float* out, float* partials, int rows, int cols,
                       hipStream_t s);

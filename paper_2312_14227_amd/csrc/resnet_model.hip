@@ -10,12 +10,20 @@
 // A convolution is a GEMM over the rows of an im2col matrix kept from the forward pass (a 1x1
 // stride-1 convolution reads the activation itself): forward cols * W^T, dw() d^T * cols (split
 // over the rows), dy() d * W followed by the gather-form adjoint of im2col fused with the branch
-// sum and the ReLU mask.  The 3x3 / stride 1 convolutions run as implicit GEMMs instead (the
-// matrix is gathered from the activation inside the kernel; dy() is a convolution with the
-// mirrored weight whose epilogue applies the ReLU mask).  The stem's convolution output stays
-// fp32 so that the max-pooling argmax is decided on unrounded values.
+// sum and the ReLU mask.  The 3x3 convolutions, the strided 1x1 ones and the stem run as implicit
+// GEMMs instead (the matrix is gathered from the activation inside the kernel; dy() of a stride-1
+// 3x3 convolution is a convolution with the mirrored weight whose epilogue applies the ReLU mask).
+// The stem's convolution output stays fp32 so that the max-pooling argmax is decided on unrounded
+// values.
 #include "conv_chain.h"
 
+// The stem (7x7, stride 2) runs as a gathered GEMM over a padded copy of the image when the image has at most four
+// channels and the output pixels come in whole slices of 64 (the weight gradient reduces over them).
+static bool stem_gathered(const et_ctx* c) {
+  const ConvUnit& u = c->stem;
+  return u.k == 7 && u.stride == 2 && u.Cin <= 4 && rows_of(c, u) % 64 == 0 && c->stem_hp >= u.H + 3 && c->stem_wp >= u.W + 3 &&
+         c->stem_hp <= 4095 && c->stem_wp <= 4095;
+}
 
 int build_resnet(et_ctx* c) {
   const et_model_desc& d = c->desc;
@@ -88,13 +96,26 @@ int build_resnet(et_ctx* c) {
   {
     ConvUnit& u = c->stem;
     const size_t M = rows_of(c, u);
-    reserve(c, &u.cols, b16 * M * u.Kc);
+    // With at most 4 input channels the stem reads a padded copy of the image through the gathered GEMM (window
+    // widened to 8 x 8 x 4 = 256 columns) instead of an im2col matrix; the weight gradient needs whole slices of 64 pixels.
+    c->stem_hp = 2 * (u.Ho - 1) + 8;
+    c->stem_wp = 2 * (u.Wo - 1) + 8;
+    const bool gathered = stem_gathered(c);
+    const size_t Kw = gathered ? 256 : (size_t)u.Kc;
+    if (gathered) reserve(c, &c->stem_xpad, b16 * B * c->stem_hp * c->stem_wp * 4);
+    else reserve(c, &u.cols, b16 * M * u.Kc);
     reserve(c, &c->stem_z32, f32 * M * u.Cout);
     reserve(c, &c->pool_y, b16 * M * u.Cout);
-    reserve(c, &c->stem_w8, b16 * (size_t)u.Cout * u.Kc);
-    reserve(c, &c->stem_dw8, f32 * (size_t)u.Cout * u.Kc);
+    reserve(c, &c->stem_w8, b16 * (size_t)u.Cout * Kw);
+    reserve(c, &c->stem_dw8, f32 * (size_t)u.Cout * Kw);
     act(M, u.Cout);
-    pe = std::max(pe, et::gemm_bf16_partial_elems(u.Cout, u.Kc, split_for(u.Cout, u.Kc, (int)M)));
+    if (gathered) {
+      int tile, split;
+      et::gemm_bf16_plan_conv_dw(u.Cout, 256, (int)M, &tile, &split);
+      pe = std::max(pe, et::gemm_bf16_partial_elems(u.Cout, 256, split));
+    } else {
+      pe = std::max(pe, et::gemm_bf16_partial_elems(u.Cout, u.Kc, split_for(u.Cout, u.Kc, (int)M)));
+    }
     const size_t Mp = B * c->rblk[0].c1.H * c->rblk[0].c1.W;
     reserve(c, &c->pooled, b16 * Mp * u.Cout);
     reserve(c, &c->pool_arg, Mp * u.Cout);
@@ -137,9 +158,19 @@ int resnet_forward(et_ctx* c, const void* x, const int32_t* y, const uint8_t* ma
   const int B = d.batch;
   {  // stem: convolution (fp32 result), affine + ReLU, max pooling
     const ConvUnit& u = c->stem;
-    ET_K(1, et::pad_rows(Wt(0), c->stem_w8, u.Cout, 49 * u.Cin, u.Kc, s));
-    int rc = conv_forward(c, u, (const bf16*)x, c->stem_w8, c->stem_z32, true);
-    if (rc != ET_OK) return rc;
+    if (stem_gathered(c)) {
+      ET_K(1, et::stem_pack_weight(Wt(0), c->stem_w8, u.Cout, u.Cin, s));
+      ET_KB(1, 2.0 * B * ((double)u.H * u.W * u.Cin + (double)c->stem_hp * c->stem_wp * 4),
+            et::stem_pad_image((const bf16*)x, c->stem_xpad, B, u.H, u.W, u.Cin, c->stem_hp, c->stem_wp, s));
+      et::GemmDesc g = linear_fwd(c->stem_xpad, c->stem_w8, nullptr, (int)rows_of(c, u), u.Cout, 256);
+      g.conv_h = c->stem_hp; g.conv_w = c->stem_wp; g.conv_c = 4; g.conv_taps = 7; g.conv_stride = 2;
+      g.C = c->stem_z32; g.c_f32 = true;
+      ET_G(g);
+    } else {
+      ET_K(1, et::pad_rows(Wt(0), c->stem_w8, u.Cout, 49 * u.Cin, u.Kc, s));
+      int rc = conv_forward(c, u, (const bf16*)x, c->stem_w8, c->stem_z32, true);
+      if (rc != ET_OK) return rc;
+    }
     const double n = (double)rows_of(c, u) * u.Cout, np = (double)B * c->rblk[0].c1.H * c->rblk[0].c1.W * u.Cout;
     ET_KB(1, 6.0 * n, et::affine_act(nullptr, c->stem_z32, Wt(1), Wt(2), nullptr, nullptr, nullptr, true, c->pool_y,
                                      (long long)rows_of(c, u), u.Cout, s));
@@ -347,8 +378,21 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
     }
     if (sel(0)) {
       Region r(c, PH_DW, 0);
-      ET_G(linear_dw(c, c->rd[0], u.Cout, u.cols, u.Kc, c->stem_dw8, (int)M, u.Cout, u.Kc));
-      ET_K(1, et::strip_rows(c->stem_dw8, c->grad[0], u.Cout, 49 * u.Cin, u.Kc, s));
+      if (stem_gathered(c)) {   // B operand: the padded image standing for [pixel][8 x 8 x 4]
+        et::GemmDesc g;
+        g.A = c->rd[0]; g.a_t = true; g.lda = u.Cout; g.B = c->stem_xpad; g.b_t = true; g.ldb = 256;
+        g.M = u.Cout; g.N = 256; g.K = (int)M;
+        g.C = c->stem_dw8; g.ldc = 256; g.c_f32 = true;
+        g.conv_h = c->stem_hp; g.conv_w = c->stem_wp; g.conv_c = 4; g.conv_taps = 7; g.conv_stride = 2;
+        et::gemm_bf16_plan_conv_dw(g.M, g.N, g.K, &g.tile, &g.split_k);
+        g.partials = c->gemm_partials;
+        if (et::gemm_bf16_partial_elems(g.M, g.N, g.split_k) > c->gemm_partial_elems) g.split_k = 1;
+        ET_G(g);
+        ET_K(1, et::stem_unpack_dw(c->stem_dw8, c->grad[0], u.Cout, u.Cin, s));
+      } else {
+        ET_G(linear_dw(c, c->rd[0], u.Cout, u.cols, u.Kc, c->stem_dw8, (int)M, u.Cout, u.Kc));
+        ET_K(1, et::strip_rows(c->stem_dw8, c->grad[0], u.Cout, 49 * u.Cin, u.Kc, s));
+      }
     }
   }
   (void)x;

@@ -243,3 +243,55 @@ def test_gathered_convolution_rejects_bad_arguments():
     assert et.et_debug_conv_gathered(0, p, p, p, 1, 8, 8, 48, 64, 3, 2) == -1     # channels
     assert et.et_debug_conv_gathered(1, p, p, p, 1, 10, 10, 8, 64, 3, 2) == -1    # 25 output pixels
     assert et.et_debug_conv_gathered(2, p, p, p, 1, 8, 8, 64, 64, 3, 2) == -1     # op
+
+
+def _case_stem(batch, H, W, C, N, seed):
+    """The stem convolution (7x7, stride 2, zero padding 3) and its weight gradient through the padded-image GEMM."""
+    import torch
+    from paper_2312_14227_amd import binding as et
+    rng = np.random.default_rng(seed)
+    x = bf16_round(rng.standard_normal((batch, H, W, C)).astype(np.float32))
+    w = bf16_round((rng.standard_normal((N, 7, 7, C)) / np.sqrt(49 * C)).astype(np.float32))
+    cv = R.Conv(x.astype(np.float64), w.astype(np.float64), 2)
+    Ho, Wo = cv.out.shape[1:3]
+    rows, kk = batch * Ho * Wo, 49 * C
+    d = bf16_round(rng.standard_normal((batch, Ho, Wo, N)).astype(np.float32))
+    dev = "cuda:0"
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(torch.bfloat16)
+    xt, wt, dt = to(x), to(w), to(d)
+    nbytes = et.et_debug_stem_ws_bytes(batch, H, W, C, N)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, device=dev, dtype=torch.uint8)
+    stream = torch.cuda.current_stream().cuda_stream
+    cols = cv.cols.reshape(rows, kk)
+    out = torch.full((rows, N), float("nan"), device=dev, dtype=torch.float32)
+    assert et.et_debug_stem(0, xt.data_ptr(), wt.data_ptr(), out.data_ptr(), ws.data_ptr(), batch, H, W, C, N, stream) == 0
+    torch.cuda.synchronize()
+    ref = cv.out.reshape(rows, N)
+    got = out.cpu().numpy().astype(np.float64)
+    bound = 2e-6 * (np.abs(cols) @ np.abs(cv.wm).T) * np.sqrt(kk) + 1e-6
+    bad = ~(np.abs(got - ref) <= bound)
+    assert not bad.any(), ("forward", int(bad.sum()), float(np.nanmax(np.abs(got - ref))))
+    if rows % 64 == 0:
+        dw = torch.full((N, kk), float("nan"), device=dev, dtype=torch.float32)
+        assert et.et_debug_stem(1, xt.data_ptr(), dt.data_ptr(), dw.data_ptr(), ws.data_ptr(), batch, H, W, C, N, stream) == 0
+        torch.cuda.synchronize()
+        ref = cv.dw(d.astype(np.float64)).reshape(N, kk)
+        got = dw.cpu().numpy().astype(np.float64)
+        bound = 2e-6 * (np.abs(d.reshape(rows, N).astype(np.float64)).T @ np.abs(cols)) * np.sqrt(rows) + 1e-6
+        bad = ~(np.abs(got - ref) <= bound)
+        assert not bad.any(), ("dw", int(bad.sum()), float(np.nanmax(np.abs(got - ref))))
+
+
+# even and odd image sizes, 1 to 4 channels, images smaller than the window, one ResNet-50 sized image pair
+@pytest.mark.parametrize("batch,H,W,C,N", [(2, 32, 32, 3, 16), (4, 16, 16, 3, 64), (1, 33, 31, 3, 24), (3, 5, 9, 1, 8), (2, 64, 48, 4, 64),
+                                           (1, 15, 17, 2, 72), (2, 224, 224, 3, 64)])
+def test_stem_convolution(batch, H, W, C, N):
+    _case_stem(batch, H, W, C, N, seed=H + W + C)
+
+
+def test_stem_convolution_rejects_bad_arguments():
+    from paper_2312_14227_amd import binding as et
+    assert et.et_debug_stem_ws_bytes(1, 32, 32, 5, 16) == 0     # channels
+    assert et.et_debug_stem_ws_bytes(1, 32, 32, 3, 12) == 0     # output channels not a multiple of 8
+    assert et.et_debug_stem_ws_bytes(0, 32, 32, 3, 16) == 0
