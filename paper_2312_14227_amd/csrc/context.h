@@ -27,8 +27,8 @@ struct TensorInfo {
   int32_t dtype;
 };
 
-struct Scope {  // one timed region of the profile
-  int phase, tensor;
+struct Scope {  // one timed region of the profile (tensor2 >= 0: its time is shared evenly by two tensors)
+  int phase, tensor, tensor2;
   hipEvent_t e0, e1;
 };
 
@@ -206,12 +206,13 @@ struct Region {
   et_ctx* c;
   bool on;
   size_t idx = 0;
-  Region(et_ctx* ctx, int phase, int tensor) : c(ctx), on(ctx->profiling) {
+  Region(et_ctx* ctx, int phase, int tensor, int tensor2 = -1) : c(ctx), on(ctx->profiling) {
     c->cur_phase = phase;
     if (!on) return;
     Scope s;
     s.phase = phase;
     s.tensor = tensor;
+    s.tensor2 = tensor2;
     if (get_event(c, &s.e0) != hipSuccess || get_event(c, &s.e1) != hipSuccess) {
       on = false;
       c->hip_err = hipErrorOutOfMemory;

@@ -18,6 +18,35 @@ namespace et_exec {
     ET_K(n, expr);                         \
   } while (0)
 
+// The per-channel pieces of a folded-BN affine y = z * gain + shift (tensors tg = gain, tg + 1 = shift) on the
+// gradient d [M][C] of y: dw(shift) = column sum of d, dw(gain) = column sum of d * z (z bf16, or float32 z32),
+// dy(gain): dout = d * gain.  With gain and shift both selected one kernel reads d once for both sums (same
+// summation order as the separate kernels, so a tensor's gradient does not depend on its neighbour's selection);
+// the profile shares that kernel's time evenly between the two tensors.  dy_used = false skips dy(gain) although
+// the chain passes the tensor: a projection shortcut's scaled gradient has no reader when its weight is not selected
+// and nothing in front of the block is (the time model then charges a few microseconds that are not spent).
+inline int affine_back(et_ctx* c, const uint8_t* mask, int jstar, int tg, const bf16* d, const bf16* z, const float* z32,
+                       bf16* dout, long long M, int C, bool dy_used = true) {
+  float* cp = c->colsum_partials;
+  hipStream_t s = c->stream;
+  const double zb = z32 ? 4.0 : 2.0;
+  if (mask[tg] && mask[tg + 1]) {
+    Region r(c, PH_DW, tg + 1, tg);
+    ET_KB(2, (2.0 + zb) * M * C, et::colsum_pair(d, z, z32, c->grad[tg + 1], c->grad[tg], cp, (int)M, C, s));
+  } else if (mask[tg + 1]) {
+    Region r(c, PH_DW, tg + 1);
+    ET_KB(2, 2.0 * M * C, et::colsum(d, nullptr, C, nullptr, 0, nullptr, nullptr, c->grad[tg + 1], cp, (int)M, C, s));
+  } else if (mask[tg]) {
+    Region r(c, PH_DW, tg);
+    ET_KB(2, (2.0 + zb) * M * C, et::colsum_mul(d, z, z32, c->grad[tg], cp, (int)M, C, s));
+  }
+  if (tg > jstar && dy_used) {
+    Region r(c, PH_DY, tg);
+    ET_KB(1, 4.0 * M * C, et::scale_cols(d, (const bf16*)c->w[tg], dout, M, C, s));
+  }
+  return ET_OK;
+}
+
 inline et::ConvGeom geom(const et_ctx* c, const ConvUnit& u) {
   et::ConvGeom g;
   g.B = c->desc.batch; g.H = u.H; g.W = u.W; g.C = u.Cin; g.k = u.k; g.stride = u.stride; g.pad = (u.k - 1) / 2;

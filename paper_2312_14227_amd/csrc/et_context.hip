@@ -908,6 +908,7 @@ int et_profile(et_ctx* c, const void* x_dev, const int32_t* y_dev, int32_t warmu
       ns -= std::min(overhead, 0.5 * ns);
       if (sc.phase == PH_FWD) sf += ns;
       else if (sc.phase == PH_UPD) su += ns;
+      else if (sc.phase == PH_DW && sc.tensor2 >= 0) { sdw[sc.tensor] += 0.5 * ns; sdw[sc.tensor2] += 0.5 * ns; }
       else if (sc.phase == PH_DW) sdw[sc.tensor] += ns;
       else sdy[sc.tensor] += ns;
     }

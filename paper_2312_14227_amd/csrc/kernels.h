@@ -218,6 +218,10 @@ hipError_t stem_unpack_dw(const float* in, float* out, int O, int C, hipStream_t
 // out[c] = sum_r d[r][c] * z[r][c]   (z bf16, or fp32 when z_f32 is given); same two stages as colsum
 hipError_t colsum_mul(const bf16* d, const bf16* z, const float* z_f32, float* out, float* partials, int rows, int cols,
                       hipStream_t s);
+// both sums from one read of d: out_sum[c] = sum_r d[r][c], out_mul[c] = sum_r d[r][c] * z[r][c], each identical to
+// what colsum / colsum_mul give; partials must hold 2 * colsum_partial_elems(rows, cols) floats
+hipError_t colsum_pair(const bf16* d, const bf16* z, const float* z_f32, float* out_sum, float* out_mul, float* partials,
+                       int rows, int cols, hipStream_t s);
 
 // ------------------------------------------------------------------------------------------
 // importance (Eq. 2) and masked optimizer update over a table of tensors

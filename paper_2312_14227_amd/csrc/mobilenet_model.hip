@@ -75,7 +75,7 @@ int build_mobilenet(et_ctx* c) {
   size_t max_act = 0, max_cs = 0, pe = 0, max_dwp = 64;
   auto act = [&](size_t rows, size_t ch) {
     max_act = std::max(max_act, rows * ch);
-    max_cs = std::max(max_cs, et::colsum_partial_elems((int)rows, (int)ch));
+    max_cs = std::max(max_cs, 2 * et::colsum_partial_elems((int)rows, (int)ch));   // (gain and shift sums in one launch)
   };
   auto wgrad = [&](int out, int in, size_t rows) {
     pe = std::max(pe, et::gemm_bf16_partial_elems(out, in, split_for(out, in, (int)rows)));
@@ -201,22 +201,8 @@ int mobilenet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
   hipStream_t s = c->stream;
   float* cp = c->colsum_partials;
 
-  // the three tiny layers of one convolution's affine, working on d [M][C] in place of the chain
-  // state: dw(b) = column sum of d, dw(g) = column sum of d * z, dy(g): out = d * g
   auto affine_back = [&](int tg, const bf16* dsrc, const bf16* z, bf16* dout, long long M, int C) -> int {
-    if (sel(tg + 1)) {
-      Region r(c, PH_DW, tg + 1);
-      ET_KB(2, 2.0 * M * C, et::colsum(dsrc, nullptr, C, nullptr, 0, nullptr, nullptr, c->grad[tg + 1], cp, (int)M, C, s));
-    }
-    if (sel(tg)) {
-      Region r(c, PH_DW, tg);
-      ET_KB(2, 4.0 * M * C, et::colsum_mul(dsrc, z, nullptr, c->grad[tg], cp, (int)M, C, s));
-    }
-    if (pass(tg)) {
-      Region r(c, PH_DY, tg);
-      ET_KB(1, 4.0 * M * C, et::scale_cols(dsrc, Wt(tg), dout, M, C, s));
-    }
-    return ET_OK;
+    return et_exec::affine_back(c, mask, jstar, tg, dsrc, z, nullptr, dout, M, C);
   };
   int rc;
 

@@ -76,7 +76,7 @@ int build_resnet(et_ctx* c) {
   size_t max_act = 0, max_cols = 0, max_cs = 0, pe = 0, max_flip = 8, dcols_b = 16;
   auto act = [&](size_t rows, size_t ch) {
     max_act = std::max(max_act, rows * ch);
-    max_cs = std::max(max_cs, et::colsum_partial_elems((int)rows, (int)ch));
+    max_cs = std::max(max_cs, 2 * et::colsum_partial_elems((int)rows, (int)ch));   // (gain and shift sums in one launch)
   };
   auto wg = [&](const ConvUnit& u) {
     const int M = (int)rows_of(c, u);
@@ -252,38 +252,15 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
     if (jstar > t + (b.proj ? 11 : 8)) break;
     const long long M3 = (long long)rows_of(c, b.c3), M2 = (long long)rows_of(c, b.c2), M1 = (long long)rows_of(c, b.c1);
     if (b.proj) {
-      if (sel(t + 11)) {
-        Region r(c, PH_DW, t + 11);
-        ET_KB(2, 2.0 * M3 * b.sc.Cout, et::colsum(c->rdsum, nullptr, b.sc.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 11], cp, (int)M3,
-                           b.sc.Cout, s));
-      }
-      if (sel(t + 10)) {
-        Region r(c, PH_DW, t + 10);
-        ET_KB(2, 4.0 * M3 * b.sc.Cout, et::colsum_mul(c->rdsum, b.sc.z, nullptr, c->grad[t + 10], cp, (int)M3, b.sc.Cout, s));
-      }
-      if (pass(t + 10)) {
-        Region r(c, PH_DY, t + 10);
-        ET_KB(1, 4.0 * M3 * b.sc.Cout, et::scale_cols(c->rdsum, Wt(t + 10), c->rdsc, M3, b.sc.Cout, s));
-      }
+      if ((rc = affine_back(c, mask, jstar, t + 10, c->rdsum, b.sc.z, nullptr, c->rdsc, M3, b.sc.Cout, sel(t + 9) || pass(t))) != ET_OK)
+        return rc;
       if (sel(t + 9)) {
         Region r(c, PH_DW, t + 9);
         if ((rc = conv_dw(c, b.sc, b.x, c->rdsc, c->grad[t + 9])) != ET_OK) return rc;
       }
     }
     // main branch: c3
-    if (sel(t + 8)) {
-      Region r(c, PH_DW, t + 8);
-      ET_KB(2, 2.0 * M3 * b.c3.Cout, et::colsum(c->rdsum, nullptr, b.c3.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 8], cp, (int)M3,
-                         b.c3.Cout, s));
-    }
-    if (sel(t + 7)) {
-      Region r(c, PH_DW, t + 7);
-      ET_KB(2, 4.0 * M3 * b.c3.Cout, et::colsum_mul(c->rdsum, b.c3.z, nullptr, c->grad[t + 7], cp, (int)M3, b.c3.Cout, s));
-    }
-    if (pass(t + 7)) {
-      Region r(c, PH_DY, t + 7);
-      ET_KB(1, 4.0 * M3 * b.c3.Cout, et::scale_cols(c->rdsum, Wt(t + 7), c->rd[0], M3, b.c3.Cout, s));
-    }
+    if ((rc = affine_back(c, mask, jstar, t + 7, c->rdsum, b.c3.z, nullptr, c->rd[0], M3, b.c3.Cout)) != ET_OK) return rc;
     if (sel(t + 6)) {
       Region r(c, PH_DW, t + 6);
       if ((rc = conv_dw(c, b.c3, b.c2.y, c->rd[0], c->grad[t + 6])) != ET_OK) return rc;
@@ -294,19 +271,7 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
       ET_KB(1, 6.0 * M2 * b.c2.Cout, et::add_mask(c->rd[1], nullptr, b.c2.y, c->rd[1], M2 * b.c2.Cout, s));
     }
     // c2
-    if (sel(t + 5)) {
-      Region r(c, PH_DW, t + 5);
-      ET_KB(2, 2.0 * M2 * b.c2.Cout, et::colsum(c->rd[1], nullptr, b.c2.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 5], cp, (int)M2,
-                         b.c2.Cout, s));
-    }
-    if (sel(t + 4)) {
-      Region r(c, PH_DW, t + 4);
-      ET_KB(2, 4.0 * M2 * b.c2.Cout, et::colsum_mul(c->rd[1], b.c2.z, nullptr, c->grad[t + 4], cp, (int)M2, b.c2.Cout, s));
-    }
-    if (pass(t + 4)) {
-      Region r(c, PH_DY, t + 4);
-      ET_KB(1, 4.0 * M2 * b.c2.Cout, et::scale_cols(c->rd[1], Wt(t + 4), c->rd[0], M2, b.c2.Cout, s));
-    }
+    if ((rc = affine_back(c, mask, jstar, t + 4, c->rd[1], b.c2.z, nullptr, c->rd[0], M2, b.c2.Cout)) != ET_OK) return rc;
     if (sel(t + 3)) {
       Region r(c, PH_DW, t + 3);
       if ((rc = conv_dw(c, b.c2, b.c1.y, c->rd[0], c->grad[t + 3])) != ET_OK) return rc;
@@ -321,19 +286,7 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
       }
     }
     // c1
-    if (sel(t + 2)) {
-      Region r(c, PH_DW, t + 2);
-      ET_KB(2, 2.0 * M1 * b.c1.Cout, et::colsum(c->rd[1], nullptr, b.c1.Cout, nullptr, 0, nullptr, nullptr, c->grad[t + 2], cp, (int)M1,
-                         b.c1.Cout, s));
-    }
-    if (sel(t + 1)) {
-      Region r(c, PH_DW, t + 1);
-      ET_KB(2, 4.0 * M1 * b.c1.Cout, et::colsum_mul(c->rd[1], b.c1.z, nullptr, c->grad[t + 1], cp, (int)M1, b.c1.Cout, s));
-    }
-    if (pass(t + 1)) {
-      Region r(c, PH_DY, t + 1);
-      ET_KB(1, 4.0 * M1 * b.c1.Cout, et::scale_cols(c->rd[1], Wt(t + 1), c->rd[0], M1, b.c1.Cout, s));
-    }
+    if ((rc = affine_back(c, mask, jstar, t + 1, c->rd[1], b.c1.z, nullptr, c->rd[0], M1, b.c1.Cout)) != ET_OK) return rc;
     if (sel(t)) {
       Region r(c, PH_DW, t);
       if ((rc = conv_dw(c, b.c1, b.x, c->rd[0], c->grad[t])) != ET_OK) return rc;
@@ -364,18 +317,7 @@ int resnet_backward(et_ctx* c, const void* x, const uint8_t* mask) {
   if (jstar <= 2) {
     const ConvUnit& u = c->stem;
     const long long M = (long long)rows_of(c, u);
-    if (sel(2)) {
-      Region r(c, PH_DW, 2);
-      ET_KB(2, 2.0 * M * u.Cout, et::colsum(c->rdsum, nullptr, u.Cout, nullptr, 0, nullptr, nullptr, c->grad[2], cp, (int)M, u.Cout, s));
-    }
-    if (sel(1)) {
-      Region r(c, PH_DW, 1);
-      ET_KB(2, 6.0 * M * u.Cout, et::colsum_mul(c->rdsum, nullptr, c->stem_z32, c->grad[1], cp, (int)M, u.Cout, s));
-    }
-    if (pass(1)) {
-      Region r(c, PH_DY, 1);
-      ET_KB(1, 4.0 * M * u.Cout, et::scale_cols(c->rdsum, Wt(1), c->rd[0], M, u.Cout, s));
-    }
+    if ((rc = affine_back(c, mask, jstar, 1, c->rdsum, nullptr, c->stem_z32, c->rd[0], M, u.Cout)) != ET_OK) return rc;
     if (sel(0)) {
       Region r(c, PH_DW, 0);
       if (stem_gathered(c)) {   // B operand: the padded image standing for [pixel][8 x 8 x 4]

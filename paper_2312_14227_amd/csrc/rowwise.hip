@@ -331,6 +331,58 @@ __global__ __launch_bounds__(256) void colsum_mul_stage1(const bf16* __restrict_
   }
 }
 
+// both of the above from one read of d: partials [chunks][cols] of the plain sums, followed by [chunks][cols] of
+// the sums with the multiplier; chunking and summation order as in the separate kernels, so the results are the same
+template <bool Z32>
+__global__ __launch_bounds__(256) void colsum_pair_stage1(const bf16* __restrict__ d, const bf16* __restrict__ z16,
+                                                          const float* __restrict__ z32, float* __restrict__ partials,
+                                                          int rows, int cols) {
+  __shared__ float red[2][32][CS_COLS + 1];
+  const int cx = threadIdx.x & 7, ry = threadIdx.x >> 3;
+  const int c0 = blockIdx.x * CS_COLS + cx * 8;
+  const int chunk_rows = cs_rows(rows, cols);
+  const int r_begin = blockIdx.y * chunk_rows, r_end = min(rows, r_begin + chunk_rows);
+  float acc[8], accz[8];
+#pragma unroll
+  for (int j = 0; j < 8; j++) acc[j] = accz[j] = 0.f;
+  if (c0 < cols) {
+    for (int r = r_begin + ry; r < r_end; r += 32) {
+      const bf16x8 a = *(const bf16x8*)(d + (long long)r * cols + c0);
+      float zz[8];
+      if (Z32) {
+        const float4 p = *(const float4*)(z32 + (long long)r * cols + c0);
+        const float4 q = *(const float4*)(z32 + (long long)r * cols + c0 + 4);
+        zz[0] = p.x; zz[1] = p.y; zz[2] = p.z; zz[3] = p.w; zz[4] = q.x; zz[5] = q.y; zz[6] = q.z; zz[7] = q.w;
+      } else {
+        const bf16x8 b = *(const bf16x8*)(z16 + (long long)r * cols + c0);
+#pragma unroll
+        for (int j = 0; j < 8; j++) zz[j] = (float)b[j];
+      }
+#pragma unroll
+      for (int j = 0; j < 8; j++) {
+        acc[j] += (float)a[j];
+        accz[j] += (float)a[j] * zz[j];
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; j++) {
+    red[0][ry][cx * 8 + j] = acc[j];
+    red[1][ry][cx * 8 + j] = accz[j];
+  }
+  __syncthreads();
+  if (threadIdx.x < 2 * CS_COLS) {
+    const int which = threadIdx.x / CS_COLS, cl = threadIdx.x % CS_COLS;
+    const int c = blockIdx.x * CS_COLS + cl;
+    if (c < cols) {
+      float s = red[which][0][cl];
+#pragma unroll
+      for (int k = 1; k < 32; k++) s += red[which][k][cl];
+      partials[((long long)which * gridDim.y + blockIdx.y) * cols + c] = s;
+    }
+  }
+}
+
 // stage 2: 16 threads per column each add every 16th row-chunk partial, then the 16 sums are added
 // in ascending order (a long serial loop per column would be bound by load latency)
 constexpr int S2_PARTS = 16, S2_COLS = 16;
@@ -351,6 +403,29 @@ __global__ __launch_bounds__(256) void colsum_stage2(const float* __restrict__ p
 #pragma unroll
     for (int q = 1; q < S2_PARTS; q++) t += red[q][cx];
     out[c] = t;
+  }
+}
+
+// stage 2 of the pair: columns [0, cols) finish the plain sums into out0, columns [cols, 2 cols) the others into out1
+__global__ __launch_bounds__(256) void colsum_pair_stage2(const float* __restrict__ partials, float* __restrict__ out0,
+                                                          float* __restrict__ out1, int chunks, int cols) {
+  __shared__ float red[S2_PARTS][S2_COLS + 1];
+  const int cx = threadIdx.x % S2_COLS, part = threadIdx.x / S2_COLS;
+  const int c2 = blockIdx.x * S2_COLS + cx;
+  const int which = c2 >= cols ? 1 : 0, c = c2 - which * cols;
+  const float* src = partials + (long long)which * chunks * cols;
+  float s = 0.f;
+  if (c2 < 2 * cols) {
+#pragma unroll 4
+    for (int k = part; k < chunks; k += S2_PARTS) s += src[(long long)k * cols + c];
+  }
+  red[part][cx] = s;
+  __syncthreads();
+  if (threadIdx.x < S2_COLS && c2 < 2 * cols) {
+    float t = red[0][cx];
+#pragma unroll
+    for (int q = 1; q < S2_PARTS; q++) t += red[q][cx];
+    (which ? out1 : out0)[c] = t;
   }
 }
 
@@ -567,6 +642,23 @@ hipError_t colsum_mul(const bf16* d, const bf16* z, const float* z_f32, float* o
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(colsum_stage2, dim3((cols + S2_COLS - 1) / S2_COLS), dim3(256), 0, s, partials, out, chunks, cols);
+  return hipGetLastError();
+}
+
+hipError_t colsum_pair(const bf16* d, const bf16* z, const float* z_f32, float* out_sum, float* out_mul, float* partials,
+                       int rows, int cols, hipStream_t s) {
+  if (rows <= 0 || cols <= 0 || (cols & 7) || !d || (!z && !z_f32) || !partials || !out_sum || !out_mul) return hipErrorInvalidValue;
+  if (!al16(d) || (z && !al16(z)) || (z_f32 && !al16(z_f32))) return hipErrorInvalidValue;
+  const int chunks = (rows + cs_rows(rows, cols) - 1) / cs_rows(rows, cols);
+  dim3 grid((cols + CS_COLS - 1) / CS_COLS, chunks), block(256);
+  if (z_f32)
+    hipLaunchKernelGGL((colsum_pair_stage1<true>), grid, block, 0, s, d, z, z_f32, partials, rows, cols);
+  else
+    hipLaunchKernelGGL((colsum_pair_stage1<false>), grid, block, 0, s, d, z, z_f32, partials, rows, cols);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(colsum_pair_stage2, dim3((2 * cols + S2_COLS - 1) / S2_COLS), dim3(256), 0, s, partials, out_sum, out_mul,
+                     chunks, cols);
   return hipGetLastError();
 }
 
