@@ -145,15 +145,22 @@ def main():
     if gemm:
         dom = max(gemm, key=lambda c: gemm[c][1])
         n, ns, work = gemm[dom]
-        traffic = None
-        try:   # measured separately with rocprofv3 --pmc (bench.py cannot run the profiler on itself)
+        # HBM-side traffic is not measured by this run: it is the stored result of two rocprofv3 --pmc runs of this same
+        # command on this workload (the file names its summary under profiles/), labelled as such in the line
+        traffic = traffic_src = traffic_alg = None
+        try:
             with open(os.path.join(ROOT, "paper_2312_14227_amd", "measured_traffic.json")) as fh:
-                traffic = json.load(fh).get(cfg.name, {}).get(GEMM_CLASS_NAMES[dom], {}).get("bytes_per_launch")
+                tw = json.load(fh).get(cfg.name, {})
+            tc = tw.get(GEMM_CLASS_NAMES[dom], {})
+            traffic = tc.get("bytes_per_launch")
+            traffic_alg = tc.get("algorithmic_bytes_per_launch")
+            traffic_src = "%s (%s); stored, not measured by this run" % (tw.get("source"), tw.get("command")) if traffic else None
         except OSError:
             pass
         roofline = {"bound": "mfma", "kernel": GEMM_CLASS_NAMES[dom], "achieved": work / ns / 1e3,
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": work / ns / 1e3 / PEAK_BF16_TFLOPS,
-                    "traffic": traffic, "avg_launch_us": ns / n / 1e3, "flops_per_launch": work / n,
+                    "traffic": traffic, "traffic_source": traffic_src, "traffic_algorithmic_bytes": traffic_alg,
+                    "avg_launch_us": ns / n / 1e3, "flops_per_launch": work / n,
                     "launches_per_step": n / a.steps}
         all_ns = sum(v[1] for v in gemm.values())
         all_work = sum(v[2] for v in gemm.values())

@@ -93,7 +93,18 @@ typedef struct et_ctx et_ctx;
  *   head.  Tensors in chain order: stem.W, stem.g, stem.b; per block [exp.W, exp.g, exp.b,] dw.W,
  *   dw.g, dw.b, proj.W, proj.g, proj.b; last.W, last.g, last.b; head.W [classes, last], head.b.
  *   All channel counts and classes must be multiples of 8.
- * Labels are int32 in [0, classes). The loss is the mean softmax cross-entropy. */
+ * Labels are int32 in [0, classes). The loss is the mean softmax cross-entropy.
+ *
+ * Storage contract of the ET_BF16 convolutional models (a property of the memory layout, whichever kernel
+ * computes a layer): every tensor that one operation of the chain hands to the next is rounded once to bf16
+ * (nearest, ties to even) -- each convolution output, each affine / activation output, pooled features, the
+ * copy of the logit gradient that feeds the matrix products, and each error gradient between two backward
+ * operations; sums are accumulated in float32 and rounded when the result is stored.  Two exceptions:
+ * the ET_RESNET stem keeps its convolution output in float32 (the max-pooling argmax is decided on unrounded
+ * values), and the column gradient d * W of a convolution with a kernel larger than 1x1 is never a stored
+ * tensor: the input gradient, the sum of its shifted copies, is rounded once after the sum.  For a 1x1
+ * convolution that product is the input gradient itself and is rounded like any other result.
+ * Weight gradients are float32. */
 typedef struct {
   int32_t kind;  /* ET_MLP | ET_VIT | ET_RESNET | ET_VGG | ET_MOBILENET */
   int32_t dtype; /* ET_F32 (MLP) | ET_BF16 (all others) */

@@ -344,25 +344,26 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   }
   int BM, BN;
   gemm::LaunchFn fn;
+  const bool conv_general = conv && !(d.conv_taps == 3 && d.conv_stride == 1);   // geometry as launch arguments
   bool resident = true;   // the two-group kernels keep one workgroup per CU that walks over the tiles
   if (conv_dw) {
     int tile = d.tile;
     if (tile != T_PP_256x256 && tile != T_PP_256x192 && tile != T_PP_128x256 && tile != T_PP_64x512)
       tile = plan_conv_dw(d.M, d.N, k_per_block).tile;
     switch (tile) {
-      case T_PP_64x512: BM = 64; BN = 512; fn = gemm::pp_convdw_64x512(epi); break;
-      case T_PP_128x256: BM = 128; BN = 256; fn = gemm::pp_convdw_128x256(epi); break;
-      case T_PP_256x192: BM = 256; BN = 192; fn = gemm::pp_convdw_256x192(epi); break;
-      default: BM = 256; BN = 256; fn = gemm::pp_convdw_256x256(epi); break;
+      case T_PP_64x512: BM = 64; BN = 512; fn = gemm::pp_convdw_64x512(epi, conv_general); break;
+      case T_PP_128x256: BM = 128; BN = 256; fn = gemm::pp_convdw_128x256(epi, conv_general); break;
+      case T_PP_256x192: BM = 256; BN = 192; fn = gemm::pp_convdw_256x192(epi, conv_general); break;
+      default: BM = 256; BN = 256; fn = gemm::pp_convdw_256x256(epi, conv_general); break;
     }
   } else if (stem) {   // few output channels, fp32 result
-    BM = 512; BN = 64; fn = gemm::pp_conv_512x64(epi);
+    BM = 512; BN = 64; fn = gemm::pp_conv_512x64(epi, conv_general);
   } else if (conv) {
     switch (choose_conv_tile(d)) {
-      case T_PP_512x64: BM = 512; BN = 64; fn = gemm::pp_conv_512x64(epi); break;
-      case T_PP_256x128: BM = 256; BN = 128; fn = gemm::pp_conv_256x128(epi); break;
-      case T_PP_256x192: BM = 256; BN = 192; fn = gemm::pp_conv_256x192(epi); break;
-      default: BM = 256; BN = 256; fn = gemm::pp_conv_256x256(epi); break;
+      case T_PP_512x64: BM = 512; BN = 64; fn = gemm::pp_conv_512x64(epi, conv_general); break;
+      case T_PP_256x128: BM = 256; BN = 128; fn = gemm::pp_conv_256x128(epi, conv_general); break;
+      case T_PP_256x192: BM = 256; BN = 192; fn = gemm::pp_conv_256x192(epi, conv_general); break;
+      default: BM = 256; BN = 256; fn = gemm::pp_conv_256x256(epi, conv_general); break;
     }
   } else
   switch (choose_tile(d, k_per_block)) {

@@ -913,12 +913,18 @@ constexpr int PBK = 64;
 // CONV = 2 (weight gradient, AT = BT = true): the B operand [output pixel][(tap, c)] is that same matrix,
 // gathered from the activation g.B; the reduction runs over the output pixels, 64 per slice, and each
 // 16-byte piece (8 channels of one tap, fixed for a lane) comes from the input pixel its tap reads.
+// GEN = false compiles the geometry of the common case in (3x3, stride 1: output size = input size); GEN = true takes
+// taps, stride and output size from the launch arguments (stride 2, 1x1 taps, the stem form below).
 // Stem form of both (cT == 8: a 7x7 / stride 2 / zero padding 3 convolution of an image with at most 4 channels):
 // the activation is the image padded to 4 channels and by 3 pixels at the top and left (zeros up to cH x cW with
 // cW even), the window is widened to 8 x 8 with zero weights, so K = 8 * 8 * 4 = 256 and a K slice is two window
 // rows of 64 contiguous bytes each, 16-byte aligned, that never leave the padded image: no validity test.
-template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, int EPI, int CONV = 0>
+template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, int EPI, int CONV = 0, bool GEN = false>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
+  // convolution geometry: compile-time constants for the common 3x3 / stride 1 form, launch arguments for the general one
+  const int cS = GEN ? g.cS : 1, cT = GEN ? g.cT : 3, cHo = GEN ? g.cHo : g.cH, cWo = GEN ? g.cWo : g.cW;
+  const bool stem = GEN && g.cT == 8;
+  const int ssh = cS >> 1;   // the stride (1 or 2) as a shift
   constexpr int NW = WGM * WGN;
   constexpr int TM = BM / WGM, TN = BN / WGN;
   constexpr int MI = TM / 32, NI = TN / 32;
@@ -998,11 +1004,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
       if (CONV == 1) {  // centre tap of the row's pixel
         const int row = q * 8 + (lane >> 3), chunk = lane & 7;
         const int m = min(m0 + row, g.M - 1);
-        const int wo = m % g.cWo, t = m / g.cWo, ho = t % g.cHo, img = t / g.cHo;
-        cow[CONV == 1 ? i : 0] = wo * g.cS;           // input coordinates of the centre tap
-        coh[CONV == 1 ? i : 0] = ho * g.cS;
-        ga[i] = A + ((long long)(img * g.cH + ho * g.cS) * g.cW + wo * g.cS) * g.cC + chunk * 8;
-        if (g.cT == 8) {   // stem form: chunk = (row of the pair, pixel pair); nothing lies outside the padded image
+        const int wo = m % cWo, t = m / cWo, ho = t % cHo, img = t / cHo;
+        cow[CONV == 1 ? i : 0] = wo * cS;           // input coordinates of the centre tap
+        coh[CONV == 1 ? i : 0] = ho * cS;
+        ga[i] = A + ((long long)(img * g.cH + ho * cS) * g.cW + wo * cS) * g.cC + chunk * 8;
+        if (stem) {   // stem form: chunk = (row of the pair, pixel pair); nothing lies outside the padded image
           cow[CONV == 1 ? i : 0] = 0;
           coh[CONV == 1 ? i : 0] = 0;
           ga[i] = A + ((long long)(img * g.cH + ho * 2 + (chunk >> 2)) * g.cW + wo * 2) * 4 + (chunk & 3) * 8;
@@ -1030,17 +1036,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
         if (gj + 8 > g.N) gj = 0;                 // N = 9 cC is a multiple of 8
         const int tap = gj / g.cC;
         int ch = gj % g.cC;
-        int dy = tap / g.cT - (g.cT >> 1), dx = tap % g.cT - (g.cT >> 1);
+        int dy = tap / cT - (cT >> 1), dx = tap % cT - (cT >> 1);
         int off = (dy * g.cW + dx) * g.cC;
-        if (g.cT == 8) {   // stem form: column = (row 0..7, pixel pair 0..3, 8 values), always inside the padded image
+        if (stem) {   // stem form: column = (row 0..7, pixel pair 0..3, 8 values), always inside the padded image
           off = ((gj >> 5) * g.cW) * 4 + ((gj >> 3) & 3) * 8;
           dy = dx = ch = 0;
         }
         const int pix = k_begin + k;               // output pixel of this k-row
-        const int wo = pix % g.cWo, t = pix / g.cWo, ho = t % g.cHo, img = t / g.cHo;
+        const int wo = pix % cWo, t = pix / cWo, ho = t % cHo, img = t / cHo;
         bpix[CONV == 2 ? i : 0] = ((dy + 1) << 26) | ((dx + 1) << 24) | (ho << 12) | wo;
         boff[CONV == 2 ? i : 0] = off;
-        gb[i] = B + ((long long)(img * g.cH + ho * g.cS) * g.cW + wo * g.cS) * g.cC + ch;   // centre tap
+        gb[i] = B + ((long long)(img * g.cH + ho * cS) * g.cW + wo * cS) * g.cC + ch;   // centre tap
       } else if (!BT) {
         const int row = q * 8 + (lane >> 3), chunk = lane & 7;
         gb[i] = B + (long long)min(n0 + row, g.N - 1) * g.ldb + k_begin + chunk * 8;
@@ -1056,10 +1062,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
     if (CONV == 1) {
       const int tap0 = k_begin / g.cC;
       c_sub = k_begin % g.cC;
-      c_dy = tap0 / g.cT - (g.cT >> 1);
-      c_dx = tap0 % g.cT - (g.cT >> 1);
+      c_dy = tap0 / cT - (cT >> 1);
+      c_dx = tap0 % cT - (cT >> 1);
       c_off_a = (long long)(c_dy * g.cW + c_dx) * g.cC + c_sub;
-      if (g.cT == 8) {   // stem form: a slice is two rows of the 8 x 8 window
+      if (stem) {   // stem form: a slice is two rows of the 8 x 8 window
         c_sub = c_dy = c_dx = 0;
         c_off_a = (long long)(k_begin / PBK) * 2 * g.cW * 4;
       }
@@ -1069,8 +1075,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   const long long b_step = BT ? (long long)PBK * g.ldb : PBK;
   // CONV 2: a slice moves every piece 64 output pixels on: (image, ho, wo) advance by (64 / (cHo cWo), (64 / cWo) % cHo,
   // 64 % cWo) with carries, and the input pointer follows by the corresponding number of input pixels
-  const int b_sw = CONV == 2 ? PBK % g.cWo : 0, b_sh = CONV == 2 ? (PBK / g.cWo) % g.cHo : 0,
-            b_sb = CONV == 2 ? PBK / (g.cWo * g.cHo) : 0;
+  const int b_sw = CONV == 2 ? PBK % cWo : 0, b_sh = CONV == 2 ? (PBK / cWo) % cHo : 0,
+            b_sb = CONV == 2 ? PBK / (cWo * cHo) : 0;
+  // element distance of that move without carries, and what a carry out of a row / out of an image adds
+  const int b_d0 = CONV == 2 ? ((b_sb * g.cH + (b_sh << ssh)) * g.cW + (b_sw << ssh)) * g.cC : 0;
+  const int b_dw = CONV == 2 ? ((g.cW - cWo) << ssh) * g.cC : 0, b_dh = CONV == 2 ? (g.cH - (cHo << ssh)) * g.cW * g.cC : 0;
 
   f32x16 acc[MI][NI];
 
@@ -1123,14 +1132,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
   };
   auto conv_advance = [&](bool advance) {
     if (!advance) return;
-    if (g.cT == 8) {
+    if (stem) {
       c_off_a += 2 * g.cW * 4;
       return;
     }
     c_sub += PBK;
     if (c_sub == g.cC) {
       c_sub = 0;
-      if (++c_dx > (g.cT >> 1)) { c_dx = -(g.cT >> 1); c_dy++; }
+      if (++c_dx > (cT >> 1)) { c_dx = -(cT >> 1); c_dy++; }
     }
     c_off_a = (long long)(c_dy * g.cW + c_dx) * g.cC + c_sub;
   };
@@ -1152,15 +1161,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pp_kernel(Params g) {
     const int k = CONV == 2 ? i : 0;
     const int dy = (bpix[k] >> 26) - 1, dx = ((bpix[k] >> 24) & 3) - 1;
     int h = (bpix[k] >> 12) & 4095, w = bpix[k] & 4095;
-    const bool ok = (unsigned)(h * g.cS + dy) < (unsigned)g.cH && (unsigned)(w * g.cS + dx) < (unsigned)g.cW;
+    const bool ok = (unsigned)((h << ssh) + dy) < (unsigned)g.cH && (unsigned)((w << ssh) + dx) < (unsigned)g.cW;
     rb[i] = *(const u32x4*)(gb[i] + (ok ? boff[k] : 0));
     b_ok = ok ? (b_ok | (1u << i)) : (b_ok & ~(1u << i));
     if (advance) {
-      int w2 = w + b_sw, h2 = h + b_sh, img = b_sb;
-      if (w2 >= g.cWo) { w2 -= g.cWo; h2++; }
-      if (h2 >= g.cHo) { h2 -= g.cHo; img++; }
-      gb[i] += ((long long)(img * g.cH + (h2 - h) * g.cS) * g.cW + (w2 - w) * g.cS) * g.cC;
-      bpix[k] = (bpix[k] & ~0xffffff) | (h2 << 12) | w2;
+      int delta = b_d0;
+      w += b_sw;
+      h += b_sh;
+      if (w >= cWo) { w -= cWo; h++; delta += b_dw; }
+      if (h >= cHo) { h -= cHo; delta += b_dh; }
+      gb[i] += delta;
+      bpix[k] = (bpix[k] & ~0xffffff) | (h << 12) | w;
     }
   };
   auto load_b_regs = [&](bool advance) {
@@ -1366,17 +1377,17 @@ LaunchFn pp_256x192(bool a_t, bool b_t, int epi);
 LaunchFn pp_256x128(bool a_t, bool b_t, int epi);
 LaunchFn pp_512x64(bool a_t, bool b_t, int epi);
 // implicit 3x3 convolution (A gathered from the activation), row-major operands
-LaunchFn pp_conv_256x256(int epi);
-LaunchFn pp_conv_256x192(int epi);
-LaunchFn pp_conv_256x128(int epi);
-LaunchFn pp_conv_512x64(int epi);
+LaunchFn pp_conv_256x256(int epi, bool general);
+LaunchFn pp_conv_256x192(int epi, bool general);
+LaunchFn pp_conv_256x128(int epi, bool general);
+LaunchFn pp_conv_512x64(int epi, bool general);
 // tiles for weight gradients with few output rows, and the implicit weight gradient of a 3x3 convolution
 LaunchFn pp_128x256(bool a_t, bool b_t, int epi);
 LaunchFn pp_64x512(bool a_t, bool b_t, int epi);
-LaunchFn pp_convdw_256x256(int epi);
-LaunchFn pp_convdw_256x192(int epi);
-LaunchFn pp_convdw_128x256(int epi);
-LaunchFn pp_convdw_64x512(int epi);
+LaunchFn pp_convdw_256x256(int epi, bool general);
+LaunchFn pp_convdw_256x192(int epi, bool general);
+LaunchFn pp_convdw_128x256(int epi, bool general);
+LaunchFn pp_convdw_64x512(int epi, bool general);
 
 }  // namespace gemm
 }  // namespace et

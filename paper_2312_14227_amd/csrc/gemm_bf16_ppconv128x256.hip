@@ -6,9 +6,9 @@ namespace et {
 namespace gemm {
 namespace {
 
-template <bool AT, bool BT, int E, int CONV>
+template <bool AT, bool BT, int E, int CONV, bool GEN = false>
 hipError_t launch(const Params& p, dim3 grid, hipStream_t s) {
-  hipLaunchKernelGGL((gemm_pp_kernel<128, 256, 2, 4, AT, BT, E, CONV>), grid, dim3(512), 0, s, p);
+  hipLaunchKernelGGL((gemm_pp_kernel<128, 256, 2, 4, AT, BT, E, CONV, GEN>), grid, dim3(512), 0, s, p);
   return hipGetLastError();
 }
 
@@ -24,7 +24,12 @@ LaunchFn pp_128x256(bool a_t, bool b_t, int epi) {
   return nullptr;
 }
 
-LaunchFn pp_convdw_128x256(int epi) {
+LaunchFn pp_convdw_128x256(int epi, bool general) {
+  if (general) {
+    if (epi == E_F32) return launch<true, true, E_F32, 2, true>;
+    if (epi == E_PARTIAL) return launch<true, true, E_PARTIAL, 2, true>;
+    return nullptr;
+  }
   if (epi == E_F32) return launch<true, true, E_F32, 2>;
   if (epi == E_PARTIAL) return launch<true, true, E_PARTIAL, 2>;
   return nullptr;

@@ -6,9 +6,9 @@ namespace et {
 namespace gemm {
 namespace {
 
-template <bool AT, bool BT, int E, int CONV>
+template <bool AT, bool BT, int E, int CONV, bool GEN = false>
 hipError_t launch(const Params& p, dim3 grid, hipStream_t s) {
-  hipLaunchKernelGGL((gemm_pp_kernel<512, 64, 8, 1, AT, BT, E, CONV>), grid, dim3(512), 0, s, p);
+  hipLaunchKernelGGL((gemm_pp_kernel<512, 64, 8, 1, AT, BT, E, CONV, GEN>), grid, dim3(512), 0, s, p);
   return hipGetLastError();
 }
 
@@ -32,10 +32,17 @@ LaunchFn pp_512x64(bool a_t, bool b_t, int epi) {
   return nullptr;
 }
 
-LaunchFn pp_conv_512x64(int epi) {
+LaunchFn pp_conv_512x64(int epi, bool general) {
+  // (general: stride 2, 1x1 taps or the stem form, geometry from the launch arguments; the epilogues those layers use)
+  if (general) {
+    if (epi == E_BF16) return launch<false, false, E_BF16, 1, true>;
+    if (epi == E_F32) return launch<false, false, E_F32, 1, true>;
+    if (epi == E_AFFINE) return launch<false, false, E_AFFINE, 1, true>;
+    if (epi == E_PARTIAL) return launch<false, false, E_PARTIAL, 1, true>;
+    return nullptr;
+  }
 #define ET_PICK(E) \
   if (epi == E) return launch<false, false, E, 1>;
-  ET_PICK(E_F32)
   ET_PICK(E_BF16)
   ET_PICK(E_BIAS_RELU)
   ET_PICK(E_AFFINE)

@@ -6,9 +6,9 @@ Stored per tensor k: element indices idx_k (512 drawn uniformly with a fixed see
 elements of largest magnitude, where the mass of the tensor's norm lies), the oracle gradient at
 those elements g_k (all tensors selected; by the invariant of selective training these are also the values for
 any mask that selects k), the gradient's L2 norm, and Eq. 2's importance with its magnitude sum
-for the workload's snapshot.  Also the loss and the logits.  For the ResNet workload, whose reference
-rounds stored tensors to bf16, also the same samples of the exact float64 gradient (gx_k) and per tensor the
-distance between two bf16-storage evaluations that differ by summation-order noise (spread).
+for the workload's snapshot.  Also the loss and the logits.  For the convolutional workloads, whose reference
+rounds stored tensors to bf16, also per tensor the distance between two bf16-storage evaluations that differ by
+summation-order noise (spread), and for the ResNet the same samples of the exact float64 gradient (gx_k).
 """
 import os
 import sys
@@ -34,7 +34,19 @@ def sample_indices(k, g, seed):
     return np.unique(np.concatenate([uniform, largest])).astype(np.int64)
 
 
-def vgg_in_chunks(cfg, wl, chunk):
+def noisy_store(seed):
+    """bf16 storage rounding of values that carry relative noise of 3e-7 (what a float32 sum in another order differs
+    by from the float64 one): a second, equally correct bf16 evaluation."""
+    from oracle import resnet
+    rng = np.random.default_rng([seed, 777])
+    return lambda a: resnet.round_bf16(a * (1.0 + 3e-7 * rng.standard_normal(a.shape)))
+
+
+def spread_of(ga, gb):
+    return np.array([np.linalg.norm((a - b).ravel()) / max(np.linalg.norm(a.ravel()), 1e-300) for a, b in zip(ga, gb)])
+
+
+def vgg_in_chunks(cfg, wl, chunk, store=None):
     """The oracle's float64 column matrices of a whole VGG16 batch do not fit this machine's memory.
     No operation of the network mixes samples, so the gradient of the batch-mean loss is the mean of the
     chunks' gradients; the batch size enters only through the factor 1/B of the logit gradient, and a
@@ -44,7 +56,7 @@ def vgg_in_chunks(cfg, wl, chunk):
     B = wl.x.shape[0]
     assert B % chunk == 0 and ((B // chunk) & (B // chunk - 1)) == 0
     parts = [vgg.vgg_step(cfg, wl.weights, wl.x[i:i + chunk], wl.y[i:i + chunk], [1] * len(wl.weights),
-                          store=resnet.round_bf16)
+                          store=store or resnet.round_bf16)
              for i in range(0, B, chunk)]
     n = len(parts)
     return dict(loss=sum(p["loss"] for p in parts) / n,
@@ -70,11 +82,8 @@ def main():
         # the float64 one) flips a few roundings; behind a flip everything is perturbed at the 2^-9 level, and a
         # ReLU mask bit that changes drops or passes a whole gradient element.  Per tensor the relative L2
         # distance between the two is stored as `spread`; the exact (unrounded) gradient is stored beside both.
-        rng = np.random.default_rng([seed, 777])
-        r2 = resnet.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights),
-                                store=lambda a: resnet.round_bf16(a * (1.0 + 3e-7 * rng.standard_normal(a.shape))))
-        extra["spread"] = np.array([np.linalg.norm((a - b).ravel()) / max(np.linalg.norm(a.ravel()), 1e-300)
-                                    for a, b in zip(r["grads"], r2["grads"])])
+        r2 = resnet.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights), store=noisy_store(seed))
+        extra["spread"] = spread_of(r["grads"], r2["grads"])
         del r2
         rx = resnet.resnet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights))
         extra["exact_grads"] = rx["grads"]
@@ -84,9 +93,15 @@ def main():
         from oracle import mobilenet, resnet
         r = mobilenet.mobilenet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights), store=resnet.round_bf16)
         I = oimp.importance_from_grads(r["grads"], wl.weights, wl.snapshot)
+        r2 = mobilenet.mobilenet_step(cfg, wl.weights, wl.x, wl.y, [1] * len(wl.weights), store=noisy_store(seed))
+        extra["spread"] = spread_of(r["grads"], r2["grads"])
+        del r2
     elif cfg.kind == "vgg":
         r = vgg_in_chunks(cfg, wl, 8)
         I = oimp.importance_from_grads(r["grads"], wl.weights, wl.snapshot)
+        r2 = vgg_in_chunks(cfg, wl, 8, store=noisy_store(seed))
+        extra["spread"] = spread_of(r["grads"], r2["grads"])
+        del r2
     else:
         I, r = oimp.importance(cfg, wl.weights, wl.snapshot, wl.x, wl.y)
     A = oimp.abs_importance_from_grads(r["grads"], wl.weights, wl.snapshot)
@@ -102,6 +117,7 @@ def main():
     if "exact_grads" in extra:
         out["exact_gnorm"] = np.array([np.linalg.norm(g.ravel()) for g in extra["exact_grads"]])
         out["exact_loss"] = extra["exact_loss"]
+    if "spread" in extra:
         out["spread"] = extra["spread"]
     tag = name if batch == cfg.batch else "%s_b%d" % (name, batch)
     path = os.path.join(ROOT, "tests", "golden", "%s_seed%d.npz" % (tag, seed))
