@@ -43,9 +43,12 @@ GOLD_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 RHO_PPM = {"vit_b": 500_000, "vit_l": 400_000, "resnet50": 500_000, "vgg16": 500_000, "mobilenetv2": 500_000}
 
 
-@pytest.mark.parametrize("name,first,tol", [("vit_b", 87, 2e-2), ("vit_l", 200, 2e-2), ("resnet50", 80, 2e-2),
-                                            ("vgg16", 11, 0.25), ("mobilenetv2", 60, 0.75)])
-def test_full_size_gradients_importance_and_masks(name, first, tol):
+# tol: the workload tolerance (relative L2 per tensor, bf16 inputs with fp32 accumulation).  cap: the widest bound a
+# tensor may get where the bf16-storage ORACLE itself, evaluated twice with summation-order noise, is further apart
+# than tol (`spread`, stored per tensor by the golden writer): bound = max(tol, min(cap, 2 spread)).
+@pytest.mark.parametrize("name,first,tol,cap", [("vit_b", 87, 2e-2, 2e-2), ("vit_l", 200, 2e-2, 2e-2), ("resnet50", 80, 2e-2, 0.1),
+                                                ("vgg16", 11, 2e-2, 0.25), ("mobilenetv2", 60, 2e-2, 0.75)])
+def test_full_size_gradients_importance_and_masks(name, first, tol, cap):
     import torch
     from oracle import select as osel
     from paper_2312_14227_amd import binding as et
@@ -60,10 +63,10 @@ def test_full_size_gradients_importance_and_masks(name, first, tol):
     snap = s.put_snapshot(wl.snapshot)
     bounds = {n: tol for n in wl.names}
     if "spread" in G.files:
-        # ResNet-50: where two bf16-storage evaluations of the ORACLE that differ by summation-order noise are
-        # further apart than the workload tolerance (stored per tensor by the golden writer; CPU pin of the
-        # mechanism in tests/test_oracle_resnet.py), that distance, doubled, is the bound of the tensor
-        bounds = {n: max(tol, 2.0 * float(G["spread"][k])) for k, n in enumerate(wl.names)}
+        # the convolutional workloads: where two bf16-storage evaluations of the ORACLE that differ by summation-order
+        # noise are further apart than the workload tolerance (CPU pins of the mechanism in tests/test_oracle_resnet.py,
+        # test_oracle_vgg.py, test_oracle_mobilenet.py), that distance, doubled, is the bound of the tensor, up to cap
+        bounds = {n: max(tol, min(cap, 2.0 * float(G["spread"][k]))) for k, n in enumerate(wl.names)}
     errs, els = {}, {}
     I = s.importance(xt, yt, snap)                 # full backward, gradients stay in the buffers
     torch.cuda.synchronize()
@@ -80,7 +83,7 @@ def test_full_size_gradients_importance_and_masks(name, first, tol):
         worst_el = max(worst_el, el)
         els[wl.names[k]] = el
         nrm = float(torch.linalg.vector_norm(full[k].double()))
-        assert abs(nrm - G["gnorm"][k]) <= tol * G["gnorm"][k], (wl.names[k], nrm, G["gnorm"][k])   # norms: always tol
+        assert abs(nrm - G["gnorm"][k]) <= bounds[wl.names[k]] * G["gnorm"][k], (wl.names[k], nrm, G["gnorm"][k])
         # a gradient within tol (relative L2) moves g.dw by at most tol |g| |dw| (Cauchy-Schwarz)
         dwn = float(np.linalg.norm((wl.snapshot[k].astype(np.float64) - wl.weights[k].astype(np.float64)).ravel()))
         bound = bounds[wl.names[k]] * max(abs(G["importance"][k]), G["gnorm"][k] * dwn)
@@ -99,7 +102,8 @@ def test_full_size_gradients_importance_and_masks(name, first, tol):
         assert all(e <= 2e-2 for n, e in errs.items() if n.startswith("fc")), errs
     if "spread" in G.files:
         wide = {n: round(b, 4) for n, b in bounds.items() if b > tol}
-        print("tensors bounded by the oracle's own spread instead of %.0e:" % tol, wide)
+        print("%d of %d tensors bounded by the oracle's own spread instead of %.0e:" % (len(wide), N, tol), wide)
+    if "gx_0" in G.files:
         ex = {n: rel_l2(full[k][torch.from_numpy(G["idx_%d" % k].astype(np.int64)).to(s.dev)].cpu().numpy(), G["gx_%d" % k])
               for k, n in enumerate(wl.names)}
         print("distance to the exact float64 gradient: median %.4f, worst %s; the bf16-storage oracle's own distance to it: "
@@ -111,8 +115,8 @@ def test_full_size_gradients_importance_and_masks(name, first, tol):
     assert all(e <= bounds[n] for n, e in errs.items()), [(n, e, bounds[n]) for n, e in errs.items() if e > bounds[n]]
     top_el = sorted(els.items(), key=lambda kv: -kv[1])[:6]
     print("largest element errors / largest element:", [(n, round(e, 4)) for n, e in top_el])
-    if tol <= 5e-2:   # (where the bound itself is of order one, VGG16 and MobileNetV2, a single element says nothing)
-        assert all(e <= bounds[n] for n, e in els.items()), [(n, e, bounds[n]) for n, e in els.items() if e > bounds[n]]
+    # (where the bound itself is of order one a single element says nothing)
+    assert all(e <= bounds[n] for n, e in els.items() if bounds[n] <= 0.1), [(n, e, bounds[n]) for n, e in els.items() if e > bounds[n]]
     print("worst sampled relative L2 gradient error at full size: %.3e; worst element error / largest element: %.3e; "
           "worst importance error / bound: %.3f" % (worst, worst_el, worst_i))
     # Eq. 3 on what the device produced: times profiled in place, the importances just computed
