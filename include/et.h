@@ -283,10 +283,15 @@ int et_last_launch_counts(const et_ctx* ctx, int32_t* forward, int32_t* backward
  * et_kernel_timing_read waits for the stream and returns, for one class, the number of timed
  * launches since timing was enabled, their summed duration, and their summed algorithmic work
  * (floating-point operations for classes 0-2 and 5-6, bytes read plus written for classes 3-4, 7).
- * Enabling clears the records.  Outputs are host pointers and may be NULL. */
+ * Enabling clears the records.  Outputs are host pointers and may be NULL.
+ * An event pair measures more than the kernel between its events: the hand-over from one command to the next
+ * is inside it too.  Enabling therefore also records 33 pairs with nothing between them on the same stream;
+ * et_kernel_timing_overhead returns their median elapsed time (about 5 us on this hardware), which a caller may
+ * take off every timed launch (summed durations are returned as measured). */
 #define ET_NUM_KERNEL_CLASSES 8
 int et_kernel_timing(et_ctx* ctx, int32_t enable);
 int et_kernel_timing_read(et_ctx* ctx, int32_t kernel_class, uint64_t* launches, double* total_ns, double* work);
+int et_kernel_timing_overhead(et_ctx* ctx, double* ns_per_pair);
 
 /* Text of the HIP error behind the last ET_EHIP returned on this context ("no error" if none). */
 const char* et_last_hip_error(const et_ctx* ctx);

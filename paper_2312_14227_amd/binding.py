@@ -65,6 +65,7 @@ def _load():
         "et_last_launch_counts": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]),
         "et_kernel_timing": (C.c_int, [vp, i32]),
         "et_kernel_timing_read": (C.c_int, [vp, i32, C.POINTER(u64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+        "et_kernel_timing_overhead": (C.c_int, [vp, C.POINTER(C.c_double)]),
         "et_last_hip_error": (C.c_char_p, [vp]),
         "et_strerror": (C.c_char_p, [C.c_int]),
         "et_debug_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
@@ -89,7 +90,7 @@ def _load():
 _lib = _load()
 EXPORTS = ["et_create", "et_destroy", "et_num_tensors", "et_tensor_info", "et_workspace_bytes", "et_state_slots",
            "et_bind", "et_profile", "et_importance", "et_importance_master", "et_importance_reduce_static", "et_select", "et_select_stats", "et_tensor_metric", "et_train_step", "et_last_launch_counts",
-           "et_kernel_timing", "et_kernel_timing_read", "et_last_hip_error", "et_strerror", "et_debug_gemm_bf16", "et_debug_copy", "et_debug_conv3x3",
+           "et_kernel_timing", "et_kernel_timing_read", "et_kernel_timing_overhead", "et_last_hip_error", "et_strerror", "et_debug_gemm_bf16", "et_debug_copy", "et_debug_conv3x3",
            "et_debug_conv3x3_dw", "et_debug_depthwise3x3", "et_debug_depthwise3x3_ws_floats",
            "et_debug_activation", "et_debug_conv3x3_split", "et_debug_attention",
            "et_debug_conv_gathered", "et_debug_stem", "et_debug_stem_ws_bytes"]
@@ -272,6 +273,13 @@ def et_last_launch_counts(ctx):
 
 def et_kernel_timing(ctx, enable):
     _check(_lib.et_kernel_timing(ctx, int(enable)), "et_kernel_timing", ctx=ctx)
+
+
+def et_kernel_timing_overhead(ctx):
+    """Median elapsed time (ns) of an event pair with nothing between its events, measured when timing was enabled."""
+    ns = C.c_double(0.0)
+    _check(_lib.et_kernel_timing_overhead(ctx, C.byref(ns)), "et_kernel_timing_overhead", ctx=ctx)
+    return ns.value
 
 
 def et_kernel_timing_read(ctx, kernel_class):

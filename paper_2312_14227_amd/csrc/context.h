@@ -154,6 +154,7 @@ struct et_ctx {
 
   // per-kernel-class timing
   bool ktiming = false;
+  std::vector<KernelRecord> kcal;   // event pairs with nothing between them, recorded when timing is enabled
   std::vector<KernelRecord> krecs;
   std::vector<hipEvent_t> kevent_pool;
   size_t kevents_used = 0;

@@ -763,7 +763,42 @@ int et_kernel_timing(et_ctx* c, int32_t enable) {
   ET_HIP(hipStreamSynchronize(c->stream));
   c->ktiming = enable != 0;
   c->krecs.clear();
+  c->kcal.clear();
   c->kevents_used = 0;
+  if (c->ktiming) {
+    // what an event pair measures with nothing between its events (the hand-over between two commands)
+    for (int i = 0; i < 33; i++) {
+      KernelRecord r;
+      r.cls = -1;
+      r.work = 0.0;
+      for (hipEvent_t* ev : {&r.e0, &r.e1}) {
+        if (c->kevents_used == c->kevent_pool.size()) {
+          hipEvent_t e;
+          ET_HIP(hipEventCreate(&e));
+          c->kevent_pool.push_back(e);
+        }
+        *ev = c->kevent_pool[c->kevents_used++];
+      }
+      ET_HIP(hipEventRecord(r.e0, c->stream));
+      ET_HIP(hipEventRecord(r.e1, c->stream));
+      c->kcal.push_back(r);
+    }
+  }
+  return ET_OK;
+}
+
+int et_kernel_timing_overhead(et_ctx* c, double* ns_per_pair) {
+  if (!c || !ns_per_pair) return ET_EINVAL;
+  if (c->kcal.empty()) return ET_ESTATE;
+  ET_HIP(hipStreamSynchronize(c->stream));
+  std::vector<double> t;
+  for (const KernelRecord& r : c->kcal) {
+    float ms = 0.f;
+    ET_HIP(hipEventElapsedTime(&ms, r.e0, r.e1));
+    t.push_back((double)ms * 1e6);
+  }
+  std::sort(t.begin(), t.end());
+  *ns_per_pair = t[t.size() / 2];
   return ET_OK;
 }
 
