@@ -95,118 +95,166 @@ __device__ __forceinline__ bf16x8 frag_rows_tr(const unsigned char* m, int row0,
 // element r of an MFMA result tile: row offset inside the 32x32 tile
 __device__ __forceinline__ int tile_row(int r, int lane) { return (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); }
 
+// Store a 32 x 64 result tile (lane = row l%32, registers t[dt][a*4 + e] = column dt*32 + a*8 + (l/32)*4 + e), times
+// `mul`, as bf16 rows of `ld` elements starting at `base` (row 0 of the tile), rows >= `rows` left out.  Straight
+// from the registers a store instruction would put 16 bytes into each of 32 rows (8-byte pieces of two lanes);
+// written that way the 19 MB of a ViT-B forward output cost 6 us.  The tile goes through a wave-private 4 KiB LDS
+// area instead (16-byte chunks XORed with the row, so the 8-byte writes of 32 rows spread over the banks) and
+// leaves as whole 128-byte rows, 8 lanes x 16 bytes each.  LDS instructions of one wave execute in order, so no
+// barrier is needed between the writes and the reads, nor between two tiles through the same area.
+constexpr int STORE_AREA = 32 * 128;
+__device__ __forceinline__ void store_tile(unsigned char* area, const f32x16 (&t)[2], float mul, bf16* base, long long ld,
+                                           int rows, int lane) {
+  asm volatile("" : "+v"(lane));   // (addresses below are computed here, not kept live through the caller's main loop)
+  const int l32 = lane & 31, khalf = lane >> 5;
+#pragma unroll
+  for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+    for (int a = 0; a < 4; a++) {
+      bf16x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; e++) v[e] = (bf16)(t[dt][a * 4 + e] * mul);
+      *(bf16x4*)(area + l32 * 128 + (((dt * 4 + a) ^ (l32 & 7)) << 4) + khalf * 8) = v;
+    }
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int row = i * 8 + (lane >> 3), chunk = lane & 7;
+    const bf16x8 v = *(const bf16x8*)(area + row * 128 + ((chunk ^ (row & 7)) << 4));
+    if (row < rows) *(bf16x8*)(base + row * ld + chunk * 8) = v;
+  }
+}
+
 // -------------------------------------------------------------------------------------------------
 // forward
 // -------------------------------------------------------------------------------------------------
+// One resident workgroup per CU walks over (batch, head) items.  K and V of an item are brought into one of two LDS
+// buffers by direct-to-LDS loads (no registers), issued while the previous item is computed, so the memory latency
+// of an item is paid once per workgroup, not once per item.  A lane's 16 bytes of a wave-wide direct load land at
+// (base in M0) + 16 * lane: the bank swizzle is therefore applied on the global side (the lane at chunk position p
+// of row r fetches chunk p ^ swz(r)).  Rows beyond the sequence repeat the last row: their keys are masked with
+// -inf, and a probability of zero times a finite V row adds nothing.
+__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+
 template <int KT>
 __global__ __launch_bounds__(NTHREADS) void attention_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ out,
-                                                                 float* __restrict__ lse, int T, int H, float scale) {
+                                                                 float* __restrict__ lse, int T, int H, float scale, int items) {
   constexpr int TP = KT * 32;
-  __shared__ __attribute__((aligned(16))) unsigned char sk[TP * PITCH];
-  __shared__ __attribute__((aligned(16))) unsigned char sv[TP * PITCH];
+  constexpr int MAT = TP * PITCH;                       // one matrix: a multiple of 1 KiB
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * 2 * MAT + NWAVES * STORE_AREA];   // [buffer][K, V], store areas
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int b = blockIdx.x / H, h = blockIdx.x % H;
   const int D = H * DH;
   const long long ld = 3LL * D;
-  const bf16* q = qkv + (long long)b * T * ld + h * DH;
-  const bf16* k = q + D;
-  const bf16* v = q + 2 * D;
-  {
-    unsigned char* const dst[2] = {sk, sv};
-    const bf16* const src[2] = {k, v};
-    const long long lds[2] = {ld, ld};
-    stage_rows<TP, 2>(dst, src, lds, T, tid);
-  }
-  __syncthreads();
-
+  const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) unsigned char*)smem;
   const int l32 = lane & 31, khalf = lane >> 5;
   // exp(scale * x) = 2^(c x): the scale is folded into the exponent, scores stay as the MFMA leaves them
   const float c = scale * 1.44269504088896341f;
-  for (int qt = wave; qt < KT; qt += NWAVES) {
-    // Q fragments straight from memory (B operand: row = query, 8 consecutive d)
-    const int qrow = min(qt * 32 + l32, T - 1);
-    bf16x8 qf[4];
+
+  // the KT * 8 one-KiB pieces (8 rows each) of an item's K and V are dealt to the 8 waves, KT each
+  // (lane-dependent address pieces come from an opaque copy of the thread index, so that they are recomputed per item
+  // instead of staying in registers through the matrix products)
+  auto issue = [&](int item, int buf) {
+    int t_ = tid;
+    asm volatile("" : "+v"(t_));
+    const int lane = t_ & 63, wave = t_ >> 6;
+    const int b = item / H, h = item % H;
+    const bf16* kbase = qkv + (long long)b * T * ld + h * DH + D;
+#pragma unroll
+    for (int i = 0; i < KT; i++) {
+      const int p = wave * KT + i, m = p / (KT * 4), rp = p % (KT * 4);
+      const int row = rp * 8 + (lane >> 3), pos = lane & 7;
+      const bf16* src = kbase + m * D + (long long)min(row, T - 1) * ld + ((pos ^ swz(row)) << 3);
+      dma16(src, __builtin_amdgcn_readfirstlane(lds0 + (buf * 2 + m) * MAT + rp * 1024));
+    }
+  };
+  // Q fragments of an item for this wave's query tile, straight from memory (B operand: row = query, 8 consecutive d)
+  auto load_q = [&](int item, bf16x8 (&qf)[4]) {
+    int t_ = tid;
+    asm volatile("" : "+v"(t_));
+    const int l32 = t_ & 31, khalf = (t_ >> 5) & 1, wave = t_ >> 6;
+    const int b = item / H, h = item % H;
+    const bf16* q = qkv + (long long)b * T * ld + h * DH;
+    const int qrow = min(wave * 32 + l32, T - 1);
 #pragma unroll
     for (int ks = 0; ks < 4; ks++) qf[ks] = *(const bf16x8*)(q + (long long)qrow * ld + ks * 16 + khalf * 8);
+  };
 
-    // S^T tile kt (unscaled): lane holds query l%32 and keys kt*32 + tile_row(r); only the last tile has keys
-    // beyond T, which get -inf
-    auto scores = [&](int kt, auto last) -> f32x16 {
-      f32x16 acc;
+  int item = blockIdx.x;
+  if (item >= items) return;
+  bf16x8 qf[4];
+  load_q(item, qf);
+  issue(item, 0);
+  for (int buf = 0; item < items; item += gridDim.x, buf ^= 1) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's pieces of the item have landed
+    asm volatile("s_barrier" ::: "memory");            // ... and everyone's; the other buffer is no longer read
+    const int next = item + gridDim.x;
+    if (next < items) issue(next, buf ^ 1);
+    const unsigned char* sk = smem + (buf * 2) * MAT;
+    const unsigned char* sv = sk + MAT;
+    if (wave < KT) {
+      const int qt = wave;
+      const int b = item / H, h = item % H;
+      // S^T tiles (unscaled), all kept in registers: lane holds query l%32 and keys kt*32 + tile_row(r)
+      f32x16 st[KT];
 #pragma unroll
-      for (int r = 0; r < 16; r++) acc[r] = 0.f;
+      for (int kt = 0; kt < KT; kt++) {
 #pragma unroll
-      for (int ks = 0; ks < 4; ks++)
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct(sk, kt * 32, ks, lane), qf[ks], acc, 0, 0, 0);
-      if (decltype(last)::value) {   // the last tile is handled outside the loops, so the others carry no selects
+        for (int r = 0; r < 16; r++) st[kt][r] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; r++) acc[r] = kt * 32 + tile_row(r, lane) < T ? acc[r] : -INFINITY;
+        for (int ks = 0; ks < 4; ks++)
+          st[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct(sk, kt * 32, ks, lane), qf[ks], st[kt], 0, 0, 0);
       }
-      return acc;
-    };
-    typedef std::integral_constant<bool, false> Inner;
-    typedef std::integral_constant<bool, true> Last;
+      // (the Q fragments are no longer needed: their registers take the next item's, which arrive under the rest of
+      // this item's work)
+      if (next < items) load_q(next, qf);
+      // only the last tile has keys beyond T
+#pragma unroll
+      for (int r = 0; r < 16; r++) st[KT - 1][r] = (KT - 1) * 32 + tile_row(r, lane) < T ? st[KT - 1][r] : -INFINITY;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < KT; kt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) mx = fmaxf(mx, st[kt][r]);
+      const float M = fmaxf(mx, __shfl_xor(mx, 32, 64));   // finite: key 0 is never masked
+      const float mc = -M * c;
 
-    // sweep 1: maximum over this lane's keys (no exponentials yet); the other half of the keys lives in lane l^32
-    float mx = -INFINITY;
-#pragma unroll 1
-    for (int kt = 0; kt < KT - 1; kt++) {
-      const f32x16 st = scores(kt, Inner());
-#pragma unroll
-      for (int r = 0; r < 16; r++) mx = fmaxf(mx, st[r]);
-    }
-    {
-      const f32x16 st = scores(KT - 1, Last());
-#pragma unroll
-      for (int r = 0; r < 16; r++) mx = fmaxf(mx, st[r]);
-    }
-    const float M = fmaxf(mx, __shfl_xor(mx, 32, 64));   // finite: key 0 is never masked
-    const float mc = -M * c;
-
-    // sweep 2: O^T = V^T exp(scale (S - M))^T with unnormalised probabilities, which are already an MFMA operand
-    // (query l%32, 8 keys per lane); the result tile has lane = query as well, so the sum of a query's
-    // probabilities, collected on the way, divides its own registers afterwards
-    float sum = 0.f;
-    f32x16 o[2];
-#pragma unroll
-    for (int dt = 0; dt < 2; dt++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
-    auto accumulate = [&](int kt, const f32x16& st) {
-#pragma unroll
-      for (int j = 0; j < 2; j++) {
-        bf16x8 pf;
-#pragma unroll
-        for (int e = 0; e < 8; e++) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(st[j * 8 + e], c, mc));
-          sum += p;
-          pf[e] = (bf16)p;
-        }
-#pragma unroll
-        for (int dt = 0; dt < 2; dt++)
-          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_tr(sv, kt * 32 + j * 16, dt * 32, lane), pf, o[dt], 0, 0, 0);
-      }
-    };
-#pragma unroll 1
-    for (int kt = 0; kt < KT - 1; kt++) accumulate(kt, scores(kt, Inner()));
-    accumulate(KT - 1, scores(KT - 1, Last()));
-    const float S = sum + __shfl_xor(sum, 32, 64);
-    const float inv = 1.f / S;
-    const int row = qt * 32 + l32;
-    if (khalf == 0 && row < T) lse[((long long)b * H + h) * T + row] = M * scale + logf(S);
-    // result tile: lane holds query l%32 and d = dt*32 + tile_row(r): four consecutive d per register quad
-    if (row < T) {
-      bf16* orow = out + ((long long)b * T + row) * D + h * DH;
+      // O^T = V^T exp(scale (S - M))^T with unnormalised probabilities, which are already an MFMA operand (query
+      // l%32, 8 keys per lane); the result tile has lane = query as well, so the sum of a query's probabilities,
+      // collected on the way, divides its own registers afterwards
+      float sum = 0.f;
+      f32x16 o[2];
 #pragma unroll
       for (int dt = 0; dt < 2; dt++)
 #pragma unroll
-        for (int a = 0; a < 4; a++) {
-          bf16x4 v;
+        for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
 #pragma unroll
-          for (int e = 0; e < 4; e++) v[e] = (bf16)(o[dt][a * 4 + e] * inv);
-          *(bf16x4*)(orow + dt * 32 + a * 8 + khalf * 4) = v;
+      for (int kt = 0; kt < KT; kt++)
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+          bf16x8 pf;
+#pragma unroll
+          for (int e = 0; e < 8; e++) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(st[kt][j * 8 + e], c, mc));
+            sum += p;
+            pf[e] = (bf16)p;
+          }
+#pragma unroll
+          for (int dt = 0; dt < 2; dt++)
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_tr(sv, kt * 32 + j * 16, dt * 32, lane), pf, o[dt], 0, 0, 0);
         }
+      const float S = sum + __shfl_xor(sum, 32, 64);
+      const float inv = 1.f / S;
+      const int row = qt * 32 + l32;
+      if (khalf == 0 && row < T) lse[((long long)b * H + h) * T + row] = M * scale + logf(S);
+      // result tile: lane holds query l%32 and d = dt*32 + tile_row(r); it is a lane's own sum that divides its registers
+#pragma unroll
+      for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) o[dt][r] *= inv;
+      store_tile(smem + 2 * 2 * MAT + wave * STORE_AREA, o, 1.f, out + ((long long)b * T + qt * 32) * D + h * DH, D, T - qt * 32, lane);
     }
+    if (wave >= KT && next < items) load_q(next, qf);   // (a wave without a query tile: keeps the loop uniform)
   }
 }
 
@@ -224,6 +272,7 @@ __global__ __launch_bounds__(NTHREADS) void attention_bwd_kernel(const bf16* __r
   __shared__ __attribute__((aligned(16))) unsigned char sdo[TP * PITCH];
   __shared__ __attribute__((aligned(16))) float s_lse[TP];
   __shared__ __attribute__((aligned(16))) float s_dot[TP];  // rowsum(P * dP) per query
+  __shared__ __attribute__((aligned(16))) unsigned char s_store[NWAVES * STORE_AREA];   // per wave: rows on their way out
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = blockIdx.x / H, h = blockIdx.x % H;
   const int D = H * DH;
@@ -297,19 +346,7 @@ __global__ __launch_bounds__(NTHREADS) void attention_bwd_kernel(const bf16* __r
           dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_tr(sk, kt * 32 + j * 16, dt * 32, lane), dsf, dq[dt], 0, 0, 0);
       }
     }
-    const int row = qt * 32 + l32;
-    if (row < T) {
-      bf16* drow = dqkv + ((long long)b * T + row) * ld + h * DH;
-#pragma unroll
-      for (int dt = 0; dt < 2; dt++)
-#pragma unroll
-        for (int a = 0; a < 4; a++) {
-          bf16x4 v;
-#pragma unroll
-          for (int e = 0; e < 4; e++) v[e] = (bf16)(dq[dt][a * 4 + e] * scale);
-          *(bf16x4*)(drow + dt * 32 + a * 8 + khalf * 4) = v;
-        }
-    }
+    store_tile(s_store + wave * STORE_AREA, dq, scale, dqkv + ((long long)b * T + qt * 32) * ld + h * DH, ld, T - qt * 32, lane);
   }
   __syncthreads();
 
@@ -364,29 +401,20 @@ __global__ __launch_bounds__(NTHREADS) void attention_bwd_kernel(const bf16* __r
         }
       }
     }
-    const int row = kt * 32 + l32;
-    if (row < T) {
-      bf16* drow = dqkv + ((long long)b * T + row) * ld + h * DH;
-#pragma unroll
-      for (int dt = 0; dt < 2; dt++)
-#pragma unroll
-        for (int a = 0; a < 4; a++) {
-          bf16x4 vk, vv;
-#pragma unroll
-          for (int e = 0; e < 4; e++) {
-            vk[e] = (bf16)(dk[dt][a * 4 + e] * scale);
-            vv[e] = (bf16)dv[dt][a * 4 + e];
-          }
-          *(bf16x4*)(drow + D + dt * 32 + a * 8 + khalf * 4) = vk;
-          *(bf16x4*)(drow + 2 * D + dt * 32 + a * 8 + khalf * 4) = vv;
-        }
-    }
+    bf16* drow0 = dqkv + ((long long)b * T + kt * 32) * ld + h * DH;
+    store_tile(s_store + wave * STORE_AREA, dk, scale, drow0 + D, ld, T - kt * 32, lane);
+    store_tile(s_store + wave * STORE_AREA, dv, 1.f, drow0 + 2 * D, ld, T - kt * 32, lane);
   }
 }
 
 template <int KT>
 hipError_t launch_fwd(const bf16* qkv, bf16* out, float* lse, int B, int T, int H, float scale, hipStream_t s) {
-  hipLaunchKernelGGL((attention_fwd_kernel<KT>), dim3(B * H), dim3(NTHREADS), 0, s, qkv, out, lse, T, H, scale);
+  // one resident workgroup per CU (two LDS buffers of K and V each); fewer when there are fewer items
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    cus = 256;
+  const int items = B * H;
+  hipLaunchKernelGGL((attention_fwd_kernel<KT>), dim3(items < cus ? items : cus), dim3(NTHREADS), 0, s, qkv, out, lse, T, H, scale, items);
   return hipGetLastError();
 }
 template <int KT>
