@@ -99,7 +99,8 @@ __device__ __forceinline__ int tile_row(int r, int lane) { return (r >> 2) * 8 +
 // `mul`, as bf16 rows of `ld` elements starting at `base` (row 0 of the tile), rows >= `rows` left out.  Straight
 // from the registers a store instruction would put 16 bytes into each of 32 rows (8-byte pieces of two lanes);
 // written that way the 19 MB of a ViT-B forward output cost 6 us.  The tile goes through a wave-private 4 KiB LDS
-// area instead (16-byte chunks XORed with the row, so the 8-byte writes of 32 rows spread over the banks) and
+// area instead (16-byte chunks XORed with (row >> 1) & 7: even and odd rows lie in different halves of the 256-byte
+// bank span, so 16 consecutive rows of one column are spread over all 64 banks) and
 // leaves as whole 128-byte rows, 8 lanes x 16 bytes each.  LDS instructions of one wave execute in order, so no
 // barrier is needed between the writes and the reads, nor between two tiles through the same area.
 constexpr int STORE_AREA = 32 * 128;
@@ -114,12 +115,12 @@ __device__ __forceinline__ void store_tile(unsigned char* area, const f32x16 (&t
       bf16x4 v;
 #pragma unroll
       for (int e = 0; e < 4; e++) v[e] = (bf16)(t[dt][a * 4 + e] * mul);
-      *(bf16x4*)(area + l32 * 128 + (((dt * 4 + a) ^ (l32 & 7)) << 4) + khalf * 8) = v;
+      *(bf16x4*)(area + l32 * 128 + (((dt * 4 + a) ^ ((l32 >> 1) & 7)) << 4) + khalf * 8) = v;
     }
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     const int row = i * 8 + (lane >> 3), chunk = lane & 7;
-    const bf16x8 v = *(const bf16x8*)(area + row * 128 + ((chunk ^ (row & 7)) << 4));
+    const bf16x8 v = *(const bf16x8*)(area + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
     if (row < rows) *(bf16x8*)(base + row * ld + chunk * 8) = v;
   }
 }
