@@ -108,3 +108,34 @@ def test_step_is_deterministic():
     for a, b in zip(g1, s.grad):
         assert torch.equal(a, b)
     s.close()
+
+
+def test_kernel_timing_records_every_launch_and_its_own_overhead():
+    """Measurement support: with timing enabled, a step's GEMM launches are all recorded with their algorithmic work,
+    the summed durations are plausible, and the event-pair overhead measured beside them is a few microseconds."""
+    from paper_2312_14227_amd import binding as et
+    cfg = CONFIGS["vit_small"]
+    wl = make_workload(cfg, seed=1, init="random")
+    N = len(wl.weights)
+    s = _session(cfg, wl)
+    xt, yt = s.put_input(wl.x, wl.y)
+    ones = np.ones(N, dtype=np.uint8)
+    s.train_step(xt, yt, ones)
+    with pytest.raises(RuntimeError):
+        et.et_kernel_timing_overhead(s.ctx)          # nothing measured while timing is off
+    et.et_kernel_timing(s.ctx, 1)
+    s.train_step(xt, yt, ones)
+    pair_ns = et.et_kernel_timing_overhead(s.ctx)
+    assert 100.0 < pair_ns < 1e5, pair_ns
+    n_fwd, ns_fwd, flop_fwd = et.et_kernel_timing_read(s.ctx, 0)
+    n_dx, ns_dx, _ = et.et_kernel_timing_read(s.ctx, 1)
+    n_dw, ns_dw, _ = et.et_kernel_timing_read(s.ctx, 2)
+    # forward products: patch embedding, four per block, the head
+    assert n_fwd == 4 * cfg.blocks + 2 and n_dw >= 4 * cfg.blocks and n_dx >= 4 * cfg.blocks - 1
+    M = cfg.batch * cfg.tokens
+    want = 2.0 * M * cfg.width * (3 * cfg.width + cfg.width + 2 * cfg.mlp) * cfg.blocks
+    assert flop_fwd > want and flop_fwd < 1.5 * want
+    for n, ns in ((n_fwd, ns_fwd), (n_dx, ns_dx), (n_dw, ns_dw)):
+        assert ns > n * 0.5 * pair_ns and ns < n * 1e6      # every launch spans at least most of a pair, none a millisecond
+    et.et_kernel_timing(s.ctx, 0)
+    s.close()
