@@ -133,6 +133,10 @@ CONFIGS = {
     "resnet_small": ResNetConfig("resnet_small", 3, 64, 3, 16, (2, 1, 2, 1), (8, 16, 24, 32), 24),
     # bottleneck width 64: the 3x3 convolutions that run as implicit GEMMs (stride 1) next to a strided one
     "resnet_c64": ResNetConfig("resnet_c64", 2, 32, 3, 64, (2, 1), (64, 128), 16),
+    # odd image sizes and output-pixel counts that are not multiples of 64: the convolutions whose weight gradient (and,
+    # for the stem, forward product) falls back to an explicit column matrix
+    "resnet_odd": ResNetConfig("resnet_odd", 1, 18, 3, 8, (1, 1), (8, 8), 8),
+    "resnet_c64_odd": ResNetConfig("resnet_c64_odd", 1, 36, 3, 64, (1, 1), (64, 128), 16),
     # second CNN family of the paper's evaluation (Section 8): VGG16 shape, 200 classes
     "vgg16": VGGConfig("vgg16", 32, 224, 3, (64, 128, 256, 512, 512), (2, 2, 3, 3, 3), (4096, 4096), 200),
     "vgg_tiny": VGGConfig("vgg_tiny", 2, 8, 3, (8, 8), (1, 2), (16,), 8),

@@ -35,7 +35,8 @@ def _run(s, xt, yt, mask):
 # tolerance itself, the cases without flips keep a tenth of it.
 @pytest.mark.parametrize("name,seed,init,factor", [("resnet_tiny", 0, "random", 0.1), ("resnet_tiny", 1, "paper", 0.1),
                                                    ("resnet_small", 2, "random", 0.1), ("resnet_small", 3, "paper", 0.1),
-                                                   ("resnet_c64", 4, "random", 1.0), ("resnet_c64", 5, "paper", 1.0)])
+                                                   ("resnet_c64", 4, "random", 1.0), ("resnet_c64", 5, "paper", 1.0),
+                                                   ("resnet_odd", 6, "random", 0.1), ("resnet_c64_odd", 7, "random", 1.0)])
 def test_resnet_masks_match_oracle(name, seed, init, factor):
     cfg = CONFIGS[name]
     wl = make_workload(cfg, seed=seed, init=init)
