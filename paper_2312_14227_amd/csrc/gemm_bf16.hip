@@ -382,7 +382,15 @@ hipError_t gemm_bf16(const GemmDesc& d, hipStream_t s, int* launches) {
   const int tiles = ((d.M + BM - 1) / BM) * ((d.N + BN - 1) / BN);
   if ((long long)tiles * zdim >= (1ll << 23)) return hipErrorInvalidValue;   // (the resident kernels' unit arithmetic)
   p.units = tiles * zdim;
-  hipError_t e = resident ? fn(p, dim3(std::min(p.units, compute_units()), 1, 1), s) : fn(p, dim3(tiles, 1, zdim), s);
+  // resident kernels: every workgroup takes the same number of units (600 tiles run as 200 workgroups of 3 rather than
+  // 256 of 2 or 3: the launch takes 3 tile times either way, and the CUs left idle lower the load the others run under)
+  int resident_grid = p.units;
+  const int cus = compute_units();
+  if (resident_grid > cus) {
+    const int rounds = (p.units + cus - 1) / cus;
+    resident_grid = std::min(cus, ((p.units + rounds - 1) / rounds + 7) & ~7);
+  }
+  hipError_t e = resident ? fn(p, dim3(resident_grid, 1, 1), s) : fn(p, dim3(tiles, 1, zdim), s);
   if (e != hipSuccess) return e;
   if (launches) *launches = 1;
   if (p.split_k > 1 && conv_split) {
