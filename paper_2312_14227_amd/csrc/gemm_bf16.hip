@@ -218,6 +218,13 @@ void gemm_bf16_plan_split(int M, int N, int K, int* tile, int* split_k) {
     const Plan pl = plan_large(M, N, K, true);
     *tile = pl.tile;
     *split_k = pl.split;
+  } else if (M >= 256 && N >= 256 && (K % gemm::DBK) == 0 && K >= 32 * gemm::DBK) {
+    // a long reduction whose length is a multiple of 32 but not of 64 (ViT-L at batch 32: 6 304 rows) takes the
+    // direct-to-LDS tiles; unsplit, its 16-64 tiles of 256x256 would leave most CUs idle.  Measured on those shapes:
+    // about 256 units in all, at most 8 chunks (4096x1024: 98 -> 71 us with 4 chunks; 1024x1024: 70 -> 31 us with 8)
+    const int tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    *split_k = std::max(1, std::min(8, 256 / tiles));
+    *tile = tiles >= 32 ? T_DMA_256x256 : T_DMA_256x128;
   } else {   // small outputs: as many chunks as keep the CUs busy, each at least 4 slices
     const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
     const int slices = (K + gemm::SBK - 1) / gemm::SBK;
