@@ -218,10 +218,11 @@ void gemm_bf16_plan_split(int M, int N, int K, int* tile, int* split_k) {
     const Plan pl = plan_large(M, N, K, true);
     *tile = pl.tile;
     *split_k = pl.split;
-  } else if (M >= 256 && N >= 256 && (K % gemm::DBK) == 0 && K >= 32 * gemm::DBK) {
+  } else if (M >= 256 && N >= 256 && (K % gemm::DBK) == 0 && K >= 128 * gemm::DBK) {
     // a long reduction whose length is a multiple of 32 but not of 64 (ViT-L at batch 32: 6 304 rows) takes the
     // direct-to-LDS tiles; unsplit, its 16-64 tiles of 256x256 would leave most CUs idle.  Measured on those shapes:
-    // about 256 units in all, at most 8 chunks (4096x1024: 98 -> 71 us with 4 chunks; 1024x1024: 70 -> 31 us with 8)
+    // about 256 units in all, at most 8 chunks (4096x1024: 98 -> 71 us with 4 chunks; 1024x1024: 70 -> 31 us with 8).
+    // Shorter reductions (1 568 rows: the last ResNet-50 stage) are better off with the rule below.
     const int tiles = ((M + 255) / 256) * ((N + 255) / 256);
     *split_k = std::max(1, std::min(8, 256 / tiles));
     *tile = tiles >= 32 ? T_DMA_256x256 : T_DMA_256x128;
