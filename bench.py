@@ -74,6 +74,34 @@ def cpu_baseline(cfg, mask, sample_batch, opt_kind, hp):
                       "rate scaled by %d/%d" % (sample_batch, cfg.batch, dt, sample_batch, cfg.batch)}
 
 
+def measured_peaks(torch, et):
+    """Sustained rate of a pure bf16 MFMA loop on all CUs and of a 1 GiB device copy (read + written bytes per second)."""
+    stream = torch.cuda.current_stream().cuda_stream
+    res = {}
+    wgs, iters = 2048, 4000
+    buf = torch.empty(wgs * 512, dtype=torch.float32, device="cuda:0")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if et.et_debug_mfma_peak(buf.data_ptr(), wgs, 200, stream) == 0:
+        torch.cuda.synchronize()
+        e0.record()
+        et.et_debug_mfma_peak(buf.data_ptr(), wgs, iters, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        res["mfma_bf16_tflops"] = wgs * 8 * iters * 4 * 32768.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    n = 1 << 30
+    src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    if et.et_debug_copy(dst.data_ptr(), src.data_ptr(), n, stream) == 0:
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(3):
+            et.et_debug_copy(dst.data_ptr(), src.data_ptr(), n, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        res["copy_gbps"] = 3 * 2.0 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -220,6 +248,11 @@ def main():
         "update": {"gbps": upd_bytes / upd_ns if upd_ns else None, "us": upd_ns / max(upd_n, 1) / 1e3,
                    "frac_of_hbm_peak": upd_bytes / upd_ns / PEAK_HBM_GBS if upd_ns else None},
     }
+    # what the chip sustains on nothing but matrix instructions and on a plain copy, measured in this run: the datasheet
+    # peaks the roofline is quoted against (2.5 PFLOP/s, 8 TB/s) are not reachable under an all-CU load
+    out["measured_peaks"] = measured_peaks(torch, et)
+    if roofline and roofline.get("bound") == "mfma" and out["measured_peaks"].get("mfma_bf16_tflops"):
+        roofline["frac_of_sustained_mfma"] = roofline["achieved"] / out["measured_peaks"]["mfma_bf16_tflops"]
     if a.copy_calibration:
         src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
         dst = torch.empty_like(src)

@@ -110,6 +110,12 @@ int et_debug_activation(const struct et_ctx* ctx, const char* name, const void**
  * pointers).  Used to calibrate hardware traffic counters against a known size. */
 int et_debug_copy(void* dst, const void* src, size_t bytes, void* stream);
 
+/* Measurement support: a loop of nothing but bf16 matrix instructions (v_mfma_f32_32x32x16_bf16, four independent
+ * accumulators per wave), `workgroups` workgroups of 8 waves, `iters` iterations each (a multiple of 4): workgroups * 8 * iters * 4
+ * instructions of 32 768 floating-point operations.  What it sustains is the matrix rate the chip holds under an
+ * all-CU load.  out: device, workgroups * 512 floats (written so that the loop is not optimised away).  Returns 0, -1, -3. */
+int et_debug_mfma_peak(float* out, int workgroups, int iters, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -69,6 +69,7 @@ def _load():
         "et_last_hip_error": (C.c_char_p, [vp]),
         "et_strerror": (C.c_char_p, [C.c_int]),
         "et_debug_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
+        "et_debug_mfma_peak": (C.c_int, [vp, C.c_int, C.c_int, vp]),
         "et_debug_activation": (C.c_int, [vp, C.c_char_p, C.POINTER(vp), C.POINTER(C.c_size_t)]),
         "et_debug_depthwise3x3_ws_floats": (C.c_size_t, [C.c_int] * 5),
         "et_debug_depthwise3x3": (C.c_int, [C.c_int] + [vp] * 7 + [C.c_int] * 5 + [vp]),
@@ -90,7 +91,7 @@ def _load():
 _lib = _load()
 EXPORTS = ["et_create", "et_destroy", "et_num_tensors", "et_tensor_info", "et_workspace_bytes", "et_state_slots",
            "et_bind", "et_profile", "et_importance", "et_importance_master", "et_importance_reduce_static", "et_select", "et_select_stats", "et_tensor_metric", "et_train_step", "et_last_launch_counts",
-           "et_kernel_timing", "et_kernel_timing_read", "et_kernel_timing_overhead", "et_last_hip_error", "et_strerror", "et_debug_gemm_bf16", "et_debug_copy", "et_debug_conv3x3",
+           "et_kernel_timing", "et_kernel_timing_read", "et_kernel_timing_overhead", "et_last_hip_error", "et_strerror", "et_debug_gemm_bf16", "et_debug_copy", "et_debug_mfma_peak", "et_debug_conv3x3",
            "et_debug_conv3x3_dw", "et_debug_depthwise3x3", "et_debug_depthwise3x3_ws_floats",
            "et_debug_activation", "et_debug_conv3x3_split", "et_debug_attention",
            "et_debug_conv_gathered", "et_debug_stem", "et_debug_stem_ws_bytes"]
@@ -346,6 +347,10 @@ def et_debug_depthwise3x3_ws_floats(batch, H, W, Cch, stride):
 def et_debug_attention(op, qkv, out, lse, dout, dqkv, B, T, H, stream=0):
     return _lib.et_debug_attention(op, C.c_void_p(qkv), C.c_void_p(out), C.c_void_p(lse), C.c_void_p(dout), C.c_void_p(dqkv),
                                    B, T, H, C.c_void_p(stream))
+
+
+def et_debug_mfma_peak(out, workgroups, iters, stream=0):
+    return _lib.et_debug_mfma_peak(C.c_void_p(out), workgroups, iters, C.c_void_p(stream))
 
 
 def et_debug_copy(dst, src, nbytes, stream=0):

@@ -202,11 +202,75 @@ extern "C" int et_debug_attention(int op, const void* qkv, void* out, float* lse
 }
 
 namespace {
-__global__ void et_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+typedef unsigned dbg_u32x4 __attribute__((ext_vector_type(4)));
+// plain streaming copy: a workgroup moves 16 KiB at a time, four 16-byte vectors per thread in flight, non-temporal
+// accesses (every byte is touched once)
+__global__ __launch_bounds__(256) void et_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  const dbg_u32x4* s = (const dbg_u32x4*)src;
+  dbg_u32x4* d = (dbg_u32x4*)dst;
+  constexpr int U = 4;
+  const size_t stride = (size_t)gridDim.x * 256 * U;
+  for (size_t i0 = (size_t)blockIdx.x * 256 * U + threadIdx.x; i0 < n16; i0 += stride) {
+    dbg_u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+      const size_t i = i0 + 256 * u;
+      v[u] = __builtin_nontemporal_load(s + (i < n16 ? i : n16 - 1));
+    }
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+      const size_t i = i0 + 256 * u;
+      if (i < n16) __builtin_nontemporal_store(v[u], d + i);
+    }
+  }
 }
 }  // namespace
+
+namespace {
+typedef et::bf16 dbg_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float dbg_f32x16 __attribute__((ext_vector_type(16)));
+// Nothing but matrix instructions: every wave keeps four independent accumulators going, so the matrix pipe of its
+// SIMD never waits for a result.  What this loop sustains is what the chip gives a GEMM at the clock it holds under
+// an all-CU MFMA load.
+__global__ __launch_bounds__(512) void mfma_peak_kernel(float* __restrict__ out, int iters) {
+  // operands with the bit patterns of random values of either sign (what a matrix unit draws, and with it the clock the
+  // chip holds, depends on how many operand bits toggle), four different pairs in turn
+  unsigned h = (threadIdx.x + 1u) * 2654435761u + blockIdx.x * 40503u;
+  dbg_bf16x8 a[4], b[4];
+#pragma unroll
+  for (int v = 0; v < 4; v++)
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      h = h * 1664525u + 1013904223u;
+      a[v][e] = (et::bf16)(((float)(h >> 8) * (1.f / 8388608.f) - 1.f) * 0.05f);
+      h = h * 1664525u + 1013904223u;
+      b[v][e] = (et::bf16)(((float)(h >> 8) * (1.f / 8388608.f) - 1.f) * 0.05f);
+    }
+  dbg_f32x16 acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; j++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) acc[j][r] = 0.f;
+  for (int it = 0; it < iters; it += 4) {   // (iters is a multiple of 4)
+#pragma unroll
+    for (int u = 0; u < 4; u++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[(j + u) & 3], acc[j], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; j++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) s += acc[j][r];
+  out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+}  // namespace
+
+extern "C" int et_debug_mfma_peak(float* out, int workgroups, int iters, void* stream) {
+  if (!out || workgroups < 1 || workgroups > (1 << 20) || iters < 4 || (iters & 3) || iters > (1 << 24)) return ET_EINVAL;
+  hipLaunchKernelGGL(mfma_peak_kernel, dim3(workgroups), dim3(512), 0, (hipStream_t)stream, out, iters);
+  return hipGetLastError() == hipSuccess ? ET_OK : ET_EHIP;
+}
 
 extern "C" int et_debug_copy(void* dst, const void* src, size_t bytes, void* stream) {
   if (!dst || !src || (bytes & 15) || ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15))
